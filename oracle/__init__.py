@@ -1,0 +1,192 @@
+"""ctypes binding of the CPU oracle (``siso_oracle.c``).
+
+TEST INFRASTRUCTURE: only ``tests/``, ``__graft_entry__.smoke()`` and the
+``cpu_baseline`` leg of ``bench.py`` may import this package.  It shares no code
+with the GPU library.  All arrays are numpy host arrays; bf16 data is carried as
+``uint16`` bit patterns.
+"""
+
+from __future__ import annotations
+
+import ctypes as C
+import os
+import subprocess
+from typing import Optional, Tuple
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "siso_oracle.c")
+_LIB = os.path.join(_HERE, "libsiso_oracle.so")
+
+F32, BF16 = 0, 1
+_DT = {"f32": F32, "bf16": BF16}
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc (generic x86-64 code, OpenMP)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        cmd = ["gcc", "-O2", "-std=c11", "-fopenmp", "-fPIC", "-shared", "-Wall", "-Wextra",
+               "-o", _LIB, _SRC, "-lm"]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+_lib = None
+
+
+def lib() -> C.CDLL:
+    global _lib
+    if _lib is None:
+        build()
+        L = C.CDLL(_LIB)
+        vp, lg, it, fl = C.c_void_p, C.c_long, C.c_int, C.c_float
+        L.oracle_lookup_rows.argtypes = [vp, lg, it, it, vp, lg, fl, vp, vp, vp, vp]
+        L.oracle_lookup_rows.restype = it
+        L.oracle_create.argtypes = [it, lg, it, C.POINTER(vp)]
+        L.oracle_create.restype = it
+        L.oracle_destroy.argtypes = [vp]
+        L.oracle_destroy.restype = None
+        L.oracle_count.argtypes = [vp]
+        L.oracle_count.restype = lg
+        L.oracle_load.argtypes = [vp, vp, vp, lg]
+        L.oracle_load.restype = it
+        L.oracle_lookup.argtypes = [vp, vp, lg, fl, vp, vp, vp, vp]
+        L.oracle_lookup.restype = it
+        L.oracle_update.argtypes = [vp, vp, vp, lg]
+        L.oracle_update.restype = it
+        L.oracle_merge.argtypes = [vp, fl, vp, lg]
+        L.oracle_merge.restype = lg
+        L.oracle_merge_apply.argtypes = [vp, vp, lg, vp]
+        L.oracle_merge_apply.restype = it
+        L.oracle_export.argtypes = [vp, vp, vp, vp]
+        L.oracle_export.restype = it
+        L.oracle_threads.argtypes = []
+        L.oracle_threads.restype = it
+        _lib = L
+    return _lib
+
+
+def threads() -> int:
+    return int(lib().oracle_threads())
+
+
+def _storage(x: np.ndarray, dtype: str, dim: int) -> np.ndarray:
+    want = np.float32 if dtype == "f32" else np.uint16
+    x = np.ascontiguousarray(x)
+    if x.dtype != want:
+        raise TypeError(f"expected {want} rows for dtype {dtype}, got {x.dtype}")
+    if x.ndim != 2 or x.shape[1] != dim:
+        raise ValueError(f"expected [*, {dim}] rows, got {x.shape}")
+    return x
+
+
+def _ptr(a: Optional[np.ndarray]):
+    return None if a is None else a.ctypes.data_as(C.c_void_p)
+
+
+def lookup_rows(centroids: np.ndarray, queries: np.ndarray, threshold: float, dtype: str,
+                want_second: bool = True):
+    """Stateless lookup.  Returns ``(idx int32, sim float64, hit uint8, second float64|None)``."""
+    dim = int(queries.shape[1]) if queries.ndim == 2 else int(centroids.shape[1])
+    cents = _storage(centroids, dtype, dim)
+    qs = _storage(queries, dtype, dim)
+    n = qs.shape[0]
+    idx = np.empty(n, np.int32)
+    sim = np.empty(n, np.float64)
+    hit = np.empty(n, np.uint8)
+    second = np.empty(n, np.float64) if want_second else None
+    rc = lib().oracle_lookup_rows(_ptr(cents), cents.shape[0], dim, _DT[dtype], _ptr(qs), n,
+                                  float(threshold), _ptr(idx), _ptr(sim), _ptr(hit), _ptr(second))
+    if rc != 0:
+        raise RuntimeError(f"oracle_lookup_rows failed ({rc})")
+    return idx, sim, hit, second
+
+
+class OracleCache:
+    """The oracle's cache object: stored centroids, exact means (float64), cluster sizes."""
+
+    def __init__(self, dim: int, capacity: int, dtype: str = "bf16"):
+        self.dim, self.capacity, self.dtype = int(dim), int(capacity), dtype
+        h = C.c_void_p()
+        rc = lib().oracle_create(self.dim, self.capacity, _DT[dtype], C.byref(h))
+        if rc != 0:
+            raise RuntimeError(f"oracle_create failed ({rc})")
+        self._h = h
+
+    def close(self) -> None:
+        if self._h:
+            lib().oracle_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    @property
+    def count(self) -> int:
+        return int(lib().oracle_count(self._h))
+
+    def load(self, centroids: np.ndarray, counts: Optional[np.ndarray] = None) -> None:
+        cents = _storage(centroids, self.dtype, self.dim)
+        cn = None if counts is None else np.ascontiguousarray(counts, dtype=np.int32)
+        rc = lib().oracle_load(self._h, _ptr(cents), _ptr(cn), cents.shape[0])
+        if rc != 0:
+            raise RuntimeError(f"oracle_load failed ({rc})")
+
+    def lookup(self, queries: np.ndarray, threshold: float, want_second: bool = True):
+        qs = _storage(queries, self.dtype, self.dim)
+        n = qs.shape[0]
+        idx = np.empty(n, np.int32)
+        sim = np.empty(n, np.float64)
+        hit = np.empty(n, np.uint8)
+        second = np.empty(n, np.float64) if want_second else None
+        rc = lib().oracle_lookup(self._h, _ptr(qs), n, float(threshold), _ptr(idx), _ptr(sim), _ptr(hit),
+                                 _ptr(second))
+        if rc != 0:
+            raise RuntimeError(f"oracle_lookup failed ({rc})")
+        return idx, sim, hit, second
+
+    def update(self, queries: np.ndarray, idx: np.ndarray) -> None:
+        qs = _storage(queries, self.dtype, self.dim)
+        ix = np.ascontiguousarray(idx, dtype=np.int32)
+        if ix.shape != (qs.shape[0],):
+            raise ValueError("idx must have one entry per query")
+        rc = lib().oracle_update(self._h, _ptr(qs), _ptr(ix), qs.shape[0])
+        if rc != 0:
+            raise RuntimeError(f"oracle_update failed ({rc})")
+
+    def merge(self, threshold: float, cap: Optional[int] = None) -> Tuple[np.ndarray, int]:
+        """Returns ``(pairs[min(total, cap), 2] int32 in lexicographic order, total)``."""
+        if cap is None:
+            total = int(lib().oracle_merge(self._h, float(threshold), None, 0))
+            if total < 0:
+                raise RuntimeError(f"oracle_merge failed ({total})")
+            cap = total
+        pairs = np.empty((max(cap, 1), 2), np.int32)
+        total = int(lib().oracle_merge(self._h, float(threshold), _ptr(pairs), cap))
+        if total < 0:
+            raise RuntimeError(f"oracle_merge failed ({total})")
+        return pairs[:min(total, cap)].copy(), total
+
+    def merge_apply(self, pairs: np.ndarray) -> np.ndarray:
+        """Merges connected groups; returns the survivor map (new index of each old row)."""
+        pr = np.ascontiguousarray(pairs, dtype=np.int32).reshape(-1, 2)
+        surv = np.empty(self.count, np.int32)
+        rc = lib().oracle_merge_apply(self._h, _ptr(pr), pr.shape[0], _ptr(surv))
+        if rc != 0:
+            raise RuntimeError(f"oracle_merge_apply failed ({rc})")
+        return surv
+
+    def export(self):
+        """Returns ``(centroids storage, means float64, sizes int32)`` of the live rows."""
+        k = self.count
+        cents = np.empty((k, self.dim), np.float32 if self.dtype == "f32" else np.uint16)
+        means = np.empty((k, self.dim), np.float64)
+        sizes = np.empty(k, np.int32)
+        rc = lib().oracle_export(self._h, _ptr(cents), _ptr(means), _ptr(sizes))
+        if rc != 0:
+            raise RuntimeError(f"oracle_export failed ({rc})")
+        return cents, means, sizes

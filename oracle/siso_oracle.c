@@ -1,0 +1,423 @@
+/*
+ * TEST INFRASTRUCTURE - NOT PART OF THE PRODUCT PATH.
+ *
+ * Brute-force, double-precision CPU oracle for the centroid-cache hot path:
+ * batched exact lookup, centroid update, all-pairs self-similarity and group
+ * merge.  It is written to be checked against the paper by eye: plain loops, no
+ * blocking, no fusion, no reordering.  The only concession to run time is an
+ * OpenMP "parallel for" over independent outer iterations (queries, rows),
+ * which does not change any arithmetic.
+ *
+ * It shares no code with the GPU library, and only tests, the smoke check and
+ * the benchmark's CPU-baseline leg may call it.
+ *
+ * What is computed, and where the paper defines it:
+ *   - CosineSimilarity(a, b) = <a,b> / (|a| |b|): the similarity measure used
+ *     throughout (section 3.1; Algorithm 1, MergeCentroids).
+ *   - FindClosestCentroid(q, C) = the centroid of C with the largest cosine
+ *     similarity to q (Algorithm 1, MergeCentroids; section 4.3 for the batched
+ *     online search).  Ties go to the lowest index.
+ *   - hit test: similarity strictly greater than the threshold (Algorithm 1
+ *     uses ">"; section 3.1 "the similarity threshold for retrieval ... judges
+ *     a cache hit").
+ *   - a centroid is the average point of its group of vectors (section 3.1):
+ *     the update keeps, per centroid, the exact mean m of its unit-length
+ *     members and their number n, and stores normalize(m) rounded to the
+ *     storage type.
+ *   - merge: all pairs i<j of cached centroids whose cosine exceeds the
+ *     clustering threshold (the comparison inside MergeCentroids, taken over
+ *     all pairs); connected groups are replaced by their count-weighted mean,
+ *     the cluster sizes add up (Algorithm 1, MergeCentroids, cluster_size).
+ *
+ * Readings where the paper is silent (all listed in the design notes):
+ *   - vectors are taken at storage precision (bf16 or fp32 widened exactly to
+ *     double); similarities are true cosines of the stored values;
+ *   - a zero-length vector has similarity 0 to everything; a query holding a
+ *     NaN or infinity gets idx -1, sim NaN, no hit; an empty cache gives idx
+ *     -1, sim -inf, no hit; a similarity that is NaN never wins;
+ *   - the update is batch-synchronous and order-free: every centroid k receives
+ *     the sum of the unit-normalised queries assigned to it in this call;
+ *   - if an updated mean has zero length the stored centroid is left as it is.
+ *
+ * parity pins: see tests/test_oracle_*.py (hand-computed cosines, closed forms
+ * for means, brute force through an independent numpy/float64 route, planted
+ * duplicates and neighbours, threshold invariants, closed-form pair counts).
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+#define ORACLE_F32 0
+#define ORACLE_BF16 1
+
+typedef struct oracle_cache {
+    int dim;
+    long capacity;
+    int dtype;
+    long count;
+    void *cent;     /* [capacity][dim] storage type, as loaded / as last rounded */
+    double *mean;   /* [capacity][dim] mean of the unit-length members           */
+    int *size;      /* [capacity] number of members (cluster_size)               */
+} oracle_cache;
+
+/* ------------------------------------------------------------------ storage */
+static size_t elem_size(int dtype) { return dtype == ORACLE_F32 ? 4 : 2; }
+
+/* element e of a storage array, widened exactly */
+static double widen(const void *base, int dtype, size_t e) {
+    if (dtype == ORACLE_F32) return (double)((const float *)base)[e];
+    uint32_t bits = (uint32_t)((const uint16_t *)base)[e] << 16;
+    float f;
+    memcpy(&f, &bits, 4);
+    return (double)f;
+}
+
+/* double -> bf16 bit pattern with one round-to-nearest-even step */
+static uint16_t round_bf16(double x) {
+    if (isnan(x)) return 0x7FC0;
+    uint16_t sign = signbit(x) ? 0x8000 : 0;
+    double a = fabs(x);
+    if (isinf(a)) return sign | 0x7F80;
+    double r;
+    if (a < ldexp(1.0, -126)) {
+        /* subnormal range of bf16: spacing 2^-133 */
+        r = ldexp(rint(ldexp(a, 133)), -133);
+    } else {
+        int e;
+        double m = frexp(a, &e);            /* a = m * 2^e, m in [0.5, 1) */
+        r = ldexp(rint(ldexp(m, 8)), e - 8); /* keep 8 significant bits    */
+    }
+    if (r >= ldexp(1.0, 128)) return sign | 0x7F80;
+    float f = (float)r; /* exact: r has at most 8 significant bits */
+    uint32_t bits;
+    memcpy(&bits, &f, 4);
+    return sign | (uint16_t)(bits >> 16);
+}
+
+static void store(void *base, int dtype, size_t e, double x) {
+    if (dtype == ORACLE_F32) ((float *)base)[e] = (float)x; /* round-to-nearest-even */
+    else ((uint16_t *)base)[e] = round_bf16(x);
+}
+
+/* ---------------------------------------------------------------- arithmetic */
+static double row_norm(const void *base, int dtype, long row, int dim) {
+    double s = 0.0;
+    for (int t = 0; t < dim; ++t) {
+        double v = widen(base, dtype, (size_t)row * dim + t);
+        s += v * v;
+    }
+    return sqrt(s);
+}
+
+static int row_finite(const void *base, int dtype, long row, int dim) {
+    for (int t = 0; t < dim; ++t)
+        if (!isfinite(widen(base, dtype, (size_t)row * dim + t))) return 0;
+    return 1;
+}
+
+/* CosineSimilarity of row ra of A and row rb of B, given their lengths */
+static double cosine(const void *A, long ra, double na, const void *B, long rb, double nb,
+                     int dtype, int dim) {
+    if (na == 0.0 || nb == 0.0) return 0.0;
+    double s = 0.0;
+    for (int t = 0; t < dim; ++t)
+        s += widen(A, dtype, (size_t)ra * dim + t) * widen(B, dtype, (size_t)rb * dim + t);
+    return s / (na * nb);
+}
+
+/* ------------------------------------------------------------------- lookup */
+/*
+ * For every query: FindClosestCentroid over rows [0,k) of `centroids`, then the
+ * strict threshold test.  out_second (nullable) receives the largest similarity
+ * among the other centroids (-inf if there is none); tests use it for the top-2
+ * gap.  All pointers are host pointers.
+ */
+int oracle_lookup_rows(const void *centroids, long k, int dim, int dtype, const void *queries, long n,
+                       float threshold, int *out_idx, double *out_sim, unsigned char *out_hit,
+                       double *out_second) {
+    if (dim <= 0 || k < 0 || n < 0) return -1;
+    if (n > 0 && (!queries || !out_idx || !out_sim)) return -1;
+    if (k > 0 && !centroids) return -1;
+    double *cn = (double *)malloc(sizeof(double) * (size_t)(k > 0 ? k : 1));
+    if (!cn) return -2;
+#pragma omp parallel for schedule(static)
+    for (long j = 0; j < k; ++j) cn[j] = row_norm(centroids, dtype, j, dim);
+
+    const double theta = (double)threshold;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (long i = 0; i < n; ++i) {
+        int best = -1;
+        double best_s = -INFINITY, second = -INFINITY;
+        if (!row_finite(queries, dtype, i, dim)) {
+            out_idx[i] = -1;
+            out_sim[i] = NAN;
+            if (out_hit) out_hit[i] = 0;
+            if (out_second) out_second[i] = NAN;
+            continue;
+        }
+        double qn = row_norm(queries, dtype, i, dim);
+        for (long j = 0; j < k; ++j) {
+            double s = cosine(queries, i, qn, centroids, j, cn[j], dtype, dim);
+            if (isnan(s)) continue;
+            if (s > best_s) { /* strict: the lowest index keeps a tie */
+                second = best_s;
+                best_s = s;
+                best = (int)j;
+            } else if (s > second) {
+                second = s;
+            }
+        }
+        out_idx[i] = best;
+        out_sim[i] = best_s;
+        if (out_hit) out_hit[i] = (best >= 0 && best_s > theta) ? 1 : 0;
+        if (out_second) out_second[i] = second;
+    }
+    free(cn);
+    return 0;
+}
+
+/* -------------------------------------------------------------- cache object */
+int oracle_create(int dim, long capacity, int dtype, oracle_cache **out) {
+    if (!out || dim <= 0 || capacity <= 0 || (dtype != ORACLE_F32 && dtype != ORACLE_BF16)) return -1;
+    oracle_cache *c = (oracle_cache *)calloc(1, sizeof(*c));
+    if (!c) return -2;
+    c->dim = dim;
+    c->capacity = capacity;
+    c->dtype = dtype;
+    c->cent = calloc((size_t)capacity * dim, elem_size(dtype));
+    c->mean = (double *)calloc((size_t)capacity * dim, sizeof(double));
+    c->size = (int *)calloc((size_t)capacity, sizeof(int));
+    if (!c->cent || !c->mean || !c->size) {
+        free(c->cent); free(c->mean); free(c->size); free(c);
+        return -2;
+    }
+    *out = c;
+    return 0;
+}
+
+void oracle_destroy(oracle_cache *c) {
+    if (!c) return;
+    free(c->cent); free(c->mean); free(c->size); free(c);
+}
+
+long oracle_count(const oracle_cache *c) { return c ? c->count : -1; }
+
+/*
+ * Replace the cache contents by k rows.  The rows are stored as given (no
+ * re-rounding); the running mean starts at the row scaled to unit length and
+ * stands for counts[j] members (1 when counts is NULL).
+ */
+int oracle_load(oracle_cache *c, const void *centroids, const int *counts, long k) {
+    if (!c || k < 0 || k > c->capacity || (k > 0 && !centroids)) return -1;
+    if (counts)
+        for (long j = 0; j < k; ++j)
+            if (counts[j] < 1) return -1;
+    memcpy(c->cent, centroids, (size_t)k * c->dim * elem_size(c->dtype));
+    for (long j = 0; j < k; ++j) {
+        double nrm = row_norm(c->cent, c->dtype, j, c->dim);
+        for (int t = 0; t < c->dim; ++t) {
+            double v = widen(c->cent, c->dtype, (size_t)j * c->dim + t);
+            c->mean[(size_t)j * c->dim + t] = (nrm > 0.0 && isfinite(nrm)) ? v / nrm : 0.0;
+        }
+        c->size[j] = counts ? counts[j] : 1;
+    }
+    c->count = k;
+    return 0;
+}
+
+int oracle_lookup(const oracle_cache *c, const void *queries, long n, float threshold, int *out_idx,
+                  double *out_sim, unsigned char *out_hit, double *out_second) {
+    if (!c) return -1;
+    return oracle_lookup_rows(c->cent, c->count, c->dim, c->dtype, queries, n, threshold, out_idx, out_sim,
+                              out_hit, out_second);
+}
+
+/*
+ * Fold query i into centroid idx[i] (idx[i] < 0: skip).  Members are the
+ * unit-normalised queries; zero-length and non-finite queries are skipped.
+ *   m_k <- (n_k m_k + sum of members) / (n_k + #members),  n_k += #members,
+ *   c_k <- round_storage(m_k / |m_k|)        (left alone when |m_k| = 0)
+ * Every centroid sees all of its members of this call at once, so the result
+ * does not depend on the order of the queries.
+ */
+int oracle_update(oracle_cache *c, const void *queries, const int *idx, long n) {
+    if (!c || n < 0 || (n > 0 && (!queries || !idx))) return -1;
+    for (long i = 0; i < n; ++i)
+        if (idx[i] >= c->count) return -1;
+    const int d = c->dim;
+    double *sum = (double *)malloc(sizeof(double) * d);
+    char *done = (char *)calloc((size_t)(n > 0 ? n : 1), 1);
+    if (!sum || !done) { free(sum); free(done); return -2; }
+    for (long i = 0; i < n; ++i) {
+        if (idx[i] < 0 || done[i]) continue;
+        const long k = idx[i];
+        long members = 0;
+        for (int t = 0; t < d; ++t) sum[t] = 0.0;
+        for (long j = i; j < n; ++j) {
+            if (idx[j] != k) continue;
+            done[j] = 1;
+            if (!row_finite(queries, c->dtype, j, d)) continue;
+            double qn = row_norm(queries, c->dtype, j, d);
+            if (qn == 0.0) continue;
+            for (int t = 0; t < d; ++t) sum[t] += widen(queries, c->dtype, (size_t)j * d + t) / qn;
+            ++members;
+        }
+        if (members == 0) continue;
+        double *m = c->mean + (size_t)k * d;
+        const double n_old = (double)c->size[k], n_new = n_old + (double)members;
+        double sq = 0.0;
+        for (int t = 0; t < d; ++t) {
+            m[t] = (n_old * m[t] + sum[t]) / n_new;
+            sq += m[t] * m[t];
+        }
+        c->size[k] += (int)members;
+        double nrm = sqrt(sq);
+        if (nrm > 0.0)
+            for (int t = 0; t < d; ++t) store(c->cent, c->dtype, (size_t)k * d + t, m[t] / nrm);
+    }
+    free(sum);
+    free(done);
+    return 0;
+}
+
+/* ------------------------------------------------------------------- merge */
+/*
+ * All pairs i<j of cached centroids with CosineSimilarity > threshold, written
+ * in lexicographic order as (i,j) int pairs.  Returns the total number of such
+ * pairs; only the first `cap` are written.
+ */
+long oracle_merge(const oracle_cache *c, float threshold, int *out_pairs, long cap) {
+    if (!c || cap < 0 || (cap > 0 && !out_pairs)) return -1;
+    const long k = c->count;
+    const double theta = (double)threshold;
+    double *cn = (double *)malloc(sizeof(double) * (size_t)(k > 0 ? k : 1));
+    int **rows = (int **)calloc((size_t)(k > 0 ? k : 1), sizeof(int *));
+    long *cnt = (long *)calloc((size_t)(k > 0 ? k : 1), sizeof(long));
+    if (!cn || !rows || !cnt) { free(cn); free(rows); free(cnt); return -2; }
+    for (long i = 0; i < k; ++i) cn[i] = row_norm(c->cent, c->dtype, i, c->dim);
+#pragma omp parallel for schedule(dynamic, 8)
+    for (long i = 0; i < k; ++i) {
+        long have = 0, room = 0;
+        int *list = NULL;
+        for (long j = i + 1; j < k; ++j) {
+            double s = cosine(c->cent, i, cn[i], c->cent, j, cn[j], c->dtype, c->dim);
+            if (s > theta) {
+                if (have == room) {
+                    room = room ? 2 * room : 8;
+                    list = (int *)realloc(list, sizeof(int) * (size_t)room);
+                }
+                list[have++] = (int)j;
+            }
+        }
+        rows[i] = list;
+        cnt[i] = have;
+    }
+    long total = 0;
+    for (long i = 0; i < k; ++i) {
+        for (long h = 0; h < cnt[i]; ++h, ++total) {
+            if (total < cap) {
+                out_pairs[2 * total] = (int)i;
+                out_pairs[2 * total + 1] = rows[i][h];
+            }
+        }
+        free(rows[i]);
+    }
+    free(cn); free(rows); free(cnt);
+    return total;
+}
+
+static long uf_find(long *parent, long x) {
+    while (parent[x] != x) x = parent[x];
+    return x;
+}
+
+/*
+ * Merge the connected groups of the pair graph.  The survivor of a group is its
+ * lowest index; it receives
+ *   m_g = sum_i n_i m_i / sum_i n_i,  n_g = sum_i n_i,  c_g = round_storage(m_g/|m_g|)
+ * (c_g keeps the survivor's stored row when |m_g| = 0); rows outside any pair
+ * are untouched.  Survivors are then packed to the front in their old order.
+ * out_survivor (nullable, [old count]) gets the new index of each old row's
+ * group.
+ */
+int oracle_merge_apply(oracle_cache *c, const int *pairs, long n_pairs, int *out_survivor) {
+    if (!c || n_pairs < 0 || (n_pairs > 0 && !pairs)) return -1;
+    const long k = c->count;
+    const int d = c->dim;
+    for (long p = 0; p < n_pairs; ++p) {
+        int a = pairs[2 * p], b = pairs[2 * p + 1];
+        if (a < 0 || b < 0 || a >= k || b >= k || a == b) return -1;
+    }
+    long *parent = (long *)malloc(sizeof(long) * (size_t)(k > 0 ? k : 1));
+    long *newpos = (long *)malloc(sizeof(long) * (size_t)(k > 0 ? k : 1));
+    double *acc = (double *)malloc(sizeof(double) * d);
+    if (!parent || !newpos || !acc) { free(parent); free(newpos); free(acc); return -2; }
+    for (long i = 0; i < k; ++i) parent[i] = i;
+    for (long p = 0; p < n_pairs; ++p) {
+        long ra = uf_find(parent, pairs[2 * p]), rb = uf_find(parent, pairs[2 * p + 1]);
+        if (ra < rb) parent[rb] = ra;       /* the lower index becomes the root */
+        else if (rb < ra) parent[ra] = rb;
+    }
+    for (long r = 0; r < k; ++r) {
+        if (uf_find(parent, r) != r) continue;
+        long members = 0;
+        double wsum = 0.0;
+        for (int t = 0; t < d; ++t) acc[t] = 0.0;
+        for (long i = r; i < k; ++i) {
+            if (uf_find(parent, i) != r) continue;
+            ++members;
+            wsum += (double)c->size[i];
+            for (int t = 0; t < d; ++t) acc[t] += (double)c->size[i] * c->mean[(size_t)i * d + t];
+        }
+        if (members == 1) continue;
+        double sq = 0.0;
+        for (int t = 0; t < d; ++t) {
+            c->mean[(size_t)r * d + t] = acc[t] / wsum;
+            sq += c->mean[(size_t)r * d + t] * c->mean[(size_t)r * d + t];
+        }
+        c->size[r] = (int)wsum;
+        double nrm = sqrt(sq);
+        if (nrm > 0.0)
+            for (int t = 0; t < d; ++t) store(c->cent, c->dtype, (size_t)r * d + t, c->mean[(size_t)r * d + t] / nrm);
+    }
+    long live = 0;
+    const size_t rowb = (size_t)d * elem_size(c->dtype);
+    for (long i = 0; i < k; ++i) {
+        if (uf_find(parent, i) != i) continue;
+        newpos[i] = live;
+        if (live != i) {
+            memmove((char *)c->cent + (size_t)live * rowb, (char *)c->cent + (size_t)i * rowb, rowb);
+            memmove(c->mean + (size_t)live * d, c->mean + (size_t)i * d, sizeof(double) * d);
+            c->size[live] = c->size[i];
+        }
+        ++live;
+    }
+    if (out_survivor)
+        for (long i = 0; i < k; ++i) out_survivor[i] = (int)newpos[uf_find(parent, i)];
+    c->count = live;
+    free(parent); free(newpos); free(acc);
+    return 0;
+}
+
+/* Copy out the live rows: stored centroids, means (double), sizes.  Any pointer may be NULL. */
+int oracle_export(const oracle_cache *c, void *centroids, double *means, int *sizes) {
+    if (!c) return -1;
+    const size_t cells = (size_t)c->count * c->dim;
+    if (centroids) memcpy(centroids, c->cent, cells * elem_size(c->dtype));
+    if (means) memcpy(means, c->mean, cells * sizeof(double));
+    if (sizes) memcpy(sizes, c->size, (size_t)c->count * sizeof(int));
+    return 0;
+}
+
+/* Number of threads the parallel loops use. */
+int oracle_threads(void) {
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
