@@ -1,0 +1,195 @@
+"""Benchmark of the centroid-cache hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c2_mid]
+
+A step is one pass of the online path over one batch of synthetic queries that already
+sit in GPU memory: siso_lookup (query norms, similarity against every cached centroid,
+top-1, hit test) followed by siso_update_hits (hit queries fold into their centroid).
+The offline merge pass (pair search + group merge) is timed once after the steps and
+reported beside them; it is not part of a step because it runs once per cache refresh,
+not once per batch.  Prints one JSON line.
+"""
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+sys.path.insert(0, os.path.join(ROOT, "tests"))
+
+PEAK_BF16_TFLOPS = 2500.0  # dense bf16 MFMA, MI355X
+PEAK_HBM_GBS = 8000.0      # HBM3E
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=None)
+    ap.add_argument("--warmup", type=int, default=None)
+    ap.add_argument("--workload", default="c2_mid", choices=["c2_mid", "c3_large", "c4_stream", "c5_merge"])
+    ap.add_argument("--cpu-seconds", type=float, default=15.0, help="CPU work given to the oracle baseline")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-merge", action="store_true")
+    ap.add_argument("--option", action="append", default=[], help="name=value for siso_set_option")
+    ap.add_argument("--path", type=int, default=0, help="siso_set_lookup_path (0 = auto)")
+    return ap.parse_args()
+
+
+def cpu_baseline(wl, n_batch, seconds):
+    """The oracle, as it stands, on a bounded sample of the same queries."""
+    import oracle
+
+    oracle.build()
+    threads = oracle.threads()
+    t0 = time.perf_counter()
+    oracle.lookup_rows(wl.centroids, wl.queries[:2], wl.thresholds[0], wl.dtype)
+    per_q = (time.perf_counter() - t0) / 2
+    m = int(max(2, min(n_batch, seconds / max(per_q, 1e-9))))
+    t0 = time.perf_counter()
+    oracle.lookup_rows(wl.centroids, wl.queries[:m], wl.thresholds[0], wl.dtype)
+    dt = time.perf_counter() - t0
+    return {"value": m / dt, "unit": "queries/s", "cores": threads, "kind": "oracle",
+            "sample": f"first {m} queries of the batch against all {wl.K} centroids, {dt:.1f} s"}
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only; --gpus must be 1", file=sys.stderr)
+        sys.exit(2)
+    import numpy as np
+    import torch
+
+    from paper_2508_18736_amd import siso
+    from paper_2508_18736_amd import workloads as W
+    from gpu_util import to_dev
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+
+    name = args.workload
+    t0 = time.perf_counter()
+    wl = W.FULL_CONFIGS[name]()
+    gen_s = time.perf_counter() - t0
+    d, K = wl.dim, wl.K
+    cache = siso.SisoCache(d, K, siso.BF16)
+    cache.set_lookup_path(args.path)
+    for o in args.option:
+        k, v = o.split("=")
+        cache.set_option(k, int(v))
+    cents = to_dev(wl.centroids, "bf16")
+    cache.load(cents)
+    del cents
+    out = {"n_gpus": 1, "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
+           "data": "synthetic"}
+    merge_info = None
+
+    if name == "c5_merge":
+        steps = args.steps or 5
+        warmup = args.warmup if args.warmup is not None else 1
+        theta = wl.thresholds[0]
+        cap = wl.meta["expected_pairs"] + 1024
+        for _ in range(warmup):
+            cache.merge(theta, cap)
+        cache.profile_enable(True)
+        cache.profile_read()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            pairs, total = cache.merge(theta, cap)
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        kern_ms, launches = cache.profile_read()
+        flop = float(K) * K * d  # upper triangle only
+        avg_s = kern_ms / 1e3 / max(launches, 1)
+        t1 = time.perf_counter()
+        cache.merge_apply(pairs)
+        apply_s = time.perf_counter() - t1
+        out.update({"metric": "merge_centroid_rows_per_s", "value": K * steps / dt, "unit": "rows/s",
+                    "steps": steps, "warmup": warmup, "ms_per_step": dt / steps * 1e3,
+                    "config": {"workload": "c5_merge", "centroids": K, "dim": d, "threshold": theta,
+                               "pairs": int(total), "groups_after_merge": cache.count,
+                               "merge_apply_ms": apply_s * 1e3},
+                    "roofline": {"bound": "mfma", "achieved": flop / avg_s / 1e12, "peak": PEAK_BF16_TFLOPS,
+                                 "unit": "TFLOP/s", "frac": flop / avg_s / 1e12 / PEAK_BF16_TFLOPS,
+                                 "traffic": None, "kernel_ms": avg_s * 1e3}})
+        print(json.dumps(out))
+        return
+
+    streaming = name == "c4_stream"
+    nb = wl.batch if streaming else wl.n
+    n_batches = wl.n // nb
+    queries = to_dev(wl.queries, "bf16")
+    steps = args.steps or (1024 if streaming else 20)
+    warmup = args.warmup if args.warmup is not None else (32 if streaming else 3)
+    thetas = list(wl.thresholds)
+    idx = torch.empty(nb, dtype=torch.int32, device="cuda:0")
+    sim = torch.empty(nb, dtype=torch.float32, device="cuda:0")
+    hit = torch.empty(nb, dtype=torch.uint8, device="cuda:0")
+
+    def step(i):
+        q = queries[(i % n_batches) * nb:(i % n_batches + 1) * nb]
+        cache.lookup(q, thetas[i % len(thetas)], idx, sim, hit)
+        cache.update(q, idx, hit)
+
+    for i in range(warmup):
+        step(i)
+    cache.profile_enable(True)
+    cache.profile_read()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(steps):
+        step(warmup + i)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    kern_ms, launches = cache.profile_read()
+    cache.profile_enable(False)
+    hit_rate = float(hit.float().mean().item())
+    avg_s = kern_ms / 1e3 / max(launches, 1)
+    flop = 2.0 * nb * K * d
+    if streaming:
+        bytes_alg = K * d * 2.0 + nb * d * 2.0 + K * 4.0  # centroids + queries + inverse lengths, read once
+        roof = {"bound": "hbm", "achieved": bytes_alg / avg_s / 1e9, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                "frac": bytes_alg / avg_s / 1e9 / PEAK_HBM_GBS, "traffic": None, "kernel_ms": avg_s * 1e3,
+                "launches": launches}
+    else:
+        roof = {"bound": "mfma", "achieved": flop / avg_s / 1e12, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                "frac": flop / avg_s / 1e12 / PEAK_BF16_TFLOPS, "traffic": None, "kernel_ms": avg_s * 1e3,
+                "launches": launches}
+
+    if not args.no_merge and name == "c2_mid":
+        theta_c = 0.90
+        cap = 1 << 20
+        cache.merge(theta_c, cap)
+        cache.profile_enable(True)
+        cache.profile_read()
+        t1 = time.perf_counter()
+        pairs, total = cache.merge(theta_c, cap)
+        merge_s = time.perf_counter() - t1
+        mk_ms, _ = cache.profile_read()
+        cache.profile_enable(False)
+        t1 = time.perf_counter()
+        cache.merge_apply(pairs)
+        apply_s = time.perf_counter() - t1
+        merge_info = {"threshold": theta_c, "pairs": int(total), "pair_search_ms": merge_s * 1e3,
+                      "pair_kernel_ms": mk_ms, "pair_kernel_tflops": float(K) * K * d / (mk_ms / 1e3) / 1e12,
+                      "group_merge_ms": apply_s * 1e3, "centroids_after": cache.count}
+
+    out.update({"metric": "lookup_queries_per_s", "value": nb * steps / dt, "unit": "queries/s", "steps": steps,
+                "warmup": warmup, "ms_per_step": dt / steps * 1e3,
+                "config": {"workload": name, "centroids": K, "dim": d, "batch": nb, "thresholds": thetas,
+                           "step": "siso_lookup + siso_update_hits", "hit_rate_last_batch": hit_rate,
+                           "offline_merge": merge_info, "generate_s": round(gen_s, 1)},
+                "roofline": roof})
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(wl, nb, args.cpu_seconds)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,190 @@
+/*
+ * siso.h - C ABI of the centroid-based semantic cache hot path on one MI355X.
+ *
+ * The library keeps a bounded set of centroid vectors resident in GPU memory
+ * (the semantic cache C_cur of Algorithm 1, bounded by the capacity M) and
+ * offers the data-parallel operations on it:
+ *
+ *   lookup  - batched FindClosestCentroid with CosineSimilarity and the strict
+ *             threshold test that judges a cache hit (Algorithm 1,
+ *             MergeCentroids; section 3.1; batched online search: section 4.3);
+ *   update  - fold queries into their centroid, the centroid being the average
+ *             point of its group of vectors (section 3.1);
+ *   merge   - all-pairs centroid self-similarity above the clustering
+ *             threshold (the comparison inside MergeCentroids taken over all
+ *             pairs), then merging connected groups into their count-weighted
+ *             mean while their cluster sizes add up (Algorithm 1,
+ *             cluster_size).
+ *
+ * Conventions
+ *   - "device pointer" = memory of the current HIP device, owned by the caller,
+ *     row-major and contiguous, element type fixed when the cache is created
+ *     (SISO_BF16: 16-bit bfloat16 bit patterns; SISO_F32: float).
+ *     The library never keeps a caller pointer after the call's work has
+ *     finished on the stream.
+ *   - All GPU work is enqueued on the stream given to siso_set_stream (the
+ *     null stream by default).  siso_lookup, siso_update and siso_update_hits
+ *     never synchronise with the host; the other calls say when they do.
+ *   - Every call returns SISO_OK (0) or a negative error code; n = 0 is a
+ *     successful no-op.  siso_last_error gives a message for the last failure
+ *     on that cache.  No C++ exception crosses this boundary.
+ *   - The calls on one cache are not thread-safe against each other.
+ */
+#ifndef SISO_H
+#define SISO_H
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct siso_cache siso_cache; /* opaque; owns all centroid state on the device */
+
+enum { SISO_F32 = 0, SISO_BF16 = 1 };
+
+enum {
+    SISO_OK = 0,
+    SISO_EINVAL = -1,    /* NULL pointer, negative size, unsupported dimension, bad index */
+    SISO_ECAPACITY = -2, /* more rows than the cache was created for */
+    SISO_EHIP = -3,      /* a HIP runtime call failed */
+    SISO_ENOMEM = -4     /* device or host allocation failed */
+};
+
+/* Lookup kernel selection for siso_set_lookup_path. */
+enum {
+    SISO_PATH_AUTO = 0,   /* choose by element type, dimension and batch size       */
+    SISO_PATH_SCALAR = 1, /* LDS-tiled fp32 FMA kernel; any type and dimension       */
+    SISO_PATH_MFMA = 2,   /* fused bf16 MFMA GEMM + running arg-max (large batches)  */
+    SISO_PATH_SKINNY = 3  /* bandwidth-bound bf16 path for batches of at most 64     */
+};
+
+/*
+ * Create a cache for `capacity` centroids of `dim` elements (bf16 storage for
+ * siso_create).  dim must be in [1, 4096]; capacity in [1, 2^31 - 1].
+ * Allocates device memory: per centroid dim * (2 or 4) bytes for the stored
+ * vector, 4 * dim bytes for its running mean, 8 bytes for its inverse length
+ * and cluster size.  *out receives the handle.  Synchronises.
+ */
+int siso_create(int dim, long capacity, siso_cache **out);
+int siso_create_ex(int dim, long capacity, int dtype, siso_cache **out);
+
+/* Waits for the cache's stream, then frees everything the cache owns. */
+void siso_destroy(siso_cache *c);
+
+/* hip_stream: a hipStream_t (NULL = the null stream).  Later calls enqueue there. */
+int siso_set_stream(siso_cache *c, void *hip_stream);
+
+/* Force one lookup kernel (SISO_PATH_*); a path that cannot handle the cache's
+ * type or dimension, or the batch size of a later call, makes that call fail
+ * with SISO_EINVAL. */
+int siso_set_lookup_path(siso_cache *c, int path);
+
+/*
+ * Tuning knobs, for benchmarking; the defaults are chosen by the library.
+ *   "mfma_config"     0 = default; 1.. = a specific tile configuration of the MFMA lookup
+ *   "tiles_per_slice" 0 = default; >0 = centroid tiles one workgroup walks through
+ *   "merge_config"    0 = default; 1.. = a specific configuration of the MFMA pair search
+ * Unknown names or values out of range give SISO_EINVAL.
+ */
+int siso_set_option(siso_cache *c, const char *name, long value);
+
+/*
+ * Replace the cache contents by k centroids.
+ *   centroids: device pointer, [k][dim] in the cache's element type.  Rows are
+ *              stored as given (they need not be exactly unit length: lookups
+ *              compute true cosines of the stored values).
+ *   counts:    device pointer to k cluster sizes (each >= 1), or NULL for all 1.
+ * The running mean of each centroid starts as the row scaled to unit length.
+ * Fails with SISO_ECAPACITY if k exceeds the capacity.  Asynchronous.
+ */
+int siso_load(siso_cache *c, const void *centroids, const int *counts, long k);
+
+/* Number of live centroids (host-side value; no synchronisation). */
+long siso_count(const siso_cache *c);
+
+/*
+ * Batched lookup (section 4.3; FindClosestCentroid + CosineSimilarity + hit test).
+ *   queries:   device pointer, [n][dim]; need not be normalised.
+ *   threshold: the retrieval threshold for this call.
+ *   out_idx:   device pointer, n ints: index of the centroid with the largest
+ *              cosine similarity (the lowest index among equal maxima), whether
+ *              or not it is a hit; -1 for an empty cache or a query that holds
+ *              a NaN or an infinity.
+ *   out_sim:   device pointer, n floats: that similarity (-inf for an empty
+ *              cache, NaN for a non-finite query, 0 for a zero-length query).
+ *   out_hit:   device pointer, n bytes, or NULL: 1 where out_sim > threshold.
+ * The similarity matrix is never written to memory.  Asynchronous; may grow an
+ * internal workspace (which allocates) the first time a larger n is seen.
+ */
+int siso_lookup(siso_cache *c, const void *queries, long n, float threshold, int *out_idx, float *out_sim,
+                unsigned char *out_hit);
+
+/*
+ * Centroid update as a segmented mean keyed by the assigned index.
+ * For every centroid k with members I_k = { i : idx[i] == k }:
+ *     mean_k  <- (size_k * mean_k + sum_{i in I_k} q_i / |q_i|) / (size_k + |I_k|)
+ *     size_k  <- size_k + |I_k|
+ *     stored centroid_k <- mean_k / |mean_k| rounded to the element type
+ *                          (left alone if |mean_k| = 0)
+ *   queries: device pointer, [n][dim];  idx: device pointer, n ints.
+ * Entries with idx[i] < 0 are skipped, and so are zero-length and non-finite
+ * queries.  An idx[i] >= siso_count() is skipped too and counted: see
+ * siso_bad_indices.  All members of a centroid are taken in ascending i, so
+ * the result does not depend on scheduling.  Asynchronous.
+ *
+ * siso_update_hits folds only the entries with hit[i] != 0 (device pointer, n
+ * bytes): the outputs of siso_lookup can be passed on without touching the host.
+ */
+int siso_update(siso_cache *c, const void *queries, const int *idx, long n);
+int siso_update_hits(siso_cache *c, const void *queries, const int *idx, const unsigned char *hit, long n);
+
+/* Number of out-of-range indices seen by updates since the cache was created.
+ * Synchronises with the stream.  Negative = error code. */
+long siso_bad_indices(siso_cache *c);
+
+/*
+ * All-pairs self-similarity: every pair i < j of live centroids whose cosine
+ * similarity exceeds `threshold` (strictly).
+ *   out_pairs: device pointer, [cap][2] ints, in no particular order.
+ * Returns the total number of such pairs, which may exceed cap; only the first
+ * cap pairs found are written.  Negative = error code.  Synchronises.
+ */
+long siso_merge(siso_cache *c, float threshold, int *out_pairs, long cap);
+
+/*
+ * Merge the connected groups of the pair graph.
+ *   pairs: device pointer, [n_pairs][2] ints, each a pair of distinct live
+ *          indices in either order (SISO_EINVAL otherwise, nothing changed).
+ *   out_survivor: device pointer, [old count] ints, or NULL: new index of the
+ *          row that each old row was merged into.
+ * The lowest index of a group survives with mean = sum size_i mean_i / sum size_i,
+ * size = sum size_i, stored centroid = mean / |mean| rounded to the element
+ * type; rows in no pair are untouched.  Survivors are packed to the front in
+ * their old order and the count shrinks.  Allocates temporary device memory.
+ * Synchronises.
+ */
+int siso_merge_apply(siso_cache *c, const int *pairs, long n_pairs, int *out_survivor);
+
+/* Copy out the live rows (device pointers, any may be NULL): stored centroids
+ * [count][dim] in the element type, running means [count][dim] floats, cluster
+ * sizes [count] ints.  Asynchronous. */
+int siso_export(siso_cache *c, void *centroids, float *means, int *counts);
+
+/*
+ * Kernel timing for benchmarks.  While enabled (on != 0), every siso_lookup and
+ * siso_merge brackets its dominant kernel (the similarity kernel, without the
+ * norm and finalize kernels) with a pair of HIP events on the cache's stream.
+ * siso_profile_read synchronises with the stream, returns the sum of the
+ * bracketed durations in milliseconds and the number of brackets since the
+ * last read (host pointers, either may be NULL), and releases the events.
+ * At most 8192 brackets are kept between reads; later ones are not recorded.
+ */
+int siso_profile_enable(siso_cache *c, int on);
+int siso_profile_read(siso_cache *c, double *total_ms, long *launches);
+
+/* Message for the last error on this cache ("" if none).  Owned by the cache. */
+const char *siso_last_error(const siso_cache *c);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SISO_H */

@@ -1,0 +1,984 @@
+// C ABI of the centroid cache (include/siso.h): state management, the kernels
+// that are not matrix-shaped (row norms, finalize, update, group merge) and the
+// LDS-tiled fp32 kernels that serve any element type and dimension.
+#include <stdarg.h>
+#include <stdio.h>
+#include <stdlib.h>
+#include <string.h>
+
+#include <new>
+
+#include "siso_internal.h"
+
+// ============================================================================
+// error plumbing
+// ============================================================================
+int siso_fail(siso_cache *c, int code, const char *fmt, ...) {
+    if (c) {
+        va_list ap;
+        va_start(ap, fmt);
+        vsnprintf(c->err, sizeof(c->err), fmt, ap);
+        va_end(ap);
+    }
+    return code;
+}
+
+int siso_check_hip(siso_cache *c, hipError_t e, const char *what) {
+    if (e == hipSuccess) return SISO_OK;
+    return siso_fail(c, SISO_EHIP, "%s: %s", what, hipGetErrorString(e));
+}
+
+#define HIP_TRY(c, call)                                          \
+    do {                                                          \
+        int rc_ = siso_check_hip((c), (call), #call);             \
+        if (rc_ != SISO_OK) return rc_;                           \
+    } while (0)
+
+#define SISO_PROF_MAX 8192
+
+void siso_prof_begin(siso_cache *c) {
+    if (!c->profile_on || c->prof_count >= SISO_PROF_MAX) return;
+    if (!c->prof_ev) {
+        c->prof_ev = (hipEvent_t *)calloc(2 * SISO_PROF_MAX, sizeof(hipEvent_t));
+        if (!c->prof_ev) return;
+    }
+    hipEvent_t *e = c->prof_ev + 2 * c->prof_count;
+    if (hipEventCreate(&e[0]) != hipSuccess || hipEventCreate(&e[1]) != hipSuccess) return;
+    (void)hipEventRecord(e[0], c->stream);
+}
+
+void siso_prof_end(siso_cache *c) {
+    if (!c->profile_on || !c->prof_ev || c->prof_count >= SISO_PROF_MAX) return;
+    hipEvent_t *e = c->prof_ev + 2 * c->prof_count;
+    if (!e[0] || !e[1]) return;
+    (void)hipEventRecord(e[1], c->stream);
+    c->prof_count++;
+}
+
+static inline size_t elem_bytes(int dtype) { return dtype == SISO_F32 ? 4 : 2; }
+
+// ============================================================================
+// small kernels
+// ============================================================================
+// Block-wide sum for 256-thread blocks; every thread gets the result.
+__device__ __forceinline__ float block_sum256(float v, float *sh) {
+    v = wave_sum(v);
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = v;
+    __syncthreads();
+    return (sh[0] + sh[1]) + (sh[2] + sh[3]);
+}
+
+// siso_load: store rows verbatim, mean = row / |row|, size = counts or 1, invn = 1/|row|.
+template <typename T>
+__global__ __launch_bounds__(256) void k_load_rows(const T *__restrict__ src, const int *__restrict__ counts, T *cent,
+                                                    float *mean, int *size, float *invn, int d) {
+    __shared__ float sh[4];
+    const long k = blockIdx.x;
+    const T *row = src + (size_t)k * d;
+    float ss = 0.f;
+    for (int e = threadIdx.x; e < d; e += 256) {
+        float x = widen(row[e]);
+        ss += x * x;
+    }
+    const float n2 = block_sum256(ss, sh);
+    const float inv = inv_length(n2);
+    const bool ok = (inv == inv) && inv > 0.f;
+    const float nrm = sqrtf(n2);
+    for (int e = threadIdx.x; e < d; e += 256) {
+        T x = row[e];
+        cent[(size_t)k * d + e] = x;
+        mean[(size_t)k * d + e] = ok ? widen(x) / nrm : 0.f;
+    }
+    if (threadIdx.x == 0) {
+        int s = counts ? counts[k] : 1;
+        size[k] = s < 1 ? 1 : s;
+        invn[k] = inv;
+    }
+}
+
+// 1/|q| for every query: one wavefront per row.
+template <typename T>
+__global__ __launch_bounds__(256) void k_query_invnorm(const T *__restrict__ Q, long n, int d, float *qinv) {
+    const long q = (long)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (q >= n) return;
+    const int lane = threadIdx.x & 63;
+    const T *row = Q + (size_t)q * d;
+    float ss = 0.f;
+    for (int e = lane; e < d; e += 64) {
+        float x = widen(row[e]);
+        ss += x * x;
+    }
+    ss = wave_sum(ss);
+    if (lane == 0) qinv[q] = inv_length(ss);
+}
+
+// Finalize: per query, max over the slice keys, then the exact cosines of the
+// winning block of SISO_BLOCK_ROWS centroids (ascending, strict ">" so the lowest
+// index keeps a tie), and the strict threshold test.  One wavefront per query.
+template <typename T>
+__global__ __launch_bounds__(256) void k_lookup_finalize(const T *__restrict__ Q, const T *__restrict__ cent,
+                                                          const float *__restrict__ invn,
+                                                          const float *__restrict__ qinv, const u64 *__restrict__ keys,
+                                                          long n, long K, int d, int slices, float threshold,
+                                                          int *out_idx, float *out_sim, unsigned char *out_hit) {
+    const long q = (long)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (q >= n) return;
+    const int lane = threadIdx.x & 63;
+    const float qi = qinv[q];
+    int best_i = -1;
+    float best_s = -INFINITY;
+    if (!(qi == qi)) {
+        best_s = __uint_as_float(0x7FC00000u);
+    } else if (K > 0) {
+        u64 key = 0;
+        for (int s = lane; s < slices; s += 64) {
+            u64 k2 = keys[(size_t)q * slices + s];
+            key = k2 > key ? k2 : key;
+        }
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) {
+            u64 o = __shfl_xor(key, off);
+            key = o > key ? o : key;
+        }
+        if (key != 0) {
+            const long block = (long)(0xFFFFFFFFu - (unsigned)(key & 0xFFFFFFFFull));
+            const long r0 = block * SISO_BLOCK_ROWS;
+            const long r1 = (r0 + SISO_BLOCK_ROWS < K) ? r0 + SISO_BLOCK_ROWS : K;
+            const T *qrow = Q + (size_t)q * d;
+            for (long r = r0; r < r1; ++r) {
+                const T *crow = cent + (size_t)r * d;
+                float acc = 0.f;
+                for (int e = lane; e < d; e += 64) acc += widen(qrow[e]) * widen(crow[e]);
+                acc = wave_sum(acc);
+                const float s = acc * qi * invn[r];
+                if (s > best_s) {
+                    best_s = s;
+                    best_i = (int)r;
+                }
+            }
+        }
+    }
+    if (lane == 0) {
+        out_idx[q] = best_i;
+        out_sim[q] = best_s;
+        if (out_hit) out_hit[q] = (best_i >= 0 && best_s > threshold) ? 1 : 0;
+    }
+}
+
+// ============================================================================
+// LDS-tiled fp32 GEMM core shared by the scalar lookup and scalar merge kernels:
+// a 64 x 64 tile of dot products per 256-thread block, thread (ty, tx) owning
+// rows ty*4..+4 of A and rows tx*4..+4 of B.
+// ============================================================================
+#define ST_M 64
+#define ST_K 16
+
+template <typename T>
+__device__ __forceinline__ void scalar_tile(const T *__restrict__ A, long a0, long a_end, const T *__restrict__ B,
+                                            long b0, long b_end, int d, float (*As)[ST_M + 4],
+                                            float (*Bs)[ST_M + 4], float acc[4][4]) {
+    const int t = threadIdx.x;
+    const int tx = t & 15, ty = t >> 4;
+    const int lr = t >> 2, lk = (t & 3) * 4;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[i][j] = 0.f;
+    for (int k0 = 0; k0 < d; k0 += ST_K) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const int k = k0 + lk + e;
+            const long ar = a0 + lr, br = b0 + lr;
+            As[lk + e][lr] = (ar < a_end && k < d) ? widen(A[(size_t)ar * d + k]) : 0.f;
+            Bs[lk + e][lr] = (br < b_end && k < d) ? widen(B[(size_t)br * d + k]) : 0.f;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int kk = 0; kk < ST_K; ++kk) {
+            float a[4], b[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) a[i] = As[kk][ty * 4 + i];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) b[j] = Bs[kk][tx * 4 + j];
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) acc[i][j] = fmaf(a[i], b[j], acc[i][j]);
+        }
+        __syncthreads();
+    }
+}
+
+// Phase 1, scalar path: block (x = query tile, y = slice of the centroid range).
+template <typename T>
+__global__ __launch_bounds__(256) void k_lookup_scalar(const T *__restrict__ Q, const T *__restrict__ cent,
+                                                        const float *__restrict__ invn, long n, long K, int d,
+                                                        long rows_per_slice, int slices, u64 *keys) {
+    __shared__ float As[ST_K][ST_M + 4];
+    __shared__ float Bs[ST_K][ST_M + 4];
+    const long q0 = (long)blockIdx.x * ST_M;
+    const int s = blockIdx.y;
+    const long c_begin = (long)s * rows_per_slice;
+    const long c_end = (c_begin + rows_per_slice < K) ? c_begin + rows_per_slice : K;
+    const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
+    float best[4];
+    long bidx[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        best[i] = -INFINITY;
+        bidx[i] = -1;
+    }
+    for (long c0 = c_begin; c0 < c_end; c0 += ST_M) {
+        float acc[4][4];
+        scalar_tile(Q, q0, n, cent, c0, c_end, d, As, Bs, acc);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const long cidx = c0 + tx * 4 + j;
+            if (cidx < c_end) {
+                const float w = invn[cidx];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const float v = acc[i][j] * w;
+                    if (v > best[i]) {
+                        best[i] = v;
+                        bidx[i] = cidx;
+                    }
+                }
+            }
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+#pragma unroll
+        for (int off = 1; off < 16; off <<= 1) {
+            const float ov = __shfl_xor(best[i], off);
+            const long oi = __shfl_xor(bidx[i], off);
+            if (oi >= 0 && (bidx[i] < 0 || ov > best[i] || (ov == best[i] && oi < bidx[i]))) {
+                best[i] = ov;
+                bidx[i] = oi;
+            }
+        }
+        const long q = q0 + ty * 4 + i;
+        if (tx == 0 && q < n)
+            keys[(size_t)q * slices + s] = bidx[i] < 0 ? 0ull : pack_key(best[i], (unsigned)(bidx[i] / SISO_BLOCK_ROWS));
+    }
+}
+
+int siso_scalar_slices(const siso_cache *c, long n) {
+    // enough blocks to fill the chip, at least one 64-row tile per slice
+    const long qtiles = (n + ST_M - 1) / ST_M;
+    const long ctiles = (c->count + ST_M - 1) / ST_M;
+    long want = (2048 + qtiles - 1) / qtiles;
+    if (want > ctiles) want = ctiles;
+    if (want < 1) want = 1;
+    if (want > 65535) want = 65535;
+    return (int)want;
+}
+
+template <typename T>
+static int scalar_launch_t(siso_cache *c, const void *queries, long n, int slices) {
+    const long ctiles = (c->count + ST_M - 1) / ST_M;
+    const long rows_per_slice = ((ctiles + slices - 1) / slices) * ST_M;
+    dim3 grid((unsigned)((n + ST_M - 1) / ST_M), (unsigned)slices);
+    hipLaunchKernelGGL(k_lookup_scalar<T>, grid, dim3(256), 0, c->stream, (const T *)queries, (const T *)c->cent,
+                       c->invn, n, c->count, c->dim, rows_per_slice, slices, c->keys);
+    return siso_check_hip(c, hipGetLastError(), "k_lookup_scalar");
+}
+
+int siso_scalar_launch(siso_cache *c, const void *queries, long n, int slices) {
+    return c->dtype == SISO_F32 ? scalar_launch_t<float>(c, queries, n, slices)
+                                : scalar_launch_t<bf16_t>(c, queries, n, slices);
+}
+
+// Self-similarity, scalar path: block (x, y) = tile pair, upper triangle only.
+template <typename T>
+__global__ __launch_bounds__(256) void k_merge_scalar(const T *__restrict__ cent, const float *__restrict__ invn, long K,
+                                                       int d, float threshold, int *out_pairs, long cap, u64 *counter) {
+    if (blockIdx.x > blockIdx.y) return;
+    __shared__ float As[ST_K][ST_M + 4];
+    __shared__ float Bs[ST_K][ST_M + 4];
+    const long i0 = (long)blockIdx.x * ST_M, j0 = (long)blockIdx.y * ST_M;
+    const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
+    float acc[4][4];
+    scalar_tile(cent, i0, K, cent, j0, K, d, As, Bs, acc);
+#pragma unroll
+    for (int a = 0; a < 4; ++a) {
+        const long i = i0 + ty * 4 + a;
+        const float wi = i < K ? invn[i] : 0.f;
+#pragma unroll
+        for (int b = 0; b < 4; ++b) {
+            const long j = j0 + tx * 4 + b;
+            const float wj = j < K ? invn[j] : 0.f;
+            const float s = acc[a][b] * wi * wj;
+            emit_pair(i < j && j < K && s > threshold, (int)i, (int)j, out_pairs, cap, counter);
+        }
+    }
+}
+
+int siso_merge_scalar_launch(siso_cache *c, float threshold, int *out_pairs, long cap) {
+    const unsigned tiles = (unsigned)((c->count + ST_M - 1) / ST_M);
+    if (tiles > 65535u) return siso_fail(c, SISO_EINVAL, "scalar merge path handles at most %d centroids", 65535 * ST_M);
+    dim3 grid(tiles, tiles);
+    if (c->dtype == SISO_F32)
+        hipLaunchKernelGGL(k_merge_scalar<float>, grid, dim3(256), 0, c->stream, (const float *)c->cent, c->invn,
+                           c->count, c->dim, threshold, out_pairs, cap, c->counters + 1);
+    else
+        hipLaunchKernelGGL(k_merge_scalar<bf16_t>, grid, dim3(256), 0, c->stream, (const bf16_t *)c->cent, c->invn,
+                           c->count, c->dim, threshold, out_pairs, cap, c->counters + 1);
+    return siso_check_hip(c, hipGetLastError(), "k_merge_scalar");
+}
+
+// ============================================================================
+// centroid update: one block per query; the block of the first member of a
+// centroid sums all members in ascending order and rewrites the centroid.
+// ============================================================================
+#define UPD_MAXE (SISO_MAX_DIM / 256)
+
+template <typename T>
+__global__ __launch_bounds__(256) void k_update(const T *__restrict__ Q, const int *__restrict__ idx,
+                                                 const unsigned char *__restrict__ hit, long n, T *cent, float *mean,
+                                                 int *size, float *invn, long count, int d, u64 *bad) {
+    __shared__ float sh[4];
+    __shared__ u64 masks[4];
+    const long me = blockIdx.x;
+    const int t = threadIdx.x;
+    if (hit && !hit[me]) return;
+    const int k = idx[me];
+    if (k < 0) return;
+    if (k >= count) {
+        if (t == 0) atomicAdd(bad, 1ull);
+        return;
+    }
+    float acc[UPD_MAXE];
+#pragma unroll
+    for (int e = 0; e < UPD_MAXE; ++e) acc[e] = 0.f;
+    int members = 0;
+    for (long base = 0; base < n; base += 256) {
+        const long j = base + t;
+        const bool m = j < n && idx[j] == k && (!hit || hit[j]);
+        const u64 mask = __ballot(m);
+        __syncthreads();
+        if ((t & 63) == 0) masks[t >> 6] = mask;
+        __syncthreads();
+        for (int w = 0; w < 4; ++w) {
+            u64 mm = masks[w];
+            while (mm) {
+                const int b = __ffsll((long long)mm) - 1;
+                mm &= mm - 1;
+                const long jj = base + w * 64 + b;
+                if (jj < me) return;  // an earlier member leads this centroid (uniform over the block)
+                float x[UPD_MAXE];
+                float ss = 0.f;
+#pragma unroll
+                for (int e = 0; e < UPD_MAXE; ++e) {
+                    const int col = t + e * 256;
+                    x[e] = col < d ? widen(Q[(size_t)jj * d + col]) : 0.f;
+                    ss += x[e] * x[e];
+                }
+                const float n2 = block_sum256(ss, sh);
+                const float inv = inv_length(n2);
+                if (inv == inv && inv > 0.f) {
+                    const float nrm = sqrtf(n2);
+#pragma unroll
+                    for (int e = 0; e < UPD_MAXE; ++e) acc[e] += x[e] / nrm;
+                    ++members;
+                }
+            }
+        }
+    }
+    if (members == 0) return;
+    const float n_old = (float)size[k];
+    const float n_new = n_old + (float)members;
+    float m[UPD_MAXE];
+    float ss = 0.f;
+#pragma unroll
+    for (int e = 0; e < UPD_MAXE; ++e) {
+        const int col = t + e * 256;
+        m[e] = 0.f;
+        if (col < d) {
+            m[e] = (n_old * mean[(size_t)k * d + col] + acc[e]) / n_new;
+            mean[(size_t)k * d + col] = m[e];
+            ss += m[e] * m[e];
+        }
+    }
+    const float n2 = block_sum256(ss, sh);
+    if (t == 0) size[k] += members;
+    if (!(n2 > 0.f) || n2 > 3.0e38f) return;
+    const float nrm = sqrtf(n2);
+    float cs = 0.f;
+#pragma unroll
+    for (int e = 0; e < UPD_MAXE; ++e) {
+        const int col = t + e * 256;
+        if (col < d) {
+            T r;
+            narrow(m[e] / nrm, &r);
+            cent[(size_t)k * d + col] = r;
+            const float back = widen(r);
+            cs += back * back;
+        }
+    }
+    const float c2 = block_sum256(cs, sh);
+    if (t == 0) invn[k] = inv_length(c2);
+}
+
+// ============================================================================
+// group merge: lock-free union-find (the lower index becomes the root), group
+// means by the group's root, stable compaction.
+// ============================================================================
+__global__ void k_pairs_validate(const int *__restrict__ pairs, long n_pairs, long K, u64 *bad) {
+    const long p = (long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (p >= n_pairs) return;
+    const int a = pairs[2 * p], b = pairs[2 * p + 1];
+    if (a < 0 || b < 0 || a >= K || b >= K || a == b) atomicAdd(bad, 1ull);
+}
+
+__global__ void k_uf_init(int *parent, unsigned char *touched, long K) {
+    const long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < K) {
+        parent[i] = (int)i;
+        touched[i] = 0;
+    }
+}
+
+__device__ __forceinline__ int uf_find(const int *parent, int x) {
+    int p = __atomic_load_n(parent + x, __ATOMIC_RELAXED);
+    while (p != x) {
+        x = p;
+        p = __atomic_load_n(parent + x, __ATOMIC_RELAXED);
+    }
+    return x;
+}
+
+// Parents only ever decrease, so every retry makes progress and the loop ends.
+__global__ void k_uf_hook(const int *__restrict__ pairs, long n_pairs, int *parent, unsigned char *touched) {
+    const long p = (long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (p >= n_pairs) return;
+    int a = pairs[2 * p], b = pairs[2 * p + 1];
+    touched[a] = 1;
+    touched[b] = 1;
+    for (;;) {
+        a = uf_find(parent, a);
+        b = uf_find(parent, b);
+        if (a == b) break;
+        const int hi = a > b ? a : b, lo = a > b ? b : a;
+        const int old = atomicCAS(parent + hi, hi, lo);
+        if (old == hi) break;
+        a = old;  // someone re-parented hi meanwhile: continue from there
+        b = lo;
+    }
+}
+
+__global__ void k_uf_roots(const int *__restrict__ parent, int *root, long K) {
+    const long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < K) root[i] = uf_find(parent, (int)i);
+}
+
+// One block per row; only roots of groups with at least two rows work.
+template <typename T>
+__global__ __launch_bounds__(256) void k_group_mean(const int *__restrict__ root, const unsigned char *__restrict__ touched,
+                                                     long K, T *cent, float *mean, int *size, float *invn, int d) {
+    __shared__ float sh[4];
+    __shared__ u64 masks[4];
+    const long r = blockIdx.x;
+    const int t = threadIdx.x;
+    if (!touched[r] || root[r] != (int)r) return;
+    float acc[UPD_MAXE];
+#pragma unroll
+    for (int e = 0; e < UPD_MAXE; ++e) acc[e] = 0.f;
+    double wsum = 0.0;
+    int members = 0;
+    for (long base = r - (r & 255); base < K; base += 256) {
+        const long j = base + t;
+        const bool m = j < K && j >= r && root[j] == (int)r;
+        const u64 mask = __ballot(m);
+        __syncthreads();
+        if ((t & 63) == 0) masks[t >> 6] = mask;
+        __syncthreads();
+        for (int w = 0; w < 4; ++w) {
+            u64 mm = masks[w];
+            while (mm) {
+                const int b = __ffsll((long long)mm) - 1;
+                mm &= mm - 1;
+                const long jj = base + w * 64 + b;
+                const float wgt = (float)size[jj];
+#pragma unroll
+                for (int e = 0; e < UPD_MAXE; ++e) {
+                    const int col = t + e * 256;
+                    if (col < d) acc[e] += wgt * mean[(size_t)jj * d + col];
+                }
+                wsum += (double)size[jj];
+                ++members;
+            }
+        }
+    }
+    if (members < 2) return;
+    const float wtot = (float)wsum;
+    float m[UPD_MAXE];
+    float ss = 0.f;
+#pragma unroll
+    for (int e = 0; e < UPD_MAXE; ++e) {
+        const int col = t + e * 256;
+        m[e] = 0.f;
+        if (col < d) {
+            m[e] = acc[e] / wtot;
+            mean[(size_t)r * d + col] = m[e];
+            ss += m[e] * m[e];
+        }
+    }
+    const float n2 = block_sum256(ss, sh);
+    if (t == 0) size[r] = wsum > 2147483647.0 ? 2147483647 : (int)wsum;
+    if (!(n2 > 0.f) || n2 > 3.0e38f) return;
+    const float nrm = sqrtf(n2);
+    float cs = 0.f;
+#pragma unroll
+    for (int e = 0; e < UPD_MAXE; ++e) {
+        const int col = t + e * 256;
+        if (col < d) {
+            T v;
+            narrow(m[e] / nrm, &v);
+            cent[(size_t)r * d + col] = v;
+            const float back = widen(v);
+            cs += back * back;
+        }
+    }
+    const float c2 = block_sum256(cs, sh);
+    if (t == 0) invn[r] = inv_length(c2);
+}
+
+// Exclusive scan of the "row survives" flags by one 1024-thread block; total -> *total.
+__global__ __launch_bounds__(1024) void k_scan_survivors(const int *__restrict__ root, long K, int *newpos, u64 *total) {
+    __shared__ int wsum[16];
+    __shared__ int carry_s;
+    const int t = threadIdx.x, lane = t & 63, w = t >> 6;
+    if (t == 0) carry_s = 0;
+    __syncthreads();
+    for (long base = 0; base < K; base += 1024) {
+        const long i = base + t;
+        const int flag = (i < K && root[i] == (int)i) ? 1 : 0;
+        int incl = flag;
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {
+            const int o = __shfl_up(incl, off);
+            if (lane >= off) incl += o;
+        }
+        if (lane == 63) wsum[w] = incl;
+        __syncthreads();
+        int before = carry_s;
+        for (int k = 0; k < w; ++k) before += wsum[k];
+        if (i < K) newpos[i] = before + incl - flag;
+        __syncthreads();
+        if (t == 1023) carry_s = before + incl;
+        __syncthreads();
+    }
+    if (t == 0) *total = (u64)carry_s;
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void k_gather_rows(const int *__restrict__ root, const int *__restrict__ newpos,
+                                                      const T *__restrict__ cent, const float *__restrict__ mean,
+                                                      const int *__restrict__ size, const float *__restrict__ invn,
+                                                      T *cent2, float *mean2, int *size2, float *invn2, int d) {
+    const long i = blockIdx.x;
+    if (root[i] != (int)i) return;
+    const long p = newpos[i];
+    for (int e = threadIdx.x; e < d; e += 256) {
+        cent2[(size_t)p * d + e] = cent[(size_t)i * d + e];
+        mean2[(size_t)p * d + e] = mean[(size_t)i * d + e];
+    }
+    if (threadIdx.x == 0) {
+        size2[p] = size[i];
+        invn2[p] = invn[i];
+    }
+}
+
+__global__ void k_survivor_map(const int *__restrict__ root, const int *__restrict__ newpos, long K, int *out) {
+    const long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < K) out[i] = newpos[root[i]];
+}
+
+// ============================================================================
+// C ABI
+// ============================================================================
+static int ensure_workspace(siso_cache *c, long n, int slices) {
+    const long need_keys = n * (long)slices;
+    if (need_keys > c->keys_cap) {
+        if (c->keys) {
+            HIP_TRY(c, hipStreamSynchronize(c->stream));
+            HIP_TRY(c, hipFree(c->keys));
+            c->keys = nullptr;
+            c->keys_cap = 0;
+        }
+        if (hipMalloc((void **)&c->keys, (size_t)need_keys * sizeof(u64)) != hipSuccess) {
+            (void)hipGetLastError();
+            return siso_fail(c, SISO_ENOMEM, "workspace of %ld keys", need_keys);
+        }
+        c->keys_cap = need_keys;
+    }
+    if (n > c->qinv_cap) {
+        if (c->qinv) {
+            HIP_TRY(c, hipStreamSynchronize(c->stream));
+            HIP_TRY(c, hipFree(c->qinv));
+            c->qinv = nullptr;
+            c->qinv_cap = 0;
+        }
+        if (hipMalloc((void **)&c->qinv, (size_t)n * sizeof(float)) != hipSuccess) {
+            (void)hipGetLastError();
+            return siso_fail(c, SISO_ENOMEM, "workspace of %ld query norms", n);
+        }
+        c->qinv_cap = n;
+    }
+    return SISO_OK;
+}
+
+extern "C" int siso_create_ex(int dim, long capacity, int dtype, siso_cache **out) {
+    if (!out) return SISO_EINVAL;
+    *out = nullptr;
+    if (dim < 1 || dim > SISO_MAX_DIM || capacity < 1 || capacity > 2147483647L ||
+        (dtype != SISO_F32 && dtype != SISO_BF16))
+        return SISO_EINVAL;
+    siso_cache *c = new (std::nothrow) siso_cache();
+    if (!c) return SISO_ENOMEM;
+    memset(c, 0, sizeof(*c));
+    c->dim = dim;
+    c->capacity = capacity;
+    c->dtype = dtype;
+    c->path = SISO_PATH_AUTO;
+    const size_t cells = (size_t)capacity * dim;
+    bool ok = hipGetDevice(&c->device) == hipSuccess;
+    // The stored centroids carry SISO_PAD_ROWS readable rows past the capacity, so that the
+    // tiled kernels may load a whole last tile; their results are discarded.
+    const size_t cent_bytes = (cells + (size_t)SISO_PAD_ROWS * dim) * elem_bytes(dtype);
+    ok = ok && hipMalloc(&c->cent, cent_bytes) == hipSuccess;
+    ok = ok && hipMemset(c->cent, 0, cent_bytes) == hipSuccess;
+    ok = ok && hipMalloc((void **)&c->mean, cells * sizeof(float)) == hipSuccess;
+    ok = ok && hipMalloc((void **)&c->size, (size_t)capacity * sizeof(int)) == hipSuccess;
+    ok = ok && hipMalloc((void **)&c->invn, (size_t)capacity * sizeof(float)) == hipSuccess;
+    ok = ok && hipMalloc((void **)&c->counters, 4 * sizeof(u64)) == hipSuccess;
+    ok = ok && hipHostMalloc((void **)&c->host_pin, 4 * sizeof(u64), hipHostMallocDefault) == hipSuccess;
+    ok = ok && hipMemset(c->counters, 0, 4 * sizeof(u64)) == hipSuccess;
+    ok = ok && hipDeviceSynchronize() == hipSuccess;
+    if (!ok) {
+        (void)hipGetLastError();
+        siso_destroy(c);
+        return SISO_ENOMEM;
+    }
+    *out = c;
+    return SISO_OK;
+}
+
+extern "C" int siso_create(int dim, long capacity, siso_cache **out) {
+    return siso_create_ex(dim, capacity, SISO_BF16, out);
+}
+
+extern "C" void siso_destroy(siso_cache *c) {
+    if (!c) return;
+    (void)hipStreamSynchronize(c->stream);
+    if (c->cent) (void)hipFree(c->cent);
+    if (c->mean) (void)hipFree(c->mean);
+    if (c->size) (void)hipFree(c->size);
+    if (c->invn) (void)hipFree(c->invn);
+    if (c->keys) (void)hipFree(c->keys);
+    if (c->qinv) (void)hipFree(c->qinv);
+    if (c->counters) (void)hipFree(c->counters);
+    if (c->host_pin) (void)hipHostFree(c->host_pin);
+    if (c->prof_ev) {
+        for (int i = 0; i < 2 * SISO_PROF_MAX; ++i)
+            if (c->prof_ev[i]) (void)hipEventDestroy(c->prof_ev[i]);
+        free(c->prof_ev);
+    }
+    delete c;
+}
+
+extern "C" int siso_set_stream(siso_cache *c, void *hip_stream) {
+    if (!c) return SISO_EINVAL;
+    c->stream = (hipStream_t)hip_stream;
+    return SISO_OK;
+}
+
+extern "C" int siso_set_lookup_path(siso_cache *c, int path) {
+    if (!c) return SISO_EINVAL;
+    if (path < SISO_PATH_AUTO || path > SISO_PATH_SKINNY) return siso_fail(c, SISO_EINVAL, "unknown lookup path %d", path);
+    c->path = path;
+    return SISO_OK;
+}
+
+extern "C" int siso_set_option(siso_cache *c, const char *name, long value) {
+    if (!c || !name) return SISO_EINVAL;
+    if (value < 0 || value > 1000000) return siso_fail(c, SISO_EINVAL, "option %s: value %ld out of range", name, value);
+    if (!strcmp(name, "mfma_config")) c->opt_mfma_config = (int)value;
+    else if (!strcmp(name, "tiles_per_slice")) c->opt_tiles_per_slice = (int)value;
+    else if (!strcmp(name, "merge_config")) c->opt_merge_config = (int)value;
+    else return siso_fail(c, SISO_EINVAL, "unknown option %s", name);
+    return SISO_OK;
+}
+
+extern "C" long siso_count(const siso_cache *c) { return c ? c->count : (long)SISO_EINVAL; }
+
+extern "C" const char *siso_last_error(const siso_cache *c) { return c ? c->err : "null cache"; }
+
+extern "C" int siso_load(siso_cache *c, const void *centroids, const int *counts, long k) {
+    if (!c) return SISO_EINVAL;
+    if (k < 0 || (k > 0 && !centroids)) return siso_fail(c, SISO_EINVAL, "siso_load: bad arguments");
+    if (k > c->capacity) return siso_fail(c, SISO_ECAPACITY, "siso_load: %ld rows exceed capacity %ld", k, c->capacity);
+    if (k > 0) {
+        if (c->dtype == SISO_F32)
+            hipLaunchKernelGGL(k_load_rows<float>, dim3((unsigned)k), dim3(256), 0, c->stream, (const float *)centroids,
+                               counts, (float *)c->cent, c->mean, c->size, c->invn, c->dim);
+        else
+            hipLaunchKernelGGL(k_load_rows<bf16_t>, dim3((unsigned)k), dim3(256), 0, c->stream,
+                               (const bf16_t *)centroids, counts, (bf16_t *)c->cent, c->mean, c->size, c->invn, c->dim);
+        HIP_TRY(c, hipGetLastError());
+    }
+    c->count = k;
+    return SISO_OK;
+}
+
+static int choose_path(const siso_cache *c, long n) {
+    if (c->path != SISO_PATH_AUTO) return c->path;
+    if (n <= 64 && siso_skinny_slices(c, n) > 0) return SISO_PATH_SKINNY;
+    if (siso_mfma_slices(c, n) > 0) return SISO_PATH_MFMA;
+    return SISO_PATH_SCALAR;
+}
+
+extern "C" int siso_lookup(siso_cache *c, const void *queries, long n, float threshold, int *out_idx, float *out_sim,
+                           unsigned char *out_hit) {
+    if (!c) return SISO_EINVAL;
+    if (n < 0 || (n > 0 && (!queries || !out_idx || !out_sim)))
+        return siso_fail(c, SISO_EINVAL, "siso_lookup: bad arguments");
+    if (n == 0) return SISO_OK;
+    if (n > 2147483647L / 4) return siso_fail(c, SISO_EINVAL, "siso_lookup: batch of %ld is too large", n);
+    int slices = 1;
+    const int path = c->count > 0 ? choose_path(c, n) : SISO_PATH_SCALAR;
+    if (c->count > 0) {
+        switch (path) {
+            case SISO_PATH_SCALAR: slices = siso_scalar_slices(c, n); break;
+            case SISO_PATH_MFMA: slices = siso_mfma_slices(c, n); break;
+            case SISO_PATH_SKINNY: slices = siso_skinny_slices(c, n); break;
+        }
+        if (slices <= 0)
+            return siso_fail(c, SISO_EINVAL, "siso_lookup: path %d cannot serve dim %d, type %d, batch %ld", path,
+                             c->dim, c->dtype, n);
+    }
+    int rc = ensure_workspace(c, n, slices);
+    if (rc != SISO_OK) return rc;
+    const unsigned qblocks = (unsigned)((n + 3) / 4);
+    if (c->dtype == SISO_F32)
+        hipLaunchKernelGGL(k_query_invnorm<float>, dim3(qblocks), dim3(256), 0, c->stream, (const float *)queries, n,
+                           c->dim, c->qinv);
+    else
+        hipLaunchKernelGGL(k_query_invnorm<bf16_t>, dim3(qblocks), dim3(256), 0, c->stream, (const bf16_t *)queries, n,
+                           c->dim, c->qinv);
+    HIP_TRY(c, hipGetLastError());
+    if (c->count > 0) {
+        siso_prof_begin(c);
+        switch (path) {
+            case SISO_PATH_SCALAR: rc = siso_scalar_launch(c, queries, n, slices); break;
+            case SISO_PATH_MFMA: rc = siso_mfma_launch(c, queries, n, slices); break;
+            case SISO_PATH_SKINNY: rc = siso_skinny_launch(c, queries, n, slices); break;
+        }
+        siso_prof_end(c);
+        if (rc != SISO_OK) return rc;
+    }
+    if (c->dtype == SISO_F32)
+        hipLaunchKernelGGL(k_lookup_finalize<float>, dim3(qblocks), dim3(256), 0, c->stream, (const float *)queries,
+                           (const float *)c->cent, c->invn, c->qinv, c->keys, n, c->count, c->dim, slices, threshold,
+                           out_idx, out_sim, out_hit);
+    else
+        hipLaunchKernelGGL(k_lookup_finalize<bf16_t>, dim3(qblocks), dim3(256), 0, c->stream, (const bf16_t *)queries,
+                           (const bf16_t *)c->cent, c->invn, c->qinv, c->keys, n, c->count, c->dim, slices, threshold,
+                           out_idx, out_sim, out_hit);
+    HIP_TRY(c, hipGetLastError());
+    return SISO_OK;
+}
+
+#define UPDATE_CHUNK 32768L
+
+extern "C" int siso_update_hits(siso_cache *c, const void *queries, const int *idx, const unsigned char *hit, long n) {
+    if (!c) return SISO_EINVAL;
+    if (n < 0 || (n > 0 && (!queries || !idx))) return siso_fail(c, SISO_EINVAL, "siso_update: bad arguments");
+    // A running mean folds chunk after chunk to the same mean as one big batch,
+    // so very large batches are cut to bound the member scan of each block.
+    for (long off = 0; off < n; off += UPDATE_CHUNK) {
+        const long m = (n - off < UPDATE_CHUNK) ? n - off : UPDATE_CHUNK;
+        const unsigned char *h = hit ? hit + off : nullptr;
+        if (c->dtype == SISO_F32)
+            hipLaunchKernelGGL(k_update<float>, dim3((unsigned)m), dim3(256), 0, c->stream,
+                               (const float *)queries + (size_t)off * c->dim, idx + off, h, m, (float *)c->cent,
+                               c->mean, c->size, c->invn, c->count, c->dim, c->counters);
+        else
+            hipLaunchKernelGGL(k_update<bf16_t>, dim3((unsigned)m), dim3(256), 0, c->stream,
+                               (const bf16_t *)queries + (size_t)off * c->dim, idx + off, h, m, (bf16_t *)c->cent,
+                               c->mean, c->size, c->invn, c->count, c->dim, c->counters);
+        HIP_TRY(c, hipGetLastError());
+    }
+    return SISO_OK;
+}
+
+extern "C" int siso_update(siso_cache *c, const void *queries, const int *idx, long n) {
+    return siso_update_hits(c, queries, idx, nullptr, n);
+}
+
+static int read_counter(siso_cache *c, int which, u64 *value) {
+    HIP_TRY(c, hipMemcpyAsync(c->host_pin, c->counters, 4 * sizeof(u64), hipMemcpyDeviceToHost, c->stream));
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    *value = c->host_pin[which];
+    return SISO_OK;
+}
+
+__global__ void k_zero_counter(u64 *p) { *p = 0; }
+
+extern "C" long siso_bad_indices(siso_cache *c) {
+    if (!c) return SISO_EINVAL;
+    u64 v = 0;
+    const int rc = read_counter(c, 0, &v);
+    return rc != SISO_OK ? (long)rc : (long)v;
+}
+
+extern "C" long siso_merge(siso_cache *c, float threshold, int *out_pairs, long cap) {
+    if (!c) return SISO_EINVAL;
+    if (cap < 0 || (cap > 0 && !out_pairs)) return siso_fail(c, SISO_EINVAL, "siso_merge: bad arguments");
+    if (c->count < 2) return 0;
+    hipLaunchKernelGGL(k_zero_counter, dim3(1), dim3(1), 0, c->stream, c->counters + 1);
+    int rc = siso_check_hip(c, hipGetLastError(), "k_zero_counter");
+    if (rc != SISO_OK) return rc;
+    siso_prof_begin(c);
+    if (siso_merge_mfma_supported(c))
+        rc = siso_merge_mfma_launch(c, threshold, out_pairs, cap);
+    else
+        rc = siso_merge_scalar_launch(c, threshold, out_pairs, cap);
+    siso_prof_end(c);
+    if (rc != SISO_OK) return rc;
+    u64 total = 0;
+    rc = read_counter(c, 1, &total);
+    return rc != SISO_OK ? (long)rc : (long)total;
+}
+
+extern "C" int siso_merge_apply(siso_cache *c, const int *pairs, long n_pairs, int *out_survivor) {
+    if (!c) return SISO_EINVAL;
+    if (n_pairs < 0 || (n_pairs > 0 && !pairs)) return siso_fail(c, SISO_EINVAL, "siso_merge_apply: bad arguments");
+    const long K = c->count;
+    if (K == 0) return SISO_OK;
+    const int d = c->dim;
+    const unsigned pb = (unsigned)((n_pairs + 255) / 256), kb = (unsigned)((K + 255) / 256);
+    u64 v = 0;
+    if (n_pairs > 0) {
+        hipLaunchKernelGGL(k_zero_counter, dim3(1), dim3(1), 0, c->stream, c->counters + 2);
+        hipLaunchKernelGGL(k_pairs_validate, dim3(pb), dim3(256), 0, c->stream, pairs, n_pairs, K, c->counters + 2);
+        HIP_TRY(c, hipGetLastError());
+        int rc = read_counter(c, 2, &v);
+        if (rc != SISO_OK) return rc;
+        if (v != 0) return siso_fail(c, SISO_EINVAL, "siso_merge_apply: %llu invalid pairs", v);
+    }
+    int *parent = nullptr, *root = nullptr, *newpos = nullptr;
+    unsigned char *touched = nullptr;
+    void *cent2 = nullptr;
+    float *mean2 = nullptr, *invn2 = nullptr;
+    int *size2 = nullptr;
+    int rc = SISO_OK;
+    bool ok = hipMalloc((void **)&parent, (size_t)K * sizeof(int)) == hipSuccess;
+    ok = ok && hipMalloc((void **)&root, (size_t)K * sizeof(int)) == hipSuccess;
+    ok = ok && hipMalloc((void **)&newpos, (size_t)K * sizeof(int)) == hipSuccess;
+    ok = ok && hipMalloc((void **)&touched, (size_t)K) == hipSuccess;
+    if (!ok) {
+        (void)hipGetLastError();
+        rc = siso_fail(c, SISO_ENOMEM, "siso_merge_apply: temporaries");
+    }
+    long live = K;
+    if (rc == SISO_OK) {
+        hipLaunchKernelGGL(k_uf_init, dim3(kb), dim3(256), 0, c->stream, parent, touched, K);
+        if (n_pairs > 0)
+            hipLaunchKernelGGL(k_uf_hook, dim3(pb), dim3(256), 0, c->stream, pairs, n_pairs, parent, touched);
+        hipLaunchKernelGGL(k_uf_roots, dim3(kb), dim3(256), 0, c->stream, parent, root, K);
+        if (c->dtype == SISO_F32)
+            hipLaunchKernelGGL(k_group_mean<float>, dim3((unsigned)K), dim3(256), 0, c->stream, root, touched, K,
+                               (float *)c->cent, c->mean, c->size, c->invn, d);
+        else
+            hipLaunchKernelGGL(k_group_mean<bf16_t>, dim3((unsigned)K), dim3(256), 0, c->stream, root, touched, K,
+                               (bf16_t *)c->cent, c->mean, c->size, c->invn, d);
+        hipLaunchKernelGGL(k_scan_survivors, dim3(1), dim3(1024), 0, c->stream, root, K, newpos, c->counters + 3);
+        rc = siso_check_hip(c, hipGetLastError(), "merge_apply kernels");
+        if (rc == SISO_OK) rc = read_counter(c, 3, &v);
+        if (rc == SISO_OK) live = (long)v;
+    }
+    if (rc == SISO_OK && out_survivor) {
+        hipLaunchKernelGGL(k_survivor_map, dim3(kb), dim3(256), 0, c->stream, root, newpos, K, out_survivor);
+        rc = siso_check_hip(c, hipGetLastError(), "k_survivor_map");
+    }
+    if (rc == SISO_OK && live < K) {
+        const size_t cells = (size_t)live * d;
+        ok = hipMalloc(&cent2, cells * elem_bytes(c->dtype)) == hipSuccess;
+        ok = ok && hipMalloc((void **)&mean2, cells * sizeof(float)) == hipSuccess;
+        ok = ok && hipMalloc((void **)&size2, (size_t)live * sizeof(int)) == hipSuccess;
+        ok = ok && hipMalloc((void **)&invn2, (size_t)live * sizeof(float)) == hipSuccess;
+        if (!ok) {
+            (void)hipGetLastError();
+            rc = siso_fail(c, SISO_ENOMEM, "siso_merge_apply: compaction buffers");
+        } else {
+            if (c->dtype == SISO_F32)
+                hipLaunchKernelGGL(k_gather_rows<float>, dim3((unsigned)K), dim3(256), 0, c->stream, root, newpos,
+                                   (const float *)c->cent, c->mean, c->size, c->invn, (float *)cent2, mean2, size2,
+                                   invn2, d);
+            else
+                hipLaunchKernelGGL(k_gather_rows<bf16_t>, dim3((unsigned)K), dim3(256), 0, c->stream, root, newpos,
+                                   (const bf16_t *)c->cent, c->mean, c->size, c->invn, (bf16_t *)cent2, mean2, size2,
+                                   invn2, d);
+            rc = siso_check_hip(c, hipGetLastError(), "k_gather_rows");
+            if (rc == SISO_OK)
+                rc = siso_check_hip(c, hipMemcpyAsync(c->cent, cent2, cells * elem_bytes(c->dtype), hipMemcpyDeviceToDevice, c->stream), "copy back");
+            if (rc == SISO_OK)
+                rc = siso_check_hip(c, hipMemcpyAsync(c->mean, mean2, cells * sizeof(float), hipMemcpyDeviceToDevice, c->stream), "copy back");
+            if (rc == SISO_OK)
+                rc = siso_check_hip(c, hipMemcpyAsync(c->size, size2, (size_t)live * sizeof(int), hipMemcpyDeviceToDevice, c->stream), "copy back");
+            if (rc == SISO_OK)
+                rc = siso_check_hip(c, hipMemcpyAsync(c->invn, invn2, (size_t)live * sizeof(float), hipMemcpyDeviceToDevice, c->stream), "copy back");
+        }
+    }
+    (void)hipStreamSynchronize(c->stream);
+    if (rc == SISO_OK) c->count = live;
+    if (parent) (void)hipFree(parent);
+    if (root) (void)hipFree(root);
+    if (newpos) (void)hipFree(newpos);
+    if (touched) (void)hipFree(touched);
+    if (cent2) (void)hipFree(cent2);
+    if (mean2) (void)hipFree(mean2);
+    if (size2) (void)hipFree(size2);
+    if (invn2) (void)hipFree(invn2);
+    return rc;
+}
+
+extern "C" int siso_profile_enable(siso_cache *c, int on) {
+    if (!c) return SISO_EINVAL;
+    c->profile_on = on ? 1 : 0;
+    return SISO_OK;
+}
+
+extern "C" int siso_profile_read(siso_cache *c, double *total_ms, long *launches) {
+    if (!c) return SISO_EINVAL;
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    double sum = 0.0;
+    for (int i = 0; i < c->prof_count; ++i) {
+        float ms = 0.f;
+        hipEvent_t *e = c->prof_ev + 2 * i;
+        if (hipEventElapsedTime(&ms, e[0], e[1]) == hipSuccess) sum += ms;
+        (void)hipEventDestroy(e[0]);
+        (void)hipEventDestroy(e[1]);
+        e[0] = e[1] = nullptr;
+    }
+    if (total_ms) *total_ms = sum;
+    if (launches) *launches = c->prof_count;
+    c->prof_count = 0;
+    return SISO_OK;
+}
+
+extern "C" int siso_export(siso_cache *c, void *centroids, float *means, int *counts) {
+    if (!c) return SISO_EINVAL;
+    const size_t cells = (size_t)c->count * c->dim;
+    if (c->count == 0) return SISO_OK;
+    if (centroids)
+        HIP_TRY(c, hipMemcpyAsync(centroids, c->cent, cells * elem_bytes(c->dtype), hipMemcpyDeviceToDevice, c->stream));
+    if (means) HIP_TRY(c, hipMemcpyAsync(means, c->mean, cells * sizeof(float), hipMemcpyDeviceToDevice, c->stream));
+    if (counts)
+        HIP_TRY(c, hipMemcpyAsync(counts, c->size, (size_t)c->count * sizeof(int), hipMemcpyDeviceToDevice, c->stream));
+    return SISO_OK;
+}

@@ -1,0 +1,146 @@
+// Internal declarations shared by the translation units of libsiso.so.
+// Nothing here is visible through the C ABI (include/siso.h).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "siso.h"
+
+typedef unsigned long long u64;
+typedef unsigned short bf16_t;  // bfloat16 bit pattern
+
+// A phase-1 lookup kernel reduces, for every query q and every slice s of the
+// centroid range, the scaled dot products <q, c_k> / |c_k| to one 64-bit key
+//     key = ordered(value) << 32 | (0xFFFFFFFF - block)
+// where block = k / SISO_BLOCK_ROWS of the best centroid, so that an unsigned
+// max over keys picks the largest value and, among equal values, the lowest
+// block.  Key 0 means "no candidate".  The finalize kernel then recomputes the
+// SISO_BLOCK_ROWS cosines of the winning block exactly and picks the lowest
+// index among its maxima.
+#define SISO_BLOCK_ROWS 32
+#define SISO_MAX_DIM 4096
+#define SISO_PAD_ROWS 256  // readable rows past the capacity of the stored-centroid array
+
+struct siso_cache {
+    int dim;
+    long capacity;
+    int dtype;
+    long count;
+    int device;
+    int path;
+    hipStream_t stream;
+
+    void *cent;   // [capacity][dim] stored centroids (bf16 bits or float)
+    float *mean;  // [capacity][dim] mean of the unit-length members
+    int *size;    // [capacity] cluster_size
+    float *invn;  // [capacity] 1 / |stored centroid| (0 for a zero row, NaN for a non-finite row)
+
+    // workspace, grown on demand
+    u64 *keys;     // [keys_cap] phase-1 keys, n * slices
+    long keys_cap;
+    float *qinv;   // [qinv_cap] 1 / |query| (0 for zero length, NaN for non-finite)
+    long qinv_cap;
+
+    u64 *counters;  // device: [0] bad update indices, [1] merge pair count, [2] scratch, [3] scratch
+    u64 *host_pin;  // pinned host mirror for counter read-back (4 entries)
+
+    // tuning knobs (siso_set_option); 0 = library default
+    int opt_mfma_config;
+    int opt_tiles_per_slice;
+    int opt_merge_config;
+
+    // kernel timing (siso_profile_enable / siso_profile_read)
+    int profile_on;
+    hipEvent_t *prof_ev;  // pairs: [2*i] start, [2*i+1] stop
+    int prof_count;       // recorded pairs
+
+    char err[256];
+};
+
+// ----------------------------------------------------------------------------
+// device helpers
+// ----------------------------------------------------------------------------
+__device__ __forceinline__ float bf16_to_f32(bf16_t v) { return __uint_as_float(((unsigned)v) << 16); }
+
+// round-to-nearest-even float -> bf16 bit pattern (NaN stays NaN)
+__device__ __forceinline__ bf16_t f32_to_bf16(float f) {
+    unsigned u = __float_as_uint(f);
+    if ((u & 0x7FFFFFFFu) > 0x7F800000u) return (bf16_t)0x7FC0;
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return (bf16_t)(u >> 16);
+}
+
+__device__ __forceinline__ float widen(float v) { return v; }
+__device__ __forceinline__ float widen(bf16_t v) { return bf16_to_f32(v); }
+
+__device__ __forceinline__ void narrow(float v, float *out) { *out = v; }
+__device__ __forceinline__ void narrow(float v, bf16_t *out) { *out = f32_to_bf16(v); }
+
+// monotone map float -> unsigned (larger float <=> larger unsigned; NaN excluded by callers)
+__device__ __forceinline__ unsigned ordered_bits(float f) {
+    unsigned u = __float_as_uint(f);
+    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+__device__ __forceinline__ float unordered_bits(unsigned o) {
+    unsigned u = (o & 0x80000000u) ? (o & 0x7FFFFFFFu) : ~o;
+    return __uint_as_float(u);
+}
+__device__ __forceinline__ u64 pack_key(float value, unsigned block) {
+    return ((u64)ordered_bits(value) << 32) | (u64)(0xFFFFFFFFu - block);
+}
+
+// 1/|x| from the sum of squares: 0 for a zero vector, NaN if the sum is not finite
+__device__ __forceinline__ float inv_length(float sumsq) {
+    if (!(sumsq == sumsq) || sumsq > 3.0e38f) return __uint_as_float(0x7FC00000u);
+    if (sumsq == 0.0f) return 0.0f;
+    return 1.0f / sqrtf(sumsq);
+}
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off);
+    return v;
+}
+
+// Wave-ballot compaction of (i, j) pairs into out[cap][2]; every lane of the wave
+// must call it.  counter accumulates the total number of pairs, also beyond cap.
+__device__ __forceinline__ void emit_pair(bool pred, int i, int j, int *out, long cap, u64 *counter) {
+    const u64 mask = __ballot(pred);
+    if (mask == 0) return;
+    const int lane = threadIdx.x & 63;
+    const int leader = __ffsll((long long)mask) - 1;
+    u64 base = 0;
+    if (lane == leader) base = atomicAdd(counter, (u64)__popcll(mask));
+    base = __shfl(base, leader);
+    if (pred) {
+        const u64 pos = base + (u64)__popcll(mask & ((1ull << lane) - 1ull));
+        if (pos < (u64)cap) {
+            out[2 * pos] = i;
+            out[2 * pos + 1] = j;
+        }
+    }
+}
+
+// ----------------------------------------------------------------------------
+// host-side plumbing shared by the translation units
+// ----------------------------------------------------------------------------
+int siso_fail(siso_cache *c, int code, const char *fmt, ...);
+void siso_prof_begin(siso_cache *c);  // bracket the dominant kernel of a call (no-ops unless enabled)
+void siso_prof_end(siso_cache *c);
+int siso_check_hip(siso_cache *c, hipError_t e, const char *what);
+
+// Phase-1 launchers.  Each fills keys[q * slices + s] for all q < n, s < slices.
+// *_slices returns the number of slices the launcher will use (0 = path cannot
+// handle this cache / batch).
+int siso_scalar_slices(const siso_cache *c, long n);
+int siso_scalar_launch(siso_cache *c, const void *queries, long n, int slices);
+int siso_mfma_slices(const siso_cache *c, long n);
+int siso_mfma_launch(siso_cache *c, const void *queries, long n, int slices);
+int siso_skinny_slices(const siso_cache *c, long n);
+int siso_skinny_launch(siso_cache *c, const void *queries, long n, int slices);
+
+// Self-similarity pair search launchers (counter = c->counters + 1, already zeroed).
+int siso_merge_scalar_launch(siso_cache *c, float threshold, int *out_pairs, long cap);
+int siso_merge_mfma_supported(const siso_cache *c);
+int siso_merge_mfma_launch(siso_cache *c, float threshold, int *out_pairs, long cap);

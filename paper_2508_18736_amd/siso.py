@@ -1,0 +1,195 @@
+"""Thin binding over the C-ABI library ``libsiso.so`` (declared in ``include/siso.h``).
+
+Argument marshalling only: every step of the hot path runs in the library's HIP
+kernels.  PyTorch supplies device memory (``tensor.data_ptr()``) and the stream.
+There is no CPU fallback: importing this module without a built library raises.
+"""
+
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional, Tuple
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libsiso.so")
+
+if not os.path.exists(LIB_PATH):
+    raise ImportError(
+        f"{LIB_PATH} is missing: build it with `python -m paper_2508_18736_amd.build` "
+        "(there is no fallback path)")
+
+_lib = C.CDLL(LIB_PATH)
+
+F32, BF16 = 0, 1
+PATH_AUTO, PATH_SCALAR, PATH_MFMA, PATH_SKINNY = 0, 1, 2, 3
+OK, EINVAL, ECAPACITY, EHIP, ENOMEM = 0, -1, -2, -3, -4
+
+# every symbol include/siso.h declares, with its signature
+_vp, _lg, _it, _fl = C.c_void_p, C.c_long, C.c_int, C.c_float
+SYMBOLS = {
+    "siso_create": ([_it, _lg, C.POINTER(_vp)], _it),
+    "siso_create_ex": ([_it, _lg, _it, C.POINTER(_vp)], _it),
+    "siso_destroy": ([_vp], None),
+    "siso_set_stream": ([_vp, _vp], _it),
+    "siso_set_lookup_path": ([_vp, _it], _it),
+    "siso_set_option": ([_vp, C.c_char_p, _lg], _it),
+    "siso_load": ([_vp, _vp, _vp, _lg], _it),
+    "siso_count": ([_vp], _lg),
+    "siso_lookup": ([_vp, _vp, _lg, _fl, _vp, _vp, _vp], _it),
+    "siso_update": ([_vp, _vp, _vp, _lg], _it),
+    "siso_update_hits": ([_vp, _vp, _vp, _vp, _lg], _it),
+    "siso_bad_indices": ([_vp], _lg),
+    "siso_merge": ([_vp, _fl, _vp, _lg], _lg),
+    "siso_merge_apply": ([_vp, _vp, _lg, _vp], _it),
+    "siso_export": ([_vp, _vp, _vp, _vp], _it),
+    "siso_profile_enable": ([_vp, _it], _it),
+    "siso_profile_read": ([_vp, C.POINTER(C.c_double), C.POINTER(C.c_long)], _it),
+    "siso_last_error": ([_vp], C.c_char_p),
+}
+for _name, (_args, _res) in SYMBOLS.items():
+    _fn = getattr(_lib, _name)
+    _fn.argtypes = _args
+    _fn.restype = _res
+
+
+class SisoError(RuntimeError):
+    def __init__(self, code: int, msg: str):
+        super().__init__(f"siso error {code}: {msg}")
+        self.code = code
+
+
+_TORCH_DT = {F32: torch.float32, BF16: torch.bfloat16}
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    return None if t is None else C.c_void_p(t.data_ptr())
+
+
+class SisoCache:
+    """Device-resident centroid cache.  Method names follow the C ABI."""
+
+    def __init__(self, dim: int, capacity: int, dtype: int = BF16, device: str = "cuda:0"):
+        self.dim, self.capacity, self.dtype = int(dim), int(capacity), int(dtype)
+        self.device = torch.device(device)
+        self._h = C.c_void_p()
+        with torch.cuda.device(self.device):
+            rc = _lib.siso_create_ex(self.dim, self.capacity, self.dtype, C.byref(self._h))
+        if rc != OK:
+            self._h = C.c_void_p()
+            raise SisoError(rc, "siso_create_ex failed")
+        self.set_stream(torch.cuda.current_stream(self.device))
+
+    # ------------------------------------------------------------------ plumbing
+    def _check(self, rc: int) -> int:
+        if rc < 0:
+            raise SisoError(rc, _lib.siso_last_error(self._h).decode())
+        return rc
+
+    def _rows(self, t: torch.Tensor, what: str) -> torch.Tensor:
+        if t.device != self.device or t.dtype != _TORCH_DT[self.dtype] or t.dim() != 2 or t.shape[1] != self.dim:
+            raise ValueError(f"{what}: expected a [*, {self.dim}] {_TORCH_DT[self.dtype]} tensor on {self.device}")
+        return t if t.is_contiguous() else t.contiguous()
+
+    def _vec(self, t: Optional[torch.Tensor], dtype: torch.dtype, n: int, what: str) -> Optional[torch.Tensor]:
+        if t is None:
+            return None
+        if t.device != self.device or t.dtype != dtype or t.shape != (n,) or not t.is_contiguous():
+            raise ValueError(f"{what}: expected a contiguous [{n}] {dtype} tensor on {self.device}")
+        return t
+
+    def close(self) -> None:
+        if getattr(self, "_h", None):
+            _lib.siso_destroy(self._h)
+            self._h = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def set_stream(self, stream: torch.cuda.Stream) -> None:
+        self._stream = stream
+        self._check(_lib.siso_set_stream(self._h, C.c_void_p(stream.cuda_stream)))
+
+    def set_lookup_path(self, path: int) -> None:
+        self._check(_lib.siso_set_lookup_path(self._h, int(path)))
+
+    def set_option(self, name: str, value: int) -> None:
+        self._check(_lib.siso_set_option(self._h, name.encode(), int(value)))
+
+    @property
+    def count(self) -> int:
+        return int(_lib.siso_count(self._h))
+
+    # ---------------------------------------------------------------------- calls
+    def load(self, centroids: torch.Tensor, counts: Optional[torch.Tensor] = None) -> None:
+        cents = self._rows(centroids, "centroids")
+        cn = self._vec(counts, torch.int32, cents.shape[0], "counts")
+        self._check(_lib.siso_load(self._h, _ptr(cents), _ptr(cn), cents.shape[0]))
+
+    def lookup(self, queries: torch.Tensor, threshold: float, out_idx: Optional[torch.Tensor] = None,
+               out_sim: Optional[torch.Tensor] = None, out_hit: Optional[torch.Tensor] = None
+               ) -> Tuple[torch.Tensor, torch.Tensor, torch.Tensor]:
+        q = self._rows(queries, "queries")
+        n = q.shape[0]
+        if out_idx is None:
+            out_idx = torch.empty(n, dtype=torch.int32, device=self.device)
+        if out_sim is None:
+            out_sim = torch.empty(n, dtype=torch.float32, device=self.device)
+        if out_hit is None:
+            out_hit = torch.empty(n, dtype=torch.uint8, device=self.device)
+        self._vec(out_idx, torch.int32, n, "out_idx")
+        self._vec(out_sim, torch.float32, n, "out_sim")
+        self._vec(out_hit, torch.uint8, n, "out_hit")
+        self._check(_lib.siso_lookup(self._h, _ptr(q), n, float(threshold), _ptr(out_idx), _ptr(out_sim),
+                                     _ptr(out_hit)))
+        return out_idx, out_sim, out_hit
+
+    def update(self, queries: torch.Tensor, idx: torch.Tensor, hit: Optional[torch.Tensor] = None) -> None:
+        q = self._rows(queries, "queries")
+        n = q.shape[0]
+        self._vec(idx, torch.int32, n, "idx")
+        if hit is None:
+            self._check(_lib.siso_update(self._h, _ptr(q), _ptr(idx), n))
+        else:
+            self._vec(hit, torch.uint8, n, "hit")
+            self._check(_lib.siso_update_hits(self._h, _ptr(q), _ptr(idx), _ptr(hit), n))
+
+    def bad_indices(self) -> int:
+        return self._check(_lib.siso_bad_indices(self._h))
+
+    def merge(self, threshold: float, cap: int) -> Tuple[torch.Tensor, int]:
+        """Returns ``(pairs[min(total, cap), 2] int32 on the device, total)``."""
+        pairs = torch.empty((max(int(cap), 1), 2), dtype=torch.int32, device=self.device)
+        total = self._check(_lib.siso_merge(self._h, float(threshold), _ptr(pairs), int(cap)))
+        return pairs[:min(total, int(cap))], total
+
+    def merge_apply(self, pairs: torch.Tensor) -> torch.Tensor:
+        """Merges the connected groups; returns the survivor map (int32, old count)."""
+        if pairs.device != self.device or pairs.dtype != torch.int32 or pairs.dim() != 2 or pairs.shape[1] != 2:
+            raise ValueError("pairs: expected a [*, 2] int32 tensor on the cache's device")
+        pr = pairs.contiguous()
+        surv = torch.empty(self.count, dtype=torch.int32, device=self.device)
+        self._check(_lib.siso_merge_apply(self._h, _ptr(pr), pr.shape[0], _ptr(surv)))
+        return surv
+
+    def profile_enable(self, on: bool) -> None:
+        self._check(_lib.siso_profile_enable(self._h, 1 if on else 0))
+
+    def profile_read(self) -> Tuple[float, int]:
+        """Sum of the bracketed kernel durations (ms) and their number since the last read."""
+        ms, cnt = C.c_double(0.0), C.c_long(0)
+        self._check(_lib.siso_profile_read(self._h, C.byref(ms), C.byref(cnt)))
+        return float(ms.value), int(cnt.value)
+
+    def export(self) -> Tuple[torch.Tensor, torch.Tensor, torch.Tensor]:
+        k = self.count
+        cents = torch.empty((k, self.dim), dtype=_TORCH_DT[self.dtype], device=self.device)
+        means = torch.empty((k, self.dim), dtype=torch.float32, device=self.device)
+        sizes = torch.empty(k, dtype=torch.int32, device=self.device)
+        self._check(_lib.siso_export(self._h, _ptr(cents), _ptr(means), _ptr(sizes)))
+        return cents, means, sizes

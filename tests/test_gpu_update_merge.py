@@ -1,0 +1,198 @@
+"""GPU parity of the centroid update, the pair search and the group merge against the
+CPU oracle, through the C ABI."""
+
+import numpy as np
+import pytest
+import torch
+
+from paper_2508_18736_amd import workloads as W
+from gpu_util import DEV, check_lookup, siso_dtype, to_dev, to_host
+
+pytestmark = pytest.mark.gpu
+
+MEAN_TOL = 2e-6       # fp32 running mean against the oracle's float64 mean, entries <= 1 in size
+STORE_TOL_F32 = 2e-6  # fp32 stored centroid
+
+
+@pytest.fixture(scope="module")
+def siso():
+    from paper_2508_18736_amd import siso as m
+    return m
+
+
+def compare_state(cache, oc, dtype, label):
+    gc, gm, gs = cache.export()
+    torch.cuda.synchronize()
+    oc_c, oc_m, oc_s = oc.export()
+    assert cache.count == oc.count, label
+    assert np.array_equal(gs.cpu().numpy(), oc_s), f"{label}: cluster sizes differ"
+    err = np.abs(gm.cpu().numpy().astype(np.float64) - oc_m).max() if oc.count else 0.0
+    assert err <= MEAN_TOL, f"{label}: mean error {err:.3e}"
+    g = to_host(gc, dtype)
+    if dtype == "f32":
+        assert np.abs(g.astype(np.float64) - oc_c).max() <= STORE_TOL_F32, label
+    else:
+        # the stored bf16 value may differ by one step where the fp32 mean sits next to a rounding
+        # boundary; everywhere else it is bit-identical
+        diff = g != oc_c
+        assert diff.mean() < 2e-3, f"{label}: {diff.mean():.2e} of stored bf16 values differ"
+        a = W.bf16_bits_to_f32(g).astype(np.float64); b = W.bf16_bits_to_f32(oc_c).astype(np.float64)
+        assert np.abs(a - b).max() <= 2.0 ** -8, label
+    return err
+
+
+def test_c1_lookup_then_update_hits(siso, oracle):
+    print("case: c1 lookup + update of hit centroids", flush=True)
+    wl = W.c1_tiny()
+    cache = siso.SisoCache(wl.dim, wl.K, siso.F32)
+    cache.load(to_dev(wl.centroids, "f32"))
+    q = to_dev(wl.queries, "f32")
+    idx, sim, hit = cache.lookup(q, 0.80)
+    cache.update(q, idx, hit)            # hits fold into their centroid, on the device
+    oc = oracle.OracleCache(wl.dim, wl.K, "f32")
+    oc.load(wl.centroids)
+    ora = oc.lookup(wl.queries, 0.80)
+    check_lookup((idx, sim, hit), ora, 0.80, "f32", "c1")
+    assert np.array_equal(idx.cpu().numpy(), ora[0]) and np.array_equal(hit.cpu().numpy(), ora[2])
+    oc.update(wl.queries, np.where(ora[2] == 1, ora[0], -1).astype(np.int32))
+    compare_state(cache, oc, "f32", "c1 update")
+    assert oc.export()[2].sum() == wl.K + int(ora[2].sum()) and ora[2].sum() > 200
+    # a second lookup sees the updated centroids
+    out2 = cache.lookup(q, 0.80)
+    check_lookup(out2, oc.lookup(wl.queries, 0.80), 0.80, "f32", "c1 after update")
+    assert cache.bad_indices() == 0
+
+
+@pytest.mark.parametrize("dtype,dim,n", [("bf16", 768, 64), ("bf16", 1024, 700), ("f32", 100, 333), ("bf16", 4096, 40)])
+def test_update_matches_oracle(siso, oracle, dtype, dim, n):
+    print(f"case: update {dtype} dim={dim} n={n}", flush=True)
+    wl = W.c4_stream(n_clusters=16, per_cluster=8, batches=1, batch=n, dim=dim, sigma=0.3, zipf_s=1.2,
+                     dtype=dtype, seed=51)
+    counts = W.random_counts(51, wl.K, 1, 20)
+    r = np.random.default_rng(10)
+    idx = wl.planted.astype(np.int32).copy()
+    idx[r.random(n) < 0.2] = -1                 # skipped entries
+    idx[: n // 4] = idx[0] if idx[0] >= 0 else 3  # a hot centroid with many members
+    q = wl.queries_f32().copy()
+    q[1] = 0.0                                  # zero-length member: skipped
+    q[2, 0] = np.nan                            # non-finite member: skipped
+    q[3] *= 37.0                                # members are normalised first
+    wl.queries = W.to_storage(q, dtype)
+    cache = siso.SisoCache(dim, wl.K + 3, siso_dtype(dtype))
+    cache.load(to_dev(wl.centroids, dtype), torch.from_numpy(counts).to(DEV))
+    oc = oracle.OracleCache(dim, wl.K + 3, dtype)
+    oc.load(wl.centroids, counts)
+    cache.update(to_dev(wl.queries, dtype), torch.from_numpy(idx).to(DEV))
+    oc.update(wl.queries, idx)
+    compare_state(cache, oc, dtype, "update")
+    # a second batch on top, given in a permuted order: the result must not depend on the order
+    perm = r.permutation(n)
+    cache.update(to_dev(wl.queries[perm].copy(), dtype), torch.from_numpy(idx[perm].copy()).to(DEV))
+    oc.update(wl.queries, idx)
+    compare_state(cache, oc, dtype, "update, permuted second batch")
+    # lookups after the update use the new centroids and their new lengths
+    out = cache.lookup(to_dev(wl.queries, dtype), 0.85)
+    gc = to_host(cache.export()[0], dtype)
+    ora = oracle.lookup_rows(gc, wl.queries, 0.85, dtype)   # oracle on the GPU's own stored rows
+    check_lookup(out, ora, 0.85, dtype, "lookup after update")
+    # out-of-range indices are skipped and counted
+    bad = np.array([wl.K, wl.K + 100, 0], np.int32)
+    before = cache.export()[1].clone()
+    cache.update(to_dev(wl.queries[:3], dtype), torch.from_numpy(bad[:2].repeat(2)[:3].copy()).to(DEV))
+    assert cache.bad_indices() == 3
+    assert torch.equal(before, cache.export()[1])
+
+
+def test_update_fold_misses_policy(siso, oracle):
+    """The library folds whatever it is told to: here the misses instead of the hits."""
+    print("case: update folding misses", flush=True)
+    wl = W.c2_mid(n_clusters=32, per_cluster=8, n_queries=300, dim=128, seed=52)
+    cache = siso.SisoCache(wl.dim, wl.K, siso.BF16)
+    cache.load(to_dev(wl.centroids, "bf16"))
+    q = to_dev(wl.queries, "bf16")
+    idx, sim, hit = cache.lookup(q, 0.85)
+    cache.update(q, idx, (1 - hit).to(torch.uint8))
+    oc = oracle.OracleCache(wl.dim, wl.K, "bf16")
+    oc.load(wl.centroids)
+    ora = oc.lookup(wl.queries, 0.85)
+    assert np.array_equal(ora[2], hit.cpu().numpy()) and 50 < (1 - ora[2]).sum() < 150
+    oc.update(wl.queries, np.where(ora[2] == 0, ora[0], -1).astype(np.int32))
+    compare_state(cache, oc, "bf16", "fold misses")
+
+
+def sorted_pairs(p):
+    p = np.asarray(p).reshape(-1, 2)
+    return p[np.lexsort((p[:, 1], p[:, 0]))]
+
+
+@pytest.mark.parametrize("dtype,dim,groups,copies,sigma,theta", [
+    ("bf16", 768, 300, 7, 0.03, 0.90), ("f32", 96, 100, 5, 0.05, 0.90), ("bf16", 128, 150, 9, 0.6, 0.7),
+    ("bf16", 1024, 33, 31, 0.03, 0.90)])
+def test_merge_pairs_and_groups_match_oracle(siso, oracle, dtype, dim, groups, copies, sigma, theta):
+    print(f"case: merge {dtype} dim={dim} K={groups * copies} sigma={sigma} theta={theta}", flush=True)
+    wl = W.c5_merge(n_groups=groups, copies=copies, dim=dim, sigma=sigma, dtype=dtype, seed=53)
+    counts = W.random_counts(53, wl.K, 1, 100)
+    cache = siso.SisoCache(dim, wl.K, siso_dtype(dtype))
+    cache.load(to_dev(wl.centroids, dtype), torch.from_numpy(counts).to(DEV))
+    oc = oracle.OracleCache(dim, wl.K, dtype)
+    oc.load(wl.centroids, counts)
+    want, total = oc.merge(theta)
+    # pairs whose cosine is within rounding of the threshold may legitimately differ
+    c64 = wl.centroids_f32().astype(np.float64)
+    u = c64 / np.linalg.norm(c64, axis=1, keepdims=True)
+    S = u @ u.T
+    edge = np.abs(S - np.float64(np.float32(theta))) < 2e-5
+    np.fill_diagonal(edge, False)
+    got, gtotal = cache.merge(theta, cap=total + 100)
+    got = sorted_pairs(got.cpu().numpy())
+    if not edge.any():
+        assert gtotal == total and np.array_equal(got, want)
+    else:
+        gs, ws = set(map(tuple, got)), set(map(tuple, want))
+        assert all(edge[i, j] for i, j in gs ^ ws)
+    assert np.all(got[:, 0] < got[:, 1]) and len(np.unique(got, axis=0)) == len(got)
+    if sigma < 0.1:
+        assert total == groups * copies * (copies - 1) // 2
+    # capped output: full count reported, only cap pairs written, all of them valid
+    few, t2 = cache.merge(theta, cap=10)
+    assert t2 == gtotal and few.shape[0] == 10
+    assert set(map(tuple, few.cpu().numpy())) <= set(map(tuple, got))
+    # group merge from the oracle's pair list on both sides
+    pr = torch.from_numpy(want[np.random.default_rng(11).permutation(len(want))].copy()).to(DEV)
+    surv = cache.merge_apply(pr)
+    osurv = oc.merge_apply(want)
+    assert np.array_equal(surv.cpu().numpy(), osurv)
+    compare_state(cache, oc, dtype, "merge_apply")
+    if sigma < 0.1:
+        assert cache.count == groups
+    # the merged cache still answers lookups consistently with its own stored rows
+    qs = wl.centroids[:50].copy()
+    out = cache.lookup(to_dev(qs, dtype), 0.9)
+    ora = oracle.lookup_rows(to_host(cache.export()[0], dtype), qs, 0.9, dtype)
+    check_lookup(out, ora, 0.9, dtype, "lookup after merge")
+
+
+def test_merge_apply_chains_and_errors(siso, oracle):
+    print("case: merge_apply chains / invalid pairs", flush=True)
+    d = 64
+    rows = np.eye(d, dtype=np.float32)[:6]
+    counts = np.array([1, 2, 3, 4, 5, 6], np.int32)
+    cache = siso.SisoCache(d, 6, siso.F32)
+    cache.load(to_dev(rows, "f32"), torch.from_numpy(counts).to(DEV))
+    oc = oracle.OracleCache(d, 6, "f32")
+    oc.load(rows, counts)
+    pairs = np.array([[3, 1], [3, 4]], np.int32)
+    surv = cache.merge_apply(torch.from_numpy(pairs).to(DEV))
+    assert np.array_equal(surv.cpu().numpy(), oc.merge_apply(pairs)) and cache.count == 4
+    compare_state(cache, oc, "f32", "chain")
+    for bad in ([[0, 0]], [[0, 9]], [[-1, 2]]):
+        with pytest.raises(siso.SisoError):
+            cache.merge_apply(torch.tensor(bad, dtype=torch.int32, device=DEV))
+    assert cache.count == 4
+    compare_state(cache, oc, "f32", "after rejected pairs")
+    cache.merge_apply(torch.zeros((0, 2), dtype=torch.int32, device=DEV))
+    assert cache.count == 4
+    # fewer than two centroids: no pairs
+    one = siso.SisoCache(d, 2, siso.F32)
+    one.load(to_dev(rows[:1], "f32"))
+    assert one.merge(0.5, cap=4)[1] == 0
