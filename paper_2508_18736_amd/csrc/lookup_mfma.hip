@@ -31,7 +31,7 @@ struct LookupCfg {
     static constexpr int BQ = 32 * WQ * NWQ;  // query rows per tile
     static constexpr int NT = 64 * NWC * NWQ; // threads
     static constexpr int CPR = BK / 8;        // 16-byte chunks per tile row
-    static constexpr int RP = 128 / (BK * 2); // tile rows per 128 bytes of LDS
+    static constexpr int RP = 256 / (BK * 2); // tile rows per 256 bytes of LDS (64 banks x 4 bytes)
     static constexpr int NA = BC * CPR / NT;  // chunks per thread, centroid tile
     static constexpr int NB = BQ * CPR / NT;  // chunks per thread, query tile
     static constexpr int STAGE = (BC + BQ) * BK * 2;
@@ -164,7 +164,7 @@ __global__ __launch_bounds__(Cfg::NT) __attribute__((amdgpu_waves_per_eu(Cfg::WP
             f32x4 w[4];
 #pragma unroll
             for (int g = 0; g < 4; ++g) w[g] = *(const f32x4 *)(inv_t + rb + 8 * g + 4 * h);
-            const unsigned blk = (unsigned)((c0 + rb) / SISO_BLOCK_ROWS);
+            const unsigned blk = (unsigned)((c0 + rb) / SISO_RUN_ROWS) * 4u + 2u * (unsigned)h;
 #pragma unroll
             for (int b = 0; b < WQ; ++b) {
                 float m = -INFINITY;
@@ -183,10 +183,7 @@ __global__ __launch_bounds__(Cfg::NT) __attribute__((amdgpu_waves_per_eu(Cfg::WP
     for (int b = 0; b < WQ; ++b) {
         const float ov = __shfl_xor(bv[b], 32);
         const unsigned ob = __shfl_xor(bb[b], 32);
-        if (ov > bv[b] || (ov == bv[b] && ob < bb[b])) {
-            bv[b] = ov;
-            bb[b] = ob;
-        }
+        siso_merge_candidate(bv[b], bb[b], ov, ob);
     }
     // waves with the same wq share query columns: meet in LDS (stage memory is free now)
     float *red_v = (float *)smem;               // [NWC][BQ]
@@ -205,12 +202,7 @@ __global__ __launch_bounds__(Cfg::NT) __attribute__((amdgpu_waves_per_eu(Cfg::WP
         unsigned blk = red_b[col];
 #pragma unroll
         for (int w2 = 1; w2 < NWC; ++w2) {
-            const float ov = red_v[w2 * BQ + col];
-            const unsigned ob = red_b[w2 * BQ + col];
-            if (ov > v || (ov == v && ob < blk)) {
-                v = ov;
-                blk = ob;
-            }
+            siso_merge_candidate(v, blk, red_v[w2 * BQ + col], red_b[w2 * BQ + col]);
         }
         const long q = q0 + col;
         if (q < n) keys[(size_t)q * slices + s] = (blk == 0xFFFFFFFFu) ? 0ull : pack_key(v, blk);

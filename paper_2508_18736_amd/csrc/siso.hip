@@ -113,20 +113,40 @@ __global__ __launch_bounds__(256) void k_query_invnorm(const T *__restrict__ Q, 
     if (lane == 0) qinv[q] = inv_length(ss);
 }
 
-// Finalize: per query, max over the slice keys, then the exact cosines of the
-// winning block of SISO_BLOCK_ROWS centroids (ascending, strict ">" so the lowest
-// index keeps a tie), and the strict threshold test.  One wavefront per query.
+// 16-byte chunk dot products for the finalize kernel
+typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ float chunk_dot(const float *a, const float *b) {
+    const float4 x = *(const float4 *)a, y = *(const float4 *)b;
+    return x.x * y.x + x.y * y.y + x.z * y.z + x.w * y.w;
+}
+__device__ __forceinline__ float chunk_dot(const bf16_t *a, const bf16_t *b) {
+    const u32x4_t x = *(const u32x4_t *)a, y = *(const u32x4_t *)b;
+    float s = 0.f;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        s += __uint_as_float(x[i] << 16) * __uint_as_float(y[i] << 16);
+        s += __uint_as_float(x[i] & 0xFFFF0000u) * __uint_as_float(y[i] & 0xFFFF0000u);
+    }
+    return s;
+}
+
+// Finalize: per query, max over the slice keys, then the exact cosines of the rows of
+// the winning block (strict ">" in ascending row order, so the lowest index keeps a
+// tie), and the strict threshold test.  One wavefront per query; its four groups of
+// 16 lanes take one centroid row each.  `vec` = rows are 16-byte aligned and a whole
+// number of 16-byte chunks.
 template <typename T>
 __global__ __launch_bounds__(256) void k_lookup_finalize(const T *__restrict__ Q, const T *__restrict__ cent,
                                                           const float *__restrict__ invn,
                                                           const float *__restrict__ qinv, const u64 *__restrict__ keys,
-                                                          long n, long K, int d, int slices, float threshold,
+                                                          long n, long K, int d, int slices, float threshold, int vec,
                                                           int *out_idx, float *out_sim, unsigned char *out_hit) {
+    constexpr int EPC = 16 / (int)sizeof(T);  // elements per 16-byte chunk
     const long q = (long)blockIdx.x * 4 + (threadIdx.x >> 6);
     if (q >= n) return;
-    const int lane = threadIdx.x & 63;
+    const int lane = threadIdx.x & 63, grp = lane >> 4, gl = lane & 15;
     const float qi = qinv[q];
-    int best_i = -1;
+    long best_i = -1;
     float best_s = -INFINITY;
     if (!(qi == qi)) {
         best_s = __uint_as_float(0x7FC00000u);
@@ -142,25 +162,45 @@ __global__ __launch_bounds__(256) void k_lookup_finalize(const T *__restrict__ Q
             key = o > key ? o : key;
         }
         if (key != 0) {
-            const long block = (long)(0xFFFFFFFFu - (unsigned)(key & 0xFFFFFFFFull));
-            const long r0 = block * SISO_BLOCK_ROWS;
-            const long r1 = (r0 + SISO_BLOCK_ROWS < K) ? r0 + SISO_BLOCK_ROWS : K;
+            const unsigned block = 0xFFFFFFFFu - (unsigned)(key & 0xFFFFFFFFull);
+            const long run0 = (long)(block >> 2) * SISO_RUN_ROWS;
+            const int code = (int)(block & 3u);
             const T *qrow = Q + (size_t)q * d;
-            for (long r = r0; r < r1; ++r) {
-                const T *crow = cent + (size_t)r * d;
+            // pass p, group grp -> local row: one half: 8*p + 4*h + grp; both halves: 4*p + grp
+            const int passes = code == 1 ? 8 : 4;
+            for (int p = 0; p < passes; ++p) {
+                const long r = run0 + (code == 1 ? 4 * p + grp : 8 * p + 2 * code + grp);
                 float acc = 0.f;
-                for (int e = lane; e < d; e += 64) acc += widen(qrow[e]) * widen(crow[e]);
-                acc = wave_sum(acc);
-                const float s = acc * qi * invn[r];
+                if (r < K) {
+                    const T *crow = cent + (size_t)r * d;
+                    if (vec) {
+                        for (int e = gl * EPC; e < d; e += 16 * EPC) acc += chunk_dot(qrow + e, crow + e);
+                    } else {
+                        for (int e = gl; e < d; e += 16) acc += widen(qrow[e]) * widen(crow[e]);
+                    }
+                }
+#pragma unroll
+                for (int off = 8; off > 0; off >>= 1) acc += __shfl_xor(acc, off);
+                const float s = r < K ? acc * qi * invn[r] : __uint_as_float(0x7FC00000u);
                 if (s > best_s) {
                     best_s = s;
-                    best_i = (int)r;
+                    best_i = r;
+                }
+            }
+            // the four groups hold interleaved rows: lowest row among equal maxima
+#pragma unroll
+            for (int off = 16; off < 64; off <<= 1) {
+                const float os = __shfl_xor(best_s, off);
+                const long oi = __shfl_xor(best_i, off);
+                if (oi >= 0 && (best_i < 0 || os > best_s || (os == best_s && oi < best_i))) {
+                    best_s = os;
+                    best_i = oi;
                 }
             }
         }
     }
     if (lane == 0) {
-        out_idx[q] = best_i;
+        out_idx[q] = (int)best_i;
         out_sim[q] = best_s;
         if (out_hit) out_hit[q] = (best_i >= 0 && best_s > threshold) ? 1 : 0;
     }
@@ -261,7 +301,7 @@ __global__ __launch_bounds__(256) void k_lookup_scalar(const T *__restrict__ Q, 
         }
         const long q = q0 + ty * 4 + i;
         if (tx == 0 && q < n)
-            keys[(size_t)q * slices + s] = bidx[i] < 0 ? 0ull : pack_key(best[i], (unsigned)(bidx[i] / SISO_BLOCK_ROWS));
+            keys[(size_t)q * slices + s] = bidx[i] < 0 ? 0ull : pack_key(best[i], siso_block_of_row(bidx[i]));
     }
 }
 
@@ -763,6 +803,7 @@ extern "C" int siso_lookup(siso_cache *c, const void *queries, long n, float thr
     int rc = ensure_workspace(c, n, slices);
     if (rc != SISO_OK) return rc;
     const unsigned qblocks = (unsigned)((n + 3) / 4);
+    const int vec = ((c->dim * elem_bytes(c->dtype)) % 16 == 0 && ((uintptr_t)queries & 15) == 0) ? 1 : 0;
     if (c->dtype == SISO_F32)
         hipLaunchKernelGGL(k_query_invnorm<float>, dim3(qblocks), dim3(256), 0, c->stream, (const float *)queries, n,
                            c->dim, c->qinv);
@@ -783,11 +824,11 @@ extern "C" int siso_lookup(siso_cache *c, const void *queries, long n, float thr
     if (c->dtype == SISO_F32)
         hipLaunchKernelGGL(k_lookup_finalize<float>, dim3(qblocks), dim3(256), 0, c->stream, (const float *)queries,
                            (const float *)c->cent, c->invn, c->qinv, c->keys, n, c->count, c->dim, slices, threshold,
-                           out_idx, out_sim, out_hit);
+                           vec, out_idx, out_sim, out_hit);
     else
         hipLaunchKernelGGL(k_lookup_finalize<bf16_t>, dim3(qblocks), dim3(256), 0, c->stream, (const bf16_t *)queries,
                            (const bf16_t *)c->cent, c->invn, c->qinv, c->keys, n, c->count, c->dim, slices, threshold,
-                           out_idx, out_sim, out_hit);
+                           vec, out_idx, out_sim, out_hit);
     HIP_TRY(c, hipGetLastError());
     return SISO_OK;
 }

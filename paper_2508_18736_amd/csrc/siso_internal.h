@@ -13,12 +13,35 @@ typedef unsigned short bf16_t;  // bfloat16 bit pattern
 // A phase-1 lookup kernel reduces, for every query q and every slice s of the
 // centroid range, the scaled dot products <q, c_k> / |c_k| to one 64-bit key
 //     key = ordered(value) << 32 | (0xFFFFFFFF - block)
-// where block = k / SISO_BLOCK_ROWS of the best centroid, so that an unsigned
-// max over keys picks the largest value and, among equal values, the lowest
-// block.  Key 0 means "no candidate".  The finalize kernel then recomputes the
-// SISO_BLOCK_ROWS cosines of the winning block exactly and picks the lowest
-// index among its maxima.
-#define SISO_BLOCK_ROWS 32
+// where block names a group of SISO_BLOCK_ROWS centroids that holds the best
+// one, so that an unsigned max over keys picks the largest value and, among
+// equal values, the lowest block.  Key 0 means "no candidate".  The finalize
+// kernel then recomputes the cosines of the winning block exactly and picks the
+// lowest index among its maxima.
+//
+// A block is what one lane of a 32x32 MFMA accumulator holds: inside an aligned
+// run of 32 centroids, half h (0 or 1) owns the 16 rows 8*g + 4*h + j, g and j in
+// 0..3.  block = 4 * (k / 32) + code with code 0 = half 0, 2 = half 1, and 1 =
+// "both halves tie" (the two lanes that share a query column found the same
+// value); the finalize kernel then looks at all 32 rows, so the lowest index
+// still wins.  A run of 32 centroids is only ever seen by one wave, so equal
+// values from different keys always belong to different runs and the lower
+// block is the lower index.
+#define SISO_RUN_ROWS 32
+__host__ __device__ __forceinline__ unsigned siso_block_of_row(long k) {
+    return (unsigned)((k >> 5) * 4 + ((k >> 2) & 1) * 2);
+}
+// merge two (value, block) candidates of the same query; NaN never reaches here
+__device__ __forceinline__ void siso_merge_candidate(float &v, unsigned &b, float ov, unsigned ob) {
+    if (ov > v) {
+        v = ov;
+        b = ob;
+    } else if (ov == v && ob != b && ob != 0xFFFFFFFFu) {
+        if (b == 0xFFFFFFFFu) b = ob;
+        else if ((ob >> 2) == (b >> 2)) b = (b & ~3u) | 1u;
+        else if (ob < b) b = ob;
+    }
+}
 #define SISO_MAX_DIM 4096
 #define SISO_PAD_ROWS 256  // readable rows past the capacity of the stored-centroid array
 
