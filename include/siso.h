@@ -82,8 +82,7 @@ int siso_set_lookup_path(siso_cache *c, int path);
  * Tuning knobs, for benchmarking; the defaults are chosen by the library.
  *   "mfma_config"     0 = default; 1.. = a specific tile configuration of the MFMA lookup
  *   "tiles_per_slice" 0 = default; >0 = centroid tiles one workgroup walks through
- *   "merge_config"    0 = default; 1.. = a specific configuration of the MFMA pair search
- * Unknown names or values out of range give SISO_EINVAL.
+ *   "merge_config"    0 = default; 1.. = a specific configuration of the MFMA pair search * Unknown names or values out of range give SISO_EINVAL.
  */
 int siso_set_option(siso_cache *c, const char *name, long value);
 

@@ -1,7 +1,9 @@
-// Phase 1 of the large-batch lookup: a fused bf16 MFMA GEMM whose epilogue keeps a
-// running maximum per query in registers, so the similarity matrix (queries x
-// centroids; CosineSimilarity inside FindClosestCentroid, Algorithm 1) never
-// leaves the compute unit.
+// Phase 1 of the bf16 lookup: a fused MFMA GEMM whose epilogue keeps a running
+// maximum per query in registers, so the similarity matrix (queries x centroids;
+// CosineSimilarity inside FindClosestCentroid, Algorithm 1) never leaves the
+// compute unit.  One kernel template serves the large-batch path (256 x 256 tiles,
+// bound by the matrix cores) and the small-batch path (256 centroids x 64 queries,
+// a deeper ring of stages, bound by memory bandwidth).
 //
 // Mapping onto v_mfma_f32_32x32x16_bf16 (D = A x B, fp32 accumulate):
 //   A rows    = 32 centroids      (lane l supplies row l%32, k = 8*(l/32) .. +8)
@@ -13,9 +15,17 @@
 // once at the end, and the waves that share a query column meet in LDS.
 //
 // A workgroup owns one tile of BQ queries and walks through `tiles_per_slice`
-// tiles of BC centroids.  Both operand tiles go through LDS in slabs of BK
-// elements of the dimension, double buffered, with a 16-byte-chunk XOR swizzle
-// so that the 128-bit fragment reads of a wave spread over all banks.
+// tiles of BC centroids, as one continuous stream of slabs of 64 elements of the
+// dimension.  Global -> LDS goes by direct loads (no staging registers): every
+// wave instruction moves 8 rows x 128 bytes, i.e. whole 128-byte lines, which is
+// the pattern that reaches the full memory bandwidth.
+//
+// LDS layout of a stage: tile row r (centroid rows first, then query rows) is 128
+// bytes = 8 chunks of 16 bytes; chunk c of row r sits in slot c ^ ((r >> 1) & 7).
+// LDS has 64 banks of 4 bytes and serves a 128-bit read 16 lanes at a time; with
+// this swizzle the 16 rows x 16 bytes of a fragment read cover all 64 banks.  A
+// direct load of one wave fills 1 KiB = 8 consecutive rows: lane i writes slot
+// i % 8 of row i / 8, so it fetches chunk (i % 8) ^ ((r >> 1) & 7) of that row.
 #include "siso_internal.h"
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
@@ -23,69 +33,117 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
-template <int WC_, int WQ_, int NWC_, int NWQ_, int BK_, int WPE_>
-struct LookupCfg {
-    static constexpr int WC = WC_, WQ = WQ_, NWC = NWC_, NWQ = NWQ_, BK = BK_;
-    static constexpr int WPE = WPE_;          // waves per SIMD the register budget is set for
+template <int WC_, int WQ_, int NWC_, int NWQ_, int NSTAGE_>
+struct PipeCfg {
+    static constexpr int WC = WC_, WQ = WQ_, NWC = NWC_, NWQ = NWQ_, NSTAGE = NSTAGE_;
     static constexpr int BC = 32 * WC * NWC;  // centroid rows per tile
     static constexpr int BQ = 32 * WQ * NWQ;  // query rows per tile
-    static constexpr int NT = 64 * NWC * NWQ; // threads
-    static constexpr int CPR = BK / 8;        // 16-byte chunks per tile row
-    static constexpr int RP = 256 / (BK * 2); // tile rows per 256 bytes of LDS (64 banks x 4 bytes)
-    static constexpr int NA = BC * CPR / NT;  // chunks per thread, centroid tile
-    static constexpr int NB = BQ * CPR / NT;  // chunks per thread, query tile
-    static constexpr int STAGE = (BC + BQ) * BK * 2;
-    static constexpr int LDS_BYTES = 2 * STAGE + 2 * BC * 4;
-    static_assert(BK == 32 || BK == 64, "slab of 32 or 64 elements");
-    static_assert((BC * CPR) % NT == 0 && (BQ * CPR) % NT == 0, "whole chunks per thread");
-    static_assert(BQ * NWC * 8 <= 2 * STAGE, "reduction scratch fits in the stage buffers");
+    static constexpr int NW = NWC * NWQ, NT = 64 * NW;
+    static constexpr int STAGE = (BC + BQ) * 128;
+    static constexpr int NLA = BC / 8 / NW, NLB = BQ / 8 / NW;  // direct loads per wave and slab
+    static constexpr int NL = NLA + NLB;
+    static constexpr int LDS_BYTES = NSTAGE * STAGE + 2 * BC * 4;
+    static_assert((BC / 8) % NW == 0 && (BQ / 8) % NW == 0, "whole row groups per wave");
+    static_assert(BC <= SISO_PAD_ROWS && BC <= NT && BC % 64 == 0, "tile of inverse lengths: one direct load per wave");
+    static_assert(BQ * NWC * 8 <= NSTAGE * STAGE, "reduction scratch fits in the stage buffers");
+    static_assert(NSTAGE >= 2 && LDS_BYTES <= 160 * 1024, "stages fit in LDS");
+    static_assert((NSTAGE - 1) * NL <= 63, "wait count fits the counter");
 };
 
+// direct global -> LDS loads: lane i of the wave writes its 16 (4) bytes at lds_wave_base + 16 (4) * i
+__device__ __forceinline__ void gload_lds16(const void *g, void *lds_wave_base) {
+    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)g,
+                                     (__attribute__((address_space(3))) void *)lds_wave_base, 16, 0, 0);
+}
+__device__ __forceinline__ void gload_lds4(const void *g, void *lds_wave_base) {
+    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)g,
+                                     (__attribute__((address_space(3))) void *)lds_wave_base, 4, 0, 0);
+}
+
+// LDS fragment reads and their waits are written out by hand: while direct loads are in
+// flight the compiler waits for *all* outstanding LDS reads before every use, which would
+// serialise the fragment double buffering.  LDS operations complete in order, so
+// "lgkmcnt(N)" = everything but the newest N reads has arrived.  Each read and its wait sit
+// in the same straight-line stretch of code.
+template <int OFF>
+__device__ __forceinline__ bf16x8 lds_frag(unsigned addr) {
+    u32x4 v;
+    asm volatile("ds_read_b128 %0, %1 offset:%2 ; hand-scheduled" : "=v"(v) : "v"(addr), "n"(OFF) : "memory");
+    return __builtin_bit_cast(bf16x8, v);
+}
+template <int N, int NA, int NB>
+__device__ __forceinline__ void lds_wait(bf16x8 (&a)[NA], bf16x8 (&b)[NB]) {
+    asm volatile("s_waitcnt lgkmcnt(%1)" : "+v"(a[0]) : "n"(N));
+#pragma unroll
+    for (int i = 1; i < NA; ++i) asm volatile("" : "+v"(a[i]));
+#pragma unroll
+    for (int i = 0; i < NB; ++i) asm volatile("" : "+v"(b[i]));
+}
+template <int NA, int NB>
+__device__ __forceinline__ void lds_frags(bf16x8 (&a)[NA], bf16x8 (&b)[NB], unsigned addr_a, unsigned addr_b) {
+    static_assert(NA <= 4 && NB <= 4, "fragment offsets are spelled out up to four");
+    a[0] = lds_frag<0>(addr_a);
+    if constexpr (NA > 1) a[1] = lds_frag<4096>(addr_a);
+    if constexpr (NA > 2) a[2] = lds_frag<8192>(addr_a);
+    if constexpr (NA > 3) a[3] = lds_frag<12288>(addr_a);
+    b[0] = lds_frag<0>(addr_b);
+    if constexpr (NB > 1) b[1] = lds_frag<4096>(addr_b);
+    if constexpr (NB > 2) b[2] = lds_frag<8192>(addr_b);
+    if constexpr (NB > 3) b[3] = lds_frag<12288>(addr_b);
+}
+template <int N>
+__device__ __forceinline__ void vm_wait() {
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+
 template <class Cfg>
-__global__ __launch_bounds__(Cfg::NT) __attribute__((amdgpu_waves_per_eu(Cfg::WPE, Cfg::WPE))) void k_lookup_mfma(const bf16_t *__restrict__ Q, const bf16_t *__restrict__ C,
-                                                          const float *__restrict__ invn, long n, long K, int d,
-                                                          int tiles_per_slice, int slices, int nqt,
-                                                          u64 *__restrict__ keys) {
-    constexpr int WC = Cfg::WC, WQ = Cfg::WQ, NWC = Cfg::NWC, BK = Cfg::BK, BC = Cfg::BC, BQ = Cfg::BQ,
-                  NT = Cfg::NT, CPR = Cfg::CPR, RP = Cfg::RP, NA = Cfg::NA, NB = Cfg::NB, STAGE = Cfg::STAGE;
+__global__ __launch_bounds__(Cfg::NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void k_lookup_pipe(
+    const bf16_t *__restrict__ Q, const bf16_t *__restrict__ C, const float *__restrict__ invn, long n, long K, int d,
+    int tiles_per_slice, int slices, int nqt, u64 *__restrict__ keys) {
+    constexpr int WC = Cfg::WC, WQ = Cfg::WQ, NWC = Cfg::NWC, BC = Cfg::BC, BQ = Cfg::BQ, NT = Cfg::NT, NW = Cfg::NW,
+                  STAGE = Cfg::STAGE, NLA = Cfg::NLA, NLB = Cfg::NLB, NL = Cfg::NL, NSTAGE = Cfg::NSTAGE;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-    float *inv_s = (float *)(smem + 2 * STAGE);  // [2][BC], by tile parity
+    float *inv_s = (float *)(smem + NSTAGE * STAGE);  // [2][BC], by tile parity
 
     const int tid = threadIdx.x;
-    const int wave = tid >> 6, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
     const int wc = wave % NWC, wq = wave / NWC;
     const int h = lane >> 5, l32 = lane & 31;
 
     const int qt = blockIdx.x % nqt, s = blockIdx.x / nqt;
     const long q0 = (long)qt * BQ;
-    const long total_ct = (K + BC - 1) / BC;
-    const long ct_begin = (long)s * tiles_per_slice;
-    const long ct_end = (ct_begin + tiles_per_slice < total_ct) ? ct_begin + tiles_per_slice : total_ct;
-    const int nk = d / BK;
+    const int total_ct = (int)((K + BC - 1) / BC);
+    const int ct_begin = s * tiles_per_slice;
+    const int ct_end = (ct_begin + tiles_per_slice < total_ct) ? ct_begin + tiles_per_slice : total_ct;
+    const int nk = d / 64;
+    const int T = (ct_end - ct_begin) * nk;  // slabs this workgroup walks through
 
-    // global -> LDS chunk assignment of this thread: chunk id = tid + j*NT, row = id / CPR,
-    // c = id % CPR, LDS slot = c ^ ((row / RP) % CPR).  Successive j move RSTEP rows down,
-    // which changes neither c nor the swizzle term.
-    constexpr int RSTEP = NT / CPR;
-    static_assert(RSTEP % (RP * CPR) == 0, "row step keeps the swizzle term");
-    const int row0 = tid / CPR, c0k = tid % CPR;
-    const int lds0 = (row0 * CPR + (c0k ^ ((row0 / RP) % CPR))) * 16;
-    unsigned b_off[NB];  // element offsets from Q + q0*d, rows clamped into the batch
+    // direct-load addressing
+    const int lr = lane >> 3, slot = lane & 7;
+    unsigned a_off[NLA], b_off[NLB];
 #pragma unroll
-    for (int j = 0; j < NB; ++j) {
-        long qr = q0 + row0 + j * RSTEP;
+    for (int j = 0; j < NLA; ++j) {
+        const int row = (j * NW + wave) * 8 + lr;
+        a_off[j] = (unsigned)(row * d + ((slot ^ ((row >> 1) & 7)) * 8));
+    }
+#pragma unroll
+    for (int j = 0; j < NLB; ++j) {
+        const int row = (j * NW + wave) * 8 + lr;
+        long qr = q0 + row;
         if (qr > n - 1) qr = n - 1;
-        b_off[j] = (unsigned)((qr - q0) * d + c0k * 8);
+        b_off[j] = (unsigned)((qr - q0) * d + ((slot ^ ((row >> 1) & 7)) * 8));
     }
     const bf16_t *qbase = Q + (size_t)q0 * d;
 
-    // fragment read offsets of this lane inside a stage
-    const int sw = (l32 / RP) % CPR;
-    int fa[WC], fb[WQ];
+    // fragment read addresses of this lane: LDS byte offset of its row in the centroid / query
+    // part of stage 0, plus the swizzled 16-byte slot of each of the four 16-element steps
+    const int sw = (l32 >> 1) & 7;
+    const unsigned lds0 = (unsigned)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)smem;
+    const unsigned row_a = lds0 + (unsigned)(((wc * WC) * 32 + l32) * 128);
+    const unsigned row_b = lds0 + (unsigned)(BC * 128 + ((wq * WQ) * 32 + l32) * 128);
+    unsigned so[4];
 #pragma unroll
-    for (int a = 0; a < WC; ++a) fa[a] = ((wc * WC + a) * 32 + l32) * CPR * 16;
-#pragma unroll
-    for (int b = 0; b < WQ; ++b) fb[b] = BC * BK * 2 + ((wq * WQ + b) * 32 + l32) * CPR * 16;
+    for (int kk = 0; kk < 4; ++kk) so[kk] = (unsigned)(((kk * 2 + h) ^ sw) * 16);
 
     float bv[WQ];
     unsigned bb[WQ];
@@ -94,89 +152,114 @@ __global__ __launch_bounds__(Cfg::NT) __attribute__((amdgpu_waves_per_eu(Cfg::WP
         bv[b] = -INFINITY;
         bb[b] = 0xFFFFFFFFu;
     }
+    f32x16 acc[WC][WQ];
+#pragma unroll
+    for (int a = 0; a < WC; ++a)
+#pragma unroll
+        for (int b = 0; b < WQ; ++b)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc[a][b][i] = 0.f;
 
-    for (long ct = ct_begin; ct < ct_end; ++ct) {
-        const long c0 = ct * BC;
-        float *inv_t = inv_s + (ct & 1) * BC;
-        for (int r = tid; r < BC; r += NT) inv_t[r] = (c0 + r < K) ? invn[c0 + r] : __uint_as_float(0x7FC00000u);
+    // slab t lives in stage t % NSTAGE; (ld_ct, ld_ks, ld_stage) name the slab the next issue fetches.
+    // With slab 0 of a tile travel the inverse lengths of the tile's centroids (the rows past the
+    // live ones hold NaN), one 4-byte direct load per lane of the first BC/64 waves.
+    int ld_ct = ct_begin, ld_ks = 0, ld_stage = 0;
+    auto issue = [&]() {
+        if (ld_ks == 0 && wave < BC / 64)
+            gload_lds4(invn + (size_t)ld_ct * BC + wave * 64 + lane, inv_s + (ld_ct & 1) * BC + wave * 64);
+        const bf16_t *cb = C + (size_t)ld_ct * BC * d + ld_ks * 64;
+        const bf16_t *qb = qbase + ld_ks * 64;
+        unsigned char *sb = smem + ld_stage * STAGE;
+#pragma unroll
+        for (int j = 0; j < NLA; ++j) gload_lds16(cb + a_off[j], sb + (j * NW + wave) * 1024);
+#pragma unroll
+        for (int j = 0; j < NLB; ++j) gload_lds16(qb + b_off[j], sb + BC * 128 + (j * NW + wave) * 1024);
+        if (++ld_ks == nk) {
+            ld_ks = 0;
+            ++ld_ct;
+        }
+        if (++ld_stage == NSTAGE) ld_stage = 0;
+    };
 
-        // rows past K are readable (the centroid array is padded by a tile) and never win
-        const bf16_t *abase = C + (size_t)(c0 + row0) * d + c0k * 8;
-        const size_t astep = (size_t)RSTEP * d;
+    // Pipeline:
+    //   steps 0..2 of slab t | wait: own reads of slab t done, own loads of slab t+1 landed | barrier |
+    //   issue the loads of slab t+NSTAGE into the stage just vacated | read step-0 fragments of slab t+1 |
+    //   step 3 of slab t | epilogue if the tile is complete
+    // so the loads have NSTAGE-1 slabs of time to land and the MFMAs of step 3 cover the barrier's
+    // tail.  Loads complete in order: "all but the newest (NSTAGE-2)*NL" = slab t+1 has landed.  (The
+    // inverse lengths ride along as one more load now and then, which only makes a wait stricter; they
+    // are older than the slab issued with them, so they have landed one barrier later at the latest,
+    // and the epilogue of their tile comes after that barrier because a tile has at least two slabs.)
+    constexpr int NF = WC + WQ;  // fragment reads per step
+    bf16x8 af[2][WC], bf[2][WQ];
+    for (int i = 0; i < NSTAGE && i < T; ++i) issue();
+    if (T >= NSTAGE) vm_wait<(NSTAGE - 1) * NL>();
+    else vm_wait<0>();
+    __syncthreads();
+    if (T > 0) lds_frags(af[0], bf[0], row_a + so[0], row_b + so[0]);
 
-        f32x16 acc[WC][WQ];
+    int ct = ct_begin, ks = 0;
+    unsigned sto = 0;  // byte offset of the stage of slab t
+    for (int t = 0; t < T; ++t) {
+        const unsigned sto_next = (sto + STAGE == NSTAGE * STAGE) ? 0u : sto + STAGE;
+#pragma unroll
+        for (int kk = 0; kk < 3; ++kk) {
+            lds_frags(af[(kk + 1) & 1], bf[(kk + 1) & 1], row_a + sto + so[kk + 1], row_b + sto + so[kk + 1]);
+            lds_wait<NF>(af[kk & 1], bf[kk & 1]);
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int a = 0; a < WC; ++a)
+#pragma unroll
+                for (int b = 0; b < WQ; ++b)
+                    acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[kk & 1][a], bf[kk & 1][b], acc[a][b], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        lds_wait<0>(af[1], bf[1]);
+        if (t + NSTAGE <= T) vm_wait<(NSTAGE - 2) * NL>();
+        else vm_wait<0>();
+        __syncthreads();
+        if (t + NSTAGE < T) issue();
+        if (t + 1 < T) lds_frags(af[0], bf[0], row_a + sto_next + so[0], row_b + sto_next + so[0]);
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int a = 0; a < WC; ++a)
 #pragma unroll
             for (int b = 0; b < WQ; ++b)
+                acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[1][a], bf[1][b], acc[a][b], 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        if (ks == nk - 1) {
+            // tile done: scale by 1/|c|, fold into the running maximum of each query column
+            const long c0 = (long)ct * BC;
+            const float *inv_t = inv_s + (ct & 1) * BC;
 #pragma unroll
-                for (int i = 0; i < 16; ++i) acc[a][b][i] = 0.f;
-
-        u32x4 pa[NA], pb[NB];
+            for (int a = 0; a < WC; ++a) {
+                const int rb = (wc * WC + a) * 32;
+                f32x4 w[4];
 #pragma unroll
-        for (int j = 0; j < NA; ++j) pa[j] = *(const u32x4 *)(abase + j * astep);
+                for (int g = 0; g < 4; ++g) w[g] = *(const f32x4 *)(inv_t + rb + 8 * g + 4 * h);
+                const unsigned blk = (unsigned)((c0 + rb) / SISO_RUN_ROWS) * 4u + 2u * (unsigned)h;
 #pragma unroll
-        for (int j = 0; j < NB; ++j) pb[j] = *(const u32x4 *)(qbase + b_off[j]);
+                for (int b = 0; b < WQ; ++b) {
+                    float m = -INFINITY;
 #pragma unroll
-        for (int j = 0; j < NA; ++j) *(u32x4 *)(smem + lds0 + j * (RSTEP * BK * 2)) = pa[j];
-#pragma unroll
-        for (int j = 0; j < NB; ++j) *(u32x4 *)(smem + BC * BK * 2 + lds0 + j * (RSTEP * BK * 2)) = pb[j];
-        __syncthreads();
-
-        for (int it = 0; it < nk; ++it) {
-            const unsigned char *st = smem + (it & 1) * STAGE;
-            const bool more = it + 1 < nk;
-            if (more) {
-                const int koff = (it + 1) * BK;
-#pragma unroll
-                for (int j = 0; j < NA; ++j) pa[j] = *(const u32x4 *)(abase + j * astep + koff);
-#pragma unroll
-                for (int j = 0; j < NB; ++j) pb[j] = *(const u32x4 *)(qbase + b_off[j] + koff);
-            }
-#pragma unroll
-            for (int kk = 0; kk < BK / 16; ++kk) {
-                const int slot = ((kk * 2 + h) ^ sw) * 16;
-                bf16x8 af[WC], bf[WQ];
-#pragma unroll
-                for (int a = 0; a < WC; ++a) af[a] = __builtin_bit_cast(bf16x8, *(const u32x4 *)(st + fa[a] + slot));
-#pragma unroll
-                for (int b = 0; b < WQ; ++b) bf[b] = __builtin_bit_cast(bf16x8, *(const u32x4 *)(st + fb[b] + slot));
-#pragma unroll
-                for (int a = 0; a < WC; ++a)
-#pragma unroll
-                    for (int b = 0; b < WQ; ++b)
-                        acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[a], bf[b], acc[a][b], 0, 0, 0);
-            }
-            if (more) {
-                unsigned char *nx = smem + ((it + 1) & 1) * STAGE;
-#pragma unroll
-                for (int j = 0; j < NA; ++j) *(u32x4 *)(nx + lds0 + j * (RSTEP * BK * 2)) = pa[j];
-#pragma unroll
-                for (int j = 0; j < NB; ++j) *(u32x4 *)(nx + BC * BK * 2 + lds0 + j * (RSTEP * BK * 2)) = pb[j];
-            }
-            __syncthreads();
-        }
-
-        // epilogue: scale by 1/|c|, fold into the running maximum of each query column
-#pragma unroll
-        for (int a = 0; a < WC; ++a) {
-            const int rb = (wc * WC + a) * 32;
-            f32x4 w[4];
-#pragma unroll
-            for (int g = 0; g < 4; ++g) w[g] = *(const f32x4 *)(inv_t + rb + 8 * g + 4 * h);
-            const unsigned blk = (unsigned)((c0 + rb) / SISO_RUN_ROWS) * 4u + 2u * (unsigned)h;
-#pragma unroll
-            for (int b = 0; b < WQ; ++b) {
-                float m = -INFINITY;
-#pragma unroll
-                for (int i = 0; i < 16; ++i) m = fmaxf(m, acc[a][b][i] * w[i >> 2][i & 3]);
-                if (m > bv[b]) {
-                    bv[b] = m;
-                    bb[b] = blk;
+                    for (int i = 0; i < 16; ++i) {
+                        m = fmaxf(m, acc[a][b][i] * w[i >> 2][i & 3]);
+                        acc[a][b][i] = 0.f;
+                    }
+                    if (m > bv[b]) {
+                        bv[b] = m;
+                        bb[b] = blk;
+                    }
                 }
             }
+            ks = 0;
+            ++ct;
+        } else {
+            ++ks;
         }
+        sto = sto_next;
     }
+    __syncthreads();
 
     // lanes l and l^32 hold the same query column
 #pragma unroll
@@ -186,7 +269,7 @@ __global__ __launch_bounds__(Cfg::NT) __attribute__((amdgpu_waves_per_eu(Cfg::WP
         siso_merge_candidate(bv[b], bb[b], ov, ob);
     }
     // waves with the same wq share query columns: meet in LDS (stage memory is free now)
-    float *red_v = (float *)smem;               // [NWC][BQ]
+    float *red_v = (float *)smem;  // [NWC][BQ]
     unsigned *red_b = (unsigned *)(smem + NWC * BQ * 4);
     if (h == 0) {
 #pragma unroll
@@ -201,39 +284,34 @@ __global__ __launch_bounds__(Cfg::NT) __attribute__((amdgpu_waves_per_eu(Cfg::WP
         float v = red_v[col];
         unsigned blk = red_b[col];
 #pragma unroll
-        for (int w2 = 1; w2 < NWC; ++w2) {
-            siso_merge_candidate(v, blk, red_v[w2 * BQ + col], red_b[w2 * BQ + col]);
-        }
+        for (int w2 = 1; w2 < NWC; ++w2) siso_merge_candidate(v, blk, red_v[w2 * BQ + col], red_b[w2 * BQ + col]);
         const long q = q0 + col;
         if (q < n) keys[(size_t)q * slices + s] = (blk == 0xFFFFFFFFu) ? 0ull : pack_key(v, blk);
     }
 }
 
+typedef PipeCfg<4, 2, 2, 4, 2> PipeLarge;  // 256 x 256 tile, waves of 128 x 64, two stages
+typedef PipeCfg<2, 2, 4, 2, 3> PipeMid;    // 256 x 128 tile, waves of 64 x 64, three stages
+typedef PipeCfg<1, 2, 8, 1, 3> PipeSmall;  // 256 x 64 tile, waves of 32 x 64, three stages
+
 // ----------------------------------------------------------------------------
 // host side
 // ----------------------------------------------------------------------------
-typedef LookupCfg<4, 4, 2, 2, 64, 1> CfgA;  // 256 x 256 tile, 4 waves of 128 x 128
-typedef LookupCfg<4, 2, 2, 4, 64, 2> CfgB;  // 256 x 256 tile, 8 waves of 128 x 64
-typedef LookupCfg<4, 2, 2, 2, 32, 2> CfgC;  // 256 x 128 tile, 4 waves of 128 x 64, several workgroups per CU
-
-struct MfmaPlan {
+struct PipePlan {
     int cfg, bc, bq, tiles_per_slice, slices, nqt;
 };
 
-static bool mfma_plan(const siso_cache *c, long n, MfmaPlan *p) {
-    if (c->dtype != SISO_BF16 || c->dim % 64 != 0 || c->count < 1 || n < 1) return false;
-    int cfg = c->opt_mfma_config;
-    if (cfg == 0) cfg = 2;
+// cfg: 1 = PipeLarge, 2 = PipeMid, 3 = PipeSmall
+static bool pipe_plan(const siso_cache *c, long n, int cfg, long want_wgs, PipePlan *p) {
+    if (c->dtype != SISO_BF16 || c->dim % 64 != 0 || c->dim < 128 || c->count < 1 || n < 1) return false;
     if (cfg < 1 || cfg > 3) return false;
     p->cfg = cfg;
-    p->bc = cfg == 1 ? CfgA::BC : cfg == 2 ? CfgB::BC : CfgC::BC;
-    p->bq = cfg == 1 ? CfgA::BQ : cfg == 2 ? CfgB::BQ : CfgC::BQ;
+    p->bc = 256;
+    p->bq = cfg == 1 ? PipeLarge::BQ : cfg == 2 ? PipeMid::BQ : PipeSmall::BQ;
     const long nqt = (n + p->bq - 1) / p->bq;
     const long ct = (c->count + p->bc - 1) / p->bc;
     long tps = c->opt_tiles_per_slice;
     if (tps <= 0) {
-        // about eight workgroups per compute unit when there is enough work
-        const long want_wgs = 2048;
         tps = (ct * nqt + want_wgs - 1) / want_wgs;
         if (tps < 1) tps = 1;
     }
@@ -246,33 +324,61 @@ static bool mfma_plan(const siso_cache *c, long n, MfmaPlan *p) {
     return true;
 }
 
-int siso_mfma_slices(const siso_cache *c, long n) {
-    MfmaPlan p;
-    return mfma_plan(c, n, &p) ? p.slices : 0;
+static bool mfma_plan(const siso_cache *c, long n, PipePlan *p) {
+    int cfg = c->opt_mfma_config;
+    if (cfg == 0) cfg = n <= 64 ? 3 : n <= 128 ? 2 : 1;
+    // about two workgroups per compute unit when there is enough work
+    return pipe_plan(c, n, cfg, 512, p);
+}
+
+static bool skinny_plan(const siso_cache *c, long n, PipePlan *p) {
+    if (n > 64) return false;
+    // exactly one workgroup per compute unit: every one streams an equal share of the centroids
+    return pipe_plan(c, n, 3, 256, p);
 }
 
 template <class Cfg>
-static int launch_cfg(siso_cache *c, const void *queries, long n, const MfmaPlan &p) {
+static int launch_cfg(siso_cache *c, const void *queries, long n, const PipePlan &p) {
     static bool attr_done = false;
     if (!attr_done) {
-        hipError_t e = hipFuncSetAttribute((const void *)k_lookup_mfma<Cfg>, hipFuncAttributeMaxDynamicSharedMemorySize,
+        hipError_t e = hipFuncSetAttribute((const void *)k_lookup_pipe<Cfg>, hipFuncAttributeMaxDynamicSharedMemorySize,
                                            Cfg::LDS_BYTES);
-        if (e != hipSuccess) return siso_check_hip(c, e, "hipFuncSetAttribute(k_lookup_mfma)");
+        if (e != hipSuccess) return siso_check_hip(c, e, "hipFuncSetAttribute(k_lookup_pipe)");
         attr_done = true;
     }
-    hipLaunchKernelGGL(k_lookup_mfma<Cfg>, dim3((unsigned)(p.nqt * p.slices)), dim3(Cfg::NT), Cfg::LDS_BYTES, c->stream,
+    hipLaunchKernelGGL(k_lookup_pipe<Cfg>, dim3((unsigned)(p.nqt * p.slices)), dim3(Cfg::NT), Cfg::LDS_BYTES, c->stream,
                        (const bf16_t *)queries, (const bf16_t *)c->cent, c->invn, n, c->count, c->dim,
                        p.tiles_per_slice, p.slices, p.nqt, c->keys);
-    return siso_check_hip(c, hipGetLastError(), "k_lookup_mfma");
+    return siso_check_hip(c, hipGetLastError(), "k_lookup_pipe");
+}
+
+static int pipe_launch(siso_cache *c, const void *queries, long n, const PipePlan &p) {
+    if (((uintptr_t)queries & 15) != 0) return siso_fail(c, SISO_EINVAL, "bf16 lookup: queries must be 16-byte aligned");
+    switch (p.cfg) {
+        case 1: return launch_cfg<PipeLarge>(c, queries, n, p);
+        case 2: return launch_cfg<PipeMid>(c, queries, n, p);
+        default: return launch_cfg<PipeSmall>(c, queries, n, p);
+    }
+}
+
+int siso_mfma_slices(const siso_cache *c, long n) {
+    PipePlan p;
+    return mfma_plan(c, n, &p) ? p.slices : 0;
 }
 
 int siso_mfma_launch(siso_cache *c, const void *queries, long n, int slices) {
-    MfmaPlan p;
+    PipePlan p;
     if (!mfma_plan(c, n, &p) || p.slices != slices) return siso_fail(c, SISO_EINVAL, "mfma lookup: plan mismatch");
-    if (((uintptr_t)queries & 15) != 0) return siso_fail(c, SISO_EINVAL, "mfma lookup: queries must be 16-byte aligned");
-    switch (p.cfg) {
-        case 1: return launch_cfg<CfgA>(c, queries, n, p);
-        case 2: return launch_cfg<CfgB>(c, queries, n, p);
-        default: return launch_cfg<CfgC>(c, queries, n, p);
-    }
+    return pipe_launch(c, queries, n, p);
+}
+
+int siso_skinny_slices(const siso_cache *c, long n) {
+    PipePlan p;
+    return skinny_plan(c, n, &p) ? p.slices : 0;
+}
+
+int siso_skinny_launch(siso_cache *c, const void *queries, long n, int slices) {
+    PipePlan p;
+    if (!skinny_plan(c, n, &p) || p.slices != slices) return siso_fail(c, SISO_EINVAL, "skinny lookup: plan mismatch");
+    return pipe_launch(c, queries, n, p);
 }

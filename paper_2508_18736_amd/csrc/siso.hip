@@ -693,7 +693,8 @@ extern "C" int siso_create_ex(int dim, long capacity, int dtype, siso_cache **ou
     ok = ok && hipMemset(c->cent, 0, cent_bytes) == hipSuccess;
     ok = ok && hipMalloc((void **)&c->mean, cells * sizeof(float)) == hipSuccess;
     ok = ok && hipMalloc((void **)&c->size, (size_t)capacity * sizeof(int)) == hipSuccess;
-    ok = ok && hipMalloc((void **)&c->invn, (size_t)capacity * sizeof(float)) == hipSuccess;
+    ok = ok && hipMalloc((void **)&c->invn, ((size_t)capacity + SISO_PAD_ROWS) * sizeof(float)) == hipSuccess;
+    ok = ok && hipMemset(c->invn, 0, ((size_t)capacity + SISO_PAD_ROWS) * sizeof(float)) == hipSuccess;
     ok = ok && hipMalloc((void **)&c->counters, 4 * sizeof(u64)) == hipSuccess;
     ok = ok && hipHostMalloc((void **)&c->host_pin, 4 * sizeof(u64), hipHostMallocDefault) == hipSuccess;
     ok = ok && hipMemset(c->counters, 0, 4 * sizeof(u64)) == hipSuccess;
@@ -757,6 +758,8 @@ extern "C" long siso_count(const siso_cache *c) { return c ? c->count : (long)SI
 
 extern "C" const char *siso_last_error(const siso_cache *c) { return c ? c->err : "null cache"; }
 
+__global__ void k_fill_nan(float *p, int count);
+
 extern "C" int siso_load(siso_cache *c, const void *centroids, const int *counts, long k) {
     if (!c) return SISO_EINVAL;
     if (k < 0 || (k > 0 && !centroids)) return siso_fail(c, SISO_EINVAL, "siso_load: bad arguments");
@@ -770,6 +773,8 @@ extern "C" int siso_load(siso_cache *c, const void *centroids, const int *counts
                                (const bf16_t *)centroids, counts, (bf16_t *)c->cent, c->mean, c->size, c->invn, c->dim);
         HIP_TRY(c, hipGetLastError());
     }
+    hipLaunchKernelGGL(k_fill_nan, dim3(1), dim3(SISO_PAD_ROWS), 0, c->stream, c->invn + k, SISO_PAD_ROWS);
+    HIP_TRY(c, hipGetLastError());
     c->count = k;
     return SISO_OK;
 }
@@ -868,6 +873,13 @@ static int read_counter(siso_cache *c, int which, u64 *value) {
 }
 
 __global__ void k_zero_counter(u64 *p) { *p = 0; }
+
+// The tiled kernels read the inverse lengths of a whole last tile; the entries just past the
+// live centroids hold NaN so that those rows never win.
+__global__ void k_fill_nan(float *p, int count) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < count) p[i] = __uint_as_float(0x7FC00000u);
+}
 
 extern "C" long siso_bad_indices(siso_cache *c) {
     if (!c) return SISO_EINVAL;
@@ -974,6 +986,10 @@ extern "C" int siso_merge_apply(siso_cache *c, const int *pairs, long n_pairs, i
             if (rc == SISO_OK)
                 rc = siso_check_hip(c, hipMemcpyAsync(c->invn, invn2, (size_t)live * sizeof(float), hipMemcpyDeviceToDevice, c->stream), "copy back");
         }
+    }
+    if (rc == SISO_OK) {
+        hipLaunchKernelGGL(k_fill_nan, dim3(1), dim3(SISO_PAD_ROWS), 0, c->stream, c->invn + live, SISO_PAD_ROWS);
+        rc = siso_check_hip(c, hipGetLastError(), "k_fill_nan");
     }
     (void)hipStreamSynchronize(c->stream);
     if (rc == SISO_OK) c->count = live;

@@ -1,0 +1,24 @@
+"""The hand-scheduled kernels rely on the compiler leaving in-flight registers alone; check the
+generated ISA (CPU only: hipcc cross-compiles)."""
+
+import shutil
+
+import pytest
+
+import isa_check
+
+
+@pytest.mark.skipif(shutil.which("hipcc") is None, reason="needs hipcc")
+@pytest.mark.parametrize("source", ["lookup_mfma.hip"])
+def test_no_instruction_touches_a_fragment_register_in_flight(source):
+    asm = isa_check.device_asm(source)
+    ks = isa_check.kernels(asm)
+    checked = 0
+    for name, lines in ks.items():
+        reads = [l for l in lines if l.startswith("ds_read_b128") and "hand-scheduled" in l]
+        if not reads:
+            continue
+        bad = isa_check.inflight_violations(lines)
+        assert not bad, f"{name}: {bad[:3]}"
+        checked += 1
+    assert checked >= 3
