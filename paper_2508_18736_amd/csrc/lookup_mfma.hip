@@ -26,6 +26,11 @@
 // this swizzle the 16 rows x 16 bytes of a fragment read cover all 64 banks.  A
 // direct load of one wave fills 1 KiB = 8 consecutive rows: lane i writes slot
 // i % 8 of row i / 8, so it fetches chunk (i % 8) ^ ((r >> 1) & 7) of that row.
+//
+// The same stream of tiles, with another epilogue, is the pair search behind
+// MergeCentroids: the "query" tile is a tile of centroids too, a workgroup walks
+// through the centroid tiles at or right of it (upper triangle), and every
+// product above the threshold is emitted as a pair (i, j), i < j.
 #include "siso_internal.h"
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
@@ -96,10 +101,14 @@ __device__ __forceinline__ void vm_wait() {
     asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
 }
 
-template <class Cfg>
+#define PIPE_LOOKUP 0
+#define PIPE_PAIRS 1
+
+template <class Cfg, int MODE>
 __global__ __launch_bounds__(Cfg::NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void k_lookup_pipe(
     const bf16_t *__restrict__ Q, const bf16_t *__restrict__ C, const float *__restrict__ invn, long n, long K, int d,
-    int tiles_per_slice, int slices, int nqt, u64 *__restrict__ keys) {
+    int tiles_per_slice, int slices, int nqt, u64 *__restrict__ keys, float threshold, int *__restrict__ out_pairs,
+    long cap, u64 *__restrict__ counter) {
     constexpr int WC = Cfg::WC, WQ = Cfg::WQ, NWC = Cfg::NWC, BC = Cfg::BC, BQ = Cfg::BQ, NT = Cfg::NT, NW = Cfg::NW,
                   STAGE = Cfg::STAGE, NLA = Cfg::NLA, NLB = Cfg::NLB, NL = Cfg::NL, NSTAGE = Cfg::NSTAGE;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
@@ -110,10 +119,22 @@ __global__ __launch_bounds__(Cfg::NT) __attribute__((amdgpu_waves_per_eu(2, 2)))
     const int wc = wave % NWC, wq = wave / NWC;
     const int h = lane >> 5, l32 = lane & 31;
 
-    const int qt = blockIdx.x % nqt, s = blockIdx.x / nqt;
-    const long q0 = (long)qt * BQ;
+    // lookup: block = (query tile, slice of the centroid tiles).  pairs: block (x, y) = (centroid tile
+    // in the role of the query tile, y-th run of centroid tiles starting at that tile).
     const int total_ct = (int)((K + BC - 1) / BC);
-    const int ct_begin = s * tiles_per_slice;
+    int qt, s, ct_begin;
+    if (MODE == PIPE_LOOKUP) {
+        qt = blockIdx.x % nqt;
+        s = blockIdx.x / nqt;
+        ct_begin = s * tiles_per_slice;
+    } else {
+        static_assert(MODE == PIPE_LOOKUP || Cfg::BC == Cfg::BQ, "pair search walks square tiles");
+        qt = blockIdx.x;
+        s = blockIdx.y;
+        ct_begin = qt + s * tiles_per_slice;
+        if (ct_begin >= total_ct) return;
+    }
+    const long q0 = (long)qt * BQ;
     const int ct_end = (ct_begin + tiles_per_slice < total_ct) ? ct_begin + tiles_per_slice : total_ct;
     const int nk = d / 64;
     const int T = (ct_end - ct_begin) * nk;  // slabs this workgroup walks through
@@ -152,6 +173,9 @@ __global__ __launch_bounds__(Cfg::NT) __attribute__((amdgpu_waves_per_eu(2, 2)))
         bv[b] = -INFINITY;
         bb[b] = 0xFFFFFFFFu;
     }
+    float wi[WQ];  // pairs: 1/|c| of this lane's columns (NaN past the live centroids)
+#pragma unroll
+    for (int b = 0; b < WQ; ++b) wi[b] = MODE == PIPE_PAIRS ? invn[q0 + (wq * WQ + b) * 32 + l32] : 0.f;
     f32x16 acc[WC][WQ];
 #pragma unroll
     for (int a = 0; a < WC; ++a)
@@ -242,14 +266,24 @@ __global__ __launch_bounds__(Cfg::NT) __attribute__((amdgpu_waves_per_eu(2, 2)))
                 for (int b = 0; b < WQ; ++b) {
                     float m = -INFINITY;
 #pragma unroll
-                    for (int i = 0; i < 16; ++i) {
-                        m = fmaxf(m, acc[a][b][i] * w[i >> 2][i & 3]);
-                        acc[a][b][i] = 0.f;
+                    for (int i = 0; i < 16; ++i) m = fmaxf(m, acc[a][b][i] * w[i >> 2][i & 3]);
+                    if (MODE == PIPE_LOOKUP) {
+                        if (m > bv[b]) {
+                            bv[b] = m;
+                            bb[b] = blk;
+                        }
+                    } else if (__ballot(m * wi[b] > threshold) != 0) {
+                        // rare: some product of this 32 x 32 block is above the threshold
+                        const long icol = q0 + (wq * WQ + b) * 32 + l32;
+#pragma unroll
+                        for (int i = 0; i < 16; ++i) {
+                            const long jrow = c0 + rb + 8 * (i >> 2) + 4 * h + (i & 3);
+                            const float sim = acc[a][b][i] * w[i >> 2][i & 3] * wi[b];
+                            emit_pair(sim > threshold && icol < jrow, (int)icol, (int)jrow, out_pairs, cap, counter);
+                        }
                     }
-                    if (m > bv[b]) {
-                        bv[b] = m;
-                        bb[b] = blk;
-                    }
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) acc[a][b][i] = 0.f;
                 }
             }
             ks = 0;
@@ -260,6 +294,7 @@ __global__ __launch_bounds__(Cfg::NT) __attribute__((amdgpu_waves_per_eu(2, 2)))
         sto = sto_next;
     }
     __syncthreads();
+    if (MODE == PIPE_PAIRS) return;
 
     // lanes l and l^32 hold the same query column
 #pragma unroll
@@ -341,14 +376,14 @@ template <class Cfg>
 static int launch_cfg(siso_cache *c, const void *queries, long n, const PipePlan &p) {
     static bool attr_done = false;
     if (!attr_done) {
-        hipError_t e = hipFuncSetAttribute((const void *)k_lookup_pipe<Cfg>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                           Cfg::LDS_BYTES);
+        hipError_t e = hipFuncSetAttribute((const void *)k_lookup_pipe<Cfg, PIPE_LOOKUP>,
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, Cfg::LDS_BYTES);
         if (e != hipSuccess) return siso_check_hip(c, e, "hipFuncSetAttribute(k_lookup_pipe)");
         attr_done = true;
     }
-    hipLaunchKernelGGL(k_lookup_pipe<Cfg>, dim3((unsigned)(p.nqt * p.slices)), dim3(Cfg::NT), Cfg::LDS_BYTES, c->stream,
-                       (const bf16_t *)queries, (const bf16_t *)c->cent, c->invn, n, c->count, c->dim,
-                       p.tiles_per_slice, p.slices, p.nqt, c->keys);
+    hipLaunchKernelGGL((k_lookup_pipe<Cfg, PIPE_LOOKUP>), dim3((unsigned)(p.nqt * p.slices)), dim3(Cfg::NT),
+                       Cfg::LDS_BYTES, c->stream, (const bf16_t *)queries, (const bf16_t *)c->cent, c->invn, n, c->count,
+                       c->dim, p.tiles_per_slice, p.slices, p.nqt, c->keys, 0.f, (int *)nullptr, 0L, (u64 *)nullptr);
     return siso_check_hip(c, hipGetLastError(), "k_lookup_pipe");
 }
 
@@ -381,4 +416,34 @@ int siso_skinny_launch(siso_cache *c, const void *queries, long n, int slices) {
     PipePlan p;
     if (!skinny_plan(c, n, &p) || p.slices != slices) return siso_fail(c, SISO_EINVAL, "skinny lookup: plan mismatch");
     return pipe_launch(c, queries, n, p);
+}
+
+// ----------------------------------------------------------------------------
+// pair search (siso_merge) on the same kernel
+// ----------------------------------------------------------------------------
+int siso_merge_mfma_supported(const siso_cache *c) {
+    if (c->opt_merge_config == 1) return 0;  // 1 = force the scalar kernel
+    return c->dtype == SISO_BF16 && c->dim % 64 == 0 && c->dim >= 128 && c->count >= 2;
+}
+
+int siso_merge_mfma_launch(siso_cache *c, float threshold, int *out_pairs, long cap) {
+    typedef PipeLarge Cfg;
+    const long T = (c->count + Cfg::BC - 1) / Cfg::BC;
+    // runs of tiles short enough for about eight workgroups per compute unit over the triangle
+    long tps = c->opt_tiles_per_slice > 0 ? c->opt_tiles_per_slice : (T * (T + 1) / 2 + 2047) / 2048;
+    if (tps < 1) tps = 1;
+    if (tps > T) tps = T;
+    const long runs = (T + tps - 1) / tps;
+    if (T > 2147483647L || runs > 65535) return siso_fail(c, SISO_EINVAL, "pair search: too many tiles");
+    static bool attr_done = false;
+    if (!attr_done) {
+        hipError_t e = hipFuncSetAttribute((const void *)k_lookup_pipe<Cfg, PIPE_PAIRS>,
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, Cfg::LDS_BYTES);
+        if (e != hipSuccess) return siso_check_hip(c, e, "hipFuncSetAttribute(pair search)");
+        attr_done = true;
+    }
+    hipLaunchKernelGGL((k_lookup_pipe<Cfg, PIPE_PAIRS>), dim3((unsigned)T, (unsigned)runs), dim3(Cfg::NT), Cfg::LDS_BYTES,
+                       c->stream, (const bf16_t *)c->cent, (const bf16_t *)c->cent, c->invn, c->count, c->count, c->dim,
+                       (int)tps, (int)runs, (int)T, (u64 *)nullptr, threshold, out_pairs, cap, c->counters + 1);
+    return siso_check_hip(c, hipGetLastError(), "pair search kernel");
 }

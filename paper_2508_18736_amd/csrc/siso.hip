@@ -97,22 +97,6 @@ __global__ __launch_bounds__(256) void k_load_rows(const T *__restrict__ src, co
     }
 }
 
-// 1/|q| for every query: one wavefront per row.
-template <typename T>
-__global__ __launch_bounds__(256) void k_query_invnorm(const T *__restrict__ Q, long n, int d, float *qinv) {
-    const long q = (long)blockIdx.x * 4 + (threadIdx.x >> 6);
-    if (q >= n) return;
-    const int lane = threadIdx.x & 63;
-    const T *row = Q + (size_t)q * d;
-    float ss = 0.f;
-    for (int e = lane; e < d; e += 64) {
-        float x = widen(row[e]);
-        ss += x * x;
-    }
-    ss = wave_sum(ss);
-    if (lane == 0) qinv[q] = inv_length(ss);
-}
-
 // 16-byte chunk dot products for the finalize kernel
 typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
 __device__ __forceinline__ float chunk_dot(const float *a, const float *b) {
@@ -137,15 +121,22 @@ __device__ __forceinline__ float chunk_dot(const bf16_t *a, const bf16_t *b) {
 // number of 16-byte chunks.
 template <typename T>
 __global__ __launch_bounds__(256) void k_lookup_finalize(const T *__restrict__ Q, const T *__restrict__ cent,
-                                                          const float *__restrict__ invn,
-                                                          const float *__restrict__ qinv, const u64 *__restrict__ keys,
+                                                          const float *__restrict__ invn, const u64 *__restrict__ keys,
                                                           long n, long K, int d, int slices, float threshold, int vec,
                                                           int *out_idx, float *out_sim, unsigned char *out_hit) {
     constexpr int EPC = 16 / (int)sizeof(T);  // elements per 16-byte chunk
     const long q = (long)blockIdx.x * 4 + (threadIdx.x >> 6);
     if (q >= n) return;
     const int lane = threadIdx.x & 63, grp = lane >> 4, gl = lane & 15;
-    const float qi = qinv[q];
+    const T *qrow = Q + (size_t)q * d;
+    // 1/|q|: 0 for a zero-length query, NaN for a non-finite one
+    float ss = 0.f;
+    if (vec) {
+        for (int e = lane * EPC; e < d; e += 64 * EPC) ss += chunk_dot(qrow + e, qrow + e);
+    } else {
+        for (int e = lane; e < d; e += 64) ss += widen(qrow[e]) * widen(qrow[e]);
+    }
+    const float qi = inv_length(wave_sum(ss));
     long best_i = -1;
     float best_s = -INFINITY;
     if (!(qi == qi)) {
@@ -165,7 +156,6 @@ __global__ __launch_bounds__(256) void k_lookup_finalize(const T *__restrict__ Q
             const unsigned block = 0xFFFFFFFFu - (unsigned)(key & 0xFFFFFFFFull);
             const long run0 = (long)(block >> 2) * SISO_RUN_ROWS;
             const int code = (int)(block & 3u);
-            const T *qrow = Q + (size_t)q * d;
             // pass p, group grp -> local row: one half: 8*p + 4*h + grp; both halves: 4*p + grp
             const int passes = code == 1 ? 8 : 4;
             for (int p = 0; p < passes; ++p) {
@@ -655,19 +645,6 @@ static int ensure_workspace(siso_cache *c, long n, int slices) {
         }
         c->keys_cap = need_keys;
     }
-    if (n > c->qinv_cap) {
-        if (c->qinv) {
-            HIP_TRY(c, hipStreamSynchronize(c->stream));
-            HIP_TRY(c, hipFree(c->qinv));
-            c->qinv = nullptr;
-            c->qinv_cap = 0;
-        }
-        if (hipMalloc((void **)&c->qinv, (size_t)n * sizeof(float)) != hipSuccess) {
-            (void)hipGetLastError();
-            return siso_fail(c, SISO_ENOMEM, "workspace of %ld query norms", n);
-        }
-        c->qinv_cap = n;
-    }
     return SISO_OK;
 }
 
@@ -720,7 +697,6 @@ extern "C" void siso_destroy(siso_cache *c) {
     if (c->size) (void)hipFree(c->size);
     if (c->invn) (void)hipFree(c->invn);
     if (c->keys) (void)hipFree(c->keys);
-    if (c->qinv) (void)hipFree(c->qinv);
     if (c->counters) (void)hipFree(c->counters);
     if (c->host_pin) (void)hipHostFree(c->host_pin);
     if (c->prof_ev) {
@@ -809,13 +785,6 @@ extern "C" int siso_lookup(siso_cache *c, const void *queries, long n, float thr
     if (rc != SISO_OK) return rc;
     const unsigned qblocks = (unsigned)((n + 3) / 4);
     const int vec = ((c->dim * elem_bytes(c->dtype)) % 16 == 0 && ((uintptr_t)queries & 15) == 0) ? 1 : 0;
-    if (c->dtype == SISO_F32)
-        hipLaunchKernelGGL(k_query_invnorm<float>, dim3(qblocks), dim3(256), 0, c->stream, (const float *)queries, n,
-                           c->dim, c->qinv);
-    else
-        hipLaunchKernelGGL(k_query_invnorm<bf16_t>, dim3(qblocks), dim3(256), 0, c->stream, (const bf16_t *)queries, n,
-                           c->dim, c->qinv);
-    HIP_TRY(c, hipGetLastError());
     if (c->count > 0) {
         siso_prof_begin(c);
         switch (path) {
@@ -828,11 +797,11 @@ extern "C" int siso_lookup(siso_cache *c, const void *queries, long n, float thr
     }
     if (c->dtype == SISO_F32)
         hipLaunchKernelGGL(k_lookup_finalize<float>, dim3(qblocks), dim3(256), 0, c->stream, (const float *)queries,
-                           (const float *)c->cent, c->invn, c->qinv, c->keys, n, c->count, c->dim, slices, threshold,
+                           (const float *)c->cent, c->invn, c->keys, n, c->count, c->dim, slices, threshold,
                            vec, out_idx, out_sim, out_hit);
     else
         hipLaunchKernelGGL(k_lookup_finalize<bf16_t>, dim3(qblocks), dim3(256), 0, c->stream, (const bf16_t *)queries,
-                           (const bf16_t *)c->cent, c->invn, c->qinv, c->keys, n, c->count, c->dim, slices, threshold,
+                           (const bf16_t *)c->cent, c->invn, c->keys, n, c->count, c->dim, slices, threshold,
                            vec, out_idx, out_sim, out_hit);
     HIP_TRY(c, hipGetLastError());
     return SISO_OK;

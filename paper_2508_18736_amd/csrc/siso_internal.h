@@ -62,8 +62,6 @@ struct siso_cache {
     // workspace, grown on demand
     u64 *keys;     // [keys_cap] phase-1 keys, n * slices
     long keys_cap;
-    float *qinv;   // [qinv_cap] 1 / |query| (0 for zero length, NaN for non-finite)
-    long qinv_cap;
 
     u64 *counters;  // device: [0] bad update indices, [1] merge pair count, [2] scratch, [3] scratch
     u64 *host_pin;  // pinned host mirror for counter read-back (4 entries)

@@ -127,7 +127,7 @@ def sorted_pairs(p):
 
 @pytest.mark.parametrize("dtype,dim,groups,copies,sigma,theta", [
     ("bf16", 768, 300, 7, 0.03, 0.90), ("f32", 96, 100, 5, 0.05, 0.90), ("bf16", 128, 150, 9, 0.6, 0.7),
-    ("bf16", 1024, 33, 31, 0.03, 0.90)])
+    ("bf16", 1024, 33, 31, 0.03, 0.90), ("bf16", 256, 429, 7, 0.03, 0.90)])
 def test_merge_pairs_and_groups_match_oracle(siso, oracle, dtype, dim, groups, copies, sigma, theta):
     print(f"case: merge {dtype} dim={dim} K={groups * copies} sigma={sigma} theta={theta}", flush=True)
     wl = W.c5_merge(n_groups=groups, copies=copies, dim=dim, sigma=sigma, dtype=dtype, seed=53)
@@ -151,6 +151,15 @@ def test_merge_pairs_and_groups_match_oracle(siso, oracle, dtype, dim, groups, c
         gs, ws = set(map(tuple, got)), set(map(tuple, want))
         assert all(edge[i, j] for i, j in gs ^ ws)
     assert np.all(got[:, 0] < got[:, 1]) and len(np.unique(got, axis=0)) == len(got)
+    # the scalar kernel finds the same set (up to the pairs at the edge of the threshold)
+    cache.set_option("merge_config", 1)
+    got_s, total_s = cache.merge(theta, cap=total + 100)
+    cache.set_option("merge_config", 0)
+    got_s = sorted_pairs(got_s.cpu().numpy())
+    assert all(edge[i, j] for i, j in set(map(tuple, got_s)) ^ set(map(tuple, got)))
+    # a second run gives the same set (the order of emission is free)
+    again, total_a = cache.merge(theta, cap=total + 100)
+    assert total_a == gtotal and np.array_equal(sorted_pairs(again.cpu().numpy()), got)
     if sigma < 0.1:
         assert total == groups * copies * (copies - 1) // 2
     # capped output: full count reported, only cap pairs written, all of them valid
