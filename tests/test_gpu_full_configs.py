@@ -1,0 +1,183 @@
+"""GPU parity at the full sizes of the five configurations, in the launch configuration the
+benchmark uses.  Where the oracle cannot run the whole problem in seconds it runs on a seeded
+sample of queries (or rows), and properties that hold at any size cover the rest."""
+
+import numpy as np
+import pytest
+import torch
+
+from paper_2508_18736_amd import workloads as W
+from gpu_util import DEV, SIM_TOL, check_lookup, to_dev, to_host
+
+pytestmark = [pytest.mark.gpu, pytest.mark.timeout(400)]
+
+
+@pytest.fixture(scope="module")
+def siso():
+    from paper_2508_18736_amd import siso as m
+    return m
+
+
+def unit64(x):
+    x = np.asarray(x, np.float64)
+    return x / np.linalg.norm(x, axis=-1, keepdims=True)
+
+
+def sample_invariant(wl, gi, gs, rows, n_cent, seed):
+    """The returned similarity is the maximum: no sampled centroid beats it (float64, library matmul)."""
+    r = np.random.default_rng(seed)
+    ks = r.choice(wl.K, size=n_cent, replace=False)
+    c = unit64(W.storage_to_f32(wl.centroids[ks], wl.dtype))
+    q = unit64(W.storage_to_f32(wl.queries[rows], wl.dtype))
+    S = q @ c.T
+    assert np.all(S.max(axis=1) <= gs[rows] + SIM_TOL[wl.dtype])
+    # and it is the cosine of the centroid it names
+    cw = unit64(W.storage_to_f32(wl.centroids[gi[rows]], wl.dtype))
+    assert np.max(np.abs(np.einsum("ij,ij->i", q, cw) - gs[rows])) <= 1e-5
+
+
+def test_c2_mid_full(siso, oracle):
+    print("case: c2_mid full size", flush=True)
+    wl = W.c2_mid()
+    assert (wl.K, wl.n, wl.dim) == (65536, 4096, 768)
+    cache = siso.SisoCache(wl.dim, wl.K, siso.BF16)
+    cache.load(to_dev(wl.centroids, "bf16"))
+    q = to_dev(wl.queries, "bf16")
+    outs = [tuple(t.clone() for t in cache.lookup(q, th)) for th in wl.thresholds]
+    torch.cuda.synchronize()
+    for o in outs[1:]:
+        assert torch.equal(o[0], outs[0][0]) and torch.equal(o[1], outs[0][1])
+    hits = [o[2].cpu().numpy() for o in outs]
+    assert np.all(hits[1] <= hits[0]) and np.all(hits[2] <= hits[1])
+    gi, gs = outs[0][0].cpu().numpy(), outs[0][1].cpu().numpy().astype(np.float64)
+    near = wl.planted >= 0
+    assert (gi[near] == wl.planted[near]).mean() > 0.995 and gs[near].min() > 0.99 and gs[~near].max() < 0.5
+    assert abs(hits[1].mean() - 0.7) < 0.03 and np.array_equal(hits[1].astype(bool), near)
+    rows = np.arange(0, wl.n, 16)  # 256 sampled queries through the oracle
+    for th, o in zip(wl.thresholds, outs):
+        ora = oracle.lookup_rows(wl.centroids, wl.queries[rows], th, "bf16")
+        st = check_lookup(tuple(t[rows] for t in o), ora, th, "bf16", f"c2 theta {th}")
+        assert st["max_err"] < 1e-4 and st["clear"] > 100
+    sample_invariant(wl, gi, gs, np.arange(0, wl.n, 32), 4096, 1)
+    # fold the hits of the middle threshold, on the device
+    cache.update(q, outs[1][0], outs[1][2])
+    sizes = cache.export()[2].cpu().numpy()
+    assert sizes.sum() == wl.K + int(hits[1].sum()) and cache.bad_indices() == 0
+
+
+def test_c3_large_full(siso, oracle):
+    print("case: c3_large full size (2 GiB of centroids)", flush=True)
+    wl = W.c3_large()
+    assert (wl.K, wl.n, wl.dim) == (1048576, 16384, 1024)
+    cache = siso.SisoCache(wl.dim, wl.K, siso.BF16)
+    cache.load(to_dev(wl.centroids, "bf16"))
+    q = to_dev(wl.queries, "bf16")
+    idx, sim, hit = cache.lookup(q, 0.85)
+    torch.cuda.synchronize()
+    print("lookup done", flush=True)
+    gi, gs, gh = idx.cpu().numpy(), sim.cpu().numpy().astype(np.float64), hit.cpu().numpy()
+    assert (gi == wl.planted).mean() > 0.995 and gs.min() > 0.99 and gh.all()
+    assert np.array_equal(gh, (sim.cpu().numpy() > np.float32(0.85)).astype(np.uint8))
+    rows = np.arange(0, wl.n, 512)  # 32 sampled queries through the oracle, against all 1,048,576 centroids
+    ora = oracle.lookup_rows(wl.centroids, wl.queries[rows], 0.85, "bf16")
+    print("oracle sample done", flush=True)
+    st = check_lookup((idx[rows], sim[rows], hit[rows]), ora, 0.85, "bf16", "c3")
+    assert st["max_err"] < 1e-4 and st["clear"] >= 16
+    sample_invariant(wl, gi, gs, np.arange(0, wl.n, 128), 8192, 2)
+    # Zipf popularity: the most popular cluster takes a visible share of the batch
+    top = np.bincount(wl.cluster_of[gi]).max()
+    assert top > 0.02 * wl.n
+
+
+def test_c4_stream_full(siso, oracle):
+    print("case: c4_stream, 262,144 centroids, micro-batches of 64 with update in between", flush=True)
+    wl = W.c4_stream(batches=96)
+    assert (wl.K, wl.dim, wl.batch) == (262144, 768, 64)
+    th = 0.85
+    cache = siso.SisoCache(wl.dim, wl.K, siso.BF16)
+    cache.load(to_dev(wl.centroids, "bf16"))
+    oc = oracle.OracleCache(wl.dim, wl.K, "bf16")
+    oc.load(wl.centroids)
+    q_all = to_dev(wl.queries, "bf16")
+    total_hits = 0
+    lock = 3  # batches run in lockstep with the oracle
+    outs = []
+    for b in range(96):
+        q = q_all[b * 64:(b + 1) * 64]
+        idx, sim, hit = cache.lookup(q, th)
+        cache.update(q, idx, hit)          # no host synchronisation between the two
+        outs.append((idx, sim, hit))
+        if b < lock:
+            ora = oc.lookup(wl.queries[b * 64:(b + 1) * 64], th)
+            check_lookup((idx, sim, hit), ora, th, "bf16", f"c4 batch {b}")
+            assert np.array_equal(idx.cpu().numpy(), ora[0]) and np.array_equal(hit.cpu().numpy(), ora[2])
+            oc.update(wl.queries[b * 64:(b + 1) * 64], np.where(ora[2] == 1, ora[0], -1).astype(np.int32))
+            print(f"batch {b} matches the oracle", flush=True)
+        if b == lock - 1:
+            gc, gm, gsz = cache.export()
+            oc_c, oc_m, oc_s = oc.export()
+            assert np.array_equal(gsz.cpu().numpy(), oc_s)
+            touched = np.nonzero(oc_s > 1)[0]
+            assert len(touched) > 50
+            assert np.abs(gm[touched].cpu().numpy().astype(np.float64) - oc_m[touched]).max() < 2e-6
+            g = to_host(gc, "bf16")
+            assert (g[touched] != oc_c[touched]).mean() < 2e-3 and np.array_equal(np.delete(g, touched, 0),
+                                                                                 np.delete(oc_c, touched, 0))
+    torch.cuda.synchronize()
+    for idx, sim, hit in outs:
+        total_hits += int(hit.sum().item())
+    gi = torch.stack([o[0] for o in outs]).cpu().numpy().reshape(-1)
+    assert (gi == wl.planted).mean() > 0.99
+    gc, gm, gsz = cache.export()
+    assert int(gsz.sum().item()) == wl.K + total_hits and total_hits > 0.95 * 96 * 64
+    norms = torch.linalg.vector_norm(gc.float(), dim=1)
+    assert float((norms - 1).abs().max()) < 3e-3 and cache.bad_indices() == 0
+
+
+def test_c5_merge_full(siso, oracle):
+    print("case: c5_merge full size", flush=True)
+    wl = W.c5_merge()
+    assert (wl.K, wl.dim) == (131072, 768)
+    th = 0.90
+    cache = siso.SisoCache(wl.dim, wl.K, siso.BF16)
+    cache.load(to_dev(wl.centroids, "bf16"))
+    expected = wl.meta["expected_pairs"]
+    assert expected == 458752
+    pairs, total = cache.merge(th, cap=expected + 4096)
+    assert total == expected            # closed form: C(8,2) pairs in each of the 16,384 groups
+    p = pairs.cpu().numpy()
+    assert np.all(p[:, 0] < p[:, 1]) and len(np.unique(p.astype(np.int64) @ np.array([1 << 20, 1]))) == expected
+    assert np.array_equal(wl.cluster_of[p[:, 0]], wl.cluster_of[p[:, 1]])
+    assert np.all(np.bincount(wl.cluster_of[p[:, 0]], minlength=16384) == 28)
+    # oracle on a subset of rows: 96 whole groups plus 1,280 other rows
+    r = np.random.default_rng(3)
+    groups = r.choice(16384, size=96, replace=False)
+    rows = np.union1d(np.nonzero(np.isin(wl.cluster_of, groups))[0], r.choice(wl.K, size=1280, replace=False))
+    oc = oracle.OracleCache(wl.dim, len(rows), "bf16")
+    oc.load(wl.centroids[rows])
+    want, _ = oc.merge(th)
+    pos = -np.ones(wl.K, np.int64); pos[rows] = np.arange(len(rows))
+    both = (pos[p[:, 0]] >= 0) & (pos[p[:, 1]] >= 0)
+    got = np.stack([pos[p[both, 0]], pos[p[both, 1]]], 1)
+    got = got[np.lexsort((got[:, 1], got[:, 0]))]
+    assert np.array_equal(got, want) and len(want) >= 96 * 28
+    print("pairs match", flush=True)
+    # group merge
+    surv = cache.merge_apply(pairs).cpu().numpy()
+    assert cache.count == 16384
+    first = np.full(16384, wl.K, np.int64)
+    np.minimum.at(first, wl.cluster_of, np.arange(wl.K))
+    order = np.argsort(first)                      # groups in the order of their lowest row
+    newidx = np.empty(16384, np.int64); newidx[order] = np.arange(16384)
+    assert np.array_equal(surv, newidx[wl.cluster_of])
+    gc, gm, gsz = cache.export()
+    assert bool((gsz == 8).all())
+    check = r.choice(16384, size=256, replace=False)
+    u = unit64(W.bf16_bits_to_f32(wl.centroids))
+    gm_h = gm.cpu().numpy().astype(np.float64)
+    gc_h = W.bf16_bits_to_f32(to_host(gc, "bf16")).astype(np.float64)
+    for g in check:
+        mem = np.nonzero(wl.cluster_of == g)[0]
+        want_m = u[mem].mean(axis=0)
+        assert np.abs(gm_h[newidx[g]] - want_m).max() < 2e-6
+        assert np.abs(gc_h[newidx[g]] - unit64(want_m)).max() <= 2.0 ** -8
