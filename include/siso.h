@@ -169,9 +169,10 @@ int siso_merge_apply(siso_cache *c, const int *pairs, long n_pairs, int *out_sur
 int siso_export(siso_cache *c, void *centroids, float *means, int *counts);
 
 /*
- * Kernel timing for benchmarks.  While enabled (on != 0), every siso_lookup and
- * siso_merge brackets its dominant kernel (the similarity kernel, without the
- * norm and finalize kernels) with a pair of HIP events on the cache's stream.
+ * Kernel timing for benchmarks.  While enabled (on = N > 0), every N-th
+ * siso_lookup / siso_merge brackets its dominant kernel (the similarity kernel,
+ * without the finalize kernel) with a pair of HIP events on the cache's stream
+ * (an event costs a few microseconds on the stream, so short steps sample).
  * siso_profile_read synchronises with the stream, returns the sum of the
  * bracketed durations in milliseconds and the number of brackets since the
  * last read (host pointers, either may be NULL), and releases the events.

@@ -37,7 +37,9 @@ int siso_check_hip(siso_cache *c, hipError_t e, const char *what) {
 #define SISO_PROF_MAX 8192
 
 void siso_prof_begin(siso_cache *c) {
+    c->prof_open = 0;
     if (!c->profile_on || c->prof_count >= SISO_PROF_MAX) return;
+    if (c->prof_calls++ % c->profile_on != 0) return;
     if (!c->prof_ev) {
         c->prof_ev = (hipEvent_t *)calloc(2 * SISO_PROF_MAX, sizeof(hipEvent_t));
         if (!c->prof_ev) return;
@@ -45,10 +47,11 @@ void siso_prof_begin(siso_cache *c) {
     hipEvent_t *e = c->prof_ev + 2 * c->prof_count;
     if (hipEventCreate(&e[0]) != hipSuccess || hipEventCreate(&e[1]) != hipSuccess) return;
     (void)hipEventRecord(e[0], c->stream);
+    c->prof_open = 1;
 }
 
 void siso_prof_end(siso_cache *c) {
-    if (!c->profile_on || !c->prof_ev || c->prof_count >= SISO_PROF_MAX) return;
+    if (!c->prof_open) return;
     hipEvent_t *e = c->prof_ev + 2 * c->prof_count;
     if (!e[0] || !e[1]) return;
     (void)hipEventRecord(e[1], c->stream);
@@ -116,80 +119,95 @@ __device__ __forceinline__ float chunk_dot(const bf16_t *a, const bf16_t *b) {
 
 // Finalize: per query, max over the slice keys, then the exact cosines of the rows of
 // the winning block (strict ">" in ascending row order, so the lowest index keeps a
-// tie), and the strict threshold test.  One wavefront per query; its four groups of
-// 16 lanes take one centroid row each.  `vec` = rows are 16-byte aligned and a whole
-// number of 16-byte chunks.
+// tie), and the strict threshold test.  One 256-thread block per query: its sixteen
+// groups of 16 lanes take one centroid row each, so the 16 rows of a block are in
+// flight together.  `vec` = rows are 16-byte aligned and a whole number of 16-byte
+// chunks.
 template <typename T>
 __global__ __launch_bounds__(256) void k_lookup_finalize(const T *__restrict__ Q, const T *__restrict__ cent,
                                                           const float *__restrict__ invn, const u64 *__restrict__ keys,
                                                           long n, long K, int d, int slices, float threshold, int vec,
                                                           int *out_idx, float *out_sim, unsigned char *out_hit) {
     constexpr int EPC = 16 / (int)sizeof(T);  // elements per 16-byte chunk
-    const long q = (long)blockIdx.x * 4 + (threadIdx.x >> 6);
-    if (q >= n) return;
-    const int lane = threadIdx.x & 63, grp = lane >> 4, gl = lane & 15;
+    __shared__ float sh_f[4];
+    __shared__ u64 sh_k[4];
+    __shared__ float sh_s[16];
+    __shared__ long sh_i[16];
+    const long q = blockIdx.x;
+    const int t = threadIdx.x, lane = t & 63, wave = t >> 6, grp = t >> 4, gl = t & 15;
     const T *qrow = Q + (size_t)q * d;
     // 1/|q|: 0 for a zero-length query, NaN for a non-finite one
     float ss = 0.f;
     if (vec) {
-        for (int e = lane * EPC; e < d; e += 64 * EPC) ss += chunk_dot(qrow + e, qrow + e);
+        for (int e = t * EPC; e < d; e += 256 * EPC) ss += chunk_dot(qrow + e, qrow + e);
     } else {
-        for (int e = lane; e < d; e += 64) ss += widen(qrow[e]) * widen(qrow[e]);
+        for (int e = t; e < d; e += 256) ss += widen(qrow[e]) * widen(qrow[e]);
     }
-    const float qi = inv_length(wave_sum(ss));
-    long best_i = -1;
-    float best_s = -INFINITY;
-    if (!(qi == qi)) {
-        best_s = __uint_as_float(0x7FC00000u);
-    } else if (K > 0) {
-        u64 key = 0;
-        for (int s = lane; s < slices; s += 64) {
-            u64 k2 = keys[(size_t)q * slices + s];
-            key = k2 > key ? k2 : key;
-        }
+    u64 key = 0;
+    for (int s = t; s < slices; s += 256) {
+        const u64 k2 = keys[(size_t)q * slices + s];
+        key = k2 > key ? k2 : key;
+    }
+    ss = wave_sum(ss);
 #pragma unroll
-        for (int off = 32; off > 0; off >>= 1) {
-            u64 o = __shfl_xor(key, off);
-            key = o > key ? o : key;
-        }
-        if (key != 0) {
-            const unsigned block = 0xFFFFFFFFu - (unsigned)(key & 0xFFFFFFFFull);
-            const long run0 = (long)(block >> 2) * SISO_RUN_ROWS;
-            const int code = (int)(block & 3u);
-            // pass p, group grp -> local row: one half: 8*p + 4*h + grp; both halves: 4*p + grp
-            const int passes = code == 1 ? 8 : 4;
-            for (int p = 0; p < passes; ++p) {
-                const long r = run0 + (code == 1 ? 4 * p + grp : 8 * p + 2 * code + grp);
-                float acc = 0.f;
-                if (r < K) {
-                    const T *crow = cent + (size_t)r * d;
-                    if (vec) {
-                        for (int e = gl * EPC; e < d; e += 16 * EPC) acc += chunk_dot(qrow + e, crow + e);
-                    } else {
-                        for (int e = gl; e < d; e += 16) acc += widen(qrow[e]) * widen(crow[e]);
-                    }
-                }
-#pragma unroll
-                for (int off = 8; off > 0; off >>= 1) acc += __shfl_xor(acc, off);
-                const float s = r < K ? acc * qi * invn[r] : __uint_as_float(0x7FC00000u);
-                if (s > best_s) {
-                    best_s = s;
-                    best_i = r;
-                }
-            }
-            // the four groups hold interleaved rows: lowest row among equal maxima
-#pragma unroll
-            for (int off = 16; off < 64; off <<= 1) {
-                const float os = __shfl_xor(best_s, off);
-                const long oi = __shfl_xor(best_i, off);
-                if (oi >= 0 && (best_i < 0 || os > best_s || (os == best_s && oi < best_i))) {
-                    best_s = os;
-                    best_i = oi;
-                }
-            }
-        }
+    for (int off = 32; off > 0; off >>= 1) {
+        const u64 o = __shfl_xor(key, off);
+        key = o > key ? o : key;
     }
     if (lane == 0) {
+        sh_f[wave] = ss;
+        sh_k[wave] = key;
+    }
+    __syncthreads();
+    const float qi = inv_length((sh_f[0] + sh_f[1]) + (sh_f[2] + sh_f[3]));
+#pragma unroll
+    for (int w = 0; w < 4; ++w) key = sh_k[w] > key ? sh_k[w] : key;
+
+    long best_i = -1;
+    float best_s = -INFINITY;
+    const bool finite_q = qi == qi;
+    if (finite_q && K > 0 && key != 0) {
+        const unsigned block = 0xFFFFFFFFu - (unsigned)(key & 0xFFFFFFFFull);
+        const long run0 = (long)(block >> 2) * SISO_RUN_ROWS;
+        const int code = (int)(block & 3u);
+        // group g of pass p -> local row: one half: 8*(g/4) + 4*h + g%4; both halves: 16*p + g
+        const int passes = code == 1 ? 2 : 1;
+        for (int p = 0; p < passes; ++p) {
+            const long r = run0 + (code == 1 ? 16 * p + grp : 8 * (grp >> 2) + 2 * code + (grp & 3));
+            float acc = 0.f;
+            if (r < K) {
+                const T *crow = cent + (size_t)r * d;
+                if (vec) {
+                    for (int e = gl * EPC; e < d; e += 16 * EPC) acc += chunk_dot(qrow + e, crow + e);
+                } else {
+                    for (int e = gl; e < d; e += 16) acc += widen(qrow[e]) * widen(crow[e]);
+                }
+            }
+#pragma unroll
+            for (int off = 8; off > 0; off >>= 1) acc += __shfl_xor(acc, off);
+            const float s = r < K ? acc * qi * invn[r] : __uint_as_float(0x7FC00000u);
+            if (s > best_s) {
+                best_s = s;
+                best_i = r;
+            }
+        }
+    }
+    if (gl == 0) {
+        sh_s[grp] = best_s;
+        sh_i[grp] = best_i;
+    }
+    __syncthreads();
+    if (t == 0) {
+        // rows ascend with the group number inside a pass, and pass 1 lies above pass 0
+        for (int g = 1; g < 16; ++g) {
+            const float os = sh_s[g];
+            const long oi = sh_i[g];
+            if (oi >= 0 && (best_i < 0 || os > best_s || (os == best_s && oi < best_i))) {
+                best_s = os;
+                best_i = oi;
+            }
+        }
+        if (!finite_q) best_s = __uint_as_float(0x7FC00000u);
         out_idx[q] = (int)best_i;
         out_sim[q] = best_s;
         if (out_hit) out_hit[q] = (best_i >= 0 && best_s > threshold) ? 1 : 0;
@@ -365,7 +383,8 @@ int siso_merge_scalar_launch(siso_cache *c, float threshold, int *out_pairs, lon
 // ============================================================================
 #define UPD_MAXE (SISO_MAX_DIM / 256)
 
-template <typename T>
+// UPD_MAXE_T = elements of a row per thread (4 for dim <= 1024, else 16)
+template <typename T, int UPD_MAXE_T>
 __global__ __launch_bounds__(256) void k_update(const T *__restrict__ Q, const int *__restrict__ idx,
                                                  const unsigned char *__restrict__ hit, long n, T *cent, float *mean,
                                                  int *size, float *invn, long count, int d, u64 *bad) {
@@ -380,9 +399,9 @@ __global__ __launch_bounds__(256) void k_update(const T *__restrict__ Q, const i
         if (t == 0) atomicAdd(bad, 1ull);
         return;
     }
-    float acc[UPD_MAXE];
+    float acc[UPD_MAXE_T];
 #pragma unroll
-    for (int e = 0; e < UPD_MAXE; ++e) acc[e] = 0.f;
+    for (int e = 0; e < UPD_MAXE_T; ++e) acc[e] = 0.f;
     int members = 0;
     for (long base = 0; base < n; base += 256) {
         const long j = base + t;
@@ -398,10 +417,10 @@ __global__ __launch_bounds__(256) void k_update(const T *__restrict__ Q, const i
                 mm &= mm - 1;
                 const long jj = base + w * 64 + b;
                 if (jj < me) return;  // an earlier member leads this centroid (uniform over the block)
-                float x[UPD_MAXE];
+                float x[UPD_MAXE_T];
                 float ss = 0.f;
 #pragma unroll
-                for (int e = 0; e < UPD_MAXE; ++e) {
+                for (int e = 0; e < UPD_MAXE_T; ++e) {
                     const int col = t + e * 256;
                     x[e] = col < d ? widen(Q[(size_t)jj * d + col]) : 0.f;
                     ss += x[e] * x[e];
@@ -411,7 +430,7 @@ __global__ __launch_bounds__(256) void k_update(const T *__restrict__ Q, const i
                 if (inv == inv && inv > 0.f) {
                     const float nrm = sqrtf(n2);
 #pragma unroll
-                    for (int e = 0; e < UPD_MAXE; ++e) acc[e] += x[e] / nrm;
+                    for (int e = 0; e < UPD_MAXE_T; ++e) acc[e] += x[e] / nrm;
                     ++members;
                 }
             }
@@ -420,10 +439,10 @@ __global__ __launch_bounds__(256) void k_update(const T *__restrict__ Q, const i
     if (members == 0) return;
     const float n_old = (float)size[k];
     const float n_new = n_old + (float)members;
-    float m[UPD_MAXE];
+    float m[UPD_MAXE_T];
     float ss = 0.f;
 #pragma unroll
-    for (int e = 0; e < UPD_MAXE; ++e) {
+    for (int e = 0; e < UPD_MAXE_T; ++e) {
         const int col = t + e * 256;
         m[e] = 0.f;
         if (col < d) {
@@ -438,7 +457,7 @@ __global__ __launch_bounds__(256) void k_update(const T *__restrict__ Q, const i
     const float nrm = sqrtf(n2);
     float cs = 0.f;
 #pragma unroll
-    for (int e = 0; e < UPD_MAXE; ++e) {
+    for (int e = 0; e < UPD_MAXE_T; ++e) {
         const int col = t + e * 256;
         if (col < d) {
             T r;
@@ -783,7 +802,7 @@ extern "C" int siso_lookup(siso_cache *c, const void *queries, long n, float thr
     }
     int rc = ensure_workspace(c, n, slices);
     if (rc != SISO_OK) return rc;
-    const unsigned qblocks = (unsigned)((n + 3) / 4);
+    const unsigned qblocks = (unsigned)n;
     const int vec = ((c->dim * elem_bytes(c->dtype)) % 16 == 0 && ((uintptr_t)queries & 15) == 0) ? 1 : 0;
     if (c->count > 0) {
         siso_prof_begin(c);
@@ -817,14 +836,20 @@ extern "C" int siso_update_hits(siso_cache *c, const void *queries, const int *i
     for (long off = 0; off < n; off += UPDATE_CHUNK) {
         const long m = (n - off < UPDATE_CHUNK) ? n - off : UPDATE_CHUNK;
         const unsigned char *h = hit ? hit + off : nullptr;
-        if (c->dtype == SISO_F32)
-            hipLaunchKernelGGL(k_update<float>, dim3((unsigned)m), dim3(256), 0, c->stream,
-                               (const float *)queries + (size_t)off * c->dim, idx + off, h, m, (float *)c->cent,
-                               c->mean, c->size, c->invn, c->count, c->dim, c->counters);
-        else
-            hipLaunchKernelGGL(k_update<bf16_t>, dim3((unsigned)m), dim3(256), 0, c->stream,
-                               (const bf16_t *)queries + (size_t)off * c->dim, idx + off, h, m, (bf16_t *)c->cent,
-                               c->mean, c->size, c->invn, c->count, c->dim, c->counters);
+        const float *qf = (const float *)queries + (size_t)off * c->dim;
+        const bf16_t *qh = (const bf16_t *)queries + (size_t)off * c->dim;
+        const dim3 grid((unsigned)m), block(256);
+#define SISO_LAUNCH_UPDATE(T, E, QP)                                                                            \
+    hipLaunchKernelGGL((k_update<T, E>), grid, block, 0, c->stream, QP, idx + off, h, m, (T *)c->cent, c->mean, \
+                       c->size, c->invn, c->count, c->dim, c->counters)
+        if (c->dtype == SISO_F32) {
+            if (c->dim <= 1024) SISO_LAUNCH_UPDATE(float, 4, qf);
+            else SISO_LAUNCH_UPDATE(float, 16, qf);
+        } else {
+            if (c->dim <= 1024) SISO_LAUNCH_UPDATE(bf16_t, 4, qh);
+            else SISO_LAUNCH_UPDATE(bf16_t, 16, qh);
+        }
+#undef SISO_LAUNCH_UPDATE
         HIP_TRY(c, hipGetLastError());
     }
     return SISO_OK;
@@ -975,7 +1000,9 @@ extern "C" int siso_merge_apply(siso_cache *c, const int *pairs, long n_pairs, i
 
 extern "C" int siso_profile_enable(siso_cache *c, int on) {
     if (!c) return SISO_EINVAL;
-    c->profile_on = on ? 1 : 0;
+    if (on < 0) return siso_fail(c, SISO_EINVAL, "siso_profile_enable: negative period");
+    c->profile_on = on;
+    c->prof_calls = 0;
     return SISO_OK;
 }
 

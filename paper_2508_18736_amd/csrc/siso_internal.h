@@ -72,7 +72,9 @@ struct siso_cache {
     int opt_merge_config;
 
     // kernel timing (siso_profile_enable / siso_profile_read)
-    int profile_on;
+    int profile_on;       // 0 = off, N = bracket every N-th call
+    long prof_calls;      // calls seen since profiling was enabled
+    int prof_open;        // a bracket was opened by the current call
     hipEvent_t *prof_ev;  // pairs: [2*i] start, [2*i+1] stop
     int prof_count;       // recorded pairs
 

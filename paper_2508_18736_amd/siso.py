@@ -177,8 +177,9 @@ class SisoCache:
         self._check(_lib.siso_merge_apply(self._h, _ptr(pr), pr.shape[0], _ptr(surv)))
         return surv
 
-    def profile_enable(self, on: bool) -> None:
-        self._check(_lib.siso_profile_enable(self._h, 1 if on else 0))
+    def profile_enable(self, on) -> None:
+        """0/False = off; N = bracket the dominant kernel of every N-th call with events."""
+        self._check(_lib.siso_profile_enable(self._h, int(on)))
 
     def profile_read(self) -> Tuple[float, int]:
         """Sum of the bracketed kernel durations (ms) and their number since the last read."""
