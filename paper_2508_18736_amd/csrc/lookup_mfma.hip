@@ -38,17 +38,24 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
-template <int WC_, int WQ_, int NWC_, int NWQ_, int NSTAGE_>
+template <int WC_, int WQ_, int NWC_, int NWQ_, int NSTAGE_, int BK_ = 64>
 struct PipeCfg {
     static constexpr int WC = WC_, WQ = WQ_, NWC = NWC_, NWQ = NWQ_, NSTAGE = NSTAGE_;
+    static constexpr int BK = BK_;            // elements of the dimension per slab (64; or 32: half lines)
+    static constexpr int RB = BK * 2;         // bytes of a tile row in a stage
+    static constexpr int CPR = BK / 8;        // 16-byte chunks per tile row
+    static constexpr int RPI = 64 / CPR;      // tile rows one direct load of a wave fills
+    static constexpr int RP = 256 / RB;       // tile rows per 256 bytes (all 64 banks)
+    static constexpr int KK = BK / 16;        // MFMA steps per slab
     static constexpr int BC = 32 * WC * NWC;  // centroid rows per tile
     static constexpr int BQ = 32 * WQ * NWQ;  // query rows per tile
     static constexpr int NW = NWC * NWQ, NT = 64 * NW;
-    static constexpr int STAGE = (BC + BQ) * 128;
-    static constexpr int NLA = BC / 8 / NW, NLB = BQ / 8 / NW;  // direct loads per wave and slab
+    static constexpr int STAGE = (BC + BQ) * RB;
+    static constexpr int NLA = BC / RPI / NW, NLB = BQ / RPI / NW;  // direct loads per wave and slab
+    static_assert(BK == 64 || BK == 32, "slab of 64 or 32 elements");
     static constexpr int NL = NLA + NLB;
     static constexpr int LDS_BYTES = NSTAGE * STAGE + 2 * BC * 4;
-    static_assert((BC / 8) % NW == 0 && (BQ / 8) % NW == 0, "whole row groups per wave");
+    static_assert((BC / RPI) % NW == 0 && (BQ / RPI) % NW == 0, "whole row groups per wave");
     static_assert(BC <= SISO_PAD_ROWS && BC <= NT && BC % 64 == 0, "tile of inverse lengths: one direct load per wave");
     static_assert(BQ * NWC * 8 <= NSTAGE * STAGE, "reduction scratch fits in the stage buffers");
     static_assert(NSTAGE >= 2 && LDS_BYTES <= 160 * 1024, "stages fit in LDS");
@@ -84,17 +91,18 @@ __device__ __forceinline__ void lds_wait(bf16x8 (&a)[NA], bf16x8 (&b)[NB]) {
 #pragma unroll
     for (int i = 0; i < NB; ++i) asm volatile("" : "+v"(b[i]));
 }
-template <int NA, int NB>
+// SUB = bytes between the 32-row blocks of a wave's tile (32 tile rows)
+template <int SUB, int NA, int NB>
 __device__ __forceinline__ void lds_frags(bf16x8 (&a)[NA], bf16x8 (&b)[NB], unsigned addr_a, unsigned addr_b) {
     static_assert(NA <= 4 && NB <= 4, "fragment offsets are spelled out up to four");
     a[0] = lds_frag<0>(addr_a);
-    if constexpr (NA > 1) a[1] = lds_frag<4096>(addr_a);
-    if constexpr (NA > 2) a[2] = lds_frag<8192>(addr_a);
-    if constexpr (NA > 3) a[3] = lds_frag<12288>(addr_a);
+    if constexpr (NA > 1) a[1] = lds_frag<SUB>(addr_a);
+    if constexpr (NA > 2) a[2] = lds_frag<2 * SUB>(addr_a);
+    if constexpr (NA > 3) a[3] = lds_frag<3 * SUB>(addr_a);
     b[0] = lds_frag<0>(addr_b);
-    if constexpr (NB > 1) b[1] = lds_frag<4096>(addr_b);
-    if constexpr (NB > 2) b[2] = lds_frag<8192>(addr_b);
-    if constexpr (NB > 3) b[3] = lds_frag<12288>(addr_b);
+    if constexpr (NB > 1) b[1] = lds_frag<SUB>(addr_b);
+    if constexpr (NB > 2) b[2] = lds_frag<2 * SUB>(addr_b);
+    if constexpr (NB > 3) b[3] = lds_frag<3 * SUB>(addr_b);
 }
 template <int N>
 __device__ __forceinline__ void vm_wait() {
@@ -110,7 +118,8 @@ __global__ __launch_bounds__(Cfg::NT) __attribute__((amdgpu_waves_per_eu(2, 2)))
     int tiles_per_slice, int slices, int nqt, u64 *__restrict__ keys, float threshold, int *__restrict__ out_pairs,
     long cap, u64 *__restrict__ counter) {
     constexpr int WC = Cfg::WC, WQ = Cfg::WQ, NWC = Cfg::NWC, BC = Cfg::BC, BQ = Cfg::BQ, NT = Cfg::NT, NW = Cfg::NW,
-                  STAGE = Cfg::STAGE, NLA = Cfg::NLA, NLB = Cfg::NLB, NL = Cfg::NL, NSTAGE = Cfg::NSTAGE;
+                  STAGE = Cfg::STAGE, NLA = Cfg::NLA, NLB = Cfg::NLB, NL = Cfg::NL, NSTAGE = Cfg::NSTAGE, BK = Cfg::BK,
+                  RB = Cfg::RB, CPR = Cfg::CPR, RPI = Cfg::RPI, RP = Cfg::RP, KK = Cfg::KK, SUB = 32 * Cfg::RB;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     float *inv_s = (float *)(smem + NSTAGE * STAGE);  // [2][BC], by tile parity
 
@@ -136,35 +145,35 @@ __global__ __launch_bounds__(Cfg::NT) __attribute__((amdgpu_waves_per_eu(2, 2)))
     }
     const long q0 = (long)qt * BQ;
     const int ct_end = (ct_begin + tiles_per_slice < total_ct) ? ct_begin + tiles_per_slice : total_ct;
-    const int nk = d / 64;
+    const int nk = d / BK;
     const int T = (ct_end - ct_begin) * nk;  // slabs this workgroup walks through
 
     // direct-load addressing
-    const int lr = lane >> 3, slot = lane & 7;
+    const int lr = lane / CPR, slot = lane % CPR;
     unsigned a_off[NLA], b_off[NLB];
 #pragma unroll
     for (int j = 0; j < NLA; ++j) {
-        const int row = (j * NW + wave) * 8 + lr;
-        a_off[j] = (unsigned)(row * d + ((slot ^ ((row >> 1) & 7)) * 8));
+        const int row = (j * NW + wave) * RPI + lr;
+        a_off[j] = (unsigned)(row * d + ((slot ^ ((row / RP) % CPR)) * 8));
     }
 #pragma unroll
     for (int j = 0; j < NLB; ++j) {
-        const int row = (j * NW + wave) * 8 + lr;
+        const int row = (j * NW + wave) * RPI + lr;
         long qr = q0 + row;
         if (qr > n - 1) qr = n - 1;
-        b_off[j] = (unsigned)((qr - q0) * d + ((slot ^ ((row >> 1) & 7)) * 8));
+        b_off[j] = (unsigned)((qr - q0) * d + ((slot ^ ((row / RP) % CPR)) * 8));
     }
     const bf16_t *qbase = Q + (size_t)q0 * d;
 
     // fragment read addresses of this lane: LDS byte offset of its row in the centroid / query
     // part of stage 0, plus the swizzled 16-byte slot of each of the four 16-element steps
-    const int sw = (l32 >> 1) & 7;
+    const int sw = (l32 / RP) % CPR;
     const unsigned lds0 = (unsigned)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)smem;
-    const unsigned row_a = lds0 + (unsigned)(((wc * WC) * 32 + l32) * 128);
-    const unsigned row_b = lds0 + (unsigned)(BC * 128 + ((wq * WQ) * 32 + l32) * 128);
-    unsigned so[4];
+    const unsigned row_a = lds0 + (unsigned)(((wc * WC) * 32 + l32) * RB);
+    const unsigned row_b = lds0 + (unsigned)(BC * RB + ((wq * WQ) * 32 + l32) * RB);
+    unsigned so[KK];
 #pragma unroll
-    for (int kk = 0; kk < 4; ++kk) so[kk] = (unsigned)(((kk * 2 + h) ^ sw) * 16);
+    for (int kk = 0; kk < KK; ++kk) so[kk] = (unsigned)(((kk * 2 + h) ^ sw) * 16);
 
     float bv[WQ];
     unsigned bb[WQ];
@@ -191,13 +200,13 @@ __global__ __launch_bounds__(Cfg::NT) __attribute__((amdgpu_waves_per_eu(2, 2)))
     auto issue = [&]() {
         if (ld_ks == 0 && wave < BC / 64)
             gload_lds4(invn + (size_t)ld_ct * BC + wave * 64 + lane, inv_s + (ld_ct & 1) * BC + wave * 64);
-        const bf16_t *cb = C + (size_t)ld_ct * BC * d + ld_ks * 64;
-        const bf16_t *qb = qbase + ld_ks * 64;
+        const bf16_t *cb = C + (size_t)ld_ct * BC * d + ld_ks * BK;
+        const bf16_t *qb = qbase + ld_ks * BK;
         unsigned char *sb = smem + ld_stage * STAGE;
 #pragma unroll
         for (int j = 0; j < NLA; ++j) gload_lds16(cb + a_off[j], sb + (j * NW + wave) * 1024);
 #pragma unroll
-        for (int j = 0; j < NLB; ++j) gload_lds16(qb + b_off[j], sb + BC * 128 + (j * NW + wave) * 1024);
+        for (int j = 0; j < NLB; ++j) gload_lds16(qb + b_off[j], sb + BC * RB + (j * NW + wave) * 1024);
         if (++ld_ks == nk) {
             ld_ks = 0;
             ++ld_ct;
@@ -206,9 +215,9 @@ __global__ __launch_bounds__(Cfg::NT) __attribute__((amdgpu_waves_per_eu(2, 2)))
     };
 
     // Pipeline:
-    //   steps 0..2 of slab t | wait: own reads of slab t done, own loads of slab t+1 landed | barrier |
+    //   all but the last step of slab t | wait: own reads of slab t done, own loads of slab t+1 landed | barrier |
     //   issue the loads of slab t+NSTAGE into the stage just vacated | read step-0 fragments of slab t+1 |
-    //   step 3 of slab t | epilogue if the tile is complete
+    //   last step of slab t | epilogue if the tile is complete
     // so the loads have NSTAGE-1 slabs of time to land and the MFMAs of step 3 cover the barrier's
     // tail.  Loads complete in order: "all but the newest (NSTAGE-2)*NL" = slab t+1 has landed.  (The
     // inverse lengths ride along as one more load now and then, which only makes a wait stricter; they
@@ -220,22 +229,33 @@ __global__ __launch_bounds__(Cfg::NT) __attribute__((amdgpu_waves_per_eu(2, 2)))
     if (T >= NSTAGE) vm_wait<(NSTAGE - 1) * NL>();
     else vm_wait<0>();
     __syncthreads();
-    if (T > 0) lds_frags(af[0], bf[0], row_a + so[0], row_b + so[0]);
+    if (T > 0) lds_frags<SUB>(af[0], bf[0], row_a + so[0], row_b + so[0]);
 
     int ct = ct_begin, ks = 0;
     unsigned sto = 0;  // byte offset of the stage of slab t
     for (int t = 0; t < T; ++t) {
         const unsigned sto_next = (sto + STAGE == NSTAGE * STAGE) ? 0u : sto + STAGE;
 #pragma unroll
-        for (int kk = 0; kk < 3; ++kk) {
-            lds_frags(af[(kk + 1) & 1], bf[(kk + 1) & 1], row_a + sto + so[kk + 1], row_b + sto + so[kk + 1]);
+        for (int kk = 0; kk < KK - 1; ++kk) {
+            lds_frags<SUB>(af[(kk + 1) & 1], bf[(kk + 1) & 1], row_a + sto + so[kk + 1], row_b + sto + so[kk + 1]);
             lds_wait<NF>(af[kk & 1], bf[kk & 1]);
             __builtin_amdgcn_sched_barrier(0);
+            if (kk == 0 && ks == 0) {
+                // first step of a tile: start from zero instead of clearing the accumulators
+                const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-            for (int a = 0; a < WC; ++a)
+                for (int a = 0; a < WC; ++a)
 #pragma unroll
-                for (int b = 0; b < WQ; ++b)
-                    acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[kk & 1][a], bf[kk & 1][b], acc[a][b], 0, 0, 0);
+                    for (int b = 0; b < WQ; ++b)
+                        acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[0][a], bf[0][b], zero, 0, 0, 0);
+            } else {
+#pragma unroll
+                for (int a = 0; a < WC; ++a)
+#pragma unroll
+                    for (int b = 0; b < WQ; ++b)
+                        acc[a][b] =
+                            __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[kk & 1][a], bf[kk & 1][b], acc[a][b], 0, 0, 0);
+            }
             __builtin_amdgcn_sched_barrier(0);
         }
         lds_wait<0>(af[1], bf[1]);
@@ -243,7 +263,7 @@ __global__ __launch_bounds__(Cfg::NT) __attribute__((amdgpu_waves_per_eu(2, 2)))
         else vm_wait<0>();
         __syncthreads();
         if (t + NSTAGE < T) issue();
-        if (t + 1 < T) lds_frags(af[0], bf[0], row_a + sto_next + so[0], row_b + sto_next + so[0]);
+        if (t + 1 < T) lds_frags<SUB>(af[0], bf[0], row_a + sto_next + so[0], row_b + sto_next + so[0]);
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int a = 0; a < WC; ++a)
@@ -282,8 +302,6 @@ __global__ __launch_bounds__(Cfg::NT) __attribute__((amdgpu_waves_per_eu(2, 2)))
                             emit_pair(sim > threshold && icol < jrow, (int)icol, (int)jrow, out_pairs, cap, counter);
                         }
                     }
-#pragma unroll
-                    for (int i = 0; i < 16; ++i) acc[a][b][i] = 0.f;
                 }
             }
             ks = 0;
@@ -328,6 +346,7 @@ __global__ __launch_bounds__(Cfg::NT) __attribute__((amdgpu_waves_per_eu(2, 2)))
 typedef PipeCfg<4, 2, 2, 4, 2> PipeLarge;  // 256 x 256 tile, waves of 128 x 64, two stages
 typedef PipeCfg<2, 2, 4, 2, 3> PipeMid;    // 256 x 128 tile, waves of 64 x 64, three stages
 typedef PipeCfg<1, 2, 8, 1, 3> PipeSmall;  // 256 x 64 tile, waves of 32 x 64, three stages
+typedef PipeCfg<4, 2, 2, 4, 4, 32> PipeLarge32;  // 256 x 256 tile, slabs of 32 elements, four stages
 
 // ----------------------------------------------------------------------------
 // host side
@@ -336,13 +355,13 @@ struct PipePlan {
     int cfg, bc, bq, tiles_per_slice, slices, nqt;
 };
 
-// cfg: 1 = PipeLarge, 2 = PipeMid, 3 = PipeSmall
+// cfg: 1 = PipeLarge, 2 = PipeMid, 3 = PipeSmall, 4 = PipeLarge32
 static bool pipe_plan(const siso_cache *c, long n, int cfg, long want_wgs, PipePlan *p) {
     if (c->dtype != SISO_BF16 || c->dim % 64 != 0 || c->dim < 128 || c->count < 1 || n < 1) return false;
-    if (cfg < 1 || cfg > 3) return false;
+    if (cfg < 1 || cfg > 4) return false;
     p->cfg = cfg;
     p->bc = 256;
-    p->bq = cfg == 1 ? PipeLarge::BQ : cfg == 2 ? PipeMid::BQ : PipeSmall::BQ;
+    p->bq = cfg == 2 ? PipeMid::BQ : cfg == 3 ? PipeSmall::BQ : PipeLarge::BQ;
     const long nqt = (n + p->bq - 1) / p->bq;
     const long ct = (c->count + p->bc - 1) / p->bc;
     long tps = c->opt_tiles_per_slice;
@@ -392,7 +411,8 @@ static int pipe_launch(siso_cache *c, const void *queries, long n, const PipePla
     switch (p.cfg) {
         case 1: return launch_cfg<PipeLarge>(c, queries, n, p);
         case 2: return launch_cfg<PipeMid>(c, queries, n, p);
-        default: return launch_cfg<PipeSmall>(c, queries, n, p);
+        case 3: return launch_cfg<PipeSmall>(c, queries, n, p);
+        default: return launch_cfg<PipeLarge32>(c, queries, n, p);
     }
 }
 
