@@ -36,6 +36,8 @@ def parse():
     ap.add_argument("--no-merge", action="store_true")
     ap.add_argument("--option", action="append", default=[], help="name=value for siso_set_option")
     ap.add_argument("--path", type=int, default=0, help="siso_set_lookup_path (0 = auto)")
+    ap.add_argument("--copy-probe-mib", type=int, default=0,
+                    help="also run one plain device copy of this many MiB (a known-size reference for byte counters)")
     return ap.parse_args()
 
 
@@ -87,6 +89,11 @@ def main():
     cents = to_dev(wl.centroids, "bf16")
     cache.load(cents)
     del cents
+    if args.copy_probe_mib > 0:
+        src = torch.ones(args.copy_probe_mib << 18, dtype=torch.float32, device="cuda:0")
+        dst = src.clone()  # reads and writes copy_probe_mib MiB each
+        torch.cuda.synchronize()
+        del src, dst
     out = {"n_gpus": 1, "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
            "data": "synthetic"}
     merge_info = None

@@ -67,6 +67,11 @@ __device__ __forceinline__ void gload_lds16(const void *g, void *lds_wave_base) 
     __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)g,
                                      (__attribute__((address_space(3))) void *)lds_wave_base, 16, 0, 0);
 }
+// the same with the non-temporal hint: data that is read once should not push reusable lines out of L2
+__device__ __forceinline__ void gload_lds16_nt(const void *g, void *lds_wave_base) {
+    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)g,
+                                     (__attribute__((address_space(3))) void *)lds_wave_base, 16, 0, 2);
+}
 __device__ __forceinline__ void gload_lds4(const void *g, void *lds_wave_base) {
     __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)g,
                                      (__attribute__((address_space(3))) void *)lds_wave_base, 4, 0, 0);
@@ -115,8 +120,8 @@ __device__ __forceinline__ void vm_wait() {
 template <class Cfg, int MODE>
 __global__ __launch_bounds__(Cfg::NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void k_lookup_pipe(
     const bf16_t *__restrict__ Q, const bf16_t *__restrict__ C, const float *__restrict__ invn, long n, long K, int d,
-    int tiles_per_slice, int slices, int nqt, u64 *__restrict__ keys, float threshold, int *__restrict__ out_pairs,
-    long cap, u64 *__restrict__ counter) {
+    int tiles_per_slice, int slices, int nqt, int qb, int nt_centroids, u64 *__restrict__ keys, float threshold,
+    int *__restrict__ out_pairs, long cap, u64 *__restrict__ counter) {
     constexpr int WC = Cfg::WC, WQ = Cfg::WQ, NWC = Cfg::NWC, BC = Cfg::BC, BQ = Cfg::BQ, NT = Cfg::NT, NW = Cfg::NW,
                   STAGE = Cfg::STAGE, NLA = Cfg::NLA, NLB = Cfg::NLB, NL = Cfg::NL, NSTAGE = Cfg::NSTAGE, BK = Cfg::BK,
                   RB = Cfg::RB, CPR = Cfg::CPR, RPI = Cfg::RPI, RP = Cfg::RP, KK = Cfg::KK, SUB = 32 * Cfg::RB;
@@ -133,8 +138,18 @@ __global__ __launch_bounds__(Cfg::NT) __attribute__((amdgpu_waves_per_eu(2, 2)))
     const int total_ct = (int)((K + BC - 1) / BC);
     int qt, s, ct_begin;
     if (MODE == PIPE_LOOKUP) {
-        qt = blockIdx.x % nqt;
-        s = blockIdx.x / nqt;
+        // Workgroups are handed to the 8 XCDs round robin and every XCD has its own L2.  The 32
+        // workgroups that run together on one XCD are made a block of qb query tiles x 32/qb slices,
+        // so that a centroid tile fetched into that L2 serves qb workgroups; an XCD owns every eighth
+        // group of 32/qb slices and walks through all query tiles for it before moving on.
+        const int sb = 32 / qb;
+        const int xcd = blockIdx.x & 7, local = blockIdx.x >> 3;
+        const int nqb = (nqt + qb - 1) / qb;
+        const int grp = local / (nqb * 32), rem = local % (nqb * 32);
+        const int i = rem & 31;
+        qt = (rem >> 5) * qb + i % qb;
+        s = (grp * 8 + xcd) * sb + i / qb;
+        if (qt >= nqt || s >= slices) return;
         ct_begin = s * tiles_per_slice;
     } else {
         static_assert(MODE == PIPE_LOOKUP || Cfg::BC == Cfg::BQ, "pair search walks square tiles");
@@ -203,8 +218,13 @@ __global__ __launch_bounds__(Cfg::NT) __attribute__((amdgpu_waves_per_eu(2, 2)))
         const bf16_t *cb = C + (size_t)ld_ct * BC * d + ld_ks * BK;
         const bf16_t *qb = qbase + ld_ks * BK;
         unsigned char *sb = smem + ld_stage * STAGE;
+        if (nt_centroids) {
 #pragma unroll
-        for (int j = 0; j < NLA; ++j) gload_lds16(cb + a_off[j], sb + (j * NW + wave) * 1024);
+            for (int j = 0; j < NLA; ++j) gload_lds16_nt(cb + a_off[j], sb + (j * NW + wave) * 1024);
+        } else {
+#pragma unroll
+            for (int j = 0; j < NLA; ++j) gload_lds16(cb + a_off[j], sb + (j * NW + wave) * 1024);
+        }
 #pragma unroll
         for (int j = 0; j < NLB; ++j) gload_lds16(qb + b_off[j], sb + BC * RB + (j * NW + wave) * 1024);
         if (++ld_ks == nk) {
@@ -352,7 +372,8 @@ typedef PipeCfg<4, 2, 2, 4, 4, 32> PipeLarge32;  // 256 x 256 tile, slabs of 32 
 // host side
 // ----------------------------------------------------------------------------
 struct PipePlan {
-    int cfg, bc, bq, tiles_per_slice, slices, nqt;
+    int cfg, bc, bq, tiles_per_slice, slices, nqt, qb;
+    long grid;
 };
 
 // cfg: 1 = PipeLarge, 2 = PipeMid, 3 = PipeSmall, 4 = PipeLarge32
@@ -368,6 +389,11 @@ static bool pipe_plan(const siso_cache *c, long n, int cfg, long want_wgs, PipeP
     if (tps <= 0) {
         tps = (ct * nqt + want_wgs - 1) / want_wgs;
         if (tps < 1) tps = 1;
+        // With several query tiles a slice is read once per block of query tiles.  Short slices keep
+        // what the 8 XCDs read at a time (8 x 4 slices) near 128 MB, so that those repeats come from
+        // the 256 MB memory-side cache instead of HBM.
+        const long mall_tps = 8192 / c->dim > 2 ? 8192 / c->dim : 2;
+        if (nqt > 1 && tps > mall_tps) tps = mall_tps;
     }
     if (tps > ct) tps = ct;
     const long slices = (ct + tps - 1) / tps;
@@ -375,6 +401,19 @@ static bool pipe_plan(const siso_cache *c, long n, int cfg, long want_wgs, PipeP
     p->tiles_per_slice = (int)tps;
     p->slices = (int)slices;
     p->nqt = (int)nqt;
+    // query tiles per XCD block: 8 when there are that many (a centroid tile fetched into an XCD's L2
+    // then serves 8 workgroups, and 8 query tiles are about what stays resident in a 4 MB L2), fewer when the batch is small, more when there are so few slices that
+    // some XCD would otherwise stay idle (an XCD owns every eighth group of 32/qb slices)
+    int qb = c->opt_mfma_qblock > 0 ? c->opt_mfma_qblock : 8;
+    if (qb != 1 && qb != 2 && qb != 4 && qb != 8 && qb != 16 && qb != 32) return false;
+    if (c->opt_mfma_qblock <= 0) {
+        while (qb > 1 && qb > nqt) qb >>= 1;
+        while (qb < 32 && slices * qb < 256) qb <<= 1;
+    }
+    p->qb = qb;
+    const long sb = 32 / qb, groups = (slices + sb - 1) / sb, nqb = (nqt + qb - 1) / qb;
+    p->grid = 8 * ((groups + 7) / 8) * nqb * 32;
+    if (p->grid > 2147483647L) return false;
     return true;
 }
 
@@ -400,9 +439,9 @@ static int launch_cfg(siso_cache *c, const void *queries, long n, const PipePlan
         if (e != hipSuccess) return siso_check_hip(c, e, "hipFuncSetAttribute(k_lookup_pipe)");
         attr_done = true;
     }
-    hipLaunchKernelGGL((k_lookup_pipe<Cfg, PIPE_LOOKUP>), dim3((unsigned)(p.nqt * p.slices)), dim3(Cfg::NT),
-                       Cfg::LDS_BYTES, c->stream, (const bf16_t *)queries, (const bf16_t *)c->cent, c->invn, n, c->count,
-                       c->dim, p.tiles_per_slice, p.slices, p.nqt, c->keys, 0.f, (int *)nullptr, 0L, (u64 *)nullptr);
+    hipLaunchKernelGGL((k_lookup_pipe<Cfg, PIPE_LOOKUP>), dim3((unsigned)p.grid), dim3(Cfg::NT), Cfg::LDS_BYTES,
+                       c->stream, (const bf16_t *)queries, (const bf16_t *)c->cent, c->invn, n, c->count, c->dim,
+                       p.tiles_per_slice, p.slices, p.nqt, p.qb, c->opt_mfma_nt ? 0 : 1, c->keys, 0.f, (int *)nullptr, 0L, (u64 *)nullptr);
     return siso_check_hip(c, hipGetLastError(), "k_lookup_pipe");
 }
 
@@ -464,6 +503,6 @@ int siso_merge_mfma_launch(siso_cache *c, float threshold, int *out_pairs, long 
     }
     hipLaunchKernelGGL((k_lookup_pipe<Cfg, PIPE_PAIRS>), dim3((unsigned)T, (unsigned)runs), dim3(Cfg::NT), Cfg::LDS_BYTES,
                        c->stream, (const bf16_t *)c->cent, (const bf16_t *)c->cent, c->invn, c->count, c->count, c->dim,
-                       (int)tps, (int)runs, (int)T, (u64 *)nullptr, threshold, out_pairs, cap, c->counters + 1);
+                       (int)tps, (int)runs, (int)T, 1, 0, (u64 *)nullptr, threshold, out_pairs, cap, c->counters + 1);
     return siso_check_hip(c, hipGetLastError(), "pair search kernel");
 }
