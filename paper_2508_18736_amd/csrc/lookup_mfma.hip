@@ -133,15 +133,18 @@ __global__ __launch_bounds__(Cfg::NT) __attribute__((amdgpu_waves_per_eu(2, 2)))
     const int wc = wave % NWC, wq = wave / NWC;
     const int h = lane >> 5, l32 = lane & 31;
 
-    // lookup: block = (query tile, slice of the centroid tiles).  pairs: block (x, y) = (centroid tile
-    // in the role of the query tile, y-th run of centroid tiles starting at that tile).
+    // Block -> (query tile qt, slice s of the centroid tiles).  Workgroups are handed to the 8 XCDs
+    // round robin and every XCD has its own L2.  The 32 workgroups that run together on one XCD are
+    // made a block of qb query tiles x 32/qb slices, so that a centroid tile fetched into that L2
+    // serves qb workgroups and qb query tiles stay resident in it; an XCD owns every eighth group of
+    // 32/qb slices and walks through all query tiles for it before moving on.
+    // In the pair search the query tile is a centroid tile too and only the tiles at or right of it
+    // are visited (upper triangle); slices are absolute ranges of tiles, so that the workgroups of a
+    // block still walk through the same centroid tiles in step.
+    static_assert(MODE == PIPE_LOOKUP || Cfg::BC == Cfg::BQ, "pair search walks square tiles");
     const int total_ct = (int)((K + BC - 1) / BC);
-    int qt, s, ct_begin;
-    if (MODE == PIPE_LOOKUP) {
-        // Workgroups are handed to the 8 XCDs round robin and every XCD has its own L2.  The 32
-        // workgroups that run together on one XCD are made a block of qb query tiles x 32/qb slices,
-        // so that a centroid tile fetched into that L2 serves qb workgroups; an XCD owns every eighth
-        // group of 32/qb slices and walks through all query tiles for it before moving on.
+    int qt, s, ct_begin, ct_end;
+    {
         const int sb = 32 / qb;
         const int xcd = blockIdx.x & 7, local = blockIdx.x >> 3;
         const int nqb = (nqt + qb - 1) / qb;
@@ -151,15 +154,13 @@ __global__ __launch_bounds__(Cfg::NT) __attribute__((amdgpu_waves_per_eu(2, 2)))
         s = (grp * 8 + xcd) * sb + i / qb;
         if (qt >= nqt || s >= slices) return;
         ct_begin = s * tiles_per_slice;
-    } else {
-        static_assert(MODE == PIPE_LOOKUP || Cfg::BC == Cfg::BQ, "pair search walks square tiles");
-        qt = blockIdx.x;
-        s = blockIdx.y;
-        ct_begin = qt + s * tiles_per_slice;
-        if (ct_begin >= total_ct) return;
+        ct_end = (ct_begin + tiles_per_slice < total_ct) ? ct_begin + tiles_per_slice : total_ct;
+        if (MODE == PIPE_PAIRS) {
+            if (ct_begin < qt) ct_begin = qt;
+            if (ct_begin >= ct_end) return;
+        }
     }
     const long q0 = (long)qt * BQ;
-    const int ct_end = (ct_begin + tiles_per_slice < total_ct) ? ct_begin + tiles_per_slice : total_ct;
     const int nk = d / BK;
     const int T = (ct_end - ct_begin) * nk;  // slabs this workgroup walks through
 
@@ -488,12 +489,17 @@ int siso_merge_mfma_supported(const siso_cache *c) {
 int siso_merge_mfma_launch(siso_cache *c, float threshold, int *out_pairs, long cap) {
     typedef PipeLarge Cfg;
     const long T = (c->count + Cfg::BC - 1) / Cfg::BC;
-    // runs of tiles short enough for about eight workgroups per compute unit over the triangle
-    long tps = c->opt_tiles_per_slice > 0 ? c->opt_tiles_per_slice : (T * (T + 1) / 2 + 2047) / 2048;
-    if (tps < 1) tps = 1;
+    // one tile pair per workgroup (the triangle balances best in small pieces), blocks of 8 tiles x 4
+    // slices per XCD; workgroups whose slice lies left of their own tile exit at once
+    long tps = c->opt_tiles_per_slice > 0 ? c->opt_tiles_per_slice : 1;
     if (tps > T) tps = T;
-    const long runs = (T + tps - 1) / tps;
-    if (T > 2147483647L || runs > 65535) return siso_fail(c, SISO_EINVAL, "pair search: too many tiles");
+    const long slices = (T + tps - 1) / tps;
+    int qb = 8;
+    while (qb > 1 && qb > T) qb >>= 1;
+    while (qb < 32 && slices * qb < 256) qb <<= 1;
+    const long sb = 32 / qb, groups = (slices + sb - 1) / sb, nqb = (T + qb - 1) / qb;
+    const long grid = 8 * ((groups + 7) / 8) * nqb * 32;
+    if (grid > 2147483647L) return siso_fail(c, SISO_EINVAL, "pair search: too many tiles");
     static bool attr_done = false;
     if (!attr_done) {
         hipError_t e = hipFuncSetAttribute((const void *)k_lookup_pipe<Cfg, PIPE_PAIRS>,
@@ -501,8 +507,8 @@ int siso_merge_mfma_launch(siso_cache *c, float threshold, int *out_pairs, long 
         if (e != hipSuccess) return siso_check_hip(c, e, "hipFuncSetAttribute(pair search)");
         attr_done = true;
     }
-    hipLaunchKernelGGL((k_lookup_pipe<Cfg, PIPE_PAIRS>), dim3((unsigned)T, (unsigned)runs), dim3(Cfg::NT), Cfg::LDS_BYTES,
-                       c->stream, (const bf16_t *)c->cent, (const bf16_t *)c->cent, c->invn, c->count, c->count, c->dim,
-                       (int)tps, (int)runs, (int)T, 1, 0, (u64 *)nullptr, threshold, out_pairs, cap, c->counters + 1);
+    hipLaunchKernelGGL((k_lookup_pipe<Cfg, PIPE_PAIRS>), dim3((unsigned)grid), dim3(Cfg::NT), Cfg::LDS_BYTES, c->stream,
+                       (const bf16_t *)c->cent, (const bf16_t *)c->cent, c->invn, c->count, c->count, c->dim, (int)tps,
+                       (int)slices, (int)T, qb, 0, (u64 *)nullptr, threshold, out_pairs, cap, c->counters + 1);
     return siso_check_hip(c, hipGetLastError(), "pair search kernel");
 }
