@@ -25,6 +25,27 @@ PEAK_BF16_TFLOPS = 2500.0  # dense bf16 MFMA, MI355X
 PEAK_HBM_GBS = 8000.0      # HBM3E
 
 
+def measured_traffic(workload):
+    """Bytes per launch of the dominant kernel from the committed counter summary, or None when the
+    kernel source has changed since the counters were taken."""
+    import hashlib
+
+    h = hashlib.sha256()
+    for f in ("lookup_mfma.hip", "siso_internal.h"):
+        with open(os.path.join(ROOT, "paper_2508_18736_amd", "csrc", f), "rb") as fh:
+            h.update(fh.read())
+    sha = h.hexdigest()[:16]
+    try:
+        with open(os.path.join(ROOT, "profiles", "traffic_counters.txt")) as fh:
+            for line in fh:
+                t = line.split()
+                if len(t) == 6 and t[0] == workload and t[1] == sha:
+                    return (float(t[2]) * float(t[3]) + float(t[4]) * float(t[5])) * 1024.0
+    except OSError:
+        pass
+    return None
+
+
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -126,7 +147,7 @@ def main():
                                "merge_apply_ms": apply_s * 1e3},
                     "roofline": {"bound": "mfma", "achieved": flop / avg_s / 1e12, "peak": PEAK_BF16_TFLOPS,
                                  "unit": "TFLOP/s", "frac": flop / avg_s / 1e12 / PEAK_BF16_TFLOPS,
-                                 "traffic": None, "kernel_ms": avg_s * 1e3}})
+                                 "traffic": measured_traffic(name), "kernel_ms": avg_s * 1e3}})
         print(json.dumps(out))
         return
 
@@ -164,11 +185,13 @@ def main():
     if streaming:
         bytes_alg = K * d * 2.0 + nb * d * 2.0 + K * 4.0  # centroids + queries + inverse lengths, read once
         roof = {"bound": "hbm", "achieved": bytes_alg / avg_s / 1e9, "peak": PEAK_HBM_GBS, "unit": "GB/s",
-                "frac": bytes_alg / avg_s / 1e9 / PEAK_HBM_GBS, "traffic": None, "kernel_ms": avg_s * 1e3,
+                "frac": bytes_alg / avg_s / 1e9 / PEAK_HBM_GBS, "traffic": measured_traffic(name),
+                "algorithmic_bytes": bytes_alg, "kernel_ms": avg_s * 1e3,
                 "launches": launches}
     else:
         roof = {"bound": "mfma", "achieved": flop / avg_s / 1e12, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                "frac": flop / avg_s / 1e12 / PEAK_BF16_TFLOPS, "traffic": None, "kernel_ms": avg_s * 1e3,
+                "frac": flop / avg_s / 1e12 / PEAK_BF16_TFLOPS, "traffic": measured_traffic(name),
+                "algorithmic_bytes": K * d * 2.0 + nb * d * 2.0 + K * 4.0, "kernel_ms": avg_s * 1e3,
                 "launches": launches}
 
     if not args.no_merge and name == "c2_mid":
