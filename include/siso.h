@@ -80,11 +80,11 @@ int siso_set_lookup_path(siso_cache *c, int path);
 
 /*
  * Tuning knobs, for benchmarking; the defaults are chosen by the library.
- *   "mfma_config"     0 = default; 1 = 256x256 tile, 2 = 256x128, 3 = 256x64, 4 = 256x256 with half-width slabs
+ *   "mfma_config"     0 = default; 1 = 256x256 tile, 2 = 256x128, 3 = 256x64, 4 = 256x256 with half-width slabs,
+ *                     5 = 256x256 with four waves of 128x128
  *   "tiles_per_slice" 0 = default; >0 = centroid tiles one workgroup walks through
  *   "merge_config"    0 = default; 1 = use the scalar pair search
  *   "mfma_qblock"     0 = default; 1, 2, 4, 8, 16, 32 = query tiles that share an XCD's centroid tiles
- *   "mfma_nt"         0 = default (centroid loads carry the non-temporal hint); 1 = plain loads
  * Unknown names or values out of range give SISO_EINVAL.
  */
 int siso_set_option(siso_cache *c, const char *name, long value);

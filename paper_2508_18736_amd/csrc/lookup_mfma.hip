@@ -114,13 +114,150 @@ __device__ __forceinline__ void vm_wait() {
     asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
 }
 
+// compile-time loop: f(IC<0>{}), f(IC<1>{}), ...
+template <int I>
+struct IC {
+    static constexpr int value = I;
+};
+template <int I, int N, class F>
+__device__ __forceinline__ void static_for(F &&f) {
+    if constexpr (I < N) {
+        f(IC<I>{});
+        static_for<I + 1, N>(f);
+    }
+}
+
+// The accumulator blocks of a wave: WC x WQ blocks of 32 x 32, 16 registers per lane each.
+// Up to 8 blocks they are ordinary values and the compiler places them.
+template <bool FIXED, int WC, int WQ>
+struct Acc {
+    f32x16 v[WC][WQ];
+    template <int A, int B>
+    __device__ __forceinline__ void first(bf16x8 a, bf16x8 b) {  // start from zero
+        const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+        v[A][B] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, zero, 0, 0, 0);
+    }
+    template <int A, int B>
+    __device__ __forceinline__ void mac(bf16x8 a, bf16x8 b) {
+        v[A][B] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, v[A][B], 0, 0, 0);
+    }
+    template <int A, int B, int I>
+    __device__ __forceinline__ float get() const {
+        return v[A][B][I];
+    }
+    __device__ __forceinline__ void reserve() {}
+};
+// With 16 blocks the accumulators fill the AGPR half of the register file exactly, which the
+// register allocator cannot pack (it spills).  So block (A, B) sits in a[16*(A*WQ+B) .. +15] by
+// hand: the MFMAs and the reads are written out, and the compiler only learns that those
+// registers are taken.  It knows of no dependence between these statements, so all of them are
+// volatile (kept in program order), and the hardware's rules are kept by construction: a block
+// is read back only after 15 more MFMAs have been issued behind the one that wrote it (or, for
+// the last blocks, after the whole scaling of the blocks before them), far beyond the 8 passes
+// such an MFMA takes; and a block is overwritten only by an MFMA issued after it was read.
+template <int WC, int WQ>
+struct Acc<true, WC, WQ> {
+    template <int A, int B>
+    __device__ __forceinline__ void first(bf16x8 a, bf16x8 b) {
+        constexpr int R = 16 * (A * WQ + B);
+        asm volatile("v_mfma_f32_32x32x16_bf16 a[%2:%3], %0, %1, 0 ; hand-placed" ::"v"(a), "v"(b), "n"(R), "n"(R + 15));
+    }
+    template <int A, int B>
+    __device__ __forceinline__ void mac(bf16x8 a, bf16x8 b) {
+        constexpr int R = 16 * (A * WQ + B);
+        asm volatile("v_mfma_f32_32x32x16_bf16 a[%2:%3], %0, %1, a[%2:%3] ; hand-placed" ::"v"(a), "v"(b), "n"(R),
+                     "n"(R + 15));
+    }
+    template <int A, int B, int I>
+    __device__ __forceinline__ float get() const {
+        float x;
+        asm volatile("v_accvgpr_read_b32 %0, a[%1] ; hand-placed" : "=v"(x) : "n"(16 * (A * WQ + B) + I));
+        return x;
+    }
+    // tells the compiler (and through it the kernel descriptor) that a0 .. a255 and the fragment
+    // registers are in use (it warns that some of them are not its to hand out anyway)
+#pragma clang diagnostic push
+#pragma clang diagnostic ignored "-Winline-asm"
+    __device__ __forceinline__ void reserve() {
+        static_assert(WC * WQ == 16, "all 256 AGPRs");
+        asm volatile("; fragments: v[208:255]" ::: "v208", "v255");
+        asm volatile("; accumulators: a[0:255]" ::: "a0", "a15", "a16", "a31", "a32", "a47", "a48", "a63", "a64", "a79", "a80",
+                     "a95", "a96", "a111", "a112", "a127", "a128", "a143", "a144", "a159", "a160", "a175", "a176", "a191",
+                     "a192", "a207", "a208", "a223", "a224", "a239", "a240", "a255");
+    }
+#pragma clang diagnostic pop
+};
+
 #define PIPE_LOOKUP 0
 #define PIPE_PAIRS 1
+
+// Block -> (query tile qt, slice s of the centroid tiles).  Workgroups are handed to the 8 XCDs
+// round robin and every XCD has its own L2.  The 32 workgroups that run together on one XCD are
+// made a block of qb query tiles x 32/qb slices, so that a centroid tile fetched into that L2
+// serves qb workgroups and qb query tiles stay resident in it; an XCD owns every eighth group of
+// 32/qb slices and walks through all query tiles for it before moving on.
+// In the pair search the query tile is a centroid tile too and only the tiles at or right of it
+// are visited (upper triangle); slices are absolute ranges of tiles, so that the workgroups of a
+// block still walk through the same centroid tiles in step.  False = nothing to do for this block.
+template <int MODE, int BC>
+__device__ __forceinline__ bool pipe_map_block(long K, int tiles_per_slice, int slices, int nqt, int qb, int &qt, int &s,
+                                               int &ct_begin, int &ct_end) {
+    const int total_ct = (int)((K + BC - 1) / BC);
+    const int sb = 32 / qb;
+    const int xcd = blockIdx.x & 7, local = blockIdx.x >> 3;
+    const int nqb = (nqt + qb - 1) / qb;
+    const int grp = local / (nqb * 32), rem = local % (nqb * 32);
+    const int i = rem & 31;
+    qt = (rem >> 5) * qb + i % qb;
+    s = (grp * 8 + xcd) * sb + i / qb;
+    if (qt >= nqt || s >= slices) return false;
+    ct_begin = s * tiles_per_slice;
+    ct_end = (ct_begin + tiles_per_slice < total_ct) ? ct_begin + tiles_per_slice : total_ct;
+    if (MODE == PIPE_PAIRS) {
+        if (ct_begin < qt) ct_begin = qt;
+        if (ct_begin >= ct_end) return false;
+    }
+    return true;
+}
+
+// End of a lookup workgroup: every lane holds (best value, block) per query column of its wave.
+// Lanes l and l^32 hold the same column; waves with the same wq share columns and meet in LDS
+// (red = at least NWC * BQ * 8 bytes that nobody reads any more).
+template <int WQ, int NWC, int BQ, int NT>
+__device__ __forceinline__ void pipe_reduce_keys(float (&bv)[WQ], unsigned (&bb)[WQ], unsigned char *red, int wc, int wq,
+                                                 int h, int l32, int tid, long q0, long n, int slices, int s,
+                                                 u64 *__restrict__ keys) {
+#pragma unroll
+    for (int b = 0; b < WQ; ++b) {
+        const float ov = __shfl_xor(bv[b], 32);
+        const unsigned ob = __shfl_xor(bb[b], 32);
+        siso_merge_candidate(bv[b], bb[b], ov, ob);
+    }
+    float *red_v = (float *)red;  // [NWC][BQ]
+    unsigned *red_b = (unsigned *)(red + NWC * BQ * 4);
+    if (h == 0) {
+#pragma unroll
+        for (int b = 0; b < WQ; ++b) {
+            const int col = (wq * WQ + b) * 32 + l32;
+            red_v[wc * BQ + col] = bv[b];
+            red_b[wc * BQ + col] = bb[b];
+        }
+    }
+    __syncthreads();
+    for (int col = tid; col < BQ; col += NT) {
+        float v = red_v[col];
+        unsigned blk = red_b[col];
+#pragma unroll
+        for (int w2 = 1; w2 < NWC; ++w2) siso_merge_candidate(v, blk, red_v[w2 * BQ + col], red_b[w2 * BQ + col]);
+        const long q = q0 + col;
+        if (q < n) keys[(size_t)q * slices + s] = (blk == 0xFFFFFFFFu) ? 0ull : pack_key(v, blk);
+    }
+}
 
 template <class Cfg, int MODE>
 __global__ __launch_bounds__(Cfg::NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void k_lookup_pipe(
     const bf16_t *__restrict__ Q, const bf16_t *__restrict__ C, const float *__restrict__ invn, long n, long K, int d,
-    int tiles_per_slice, int slices, int nqt, int qb, int nt_centroids, u64 *__restrict__ keys, float threshold,
+    int tiles_per_slice, int slices, int nqt, int qb, u64 *__restrict__ keys, float threshold,
     int *__restrict__ out_pairs, long cap, u64 *__restrict__ counter) {
     constexpr int WC = Cfg::WC, WQ = Cfg::WQ, NWC = Cfg::NWC, BC = Cfg::BC, BQ = Cfg::BQ, NT = Cfg::NT, NW = Cfg::NW,
                   STAGE = Cfg::STAGE, NLA = Cfg::NLA, NLB = Cfg::NLB, NL = Cfg::NL, NSTAGE = Cfg::NSTAGE, BK = Cfg::BK,
@@ -133,51 +270,28 @@ __global__ __launch_bounds__(Cfg::NT) __attribute__((amdgpu_waves_per_eu(2, 2)))
     const int wc = wave % NWC, wq = wave / NWC;
     const int h = lane >> 5, l32 = lane & 31;
 
-    // Block -> (query tile qt, slice s of the centroid tiles).  Workgroups are handed to the 8 XCDs
-    // round robin and every XCD has its own L2.  The 32 workgroups that run together on one XCD are
-    // made a block of qb query tiles x 32/qb slices, so that a centroid tile fetched into that L2
-    // serves qb workgroups and qb query tiles stay resident in it; an XCD owns every eighth group of
-    // 32/qb slices and walks through all query tiles for it before moving on.
-    // In the pair search the query tile is a centroid tile too and only the tiles at or right of it
-    // are visited (upper triangle); slices are absolute ranges of tiles, so that the workgroups of a
-    // block still walk through the same centroid tiles in step.
     static_assert(MODE == PIPE_LOOKUP || Cfg::BC == Cfg::BQ, "pair search walks square tiles");
-    const int total_ct = (int)((K + BC - 1) / BC);
     int qt, s, ct_begin, ct_end;
-    {
-        const int sb = 32 / qb;
-        const int xcd = blockIdx.x & 7, local = blockIdx.x >> 3;
-        const int nqb = (nqt + qb - 1) / qb;
-        const int grp = local / (nqb * 32), rem = local % (nqb * 32);
-        const int i = rem & 31;
-        qt = (rem >> 5) * qb + i % qb;
-        s = (grp * 8 + xcd) * sb + i / qb;
-        if (qt >= nqt || s >= slices) return;
-        ct_begin = s * tiles_per_slice;
-        ct_end = (ct_begin + tiles_per_slice < total_ct) ? ct_begin + tiles_per_slice : total_ct;
-        if (MODE == PIPE_PAIRS) {
-            if (ct_begin < qt) ct_begin = qt;
-            if (ct_begin >= ct_end) return;
-        }
-    }
+    if (!pipe_map_block<MODE, BC>(K, tiles_per_slice, slices, nqt, qb, qt, s, ct_begin, ct_end)) return;
     const long q0 = (long)qt * BQ;
     const int nk = d / BK;
     const int T = (ct_end - ct_begin) * nk;  // slabs this workgroup walks through
+    if (T <= 0) return;
 
-    // direct-load addressing
+    // direct-load addressing: byte offset of this lane's 16 bytes from the slab's first element, per load
     const int lr = lane / CPR, slot = lane % CPR;
     unsigned a_off[NLA], b_off[NLB];
 #pragma unroll
     for (int j = 0; j < NLA; ++j) {
         const int row = (j * NW + wave) * RPI + lr;
-        a_off[j] = (unsigned)(row * d + ((slot ^ ((row / RP) % CPR)) * 8));
+        a_off[j] = (unsigned)(row * d + ((slot ^ ((row / RP) % CPR)) * 8)) * 2u;
     }
 #pragma unroll
     for (int j = 0; j < NLB; ++j) {
         const int row = (j * NW + wave) * RPI + lr;
         long qr = q0 + row;
         if (qr > n - 1) qr = n - 1;
-        b_off[j] = (unsigned)((qr - q0) * d + ((slot ^ ((row / RP) % CPR)) * 8));
+        b_off[j] = (unsigned)((qr - q0) * d + ((slot ^ ((row / RP) % CPR)) * 8)) * 2u;
     }
     const bf16_t *qbase = Q + (size_t)q0 * d;
 
@@ -201,39 +315,56 @@ __global__ __launch_bounds__(Cfg::NT) __attribute__((amdgpu_waves_per_eu(2, 2)))
     float wi[WQ];  // pairs: 1/|c| of this lane's columns (NaN past the live centroids)
 #pragma unroll
     for (int b = 0; b < WQ; ++b) wi[b] = MODE == PIPE_PAIRS ? invn[q0 + (wq * WQ + b) * 32 + l32] : 0.f;
-    f32x16 acc[WC][WQ];
-#pragma unroll
-    for (int a = 0; a < WC; ++a)
-#pragma unroll
-        for (int b = 0; b < WQ; ++b)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) acc[a][b][i] = 0.f;
+    Acc<false, WC, WQ> acc;  // every tile starts from a zero operand, so nothing to clear
+    acc.reserve();
 
     // slab t lives in stage t % NSTAGE; (ld_ct, ld_ks, ld_stage) name the slab the next issue fetches.
     // With slab 0 of a tile travel the inverse lengths of the tile's centroids (the rows past the
     // live ones hold NaN), one 4-byte direct load per lane of the first BC/64 waves.
     int ld_ct = ct_begin, ld_ks = 0, ld_stage = 0;
-    auto issue = [&]() {
-        if (ld_ks == 0 && wave < BC / 64)
-            gload_lds4(invn + (size_t)ld_ct * BC + wave * 64 + lane, inv_s + (ld_ct & 1) * BC + wave * 64);
-        const bf16_t *cb = C + (size_t)ld_ct * BC * d + ld_ks * BK;
-        const bf16_t *qb = qbase + ld_ks * BK;
-        unsigned char *sb = smem + ld_stage * STAGE;
-        if (nt_centroids) {
-#pragma unroll
-            for (int j = 0; j < NLA; ++j) gload_lds16_nt(cb + a_off[j], sb + (j * NW + wave) * 1024);
+    // One part = one direct load of this wave; part NL - 1 also moves on to the next slab, but
+    // never past the last one (the wide path issues unconditionally and so fetches the last slab
+    // again, into a stage nobody reads any more).  The centroids are read once per block of query
+    // tiles: in a lookup their loads carry the non-temporal hint so that they do not push the
+    // query tiles out of L2.
+    const char *ld_c = (const char *)(C + (size_t)ct_begin * BC * d);  // first element of the slab, centroid side
+    const char *ld_q = (const char *)qbase;                              // and query side
+    unsigned char *ld_sb = smem + wave * 1024;                           // this wave's first KiB of the stage
+    int ld_t = 0;
+    auto issue_part = [&](auto jj) {
+        constexpr int j = decltype(jj)::value;
+        if constexpr (j == 0) {
+            if (ld_ks == 0 && wave < BC / 64)
+                gload_lds4(invn + (size_t)ld_ct * BC + wave * 64 + lane, inv_s + (ld_ct & 1) * BC + wave * 64);
+        }
+        // (the empty statement keeps the 32-bit offset next to its use, which lets the load take the
+        // uniform base from scalar registers instead of a 64-bit address per lane)
+        if constexpr (j < NLA) {
+            unsigned off = a_off[j];
+            asm volatile("" : "+v"(off));
+            if constexpr (MODE == PIPE_LOOKUP) gload_lds16_nt(ld_c + off, ld_sb + j * NW * 1024);
+            else gload_lds16(ld_c + off, ld_sb + j * NW * 1024);
         } else {
-#pragma unroll
-            for (int j = 0; j < NLA; ++j) gload_lds16(cb + a_off[j], sb + (j * NW + wave) * 1024);
+            unsigned off = b_off[j - NLA];
+            asm volatile("" : "+v"(off));
+            gload_lds16(ld_q + off, ld_sb + BC * RB + (j - NLA) * NW * 1024);
         }
-#pragma unroll
-        for (int j = 0; j < NLB; ++j) gload_lds16(qb + b_off[j], sb + BC * RB + (j * NW + wave) * 1024);
-        if (++ld_ks == nk) {
-            ld_ks = 0;
-            ++ld_ct;
+        if constexpr (j == NL - 1) {
+            if (ld_t + 1 < T) {
+                ++ld_t;
+                if (++ld_ks == nk) {
+                    ld_ks = 0;
+                    ++ld_ct;
+                    ld_c += (size_t)(BC - 1) * d * 2;  // with the step below: on to the next tile's first slab
+                    ld_q = (const char *)qbase - BK * 2;
+                }
+                ld_c += BK * 2;
+                ld_q += BK * 2;
+            }
+            ld_sb = (++ld_stage == NSTAGE) ? (ld_stage = 0, smem + wave * 1024) : ld_sb + STAGE;
         }
-        if (++ld_stage == NSTAGE) ld_stage = 0;
     };
+    auto issue = [&]() { static_for<0, NL>(issue_part); };
 
     // Pipeline:
     //   all but the last step of slab t | wait: own reads of slab t done, own loads of slab t+1 landed | barrier |
@@ -250,7 +381,7 @@ __global__ __launch_bounds__(Cfg::NT) __attribute__((amdgpu_waves_per_eu(2, 2)))
     if (T >= NSTAGE) vm_wait<(NSTAGE - 1) * NL>();
     else vm_wait<0>();
     __syncthreads();
-    if (T > 0) lds_frags<SUB>(af[0], bf[0], row_a + so[0], row_b + so[0]);
+    lds_frags<SUB>(af[0], bf[0], row_a + so[0], row_b + so[0]);
 
     int ct = ct_begin, ks = 0;
     unsigned sto = 0;  // byte offset of the stage of slab t
@@ -263,19 +394,19 @@ __global__ __launch_bounds__(Cfg::NT) __attribute__((amdgpu_waves_per_eu(2, 2)))
             __builtin_amdgcn_sched_barrier(0);
             if (kk == 0 && ks == 0) {
                 // first step of a tile: start from zero instead of clearing the accumulators
-                const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-                for (int a = 0; a < WC; ++a)
-#pragma unroll
-                    for (int b = 0; b < WQ; ++b)
-                        acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[0][a], bf[0][b], zero, 0, 0, 0);
+                static_for<0, WC>([&](auto ia) {
+                    static_for<0, WQ>([&](auto ib) {
+                        constexpr int A = decltype(ia)::value, B = decltype(ib)::value;
+                        acc.template first<A, B>(af[0][A], bf[0][B]);
+                    });
+                });
             } else {
-#pragma unroll
-                for (int a = 0; a < WC; ++a)
-#pragma unroll
-                    for (int b = 0; b < WQ; ++b)
-                        acc[a][b] =
-                            __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[kk & 1][a], bf[kk & 1][b], acc[a][b], 0, 0, 0);
+                static_for<0, WC>([&](auto ia) {
+                    static_for<0, WQ>([&](auto ib) {
+                        constexpr int A = decltype(ia)::value, B = decltype(ib)::value;
+                        acc.template mac<A, B>(af[kk & 1][A], bf[kk & 1][B]);
+                    });
+                });
             }
             __builtin_amdgcn_sched_barrier(0);
         }
@@ -286,45 +417,48 @@ __global__ __launch_bounds__(Cfg::NT) __attribute__((amdgpu_waves_per_eu(2, 2)))
         if (t + NSTAGE < T) issue();
         if (t + 1 < T) lds_frags<SUB>(af[0], bf[0], row_a + sto_next + so[0], row_b + sto_next + so[0]);
         __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-        for (int a = 0; a < WC; ++a)
-#pragma unroll
-            for (int b = 0; b < WQ; ++b)
-                acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[1][a], bf[1][b], acc[a][b], 0, 0, 0);
+        static_for<0, WC>([&](auto ia) {
+            static_for<0, WQ>([&](auto ib) {
+                constexpr int A = decltype(ia)::value, B = decltype(ib)::value;
+                acc.template mac<A, B>(af[1][A], bf[1][B]);
+            });
+        });
         __builtin_amdgcn_sched_barrier(0);
         if (ks == nk - 1) {
             // tile done: scale by 1/|c|, fold into the running maximum of each query column
             const long c0 = (long)ct * BC;
             const float *inv_t = inv_s + (ct & 1) * BC;
-#pragma unroll
-            for (int a = 0; a < WC; ++a) {
-                const int rb = (wc * WC + a) * 32;
+            static_for<0, WC>([&](auto ia) {
+                constexpr int A = decltype(ia)::value;
+                const int rb = (wc * WC + A) * 32;
                 f32x4 w[4];
 #pragma unroll
                 for (int g = 0; g < 4; ++g) w[g] = *(const f32x4 *)(inv_t + rb + 8 * g + 4 * h);
                 const unsigned blk = (unsigned)((c0 + rb) / SISO_RUN_ROWS) * 4u + 2u * (unsigned)h;
-#pragma unroll
-                for (int b = 0; b < WQ; ++b) {
+                static_for<0, WQ>([&](auto ib) {
+                    constexpr int B = decltype(ib)::value;
                     float m = -INFINITY;
-#pragma unroll
-                    for (int i = 0; i < 16; ++i) m = fmaxf(m, acc[a][b][i] * w[i >> 2][i & 3]);
+                    static_for<0, 16>([&](auto ii) {
+                        constexpr int I = decltype(ii)::value;
+                        m = fmaxf(m, acc.template get<A, B, I>() * w[I >> 2][I & 3]);
+                    });
                     if (MODE == PIPE_LOOKUP) {
-                        if (m > bv[b]) {
-                            bv[b] = m;
-                            bb[b] = blk;
+                        if (m > bv[B]) {
+                            bv[B] = m;
+                            bb[B] = blk;
                         }
-                    } else if (__ballot(m * wi[b] > threshold) != 0) {
+                    } else if (__ballot(m * wi[B] > threshold) != 0) {
                         // rare: some product of this 32 x 32 block is above the threshold
-                        const long icol = q0 + (wq * WQ + b) * 32 + l32;
-#pragma unroll
-                        for (int i = 0; i < 16; ++i) {
-                            const long jrow = c0 + rb + 8 * (i >> 2) + 4 * h + (i & 3);
-                            const float sim = acc[a][b][i] * w[i >> 2][i & 3] * wi[b];
+                        const long icol = q0 + (wq * WQ + B) * 32 + l32;
+                        static_for<0, 16>([&](auto ii) {
+                            constexpr int I = decltype(ii)::value;
+                            const long jrow = c0 + rb + 8 * (I >> 2) + 4 * h + (I & 3);
+                            const float sim = acc.template get<A, B, I>() * w[I >> 2][I & 3] * wi[B];
                             emit_pair(sim > threshold && icol < jrow, (int)icol, (int)jrow, out_pairs, cap, counter);
-                        }
+                        });
                     }
-                }
-            }
+                });
+            });
             ks = 0;
             ++ct;
         } else {
@@ -335,33 +469,315 @@ __global__ __launch_bounds__(Cfg::NT) __attribute__((amdgpu_waves_per_eu(2, 2)))
     __syncthreads();
     if (MODE == PIPE_PAIRS) return;
 
-    // lanes l and l^32 hold the same query column
+    pipe_reduce_keys<WQ, NWC, BQ, NT>(bv, bb, smem, wc, wq, h, l32, tid, q0, n, slices, s, keys);
+}
+
+// ----------------------------------------------------------------------------
+// The wide variant of the same kernel: four waves (one per SIMD), each with a tile of 128 x 128
+// = 16 accumulator blocks, so that a fragment read from LDS feeds four MFMAs instead of two
+// or four-thirds.  With one wave per SIMD nothing hides a stall, and a direct load into LDS
+// can only be issued once its stage is free, i.e. one slab ahead, which is less than such a
+// load takes under full traffic.  So the global loads go through registers here: the loads of slab
+// t+4 are issued while slab t is being multiplied, land in one of two register buffers, and are
+// written to the LDS stage of slab t+2 two slabs later: two slabs of flight time instead of one.
+//
+// Per slab t (parity p = t & 1, stage p, register buffer G[p]):
+//   steps 0..2: MFMAs; behind them the fragment reads of the next step and, one per four MFMAs, parts
+//               4..15 of buffer 1-p: write to stage 1-p (slab t+1), load again (slab t+3)
+//   wait for own LDS traffic | barrier: everyone has read all of stage p and written all of stage 1-p
+//   step 3:     MFMAs; behind them the first fragment reads of slab t+1 and parts 0..3 of buffer p:
+//               write to stage p (slab t+2), load again (slab t+4)
+//   epilogue if the tile is complete
+// Behind the last slabs the loads fetch the last slab again and the writes put it into a stage
+// nobody reads any more: one code path, no conditions between the MFMAs.
+// ----------------------------------------------------------------------------
+// Fragments at fixed registers, for the wide kernel: a value that the compiler knows about can be
+// copied or moved by it at any time, also while the LDS read that produces it is still in flight.
+// With one wave per SIMD the reads must stay in flight across branches and the loop edge, so the
+// wide kernel keeps its fragments out of the compiler's sight, in v[WIDE_FRAG0 .. 255], which the
+// kernel's register limit takes away from the allocator.
+#define WIDE_FRAG0 208
+template <int REG, int OFF>
+__device__ __forceinline__ void frag_read(unsigned addr) {
+    asm volatile("ds_read_b128 v[%1:%2], %0 offset:%3 ; hand-placed" ::"v"(addr), "n"(REG), "n"(REG + 3), "n"(OFF) : "memory");
+}
+template <int ACC, int RA, int RB>
+__device__ __forceinline__ void frag_mac() {
+    asm volatile("v_mfma_f32_32x32x16_bf16 a[%0:%1], v[%2:%3], v[%4:%5], a[%0:%1] ; hand-placed" ::"n"(ACC), "n"(ACC + 15),
+                 "n"(RA), "n"(RA + 3), "n"(RB), "n"(RB + 3));
+}
+template <int ACC, int RA, int RB>
+__device__ __forceinline__ void frag_first() {
+    asm volatile("v_mfma_f32_32x32x16_bf16 a[%0:%1], v[%2:%3], v[%4:%5], 0 ; hand-placed" ::"n"(ACC), "n"(ACC + 15), "n"(RA),
+                 "n"(RA + 3), "n"(RB), "n"(RB + 3));
+}
+template <int N>
+__device__ __forceinline__ void lgkm_wait() {
+    asm volatile("s_waitcnt lgkmcnt(%0)" ::"n"(N) : "memory");
+}
+
+struct WideCfg {
+    static constexpr int WC = 4, WQ = 4, NWC = 2, NWQ = 2, NW = 4, NT = 256;
+    static constexpr int BC = 256, BQ = 256, BK = 64, RB = 128, KK = 4;
+    static constexpr int STAGE = (BC + BQ) * RB;  // 64 KiB
+    static constexpr int NLA = BC / 8 / NW, NLB = BQ / 8 / NW, NL = NLA + NLB;  // 16-byte loads per lane and slab
+    static constexpr int LDS_BYTES = 2 * STAGE + 2 * BC * 4;
+    static_assert(NL == WC * WQ, "one load and one write behind every MFMA of a step");
+    // fragment registers: A fragment k (one buffer), B fragment k of buffer b (two buffers)
+    static constexpr int ra(int k) { return WIDE_FRAG0 + 4 * k; }
+    static constexpr int rb(int b, int k) { return WIDE_FRAG0 + 4 * WC + 4 * WQ * b + 4 * k; }
+    static_assert(WIDE_FRAG0 + 4 * WC + 8 * WQ == 256, "fragments fill the registers behind the allocator's share");
+};
+
+template <int MODE>
+__global__ __launch_bounds__(WideCfg::NT) __attribute__((amdgpu_waves_per_eu(1, 1), amdgpu_num_vgpr(WIDE_FRAG0))) void k_lookup_wide(
+    const bf16_t *__restrict__ Q, const bf16_t *__restrict__ C, const float *__restrict__ invn, long n, long K, int d,
+    int tiles_per_slice, int slices, int nqt, int qb, u64 *__restrict__ keys, float threshold,
+    int *__restrict__ out_pairs, long cap, u64 *__restrict__ counter) {
+    typedef WideCfg Cfg;
+    constexpr int WC = Cfg::WC, WQ = Cfg::WQ, NWC = Cfg::NWC, BC = Cfg::BC, BQ = Cfg::BQ, NT = Cfg::NT, NW = Cfg::NW,
+                  STAGE = Cfg::STAGE, NLA = Cfg::NLA, NL = Cfg::NL, BK = Cfg::BK, RB = Cfg::RB, KK = Cfg::KK,
+                  SUB = 32 * Cfg::RB, NF = WC + WQ;
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    float *inv_s = (float *)(smem + 2 * STAGE);  // [2][BC], by tile parity
+
+    const int tid = threadIdx.x;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
+    const int wc = wave % NWC, wq = wave / NWC;
+    const int h = lane >> 5, l32 = lane & 31;
+
+    int qt, s, ct_begin, ct_end;
+    if (!pipe_map_block<MODE, BC>(K, tiles_per_slice, slices, nqt, qb, qt, s, ct_begin, ct_end)) return;
+    const long q0 = (long)qt * BQ;
+    const int nk = d / BK;
+    const int T = (ct_end - ct_begin) * nk;  // slabs this workgroup walks through
+    if (T <= 0) return;
+
+    // Global loads: load j of a wave covers the 8 tile rows (4 j + wave) * 8 .. + 8, 128 bytes each;
+    // lane i takes the 16 bytes that belong in slot i % 8 of row i / 8 (the swizzle of the LDS layout
+    // is applied to the global chunk; it does not depend on j because rows advance by 32).
+    const int lr = lane >> 3, slot = lane & 7;
+    const int row0 = wave * 8 + lr;
+    const unsigned chunk = (unsigned)((slot ^ ((row0 >> 1) & 7)) * 16);
+    const unsigned a_voff = (unsigned)row0 * (unsigned)d * 2u + chunk;
+    const int last_q = (int)((n - 1 - q0 < BQ - 1) ? n - 1 - q0 : BQ - 1);  // rows past the batch read its last row
+    const bf16_t *qbase = Q + (size_t)q0 * d;
+    const unsigned lds0 = (unsigned)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)smem;
+    unsigned char *wr = smem + wave * 1024 + lane * 16;  // this lane's 16 bytes of load 0 in stage 0
+
+    // fragment read addresses, as in k_lookup_pipe
+    const int sw = (l32 >> 1) & 7;
+    const unsigned row_a = lds0 + (unsigned)(((wc * WC) * 32 + l32) * RB);
+    const unsigned row_b = lds0 + (unsigned)(BC * RB + ((wq * WQ) * 32 + l32) * RB);
+    unsigned so[KK];
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk) so[kk] = (unsigned)(((kk * 2 + h) ^ sw) * 16);
+
+    float bv[WQ];
+    unsigned bb[WQ];
 #pragma unroll
     for (int b = 0; b < WQ; ++b) {
-        const float ov = __shfl_xor(bv[b], 32);
-        const unsigned ob = __shfl_xor(bb[b], 32);
-        siso_merge_candidate(bv[b], bb[b], ov, ob);
+        bv[b] = -INFINITY;
+        bb[b] = 0xFFFFFFFFu;
     }
-    // waves with the same wq share query columns: meet in LDS (stage memory is free now)
-    float *red_v = (float *)smem;  // [NWC][BQ]
-    unsigned *red_b = (unsigned *)(smem + NWC * BQ * 4);
-    if (h == 0) {
+    float wi[WQ];  // pairs: 1/|c| of this lane's columns (NaN past the live centroids)
 #pragma unroll
-        for (int b = 0; b < WQ; ++b) {
-            const int col = (wq * WQ + b) * 32 + l32;
-            red_v[wc * BQ + col] = bv[b];
-            red_b[wc * BQ + col] = bb[b];
+    for (int b = 0; b < WQ; ++b) wi[b] = MODE == PIPE_PAIRS ? invn[q0 + (wq * WQ + b) * 32 + l32] : 0.f;
+    Acc<true, WC, WQ> acc;
+    acc.reserve();
+
+    // register buffers: G[p][j] = the 16 bytes of load j of a slab of parity p; gi = inverse lengths
+    // of the slab's tile when it is the tile's first slab (they travel with it into inv_s)
+    u32x4 G[2][NL];
+    float gi0 = 0.f, gi1 = 0.f;
+    int gs0 = -1, gs1 = -1;  // where gi belongs in inv_s (tile parity), -1 = nothing to write
+    const char *ld_c = (const char *)(C + (size_t)ct_begin * BC * d);  // first element of the slab to load, centroid side
+    const char *ld_q = (const char *)qbase;                              // and query side
+    int ld_t = 0, ld_ks = 0, ld_ct = ct_begin;
+    auto load_part = [&](auto pp, auto jj) __attribute__((always_inline)) {
+        constexpr int p = decltype(pp)::value, j = decltype(jj)::value;
+        if constexpr (j == 0) {
+            float &gi = p == 0 ? gi0 : gi1;
+            int &gs = p == 0 ? gs0 : gs1;
+            gs = -1;
+            if (ld_ks == 0) {
+                gi = invn[(size_t)ld_ct * BC + wave * 64 + lane];
+                gs = ld_ct & 1;
+            }
         }
-    }
-    __syncthreads();
-    for (int col = tid; col < BQ; col += NT) {
-        float v = red_v[col];
-        unsigned blk = red_b[col];
+        if constexpr (j < NLA) {
+            unsigned off = a_voff;
+            asm volatile("" : "+v"(off));  // keeps the 32-bit offset next to its use: scalar base + lane offset
+            const u32x4 *src = (const u32x4 *)(ld_c + (size_t)j * 64 * d + off);
+            if constexpr (MODE == PIPE_LOOKUP) G[p][j] = __builtin_nontemporal_load(src);
+            else G[p][j] = *src;
+        } else {
+            // (computed here every time: eight more loop-invariant registers would not fit)
+            int row = row0;
+            asm volatile("" : "+v"(row));
+            row += 32 * (j - NLA);
+            row = row < last_q ? row : last_q;
+            const unsigned off = (unsigned)row * (unsigned)d * 2u + chunk;
+            G[p][j] = *(const u32x4 *)(ld_q + off);
+        }
+        if constexpr (j == NL - 1) {
+            if (ld_t + 1 < T) {
+                ++ld_t;
+                if (++ld_ks == nk) {
+                    ld_ks = 0;
+                    ++ld_ct;
+                    ld_c += (size_t)(BC - 1) * d * 2;  // with the step below: on to the next tile's first slab
+                    ld_q = (const char *)qbase - BK * 2;
+                }
+                ld_c += BK * 2;
+                ld_q += BK * 2;
+            }
+        }
+    };
+    auto write_part = [&](auto pp, auto jj) __attribute__((always_inline)) {
+        constexpr int p = decltype(pp)::value, j = decltype(jj)::value;
+        if constexpr (j == 0) {
+            const float gi = p == 0 ? gi0 : gi1;
+            const int gs = p == 0 ? gs0 : gs1;
+            if (gs >= 0) inv_s[gs * BC + wave * 64 + lane] = gi;
+        }
+        // loads 0 .. NLA-1 fill the centroid rows of the stage, the others the query rows behind them
+        *(u32x4 *)(wr + p * STAGE + j * NW * 1024) = G[p][j];
+    };
+    // One step = 16 MFMAs, block (A, B) = A fragment A x B fragment B of buffer `cur`, A-major.  The
+    // fragments of the next step are read meanwhile: the four B fragments behind the first four
+    // MFMAs into the other B buffer, and A fragment k into its own registers behind the last MFMA
+    // that uses it (an MFMA has taken its operands when the next instruction issues, and LDS data
+    // takes far longer to come).  So a step may start when all but the newest read (A fragment 3)
+    // have arrived, and waits for that one before its 13th MFMA (by then at most the 4 reads and
+    // writes issued last are younger than it needs to be).
+    auto step = [&](auto first_tag, auto cur_tag, unsigned addr_a, unsigned addr_b, auto &&extra) __attribute__((always_inline)) {
+        constexpr int cur = decltype(cur_tag)::value;
+        lgkm_wait<1>();
+        static_for<0, WC * WQ>([&](auto ii) __attribute__((always_inline)) {
+            constexpr int i = decltype(ii)::value, A = i / WQ, B = i % WQ;
+            if constexpr (i == (WC - 1) * WQ) lgkm_wait<4>();
+            if constexpr (decltype(first_tag)::value) frag_first<16 * i, Cfg::ra(A), Cfg::rb(cur, B)>();
+            else frag_mac<16 * i, Cfg::ra(A), Cfg::rb(cur, B)>();
+            extra(ii);
+            if constexpr (i < WQ) frag_read<Cfg::rb(1 - cur, i), i * SUB>(addr_b);
+            if constexpr (B == WQ - 1) frag_read<Cfg::ra(A), A * SUB>(addr_a);
+        });
+    };
+    auto lds_barrier = [&]() __attribute__((always_inline)) {
+        // own LDS reads and writes are done (lgkmcnt(0) just before); global loads stay in flight
+        asm volatile("s_barrier" ::: "memory");
+    };
+
+    // Part j of a buffer is written to its stage and loaded again right away, one part behind every
+    // fourth MFMA: the traffic is even over time (a burst of loads would hold up the wave, and with
+    // it the MFMAs, while the texture unit works it off) and every load has two slabs to land.
+    // The stage of parity p is free between the barrier of slab t (parity p) and that of slab t+1:
+    // parts 0..3 of buffer p go with step 3 of slab t, parts 4..15 with steps 0..2 of slab t+1.
+    auto xfer = [&](auto pp, auto jj) __attribute__((always_inline)) {
+        write_part(pp, jj);
+        load_part(pp, jj);
+    };
+    // prologue: slab 0 in stage 0, slab 2 on its way into buffer 0; the first four parts of slab 1 in
+    // stage 1 and those of slab 3 on their way, the other parts of slab 1 still in buffer 1, as if
+    // a slab of parity 1 had just gone by
+    static_for<0, NL>([&](auto jj) __attribute__((always_inline)) { load_part(IC<0>{}, jj); });
+    static_for<0, NL>([&](auto jj) __attribute__((always_inline)) { load_part(IC<1>{}, jj); });
+    static_for<0, NL>([&](auto jj) __attribute__((always_inline)) { xfer(IC<0>{}, jj); });
+    static_for<0, 4>([&](auto jj) __attribute__((always_inline)) { xfer(IC<1>{}, jj); });
+    lgkm_wait<0>();
+    lds_barrier();
+    static_for<0, WQ>([&](auto kk) __attribute__((always_inline)) {
+        constexpr int k = decltype(kk)::value;
+        frag_read<Cfg::rb(0, k), k * SUB>(row_b + so[0]);
+    });
+    static_for<0, WC>([&](auto kk) __attribute__((always_inline)) {
+        constexpr int k = decltype(kk)::value;
+        frag_read<Cfg::ra(k), k * SUB>(row_a + so[0]);
+    });
+
+    int ct = ct_begin, ks = 0;
+    // One slab of parity p.  The B fragments of step kk are in buffer kk & 1; KK is even, so every
+    // slab starts in buffer 0.
+    static_assert(KK == 4, "steps are spelled out");
+    auto slab = [&](auto pp) __attribute__((always_inline)) {
+        constexpr int p = decltype(pp)::value;
+        constexpr unsigned sto = p * STAGE, sto_next = (1 - p) * STAGE;
+        // (read addresses are summed up here every time: more loop-invariant registers would not fit)
+        auto at = [&](unsigned row, unsigned stage, int k) __attribute__((always_inline)) {
+            unsigned sk = so[k];
+            asm volatile("" : "+v"(sk));
+            return row + stage + sk;
+        };
+        // the part that goes behind MFMA i of step kk: buffer and first part by step, one per four MFMAs
+        auto part = [&](auto bb_, auto j0, auto ii) __attribute__((always_inline)) {
+            constexpr int i = decltype(ii)::value;
+            if constexpr (i % 4 == 1) xfer(bb_, IC<decltype(j0)::value + i / 4>{});
+        };
+        if (ks == 0)  // a tile starts from zero
+            step(IC<1>{}, IC<0>{}, at(row_a, sto, 1), at(row_b, sto, 1), [&](auto ii) __attribute__((always_inline)) { part(IC<1 - p>{}, IC<4>{}, ii); });
+        else
+            step(IC<0>{}, IC<0>{}, at(row_a, sto, 1), at(row_b, sto, 1), [&](auto ii) __attribute__((always_inline)) { part(IC<1 - p>{}, IC<4>{}, ii); });
+        step(IC<0>{}, IC<1>{}, at(row_a, sto, 2), at(row_b, sto, 2), [&](auto ii) __attribute__((always_inline)) { part(IC<1 - p>{}, IC<8>{}, ii); });
+        step(IC<0>{}, IC<0>{}, at(row_a, sto, 3), at(row_b, sto, 3), [&](auto ii) __attribute__((always_inline)) { part(IC<1 - p>{}, IC<12>{}, ii); });
+        // all own reads of this stage have been issued; the barrier needs them, and the LDS writes
+        // into the other stage, complete
+        lgkm_wait<0>();
+        lds_barrier();
+        step(IC<0>{}, IC<1>{}, at(row_a, sto_next, 0), at(row_b, sto_next, 0), [&](auto ii) __attribute__((always_inline)) { part(pp, IC<0>{}, ii); });
+        __builtin_amdgcn_sched_barrier(0);
+        const bool tile_done = ks == nk - 1;
+        if (tile_done) {
+            // scale by 1/|c|, fold into the running maximum of each query column
+            const long c0 = (long)ct * BC;
+            const float *inv_t = inv_s + (ct & 1) * BC;
+            static_for<0, WC>([&](auto ia) __attribute__((always_inline)) {
+                constexpr int A = decltype(ia)::value;
+                const int rb = (wc * WC + A) * 32;
+                f32x4 w[4];
 #pragma unroll
-        for (int w2 = 1; w2 < NWC; ++w2) siso_merge_candidate(v, blk, red_v[w2 * BQ + col], red_b[w2 * BQ + col]);
-        const long q = q0 + col;
-        if (q < n) keys[(size_t)q * slices + s] = (blk == 0xFFFFFFFFu) ? 0ull : pack_key(v, blk);
+                for (int g = 0; g < 4; ++g) w[g] = *(const f32x4 *)(inv_t + rb + 8 * g + 4 * h);
+                const unsigned blk = (unsigned)((c0 + rb) / SISO_RUN_ROWS) * 4u + 2u * (unsigned)h;
+                static_for<0, WQ>([&](auto ib) __attribute__((always_inline)) {
+                    constexpr int B = decltype(ib)::value;
+                    float m = -INFINITY;
+                    static_for<0, 16>([&](auto ii) __attribute__((always_inline)) {
+                        constexpr int I = decltype(ii)::value;
+                        m = fmaxf(m, acc.template get<A, B, I>() * w[I >> 2][I & 3]);
+                    });
+                    if (MODE == PIPE_LOOKUP) {
+                        if (m > bv[B]) {
+                            bv[B] = m;
+                            bb[B] = blk;
+                        }
+                    } else if (__ballot(m * wi[B] > threshold) != 0) {
+                        // rare: some product of this 32 x 32 block is above the threshold
+                        const long icol = q0 + (wq * WQ + B) * 32 + l32;
+                        static_for<0, 16>([&](auto ii) __attribute__((always_inline)) {
+                            constexpr int I = decltype(ii)::value;
+                            const long jrow = c0 + rb + 8 * (I >> 2) + 4 * h + (I & 3);
+                            const float sim = acc.template get<A, B, I>() * w[I >> 2][I & 3] * wi[B];
+                            emit_pair(sim > threshold && icol < jrow, (int)icol, (int)jrow, out_pairs, cap, counter);
+                        });
+                    }
+                });
+            });
+        }
+        ct += tile_done ? 1 : 0;
+        ks = tile_done ? 0 : ks + 1;
+    };
+    // (two slabs per trip with nothing conditional between them: the compiler counts the loads in
+    // flight itself and must see that those of the other parity are always the younger ones)
+    int t = 0;
+    for (; t + 1 < T; t += 2) {
+        slab(IC<0>{});
+        slab(IC<1>{});
     }
+    if (t < T) slab(IC<0>{});
+    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");  // reads, loads and writes of the tail have landed
+    lds_barrier();
+    if (MODE == PIPE_PAIRS) return;
+    pipe_reduce_keys<WQ, NWC, BQ, NT>(bv, bb, smem, wc, wq, h, l32, tid, q0, n, slices, s, keys);
 }
 
 typedef PipeCfg<4, 2, 2, 4, 2> PipeLarge;  // 256 x 256 tile, waves of 128 x 64, two stages
@@ -377,10 +793,10 @@ struct PipePlan {
     long grid;
 };
 
-// cfg: 1 = PipeLarge, 2 = PipeMid, 3 = PipeSmall, 4 = PipeLarge32
+// cfg: 1 = PipeLarge, 2 = PipeMid, 3 = PipeSmall, 4 = PipeLarge32, 5 = the wide kernel (same tile as 1)
 static bool pipe_plan(const siso_cache *c, long n, int cfg, long want_wgs, PipePlan *p) {
     if (c->dtype != SISO_BF16 || c->dim % 64 != 0 || c->dim < 128 || c->count < 1 || n < 1) return false;
-    if (cfg < 1 || cfg > 4) return false;
+    if (cfg < 1 || cfg > 5) return false;
     p->cfg = cfg;
     p->bc = 256;
     p->bq = cfg == 2 ? PipeMid::BQ : cfg == 3 ? PipeSmall::BQ : PipeLarge::BQ;
@@ -442,8 +858,22 @@ static int launch_cfg(siso_cache *c, const void *queries, long n, const PipePlan
     }
     hipLaunchKernelGGL((k_lookup_pipe<Cfg, PIPE_LOOKUP>), dim3((unsigned)p.grid), dim3(Cfg::NT), Cfg::LDS_BYTES,
                        c->stream, (const bf16_t *)queries, (const bf16_t *)c->cent, c->invn, n, c->count, c->dim,
-                       p.tiles_per_slice, p.slices, p.nqt, p.qb, c->opt_mfma_nt ? 0 : 1, c->keys, 0.f, (int *)nullptr, 0L, (u64 *)nullptr);
+                       p.tiles_per_slice, p.slices, p.nqt, p.qb, c->keys, 0.f, (int *)nullptr, 0L, (u64 *)nullptr);
     return siso_check_hip(c, hipGetLastError(), "k_lookup_pipe");
+}
+
+static int launch_wide(siso_cache *c, const void *queries, long n, const PipePlan &p) {
+    static bool attr_done = false;
+    if (!attr_done) {
+        hipError_t e = hipFuncSetAttribute((const void *)k_lookup_wide<PIPE_LOOKUP>,
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, WideCfg::LDS_BYTES);
+        if (e != hipSuccess) return siso_check_hip(c, e, "hipFuncSetAttribute(k_lookup_wide)");
+        attr_done = true;
+    }
+    hipLaunchKernelGGL((k_lookup_wide<PIPE_LOOKUP>), dim3((unsigned)p.grid), dim3(WideCfg::NT), WideCfg::LDS_BYTES, c->stream,
+                       (const bf16_t *)queries, (const bf16_t *)c->cent, c->invn, n, c->count, c->dim, p.tiles_per_slice,
+                       p.slices, p.nqt, p.qb, c->keys, 0.f, (int *)nullptr, 0L, (u64 *)nullptr);
+    return siso_check_hip(c, hipGetLastError(), "k_lookup_wide");
 }
 
 static int pipe_launch(siso_cache *c, const void *queries, long n, const PipePlan &p) {
@@ -452,7 +882,8 @@ static int pipe_launch(siso_cache *c, const void *queries, long n, const PipePla
         case 1: return launch_cfg<PipeLarge>(c, queries, n, p);
         case 2: return launch_cfg<PipeMid>(c, queries, n, p);
         case 3: return launch_cfg<PipeSmall>(c, queries, n, p);
-        default: return launch_cfg<PipeLarge32>(c, queries, n, p);
+        case 4: return launch_cfg<PipeLarge32>(c, queries, n, p);
+        default: return launch_wide(c, queries, n, p);
     }
 }
 
@@ -509,6 +940,6 @@ int siso_merge_mfma_launch(siso_cache *c, float threshold, int *out_pairs, long 
     }
     hipLaunchKernelGGL((k_lookup_pipe<Cfg, PIPE_PAIRS>), dim3((unsigned)grid), dim3(Cfg::NT), Cfg::LDS_BYTES, c->stream,
                        (const bf16_t *)c->cent, (const bf16_t *)c->cent, c->invn, c->count, c->count, c->dim, (int)tps,
-                       (int)slices, (int)T, qb, 0, (u64 *)nullptr, threshold, out_pairs, cap, c->counters + 1);
+                       (int)slices, (int)T, qb, (u64 *)nullptr, threshold, out_pairs, cap, c->counters + 1);
     return siso_check_hip(c, hipGetLastError(), "pair search kernel");
 }

@@ -746,7 +746,6 @@ extern "C" int siso_set_option(siso_cache *c, const char *name, long value) {
     else if (!strcmp(name, "tiles_per_slice")) c->opt_tiles_per_slice = (int)value;
     else if (!strcmp(name, "merge_config")) c->opt_merge_config = (int)value;
     else if (!strcmp(name, "mfma_qblock")) c->opt_mfma_qblock = (int)value;
-    else if (!strcmp(name, "mfma_nt")) c->opt_mfma_nt = (int)value;
     else return siso_fail(c, SISO_EINVAL, "unknown option %s", name);
     return SISO_OK;
 }

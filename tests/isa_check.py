@@ -35,7 +35,7 @@ def _regs(text: str):
 
 
 def kernels(asm: str):
-    """name -> list of instruction lines"""
+    """name -> list of instruction lines and local labels (`.LBBn_m:`), in program order"""
     out, name = {}, None
     for line in asm.split("\n"):
         m = re.match(r"^(_Z\w+):\s*(;.*)?$", line)
@@ -48,15 +48,20 @@ def kernels(asm: str):
         if re.match(r"^\s+s_endpgm", line):
             name = None
             continue
-        if re.match(r"^\s+[a-z]", line):
+        m = re.match(r"^(\.LBB\w+):", line)
+        if m:
+            out[name].append(m.group(1) + ":")
+        elif re.match(r"^\s+[a-z]", line):
             out[name].append(line.strip())
     return out
 
 
 def inflight_violations(lines):
-    """For every hand-written `ds_read_b128 v[a:b], vN offset:K` find the first later MFMA that reads
-    v[a:b]; any other instruction in between that reads or writes those registers is a violation.
-    Branches are followed in program order only, which is how the reads and their waits are laid out."""
+    """For every hand-written `ds_read_b128 v[a:b], vN offset:K` find the first later MFMA (in program
+    order) that reads v[a:b]; any other instruction in between that reads or writes those registers is
+    a violation.  The same read met again first (the other arm of a branch) ends the search: it is
+    checked on its own.  Program order is how the reads, their waits and their MFMAs are laid out;
+    branches in between only skip parts of it."""
     bad = []
     for i, line in enumerate(lines):
         m = re.match(r"ds_read_b128 v\[(\d+):(\d+)\], v(\d+) offset:\S+ ; hand-scheduled", line)
@@ -65,18 +70,23 @@ def inflight_violations(lines):
         dst = set(range(int(m.group(1)), int(m.group(2)) + 1))
         for j in range(i + 1, min(len(lines), i + 400)):
             other = lines[j]
+            if other.endswith(":") or other == line:
+                if other == line:
+                    break
+                continue
             if other.startswith("v_mfma"):
-                ops = other.split(None, 1)[1].split(", ")
-                srcs = _regs(", ".join(ops[1:3]))
-                if srcs & dst:
+                ops = other.split(";")[0].split(None, 1)[1].split(", ")
+                if _regs(", ".join(ops[1:3])) & dst:
                     break
                 if _regs(ops[0]) & dst or _regs(ops[3]) & dst:
                     bad.append((line, other))
                     break
                 continue
-            if other.startswith(("s_", "ds_read_b128", "global_load_lds")):
+            if other.startswith(("s_", "global_load_lds")):
+                continue
+            if other.startswith("ds_read_b128"):
                 # other reads may reuse the address register, never the data registers
-                if other.startswith("ds_read_b128") and _regs(other.split(",")[0]) & dst:
+                if _regs(other.split(",")[0]) & dst:
                     bad.append((line, other))
                     break
                 continue
@@ -84,3 +94,39 @@ def inflight_violations(lines):
                 bad.append((line, other))
                 break
     return bad
+
+
+def agpr_users_not_hand_placed(lines):
+    """In a kernel whose accumulators sit at fixed AGPRs (instructions tagged `hand-placed`), the
+    compiler must not use any AGPR itself: it does not know that they hold live values."""
+    if not any("hand-placed" in l for l in lines):
+        return []
+    return [l for l in lines if re.search(r"\ba\[\d+:\d+\]|\ba\d+\b|accvgpr", l.split(";")[0]) and "hand-placed" not in l]
+
+
+def early_accumulator_reads(lines, distance=12):
+    """A hand-placed v_accvgpr_read of aN must come at least `distance` instructions after the last
+    MFMA that wrote aN (the compiler inserts no wait states for instructions it cannot see into)."""
+    bad = []
+    last_write = {}
+    for i, line in enumerate(lines):
+        if "hand-placed" not in line:
+            continue
+        m = re.match(r"v_mfma\S* a\[(\d+|0x[0-9a-f]+):(\d+|0x[0-9a-f]+)\]", line)
+        if m:
+            for r in range(int(m.group(1), 0), int(m.group(2), 0) + 1):
+                last_write[r] = i
+            continue
+        m = re.match(r"v_accvgpr_read_b32 v\d+, a\[(\d+|0x[0-9a-f]+)\]", line)
+        if m and i - last_write.get(int(m.group(1), 0), -10 ** 9) < distance:
+            bad.append(line)
+    return bad
+
+
+def fixed_fragment_users_not_hand_placed(lines, first=208):
+    """The wide kernel keeps its MFMA operand fragments in v[first .. 255] by hand; the compiler's
+    own instructions must stay below."""
+    if not any(l.startswith("ds_read_b128") and "hand-placed" in l for l in lines):
+        return []
+    return [l for l in lines if "hand-placed" not in l and not l.endswith(":")
+            and any(r >= first for r in _regs(l.split(";")[0]))]

@@ -53,7 +53,7 @@ def test_scalar_path_ragged_shapes(siso, oracle, dtype, dim, K, n):
     check_lookup(out, ora, 0.85, dtype, "scalar ragged")
 
 
-@pytest.mark.parametrize("cfg", [1, 2, 3, 4])
+@pytest.mark.parametrize("cfg", [1, 2, 3, 4, 5])
 @pytest.mark.parametrize("dim,K,n,tps", [(128, 5000, 300, 0), (768, 2049, 513, 3), (192, 700, 1, 1), (1024, 1500, 257, 2)])
 def test_mfma_path_vs_oracle(siso, oracle, cfg, dim, K, n, tps):
     print(f"case: mfma cfg={cfg} dim={dim} K={K} n={n} tiles_per_slice={tps}", flush=True)
@@ -95,7 +95,7 @@ def test_skinny_path_vs_oracle(siso, oracle, dim, K, n):
         cache.lookup(torch.zeros((65, dim), dtype=torch.bfloat16, device=DEV), 0.5)
 
 
-@pytest.mark.parametrize("path,cfg", [(1, 0), (2, 1), (2, 2), (2, 3), (2, 4), (3, 0)])
+@pytest.mark.parametrize("path,cfg", [(1, 0), (2, 1), (2, 2), (2, 3), (2, 4), (2, 5), (3, 0)])
 def test_exact_duplicates_lowest_index_wins(siso, oracle, path, cfg):
     """Bit-identical copies of a centroid at distant rows (other tiles, other slices) tie
     exactly; the lowest index must be returned."""

@@ -15,10 +15,16 @@ def test_no_instruction_touches_a_fragment_register_in_flight(source):
     ks = isa_check.kernels(asm)
     checked = 0
     for name, lines in ks.items():
-        reads = [l for l in lines if l.startswith("ds_read_b128") and "hand-scheduled" in l]
+        reads = [l for l in lines if l.startswith("ds_read_b128") and ("hand-scheduled" in l or "hand-placed" in l)]
         if not reads:
             continue
+        high = isa_check.fixed_fragment_users_not_hand_placed(lines)
+        assert not high, f"{name}: compiler-placed use of the hand-placed fragment registers: {high[:3]}"
         bad = isa_check.inflight_violations(lines)
         assert not bad, f"{name}: {bad[:3]}"
+        stray = isa_check.agpr_users_not_hand_placed(lines)
+        assert not stray, f"{name}: compiler-placed AGPR use next to hand-placed accumulators: {stray[:3]}"
+        early = isa_check.early_accumulator_reads(lines)
+        assert not early, f"{name}: accumulator read too close behind its MFMA: {early[:3]}"
         checked += 1
     assert checked >= 3
