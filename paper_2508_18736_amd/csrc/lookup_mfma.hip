@@ -193,23 +193,40 @@ struct Acc<true, WC, WQ> {
 
 // Block -> (query tile qt, slice s of the centroid tiles).  Workgroups are handed to the 8 XCDs
 // round robin and every XCD has its own L2.  The 32 workgroups that run together on one XCD are
-// made a block of qb query tiles x 32/qb slices, so that a centroid tile fetched into that L2
-// serves qb workgroups and qb query tiles stay resident in it; an XCD owns every eighth group of
-// 32/qb slices and walks through all query tiles for it before moving on.
+// made a unit of qb query tiles x 32/qb slices, so that a centroid tile fetched into that L2
+// serves qb workgroups and qb query tiles stay resident in it.  With many groups of 32/qb slices
+// an XCD owns every eighth group and walks through all blocks of query tiles for it before moving
+// on (the same slices again and again: repeats come from the caches); with at most four groups
+// the XCDs also split the blocks of query tiles among them, so that none stays idle.
 // In the pair search the query tile is a centroid tile too and only the tiles at or right of it
 // are visited (upper triangle); slices are absolute ranges of tiles, so that the workgroups of a
-// block still walk through the same centroid tiles in step.  False = nothing to do for this block.
+// unit still walk through the same centroid tiles in step.  False = nothing to do for this block.
+__host__ __device__ __forceinline__ int pipe_group_split(int groups) { return groups <= 1 ? 1 : groups == 2 ? 2 : 4; }
+static long pipe_grid(long slices, long nqt, int qb) {
+    const long sb = 32 / qb, groups = (slices + sb - 1) / sb, nqb = (nqt + qb - 1) / qb;
+    if (groups > 4) return 8 * ((groups + 7) / 8) * nqb * 32;
+    const long r = 8 / pipe_group_split((int)groups);  // XCDs per group of slices
+    return 8 * ((nqb + r - 1) / r) * 32;
+}
 template <int MODE, int BC>
 __device__ __forceinline__ bool pipe_map_block(long K, int tiles_per_slice, int slices, int nqt, int qb, int &qt, int &s,
                                                int &ct_begin, int &ct_end) {
     const int total_ct = (int)((K + BC - 1) / BC);
-    const int sb = 32 / qb;
+    const int sb = 32 / qb, groups = (slices + sb - 1) / sb, nqb = (nqt + qb - 1) / qb;
     const int xcd = blockIdx.x & 7, local = blockIdx.x >> 3;
-    const int nqb = (nqt + qb - 1) / qb;
-    const int grp = local / (nqb * 32), rem = local % (nqb * 32);
-    const int i = rem & 31;
-    qt = (rem >> 5) * qb + i % qb;
-    s = (grp * 8 + xcd) * sb + i / qb;
+    const int i = local & 31, u = local >> 5;  // place in the unit, number of the unit on this XCD
+    int g, b;
+    if (groups > 4) {
+        g = (u / nqb) * 8 + xcd;
+        b = u % nqb;
+    } else {
+        const int gp = pipe_group_split(groups);
+        g = xcd % gp;
+        b = xcd / gp + (8 / gp) * u;
+    }
+    if (g >= groups || b >= nqb) return false;
+    qt = b * qb + i % qb;
+    s = g * sb + i / qb;
     if (qt >= nqt || s >= slices) return false;
     ct_begin = s * tiles_per_slice;
     ct_end = (ct_begin + tiles_per_slice < total_ct) ? ct_begin + tiles_per_slice : total_ct;
@@ -537,7 +554,7 @@ __global__ __launch_bounds__(WideCfg::NT) __attribute__((amdgpu_waves_per_eu(1, 
     typedef WideCfg Cfg;
     constexpr int WC = Cfg::WC, WQ = Cfg::WQ, NWC = Cfg::NWC, BC = Cfg::BC, BQ = Cfg::BQ, NT = Cfg::NT, NW = Cfg::NW,
                   STAGE = Cfg::STAGE, NLA = Cfg::NLA, NL = Cfg::NL, BK = Cfg::BK, RB = Cfg::RB, KK = Cfg::KK,
-                  SUB = 32 * Cfg::RB, NF = WC + WQ;
+                  SUB = 32 * Cfg::RB;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     float *inv_s = (float *)(smem + 2 * STAGE);  // [2][BC], by tile parity
 
@@ -813,30 +830,31 @@ static bool pipe_plan(const siso_cache *c, long n, int cfg, long want_wgs, PipeP
         if (nqt > 1 && tps > mall_tps) tps = mall_tps;
     }
     if (tps > ct) tps = ct;
+    // query tiles per unit: 8 when there are that many (a centroid tile fetched into an XCD's L2 then
+    // serves 8 workgroups, and 8 query tiles are about what stays resident in a 4 MB L2), fewer when the
+    // batch is small; a unit should be full, so with few centroid tiles the slices get shorter until
+    // there are 32/qb of them, and with very few tiles more query tiles share one
+    int qb = c->opt_mfma_qblock > 0 ? c->opt_mfma_qblock : 8;
+    if (qb != 1 && qb != 2 && qb != 4 && qb != 8 && qb != 16 && qb != 32) return false;
+    if (c->opt_mfma_qblock <= 0) {
+        while (qb > 1 && qb > nqt) qb >>= 1;
+        if (c->opt_tiles_per_slice <= 0 && (ct + tps - 1) / tps < 32 / qb) tps = ct / (32 / qb) > 1 ? ct / (32 / qb) : 1;
+        while (qb < 32 && qb * 2 <= nqt && (ct + tps - 1) / tps < 32 / qb) qb <<= 1;
+    }
     const long slices = (ct + tps - 1) / tps;
     if (nqt * slices > 2147483647L || slices > 1000000) return false;
     p->tiles_per_slice = (int)tps;
     p->slices = (int)slices;
     p->nqt = (int)nqt;
-    // query tiles per XCD block: 8 when there are that many (a centroid tile fetched into an XCD's L2
-    // then serves 8 workgroups, and 8 query tiles are about what stays resident in a 4 MB L2), fewer when the batch is small, more when there are so few slices that
-    // some XCD would otherwise stay idle (an XCD owns every eighth group of 32/qb slices)
-    int qb = c->opt_mfma_qblock > 0 ? c->opt_mfma_qblock : 8;
-    if (qb != 1 && qb != 2 && qb != 4 && qb != 8 && qb != 16 && qb != 32) return false;
-    if (c->opt_mfma_qblock <= 0) {
-        while (qb > 1 && qb > nqt) qb >>= 1;
-        while (qb < 32 && slices * qb < 256) qb <<= 1;
-    }
     p->qb = qb;
-    const long sb = 32 / qb, groups = (slices + sb - 1) / sb, nqb = (nqt + qb - 1) / qb;
-    p->grid = 8 * ((groups + 7) / 8) * nqb * 32;
+    p->grid = pipe_grid(slices, nqt, qb);
     if (p->grid > 2147483647L) return false;
     return true;
 }
 
 static bool mfma_plan(const siso_cache *c, long n, PipePlan *p) {
     int cfg = c->opt_mfma_config;
-    if (cfg == 0) cfg = n <= 64 ? 3 : n <= 128 ? 2 : 1;
+    if (cfg == 0) cfg = n <= 64 ? 3 : n <= 128 ? 2 : 5;
     // about two workgroups per compute unit when there is enough work
     return pipe_plan(c, n, cfg, 512, p);
 }
@@ -927,9 +945,8 @@ int siso_merge_mfma_launch(siso_cache *c, float threshold, int *out_pairs, long 
     const long slices = (T + tps - 1) / tps;
     int qb = 8;
     while (qb > 1 && qb > T) qb >>= 1;
-    while (qb < 32 && slices * qb < 256) qb <<= 1;
-    const long sb = 32 / qb, groups = (slices + sb - 1) / sb, nqb = (T + qb - 1) / qb;
-    const long grid = 8 * ((groups + 7) / 8) * nqb * 32;
+    while (qb < 32 && qb * 2 <= T && slices < 32 / qb) qb <<= 1;
+    const long grid = pipe_grid(slices, T, qb);
     if (grid > 2147483647L) return siso_fail(c, SISO_EINVAL, "pair search: too many tiles");
     static bool attr_done = false;
     if (!attr_done) {

@@ -45,7 +45,7 @@ def kernels(asm: str):
             continue
         if name is None:
             continue
-        if re.match(r"^\s+s_endpgm", line):
+        if re.match(r"^\.Lfunc_end", line):  # (an early exit puts an s_endpgm in the middle of a kernel)
             name = None
             continue
         m = re.match(r"^(\.LBB\w+):", line)
