@@ -63,6 +63,15 @@ def lib() -> C.CDLL:
         L.oracle_export.restype = it
         L.oracle_threads.argtypes = []
         L.oracle_threads.restype = it
+        db = C.c_double
+        L.oracle_t2h.argtypes = [vp, vp, lg, vp, it, vp]
+        L.oracle_t2h.restype = it
+        L.oracle_md1_wait.argtypes = [db, db, db]
+        L.oracle_md1_wait.restype = db
+        L.oracle_pick_threshold.argtypes = [vp, vp, it, db, db, db]
+        L.oracle_pick_threshold.restype = it
+        L.oracle_adjust_threshold.argtypes = [vp, it, it, db, db]
+        L.oracle_adjust_threshold.restype = it
         _lib = L
     return _lib
 
@@ -103,6 +112,25 @@ def lookup_rows(centroids: np.ndarray, queries: np.ndarray, threshold: float, dt
     return idx, sim, hit, second
 
 
+def md1_wait(L: float, lam: float, h: float) -> float:
+    """Expected M/D/1 waiting time at hit ratio ``h`` (inf when the queue is unstable)."""
+    return float(lib().oracle_md1_wait(float(L), float(lam), float(h)))
+
+
+def pick_threshold(thetas, hit_ratio, L: float, lam: float, slo: float) -> int:
+    """Position of the highest threshold with ``slo > W``; -1 if none."""
+    th = np.ascontiguousarray(thetas, dtype=np.float32)
+    hr = np.ascontiguousarray(hit_ratio, dtype=np.float64)
+    assert th.shape == hr.shape and th.ndim == 1
+    return int(lib().oracle_pick_threshold(_ptr(th), _ptr(hr), th.shape[0], float(L), float(lam), float(slo)))
+
+
+def adjust_threshold(thetas, index: int, w_est: float, w_actual: float) -> int:
+    """Position after the 10 % correction."""
+    th = np.ascontiguousarray(thetas, dtype=np.float32)
+    return int(lib().oracle_adjust_threshold(_ptr(th), th.shape[0], int(index), float(w_est), float(w_actual)))
+
+
 class OracleCache:
     """The oracle's cache object: stored centroids, exact means (float64), cluster sizes."""
 
@@ -135,6 +163,16 @@ class OracleCache:
         rc = lib().oracle_load(self._h, _ptr(cents), _ptr(cn), cents.shape[0])
         if rc != 0:
             raise RuntimeError(f"oracle_load failed ({rc})")
+
+    def t2h(self, queries: np.ndarray, thetas) -> np.ndarray:
+        """Hits per threshold (int64) of the sample queries."""
+        qs = _storage(queries, self.dtype, self.dim)
+        th = np.ascontiguousarray(thetas, dtype=np.float32)
+        hits = np.zeros(th.shape[0], np.int64)
+        rc = lib().oracle_t2h(self._h, _ptr(qs), qs.shape[0], _ptr(th), th.shape[0], _ptr(hits))
+        if rc != 0:
+            raise RuntimeError(f"oracle_t2h failed ({rc})")
+        return hits
 
     def lookup(self, queries: np.ndarray, threshold: float, want_second: bool = True):
         qs = _storage(queries, self.dtype, self.dim)

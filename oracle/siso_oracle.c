@@ -413,6 +413,89 @@ int oracle_export(const oracle_cache *c, void *centroids, double *means, int *si
     return 0;
 }
 
+/* ------------------------------------------------------------------------ */
+/* Threshold-to-hit-ratio table and SLO-aware threshold choice (section 4.3,  */
+/* "Adjusting theta_R to meet SLO", equations 1 and 2)                         */
+/* ------------------------------------------------------------------------ */
+
+/*
+ * T2H table: out_hits[j] = number of sample queries that hit the cache at the
+ * retrieval threshold thetas[j], i.e. whose top-1 cosine similarity exceeds it
+ * (strictly; the threshold is a float widened to double, as in oracle_lookup).
+ * The hit ratio h(theta_j) is out_hits[j] / n.
+ */
+int oracle_t2h(const oracle_cache *c, const void *queries, long n, const float *thetas, int m, long *out_hits) {
+    if (!c || n < 0 || m < 0 || (m > 0 && (!thetas || !out_hits)) || (n > 0 && !queries)) return -1;
+    for (int j = 0; j < m; ++j) out_hits[j] = 0;
+    if (n == 0 || m == 0) return 0;
+    int *idx = (int *)malloc((size_t)n * sizeof(int));
+    double *sim = (double *)malloc((size_t)n * sizeof(double));
+    if (!idx || !sim) {
+        free(idx);
+        free(sim);
+        return -4;
+    }
+    int rc = oracle_lookup(c, queries, n, 0.0f, idx, sim, NULL, NULL);
+    if (rc == 0) {
+        for (long i = 0; i < n; ++i)
+            for (int j = 0; j < m; ++j)
+                if (sim[i] > (double)thetas[j]) out_hits[j] += 1; /* NaN and -inf never hit */
+    }
+    free(idx);
+    free(sim);
+    return rc;
+}
+
+/*
+ * Expected waiting time of the LLM system seen as an M/D/1 queue (equation 2):
+ *   E = L (1 - h),  W = E + lambda E^2 / (2 (1 - lambda E)),
+ * L = average serving time of the LLM, lambda = arrival rate, h = hit ratio.
+ * The queue is unstable for lambda E >= 1: W = +infinity.
+ */
+double oracle_md1_wait(double L, double lambda, double h) {
+    const double E = L * (1.0 - h);
+    const double rho = lambda * E;
+    if (!(rho < 1.0)) return INFINITY;
+    return E + lambda * E * E / (2.0 * (1.0 - rho));
+}
+
+/*
+ * The highest threshold of the table whose expected waiting time stays below the
+ * SLO latency S (S > W, strictly).  Returns its position in thetas, or -1 if no
+ * entry satisfies the SLO.  The table may be in any order.
+ */
+int oracle_pick_threshold(const float *thetas, const double *hit_ratio, int m, double L, double lambda, double slo) {
+    int best = -1;
+    for (int j = 0; j < m; ++j) {
+        const double W = oracle_md1_wait(L, lambda, hit_ratio[j]);
+        if (slo > W && (best < 0 || thetas[j] > thetas[best])) best = j;
+    }
+    return best;
+}
+
+/*
+ * Correction when the measured waiting time W' is off the estimate W by more
+ * than 10 %: if W' is longer, move to the next lower threshold of the table
+ * (more hits, less traffic to the LLM); if it is shorter, to the next higher
+ * one.  At the end of the table, or within 10 %, the position stays.
+ */
+int oracle_adjust_threshold(const float *thetas, int m, int index, double w_est, double w_actual) {
+    if (index < 0 || index >= m) return index;
+    int want_lower;
+    if (w_actual > 1.1 * w_est) want_lower = 1;
+    else if (w_actual < 0.9 * w_est) want_lower = 0;
+    else return index;
+    int next = -1;
+    for (int j = 0; j < m; ++j) {
+        if (want_lower) {
+            if (thetas[j] < thetas[index] && (next < 0 || thetas[j] > thetas[next])) next = j;
+        } else {
+            if (thetas[j] > thetas[index] && (next < 0 || thetas[j] < thetas[next])) next = j;
+        }
+    }
+    return next < 0 ? index : next;
+}
+
 /* Number of threads the parallel loops use. */
 int oracle_threads(void) {
 #ifdef _OPENMP

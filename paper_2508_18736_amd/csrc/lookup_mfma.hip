@@ -467,12 +467,15 @@ __global__ __launch_bounds__(Cfg::NT) __attribute__((amdgpu_waves_per_eu(2, 2)))
                     } else if (__ballot(m * wi[B] > threshold) != 0) {
                         // rare: some product of this 32 x 32 block is above the threshold
                         const long icol = q0 + (wq * WQ + B) * 32 + l32;
+                        const long jrow0 = c0 + rb + 4 * h;  // register I holds row jrow0 + 8 * (I / 4) + I % 4
+                        unsigned found = 0;
                         static_for<0, 16>([&](auto ii) {
                             constexpr int I = decltype(ii)::value;
-                            const long jrow = c0 + rb + 8 * (I >> 2) + 4 * h + (I & 3);
                             const float sim = acc.template get<A, B, I>() * w[I >> 2][I & 3] * wi[B];
-                            emit_pair(sim > threshold && icol < jrow, (int)icol, (int)jrow, out_pairs, cap, counter);
+                            if (sim > threshold && icol < jrow0 + 8 * (I >> 2) + (I & 3)) found |= 1u << I;
                         });
+                        emit_pairs(found, (int)icol, [&](int I) { return (int)(jrow0 + 8 * (I >> 2) + (I & 3)); }, out_pairs,
+                                   cap, counter);
                     }
                 });
             });
@@ -770,12 +773,15 @@ __global__ __launch_bounds__(WideCfg::NT) __attribute__((amdgpu_waves_per_eu(1, 
                     } else if (__ballot(m * wi[B] > threshold) != 0) {
                         // rare: some product of this 32 x 32 block is above the threshold
                         const long icol = q0 + (wq * WQ + B) * 32 + l32;
+                        const long jrow0 = c0 + rb + 4 * h;  // register I holds row jrow0 + 8 * (I / 4) + I % 4
+                        unsigned found = 0;
                         static_for<0, 16>([&](auto ii) __attribute__((always_inline)) {
                             constexpr int I = decltype(ii)::value;
-                            const long jrow = c0 + rb + 8 * (I >> 2) + 4 * h + (I & 3);
                             const float sim = acc.template get<A, B, I>() * w[I >> 2][I & 3] * wi[B];
-                            emit_pair(sim > threshold && icol < jrow, (int)icol, (int)jrow, out_pairs, cap, counter);
+                            if (sim > threshold && icol < jrow0 + 8 * (I >> 2) + (I & 3)) found |= 1u << I;
                         });
+                        emit_pairs(found, (int)icol, [&](int I) __attribute__((always_inline)) { return (int)(jrow0 + 8 * (I >> 2) + (I & 3)); },
+                                   out_pairs, cap, counter);
                     }
                 });
             });

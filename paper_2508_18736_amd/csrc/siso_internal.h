@@ -146,6 +146,36 @@ __device__ __forceinline__ void emit_pair(bool pred, int i, int j, int *out, lon
     }
 }
 
+// The same for up to 32 candidates per lane at once: bit I of `mask` says that this lane has the
+// pair (i, j0 + row_of(I)); the wave takes one slot range with a single atomic and every lane
+// writes its pairs behind those of the lanes before it.  Every lane of the wave must call it.
+template <class RowOf>
+__device__ __forceinline__ void emit_pairs(unsigned mask, int i, RowOf row_of, int *out, long cap, u64 *counter) {
+    const int lane = threadIdx.x & 63;
+    const int cnt = __popc(mask);
+    int incl = cnt;  // inclusive prefix sum over the wave
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        const int t = __shfl_up(incl, off);
+        if (lane >= off) incl += t;
+    }
+    const int total = __shfl(incl, 63);
+    if (total == 0) return;
+    u64 base = 0;
+    if (lane == 63) base = atomicAdd(counter, (u64)total);
+    base = __shfl(base, 63);
+    u64 pos = base + (u64)(incl - cnt);
+    while (mask != 0) {
+        const int I = __ffs((int)mask) - 1;
+        mask &= mask - 1;
+        if (pos < (u64)cap) {
+            out[2 * pos] = i;
+            out[2 * pos + 1] = row_of(I);
+        }
+        ++pos;
+    }
+}
+
 // ----------------------------------------------------------------------------
 // host-side plumbing shared by the translation units
 // ----------------------------------------------------------------------------
