@@ -91,7 +91,7 @@ def main():
 
     from paper_2508_18736_amd import siso
     from paper_2508_18736_amd import workloads as W
-    from gpu_util import to_dev
+    from gpu_util import to_dev, to_host
 
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
@@ -194,6 +194,23 @@ def main():
                 "algorithmic_bytes": K * d * 2.0 + nb * d * 2.0 + K * 4.0, "kernel_ms": avg_s * 1e3,
                 "launches": launches}
 
+    t2h_info = None
+    if not args.no_merge and name == "c2_mid":
+        # threshold-to-hit-ratio table over a sample whose similarities spread over the sweep, then the
+        # SLO-aware choice for one made-up operating point (LLM time 1 s, 1.2 requests/s, SLO 1.3 s)
+        sweep = np.round(np.arange(0.98, 0.599, -0.02), 2).astype(np.float32)
+        cents_now, _, _ = cache.export()
+        sample = to_dev(W.spread_sample(to_host(cents_now, wl.dtype), wl.dtype, nb), wl.dtype)
+        cache.t2h(sample, sweep)
+        t1 = time.perf_counter()
+        hits = cache.t2h(sample, sweep)
+        t2h_s = time.perf_counter() - t1
+        ratio = hits / float(nb)
+        pick = siso.pick_threshold(sweep, ratio, 1.0, 1.2, 1.3)
+        t2h_info = {"sample": nb, "thresholds": int(sweep.shape[0]), "ms": t2h_s * 1e3,
+                    "hit_ratio_at_0.98_0.80_0.60": [float(ratio[0]), float(ratio[9]), float(ratio[19])],
+                    "picked_theta": float(sweep[pick]) if pick >= 0 else None}
+
     if not args.no_merge and name == "c2_mid":
         theta_c = 0.90
         cap = 1 << 20
@@ -216,7 +233,7 @@ def main():
                 "warmup": warmup, "ms_per_step": dt / steps * 1e3,
                 "config": {"workload": name, "centroids": K, "dim": d, "batch": nb, "thresholds": thetas,
                            "step": "siso_lookup + siso_update_hits", "hit_rate_last_batch": hit_rate,
-                           "offline_merge": merge_info, "generate_s": round(gen_s, 1)},
+                           "offline_merge": merge_info, "t2h": t2h_info, "generate_s": round(gen_s, 1)},
                 "roofline": roof})
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl, nb, args.cpu_seconds)

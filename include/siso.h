@@ -172,6 +172,43 @@ int siso_merge_apply(siso_cache *c, const int *pairs, long n_pairs, int *out_sur
 int siso_export(siso_cache *c, void *centroids, float *means, int *counts);
 
 /*
+ * Threshold-to-hit-ratio (T2H) table (section 4.3, "Adjusting theta_R to meet
+ * SLO"): test lookups of a sample of queries, counted against a sweep of
+ * retrieval thresholds (the paper sweeps 0.98 down to 0.6).
+ *   queries:  device pointer, [n][dim] sample queries.
+ *   thetas:   HOST pointer, m thresholds in any order, m <= 1024.
+ *   out_hits: HOST pointer, m counts: out_hits[j] = number of sample queries
+ *             whose top-1 similarity exceeds thetas[j] (strictly, compared as
+ *             floats like the hit test of siso_lookup); h(theta_j) = out_hits[j] / n.
+ * One lookup serves all thresholds (the similarity does not depend on them).
+ * Allocates temporary device memory.  Synchronises.
+ */
+int siso_t2h(siso_cache *c, const void *queries, long n, const float *thetas, int m, long *out_hits);
+
+/*
+ * Host-side arithmetic of the same section; no GPU work, no cache needed.
+ *
+ * siso_md1_wait: expected waiting time W of the LLM system modelled as an M/D/1
+ * queue (equation 2): E = llm_time * (1 - hit_ratio),
+ * W = E + arrival_rate * E^2 / (2 * (1 - arrival_rate * E)); +infinity when the
+ * queue is unstable (arrival_rate * E >= 1).
+ *
+ * siso_pick_threshold: the highest threshold of a T2H table (thetas[j],
+ * hit_ratio[j], j < m, any order, host pointers) whose W stays below the SLO
+ * latency (slo > W, strictly).  *out_index = its position, -1 if no entry meets
+ * the SLO.  Returns SISO_OK or SISO_EINVAL.
+ *
+ * siso_adjust_threshold: the correction applied when the measured waiting time
+ * is more than 10 % off the estimate: longer -> the next lower threshold of the
+ * table, shorter -> the next higher one; otherwise, or at the end of the table,
+ * or for an index outside [0, m), the position is returned unchanged.
+ */
+double siso_md1_wait(double llm_time, double arrival_rate, double hit_ratio);
+int siso_pick_threshold(const float *thetas, const double *hit_ratio, int m, double llm_time, double arrival_rate,
+                        double slo, int *out_index);
+int siso_adjust_threshold(const float *thetas, int m, int index, double wait_estimated, double wait_measured);
+
+/*
  * Kernel timing for benchmarks.  While enabled (on = N > 0), every N-th
  * siso_lookup / siso_merge brackets its dominant kernel (the similarity kernel,
  * without the finalize kernel) with a pair of HIP events on the cache's stream

@@ -1,6 +1,7 @@
 // C ABI of the centroid cache (include/siso.h): state management, the kernels
 // that are not matrix-shaped (row norms, finalize, update, group merge) and the
 // LDS-tiled fp32 kernels that serve any element type and dimension.
+#include <math.h>
 #include <stdarg.h>
 #include <stdio.h>
 #include <stdlib.h>
@@ -1035,4 +1036,104 @@ extern "C" int siso_export(siso_cache *c, void *centroids, float *means, int *co
     if (counts)
         HIP_TRY(c, hipMemcpyAsync(counts, c->size, (size_t)c->count * sizeof(int), hipMemcpyDeviceToDevice, c->stream));
     return SISO_OK;
+}
+
+// ----------------------------------------------------------------------------
+// Threshold-to-hit-ratio table and the SLO-aware choice of the retrieval threshold
+// (section 4.3, "Adjusting theta_R to meet SLO")
+// ----------------------------------------------------------------------------
+#define SISO_T2H_MAX 1024
+
+// hits[j] += number of queries of this block whose similarity exceeds thetas[j]
+__global__ void k_t2h_count(const float *__restrict__ sim, long n, const float *__restrict__ thetas, int m,
+                            u64 *__restrict__ hits) {
+    __shared__ unsigned local[SISO_T2H_MAX];
+    for (int j = threadIdx.x; j < m; j += blockDim.x) local[j] = 0;
+    __syncthreads();
+    const long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
+    const float s = i < n ? sim[i] : __uint_as_float(0x7FC00000u);  // NaN hits nothing
+    for (int j = 0; j < m; ++j) {
+        const u64 above = __ballot(s > thetas[j]);
+        if ((threadIdx.x & 63) == 0 && above != 0) atomicAdd(&local[j], (unsigned)__popcll(above));
+    }
+    __syncthreads();
+    for (int j = threadIdx.x; j < m; j += blockDim.x)
+        if (local[j] != 0) atomicAdd(&hits[j], (u64)local[j]);
+}
+
+extern "C" int siso_t2h(siso_cache *c, const void *queries, long n, const float *thetas, int m, long *out_hits) {
+    if (!c) return SISO_EINVAL;
+    if (n < 0 || m < 0 || m > SISO_T2H_MAX || (m > 0 && (!thetas || !out_hits)) || (n > 0 && !queries))
+        return siso_fail(c, SISO_EINVAL, "siso_t2h: bad arguments (at most %d thresholds)", SISO_T2H_MAX);
+    for (int j = 0; j < m; ++j) out_hits[j] = 0;
+    if (n == 0 || m == 0) return SISO_OK;
+    // one lookup of the sample, then every threshold is a comparison against the same similarities
+    char *ws = nullptr;
+    const size_t off_sim = (size_t)n * sizeof(int), off_th = off_sim + (size_t)n * sizeof(float);
+    const size_t off_hits = (off_th + (size_t)m * sizeof(float) + 7) & ~(size_t)7;
+    if (hipMalloc((void **)&ws, off_hits + (size_t)m * sizeof(u64)) != hipSuccess) {
+        (void)hipGetLastError();
+        return siso_fail(c, SISO_ENOMEM, "siso_t2h: workspace for %ld queries", n);
+    }
+    int *idx = (int *)ws;
+    float *sim = (float *)(ws + off_sim), *d_th = (float *)(ws + off_th);
+    u64 *d_hits = (u64 *)(ws + off_hits);
+    int rc = SISO_OK;
+    hipError_t e = hipMemcpyAsync(d_th, thetas, (size_t)m * sizeof(float), hipMemcpyHostToDevice, c->stream);
+    if (e == hipSuccess) e = hipMemsetAsync(d_hits, 0, (size_t)m * sizeof(u64), c->stream);
+    if (e != hipSuccess) rc = siso_check_hip(c, e, "siso_t2h: set-up");
+    if (rc == SISO_OK) rc = siso_lookup(c, queries, n, 0.f, idx, sim, nullptr);
+    u64 host_hits[SISO_T2H_MAX];
+    if (rc == SISO_OK) {
+        hipLaunchKernelGGL(k_t2h_count, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, c->stream, sim, n, d_th, m, d_hits);
+        e = hipGetLastError();
+        if (e == hipSuccess)
+            e = hipMemcpyAsync(host_hits, d_hits, (size_t)m * sizeof(u64), hipMemcpyDeviceToHost, c->stream);
+        if (e != hipSuccess) rc = siso_check_hip(c, e, "siso_t2h: count");
+    }
+    e = hipStreamSynchronize(c->stream);
+    if (rc == SISO_OK && e != hipSuccess) rc = siso_check_hip(c, e, "siso_t2h: synchronize");
+    (void)hipFree(ws);
+    if (rc == SISO_OK)
+        for (int j = 0; j < m; ++j) out_hits[j] = (long)host_hits[j];
+    return rc;
+}
+
+// Equation 2.  rho = lambda E is the load of the single server; the mean time in an M/D/1 system
+// is the serving time plus rho E / (2 (1 - rho)) of queueing.
+extern "C" double siso_md1_wait(double llm_time, double arrival_rate, double hit_ratio) {
+    const double serve = llm_time * (1.0 - hit_ratio);
+    const double load = arrival_rate * serve;
+    if (load >= 1.0 || load != load) return HUGE_VAL;
+    return serve + load * serve / (2.0 * (1.0 - load));
+}
+
+extern "C" int siso_pick_threshold(const float *thetas, const double *hit_ratio, int m, double llm_time,
+                                   double arrival_rate, double slo, int *out_index) {
+    if (!out_index) return SISO_EINVAL;
+    *out_index = -1;
+    if (m < 0 || (m > 0 && (!thetas || !hit_ratio))) return SISO_EINVAL;
+    float chosen_theta = 0.f;
+    for (int j = 0; j < m; ++j) {
+        if (!(siso_md1_wait(llm_time, arrival_rate, hit_ratio[j]) < slo)) continue;
+        if (*out_index < 0 || thetas[j] > chosen_theta) {
+            *out_index = j;
+            chosen_theta = thetas[j];
+        }
+    }
+    return SISO_OK;
+}
+
+extern "C" int siso_adjust_threshold(const float *thetas, int m, int index, double wait_estimated, double wait_measured) {
+    if (!thetas || index < 0 || index >= m) return index;
+    const bool longer = wait_measured > 1.1 * wait_estimated, shorter = wait_measured < 0.9 * wait_estimated;
+    if (!longer && !shorter) return index;
+    // the neighbour in the order of the thresholds: the largest one below, or the smallest one above
+    int neighbour = index;
+    for (int j = 0; j < m; ++j) {
+        const bool right_side = longer ? thetas[j] < thetas[index] : thetas[j] > thetas[index];
+        if (!right_side) continue;
+        if (neighbour == index || (longer ? thetas[j] > thetas[neighbour] : thetas[j] < thetas[neighbour])) neighbour = j;
+    }
+    return neighbour;
 }

@@ -48,11 +48,41 @@ SYMBOLS = {
     "siso_profile_enable": ([_vp, _it], _it),
     "siso_profile_read": ([_vp, C.POINTER(C.c_double), C.POINTER(C.c_long)], _it),
     "siso_last_error": ([_vp], C.c_char_p),
+    "siso_t2h": ([_vp, _vp, _lg, _vp, _it, _vp], _it),
+    "siso_md1_wait": ([C.c_double, C.c_double, C.c_double], C.c_double),
+    "siso_pick_threshold": ([_vp, _vp, _it, C.c_double, C.c_double, C.c_double, C.POINTER(_it)], _it),
+    "siso_adjust_threshold": ([_vp, _it, _it, C.c_double, C.c_double], _it),
 }
 for _name, (_args, _res) in SYMBOLS.items():
     _fn = getattr(_lib, _name)
     _fn.argtypes = _args
     _fn.restype = _res
+
+
+def md1_wait(llm_time: float, arrival_rate: float, hit_ratio: float) -> float:
+    return float(_lib.siso_md1_wait(float(llm_time), float(arrival_rate), float(hit_ratio)))
+
+
+def pick_threshold(thetas, hit_ratio, llm_time: float, arrival_rate: float, slo: float) -> int:
+    """Position of the highest threshold of the table that meets the SLO, -1 if none."""
+    import numpy as np
+    th = np.ascontiguousarray(thetas, dtype=np.float32)
+    hr = np.ascontiguousarray(hit_ratio, dtype=np.float64)
+    if th.ndim != 1 or th.shape != hr.shape:
+        raise ValueError("thetas and hit_ratio: one-dimensional arrays of the same length")
+    out = _it(-1)
+    rc = _lib.siso_pick_threshold(th.ctypes.data_as(_vp), hr.ctypes.data_as(_vp), th.shape[0], float(llm_time),
+                                  float(arrival_rate), float(slo), C.byref(out))
+    if rc != OK:
+        raise SisoError(rc, "siso_pick_threshold failed")
+    return int(out.value)
+
+
+def adjust_threshold(thetas, index: int, wait_estimated: float, wait_measured: float) -> int:
+    import numpy as np
+    th = np.ascontiguousarray(thetas, dtype=np.float32)
+    return int(_lib.siso_adjust_threshold(th.ctypes.data_as(_vp), th.shape[0], int(index), float(wait_estimated),
+                                          float(wait_measured)))
 
 
 class SisoError(RuntimeError):
@@ -176,6 +206,16 @@ class SisoCache:
         surv = torch.empty(self.count, dtype=torch.int32, device=self.device)
         self._check(_lib.siso_merge_apply(self._h, _ptr(pr), pr.shape[0], _ptr(surv)))
         return surv
+
+    def t2h(self, queries: torch.Tensor, thetas):
+        """Hits per threshold (numpy int64) of the sample queries; thresholds are host values."""
+        import numpy as np
+        q = self._rows(queries, "queries")
+        th = np.ascontiguousarray(thetas, dtype=np.float32)
+        hits = np.zeros(th.shape[0], dtype=np.int64)
+        self._check(_lib.siso_t2h(self._h, _ptr(q), q.shape[0], th.ctypes.data_as(_vp), th.shape[0],
+                                  hits.ctypes.data_as(_vp)))
+        return hits
 
     def profile_enable(self, on) -> None:
         """0/False = off; N = bracket the dominant kernel of every N-th call with events."""

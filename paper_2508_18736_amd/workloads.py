@@ -252,6 +252,28 @@ def c2_mid(n_clusters: int = 4096, per_cluster: int = 16, n_queries: int = 4096,
                     meta={"sigma": sigma, "sigma_mode": sigma_mode})
 
 
+def spread_sample(centroids: np.ndarray, dtype: str, n_queries: int, sigma_lo: float = 0.1,
+                  sigma_hi: float = 1.3, seed: int = BASE_SEED + 6) -> np.ndarray:
+    """Sample queries for a threshold-to-hit-ratio table: query i is a jittered copy of a random
+    stored centroid with its own noise length, drawn uniformly from ``[sigma_lo, sigma_hi]`` (the
+    length of the whole noise vector), so that the top-1 similarities spread over roughly
+    ``1/sqrt(1 + sigma^2)`` = 0.61 .. 0.995 and the hit ratio falls gradually as the threshold
+    rises, like the curves measured on text embeddings.  Returns rows in the storage type."""
+    K, dim = centroids.shape
+    r = _rng(seed, _STREAM_POP)
+    targets = r.integers(0, K, size=n_queries).astype(np.int64)
+    lengths = r.uniform(sigma_lo, sigma_hi, size=n_queries).astype(np.float32)
+    cf = storage_to_f32(centroids, dtype)
+    out = np.empty((n_queries, dim), dtype=np.float32 if dtype == "f32" else np.uint16)
+    for c in range((n_queries + _CHUNK_ROWS - 1) // _CHUNK_ROWS):
+        lo, hi = c * _CHUNK_ROWS, min(n_queries, (c + 1) * _CHUNK_ROWS)
+        g = _rng(seed, _STREAM_QUERIES, c).standard_normal((hi - lo, dim), dtype=np.float32)
+        g *= (lengths[lo:hi] / np.sqrt(np.float32(dim)))[:, None]
+        g += cf[targets[lo:hi]]
+        out[lo:hi] = to_storage(_unit_rows(g), dtype)
+    return out
+
+
 def _popular_targets(r: np.random.Generator, p: np.ndarray, rank_to_cluster: np.ndarray,
                      order: np.ndarray, starts: np.ndarray, n: int) -> np.ndarray:
     ranks = r.choice(len(p), size=n, p=p)

@@ -13,7 +13,7 @@ LIB = os.path.join(ROOT, "paper_2508_18736_amd", "libsiso.so")
 def declared_functions():
     text = open(HEADER).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(siso_[a-z_]+)\s*\(", text)))
+    return sorted(set(re.findall(r"\b(siso_[a-z0-9_]+)\s*\(", text)))
 
 
 def test_header_declares_the_four_named_calls():
