@@ -63,6 +63,10 @@ def lib() -> C.CDLL:
         L.oracle_export.restype = it
         L.oracle_threads.argtypes = []
         L.oracle_threads.restype = it
+        L.oracle_export_meta.argtypes = [vp, vp, vp]
+        L.oracle_export_meta.restype = it
+        L.oracle_refresh.argtypes = [vp, vp, vp, lg, fl, lg, vp, vp]
+        L.oracle_refresh.restype = it
         db = C.c_double
         L.oracle_t2h.argtypes = [vp, vp, lg, vp, it, vp]
         L.oracle_t2h.restype = it
@@ -163,6 +167,29 @@ class OracleCache:
         rc = lib().oracle_load(self._h, _ptr(cents), _ptr(cn), cents.shape[0])
         if rc != 0:
             raise RuntimeError(f"oracle_load failed ({rc})")
+
+    def export_meta(self):
+        """``(cluster_size float32, access_count uint32)`` of the live rows; 0xFFFFFFFF = infinity."""
+        k = self.count
+        loc = np.empty(k, np.float32)
+        acc = np.empty(k, np.uint32)
+        rc = lib().oracle_export_meta(self._h, _ptr(loc), _ptr(acc))
+        if rc != 0:
+            raise RuntimeError(f"oracle_export_meta failed ({rc})")
+        return loc, acc
+
+    def refresh(self, repo: np.ndarray, repo_size, theta_c: float, max_centroids: int):
+        """Algorithm 1.  Returns ``(merged, added, evicted, min_margin)``."""
+        rows = _storage(repo, self.dtype, self.dim)
+        sizes = np.ascontiguousarray(repo_size, dtype=np.float32)
+        assert sizes.shape == (rows.shape[0],)
+        stats = np.zeros(3, np.int64)
+        margin = C.c_double(0.0)
+        rc = lib().oracle_refresh(self._h, _ptr(rows), _ptr(sizes), rows.shape[0], float(theta_c),
+                                  int(max_centroids), _ptr(stats), C.byref(margin))
+        if rc != 0:
+            raise RuntimeError(f"oracle_refresh failed ({rc})")
+        return int(stats[0]), int(stats[1]), int(stats[2]), float(margin.value)
 
     def t2h(self, queries: np.ndarray, thetas) -> np.ndarray:
         """Hits per threshold (int64) of the sample queries."""

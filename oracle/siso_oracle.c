@@ -61,8 +61,12 @@ typedef struct oracle_cache {
     long count;
     void *cent;     /* [capacity][dim] storage type, as loaded / as last rounded */
     double *mean;   /* [capacity][dim] mean of the unit-length members           */
-    int *size;      /* [capacity] number of members (cluster_size)               */
+    int *size;      /* [capacity] number of members: the weight of the mean      */
+    float *locality;    /* [capacity] cluster_size of Algorithm 1 (decays by 1.1 per refresh: a float) */
+    uint32_t *access;   /* [capacity] access_count of Algorithm 1; ORACLE_ACCESS_INF = infinity        */
 } oracle_cache;
+
+#define ORACLE_ACCESS_INF 0xFFFFFFFFu
 
 /* ------------------------------------------------------------------ storage */
 static size_t elem_size(int dtype) { return dtype == ORACLE_F32 ? 4 : 2; }
@@ -191,8 +195,10 @@ int oracle_create(int dim, long capacity, int dtype, oracle_cache **out) {
     c->cent = calloc((size_t)capacity * dim, elem_size(dtype));
     c->mean = (double *)calloc((size_t)capacity * dim, sizeof(double));
     c->size = (int *)calloc((size_t)capacity, sizeof(int));
-    if (!c->cent || !c->mean || !c->size) {
-        free(c->cent); free(c->mean); free(c->size); free(c);
+    c->locality = (float *)calloc((size_t)capacity, sizeof(float));
+    c->access = (uint32_t *)calloc((size_t)capacity, sizeof(uint32_t));
+    if (!c->cent || !c->mean || !c->size || !c->locality || !c->access) {
+        free(c->cent); free(c->mean); free(c->size); free(c->locality); free(c->access); free(c);
         return -2;
     }
     *out = c;
@@ -201,7 +207,7 @@ int oracle_create(int dim, long capacity, int dtype, oracle_cache **out) {
 
 void oracle_destroy(oracle_cache *c) {
     if (!c) return;
-    free(c->cent); free(c->mean); free(c->size); free(c);
+    free(c->cent); free(c->mean); free(c->size); free(c->locality); free(c->access); free(c);
 }
 
 long oracle_count(const oracle_cache *c) { return c ? c->count : -1; }
@@ -224,16 +230,27 @@ int oracle_load(oracle_cache *c, const void *centroids, const int *counts, long 
             c->mean[(size_t)j * c->dim + t] = (nrm > 0.0 && isfinite(nrm)) ? v / nrm : 0.0;
         }
         c->size[j] = counts ? counts[j] : 1;
+        c->locality[j] = (float)c->size[j];
+        c->access[j] = 0;
     }
     c->count = k;
     return 0;
 }
 
-int oracle_lookup(const oracle_cache *c, const void *queries, long n, float threshold, int *out_idx,
+/*
+ * Lookup in the cache.  Every hit is a reference to its centroid: access_count of
+ * that centroid goes up by one (section 4.2, "Merge step"); infinity stays infinity.
+ */
+int oracle_lookup(oracle_cache *c, const void *queries, long n, float threshold, int *out_idx,
                   double *out_sim, unsigned char *out_hit, double *out_second) {
     if (!c) return -1;
-    return oracle_lookup_rows(c->cent, c->count, c->dim, c->dtype, queries, n, threshold, out_idx, out_sim,
-                              out_hit, out_second);
+    int rc = oracle_lookup_rows(c->cent, c->count, c->dim, c->dtype, queries, n, threshold, out_idx, out_sim,
+                                out_hit, out_second);
+    if (rc != 0) return rc;
+    for (long i = 0; i < n; ++i)
+        if (out_idx[i] >= 0 && out_sim[i] > (double)threshold && c->access[out_idx[i]] != ORACLE_ACCESS_INF)
+            c->access[out_idx[i]] += 1;
+    return 0;
 }
 
 /*
@@ -366,14 +383,20 @@ int oracle_merge_apply(oracle_cache *c, const int *pairs, long n_pairs, int *out
         if (uf_find(parent, r) != r) continue;
         long members = 0;
         double wsum = 0.0;
+        float loc = 0.0f;      /* cluster sizes add up, in ascending order of the members */
+        uint64_t refs = 0;     /* so do the access counts, saturating at infinity          */
         for (int t = 0; t < d; ++t) acc[t] = 0.0;
         for (long i = r; i < k; ++i) {
             if (uf_find(parent, i) != r) continue;
             ++members;
+            loc = loc + c->locality[i];
+            refs += c->access[i];
             wsum += (double)c->size[i];
             for (int t = 0; t < d; ++t) acc[t] += (double)c->size[i] * c->mean[(size_t)i * d + t];
         }
         if (members == 1) continue;
+        c->locality[r] = loc;
+        c->access[r] = refs >= ORACLE_ACCESS_INF ? ORACLE_ACCESS_INF : (uint32_t)refs;
         double sq = 0.0;
         for (int t = 0; t < d; ++t) {
             c->mean[(size_t)r * d + t] = acc[t] / wsum;
@@ -393,6 +416,8 @@ int oracle_merge_apply(oracle_cache *c, const int *pairs, long n_pairs, int *out
             memmove((char *)c->cent + (size_t)live * rowb, (char *)c->cent + (size_t)i * rowb, rowb);
             memmove(c->mean + (size_t)live * d, c->mean + (size_t)i * d, sizeof(double) * d);
             c->size[live] = c->size[i];
+            c->locality[live] = c->locality[i];
+            c->access[live] = c->access[i];
         }
         ++live;
     }
@@ -410,6 +435,138 @@ int oracle_export(const oracle_cache *c, void *centroids, double *means, int *si
     if (centroids) memcpy(centroids, c->cent, cells * elem_size(c->dtype));
     if (means) memcpy(means, c->mean, cells * sizeof(double));
     if (sizes) memcpy(sizes, c->size, (size_t)c->count * sizeof(int));
+    return 0;
+}
+
+/* Copy out cluster_size (float) and access_count (infinity = 0xFFFFFFFF) of the live rows. */
+int oracle_export_meta(const oracle_cache *c, float *locality, uint32_t *access) {
+    if (!c) return -1;
+    if (locality) memcpy(locality, c->locality, (size_t)c->count * sizeof(float));
+    if (access) memcpy(access, c->access, (size_t)c->count * sizeof(uint32_t));
+    return 0;
+}
+
+/* ------------------------------------------------------------------------ */
+/* Cache replacement: Algorithm 1 (SISO-CacheManager), section 4.2            */
+/* ------------------------------------------------------------------------ */
+
+/*
+ * Refresh the cache from r repository centroids (rows `repo`, cluster sizes
+ * `repo_size`), clustering threshold theta_c, at most max_centroids survivors.
+ *
+ * MergeCentroids: C_new starts as the cache; the repository centroids are taken
+ * in order; each looks for its closest centroid in C_new as it stands then (lowest
+ * index among equals; the cache rows come first, added rows follow in the order
+ * they were added).  If the cosine exceeds theta_c its cluster size is added to
+ * that centroid's; otherwise it joins C_new with access_count = infinity.
+ * FilteringCentroids: while C_new has more than max_centroids rows, the row with
+ * the smallest (cluster_size, access_count) goes, the first such row in the order
+ * of C_new; then every cluster size is divided by 1.1 and every access count reset.
+ * UpdateCentroids: C_new becomes the cache (survivors keep their order).
+ *
+ * cluster_size is single precision here as on the GPU (additions in the order of
+ * the repository, one division by 1.1f), because it decides who is evicted.
+ * A row that joins starts a mean at its own direction with weight
+ * max(1, round(repo_size)).  stats (nullable) = {merged, added, evicted};
+ * min_margin (nullable) = the smallest |cosine - theta_c| met in a decision.
+ */
+int oracle_refresh(oracle_cache *c, const void *repo, const float *repo_size, long r, float theta_c,
+                   long max_centroids, long *stats, double *min_margin) {
+    if (!c || r < 0 || max_centroids < 1 || max_centroids > c->capacity || (r > 0 && (!repo || !repo_size))) return -1;
+    const int d = c->dim, dt = c->dtype;
+    for (long i = 0; i < r; ++i)
+        if (!row_finite(repo, dt, i, d) || !(repo_size[i] > 0.0f) || !isfinite(repo_size[i])) return -1;
+    const long k0 = c->count, cap = k0 + r;
+    const size_t rowb = (size_t)d * elem_size(dt);
+    /* C_new, with room for every repository row */
+    char *cent = (char *)malloc((size_t)(cap > 0 ? cap : 1) * rowb);
+    double *mean = (double *)malloc((size_t)(cap > 0 ? cap : 1) * d * sizeof(double));
+    double *norm = (double *)malloc((size_t)(cap > 0 ? cap : 1) * sizeof(double));
+    int *size = (int *)malloc((size_t)(cap > 0 ? cap : 1) * sizeof(int));
+    float *loc = (float *)malloc((size_t)(cap > 0 ? cap : 1) * sizeof(float));
+    uint32_t *acc = (uint32_t *)malloc((size_t)(cap > 0 ? cap : 1) * sizeof(uint32_t));
+    if (!cent || !mean || !norm || !size || !loc || !acc) {
+        free(cent); free(mean); free(norm); free(size); free(loc); free(acc);
+        return -2;
+    }
+    memcpy(cent, c->cent, (size_t)k0 * rowb);
+    memcpy(mean, c->mean, (size_t)k0 * d * sizeof(double));
+    memcpy(size, c->size, (size_t)k0 * sizeof(int));
+    memcpy(loc, c->locality, (size_t)k0 * sizeof(float));
+    memcpy(acc, c->access, (size_t)k0 * sizeof(uint32_t));
+    for (long j = 0; j < k0; ++j) norm[j] = row_norm(cent, dt, j, d);
+    long cnt = k0, merged = 0, added = 0, evicted = 0;
+    double margin = INFINITY;
+
+    /* merge step */
+    for (long i = 0; i < r; ++i) {
+        const double ni = row_norm(repo, dt, i, d);
+        long best = -1;
+        double bsim = -INFINITY;
+#ifdef _OPENMP
+#pragma omp parallel
+#endif
+        {
+            long lbest = -1;
+            double lsim = -INFINITY;
+#ifdef _OPENMP
+#pragma omp for nowait schedule(static)
+#endif
+            for (long j = 0; j < cnt; ++j) {
+                double sj = cosine(repo, i, ni, cent, j, norm[j], dt, d);
+                if (sj > lsim) { lsim = sj; lbest = j; }   /* ascending j: the lowest index keeps a tie */
+            }
+#ifdef _OPENMP
+#pragma omp critical
+#endif
+            if (lbest >= 0 && (lsim > bsim || (lsim == bsim && lbest < best))) { bsim = lsim; best = lbest; }
+        }
+        if (best >= 0 && fabs(bsim - (double)theta_c) < margin) margin = fabs(bsim - (double)theta_c);
+        if (best >= 0 && bsim > (double)theta_c) {
+            loc[best] = loc[best] + repo_size[i];
+            ++merged;
+        } else {
+            memcpy(cent + (size_t)cnt * rowb, (const char *)repo + (size_t)i * rowb, rowb);
+            norm[cnt] = ni;
+            for (int t = 0; t < d; ++t)
+                mean[(size_t)cnt * d + t] = ni > 0.0 ? widen(repo, dt, (size_t)i * d + t) / ni : 0.0;
+            long w = lrintf(repo_size[i]);
+            size[cnt] = w < 1 ? 1 : (w > 2147483647L ? 2147483647 : (int)w);
+            loc[cnt] = repo_size[i];
+            acc[cnt] = ORACLE_ACCESS_INF;
+            ++cnt;
+            ++added;
+        }
+    }
+
+    /* filtering step */
+    while (cnt > max_centroids) {
+        long victim = 0;
+        for (long j = 1; j < cnt; ++j)
+            if (loc[j] < loc[victim] || (loc[j] == loc[victim] && acc[j] < acc[victim])) victim = j;
+        memmove(cent + (size_t)victim * rowb, cent + (size_t)(victim + 1) * rowb, (size_t)(cnt - victim - 1) * rowb);
+        memmove(mean + (size_t)victim * d, mean + (size_t)(victim + 1) * d, (size_t)(cnt - victim - 1) * d * sizeof(double));
+        memmove(size + victim, size + victim + 1, (size_t)(cnt - victim - 1) * sizeof(int));
+        memmove(loc + victim, loc + victim + 1, (size_t)(cnt - victim - 1) * sizeof(float));
+        memmove(acc + victim, acc + victim + 1, (size_t)(cnt - victim - 1) * sizeof(uint32_t));
+        --cnt;
+        ++evicted;
+    }
+    for (long j = 0; j < cnt; ++j) {
+        loc[j] = loc[j] / 1.1f;
+        acc[j] = 0;
+    }
+
+    /* update step */
+    memcpy(c->cent, cent, (size_t)cnt * rowb);
+    memcpy(c->mean, mean, (size_t)cnt * d * sizeof(double));
+    memcpy(c->size, size, (size_t)cnt * sizeof(int));
+    memcpy(c->locality, loc, (size_t)cnt * sizeof(float));
+    memcpy(c->access, acc, (size_t)cnt * sizeof(uint32_t));
+    c->count = cnt;
+    if (stats) { stats[0] = merged; stats[1] = added; stats[2] = evicted; }
+    if (min_margin) *min_margin = margin;
+    free(cent); free(mean); free(norm); free(size); free(loc); free(acc);
     return 0;
 }
 
@@ -435,7 +592,8 @@ int oracle_t2h(const oracle_cache *c, const void *queries, long n, const float *
         free(sim);
         return -4;
     }
-    int rc = oracle_lookup(c, queries, n, 0.0f, idx, sim, NULL, NULL);
+    /* test lookups: they are no references to the centroids, access_count stays */
+    int rc = oracle_lookup_rows(c->cent, c->count, c->dim, c->dtype, queries, n, 0.0f, idx, sim, NULL, NULL);
     if (rc == 0) {
         for (long i = 0; i < n; ++i)
             for (int j = 0; j < m; ++j)
