@@ -172,6 +172,47 @@ int siso_merge_apply(siso_cache *c, const int *pairs, long n_pairs, int *out_sur
 int siso_export(siso_cache *c, void *centroids, float *means, int *counts);
 
 /*
+ * Cache replacement: Algorithm 1 (SISO-CacheManager), section 4.2.
+ *
+ * Besides its vector every centroid carries the two numbers of that algorithm:
+ * cluster_size (a float: siso_load sets it to counts[k] or 1, a refresh adds the
+ * cluster sizes of merged repository centroids and then divides by 1.1) and
+ * access_count (the number of hits siso_lookup has reported for it since the
+ * last refresh; 0xFFFFFFFF stands for infinity, the value a centroid has while
+ * it is new).  siso_merge_apply adds both up per group.
+ *
+ *   repo:          device pointer, [r][dim] repository centroids, element type
+ *                  of the cache, 16-byte aligned, every value finite.
+ *   repo_size:     device pointer, r cluster sizes (> 0).
+ *   theta_c:       clustering threshold.
+ *   max_centroids: M, the number of centroids the cache may hold afterwards,
+ *                  1 <= M <= capacity.
+ *   out_stats:     HOST pointer to 3 longs or NULL: merged, added, evicted.
+ * MergeCentroids: C_new starts as the cache; the repository centroids are taken
+ * in order; each looks for its closest centroid in C_new as it stands then
+ * (lowest index among equals; cached centroids first, then the added ones in
+ * the order they were added); if the cosine exceeds theta_c (strictly) its
+ * cluster size is added to that centroid's, otherwise it joins C_new, stored as
+ * given, with access_count = infinity.  FilteringCentroids: while C_new has more
+ * than M rows the row with the smallest (cluster_size, access_count) goes, the
+ * first such row in the order of C_new; then every cluster_size is divided by
+ * 1.1 (in single precision) and every access_count reset to 0.  UpdateCentroids:
+ * C_new becomes the cache, survivors keep their order; a lookup enqueued before
+ * the call sees the old set, one enqueued after it the new one.
+ * The similarity work (repository against cache, repository against itself)
+ * runs on the GPU; the chain of decisions and the choice of the survivors are
+ * bookkeeping on the host.  Nothing changes if an error is returned before the
+ * update step (bad arguments, a non-finite row, a cluster size <= 0).
+ * Allocates temporary device memory.  Synchronises.
+ *
+ * siso_export_meta: copy out cluster_size [count] floats and access_count
+ * [count] unsigned ints (device pointers, either may be NULL).  Asynchronous.
+ */
+int siso_refresh(siso_cache *c, const void *repo, const float *repo_size, long r, float theta_c, long max_centroids,
+                 long *out_stats);
+int siso_export_meta(siso_cache *c, float *cluster_size, unsigned *access_count);
+
+/*
  * Threshold-to-hit-ratio (T2H) table (section 4.3, "Adjusting theta_R to meet
  * SLO"): test lookups of a sample of queries, counted against a sweep of
  * retrieval thresholds (the paper sweeps 0.98 down to 0.6).

@@ -936,14 +936,16 @@ int siso_skinny_launch(siso_cache *c, const void *queries, long n, int slices) {
 // ----------------------------------------------------------------------------
 // pair search (siso_merge) on the same kernel
 // ----------------------------------------------------------------------------
-int siso_merge_mfma_supported(const siso_cache *c) {
+int siso_pairs_mfma_supported(const siso_cache *c, long count) {
     if (c->opt_merge_config == 1) return 0;  // 1 = force the scalar kernel
-    return c->dtype == SISO_BF16 && c->dim % 64 == 0 && c->dim >= 128 && c->count >= 2;
+    return c->dtype == SISO_BF16 && c->dim % 64 == 0 && c->dim >= 128 && count >= 2;
 }
 
-int siso_merge_mfma_launch(siso_cache *c, float threshold, int *out_pairs, long cap) {
+int siso_pairs_mfma_launch(siso_cache *c, const void *rows, const float *invn, long count, float threshold,
+                           int *out_pairs, long cap, u64 *counter) {
     typedef PipeLarge Cfg;
-    const long T = (c->count + Cfg::BC - 1) / Cfg::BC;
+    if (((uintptr_t)rows & 15) != 0) return siso_fail(c, SISO_EINVAL, "pair search: rows must be 16-byte aligned");
+    const long T = (count + Cfg::BC - 1) / Cfg::BC;
     // one tile pair per workgroup (the triangle balances best in small pieces), blocks of 8 tiles x 4
     // slices per XCD; workgroups whose slice lies left of their own tile exit at once
     long tps = c->opt_tiles_per_slice > 0 ? c->opt_tiles_per_slice : 1;
@@ -962,7 +964,7 @@ int siso_merge_mfma_launch(siso_cache *c, float threshold, int *out_pairs, long 
         attr_done = true;
     }
     hipLaunchKernelGGL((k_lookup_pipe<Cfg, PIPE_PAIRS>), dim3((unsigned)grid), dim3(Cfg::NT), Cfg::LDS_BYTES, c->stream,
-                       (const bf16_t *)c->cent, (const bf16_t *)c->cent, c->invn, c->count, c->count, c->dim, (int)tps,
-                       (int)slices, (int)T, qb, (u64 *)nullptr, threshold, out_pairs, cap, c->counters + 1);
+                       (const bf16_t *)rows, (const bf16_t *)rows, invn, count, count, c->dim, (int)tps, (int)slices,
+                       (int)T, qb, (u64 *)nullptr, threshold, out_pairs, cap, counter);
     return siso_check_hip(c, hipGetLastError(), "pair search kernel");
 }

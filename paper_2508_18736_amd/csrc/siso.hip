@@ -76,7 +76,8 @@ __device__ __forceinline__ float block_sum256(float v, float *sh) {
 // siso_load: store rows verbatim, mean = row / |row|, size = counts or 1, invn = 1/|row|.
 template <typename T>
 __global__ __launch_bounds__(256) void k_load_rows(const T *__restrict__ src, const int *__restrict__ counts, T *cent,
-                                                    float *mean, int *size, float *invn, int d) {
+                                                    float *mean, int *size, float *invn, float *locality,
+                                                    unsigned *access, int d) {
     __shared__ float sh[4];
     const long k = blockIdx.x;
     const T *row = src + (size_t)k * d;
@@ -98,6 +99,8 @@ __global__ __launch_bounds__(256) void k_load_rows(const T *__restrict__ src, co
         int s = counts ? counts[k] : 1;
         size[k] = s < 1 ? 1 : s;
         invn[k] = inv;
+        locality[k] = (float)(s < 1 ? 1 : s);
+        access[k] = 0;
     }
 }
 
@@ -128,7 +131,8 @@ template <typename T>
 __global__ __launch_bounds__(256) void k_lookup_finalize(const T *__restrict__ Q, const T *__restrict__ cent,
                                                           const float *__restrict__ invn, const u64 *__restrict__ keys,
                                                           long n, long K, int d, int slices, float threshold, int vec,
-                                                          int *out_idx, float *out_sim, unsigned char *out_hit) {
+                                                          int *out_idx, float *out_sim, unsigned char *out_hit,
+                                                          unsigned *access) {
     constexpr int EPC = 16 / (int)sizeof(T);  // elements per 16-byte chunk
     __shared__ float sh_f[4];
     __shared__ u64 sh_k[4];
@@ -211,7 +215,10 @@ __global__ __launch_bounds__(256) void k_lookup_finalize(const T *__restrict__ Q
         if (!finite_q) best_s = __uint_as_float(0x7FC00000u);
         out_idx[q] = (int)best_i;
         out_sim[q] = best_s;
-        if (out_hit) out_hit[q] = (best_i >= 0 && best_s > threshold) ? 1 : 0;
+        const bool hit = best_i >= 0 && best_s > threshold;
+        if (out_hit) out_hit[q] = hit ? 1 : 0;
+        // a hit is a reference to its centroid (access_count of Algorithm 1); infinity stays infinity
+        if (hit && access && access[best_i] != SISO_ACCESS_INF) atomicAdd(&access[best_i], 1u);
     }
 }
 
@@ -365,16 +372,17 @@ __global__ __launch_bounds__(256) void k_merge_scalar(const T *__restrict__ cent
     }
 }
 
-int siso_merge_scalar_launch(siso_cache *c, float threshold, int *out_pairs, long cap) {
-    const unsigned tiles = (unsigned)((c->count + ST_M - 1) / ST_M);
-    if (tiles > 65535u) return siso_fail(c, SISO_EINVAL, "scalar merge path handles at most %d centroids", 65535 * ST_M);
+int siso_pairs_scalar_launch(siso_cache *c, const void *rows, const float *invn, long count, float threshold,
+                             int *out_pairs, long cap, u64 *counter) {
+    const unsigned tiles = (unsigned)((count + ST_M - 1) / ST_M);
+    if (tiles > 65535u) return siso_fail(c, SISO_EINVAL, "scalar pair search handles at most %d rows", 65535 * ST_M);
     dim3 grid(tiles, tiles);
     if (c->dtype == SISO_F32)
-        hipLaunchKernelGGL(k_merge_scalar<float>, grid, dim3(256), 0, c->stream, (const float *)c->cent, c->invn,
-                           c->count, c->dim, threshold, out_pairs, cap, c->counters + 1);
+        hipLaunchKernelGGL(k_merge_scalar<float>, grid, dim3(256), 0, c->stream, (const float *)rows, invn, count, c->dim,
+                           threshold, out_pairs, cap, counter);
     else
-        hipLaunchKernelGGL(k_merge_scalar<bf16_t>, grid, dim3(256), 0, c->stream, (const bf16_t *)c->cent, c->invn,
-                           c->count, c->dim, threshold, out_pairs, cap, c->counters + 1);
+        hipLaunchKernelGGL(k_merge_scalar<bf16_t>, grid, dim3(256), 0, c->stream, (const bf16_t *)rows, invn, count,
+                           c->dim, threshold, out_pairs, cap, counter);
     return siso_check_hip(c, hipGetLastError(), "k_merge_scalar");
 }
 
@@ -527,7 +535,8 @@ __global__ void k_uf_roots(const int *__restrict__ parent, int *root, long K) {
 // One block per row; only roots of groups with at least two rows work.
 template <typename T>
 __global__ __launch_bounds__(256) void k_group_mean(const int *__restrict__ root, const unsigned char *__restrict__ touched,
-                                                     long K, T *cent, float *mean, int *size, float *invn, int d) {
+                                                     long K, T *cent, float *mean, int *size, float *invn,
+                                                     float *locality, unsigned *access, int d) {
     __shared__ float sh[4];
     __shared__ u64 masks[4];
     const long r = blockIdx.x;
@@ -538,6 +547,8 @@ __global__ __launch_bounds__(256) void k_group_mean(const int *__restrict__ root
     for (int e = 0; e < UPD_MAXE; ++e) acc[e] = 0.f;
     double wsum = 0.0;
     int members = 0;
+    float loc = 0.f;  // cluster sizes of Algorithm 1 add up, in ascending order of the members
+    u64 refs = 0;     // so do the access counts, saturating at infinity
     for (long base = r - (r & 255); base < K; base += 256) {
         const long j = base + t;
         const bool m = j < K && j >= r && root[j] == (int)r;
@@ -558,6 +569,8 @@ __global__ __launch_bounds__(256) void k_group_mean(const int *__restrict__ root
                     if (col < d) acc[e] += wgt * mean[(size_t)jj * d + col];
                 }
                 wsum += (double)size[jj];
+                loc = loc + locality[jj];
+                refs += access[jj];
                 ++members;
             }
         }
@@ -577,7 +590,11 @@ __global__ __launch_bounds__(256) void k_group_mean(const int *__restrict__ root
         }
     }
     const float n2 = block_sum256(ss, sh);
-    if (t == 0) size[r] = wsum > 2147483647.0 ? 2147483647 : (int)wsum;
+    if (t == 0) {
+        size[r] = wsum > 2147483647.0 ? 2147483647 : (int)wsum;
+        locality[r] = loc;
+        access[r] = refs >= (u64)SISO_ACCESS_INF ? SISO_ACCESS_INF : (unsigned)refs;
+    }
     if (!(n2 > 0.f) || n2 > 3.0e38f) return;
     const float nrm = sqrtf(n2);
     float cs = 0.f;
@@ -628,7 +645,10 @@ template <typename T>
 __global__ __launch_bounds__(256) void k_gather_rows(const int *__restrict__ root, const int *__restrict__ newpos,
                                                       const T *__restrict__ cent, const float *__restrict__ mean,
                                                       const int *__restrict__ size, const float *__restrict__ invn,
-                                                      T *cent2, float *mean2, int *size2, float *invn2, int d) {
+                                                      const float *__restrict__ locality,
+                                                      const unsigned *__restrict__ access, T *cent2, float *mean2,
+                                                      int *size2, float *invn2, float *locality2, unsigned *access2,
+                                                      int d) {
     const long i = blockIdx.x;
     if (root[i] != (int)i) return;
     const long p = newpos[i];
@@ -639,6 +659,8 @@ __global__ __launch_bounds__(256) void k_gather_rows(const int *__restrict__ roo
     if (threadIdx.x == 0) {
         size2[p] = size[i];
         invn2[p] = invn[i];
+        locality2[p] = locality[i];
+        access2[p] = access[i];
     }
 }
 
@@ -692,6 +714,8 @@ extern "C" int siso_create_ex(int dim, long capacity, int dtype, siso_cache **ou
     ok = ok && hipMalloc((void **)&c->size, (size_t)capacity * sizeof(int)) == hipSuccess;
     ok = ok && hipMalloc((void **)&c->invn, ((size_t)capacity + SISO_PAD_ROWS) * sizeof(float)) == hipSuccess;
     ok = ok && hipMemset(c->invn, 0, ((size_t)capacity + SISO_PAD_ROWS) * sizeof(float)) == hipSuccess;
+    ok = ok && hipMalloc((void **)&c->locality, (size_t)capacity * sizeof(float)) == hipSuccess;
+    ok = ok && hipMalloc((void **)&c->access, (size_t)capacity * sizeof(unsigned)) == hipSuccess;
     ok = ok && hipMalloc((void **)&c->counters, 4 * sizeof(u64)) == hipSuccess;
     ok = ok && hipHostMalloc((void **)&c->host_pin, 4 * sizeof(u64), hipHostMallocDefault) == hipSuccess;
     ok = ok && hipMemset(c->counters, 0, 4 * sizeof(u64)) == hipSuccess;
@@ -716,6 +740,8 @@ extern "C" void siso_destroy(siso_cache *c) {
     if (c->mean) (void)hipFree(c->mean);
     if (c->size) (void)hipFree(c->size);
     if (c->invn) (void)hipFree(c->invn);
+    if (c->locality) (void)hipFree(c->locality);
+    if (c->access) (void)hipFree(c->access);
     if (c->keys) (void)hipFree(c->keys);
     if (c->counters) (void)hipFree(c->counters);
     if (c->host_pin) (void)hipHostFree(c->host_pin);
@@ -764,10 +790,11 @@ extern "C" int siso_load(siso_cache *c, const void *centroids, const int *counts
     if (k > 0) {
         if (c->dtype == SISO_F32)
             hipLaunchKernelGGL(k_load_rows<float>, dim3((unsigned)k), dim3(256), 0, c->stream, (const float *)centroids,
-                               counts, (float *)c->cent, c->mean, c->size, c->invn, c->dim);
+                               counts, (float *)c->cent, c->mean, c->size, c->invn, c->locality, c->access, c->dim);
         else
             hipLaunchKernelGGL(k_load_rows<bf16_t>, dim3((unsigned)k), dim3(256), 0, c->stream,
-                               (const bf16_t *)centroids, counts, (bf16_t *)c->cent, c->mean, c->size, c->invn, c->dim);
+                               (const bf16_t *)centroids, counts, (bf16_t *)c->cent, c->mean, c->size, c->invn, c->locality,
+                               c->access, c->dim);
         HIP_TRY(c, hipGetLastError());
     }
     hipLaunchKernelGGL(k_fill_nan, dim3(1), dim3(SISO_PAD_ROWS), 0, c->stream, c->invn + k, SISO_PAD_ROWS);
@@ -788,6 +815,11 @@ extern "C" int siso_lookup(siso_cache *c, const void *queries, long n, float thr
     if (!c) return SISO_EINVAL;
     if (n < 0 || (n > 0 && (!queries || !out_idx || !out_sim)))
         return siso_fail(c, SISO_EINVAL, "siso_lookup: bad arguments");
+    return siso_lookup_impl(c, queries, n, threshold, out_idx, out_sim, out_hit, 1);
+}
+
+int siso_lookup_impl(siso_cache *c, const void *queries, long n, float threshold, int *out_idx, float *out_sim,
+                     unsigned char *out_hit, int count_access) {
     if (n == 0) return SISO_OK;
     if (n > 2147483647L / 4) return siso_fail(c, SISO_EINVAL, "siso_lookup: batch of %ld is too large", n);
     int slices = 1;
@@ -819,11 +851,11 @@ extern "C" int siso_lookup(siso_cache *c, const void *queries, long n, float thr
     if (c->dtype == SISO_F32)
         hipLaunchKernelGGL(k_lookup_finalize<float>, dim3(qblocks), dim3(256), 0, c->stream, (const float *)queries,
                            (const float *)c->cent, c->invn, c->keys, n, c->count, c->dim, slices, threshold,
-                           vec, out_idx, out_sim, out_hit);
+                           vec, out_idx, out_sim, out_hit, count_access ? c->access : nullptr);
     else
         hipLaunchKernelGGL(k_lookup_finalize<bf16_t>, dim3(qblocks), dim3(256), 0, c->stream, (const bf16_t *)queries,
                            (const bf16_t *)c->cent, c->invn, c->keys, n, c->count, c->dim, slices, threshold,
-                           vec, out_idx, out_sim, out_hit);
+                           vec, out_idx, out_sim, out_hit, count_access ? c->access : nullptr);
     HIP_TRY(c, hipGetLastError());
     return SISO_OK;
 }
@@ -861,7 +893,7 @@ extern "C" int siso_update(siso_cache *c, const void *queries, const int *idx, l
     return siso_update_hits(c, queries, idx, nullptr, n);
 }
 
-static int read_counter(siso_cache *c, int which, u64 *value) {
+int siso_read_counter(siso_cache *c, int which, u64 *value) {
     HIP_TRY(c, hipMemcpyAsync(c->host_pin, c->counters, 4 * sizeof(u64), hipMemcpyDeviceToHost, c->stream));
     HIP_TRY(c, hipStreamSynchronize(c->stream));
     *value = c->host_pin[which];
@@ -877,10 +909,20 @@ __global__ void k_fill_nan(float *p, int count) {
     if (i < count) p[i] = __uint_as_float(0x7FC00000u);
 }
 
+extern "C" int siso_export_meta(siso_cache *c, float *cluster_size, unsigned *access_count) {
+    if (!c) return SISO_EINVAL;
+    if (c->count == 0) return SISO_OK;
+    if (cluster_size)
+        HIP_TRY(c, hipMemcpyAsync(cluster_size, c->locality, (size_t)c->count * sizeof(float), hipMemcpyDeviceToDevice, c->stream));
+    if (access_count)
+        HIP_TRY(c, hipMemcpyAsync(access_count, c->access, (size_t)c->count * sizeof(unsigned), hipMemcpyDeviceToDevice, c->stream));
+    return SISO_OK;
+}
+
 extern "C" long siso_bad_indices(siso_cache *c) {
     if (!c) return SISO_EINVAL;
     u64 v = 0;
-    const int rc = read_counter(c, 0, &v);
+    const int rc = siso_read_counter(c, 0, &v);
     return rc != SISO_OK ? (long)rc : (long)v;
 }
 
@@ -892,14 +934,14 @@ extern "C" long siso_merge(siso_cache *c, float threshold, int *out_pairs, long 
     int rc = siso_check_hip(c, hipGetLastError(), "k_zero_counter");
     if (rc != SISO_OK) return rc;
     siso_prof_begin(c);
-    if (siso_merge_mfma_supported(c))
-        rc = siso_merge_mfma_launch(c, threshold, out_pairs, cap);
+    if (siso_pairs_mfma_supported(c, c->count))
+        rc = siso_pairs_mfma_launch(c, c->cent, c->invn, c->count, threshold, out_pairs, cap, c->counters + 1);
     else
-        rc = siso_merge_scalar_launch(c, threshold, out_pairs, cap);
+        rc = siso_pairs_scalar_launch(c, c->cent, c->invn, c->count, threshold, out_pairs, cap, c->counters + 1);
     siso_prof_end(c);
     if (rc != SISO_OK) return rc;
     u64 total = 0;
-    rc = read_counter(c, 1, &total);
+    rc = siso_read_counter(c, 1, &total);
     return rc != SISO_OK ? (long)rc : (long)total;
 }
 
@@ -915,14 +957,15 @@ extern "C" int siso_merge_apply(siso_cache *c, const int *pairs, long n_pairs, i
         hipLaunchKernelGGL(k_zero_counter, dim3(1), dim3(1), 0, c->stream, c->counters + 2);
         hipLaunchKernelGGL(k_pairs_validate, dim3(pb), dim3(256), 0, c->stream, pairs, n_pairs, K, c->counters + 2);
         HIP_TRY(c, hipGetLastError());
-        int rc = read_counter(c, 2, &v);
+        int rc = siso_read_counter(c, 2, &v);
         if (rc != SISO_OK) return rc;
         if (v != 0) return siso_fail(c, SISO_EINVAL, "siso_merge_apply: %llu invalid pairs", v);
     }
     int *parent = nullptr, *root = nullptr, *newpos = nullptr;
     unsigned char *touched = nullptr;
     void *cent2 = nullptr;
-    float *mean2 = nullptr, *invn2 = nullptr;
+    float *mean2 = nullptr, *invn2 = nullptr, *loc2 = nullptr;
+    unsigned *acc2 = nullptr;
     int *size2 = nullptr;
     int rc = SISO_OK;
     bool ok = hipMalloc((void **)&parent, (size_t)K * sizeof(int)) == hipSuccess;
@@ -941,13 +984,13 @@ extern "C" int siso_merge_apply(siso_cache *c, const int *pairs, long n_pairs, i
         hipLaunchKernelGGL(k_uf_roots, dim3(kb), dim3(256), 0, c->stream, parent, root, K);
         if (c->dtype == SISO_F32)
             hipLaunchKernelGGL(k_group_mean<float>, dim3((unsigned)K), dim3(256), 0, c->stream, root, touched, K,
-                               (float *)c->cent, c->mean, c->size, c->invn, d);
+                               (float *)c->cent, c->mean, c->size, c->invn, c->locality, c->access, d);
         else
             hipLaunchKernelGGL(k_group_mean<bf16_t>, dim3((unsigned)K), dim3(256), 0, c->stream, root, touched, K,
-                               (bf16_t *)c->cent, c->mean, c->size, c->invn, d);
+                               (bf16_t *)c->cent, c->mean, c->size, c->invn, c->locality, c->access, d);
         hipLaunchKernelGGL(k_scan_survivors, dim3(1), dim3(1024), 0, c->stream, root, K, newpos, c->counters + 3);
         rc = siso_check_hip(c, hipGetLastError(), "merge_apply kernels");
-        if (rc == SISO_OK) rc = read_counter(c, 3, &v);
+        if (rc == SISO_OK) rc = siso_read_counter(c, 3, &v);
         if (rc == SISO_OK) live = (long)v;
     }
     if (rc == SISO_OK && out_survivor) {
@@ -960,18 +1003,20 @@ extern "C" int siso_merge_apply(siso_cache *c, const int *pairs, long n_pairs, i
         ok = ok && hipMalloc((void **)&mean2, cells * sizeof(float)) == hipSuccess;
         ok = ok && hipMalloc((void **)&size2, (size_t)live * sizeof(int)) == hipSuccess;
         ok = ok && hipMalloc((void **)&invn2, (size_t)live * sizeof(float)) == hipSuccess;
+        ok = ok && hipMalloc((void **)&loc2, (size_t)live * sizeof(float)) == hipSuccess;
+        ok = ok && hipMalloc((void **)&acc2, (size_t)live * sizeof(unsigned)) == hipSuccess;
         if (!ok) {
             (void)hipGetLastError();
             rc = siso_fail(c, SISO_ENOMEM, "siso_merge_apply: compaction buffers");
         } else {
             if (c->dtype == SISO_F32)
                 hipLaunchKernelGGL(k_gather_rows<float>, dim3((unsigned)K), dim3(256), 0, c->stream, root, newpos,
-                                   (const float *)c->cent, c->mean, c->size, c->invn, (float *)cent2, mean2, size2,
-                                   invn2, d);
+                                   (const float *)c->cent, c->mean, c->size, c->invn, c->locality, c->access,
+                                   (float *)cent2, mean2, size2, invn2, loc2, acc2, d);
             else
                 hipLaunchKernelGGL(k_gather_rows<bf16_t>, dim3((unsigned)K), dim3(256), 0, c->stream, root, newpos,
-                                   (const bf16_t *)c->cent, c->mean, c->size, c->invn, (bf16_t *)cent2, mean2, size2,
-                                   invn2, d);
+                                   (const bf16_t *)c->cent, c->mean, c->size, c->invn, c->locality, c->access,
+                                   (bf16_t *)cent2, mean2, size2, invn2, loc2, acc2, d);
             rc = siso_check_hip(c, hipGetLastError(), "k_gather_rows");
             if (rc == SISO_OK)
                 rc = siso_check_hip(c, hipMemcpyAsync(c->cent, cent2, cells * elem_bytes(c->dtype), hipMemcpyDeviceToDevice, c->stream), "copy back");
@@ -981,6 +1026,10 @@ extern "C" int siso_merge_apply(siso_cache *c, const int *pairs, long n_pairs, i
                 rc = siso_check_hip(c, hipMemcpyAsync(c->size, size2, (size_t)live * sizeof(int), hipMemcpyDeviceToDevice, c->stream), "copy back");
             if (rc == SISO_OK)
                 rc = siso_check_hip(c, hipMemcpyAsync(c->invn, invn2, (size_t)live * sizeof(float), hipMemcpyDeviceToDevice, c->stream), "copy back");
+            if (rc == SISO_OK)
+                rc = siso_check_hip(c, hipMemcpyAsync(c->locality, loc2, (size_t)live * sizeof(float), hipMemcpyDeviceToDevice, c->stream), "copy back");
+            if (rc == SISO_OK)
+                rc = siso_check_hip(c, hipMemcpyAsync(c->access, acc2, (size_t)live * sizeof(unsigned), hipMemcpyDeviceToDevice, c->stream), "copy back");
         }
     }
     if (rc == SISO_OK) {
@@ -997,6 +1046,8 @@ extern "C" int siso_merge_apply(siso_cache *c, const int *pairs, long n_pairs, i
     if (mean2) (void)hipFree(mean2);
     if (size2) (void)hipFree(size2);
     if (invn2) (void)hipFree(invn2);
+    if (loc2) (void)hipFree(loc2);
+    if (acc2) (void)hipFree(acc2);
     return rc;
 }
 
@@ -1082,7 +1133,7 @@ extern "C" int siso_t2h(siso_cache *c, const void *queries, long n, const float 
     hipError_t e = hipMemcpyAsync(d_th, thetas, (size_t)m * sizeof(float), hipMemcpyHostToDevice, c->stream);
     if (e == hipSuccess) e = hipMemsetAsync(d_hits, 0, (size_t)m * sizeof(u64), c->stream);
     if (e != hipSuccess) rc = siso_check_hip(c, e, "siso_t2h: set-up");
-    if (rc == SISO_OK) rc = siso_lookup(c, queries, n, 0.f, idx, sim, nullptr);
+    if (rc == SISO_OK) rc = siso_lookup_impl(c, queries, n, 0.f, idx, sim, nullptr, 0);  // test lookups are no references
     u64 host_hits[SISO_T2H_MAX];
     if (rc == SISO_OK) {
         hipLaunchKernelGGL(k_t2h_count, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, c->stream, sim, n, d_th, m, d_hits);

@@ -42,6 +42,7 @@ __device__ __forceinline__ void siso_merge_candidate(float &v, unsigned &b, floa
         else if (ob < b) b = ob;
     }
 }
+#define SISO_ACCESS_INF 0xFFFFFFFFu
 #define SISO_MAX_DIM 4096
 #define SISO_PAD_ROWS 256  // readable rows past the capacity of the stored-centroid array
 
@@ -58,6 +59,8 @@ struct siso_cache {
     float *mean;  // [capacity][dim] mean of the unit-length members
     int *size;    // [capacity] cluster_size
     float *invn;  // [capacity] 1 / |stored centroid| (0 for a zero row, NaN for a non-finite row)
+    float *locality;   // [capacity] cluster_size of Algorithm 1: grows by merges, decays by 1.1 per refresh
+    unsigned *access;  // [capacity] access_count of Algorithm 1: hits since the last refresh; SISO_ACCESS_INF = infinity
 
     // workspace, grown on demand
     u64 *keys;     // [keys_cap] phase-1 keys, n * slices
@@ -194,7 +197,17 @@ int siso_mfma_launch(siso_cache *c, const void *queries, long n, int slices);
 int siso_skinny_slices(const siso_cache *c, long n);
 int siso_skinny_launch(siso_cache *c, const void *queries, long n, int slices);
 
-// Self-similarity pair search launchers (counter = c->counters + 1, already zeroed).
-int siso_merge_scalar_launch(siso_cache *c, float threshold, int *out_pairs, long cap);
-int siso_merge_mfma_supported(const siso_cache *c);
-int siso_merge_mfma_launch(siso_cache *c, float threshold, int *out_pairs, long cap);
+// Self-similarity pair search over `count` rows of the cache's element type and dimension with
+// their inverse lengths (counter already zeroed).  The MFMA kernel reads whole tiles: rows and invn
+// must be readable for SISO_PAD_ROWS entries past count, the invn entries there holding NaN.
+int siso_pairs_scalar_launch(siso_cache *c, const void *rows, const float *invn, long count, float threshold,
+                             int *out_pairs, long cap, u64 *counter);
+int siso_pairs_mfma_supported(const siso_cache *c, long count);
+int siso_pairs_mfma_launch(siso_cache *c, const void *rows, const float *invn, long count, float threshold,
+                           int *out_pairs, long cap, u64 *counter);
+
+// siso_lookup without the argument checks of the ABI; count_access = hits are references to their
+// centroids (access_count goes up), as in serving; 0 for test lookups
+int siso_lookup_impl(siso_cache *c, const void *queries, long n, float threshold, int *out_idx, float *out_sim,
+                     unsigned char *out_hit, int count_access);
+int siso_read_counter(siso_cache *c, int which, u64 *value);  // synchronises

