@@ -229,11 +229,33 @@ def main():
                       "pair_kernel_ms": mk_ms, "pair_kernel_tflops": float(K) * K * d / (mk_ms / 1e3) / 1e12,
                       "group_merge_ms": apply_s * 1e3, "centroids_after": cache.count}
 
+    refresh_info = None
+    if not args.no_merge and name == "c2_mid":
+        # cache replacement (Algorithm 1) on a fresh copy of the cache: a repository of 10 % of its size, half of
+        # it near cached centroids (they merge), half of it new directions (they join); room for 2 % more rows
+        rng = np.random.Generator(np.random.Philox(key=4242))
+        r = K // 10
+        near = W.spread_sample(wl.centroids, wl.dtype, r // 2, sigma_lo=0.02, sigma_hi=0.1, seed=W.BASE_SEED + 8)
+        fresh = W.to_storage(W.uniform_directions(W.BASE_SEED + 9, 7, r - r // 2, d), wl.dtype)
+        repo = to_dev(np.concatenate([near, fresh])[rng.permutation(r)], wl.dtype)
+        sizes = torch.from_numpy(rng.integers(1, 40, size=r).astype(np.float32)).to("cuda:0")
+        c2 = siso.SisoCache(d, K + r, siso.BF16)
+        c2.load(to_dev(wl.centroids, wl.dtype))
+        c2.lookup(queries[:nb], 0.85)
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        merged, added, evicted = c2.refresh(repo, sizes, 0.90, K + K // 50)
+        refresh_s = time.perf_counter() - t1
+        refresh_info = {"repository": r, "threshold": 0.9, "max_centroids": K + K // 50, "ms": refresh_s * 1e3,
+                        "merged": merged, "added": added, "evicted": evicted, "centroids_after": c2.count}
+        c2.close()
+
     out.update({"metric": "lookup_queries_per_s", "value": nb * steps / dt, "unit": "queries/s", "steps": steps,
                 "warmup": warmup, "ms_per_step": dt / steps * 1e3,
                 "config": {"workload": name, "centroids": K, "dim": d, "batch": nb, "thresholds": thetas,
                            "step": "siso_lookup + siso_update_hits", "hit_rate_last_batch": hit_rate,
-                           "offline_merge": merge_info, "t2h": t2h_info, "generate_s": round(gen_s, 1)},
+                           "offline_merge": merge_info, "t2h": t2h_info, "refresh": refresh_info,
+                           "generate_s": round(gen_s, 1)},
                 "roofline": roof})
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl, nb, args.cpu_seconds)

@@ -181,3 +181,38 @@ def test_c5_merge_full(siso, oracle):
         want_m = u[mem].mean(axis=0)
         assert np.abs(gm_h[newidx[g]] - want_m).max() < 2e-6
         assert np.abs(gc_h[newidx[g]] - unit64(want_m)).max() <= 2.0 ** -8
+
+
+def test_refresh_mid_size_vs_oracle(siso, oracle):
+    """Cache replacement at a size where the MFMA lookup and the MFMA pair search serve it: 16,384 cached
+    centroids, a repository of 2,048 (half near cached ones, half new directions, a few duplicates of
+    each other), more rows than the cache may keep."""
+    import torch
+    from gpu_util import SIM_TOL, to_dev, to_host
+    dim, K, r = 768, 16384, 2048
+    print(f"case: refresh K={K} r={r} dim={dim}", flush=True)
+    wl = W.c2_mid(n_clusters=4096, per_cluster=4, n_queries=8, dim=dim, seed=333)
+    rng = np.random.Generator(np.random.Philox(key=334))
+    near = W.spread_sample(wl.centroids, "bf16", r // 2, sigma_lo=0.02, sigma_hi=0.1, seed=335)
+    fresh = W.to_storage(W.uniform_directions(336, 7, r // 2 - 64, dim), "bf16")
+    twins = W.spread_sample(fresh[:64], "bf16", 64, sigma_lo=0.02, sigma_hi=0.05, seed=337)  # near other new rows
+    repo = np.concatenate([near, fresh, twins])[rng.permutation(r)]
+    sizes = rng.integers(1, 40, size=r).astype(np.float32)
+    counts = rng.integers(1, 40, size=K).astype(np.int32)
+    M = K + 600
+    ora = oracle.OracleCache(dim, K + r, "bf16")
+    ora.load(wl.centroids, counts)
+    gpu = siso.SisoCache(dim, K + r, siso.BF16)
+    gpu.load(to_dev(wl.centroids, "bf16"), torch.from_numpy(counts).to("cuda:0"))
+    want = ora.refresh(repo, sizes, 0.9, M)
+    got = gpu.refresh(to_dev(repo, "bf16"), torch.from_numpy(sizes).to("cuda:0"), 0.9, M)
+    print(f"  oracle (merged, added, evicted, margin) = {want}; gpu = {got}", flush=True)
+    assert want[3] > 10 * SIM_TOL["bf16"]
+    assert got == want[:3] and want[1] > 900 and want[2] > 300
+    oc, _, osz = ora.export()
+    gc, _, gsz = gpu.export()
+    assert gpu.count == ora.count == M
+    assert (to_host(gc, "bf16") == oc).all() and (gsz.cpu().numpy() == osz).all()
+    ol, oa = ora.export_meta()
+    gl, ga = gpu.export_meta()
+    assert (gl.cpu().numpy() == ol).all() and (ga.cpu().numpy().astype(np.uint32) == oa).all()
