@@ -84,7 +84,7 @@ def cpu_baseline(wl, n_batch, seconds):
 def main():
     args = parse()
     if args.gpus != 1:
-        print("bench.py: this build runs on one GPU only; --gpus must be 1", file=sys.stderr)
+        print("bench.py: the library runs on one GPU only; --gpus must be 1", file=sys.stderr)
         sys.exit(2)
     import numpy as np
     import torch
