@@ -131,7 +131,8 @@ int siso_lookup(siso_cache *c, const void *queries, long n, float threshold, int
  * Entries with idx[i] < 0 are skipped, and so are zero-length and non-finite
  * queries.  An idx[i] >= siso_count() is skipped too and counted: see
  * siso_bad_indices.  All members of a centroid are taken in ascending i, so
- * the result does not depend on scheduling.  Asynchronous.
+ * the result does not depend on scheduling.  Asynchronous; the first batch of
+ * more than 256 queries allocates 8 bytes per centroid of capacity for notes.
  *
  * siso_update_hits folds only the entries with hit[i] != 0 (device pointer, n
  * bytes): the outputs of siso_lookup can be passed on without touching the host.

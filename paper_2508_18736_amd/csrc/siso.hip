@@ -392,11 +392,35 @@ int siso_pairs_scalar_launch(siso_cache *c, const void *rows, const float *invn,
 // ============================================================================
 #define UPD_MAXE (SISO_MAX_DIM / 256)
 
-// UPD_MAXE_T = elements of a row per thread (4 for dim <= 1024, else 16)
+// Large batches: every block searching the whole index array for the members of its centroid costs
+// n^2 / 256 steps.  A first pass notes, per centroid, its first member and the number of its members;
+// then only the first member's block does anything, and it looks through the index array only if
+// there is more than one member (queries of one batch rarely share a centroid).
+#define UPD_NO_OWNER 0x7FFFFFFF
+__global__ void k_update_mark(const int *__restrict__ idx, const unsigned char *__restrict__ hit, long n, long count,
+                              int *owner, int *members) {
+    const long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n || (hit && !hit[i])) return;
+    const int k = idx[i];
+    if (k < 0 || k >= count) return;
+    atomicMin(&owner[k], (int)i);
+    atomicAdd(&members[k], 1);
+}
+__global__ void k_update_mark_init(int *owner, int *members, long capacity) {
+    const long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < capacity) {
+        owner[i] = UPD_NO_OWNER;
+        members[i] = 0;
+    }
+}
+
+// UPD_MAXE_T = elements of a row per thread (4 for dim <= 1024, else 16).  owner / marked = the notes
+// of k_update_mark, or NULL: then every block finds out by itself whether it is the first member.
 template <typename T, int UPD_MAXE_T>
 __global__ __launch_bounds__(256) void k_update(const T *__restrict__ Q, const int *__restrict__ idx,
                                                  const unsigned char *__restrict__ hit, long n, T *cent, float *mean,
-                                                 int *size, float *invn, long count, int d, u64 *bad) {
+                                                 int *size, float *invn, long count, int d, u64 *bad, int *owner,
+                                                 int *marked) {
     __shared__ float sh[4];
     __shared__ u64 masks[4];
     const long me = blockIdx.x;
@@ -408,13 +432,26 @@ __global__ __launch_bounds__(256) void k_update(const T *__restrict__ Q, const i
         if (t == 0) atomicAdd(bad, 1ull);
         return;
     }
+    long scan_from = 0, scan_to = n;
+    if (owner) {
+        if (owner[k] != (int)me) return;  // an earlier member leads this centroid
+        if (marked[k] == 1) {
+            scan_from = me - (me & 255);  // the only member: just the 256 entries around this one
+            scan_to = scan_from + 256 < n ? scan_from + 256 : n;
+        }
+        __syncthreads();  // everyone has read the notes
+        if (t == 0) {     // leave them as they were found
+            owner[k] = UPD_NO_OWNER;
+            marked[k] = 0;
+        }
+    }
     float acc[UPD_MAXE_T];
 #pragma unroll
     for (int e = 0; e < UPD_MAXE_T; ++e) acc[e] = 0.f;
     int members = 0;
-    for (long base = 0; base < n; base += 256) {
+    for (long base = scan_from; base < scan_to; base += 256) {
         const long j = base + t;
-        const bool m = j < n && idx[j] == k && (!hit || hit[j]);
+        const bool m = j < scan_to && idx[j] == k && (!hit || hit[j]);
         const u64 mask = __ballot(m);
         __syncthreads();
         if ((t & 63) == 0) masks[t >> 6] = mask;
@@ -741,6 +778,8 @@ extern "C" void siso_destroy(siso_cache *c) {
     if (c->size) (void)hipFree(c->size);
     if (c->invn) (void)hipFree(c->invn);
     if (c->locality) (void)hipFree(c->locality);
+    if (c->upd_owner) (void)hipFree(c->upd_owner);
+    if (c->upd_members) (void)hipFree(c->upd_members);
     if (c->access) (void)hipFree(c->access);
     if (c->keys) (void)hipFree(c->keys);
     if (c->counters) (void)hipFree(c->counters);
@@ -873,9 +912,28 @@ extern "C" int siso_update_hits(siso_cache *c, const void *queries, const int *i
         const float *qf = (const float *)queries + (size_t)off * c->dim;
         const bf16_t *qh = (const bf16_t *)queries + (size_t)off * c->dim;
         const dim3 grid((unsigned)m), block(256);
+        int *owner = nullptr, *marked = nullptr;
+        if (m > 256) {
+            if (!c->upd_owner) {
+                bool ok = hipMalloc((void **)&c->upd_owner, (size_t)c->capacity * sizeof(int)) == hipSuccess;
+                ok = ok && hipMalloc((void **)&c->upd_members, (size_t)c->capacity * sizeof(int)) == hipSuccess;
+                if (!ok) {
+                    (void)hipGetLastError();
+                    if (c->upd_owner) (void)hipFree(c->upd_owner);
+                    c->upd_owner = nullptr;
+                    return siso_fail(c, SISO_ENOMEM, "siso_update: notes for %ld centroids", c->capacity);
+                }
+                hipLaunchKernelGGL(k_update_mark_init, dim3((unsigned)((c->capacity + 255) / 256)), dim3(256), 0, c->stream,
+                                   c->upd_owner, c->upd_members, c->capacity);
+            }
+            owner = c->upd_owner;
+            marked = c->upd_members;
+            hipLaunchKernelGGL(k_update_mark, dim3((unsigned)((m + 255) / 256)), dim3(256), 0, c->stream, idx + off, h, m,
+                               c->count, owner, marked);
+        }
 #define SISO_LAUNCH_UPDATE(T, E, QP)                                                                            \
     hipLaunchKernelGGL((k_update<T, E>), grid, block, 0, c->stream, QP, idx + off, h, m, (T *)c->cent, c->mean, \
-                       c->size, c->invn, c->count, c->dim, c->counters)
+                       c->size, c->invn, c->count, c->dim, c->counters, owner, marked)
         if (c->dtype == SISO_F32) {
             if (c->dim <= 1024) SISO_LAUNCH_UPDATE(float, 4, qf);
             else SISO_LAUNCH_UPDATE(float, 16, qf);

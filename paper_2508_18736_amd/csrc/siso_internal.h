@@ -62,6 +62,11 @@ struct siso_cache {
     float *locality;   // [capacity] cluster_size of Algorithm 1: grows by merges, decays by 1.1 per refresh
     unsigned *access;  // [capacity] access_count of Algorithm 1: hits since the last refresh; SISO_ACCESS_INF = infinity
 
+    // large update batches: first member and number of members per centroid, [capacity] each, allocated at
+    // the first such batch; between calls every entry is back at (INT_MAX, 0)
+    int *upd_owner;
+    int *upd_members;
+
     // workspace, grown on demand
     u64 *keys;     // [keys_cap] phase-1 keys, n * slices
     long keys_cap;
