@@ -27,10 +27,9 @@
 // direct load of one wave fills 1 KiB = 8 consecutive rows: lane i writes slot
 // i % 8 of row i / 8, so it fetches chunk (i % 8) ^ ((r >> 1) & 7) of that row.
 //
-// The same stream of tiles, with another epilogue, is the pair search behind
-// MergeCentroids: the "query" tile is a tile of centroids too, a workgroup walks
-// through the centroid tiles at or right of it (upper triangle), and every
-// product above the threshold is emitted as a pair (i, j), i < j.
+// The same pipeline, fed with pairs of centroid tiles and with another epilogue, is
+// the pair search behind MergeCentroids (k_pairs_stream): every product above the
+// threshold in the upper triangle is emitted as a pair (i, j), i < j.
 #include "siso_internal.h"
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
@@ -188,9 +187,6 @@ struct Acc<true, WC, WQ> {
 #pragma clang diagnostic pop
 };
 
-#define PIPE_LOOKUP 0
-#define PIPE_PAIRS 1
-
 // Block -> (query tile qt, slice s of the centroid tiles).  Workgroups are handed to the 8 XCDs
 // round robin and every XCD has its own L2.  The 32 workgroups that run together on one XCD are
 // made a unit of qb query tiles x 32/qb slices, so that a centroid tile fetched into that L2
@@ -198,9 +194,7 @@ struct Acc<true, WC, WQ> {
 // an XCD owns every eighth group and walks through all blocks of query tiles for it before moving
 // on (the same slices again and again: repeats come from the caches); with at most four groups
 // the XCDs also split the blocks of query tiles among them, so that none stays idle.
-// In the pair search the query tile is a centroid tile too and only the tiles at or right of it
-// are visited (upper triangle); slices are absolute ranges of tiles, so that the workgroups of a
-// unit still walk through the same centroid tiles in step.  False = nothing to do for this block.
+// False = nothing to do for this block.
 __host__ __device__ __forceinline__ int pipe_group_split(int groups) { return groups <= 1 ? 1 : groups == 2 ? 2 : 4; }
 static long pipe_grid(long slices, long nqt, int qb) {
     const long sb = 32 / qb, groups = (slices + sb - 1) / sb, nqb = (nqt + qb - 1) / qb;
@@ -208,7 +202,7 @@ static long pipe_grid(long slices, long nqt, int qb) {
     const long r = 8 / pipe_group_split((int)groups);  // XCDs per group of slices
     return 8 * ((nqb + r - 1) / r) * 32;
 }
-template <int MODE, int BC>
+template <int BC>
 __device__ __forceinline__ bool pipe_map_block(long K, int tiles_per_slice, int slices, int nqt, int qb, int &qt, int &s,
                                                int &ct_begin, int &ct_end) {
     const int total_ct = (int)((K + BC - 1) / BC);
@@ -230,10 +224,6 @@ __device__ __forceinline__ bool pipe_map_block(long K, int tiles_per_slice, int 
     if (qt >= nqt || s >= slices) return false;
     ct_begin = s * tiles_per_slice;
     ct_end = (ct_begin + tiles_per_slice < total_ct) ? ct_begin + tiles_per_slice : total_ct;
-    if (MODE == PIPE_PAIRS) {
-        if (ct_begin < qt) ct_begin = qt;
-        if (ct_begin >= ct_end) return false;
-    }
     return true;
 }
 
@@ -271,11 +261,10 @@ __device__ __forceinline__ void pipe_reduce_keys(float (&bv)[WQ], unsigned (&bb)
     }
 }
 
-template <class Cfg, int MODE>
+template <class Cfg>
 __global__ __launch_bounds__(Cfg::NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void k_lookup_pipe(
     const bf16_t *__restrict__ Q, const bf16_t *__restrict__ C, const float *__restrict__ invn, long n, long K, int d,
-    int tiles_per_slice, int slices, int nqt, int qb, u64 *__restrict__ keys, float threshold,
-    int *__restrict__ out_pairs, long cap, u64 *__restrict__ counter) {
+    int tiles_per_slice, int slices, int nqt, int qb, u64 *__restrict__ keys) {
     constexpr int WC = Cfg::WC, WQ = Cfg::WQ, NWC = Cfg::NWC, BC = Cfg::BC, BQ = Cfg::BQ, NT = Cfg::NT, NW = Cfg::NW,
                   STAGE = Cfg::STAGE, NLA = Cfg::NLA, NLB = Cfg::NLB, NL = Cfg::NL, NSTAGE = Cfg::NSTAGE, BK = Cfg::BK,
                   RB = Cfg::RB, CPR = Cfg::CPR, RPI = Cfg::RPI, RP = Cfg::RP, KK = Cfg::KK, SUB = 32 * Cfg::RB;
@@ -287,9 +276,8 @@ __global__ __launch_bounds__(Cfg::NT) __attribute__((amdgpu_waves_per_eu(2, 2)))
     const int wc = wave % NWC, wq = wave / NWC;
     const int h = lane >> 5, l32 = lane & 31;
 
-    static_assert(MODE == PIPE_LOOKUP || Cfg::BC == Cfg::BQ, "pair search walks square tiles");
     int qt, s, ct_begin, ct_end;
-    if (!pipe_map_block<MODE, BC>(K, tiles_per_slice, slices, nqt, qb, qt, s, ct_begin, ct_end)) return;
+    if (!pipe_map_block<BC>(K, tiles_per_slice, slices, nqt, qb, qt, s, ct_begin, ct_end)) return;
     const long q0 = (long)qt * BQ;
     const int nk = d / BK;
     const int T = (ct_end - ct_begin) * nk;  // slabs this workgroup walks through
@@ -329,9 +317,6 @@ __global__ __launch_bounds__(Cfg::NT) __attribute__((amdgpu_waves_per_eu(2, 2)))
         bv[b] = -INFINITY;
         bb[b] = 0xFFFFFFFFu;
     }
-    float wi[WQ];  // pairs: 1/|c| of this lane's columns (NaN past the live centroids)
-#pragma unroll
-    for (int b = 0; b < WQ; ++b) wi[b] = MODE == PIPE_PAIRS ? invn[q0 + (wq * WQ + b) * 32 + l32] : 0.f;
     Acc<false, WC, WQ> acc;  // every tile starts from a zero operand, so nothing to clear
     acc.reserve();
 
@@ -359,8 +344,7 @@ __global__ __launch_bounds__(Cfg::NT) __attribute__((amdgpu_waves_per_eu(2, 2)))
         if constexpr (j < NLA) {
             unsigned off = a_off[j];
             asm volatile("" : "+v"(off));
-            if constexpr (MODE == PIPE_LOOKUP) gload_lds16_nt(ld_c + off, ld_sb + j * NW * 1024);
-            else gload_lds16(ld_c + off, ld_sb + j * NW * 1024);
+            gload_lds16_nt(ld_c + off, ld_sb + j * NW * 1024);
         } else {
             unsigned off = b_off[j - NLA];
             asm volatile("" : "+v"(off));
@@ -459,23 +443,9 @@ __global__ __launch_bounds__(Cfg::NT) __attribute__((amdgpu_waves_per_eu(2, 2)))
                         constexpr int I = decltype(ii)::value;
                         m = fmaxf(m, acc.template get<A, B, I>() * w[I >> 2][I & 3]);
                     });
-                    if (MODE == PIPE_LOOKUP) {
-                        if (m > bv[B]) {
-                            bv[B] = m;
-                            bb[B] = blk;
-                        }
-                    } else if (__ballot(m * wi[B] > threshold) != 0) {
-                        // rare: some product of this 32 x 32 block is above the threshold
-                        const long icol = q0 + (wq * WQ + B) * 32 + l32;
-                        const long jrow0 = c0 + rb + 4 * h;  // register I holds row jrow0 + 8 * (I / 4) + I % 4
-                        unsigned found = 0;
-                        static_for<0, 16>([&](auto ii) {
-                            constexpr int I = decltype(ii)::value;
-                            const float sim = acc.template get<A, B, I>() * w[I >> 2][I & 3] * wi[B];
-                            if (sim > threshold && icol < jrow0 + 8 * (I >> 2) + (I & 3)) found |= 1u << I;
-                        });
-                        emit_pairs(found, (int)icol, [&](int I) { return (int)(jrow0 + 8 * (I >> 2) + (I & 3)); }, out_pairs,
-                                   cap, counter);
+                    if (m > bv[B]) {
+                        bv[B] = m;
+                        bb[B] = blk;
                     }
                 });
             });
@@ -487,8 +457,6 @@ __global__ __launch_bounds__(Cfg::NT) __attribute__((amdgpu_waves_per_eu(2, 2)))
         sto = sto_next;
     }
     __syncthreads();
-    if (MODE == PIPE_PAIRS) return;
-
     pipe_reduce_keys<WQ, NWC, BQ, NT>(bv, bb, smem, wc, wq, h, l32, tid, q0, n, slices, s, keys);
 }
 
@@ -511,6 +479,234 @@ __global__ __launch_bounds__(Cfg::NT) __attribute__((amdgpu_waves_per_eu(2, 2)))
 // Behind the last slabs the loads fetch the last slab again and the writes put it into a stage
 // nobody reads any more: one code path, no conditions between the MFMAs.
 // ----------------------------------------------------------------------------
+// ----------------------------------------------------------------------------
+// Pair search as one stream of tile pairs per workgroup.  A workgroup that handles a single tile
+// pair spends a good part of its life filling and draining the pipeline and waiting to be
+// replaced (with 130 KB of LDS only one fits a compute unit), so here 8 x 32 workgroups stay and
+// each walks through its share of the upper triangle: the slabs of consecutive tile pairs follow
+// each other without a gap, only the accumulators start from zero again.
+// The 32 workgroups of an XCD take the tile pairs of one unit (8 column tiles x 4 row tiles) at a
+// time, as in the lookup, so that a tile fetched into that L2 serves several of them; the XCDs own
+// the groups of four row tiles in turns, in alternating direction, which gives each an equal share
+// of the triangle.
+// ----------------------------------------------------------------------------
+struct PairItems {
+    int xcd, i, qb, sb, nqb, groups, tiles, units, u;
+    __device__ __forceinline__ void init(int tiles_, int qb_) {
+        xcd = blockIdx.x & 7;
+        i = (blockIdx.x >> 3) & 31;
+        tiles = tiles_;
+        qb = qb_;
+        sb = 32 / qb;
+        nqb = (tiles + qb - 1) / qb;
+        groups = (tiles + sb - 1) / sb;
+        units = ((groups + 7) / 8) * nqb;
+        u = 0;
+    }
+    // next tile pair (column tile qt <= row tile ct) of this workgroup; false = none left
+    __device__ __forceinline__ bool next(int &qt, int &ct) {
+        while (u < units) {
+            const int round = u / nqb, b = u % nqb;
+            ++u;
+            const int g = round * 8 + ((round & 1) ? 7 - xcd : xcd);
+            const int q = b * qb + i % qb, s = g * sb + i / qb;
+            if (g >= groups || q >= tiles || s >= tiles || s < q) continue;
+            qt = q;
+            ct = s;
+            return true;
+        }
+        return false;
+    }
+};
+
+#define PAIR_STAGE 2048  // pairs a workgroup collects in LDS
+template <class Cfg>
+__global__ __launch_bounds__(Cfg::NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void k_pairs_stream(
+    const bf16_t *__restrict__ C, const float *__restrict__ invn, long K, int d, int qb, float threshold,
+    int *__restrict__ out_pairs, long cap, u64 *__restrict__ counter) {
+    constexpr int WC = Cfg::WC, WQ = Cfg::WQ, NWC = Cfg::NWC, BC = Cfg::BC, BQ = Cfg::BQ, NW = Cfg::NW,
+                  STAGE = Cfg::STAGE, NLA = Cfg::NLA, NLB = Cfg::NLB, NL = Cfg::NL, NSTAGE = Cfg::NSTAGE, BK = Cfg::BK,
+                  RB = Cfg::RB, CPR = Cfg::CPR, RPI = Cfg::RPI, RP = Cfg::RP, KK = Cfg::KK, SUB = 32 * Cfg::RB;
+    static_assert(BC == BQ && BC / 64 + BQ / 64 <= NW, "square tiles; one wave per 64 inverse lengths of either side");
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    float *inv_a = (float *)(smem + NSTAGE * STAGE);  // [2][BC] inverse lengths of the row tile, by parity of the pair's number
+    float *inv_b = inv_a + 2 * BC;                    // [2][BQ] and of the column tile
+    // pairs are collected here and moved to the global list when the buffer is half full, and at the end
+    int *stage = (int *)(inv_b + 2 * BQ);             // [PAIR_STAGE][2]
+    int *staged = stage + 2 * PAIR_STAGE;             // entries taken (may run past PAIR_STAGE)
+    u64 *flush_slot = (u64 *)(staged + 2);
+    if (threadIdx.x == 0) *staged = 0;
+
+    const int tid = threadIdx.x;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
+    const int wc = wave % NWC, wq = wave / NWC;
+    const int h = lane >> 5, l32 = lane & 31;
+    const int nk = d / BK;
+    const int tiles = (int)((K + BC - 1) / BC);
+
+    PairItems ld_items, cp_items;  // the same sequence twice: the loads run ahead of the MFMAs
+    ld_items.init(tiles, qb);
+    cp_items.init(tiles, qb);
+    int ld_qt = 0, ld_ct = 0, cp_qt = 0, cp_ct = 0;
+    bool ld_more = ld_items.next(ld_qt, ld_ct);
+    if (!ld_more) return;
+    cp_items.next(cp_qt, cp_ct);
+
+    // direct-load addressing (rows past the live ones exist and are never above the threshold)
+    const int lr = lane / CPR, slot = lane % CPR;
+    unsigned a_off[NLA], b_off[NLB];
+#pragma unroll
+    for (int j = 0; j < NLA; ++j) {
+        const int row = (j * NW + wave) * RPI + lr;
+        a_off[j] = (unsigned)(row * d + ((slot ^ ((row / RP) % CPR)) * 8)) * 2u;
+    }
+#pragma unroll
+    for (int j = 0; j < NLB; ++j) b_off[j] = a_off[j];
+    const int sw = (l32 / RP) % CPR;
+    const unsigned lds0 = (unsigned)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)smem;
+    const unsigned row_a = lds0 + (unsigned)(((wc * WC) * 32 + l32) * RB);
+    const unsigned row_b = lds0 + (unsigned)(BC * RB + ((wq * WQ) * 32 + l32) * RB);
+    unsigned so[KK];
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk) so[kk] = (unsigned)(((kk * 2 + h) ^ sw) * 16);
+
+    Acc<false, WC, WQ> acc;
+
+    // loader: slab ld_ks of the pair (ld_qt, ld_ct), the ld_seq-th pair of this workgroup
+    int ld_ks = 0, ld_seq = 0, ld_stage = 0, issued = 0;
+    auto issue = [&]() {
+        unsigned char *sb = smem + ld_stage * STAGE + wave * 1024;
+        const char *ca = (const char *)(C + ((size_t)ld_ct * BC * d + (size_t)ld_ks * BK));
+        const char *cq = (const char *)(C + ((size_t)ld_qt * BQ * d + (size_t)ld_ks * BK));
+        if (ld_ks == 0) {
+            // the inverse lengths of both tiles travel with the pair's first slab
+            if (wave < BC / 64) gload_lds4(invn + (size_t)ld_ct * BC + wave * 64 + lane, inv_a + (ld_seq & 1) * BC + wave * 64);
+            else if (wave < BC / 64 + BQ / 64)
+                gload_lds4(invn + (size_t)ld_qt * BQ + (wave - BC / 64) * 64 + lane, inv_b + (ld_seq & 1) * BQ + (wave - BC / 64) * 64);
+        }
+        static_for<0, NLA>([&](auto jj) {
+            constexpr int j = decltype(jj)::value;
+            unsigned off = a_off[j];
+            asm volatile("" : "+v"(off));
+            gload_lds16(ca + off, sb + j * NW * 1024);
+        });
+        static_for<0, NLB>([&](auto jj) {
+            constexpr int j = decltype(jj)::value;
+            unsigned off = b_off[j];
+            asm volatile("" : "+v"(off));
+            gload_lds16(cq + off, sb + BC * RB + j * NW * 1024);
+        });
+        if (++ld_ks == nk) {
+            ld_ks = 0;
+            ++ld_seq;
+            ld_more = ld_items.next(ld_qt, ld_ct);
+        }
+        if (++ld_stage == NSTAGE) ld_stage = 0;
+        ++issued;
+    };
+
+    constexpr int NF = WC + WQ;
+    bf16x8 af[2][WC], bf[2][WQ];
+    for (int s = 0; s < NSTAGE && ld_more; ++s) issue();
+    if (issued == NSTAGE) vm_wait<(NSTAGE - 1) * NL>();
+    else vm_wait<0>();
+    __syncthreads();
+    lds_frags<SUB>(af[0], bf[0], row_a + so[0], row_b + so[0]);
+
+    int ks = 0, cp_seq = 0, consumed = 0;
+    unsigned sto = 0;
+    for (;;) {
+        const unsigned sto_next = (sto + STAGE == NSTAGE * STAGE) ? 0u : sto + STAGE;
+#pragma unroll
+        for (int kk = 0; kk < KK - 1; ++kk) {
+            lds_frags<SUB>(af[(kk + 1) & 1], bf[(kk + 1) & 1], row_a + sto + so[kk + 1], row_b + sto + so[kk + 1]);
+            lds_wait<NF>(af[kk & 1], bf[kk & 1]);
+            __builtin_amdgcn_sched_barrier(0);
+            if (kk == 0 && ks == 0) {
+                static_for<0, WC>([&](auto ia) {
+                    static_for<0, WQ>([&](auto ib) {
+                        constexpr int A = decltype(ia)::value, B = decltype(ib)::value;
+                        acc.template first<A, B>(af[0][A], bf[0][B]);
+                    });
+                });
+            } else {
+                static_for<0, WC>([&](auto ia) {
+                    static_for<0, WQ>([&](auto ib) {
+                        constexpr int A = decltype(ia)::value, B = decltype(ib)::value;
+                        acc.template mac<A, B>(af[kk & 1][A], bf[kk & 1][B]);
+                    });
+                });
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        lds_wait<0>(af[1], bf[1]);
+        // the next slab has landed: all but the loads of the slabs behind it may still be in flight
+        if (issued - consumed >= NSTAGE) vm_wait<(NSTAGE - 2) * NL>();
+        else vm_wait<0>();
+        __syncthreads();
+        if (ld_more) issue();
+        const bool has_next = issued > consumed + 1;
+        if (has_next) lds_frags<SUB>(af[0], bf[0], row_a + sto_next + so[0], row_b + sto_next + so[0]);
+        __builtin_amdgcn_sched_barrier(0);
+        static_for<0, WC>([&](auto ia) {
+            static_for<0, WQ>([&](auto ib) {
+                constexpr int A = decltype(ia)::value, B = decltype(ib)::value;
+                acc.template mac<A, B>(af[1][A], bf[1][B]);
+            });
+        });
+        __builtin_amdgcn_sched_barrier(0);
+        if (ks == nk - 1) {
+            // pair done: every product above the threshold is a pair (column index < row index)
+            const long c0 = (long)cp_ct * BC, q0 = (long)cp_qt * BQ;
+            const float *inv_t = inv_a + (cp_seq & 1) * BC;
+            const float *inv_q = inv_b + (cp_seq & 1) * BQ;
+            float wi[WQ];
+#pragma unroll
+            for (int b = 0; b < WQ; ++b) wi[b] = inv_q[(wq * WQ + b) * 32 + l32];
+            static_for<0, WC>([&](auto ia) {
+                constexpr int A = decltype(ia)::value;
+                const int rb = (wc * WC + A) * 32;
+                f32x4 w[4];
+#pragma unroll
+                for (int g = 0; g < 4; ++g) w[g] = *(const f32x4 *)(inv_t + rb + 8 * g + 4 * h);
+                static_for<0, WQ>([&](auto ib) {
+                    constexpr int B = decltype(ib)::value;
+                    float m = -INFINITY;
+                    static_for<0, 16>([&](auto ii) {
+                        constexpr int I = decltype(ii)::value;
+                        m = fmaxf(m, acc.template get<A, B, I>() * w[I >> 2][I & 3]);
+                    });
+                    if (__ballot(m * wi[B] > threshold) != 0) {
+                        const long icol = q0 + (wq * WQ + B) * 32 + l32;
+                        const long jrow0 = c0 + rb + 4 * h;  // register I holds row jrow0 + 8 * (I / 4) + I % 4
+                        unsigned found = 0;
+                        static_for<0, 16>([&](auto ii) {
+                            constexpr int I = decltype(ii)::value;
+                            const float sim = acc.template get<A, B, I>() * w[I >> 2][I & 3] * wi[B];
+                            if (sim > threshold && icol < jrow0 + 8 * (I >> 2) + (I & 3)) found |= 1u << I;
+                        });
+                        emit_pairs_staged(found, (int)icol, [&](int I) { return (int)(jrow0 + 8 * (I >> 2) + (I & 3)); }, stage,
+                                          staged, PAIR_STAGE, out_pairs, cap, counter);
+                    }
+                });
+            });
+            ks = 0;
+            ++cp_seq;
+            cp_items.next(cp_qt, cp_ct);
+            // the pairs of this tile pair are staged (own LDS traffic done, then the barrier by hand: the
+            // compiler's barrier would also wait for the direct loads in flight)
+            asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+            if (*staged > PAIR_STAGE / 2) flush_staged_pairs(stage, staged, PAIR_STAGE, flush_slot, out_pairs, cap, counter);
+        } else {
+            ++ks;
+        }
+        ++consumed;
+        sto = sto_next;
+        if (!has_next) break;
+    }
+    flush_staged_pairs(stage, staged, PAIR_STAGE, flush_slot, out_pairs, cap, counter);
+}
+
 // Fragments at fixed registers, for the wide kernel: a value that the compiler knows about can be
 // copied or moved by it at any time, also while the LDS read that produces it is still in flight.
 // With one wave per SIMD the reads must stay in flight across branches and the loop edge, so the
@@ -549,11 +745,9 @@ struct WideCfg {
     static_assert(WIDE_FRAG0 + 4 * WC + 8 * WQ == 256, "fragments fill the registers behind the allocator's share");
 };
 
-template <int MODE>
 __global__ __launch_bounds__(WideCfg::NT) __attribute__((amdgpu_waves_per_eu(1, 1), amdgpu_num_vgpr(WIDE_FRAG0))) void k_lookup_wide(
     const bf16_t *__restrict__ Q, const bf16_t *__restrict__ C, const float *__restrict__ invn, long n, long K, int d,
-    int tiles_per_slice, int slices, int nqt, int qb, u64 *__restrict__ keys, float threshold,
-    int *__restrict__ out_pairs, long cap, u64 *__restrict__ counter) {
+    int tiles_per_slice, int slices, int nqt, int qb, u64 *__restrict__ keys) {
     typedef WideCfg Cfg;
     constexpr int WC = Cfg::WC, WQ = Cfg::WQ, NWC = Cfg::NWC, BC = Cfg::BC, BQ = Cfg::BQ, NT = Cfg::NT, NW = Cfg::NW,
                   STAGE = Cfg::STAGE, NLA = Cfg::NLA, NL = Cfg::NL, BK = Cfg::BK, RB = Cfg::RB, KK = Cfg::KK,
@@ -567,7 +761,7 @@ __global__ __launch_bounds__(WideCfg::NT) __attribute__((amdgpu_waves_per_eu(1, 
     const int h = lane >> 5, l32 = lane & 31;
 
     int qt, s, ct_begin, ct_end;
-    if (!pipe_map_block<MODE, BC>(K, tiles_per_slice, slices, nqt, qb, qt, s, ct_begin, ct_end)) return;
+    if (!pipe_map_block<BC>(K, tiles_per_slice, slices, nqt, qb, qt, s, ct_begin, ct_end)) return;
     const long q0 = (long)qt * BQ;
     const int nk = d / BK;
     const int T = (ct_end - ct_begin) * nk;  // slabs this workgroup walks through
@@ -600,9 +794,6 @@ __global__ __launch_bounds__(WideCfg::NT) __attribute__((amdgpu_waves_per_eu(1, 
         bv[b] = -INFINITY;
         bb[b] = 0xFFFFFFFFu;
     }
-    float wi[WQ];  // pairs: 1/|c| of this lane's columns (NaN past the live centroids)
-#pragma unroll
-    for (int b = 0; b < WQ; ++b) wi[b] = MODE == PIPE_PAIRS ? invn[q0 + (wq * WQ + b) * 32 + l32] : 0.f;
     Acc<true, WC, WQ> acc;
     acc.reserve();
 
@@ -629,8 +820,7 @@ __global__ __launch_bounds__(WideCfg::NT) __attribute__((amdgpu_waves_per_eu(1, 
             unsigned off = a_voff;
             asm volatile("" : "+v"(off));  // keeps the 32-bit offset next to its use: scalar base + lane offset
             const u32x4 *src = (const u32x4 *)(ld_c + (size_t)j * 64 * d + off);
-            if constexpr (MODE == PIPE_LOOKUP) G[p][j] = __builtin_nontemporal_load(src);
-            else G[p][j] = *src;
+            G[p][j] = __builtin_nontemporal_load(src);
         } else {
             // (computed here every time: eight more loop-invariant registers would not fit)
             int row = row0;
@@ -765,23 +955,9 @@ __global__ __launch_bounds__(WideCfg::NT) __attribute__((amdgpu_waves_per_eu(1, 
                         constexpr int I = decltype(ii)::value;
                         m = fmaxf(m, acc.template get<A, B, I>() * w[I >> 2][I & 3]);
                     });
-                    if (MODE == PIPE_LOOKUP) {
-                        if (m > bv[B]) {
-                            bv[B] = m;
-                            bb[B] = blk;
-                        }
-                    } else if (__ballot(m * wi[B] > threshold) != 0) {
-                        // rare: some product of this 32 x 32 block is above the threshold
-                        const long icol = q0 + (wq * WQ + B) * 32 + l32;
-                        const long jrow0 = c0 + rb + 4 * h;  // register I holds row jrow0 + 8 * (I / 4) + I % 4
-                        unsigned found = 0;
-                        static_for<0, 16>([&](auto ii) __attribute__((always_inline)) {
-                            constexpr int I = decltype(ii)::value;
-                            const float sim = acc.template get<A, B, I>() * w[I >> 2][I & 3] * wi[B];
-                            if (sim > threshold && icol < jrow0 + 8 * (I >> 2) + (I & 3)) found |= 1u << I;
-                        });
-                        emit_pairs(found, (int)icol, [&](int I) __attribute__((always_inline)) { return (int)(jrow0 + 8 * (I >> 2) + (I & 3)); },
-                                   out_pairs, cap, counter);
+                    if (m > bv[B]) {
+                        bv[B] = m;
+                        bb[B] = blk;
                     }
                 });
             });
@@ -799,7 +975,6 @@ __global__ __launch_bounds__(WideCfg::NT) __attribute__((amdgpu_waves_per_eu(1, 
     if (t < T) slab(IC<0>{});
     asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");  // reads, loads and writes of the tail have landed
     lds_barrier();
-    if (MODE == PIPE_PAIRS) return;
     pipe_reduce_keys<WQ, NWC, BQ, NT>(bv, bb, smem, wc, wq, h, l32, tid, q0, n, slices, s, keys);
 }
 
@@ -875,28 +1050,28 @@ template <class Cfg>
 static int launch_cfg(siso_cache *c, const void *queries, long n, const PipePlan &p) {
     static bool attr_done = false;
     if (!attr_done) {
-        hipError_t e = hipFuncSetAttribute((const void *)k_lookup_pipe<Cfg, PIPE_LOOKUP>,
+        hipError_t e = hipFuncSetAttribute((const void *)k_lookup_pipe<Cfg>,
                                            hipFuncAttributeMaxDynamicSharedMemorySize, Cfg::LDS_BYTES);
         if (e != hipSuccess) return siso_check_hip(c, e, "hipFuncSetAttribute(k_lookup_pipe)");
         attr_done = true;
     }
-    hipLaunchKernelGGL((k_lookup_pipe<Cfg, PIPE_LOOKUP>), dim3((unsigned)p.grid), dim3(Cfg::NT), Cfg::LDS_BYTES,
+    hipLaunchKernelGGL((k_lookup_pipe<Cfg>), dim3((unsigned)p.grid), dim3(Cfg::NT), Cfg::LDS_BYTES,
                        c->stream, (const bf16_t *)queries, (const bf16_t *)c->cent, c->invn, n, c->count, c->dim,
-                       p.tiles_per_slice, p.slices, p.nqt, p.qb, c->keys, 0.f, (int *)nullptr, 0L, (u64 *)nullptr);
+                       p.tiles_per_slice, p.slices, p.nqt, p.qb, c->keys);
     return siso_check_hip(c, hipGetLastError(), "k_lookup_pipe");
 }
 
 static int launch_wide(siso_cache *c, const void *queries, long n, const PipePlan &p) {
     static bool attr_done = false;
     if (!attr_done) {
-        hipError_t e = hipFuncSetAttribute((const void *)k_lookup_wide<PIPE_LOOKUP>,
+        hipError_t e = hipFuncSetAttribute((const void *)k_lookup_wide,
                                            hipFuncAttributeMaxDynamicSharedMemorySize, WideCfg::LDS_BYTES);
         if (e != hipSuccess) return siso_check_hip(c, e, "hipFuncSetAttribute(k_lookup_wide)");
         attr_done = true;
     }
-    hipLaunchKernelGGL((k_lookup_wide<PIPE_LOOKUP>), dim3((unsigned)p.grid), dim3(WideCfg::NT), WideCfg::LDS_BYTES, c->stream,
+    hipLaunchKernelGGL((k_lookup_wide), dim3((unsigned)p.grid), dim3(WideCfg::NT), WideCfg::LDS_BYTES, c->stream,
                        (const bf16_t *)queries, (const bf16_t *)c->cent, c->invn, n, c->count, c->dim, p.tiles_per_slice,
-                       p.slices, p.nqt, p.qb, c->keys, 0.f, (int *)nullptr, 0L, (u64 *)nullptr);
+                       p.slices, p.nqt, p.qb, c->keys);
     return siso_check_hip(c, hipGetLastError(), "k_lookup_wide");
 }
 
@@ -945,26 +1120,20 @@ int siso_pairs_mfma_launch(siso_cache *c, const void *rows, const float *invn, l
                            int *out_pairs, long cap, u64 *counter) {
     typedef PipeLarge Cfg;
     if (((uintptr_t)rows & 15) != 0) return siso_fail(c, SISO_EINVAL, "pair search: rows must be 16-byte aligned");
+    // one stream of tile pairs per workgroup, one workgroup per compute unit
     const long T = (count + Cfg::BC - 1) / Cfg::BC;
-    // one tile pair per workgroup (the triangle balances best in small pieces), blocks of 8 tiles x 4
-    // slices per XCD; workgroups whose slice lies left of their own tile exit at once
-    long tps = c->opt_tiles_per_slice > 0 ? c->opt_tiles_per_slice : 1;
-    if (tps > T) tps = T;
-    const long slices = (T + tps - 1) / tps;
+    if (T > 1000000) return siso_fail(c, SISO_EINVAL, "pair search: too many tiles");
     int qb = 8;
     while (qb > 1 && qb > T) qb >>= 1;
-    while (qb < 32 && qb * 2 <= T && slices < 32 / qb) qb <<= 1;
-    const long grid = pipe_grid(slices, T, qb);
-    if (grid > 2147483647L) return siso_fail(c, SISO_EINVAL, "pair search: too many tiles");
-    static bool attr_done = false;
-    if (!attr_done) {
-        hipError_t e = hipFuncSetAttribute((const void *)k_lookup_pipe<Cfg, PIPE_PAIRS>,
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, Cfg::LDS_BYTES);
-        if (e != hipSuccess) return siso_check_hip(c, e, "hipFuncSetAttribute(pair search)");
-        attr_done = true;
+    constexpr int lds = Cfg::NSTAGE * Cfg::STAGE + 2 * Cfg::BC * 4 + 2 * Cfg::BQ * 4 + PAIR_STAGE * 8 + 16;
+    static_assert(lds <= 160 * 1024, "fits in LDS");
+    static bool stream_attr_done = false;
+    if (!stream_attr_done) {
+        hipError_t e = hipFuncSetAttribute((const void *)k_pairs_stream<Cfg>, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+        if (e != hipSuccess) return siso_check_hip(c, e, "hipFuncSetAttribute(k_pairs_stream)");
+        stream_attr_done = true;
     }
-    hipLaunchKernelGGL((k_lookup_pipe<Cfg, PIPE_PAIRS>), dim3((unsigned)grid), dim3(Cfg::NT), Cfg::LDS_BYTES, c->stream,
-                       (const bf16_t *)rows, (const bf16_t *)rows, invn, count, count, c->dim, (int)tps, (int)slices,
-                       (int)T, qb, (u64 *)nullptr, threshold, out_pairs, cap, counter);
-    return siso_check_hip(c, hipGetLastError(), "pair search kernel");
+    hipLaunchKernelGGL((k_pairs_stream<Cfg>), dim3(256), dim3(Cfg::NT), lds, c->stream, (const bf16_t *)rows, invn, count,
+                       c->dim, qb, threshold, out_pairs, cap, counter);
+    return siso_check_hip(c, hipGetLastError(), "k_pairs_stream");
 }

@@ -184,6 +184,63 @@ __device__ __forceinline__ void emit_pairs(unsigned mask, int i, RowOf row_of, i
     }
 }
 
+// The same with a staging buffer of the workgroup in LDS (stage[room][2], *staged = entries taken):
+// the wave takes its slots with one LDS atomic, which costs a fraction of the round trip of a global
+// one; what does not fit any more goes straight to the global list.  Every lane must call it.
+template <class RowOf>
+__device__ __forceinline__ void emit_pairs_staged(unsigned mask, int i, RowOf row_of, int *stage, int *staged, int room,
+                                                  int *out, long cap, u64 *counter) {
+    const int lane = threadIdx.x & 63;
+    const int cnt = __popc(mask);
+    int incl = cnt;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        const int t = __shfl_up(incl, off);
+        if (lane >= off) incl += t;
+    }
+    const int total = __shfl(incl, 63);
+    if (total == 0) return;
+    int base = 0;
+    if (lane == 63) base = atomicAdd(staged, total);
+    base = __shfl(base, 63);
+    int pos = base + incl - cnt;
+    unsigned rest = 0;  // pairs of this lane that found no room
+    while (mask != 0) {
+        const int I = __ffs((int)mask) - 1;
+        mask &= mask - 1;
+        if (pos < room) {
+            stage[2 * pos] = i;
+            stage[2 * pos + 1] = row_of(I);
+        } else {
+            rest |= 1u << I;
+        }
+        ++pos;
+    }
+    if (base + total > room) emit_pairs(rest, i, row_of, out, cap, counter);  // uniform over the wave
+}
+
+// Move the staged pairs of the workgroup to the global list and empty the buffer.  Every thread of
+// the workgroup must call it (it synchronises); `slot` = one u64 of LDS for the broadcast.
+__device__ __forceinline__ void flush_staged_pairs(const int *stage, int *staged, int room, u64 *slot, int *out, long cap,
+                                                   u64 *counter) {
+    __syncthreads();
+    const int n = *staged < room ? *staged : room;
+    if (threadIdx.x == 0 && n > 0) *slot = atomicAdd(counter, (u64)n);
+    __syncthreads();
+    if (n > 0) {
+        const u64 base = *slot;
+        for (int p = threadIdx.x; p < n; p += blockDim.x) {
+            if (base + (u64)p < (u64)cap) {
+                out[2 * (base + p)] = stage[2 * p];
+                out[2 * (base + p) + 1] = stage[2 * p + 1];
+            }
+        }
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) *staged = 0;
+    __syncthreads();
+}
+
 // ----------------------------------------------------------------------------
 // host-side plumbing shared by the translation units
 // ----------------------------------------------------------------------------
