@@ -205,3 +205,27 @@ def test_merge_apply_chains_and_errors(siso, oracle):
     one = siso.SisoCache(d, 2, siso.F32)
     one.load(to_dev(rows[:1], "f32"))
     assert one.merge(0.5, cap=4)[1] == 0
+
+
+def test_merge_dense_pairs_overflow_the_staging_buffer(siso, oracle):
+    """Four groups of 300 exact copies: every tile pair holds tens of thousands of pairs, far more than a
+    workgroup stages at a time, so the staging buffer fills, spills and is flushed again and again."""
+    dim, groups, copies = 128, 4, 300
+    print(f"case: dense merge dim={dim} K={groups * copies}", flush=True)
+    base = W.to_storage(W.uniform_directions(61, 3, groups, dim), "bf16")
+    rows = np.repeat(base, copies, axis=0)[np.random.default_rng(62).permutation(groups * copies)]
+    K = rows.shape[0]
+    cache = siso.SisoCache(dim, K, siso.BF16)
+    cache.load(to_dev(rows, "bf16"))
+    oc = oracle.OracleCache(dim, K, "bf16")
+    oc.load(rows)
+    want, total = oc.merge(0.9)
+    assert total == groups * copies * (copies - 1) // 2
+    got, gtotal = cache.merge(0.9, cap=total)
+    assert gtotal == total
+    assert np.array_equal(sorted_pairs(got.cpu().numpy()), want)
+    # a cap in the middle of it all: full count, exactly cap valid pairs, no duplicates
+    few, t2 = cache.merge(0.9, cap=5000)
+    few = few.cpu().numpy()
+    assert t2 == total and few.shape[0] == 5000 and len(np.unique(few, axis=0)) == 5000
+    assert set(map(tuple, few)) <= set(map(tuple, want))
