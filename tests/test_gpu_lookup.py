@@ -54,7 +54,8 @@ def test_scalar_path_ragged_shapes(siso, oracle, dtype, dim, K, n):
 
 
 @pytest.mark.parametrize("cfg", [1, 2, 3, 4, 5])
-@pytest.mark.parametrize("dim,K,n,tps", [(128, 5000, 300, 0), (768, 2049, 513, 3), (192, 700, 1, 1), (1024, 1500, 257, 2)])
+@pytest.mark.parametrize("dim,K,n,tps", [(128, 5000, 300, 0), (768, 2049, 513, 3), (192, 700, 1, 1), (1024, 1500, 257, 2),
+                                          (4096, 600, 130, 0), (320, 37, 700, 0), (64 * 7, 3000, 2000, 5)])
 def test_mfma_path_vs_oracle(siso, oracle, cfg, dim, K, n, tps):
     print(f"case: mfma cfg={cfg} dim={dim} K={K} n={n} tiles_per_slice={tps}", flush=True)
     wl = W.c2_mid(n_clusters=128, per_cluster=(K + 127) // 128, n_queries=n, dim=dim, seed=32 + cfg)
