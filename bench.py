@@ -46,6 +46,21 @@ def measured_traffic(workload):
     return None
 
 
+def add_measured_peak(siso, roof):
+    """Beside the published peak: what a bare MFMA loop (random operands, as real data) or a bare streaming
+    read reaches on this very chip, measured now with the library's probe, and the fraction of that."""
+    try:
+        if roof["bound"] == "mfma":
+            roof["measured_peak"] = siso.probe(0)
+            roof["measured_peak_constant_operands"] = siso.probe(1)
+        else:
+            roof["measured_peak"] = siso.probe(2)
+        roof["frac_of_measured_peak"] = roof["achieved"] / roof["measured_peak"]
+    except Exception as e:  # the probe is an extra: the line stands without it
+        roof["measured_peak"] = None
+        roof["measured_peak_error"] = str(e)
+
+
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -148,6 +163,7 @@ def main():
                     "roofline": {"bound": "mfma", "achieved": flop / avg_s / 1e12, "peak": PEAK_BF16_TFLOPS,
                                  "unit": "TFLOP/s", "frac": flop / avg_s / 1e12 / PEAK_BF16_TFLOPS,
                                  "traffic": measured_traffic(name), "kernel_ms": avg_s * 1e3}})
+        add_measured_peak(siso, out["roofline"])
         print(json.dumps(out))
         return
 
@@ -257,6 +273,7 @@ def main():
                            "offline_merge": merge_info, "t2h": t2h_info, "refresh": refresh_info,
                            "generate_s": round(gen_s, 1)},
                 "roofline": roof})
+    add_measured_peak(siso, out["roofline"])
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl, nb, args.cpu_seconds)
     print(json.dumps(out))

@@ -263,6 +263,18 @@ int siso_adjust_threshold(const float *thetas, int m, int index, double wait_est
 int siso_profile_enable(siso_cache *c, int on);
 int siso_profile_read(siso_cache *c, double *total_ms, long *launches);
 
+/*
+ * What this chip delivers, for the roofline lines of a benchmark (no cache
+ * needed; runs on the null stream of the current device, allocates and frees
+ * its own memory, synchronises; takes a fraction of a second):
+ *   which = 0: a register-resident bf16 MFMA loop on random operands, TFLOP/s
+ *              (the clock the chip sustains depends on how much operands toggle);
+ *   which = 1: the same on constant operands, TFLOP/s;
+ *   which = 2: a plain streaming read of 2 GiB from HBM, GB/s.
+ * *out_value (host pointer) receives the rate.  SISO_OK, SISO_EINVAL or SISO_EHIP.
+ */
+int siso_probe(int which, double *out_value);
+
 /* Message for the last error on this cache ("" if none).  Owned by the cache. */
 const char *siso_last_error(const siso_cache *c);
 

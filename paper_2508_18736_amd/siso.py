@@ -48,6 +48,7 @@ SYMBOLS = {
     "siso_profile_enable": ([_vp, _it], _it),
     "siso_profile_read": ([_vp, C.POINTER(C.c_double), C.POINTER(C.c_long)], _it),
     "siso_last_error": ([_vp], C.c_char_p),
+    "siso_probe": ([_it, C.POINTER(C.c_double)], _it),
     "siso_refresh": ([_vp, _vp, _vp, _lg, _fl, _lg, _vp], _it),
     "siso_export_meta": ([_vp, _vp, _vp], _it),
     "siso_t2h": ([_vp, _vp, _lg, _vp, _it, _vp], _it),
@@ -85,6 +86,16 @@ def adjust_threshold(thetas, index: int, wait_estimated: float, wait_measured: f
     th = np.ascontiguousarray(thetas, dtype=np.float32)
     return int(_lib.siso_adjust_threshold(th.ctypes.data_as(_vp), th.shape[0], int(index), float(wait_estimated),
                                           float(wait_measured)))
+
+
+def probe(which: int) -> float:
+    """What the chip delivers: 0 = bf16 MFMA loop, random operands (TFLOP/s); 1 = the same with constant
+    operands; 2 = streaming read from HBM (GB/s).  Runs on the current device's null stream."""
+    v = C.c_double(0.0)
+    rc = _lib.siso_probe(int(which), C.byref(v))
+    if rc != OK:
+        raise SisoError(rc, "siso_probe failed")
+    return float(v.value)
 
 
 class SisoError(RuntimeError):

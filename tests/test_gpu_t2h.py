@@ -86,3 +86,14 @@ def test_t2h_edges(siso):
     assert cache.t2h(q, thetas[:0]).tolist() == []
     with pytest.raises(siso.SisoError):
         cache.t2h(q, np.zeros(2000, np.float32))  # more thresholds than the table holds
+
+
+def test_probe_reports_plausible_rates(siso):
+    """The chip's own ceilings, as the benchmark reports them beside the published peaks."""
+    random_ops, constant_ops, stream = siso.probe(0), siso.probe(1), siso.probe(2)
+    print(f"  MFMA loop: {random_ops:.0f} TFLOP/s on random operands, {constant_ops:.0f} on constant ones; "
+          f"streaming read {stream:.0f} GB/s", flush=True)
+    assert 500 < random_ops <= 2600 and random_ops <= constant_ops * 1.05 <= 2600 * 1.05
+    assert 2000 < stream <= 8200
+    with pytest.raises(siso.SisoError):
+        siso.probe(3)
