@@ -654,6 +654,125 @@ int oracle_adjust_threshold(const float *thetas, int m, int index, double w_est,
     return next < 0 ? index : next;
 }
 
+/* ------------------------------------------------------------------------ */
+/* Clustering of the query log into the centroid repository (section 4.1)    */
+/* ------------------------------------------------------------------------ */
+
+/*
+ * Community detection at the clustering threshold theta_c ("Selecting a
+ * clustering algorithm"), followed by "Keeping centroids in a repository": every
+ * cluster gets an id, its centroid (the average of its members, section 3.1)
+ * and cluster_size (the number of its members).  The paper names the algorithm
+ * and its threshold and cites it; the steps below are that published greedy
+ * scheme, a reading listed in the design notes:
+ *   1. two vectors are neighbours when their cosine exceeds theta_c (strictly,
+ *      as every threshold test of the paper);
+ *   2. the candidate community of vector i is i together with its neighbours;
+ *      candidates with fewer than min_size vectors are dropped;
+ *   3. the candidates are taken by size, largest first, equal sizes by index;
+ *   4. of a candidate the vectors not yet in a cluster remain (i itself may be
+ *      gone already); if at least min_size remain they become the next cluster
+ *      (ids count up from 0 in this order), otherwise the candidate is dropped;
+ *   5. vectors that end in no cluster get label -1.
+ * Then the cache `c` is replaced by the clusters: row id = cluster id, mean =
+ * average of the unit-length members, size = cluster_size = their number,
+ * stored centroid = mean / |mean| rounded to the storage type (a zero row if the
+ * mean has no length), access_count 0.
+ *
+ * out_label [n], out_seed [number of clusters] (the vector whose candidate
+ * formed the cluster; room for n) and min_margin (the smallest |cosine -
+ * theta_c| over all pairs) may each be NULL.  Returns the number of clusters;
+ * -1 bad arguments or a vector that is not finite or has no length; -2 out of
+ * memory; -3 more clusters than the capacity of c (nothing changed then).
+ */
+long oracle_cluster(oracle_cache *c, const void *vectors, long n, float theta_c, int min_size,
+                    int *out_label, int *out_seed, double *min_margin) {
+    if (!c || n < 0 || min_size < 1 || (n > 0 && !vectors)) return -1;
+    const int d = c->dim, dt = c->dtype;
+    const long n1 = n > 0 ? n : 1;
+    double *norm = (double *)malloc((size_t)n1 * sizeof(double));
+    unsigned char *adj = (unsigned char *)calloc((size_t)n1 * (size_t)n1, 1); /* adj[i*n+j] = neighbours */
+    long *size = (long *)calloc((size_t)n1, sizeof(long));
+    int *label = (int *)malloc((size_t)n1 * sizeof(int));
+    int *seed = (int *)malloc((size_t)n1 * sizeof(int));
+    if (!norm || !adj || !size || !label || !seed) {
+        free(norm); free(adj); free(size); free(label); free(seed);
+        return -2;
+    }
+    long rc = 0;
+    for (long i = 0; i < n; ++i) {
+        norm[i] = row_finite(vectors, dt, i, d) ? row_norm(vectors, dt, i, d) : 0.0;
+        if (!(norm[i] > 0.0) || !isfinite(norm[i])) rc = -1;
+    }
+    double margin = INFINITY;
+    if (rc == 0) {
+        /* step 1: the neighbour relation */
+#ifdef _OPENMP
+#pragma omp parallel for schedule(dynamic, 8) reduction(min : margin)
+#endif
+        for (long i = 0; i < n; ++i)
+            for (long j = i + 1; j < n; ++j) {
+                const double s = cosine(vectors, i, norm[i], vectors, j, norm[j], dt, d);
+                if (s > (double)theta_c) adj[(size_t)i * n + j] = adj[(size_t)j * n + i] = 1;
+                const double g = fabs(s - (double)theta_c);
+                if (g < margin) margin = g;
+            }
+        /* step 2: candidate sizes */
+        for (long i = 0; i < n; ++i) {
+            size[i] = 1;
+            for (long j = 0; j < n; ++j) size[i] += adj[(size_t)i * n + j];
+            label[i] = -1;
+        }
+        /* steps 3 and 4: largest candidate first, equal sizes in index order */
+        long clusters = 0;
+        for (long s = n; s >= (long)min_size; --s)
+            for (long i = 0; i < n; ++i) {
+                if (size[i] != s) continue;
+                long left = label[i] < 0 ? 1 : 0;
+                for (long j = 0; j < n; ++j)
+                    if (adj[(size_t)i * n + j] && label[j] < 0) ++left;
+                if (left < (long)min_size) continue;
+                if (label[i] < 0) label[i] = (int)clusters;
+                for (long j = 0; j < n; ++j)
+                    if (adj[(size_t)i * n + j] && label[j] < 0) label[j] = (int)clusters;
+                seed[clusters++] = (int)i;
+            }
+        rc = clusters;
+        if (clusters > c->capacity) rc = -3;
+    }
+    if (rc >= 0) {
+        /* the repository: centroid = average of the members, cluster_size = their number */
+        const long clusters = rc;
+        for (long k = 0; k < clusters; ++k) {
+            double *m = c->mean + (size_t)k * d;
+            long members = 0;
+            for (int t = 0; t < d; ++t) m[t] = 0.0;
+            for (long i = 0; i < n; ++i) {
+                if (label[i] != (int)k) continue;
+                for (int t = 0; t < d; ++t) m[t] += widen(vectors, dt, (size_t)i * d + t) / norm[i];
+                ++members;
+            }
+            double sq = 0.0;
+            for (int t = 0; t < d; ++t) {
+                m[t] /= (double)members;
+                sq += m[t] * m[t];
+            }
+            const double len = sqrt(sq);
+            for (int t = 0; t < d; ++t) store(c->cent, dt, (size_t)k * d + t, len > 0.0 ? m[t] / len : 0.0);
+            c->size[k] = (int)members;
+            c->locality[k] = (float)members;
+            c->access[k] = 0;
+        }
+        c->count = clusters;
+        if (out_label) memcpy(out_label, label, (size_t)n * sizeof(int));
+        if (out_seed) memcpy(out_seed, seed, (size_t)clusters * sizeof(int));
+        if (min_margin) *min_margin = margin;
+    }
+    free(norm); free(adj); free(size); free(label); free(seed);
+    return rc;
+}
+
+
 /* Number of threads the parallel loops use. */
 int oracle_threads(void) {
 #ifdef _OPENMP

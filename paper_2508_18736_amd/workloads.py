@@ -350,3 +350,46 @@ FULL_CONFIGS = {
     "c4_stream": c4_stream,
     "c5_merge": c5_merge,
 }
+
+
+def query_log_chains(n_chains: int = 24, chain_len: int = 5, members_lo: int = 2, members_hi: int = 12,
+                     n_noise: int = 64, dim: int = 256, step_cos: float = 0.90, sigma: float = 0.1,
+                     dtype: str = "bf16", seed: int = BASE_SEED + 8):
+    """A query log for clustering: topics whose members are jittered copies of a topic direction
+    (noise of total length ``sigma``: cosine to the direction about ``1/sqrt(1+sigma^2)``), the
+    topics strung into chains in which neighbouring directions have cosine ``step_cos`` and
+    directions two apart about ``step_cos**2``; plus ``n_noise`` unrelated directions; all in a
+    seeded random order.  With the defaults members of one topic have cosine about 0.99, members
+    of neighbouring topics about 0.89, two apart at most 0.84: at a clustering threshold of 0.86
+    neighbourhoods overlap along a chain, so what a greedy clustering returns depends on its
+    order, and no cosine comes close to the threshold.  Returns ``(rows in the storage type,
+    topic of every row, -1 for the unrelated ones)``."""
+    r = _rng(seed, _STREAM_MISC, 11)
+    topics = n_chains * chain_len
+    start = uniform_directions(seed, _STREAM_MEANS, n_chains, dim)
+    turn = uniform_directions(seed, _STREAM_MEMBERS, topics, dim)
+    dirs = np.empty((topics, dim), np.float32)
+    side = np.float32(np.sqrt(1.0 - step_cos * step_cos))
+    for c in range(n_chains):
+        cur = start[c]
+        for s in range(chain_len):
+            t = c * chain_len + s
+            if s > 0:
+                u = turn[t] - np.dot(turn[t], cur) * cur          # a direction at right angles to the last one
+                u /= np.sqrt(np.dot(u, u))
+                cur = np.float32(step_cos) * cur + side * u
+                cur /= np.sqrt(np.dot(cur, cur))
+            dirs[t] = cur
+    members = r.integers(members_lo, members_hi + 1, size=topics)
+    topic_of = np.concatenate([np.repeat(np.arange(topics), members), np.full(n_noise, -1)]).astype(np.int64)
+    base = np.concatenate([dirs, uniform_directions(seed, _STREAM_PERM, max(n_noise, 1), dim)[:n_noise]])
+    rows_of = np.where(topic_of >= 0, topic_of, topics + np.arange(len(topic_of)) - int(members.sum()))
+    perm = r.permutation(len(topic_of))
+    topic_of, rows_of = topic_of[perm], rows_of[perm]
+    noise = np.where(topic_of >= 0, np.float32(sigma), np.float32(0.0))
+    out = np.empty((len(topic_of), dim), dtype=np.float32 if dtype == "f32" else np.uint16)
+    g = _rng(seed, _STREAM_QUERIES, 1).standard_normal((len(topic_of), dim), dtype=np.float32)
+    g *= (noise / np.sqrt(np.float32(dim)))[:, None]
+    g += base[rows_of]
+    out[:] = to_storage(_unit_rows(g), dtype)
+    return out, topic_of
