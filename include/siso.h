@@ -214,6 +214,41 @@ int siso_refresh(siso_cache *c, const void *repo, const float *repo_size, long r
 int siso_export_meta(siso_cache *c, float *cluster_size, unsigned *access_count);
 
 /*
+ * Clustering of a query log into the centroid repository: section 4.1
+ * ("Selecting a clustering algorithm": community detection at the clustering
+ * threshold; "Keeping centroids in a repository": id, centroid, cluster_size)
+ * with the centroid of section 3.1, the average of the group.
+ *
+ *   vectors:   device pointer, [n][dim] query vectors, element type of the
+ *              cache, 16-byte aligned, every one finite and of non-zero length
+ *              (SISO_EINVAL otherwise, nothing changed).
+ *   theta_c:   clustering threshold;  min_size: smallest cluster kept (>= 1).
+ *   out_label: device pointer, n ints, or NULL: cluster id of every vector,
+ *              -1 for a vector that ends in no cluster.
+ *   out_stats: HOST pointer to 2 longs or NULL: pairs above the threshold,
+ *              vectors that ended in a cluster.
+ * Two vectors are neighbours when their cosine exceeds theta_c (strictly).  The
+ * candidate community of a vector is itself with its neighbours; candidates
+ * are taken by size, largest first, equal sizes by index; of a candidate the
+ * vectors that no earlier cluster holds remain (the vector it was built around
+ * may be gone), and if at least min_size remain they become the next cluster;
+ * ids count up from 0 in that order.
+ * Afterwards the cache `c` IS the repository: row id holds cluster id, mean =
+ * average of the unit-length members (summed in ascending index), size =
+ * cluster_size = their number, stored centroid = mean / |mean| rounded to the
+ * element type (a zero row if the mean has no length), access_count 0; what
+ * the cache held before is gone.  siso_export / siso_export_meta hand the rows
+ * and sizes on, e.g. to siso_refresh of the serving cache.
+ * Returns the number of clusters; SISO_ECAPACITY (nothing changed) if that
+ * exceeds the capacity of `c`; other negative values are error codes.
+ * The all-pairs similarity and the averages run on the GPU; the choice of the
+ * communities walks the list of pairs on the host.  Allocates temporary device
+ * memory (the vectors once more, 8 bytes per pair).  Synchronises.
+ */
+long siso_cluster(siso_cache *c, const void *vectors, long n, float theta_c, int min_size, int *out_label,
+                  long *out_stats);
+
+/*
  * Threshold-to-hit-ratio (T2H) table (section 4.3, "Adjusting theta_R to meet
  * SLO"): test lookups of a sample of queries, counted against a sweep of
  * retrieval thresholds (the paper sweeps 0.98 down to 0.6).
