@@ -155,11 +155,20 @@ def main():
         t1 = time.perf_counter()
         cache.merge_apply(pairs)
         apply_s = time.perf_counter() - t1
+        # the same rows taken as a query log: community detection into a repository (second use of the pair search)
+        repo = siso.SisoCache(d, K, siso.BF16)
+        rows = to_dev(wl.centroids, "bf16")
+        repo.cluster(rows, 0.86, 2)
+        t1 = time.perf_counter()
+        _, clusters, cluster_pairs = repo.cluster(rows, 0.86, 2)
+        cluster_s = time.perf_counter() - t1
         out.update({"metric": "merge_centroid_rows_per_s", "value": K * steps / dt, "unit": "rows/s",
                     "steps": steps, "warmup": warmup, "ms_per_step": dt / steps * 1e3,
                     "config": {"workload": "c5_merge", "centroids": K, "dim": d, "threshold": theta,
                                "pairs": int(total), "groups_after_merge": cache.count,
-                               "merge_apply_ms": apply_s * 1e3},
+                               "merge_apply_ms": apply_s * 1e3,
+                               "cluster": {"vectors": K, "theta_c": 0.86, "min_size": 2, "clusters": clusters,
+                                           "pairs": cluster_pairs, "ms": cluster_s * 1e3}},
                     "roofline": {"bound": "mfma", "achieved": flop / avg_s / 1e12, "peak": PEAK_BF16_TFLOPS,
                                  "unit": "TFLOP/s", "frac": flop / avg_s / 1e12 / PEAK_BF16_TFLOPS,
                                  "traffic": measured_traffic(name), "kernel_ms": avg_s * 1e3}})

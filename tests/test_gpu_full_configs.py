@@ -216,3 +216,56 @@ def test_refresh_mid_size_vs_oracle(siso, oracle):
     ol, oa = ora.export_meta()
     gl, ga = gpu.export_meta()
     assert (gl.cpu().numpy() == ol).all() and (ga.cpu().numpy().astype(np.uint32) == oa).all()
+
+
+def test_cluster_mid_size_vs_oracle(siso, oracle):
+    """Clustering at a size of many tile pairs: about 6,000 vectors in chains of overlapping topics."""
+    from gpu_util import SIM_TOL
+    from test_gpu_update_merge import compare_state
+    dim = 512
+    x, topic = W.query_log_chains(n_chains=150, chain_len=6, members_lo=2, members_hi=11, n_noise=300, dim=dim,
+                                  dtype="bf16", seed=4242)
+    n = len(x)
+    print(f"case: cluster n={n} dim={dim}", flush=True)
+    ora = oracle.OracleCache(dim, n, "bf16")
+    want, seeds, margin = ora.cluster(x, 0.86, 2)
+    print(f"  oracle: {len(seeds)} clusters, margin {margin:.4f}", flush=True)
+    assert margin > 5 * SIM_TOL["bf16"] and n > 5500 and len(seeds) > 400
+    gpu = siso.SisoCache(dim, n, siso.BF16)
+    labels, clusters, pairs = gpu.cluster(to_dev(x, "bf16"), 0.86, 2)
+    assert clusters == len(seeds) and np.array_equal(labels.cpu().numpy(), want)
+    compare_state(gpu, ora, "bf16", "repository")
+
+
+def test_cluster_full_size(siso, oracle):
+    """The 131,072 rows of the merge workload taken as a query log: 16,384 topics of 8 near-duplicates."""
+    print("case: cluster full size", flush=True)
+    wl = W.c5_merge()
+    gpu = siso.SisoCache(wl.dim, 16384, siso.BF16)
+    labels, clusters, pairs = gpu.cluster(to_dev(wl.centroids, "bf16"), 0.86, 2)
+    lab = labels.cpu().numpy()
+    assert clusters == 16384 and pairs == wl.meta["expected_pairs"] and (lab >= 0).all()
+    # all candidates have 8 vectors, so the clusters come in the order of their lowest rows
+    first = np.full(16384, wl.K, np.int64)
+    np.minimum.at(first, wl.cluster_of, np.arange(wl.K))
+    newidx = np.empty(16384, np.int64); newidx[np.argsort(first)] = np.arange(16384)
+    assert np.array_equal(lab, newidx[wl.cluster_of])
+    gc, gm, gsz = gpu.export()
+    sizes, acc = gpu.export_meta()
+    assert bool((gsz == 8).all()) and bool((sizes == 8.0).all()) and bool((acc == 0).all())
+    r = np.random.default_rng(5)
+    u = unit64(W.bf16_bits_to_f32(wl.centroids))
+    gm_h = gm.cpu().numpy().astype(np.float64)
+    gc_h = W.bf16_bits_to_f32(to_host(gc, "bf16")).astype(np.float64)
+    for g in r.choice(16384, size=256, replace=False):
+        want_m = u[np.nonzero(wl.cluster_of == g)[0]].mean(axis=0)
+        assert np.abs(gm_h[newidx[g]] - want_m).max() < 2e-6
+        assert np.abs(gc_h[newidx[g]] - unit64(want_m)).max() <= 2.0 ** -8
+    # the oracle on 64 whole topics plus 700 other rows clusters them the same way
+    groups = r.choice(16384, size=64, replace=False)
+    rows = np.union1d(np.nonzero(np.isin(wl.cluster_of, groups))[0], r.choice(wl.K, size=700, replace=False))
+    oc = oracle.OracleCache(wl.dim, len(rows), "bf16")
+    want, seeds, margin = oc.cluster(wl.centroids[rows], 0.86, 2)
+    for g in groups:
+        sel = wl.cluster_of[rows] == g
+        assert len(set(want[sel].tolist())) == 1 and want[sel][0] >= 0 and (want[sel][0] != want[~sel]).all()
