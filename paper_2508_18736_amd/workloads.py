@@ -194,13 +194,23 @@ class Workload:
         return storage_to_f32(self.queries, self.dtype)
 
 
+def into_cone(x: np.ndarray, seed: int, cone: float) -> np.ndarray:
+    """``normalize(x_i + cone * e)`` with one seeded unit direction ``e`` shared by all rows: two
+    unrelated rows then have cosine about ``cone^2 / (1 + cone^2)`` instead of about 0, the way
+    text embeddings of unrelated sentences sit in a cone (``cone`` = 1.28 gives 0.62)."""
+    if cone == 0.0:
+        return x
+    e = uniform_directions(seed, _STREAM_MISC + 1, 1, x.shape[1])[0]
+    return _unit_rows(x + np.float32(cone) * e)
+
+
 def mixture_centroids(seed: int, n_clusters: int, per_cluster: int, dim: int, sigma: float,
-                      sigma_mode: str, dtype: str, shuffle: bool = True):
-    """Cluster means uniform on the sphere; every centroid is a jittered copy of
-    its mean.  Returns ``(centroids_storage, cluster_of, means_f32)``.  With
+                      sigma_mode: str, dtype: str, shuffle: bool = True, cone: float = 0.0):
+    """Cluster means uniform on the sphere (or in a cone, see ``into_cone``); every centroid is a
+    jittered copy of its mean.  Returns ``(centroids_storage, cluster_of, means_f32)``.  With
     ``shuffle`` the rows are put in a seeded random order, so that members of a
     cluster are spread over the array instead of sitting side by side."""
-    means = uniform_directions(seed, _STREAM_MEANS, n_clusters, dim)
+    means = into_cone(uniform_directions(seed, _STREAM_MEANS, n_clusters, dim), seed, cone)
     cluster_of = np.repeat(np.arange(n_clusters, dtype=np.int32), per_cluster)
     if shuffle:
         cluster_of = cluster_of[_rng(seed, _STREAM_PERM).permutation(len(cluster_of))]
@@ -234,22 +244,22 @@ def c1_tiny(n_clusters: int = 64, per_cluster: int = 16, n_queries: int = 256, d
 
 def c2_mid(n_clusters: int = 4096, per_cluster: int = 16, n_queries: int = 4096, dim: int = 768,
            sigma: float = 0.08, near_fraction: float = 0.7, sigma_mode: str = "total",
-           dtype: str = "bf16", seed: int = BASE_SEED + 2) -> Workload:
+           dtype: str = "bf16", seed: int = BASE_SEED + 2, cone: float = 0.0) -> Workload:
     """Mid lookup: 65,536 bf16 centroids; 70 % of the queries are jittered copies of
     a random existing centroid (its index is recorded in ``planted``), 30 % are
     fresh uniform directions.  Thresholds 0.75 / 0.85 / 0.92."""
-    cents, cluster_of, _ = mixture_centroids(seed, n_clusters, per_cluster, dim, sigma, sigma_mode, dtype)
+    cents, cluster_of, _ = mixture_centroids(seed, n_clusters, per_cluster, dim, sigma, sigma_mode, dtype, cone=cone)
     K = cents.shape[0]
     r = _rng(seed, _STREAM_POP)
     near = r.random(n_queries) < near_fraction
     targets = r.integers(0, K, size=n_queries).astype(np.int64)
     cf = storage_to_f32(cents, dtype)
     queries = _queries_near(seed, cf, targets, sigma, sigma_mode, dtype)
-    fresh = to_storage(uniform_directions(seed, _STREAM_MISC, n_queries, dim), dtype)
+    fresh = to_storage(into_cone(uniform_directions(seed, _STREAM_MISC, n_queries, dim), seed, cone), dtype)
     queries[~near] = fresh[~near]
     planted = np.where(near, targets, -1)
     return Workload("c2_mid", dim, dtype, cents, cluster_of, queries, planted, (0.75, 0.85, 0.92),
-                    meta={"sigma": sigma, "sigma_mode": sigma_mode})
+                    meta={"sigma": sigma, "sigma_mode": sigma_mode, "cone": cone})
 
 
 def spread_sample(centroids: np.ndarray, dtype: str, n_queries: int, sigma_lo: float = 0.1,
