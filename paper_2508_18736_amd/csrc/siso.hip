@@ -425,6 +425,11 @@ __global__ __launch_bounds__(256) void k_update(const T *__restrict__ Q, const i
     __shared__ u64 masks[4];
     const long me = blockIdx.x;
     const int t = threadIdx.x;
+    // what does not depend on anything else is asked for first: the first 256 entries of the index
+    // array (all of it in a small batch), this block's own entry
+    const bool first_ok = !owner && t < n;
+    const int first_idx = first_ok ? idx[t] : -1;
+    const unsigned char first_hit = first_ok && hit ? hit[t] : 1;
     if (hit && !hit[me]) return;
     const int k = idx[me];
     if (k < 0) return;
@@ -432,13 +437,33 @@ __global__ __launch_bounds__(256) void k_update(const T *__restrict__ Q, const i
         if (t == 0) atomicAdd(bad, 1ull);
         return;
     }
-    long scan_from = 0, scan_to = n;
+    // ... then this block's own query and the centroid's mean, before it is known whether this block
+    // leads the centroid: most do, and the rows are on their way while the notes are read
+    // (without notes the two loads read this block's own index entry instead: no branch, no wait here)
+    const int lead_raw = *(owner ? owner + k : idx + me);
+    const int noted_raw = *(owner ? marked + k : idx + me);
+    // loads without conditions (a column past the end reads column 0 and is zeroed afterwards), so
+    // that all of them are in flight together
+    float x_me[UPD_MAXE_T], m_old[UPD_MAXE_T];
+    T xr[UPD_MAXE_T];
+#pragma unroll
+    for (int e = 0; e < UPD_MAXE_T; ++e) {
+        const int col = t + e * 256;
+        xr[e] = Q[(size_t)me * d + (col < d ? col : 0)];
+        m_old[e] = mean[(size_t)k * d + (col < d ? col : 0)];
+    }
+    const int size_old = size[k];
+#pragma unroll
+    for (int e = 0; e < UPD_MAXE_T; ++e) {
+        x_me[e] = t + e * 256 < d ? widen(xr[e]) : 0.f;
+        // the values exist from here on: otherwise the compiler moves the loads behind the test below,
+        // where they would only start once the notes have arrived
+        asm volatile("" ::"v"(x_me[e]), "v"(m_old[e]));
+    }
+    const long scan_from = 0, scan_to = n;
+    if (owner && lead_raw != (int)me) return;  // an earlier member leads this centroid
+    const bool alone = owner && noted_raw == 1;  // the only member: nothing to look for
     if (owner) {
-        if (owner[k] != (int)me) return;  // an earlier member leads this centroid
-        if (marked[k] == 1) {
-            scan_from = me - (me & 255);  // the only member: just the 256 entries around this one
-            scan_to = scan_from + 256 < n ? scan_from + 256 : n;
-        }
         __syncthreads();  // everyone has read the notes
         if (t == 0) {     // leave them as they were found
             owner[k] = UPD_NO_OWNER;
@@ -449,41 +474,61 @@ __global__ __launch_bounds__(256) void k_update(const T *__restrict__ Q, const i
 #pragma unroll
     for (int e = 0; e < UPD_MAXE_T; ++e) acc[e] = 0.f;
     int members = 0;
-    for (long base = scan_from; base < scan_to; base += 256) {
-        const long j = base + t;
-        const bool m = j < scan_to && idx[j] == k && (!hit || hit[j]);
-        const u64 mask = __ballot(m);
-        __syncthreads();
-        if ((t & 63) == 0) masks[t >> 6] = mask;
-        __syncthreads();
-        for (int w = 0; w < 4; ++w) {
-            u64 mm = masks[w];
-            while (mm) {
-                const int b = __ffsll((long long)mm) - 1;
-                mm &= mm - 1;
-                const long jj = base + w * 64 + b;
-                if (jj < me) return;  // an earlier member leads this centroid (uniform over the block)
-                float x[UPD_MAXE_T];
-                float ss = 0.f;
+    // fold one query (its elements of this thread in x) into the sum; uniform over the block
+    auto fold = [&](const float(&x)[UPD_MAXE_T]) {
+        float ss = 0.f;
 #pragma unroll
-                for (int e = 0; e < UPD_MAXE_T; ++e) {
-                    const int col = t + e * 256;
-                    x[e] = col < d ? widen(Q[(size_t)jj * d + col]) : 0.f;
-                    ss += x[e] * x[e];
-                }
-                const float n2 = block_sum256(ss, sh);
-                const float inv = inv_length(n2);
-                if (inv == inv && inv > 0.f) {
-                    const float nrm = sqrtf(n2);
+        for (int e = 0; e < UPD_MAXE_T; ++e) ss += x[e] * x[e];
+        const float n2 = block_sum256(ss, sh);
+        const float inv = inv_length(n2);
+        if (inv == inv && inv > 0.f) {
+            const float nrm = sqrtf(n2);
 #pragma unroll
-                    for (int e = 0; e < UPD_MAXE_T; ++e) acc[e] += x[e] / nrm;
-                    ++members;
+            for (int e = 0; e < UPD_MAXE_T; ++e) acc[e] += x[e] / nrm;
+            ++members;
+        }
+    };
+    if (alone) {
+        fold(x_me);
+    } else {
+        for (long base = scan_from; base < scan_to; base += 256) {
+            const long j = base + t;
+            bool m;
+            if (base == 0 && !owner)
+                m = first_ok && first_idx == k && first_hit;
+            else
+                m = j < scan_to && idx[j] == k && (!hit || hit[j]);
+            const u64 mask = __ballot(m);
+            __syncthreads();
+            if ((t & 63) == 0) masks[t >> 6] = mask;
+            __syncthreads();
+            for (int w = 0; w < 4; ++w) {
+                u64 mm = masks[w];
+                while (mm) {
+                    const int b = __ffsll((long long)mm) - 1;
+                    mm &= mm - 1;
+                    const long jj = base + w * 64 + b;
+                    if (jj < me) return;  // an earlier member leads this centroid (uniform over the block)
+                    if (jj == me) {
+                        fold(x_me);
+                        continue;
+                    }
+                    T xr[UPD_MAXE_T];
+                    float x[UPD_MAXE_T];
+#pragma unroll
+                    for (int e = 0; e < UPD_MAXE_T; ++e) {
+                        const int col = t + e * 256;
+                        xr[e] = Q[(size_t)jj * d + (col < d ? col : 0)];
+                    }
+#pragma unroll
+                    for (int e = 0; e < UPD_MAXE_T; ++e) x[e] = t + e * 256 < d ? widen(xr[e]) : 0.f;
+                    fold(x);
                 }
             }
         }
     }
     if (members == 0) return;
-    const float n_old = (float)size[k];
+    const float n_old = (float)size_old;
     const float n_new = n_old + (float)members;
     float m[UPD_MAXE_T];
     float ss = 0.f;
@@ -492,13 +537,13 @@ __global__ __launch_bounds__(256) void k_update(const T *__restrict__ Q, const i
         const int col = t + e * 256;
         m[e] = 0.f;
         if (col < d) {
-            m[e] = (n_old * mean[(size_t)k * d + col] + acc[e]) / n_new;
+            m[e] = (n_old * m_old[e] + acc[e]) / n_new;
             mean[(size_t)k * d + col] = m[e];
             ss += m[e] * m[e];
         }
     }
     const float n2 = block_sum256(ss, sh);
-    if (t == 0) size[k] += members;
+    if (t == 0) size[k] = size_old + members;
     if (!(n2 > 0.f) || n2 > 3.0e38f) return;
     const float nrm = sqrtf(n2);
     float cs = 0.f;
