@@ -121,6 +121,22 @@ __device__ __forceinline__ float chunk_dot(const bf16_t *a, const bf16_t *b) {
     return s;
 }
 
+// the same sums from chunks that are already in registers
+__device__ __forceinline__ float chunk_dot(u32x4_t x, u32x4_t y, float) {
+    return __uint_as_float(x[0]) * __uint_as_float(y[0]) + __uint_as_float(x[1]) * __uint_as_float(y[1]) +
+           __uint_as_float(x[2]) * __uint_as_float(y[2]) + __uint_as_float(x[3]) * __uint_as_float(y[3]);
+}
+__device__ __forceinline__ float chunk_dot(u32x4_t x, u32x4_t y, bf16_t) {
+    float s = 0.f;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        s += __uint_as_float(x[i] << 16) * __uint_as_float(y[i] << 16);
+        s += __uint_as_float(x[i] & 0xFFFF0000u) * __uint_as_float(y[i] & 0xFFFF0000u);
+    }
+    return s;
+}
+#define FIN_CHUNKS 8  // 16-byte chunks of a row that a lane keeps in flight
+
 // Finalize: per query, max over the slice keys, then the exact cosines of the rows of
 // the winning block (strict ">" in ascending row order, so the lowest index keeps a
 // tie), and the strict threshold test.  One 256-thread block per query: its sixteen
@@ -138,13 +154,18 @@ __global__ __launch_bounds__(256) void k_lookup_finalize(const T *__restrict__ Q
     __shared__ u64 sh_k[4];
     __shared__ float sh_s[16];
     __shared__ long sh_i[16];
+    __shared__ u32x4_t sh_q[SISO_MAX_DIM / EPC];  // the query row
     const long q = blockIdx.x;
     const int t = threadIdx.x, lane = t & 63, wave = t >> 6, grp = t >> 4, gl = t & 15;
     const T *qrow = Q + (size_t)q * d;
     // 1/|q|: 0 for a zero-length query, NaN for a non-finite one
     float ss = 0.f;
-    if (vec) {
-        for (int e = t * EPC; e < d; e += 256 * EPC) ss += chunk_dot(qrow + e, qrow + e);
+    if (vec) {  // the row also goes to LDS: sixteen groups of lanes will read it again
+        for (int e = t * EPC; e < d; e += 256 * EPC) {
+            const u32x4_t v = *(const u32x4_t *)(qrow + e);
+            sh_q[e / EPC] = v;
+            ss += chunk_dot(v, v, T());
+        }
     } else {
         for (int e = t; e < d; e += 256) ss += widen(qrow[e]) * widen(qrow[e]);
     }
@@ -180,13 +201,27 @@ __global__ __launch_bounds__(256) void k_lookup_finalize(const T *__restrict__ Q
         for (int p = 0; p < passes; ++p) {
             const long r = run0 + (code == 1 ? 16 * p + grp : 8 * (grp >> 2) + 2 * code + (grp & 3));
             float acc = 0.f;
-            if (r < K) {
-                const T *crow = cent + (size_t)r * d;
-                if (vec) {
-                    for (int e = gl * EPC; e < d; e += 16 * EPC) acc += chunk_dot(qrow + e, crow + e);
-                } else {
-                    for (int e = gl; e < d; e += 16) acc += widen(qrow[e]) * widen(crow[e]);
+            if (vec) {
+                // FIN_CHUNKS chunks of the row at a time, all in flight together; the sums are added in the
+                // order of the columns.  A row past the end reads the last row and is discarded below.
+                const T *crow = cent + (size_t)(r < K ? r : K - 1) * d;
+                for (int e0 = gl * EPC; e0 < d; e0 += FIN_CHUNKS * 16 * EPC) {
+                    u32x4_t cc[FIN_CHUNKS];
+#pragma unroll
+                    for (int i = 0; i < FIN_CHUNKS; ++i) {
+                        const int e = e0 + 16 * i * EPC;
+                        cc[i] = *(const u32x4_t *)(crow + (e < d ? e : 0));
+                    }
+#pragma unroll
+                    for (int i = 0; i < FIN_CHUNKS; ++i) {
+                        const int e = e0 + 16 * i * EPC;
+                        const float part = chunk_dot(sh_q[(e < d ? e : 0) / EPC], cc[i], T());
+                        acc += e < d ? part : 0.f;
+                    }
                 }
+            } else if (r < K) {
+                const T *crow = cent + (size_t)r * d;
+                for (int e = gl; e < d; e += 16) acc += widen(qrow[e]) * widen(crow[e]);
             }
 #pragma unroll
             for (int off = 8; off > 0; off >>= 1) acc += __shfl_xor(acc, off);
