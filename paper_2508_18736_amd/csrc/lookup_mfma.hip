@@ -37,9 +37,13 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
-template <int WC_, int WQ_, int NWC_, int NWQ_, int NSTAGE_, int BK_ = 64>
+// ROWS: the keys of the lookup carry the winning row itself instead of its block of 16 rows (more
+// compares per product, affordable where the kernel waits for memory anyway; the finalize step then
+// has no centroid rows to read)
+template <int WC_, int WQ_, int NWC_, int NWQ_, int NSTAGE_, int BK_ = 64, bool ROWS_ = false>
 struct PipeCfg {
     static constexpr int WC = WC_, WQ = WQ_, NWC = NWC_, NWQ = NWQ_, NSTAGE = NSTAGE_;
+    static constexpr bool ROWS = ROWS_;
     static constexpr int BK = BK_;            // elements of the dimension per slab (64; or 32: half lines)
     static constexpr int RB = BK * 2;         // bytes of a tile row in a stage
     static constexpr int CPR = BK / 8;        // 16-byte chunks per tile row
@@ -230,7 +234,19 @@ __device__ __forceinline__ bool pipe_map_block(long K, int tiles_per_slice, int 
 // End of a lookup workgroup: every lane holds (best value, block) per query column of its wave.
 // Lanes l and l^32 hold the same column; waves with the same wq share columns and meet in LDS
 // (red = at least NWC * BQ * 8 bytes that nobody reads any more).
-template <int WQ, int NWC, int BQ, int NT>
+template <bool ROWS>
+__device__ __forceinline__ void pipe_merge(float &v, unsigned &b, float ov, unsigned ob) {
+    if constexpr (ROWS) {  // (value, row): the larger value, then the lower row; 0xFFFFFFFF = none
+        if (ov > v || (ov == v && ob < b)) {
+            v = ov;
+            b = ob;
+        }
+    } else {
+        siso_merge_candidate(v, b, ov, ob);
+    }
+}
+
+template <int WQ, int NWC, int BQ, int NT, bool ROWS = false>
 __device__ __forceinline__ void pipe_reduce_keys(float (&bv)[WQ], unsigned (&bb)[WQ], unsigned char *red, int wc, int wq,
                                                  int h, int l32, int tid, long q0, long n, int slices, int s,
                                                  u64 *__restrict__ keys) {
@@ -238,7 +254,7 @@ __device__ __forceinline__ void pipe_reduce_keys(float (&bv)[WQ], unsigned (&bb)
     for (int b = 0; b < WQ; ++b) {
         const float ov = __shfl_xor(bv[b], 32);
         const unsigned ob = __shfl_xor(bb[b], 32);
-        siso_merge_candidate(bv[b], bb[b], ov, ob);
+        pipe_merge<ROWS>(bv[b], bb[b], ov, ob);
     }
     float *red_v = (float *)red;  // [NWC][BQ]
     unsigned *red_b = (unsigned *)(red + NWC * BQ * 4);
@@ -255,7 +271,7 @@ __device__ __forceinline__ void pipe_reduce_keys(float (&bv)[WQ], unsigned (&bb)
         float v = red_v[col];
         unsigned blk = red_b[col];
 #pragma unroll
-        for (int w2 = 1; w2 < NWC; ++w2) siso_merge_candidate(v, blk, red_v[w2 * BQ + col], red_b[w2 * BQ + col]);
+        for (int w2 = 1; w2 < NWC; ++w2) pipe_merge<ROWS>(v, blk, red_v[w2 * BQ + col], red_b[w2 * BQ + col]);
         const long q = q0 + col;
         if (q < n) keys[(size_t)q * slices + s] = (blk == 0xFFFFFFFFu) ? 0ull : pack_key(v, blk);
     }
@@ -439,13 +455,31 @@ __global__ __launch_bounds__(Cfg::NT) __attribute__((amdgpu_waves_per_eu(2, 2)))
                 static_for<0, WQ>([&](auto ib) {
                     constexpr int B = decltype(ib)::value;
                     float m = -INFINITY;
-                    static_for<0, 16>([&](auto ii) {
-                        constexpr int I = decltype(ii)::value;
-                        m = fmaxf(m, acc.template get<A, B, I>() * w[I >> 2][I & 3]);
-                    });
-                    if (m > bv[B]) {
-                        bv[B] = m;
-                        bb[B] = blk;
+                    if constexpr (Cfg::ROWS) {
+                        // the rows of a lane ascend with the register number, the tiles of a workgroup with
+                        // time: ">" keeps the lowest row among equal values
+                        unsigned mi = 0;
+                        static_for<0, 16>([&](auto ii) {
+                            constexpr int I = decltype(ii)::value;
+                            const float v = acc.template get<A, B, I>() * w[I >> 2][I & 3];
+                            if (v > m) {
+                                m = v;
+                                mi = (unsigned)(8 * (I >> 2) + (I & 3));
+                            }
+                        });
+                        if (m > bv[B]) {
+                            bv[B] = m;
+                            bb[B] = (unsigned)(c0 + rb) + 4u * (unsigned)h + mi;
+                        }
+                    } else {
+                        static_for<0, 16>([&](auto ii) {
+                            constexpr int I = decltype(ii)::value;
+                            m = fmaxf(m, acc.template get<A, B, I>() * w[I >> 2][I & 3]);
+                        });
+                        if (m > bv[B]) {
+                            bv[B] = m;
+                            bb[B] = blk;
+                        }
                     }
                 });
             });
@@ -457,7 +491,7 @@ __global__ __launch_bounds__(Cfg::NT) __attribute__((amdgpu_waves_per_eu(2, 2)))
         sto = sto_next;
     }
     __syncthreads();
-    pipe_reduce_keys<WQ, NWC, BQ, NT>(bv, bb, smem, wc, wq, h, l32, tid, q0, n, slices, s, keys);
+    pipe_reduce_keys<WQ, NWC, BQ, NT, Cfg::ROWS>(bv, bb, smem, wc, wq, h, l32, tid, q0, n, slices, s, keys);
 }
 
 // ----------------------------------------------------------------------------
@@ -979,8 +1013,8 @@ __global__ __launch_bounds__(WideCfg::NT) __attribute__((amdgpu_waves_per_eu(1, 
 }
 
 typedef PipeCfg<4, 2, 2, 4, 2> PipeLarge;  // 256 x 256 tile, waves of 128 x 64, two stages
-typedef PipeCfg<2, 2, 4, 2, 3> PipeMid;    // 256 x 128 tile, waves of 64 x 64, three stages
-typedef PipeCfg<1, 2, 8, 1, 3> PipeSmall;  // 256 x 64 tile, waves of 32 x 64, three stages
+typedef PipeCfg<2, 2, 4, 2, 3, 64, true> PipeMid;    // 256 x 128 tile, waves of 64 x 64, three stages; keys carry rows
+typedef PipeCfg<1, 2, 8, 1, 3, 64, true> PipeSmall;  // 256 x 64 tile, waves of 32 x 64, three stages; keys carry rows
 typedef PipeCfg<4, 2, 2, 4, 4, 32> PipeLarge32;  // 256 x 256 tile, slabs of 32 elements, four stages
 
 // ----------------------------------------------------------------------------
@@ -1091,9 +1125,13 @@ int siso_mfma_slices(const siso_cache *c, long n) {
     return mfma_plan(c, n, &p) ? p.slices : 0;
 }
 
-int siso_mfma_launch(siso_cache *c, const void *queries, long n, int slices) {
+// which kernels write keys that carry the row itself
+static int keys_carry_rows(const PipePlan &p) { return (p.cfg == 2 && PipeMid::ROWS) || (p.cfg == 3 && PipeSmall::ROWS) ? 1 : 0; }
+
+int siso_mfma_launch(siso_cache *c, const void *queries, long n, int slices, int *row_keys) {
     PipePlan p;
     if (!mfma_plan(c, n, &p) || p.slices != slices) return siso_fail(c, SISO_EINVAL, "mfma lookup: plan mismatch");
+    *row_keys = keys_carry_rows(p);
     return pipe_launch(c, queries, n, p);
 }
 
@@ -1102,9 +1140,10 @@ int siso_skinny_slices(const siso_cache *c, long n) {
     return skinny_plan(c, n, &p) ? p.slices : 0;
 }
 
-int siso_skinny_launch(siso_cache *c, const void *queries, long n, int slices) {
+int siso_skinny_launch(siso_cache *c, const void *queries, long n, int slices, int *row_keys) {
     PipePlan p;
     if (!skinny_plan(c, n, &p) || p.slices != slices) return siso_fail(c, SISO_EINVAL, "skinny lookup: plan mismatch");
+    *row_keys = keys_carry_rows(p);
     return pipe_launch(c, queries, n, p);
 }
 

@@ -147,8 +147,8 @@ template <typename T>
 __global__ __launch_bounds__(256) void k_lookup_finalize(const T *__restrict__ Q, const T *__restrict__ cent,
                                                           const float *__restrict__ invn, const u64 *__restrict__ keys,
                                                           long n, long K, int d, int slices, float threshold, int vec,
-                                                          int *out_idx, float *out_sim, unsigned char *out_hit,
-                                                          unsigned *access) {
+                                                          int row_keys, int *out_idx, float *out_sim,
+                                                          unsigned char *out_hit, unsigned *access) {
     constexpr int EPC = 16 / (int)sizeof(T);  // elements per 16-byte chunk
     __shared__ float sh_f[4];
     __shared__ u64 sh_k[4];
@@ -192,7 +192,13 @@ __global__ __launch_bounds__(256) void k_lookup_finalize(const T *__restrict__ Q
     long best_i = -1;
     float best_s = -INFINITY;
     const bool finite_q = qi == qi;
-    if (finite_q && K > 0 && key != 0) {
+    if (row_keys) {
+        // the key names the row and carries <q, c> / |c| as the kernel summed it: nothing left to read
+        if (finite_q && K > 0 && key != 0) {
+            best_i = (long)(0xFFFFFFFFu - (unsigned)(key & 0xFFFFFFFFull));
+            best_s = unordered_bits((unsigned)(key >> 32)) * qi;
+        }
+    } else if (finite_q && K > 0 && key != 0) {
         const unsigned block = 0xFFFFFFFFu - (unsigned)(key & 0xFFFFFFFFull);
         const long run0 = (long)(block >> 2) * SISO_RUN_ROWS;
         const int code = (int)(block & 3u);
@@ -239,7 +245,7 @@ __global__ __launch_bounds__(256) void k_lookup_finalize(const T *__restrict__ Q
     __syncthreads();
     if (t == 0) {
         // rows ascend with the group number inside a pass, and pass 1 lies above pass 0
-        for (int g = 1; g < 16; ++g) {
+        for (int g = 1; g < (row_keys ? 1 : 16); ++g) {
             const float os = sh_s[g];
             const long oi = sh_i[g];
             if (oi >= 0 && (best_i < 0 || os > best_s || (os == best_s && oi < best_i))) {
@@ -957,12 +963,13 @@ int siso_lookup_impl(siso_cache *c, const void *queries, long n, float threshold
     if (rc != SISO_OK) return rc;
     const unsigned qblocks = (unsigned)n;
     const int vec = ((c->dim * elem_bytes(c->dtype)) % 16 == 0 && ((uintptr_t)queries & 15) == 0) ? 1 : 0;
+    int row_keys = 0;  // what the keys of the chosen kernel carry: the winning row, or its block of rows
     if (c->count > 0) {
         siso_prof_begin(c);
         switch (path) {
             case SISO_PATH_SCALAR: rc = siso_scalar_launch(c, queries, n, slices); break;
-            case SISO_PATH_MFMA: rc = siso_mfma_launch(c, queries, n, slices); break;
-            case SISO_PATH_SKINNY: rc = siso_skinny_launch(c, queries, n, slices); break;
+            case SISO_PATH_MFMA: rc = siso_mfma_launch(c, queries, n, slices, &row_keys); break;
+            case SISO_PATH_SKINNY: rc = siso_skinny_launch(c, queries, n, slices, &row_keys); break;
         }
         siso_prof_end(c);
         if (rc != SISO_OK) return rc;
@@ -970,11 +977,11 @@ int siso_lookup_impl(siso_cache *c, const void *queries, long n, float threshold
     if (c->dtype == SISO_F32)
         hipLaunchKernelGGL(k_lookup_finalize<float>, dim3(qblocks), dim3(256), 0, c->stream, (const float *)queries,
                            (const float *)c->cent, c->invn, c->keys, n, c->count, c->dim, slices, threshold,
-                           vec, out_idx, out_sim, out_hit, count_access ? c->access : nullptr);
+                           vec, row_keys, out_idx, out_sim, out_hit, count_access ? c->access : nullptr);
     else
         hipLaunchKernelGGL(k_lookup_finalize<bf16_t>, dim3(qblocks), dim3(256), 0, c->stream, (const bf16_t *)queries,
                            (const bf16_t *)c->cent, c->invn, c->keys, n, c->count, c->dim, slices, threshold,
-                           vec, out_idx, out_sim, out_hit, count_access ? c->access : nullptr);
+                           vec, row_keys, out_idx, out_sim, out_hit, count_access ? c->access : nullptr);
     HIP_TRY(c, hipGetLastError());
     return SISO_OK;
 }

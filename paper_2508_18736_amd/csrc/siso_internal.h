@@ -255,9 +255,9 @@ int siso_check_hip(siso_cache *c, hipError_t e, const char *what);
 int siso_scalar_slices(const siso_cache *c, long n);
 int siso_scalar_launch(siso_cache *c, const void *queries, long n, int slices);
 int siso_mfma_slices(const siso_cache *c, long n);
-int siso_mfma_launch(siso_cache *c, const void *queries, long n, int slices);
+int siso_mfma_launch(siso_cache *c, const void *queries, long n, int slices, int *row_keys);
 int siso_skinny_slices(const siso_cache *c, long n);
-int siso_skinny_launch(siso_cache *c, const void *queries, long n, int slices);
+int siso_skinny_launch(siso_cache *c, const void *queries, long n, int slices, int *row_keys);
 
 // Self-similarity pair search over `count` rows of the cache's element type and dimension with
 // their inverse lengths (counter already zeroed).  The MFMA kernel reads whole tiles: rows and invn
