@@ -290,6 +290,9 @@ int siso_adjust_threshold(const float *thetas, int m, int index, double wait_est
  * siso_lookup / siso_merge brackets its dominant kernel (the similarity kernel,
  * without the finalize kernel) with a pair of HIP events on the cache's stream
  * (an event costs a few microseconds on the stream, so short steps sample).
+ * A pair of events with nothing between them already reads about 4 us;
+ * siso_profile_enable measures that on the stream (it synchronises) and every
+ * bracket is reduced by it.
  * siso_profile_read synchronises with the stream, returns the sum of the
  * bracketed durations in milliseconds and the number of brackets since the
  * last read (host pointers, either may be NULL), and releases the events.

@@ -86,6 +86,7 @@ struct siso_cache {
     int prof_open;        // a bracket was opened by the current call
     hipEvent_t *prof_ev;  // pairs: [2*i] start, [2*i+1] stop
     int prof_count;       // recorded pairs
+    double prof_empty_ms; // what a pair of events with nothing between them measures on this stream
 
     char err[256];
 };
