@@ -614,12 +614,30 @@ __global__ void k_pairs_validate(const int *__restrict__ pairs, long n_pairs, lo
     if (a < 0 || b < 0 || a >= K || b >= K || a == b) atomicAdd(bad, 1ull);
 }
 
-__global__ void k_uf_init(int *parent, unsigned char *touched, long K) {
+__global__ void k_uf_init(int *parent, unsigned char *touched, int *members_of, int *cursor, long K) {
     const long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
     if (i < K) {
         parent[i] = (int)i;
         touched[i] = 0;
+        members_of[i] = 0;
+        cursor[i] = 0;
     }
+}
+
+// Member lists of the groups: how many rows each root leads (itself included), then, once the counts
+// have been scanned into list starts, the rows themselves (in the order they arrive; the root's block
+// sorts its list).  Only rows that occur in a pair take part.
+__global__ void k_group_count(const int *__restrict__ root, const unsigned char *__restrict__ touched, long K,
+                              int *members_of) {
+    const long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < K && touched[i]) atomicAdd(&members_of[root[i]], 1);
+}
+__global__ void k_group_fill(const int *__restrict__ root, const unsigned char *__restrict__ touched, long K,
+                             const int *__restrict__ first, int *cursor, int *list) {
+    const long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= K || !touched[i]) return;
+    const int r = root[i];
+    list[first[r] + atomicAdd(&cursor[r], 1)] = (int)i;
 }
 
 __device__ __forceinline__ int uf_find(const int *parent, int x) {
@@ -656,12 +674,16 @@ __global__ void k_uf_roots(const int *__restrict__ parent, int *root, long K) {
 }
 
 // One block per row; only roots of groups with at least two rows work.
+#define GROUP_LIST_MAX 1024  // members of a group that its block sorts in LDS; larger groups are searched for
 template <typename T>
 __global__ __launch_bounds__(256) void k_group_mean(const int *__restrict__ root, const unsigned char *__restrict__ touched,
-                                                     long K, T *cent, float *mean, int *size, float *invn,
+                                                     long K, const int *__restrict__ members_of,
+                                                     const int *__restrict__ first, const int *__restrict__ list,
+                                                     T *cent, float *mean, int *size, float *invn,
                                                      float *locality, unsigned *access, int d) {
     __shared__ float sh[4];
     __shared__ u64 masks[4];
+    __shared__ int raw[GROUP_LIST_MAX], sorted[GROUP_LIST_MAX];
     const long r = blockIdx.x;
     const int t = threadIdx.x;
     if (!touched[r] || root[r] != (int)r) return;
@@ -672,6 +694,34 @@ __global__ __launch_bounds__(256) void k_group_mean(const int *__restrict__ root
     int members = 0;
     float loc = 0.f;  // cluster sizes of Algorithm 1 add up, in ascending order of the members
     u64 refs = 0;     // so do the access counts, saturating at infinity
+    auto take = [&](long jj) {
+        const float wgt = (float)size[jj];
+#pragma unroll
+        for (int e = 0; e < UPD_MAXE; ++e) {
+            const int col = t + e * 256;
+            if (col < d) acc[e] += wgt * mean[(size_t)jj * d + col];
+        }
+        wsum += (double)size[jj];
+        loc = loc + locality[jj];
+        refs += access[jj];
+        ++members;
+    };
+    const int listed = members_of[r];
+    if (listed <= GROUP_LIST_MAX) {
+        // the list arrives in no particular order; the sums take the members in ascending order, so the
+        // result does not depend on scheduling: every thread places its entries by counting the smaller ones
+        const int lo = first[r];
+        for (int i = t; i < listed; i += 256) raw[i] = list[lo + i];
+        __syncthreads();
+        for (int i = t; i < listed; i += 256) {
+            const int mine = raw[i];
+            int below = 0;
+            for (int k = 0; k < listed; ++k) below += raw[k] < mine ? 1 : 0;
+            sorted[below] = mine;
+        }
+        __syncthreads();
+        for (int p = 0; p < listed; ++p) take(sorted[p]);
+    } else
     for (long base = r - (r & 255); base < K; base += 256) {
         const long j = base + t;
         const bool m = j < K && j >= r && root[j] == (int)r;
@@ -684,17 +734,7 @@ __global__ __launch_bounds__(256) void k_group_mean(const int *__restrict__ root
             while (mm) {
                 const int b = __ffsll((long long)mm) - 1;
                 mm &= mm - 1;
-                const long jj = base + w * 64 + b;
-                const float wgt = (float)size[jj];
-#pragma unroll
-                for (int e = 0; e < UPD_MAXE; ++e) {
-                    const int col = t + e * 256;
-                    if (col < d) acc[e] += wgt * mean[(size_t)jj * d + col];
-                }
-                wsum += (double)size[jj];
-                loc = loc + locality[jj];
-                refs += access[jj];
-                ++members;
+                take(base + w * 64 + b);
             }
         }
     }
@@ -736,17 +776,25 @@ __global__ __launch_bounds__(256) void k_group_mean(const int *__restrict__ root
     if (t == 0) invn[r] = inv_length(c2);
 }
 
-// Exclusive scan of the "row survives" flags by one 1024-thread block; total -> *total.
-__global__ __launch_bounds__(1024) void k_scan_survivors(const int *__restrict__ root, long K, int *newpos, u64 *total) {
+// Exclusive scan by one 1024-thread block, four entries per thread and trip; total -> *total.
+// The entries are vals[i], or, without vals, the flags "row i survives" (root[i] == i).
+__global__ __launch_bounds__(1024) void k_scan_exclusive(const int *__restrict__ vals, const int *__restrict__ root, long K,
+                                                          int *out, u64 *total) {
     __shared__ int wsum[16];
     __shared__ int carry_s;
     const int t = threadIdx.x, lane = t & 63, w = t >> 6;
     if (t == 0) carry_s = 0;
     __syncthreads();
-    for (long base = 0; base < K; base += 1024) {
-        const long i = base + t;
-        const int flag = (i < K && root[i] == (int)i) ? 1 : 0;
-        int incl = flag;
+    for (long base = 0; base < K; base += 4096) {
+        const long i0 = base + 4 * t;
+        int v[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const long i = i0 + k;
+            v[k] = i < K ? (vals ? vals[i] : (root[i] == (int)i ? 1 : 0)) : 0;
+        }
+        const int mine = (v[0] + v[1]) + (v[2] + v[3]);
+        int incl = mine;
 #pragma unroll
         for (int off = 1; off < 64; off <<= 1) {
             const int o = __shfl_up(incl, off);
@@ -756,14 +804,18 @@ __global__ __launch_bounds__(1024) void k_scan_survivors(const int *__restrict__
         __syncthreads();
         int before = carry_s;
         for (int k = 0; k < w; ++k) before += wsum[k];
-        if (i < K) newpos[i] = before + incl - flag;
+        int run = before + incl - mine;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            if (i0 + k < K) out[i0 + k] = run;
+            run += v[k];
+        }
         __syncthreads();
         if (t == 1023) carry_s = before + incl;
         __syncthreads();
     }
-    if (t == 0) *total = (u64)carry_s;
+    if (total && t == 0) *total = (u64)carry_s;
 }
-
 template <typename T>
 __global__ __launch_bounds__(256) void k_gather_rows(const int *__restrict__ root, const int *__restrict__ newpos,
                                                       const T *__restrict__ cent, const float *__restrict__ mean,
@@ -1106,7 +1158,8 @@ extern "C" int siso_merge_apply(siso_cache *c, const int *pairs, long n_pairs, i
         if (rc != SISO_OK) return rc;
         if (v != 0) return siso_fail(c, SISO_EINVAL, "siso_merge_apply: %llu invalid pairs", v);
     }
-    int *parent = nullptr, *root = nullptr, *newpos = nullptr;
+    int *parent = nullptr, *root = nullptr, *newpos = nullptr, *members_of = nullptr, *cursor = nullptr, *first = nullptr,
+        *list = nullptr;
     unsigned char *touched = nullptr;
     void *cent2 = nullptr;
     float *mean2 = nullptr, *invn2 = nullptr, *loc2 = nullptr;
@@ -1117,23 +1170,32 @@ extern "C" int siso_merge_apply(siso_cache *c, const int *pairs, long n_pairs, i
     ok = ok && hipMalloc((void **)&root, (size_t)K * sizeof(int)) == hipSuccess;
     ok = ok && hipMalloc((void **)&newpos, (size_t)K * sizeof(int)) == hipSuccess;
     ok = ok && hipMalloc((void **)&touched, (size_t)K) == hipSuccess;
+    ok = ok && hipMalloc((void **)&members_of, (size_t)K * 4 * sizeof(int)) == hipSuccess;  // four arrays of K
     if (!ok) {
         (void)hipGetLastError();
         rc = siso_fail(c, SISO_ENOMEM, "siso_merge_apply: temporaries");
+    } else {
+        cursor = members_of + K;
+        first = cursor + K;
+        list = first + K;
     }
     long live = K;
     if (rc == SISO_OK) {
-        hipLaunchKernelGGL(k_uf_init, dim3(kb), dim3(256), 0, c->stream, parent, touched, K);
+        hipLaunchKernelGGL(k_uf_init, dim3(kb), dim3(256), 0, c->stream, parent, touched, members_of, cursor, K);
         if (n_pairs > 0)
             hipLaunchKernelGGL(k_uf_hook, dim3(pb), dim3(256), 0, c->stream, pairs, n_pairs, parent, touched);
         hipLaunchKernelGGL(k_uf_roots, dim3(kb), dim3(256), 0, c->stream, parent, root, K);
+        hipLaunchKernelGGL(k_group_count, dim3(kb), dim3(256), 0, c->stream, root, touched, K, members_of);
+        hipLaunchKernelGGL(k_scan_exclusive, dim3(1), dim3(1024), 0, c->stream, members_of, root, K, first, (u64 *)nullptr);
+        hipLaunchKernelGGL(k_group_fill, dim3(kb), dim3(256), 0, c->stream, root, touched, K, first, cursor, list);
         if (c->dtype == SISO_F32)
-            hipLaunchKernelGGL(k_group_mean<float>, dim3((unsigned)K), dim3(256), 0, c->stream, root, touched, K,
-                               (float *)c->cent, c->mean, c->size, c->invn, c->locality, c->access, d);
+            hipLaunchKernelGGL(k_group_mean<float>, dim3((unsigned)K), dim3(256), 0, c->stream, root, touched, K, members_of,
+                               first, list, (float *)c->cent, c->mean, c->size, c->invn, c->locality, c->access, d);
         else
-            hipLaunchKernelGGL(k_group_mean<bf16_t>, dim3((unsigned)K), dim3(256), 0, c->stream, root, touched, K,
-                               (bf16_t *)c->cent, c->mean, c->size, c->invn, c->locality, c->access, d);
-        hipLaunchKernelGGL(k_scan_survivors, dim3(1), dim3(1024), 0, c->stream, root, K, newpos, c->counters + 3);
+            hipLaunchKernelGGL(k_group_mean<bf16_t>, dim3((unsigned)K), dim3(256), 0, c->stream, root, touched, K, members_of,
+                               first, list, (bf16_t *)c->cent, c->mean, c->size, c->invn, c->locality, c->access, d);
+        hipLaunchKernelGGL(k_scan_exclusive, dim3(1), dim3(1024), 0, c->stream, (const int *)nullptr, root, K, newpos,
+                           c->counters + 3);
         rc = siso_check_hip(c, hipGetLastError(), "merge_apply kernels");
         if (rc == SISO_OK) rc = siso_read_counter(c, 3, &v);
         if (rc == SISO_OK) live = (long)v;
@@ -1187,6 +1249,7 @@ extern "C" int siso_merge_apply(siso_cache *c, const int *pairs, long n_pairs, i
     if (root) (void)hipFree(root);
     if (newpos) (void)hipFree(newpos);
     if (touched) (void)hipFree(touched);
+    if (members_of) (void)hipFree(members_of);
     if (cent2) (void)hipFree(cent2);
     if (mean2) (void)hipFree(mean2);
     if (size2) (void)hipFree(size2);

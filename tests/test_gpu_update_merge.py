@@ -229,3 +229,31 @@ def test_merge_dense_pairs_overflow_the_staging_buffer(siso, oracle):
     few = few.cpu().numpy()
     assert t2 == total and few.shape[0] == 5000 and len(np.unique(few, axis=0)) == 5000
     assert set(map(tuple, few)) <= set(map(tuple, want))
+
+
+def test_merge_apply_groups_of_many_sizes(siso, oracle):
+    """Groups given as chains of pairs in a shuffled order: of 2, 3, 257 and 700 rows (sorted by their
+    block in LDS, several entries per thread) and of 1,500 rows (beyond the list a block sorts: the block
+    searches the root array instead), with different weights, among rows that stay alone."""
+    dim, dtype = 128, "bf16"
+    sizes = [2, 3, 257, 700, 1500]
+    K = sum(sizes) + 40
+    print(f"case: merge_apply groups of {sizes} rows, K={K}", flush=True)
+    rng = np.random.default_rng(77)
+    rows = W.to_storage(W.uniform_directions(78, 2, K, dim), dtype)
+    counts = rng.integers(1, 9, size=K).astype(np.int32)
+    perm = rng.permutation(K)
+    pairs, at = [], 0
+    for m in sizes:
+        mem = perm[at:at + m]
+        at += m
+        pairs += [(int(mem[i]), int(mem[i + 1])) for i in range(m - 1)]
+    pairs = np.array(pairs, np.int32)[rng.permutation(len(pairs))]
+    cache = siso.SisoCache(dim, K, siso.BF16)
+    cache.load(to_dev(rows, dtype), torch.from_numpy(counts).to(DEV))
+    oc = oracle.OracleCache(dim, K, dtype)
+    oc.load(rows, counts)
+    surv = cache.merge_apply(torch.from_numpy(pairs).to(DEV))
+    assert np.array_equal(surv.cpu().numpy(), oc.merge_apply(pairs))
+    assert cache.count == oc.count == K - sum(sizes) + len(sizes)
+    compare_state(cache, oc, dtype, "groups of many sizes")
