@@ -29,7 +29,7 @@
  *     all pairs); connected groups are replaced by their count-weighted mean,
  *     the cluster sizes add up (Algorithm 1, MergeCentroids, cluster_size).
  *
- * Readings where the paper is silent (all listed in the design notes):
+ * Readings where the paper is silent:
  *   - vectors are taken at storage precision (bf16 or fp32 widened exactly to
  *     double); similarities are true cosines of the stored values;
  *   - a zero-length vector has similarity 0 to everything; a query holding a
@@ -664,7 +664,7 @@ int oracle_adjust_threshold(const float *thetas, int m, int index, double w_est,
  * cluster gets an id, its centroid (the average of its members, section 3.1)
  * and cluster_size (the number of its members).  The paper names the algorithm
  * and its threshold and cites it; the steps below are that published greedy
- * scheme, a reading listed in the design notes:
+ * scheme (a reading: the paper itself prints no steps):
  *   1. two vectors are neighbours when their cosine exceeds theta_c (strictly,
  *      as every threshold test of the paper);
  *   2. the candidate community of vector i is i together with its neighbours;
