@@ -135,8 +135,8 @@ def main():
     merge_info = None
 
     if name == "c5_merge":
-        steps = args.steps or 5
-        warmup = args.warmup if args.warmup is not None else 1
+        steps = args.steps or 10
+        warmup = args.warmup if args.warmup is not None else 2
         theta = wl.thresholds[0]
         cap = wl.meta["expected_pairs"] + 1024
         for _ in range(warmup):
@@ -180,8 +180,10 @@ def main():
     nb = wl.batch if streaming else wl.n
     n_batches = wl.n // nb
     queries = to_dev(wl.queries, "bf16")
-    steps = args.steps or (1024 if streaming else 20)
-    warmup = args.warmup if args.warmup is not None else (32 if streaming else 3)
+    # enough steps for a steady state (the first ones run on a chip that is still ramping its clocks up):
+    # the whole stream of 4,096 batches; 200 mid-size batches; 10 large ones
+    steps = args.steps or (4096 if streaming else 10 if name == "c3_large" else 200)
+    warmup = args.warmup if args.warmup is not None else (64 if streaming else 2 if name == "c3_large" else 10)
     thetas = list(wl.thresholds)
     idx = torch.empty(nb, dtype=torch.int32, device="cuda:0")
     sim = torch.empty(nb, dtype=torch.float32, device="cuda:0")
