@@ -76,7 +76,7 @@ def lib() -> C.CDLL:
         L.oracle_pick_threshold.restype = it
         L.oracle_adjust_threshold.argtypes = [vp, it, it, db, db]
         L.oracle_adjust_threshold.restype = it
-        L.oracle_cluster.argtypes = [vp, vp, lg, fl, it, vp, vp, vp]
+        L.oracle_cluster.argtypes = [vp, vp, lg, fl, it, vp, vp, vp, vp, vp]
         L.oracle_cluster.restype = lg
         _lib = L
     return _lib
@@ -193,18 +193,23 @@ class OracleCache:
             raise RuntimeError(f"oracle_refresh failed ({rc})")
         return int(stats[0]), int(stats[1]), int(stats[2]), float(margin.value)
 
-    def cluster(self, vectors: np.ndarray, theta_c: float, min_size: int = 1):
+    def cluster(self, vectors: np.ndarray, theta_c: float, min_size: int = 1, representatives: bool = False):
         """Community detection; the cache becomes the repository of the clusters.
-        Returns ``(labels int32 [n], seeds int32 [clusters], min_margin)``."""
+        Returns ``(labels int32 [n], seeds int32 [clusters], min_margin)``, with ``representatives``
+        also ``(rep int32 [clusters], rep_gap float64 [clusters])``: the member closest to each centroid."""
         rows = _storage(vectors, self.dtype, self.dim)
         n = rows.shape[0]
         labels = np.full(n, -1, np.int32)
         seeds = np.zeros(max(n, 1), np.int32)
+        rep = np.zeros(max(n, 1), np.int32)
+        gap = np.zeros(max(n, 1), np.float64)
         margin = C.c_double(0.0)
         rc = lib().oracle_cluster(self._h, _ptr(rows), n, float(theta_c), int(min_size), _ptr(labels), _ptr(seeds),
-                                  C.byref(margin))
+                                  _ptr(rep), _ptr(gap), C.byref(margin))
         if rc < 0:
             raise RuntimeError(f"oracle_cluster failed ({rc})")
+        if representatives:
+            return labels, seeds[:rc].copy(), float(margin.value), rep[:rc].copy(), gap[:rc].copy()
         return labels, seeds[:rc].copy(), float(margin.value)
 
     def t2h(self, queries: np.ndarray, thetas) -> np.ndarray:

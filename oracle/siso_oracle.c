@@ -679,14 +679,20 @@ int oracle_adjust_threshold(const float *thetas, int m, int index, double w_est,
  * stored centroid = mean / |mean| rounded to the storage type (a zero row if the
  * mean has no length), access_count 0.
  *
+ * The repository also names, per cluster, the input query closest to the centroid
+ * (its output text stands for the cluster, "Keeping centroids in a repository"):
+ * out_rep [clusters] = the member with the largest cosine to the mean, the lowest
+ * index among equals; out_rep_gap [clusters] = that cosine minus the second
+ * largest (infinity for a cluster of one).
+ *
  * out_label [n], out_seed [number of clusters] (the vector whose candidate
- * formed the cluster; room for n) and min_margin (the smallest |cosine -
- * theta_c| over all pairs) may each be NULL.  Returns the number of clusters;
+ * formed the cluster; room for n), out_rep, out_rep_gap (room for n each) and
+ * min_margin (the smallest |cosine - theta_c| over all pairs) may each be NULL.  Returns the number of clusters;
  * -1 bad arguments or a vector that is not finite or has no length; -2 out of
  * memory; -3 more clusters than the capacity of c (nothing changed then).
  */
 long oracle_cluster(oracle_cache *c, const void *vectors, long n, float theta_c, int min_size,
-                    int *out_label, int *out_seed, double *min_margin) {
+                    int *out_label, int *out_seed, int *out_rep, double *out_rep_gap, double *min_margin) {
     if (!c || n < 0 || min_size < 1 || (n > 0 && !vectors)) return -1;
     const int d = c->dim, dt = c->dtype;
     const long n1 = n > 0 ? n : 1;
@@ -759,6 +765,19 @@ long oracle_cluster(oracle_cache *c, const void *vectors, long n, float theta_c,
             }
             const double len = sqrt(sq);
             for (int t = 0; t < d; ++t) store(c->cent, dt, (size_t)k * d + t, len > 0.0 ? m[t] / len : 0.0);
+            /* the member closest to the centroid: cosine(x_i, m) = <x_i, m> / (|x_i| |m|) */
+            long rep = -1;
+            double best = -INFINITY, second = -INFINITY;
+            for (long i = 0; i < n; ++i) {
+                if (label[i] != (int)k) continue;
+                double dot = 0.0;
+                for (int t = 0; t < d; ++t) dot += widen(vectors, dt, (size_t)i * d + t) * m[t];
+                const double cs = len > 0.0 ? dot / (norm[i] * len) : 0.0;
+                if (cs > best) { second = best; best = cs; rep = i; }   /* ascending i: the lowest index keeps a tie */
+                else if (cs > second) second = cs;
+            }
+            if (out_rep) out_rep[k] = (int)rep;
+            if (out_rep_gap) out_rep_gap[k] = best - second;
             c->size[k] = (int)members;
             c->locality[k] = (float)members;
             c->access[k] = 0;

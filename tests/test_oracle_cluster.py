@@ -26,6 +26,9 @@ def golden():
         if t[0] == "v":
             assert int(t[1]) == len(angles)
             angles.append(float(t[2]))
+        elif t[0] == "rep_case":
+            cases["rep"] = {"angles": [float(v) for v in t[2:t.index("rep")]], "rep": int(t[t.index("rep") + 1]),
+                            "gap": float(t[t.index("gap") + 1])}
         elif t[0] == "min_size":
             case = cases.setdefault(int(t[1]), {})
             rest, key = t[2:], None
@@ -156,3 +159,35 @@ def test_cluster_rejects_what_it_cannot_place(oracle):
     bad[1, 0] = np.nan
     with pytest.raises(RuntimeError):
         big.cluster(bad, 0.9, 1)
+
+
+def test_representative_hand_worked(oracle):
+    angles, cases = golden()
+    # cluster 1 of the first example: 0, 15, 30 degrees -> the middle one, ahead by 1 - cos 15 degrees
+    cache = oracle.OracleCache(8, 16, "f32")
+    labels, seeds, _, rep, gap = cache.cluster(plane(angles), 0.94, 2, representatives=True)
+    assert rep[1] == 1 and gap[1] == pytest.approx(1 - math.cos(math.radians(15)), abs=1e-6)
+    assert all(labels[rep[k]] == k for k in range(len(seeds)))
+    # the lopsided example
+    c = cases["rep"]
+    labels, seeds, _, rep, gap = cache.cluster(plane(c["angles"]), 0.94, 2, representatives=True)
+    assert labels.tolist() == [0, 0, 0] and rep.tolist() == [c["rep"]]
+    assert gap[0] == pytest.approx(c["gap"], abs=2e-5)
+    # a cluster of one stands for itself; two exact copies: the lower index
+    labels, seeds, _, rep, gap = cache.cluster(plane([10, 100, 100]), 0.94, 1, representatives=True)
+    assert labels.tolist() == [1, 0, 0] and rep.tolist() == [1, 0] and gap[0] == 0.0 and np.isinf(gap[1])
+
+
+def test_representative_against_numpy(oracle):
+    x, _ = W.query_log_chains(n_chains=8, dim=64, dtype="bf16", seed=12, sigma=0.1)
+    cache = oracle.OracleCache(64, len(x), "bf16")
+    labels, seeds, _, rep, gap = cache.cluster(x, 0.86, 2, representatives=True)
+    u = W.storage_to_f32(x, "bf16").astype(np.float64)
+    u /= np.linalg.norm(u, axis=1, keepdims=True)
+    for k in range(len(seeds)):
+        mem = np.flatnonzero(labels == k)
+        m = u[mem].mean(axis=0)
+        cs = np.sort(u[mem] @ (m / np.linalg.norm(m)))
+        best = mem[np.argmax(u[mem] @ m)]
+        assert rep[k] == best or gap[k] < 1e-12
+        assert gap[k] == pytest.approx(cs[-1] - cs[-2], abs=1e-12)
