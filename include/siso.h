@@ -225,6 +225,10 @@ int siso_export_meta(siso_cache *c, float *cluster_size, unsigned *access_count)
  *   theta_c:   clustering threshold;  min_size: smallest cluster kept (>= 1).
  *   out_label: device pointer, n ints, or NULL: cluster id of every vector,
  *              -1 for a vector that ends in no cluster.
+ *   out_representative: device pointer, room for min(n, capacity) ints, or
+ *              NULL: per cluster the member with the largest cosine to the
+ *              centroid (the lowest index among equals): the query whose
+ *              output text stands for the cluster in the repository.
  *   out_stats: HOST pointer to 2 longs or NULL: pairs above the threshold,
  *              vectors that ended in a cluster.
  * Two vectors are neighbours when their cosine exceeds theta_c (strictly).  The
@@ -246,7 +250,7 @@ int siso_export_meta(siso_cache *c, float *cluster_size, unsigned *access_count)
  * memory (the vectors once more, 8 bytes per pair).  Synchronises.
  */
 long siso_cluster(siso_cache *c, const void *vectors, long n, float theta_c, int min_size, int *out_label,
-                  long *out_stats);
+                  int *out_representative, long *out_stats);
 
 /*
  * Threshold-to-hit-ratio (T2H) table (section 4.3, "Adjusting theta_R to meet

@@ -61,12 +61,16 @@ __device__ __forceinline__ float block_total(float v, float *sh) {
 // One block per cluster k: members member[first[k] .. first[k+1]) in ascending order.
 // mean = average of the unit-length members; stored centroid = mean / |mean| rounded to the element
 // type (a zero row when the mean has no length); size = cluster_size = number of members; no references yet.
+// rep (nullable): the member with the largest cosine to the mean, the lowest index among equals.
 template <typename T>
 __global__ __launch_bounds__(256) void k_cluster_rows(const T *__restrict__ vec, const float *__restrict__ vinv,
                                                        const long *__restrict__ first, const int *__restrict__ member,
                                                        T *cent, float *mean, int *size, float *invn, float *locality,
-                                                       unsigned *access, int d) {
+                                                       unsigned *access, int *rep, int d) {
     __shared__ float sh[4];
+    __shared__ float sh_mean[SISO_MAX_DIM];
+    __shared__ float sh_best[4];
+    __shared__ int sh_who[4];
     const long k = blockIdx.x;
     const int t = threadIdx.x;
     const long lo = first[k], hi = first[k + 1];
@@ -80,6 +84,7 @@ __global__ __launch_bounds__(256) void k_cluster_rows(const T *__restrict__ vec,
         }
         const float m = acc / count;
         mean[(size_t)k * d + col] = m;
+        sh_mean[col] = m;
         ss += m * m;
     }
     const float n2 = block_total(ss, sh);
@@ -93,12 +98,41 @@ __global__ __launch_bounds__(256) void k_cluster_rows(const T *__restrict__ vec,
         const float back = widen(v);
         cs += back * back;
     }
-    const float c2 = block_total(cs, sh);
+    const float c2 = block_total(cs, sh);  // (its barriers also make the whole mean in LDS visible)
     if (t == 0) {
         size[k] = hi - lo > 2147483647L ? 2147483647 : (int)(hi - lo);
         invn[k] = inv_length(c2);
         locality[k] = count;
         access[k] = 0u;
+    }
+    if (!rep) return;
+    // the member closest to the centroid: cosine(x_j, m) = <x_j, m> / (|x_j| |m|), and |m| is the same for
+    // all of them.  One wave per member, members in ascending order within a wave.
+    const int lane = t & 63, wave = t >> 6;
+    float best = -INFINITY;
+    int who = 0x7FFFFFFF;
+    for (long p = lo + wave; p < hi; p += 4) {
+        const long j = member[p];
+        float dot = 0.f;
+        for (int col = lane; col < d; col += 64) dot += widen(vec[(size_t)j * d + col]) * sh_mean[col];
+        dot = wave_sum(dot) * vinv[j];
+        if (dot > best) {
+            best = dot;
+            who = (int)j;
+        }
+    }
+    if (lane == 0) {
+        sh_best[wave] = best;
+        sh_who[wave] = who;
+    }
+    __syncthreads();
+    if (t == 0) {
+        for (int w = 1; w < 4; ++w)
+            if (sh_best[w] > best || (sh_best[w] == best && sh_who[w] < who)) {
+                best = sh_best[w];
+                who = sh_who[w];
+            }
+        rep[k] = who;
     }
 }
 
@@ -122,7 +156,7 @@ struct DeviceMem {  // frees on every way out
 }  // namespace
 
 extern "C" long siso_cluster(siso_cache *c, const void *vectors, long n, float theta_c, int min_size, int *out_label,
-                             long *out_stats) {
+                             int *out_representative, long *out_stats) {
     if (!c) return SISO_EINVAL;
     if (out_stats) out_stats[0] = out_stats[1] = 0;
     if (n < 0 || min_size < 1 || (n > 0 && !vectors))
@@ -261,11 +295,11 @@ extern "C" long siso_cluster(siso_cache *c, const void *vectors, long n, float t
         if (c->dtype == SISO_F32)
             hipLaunchKernelGGL(k_cluster_rows<float>, dim3((unsigned)clusters), dim3(256), 0, st, d_rows.as<float>(),
                                d_inv.as<float>(), d_first.as<long>(), d_member.as<int>(), (float *)c->cent, c->mean, c->size,
-                               c->invn, c->locality, c->access, d);
+                               c->invn, c->locality, c->access, out_representative, d);
         else
             hipLaunchKernelGGL(k_cluster_rows<bf16_t>, dim3((unsigned)clusters), dim3(256), 0, st, d_rows.as<bf16_t>(),
                                d_inv.as<float>(), d_first.as<long>(), d_member.as<int>(), (bf16_t *)c->cent, c->mean, c->size,
-                               c->invn, c->locality, c->access, d);
+                               c->invn, c->locality, c->access, out_representative, d);
         CLUSTER_TRY(hipGetLastError(), "k_cluster_rows");
     }
     hipLaunchKernelGGL(k_nan_fill, dim3(1), dim3(SISO_PAD_ROWS), 0, st, c->invn + clusters, SISO_PAD_ROWS);

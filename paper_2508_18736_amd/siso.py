@@ -50,7 +50,7 @@ SYMBOLS = {
     "siso_last_error": ([_vp], C.c_char_p),
     "siso_probe": ([_it, C.POINTER(C.c_double)], _it),
     "siso_refresh": ([_vp, _vp, _vp, _lg, _fl, _lg, _vp], _it),
-    "siso_cluster": ([_vp, _vp, _lg, _fl, _it, _vp, _vp], _lg),
+    "siso_cluster": ([_vp, _vp, _lg, _fl, _it, _vp, _vp, _vp], _lg),
     "siso_export_meta": ([_vp, _vp, _vp], _it),
     "siso_t2h": ([_vp, _vp, _lg, _vp, _it, _vp], _it),
     "siso_md1_wait": ([C.c_double, C.c_double, C.c_double], C.c_double),
@@ -230,15 +230,20 @@ class SisoCache:
                                       int(max_centroids), stats))
         return int(stats[0]), int(stats[1]), int(stats[2])
 
-    def cluster(self, vectors: torch.Tensor, theta_c: float, min_size: int = 1):
+    def cluster(self, vectors: torch.Tensor, theta_c: float, min_size: int = 1, representatives: bool = False):
         """Community detection over the vectors; this cache becomes the repository of the clusters.
-        Returns ``(labels int32 [n] on the device, number of clusters, pairs above the threshold)``."""
+        Returns ``(labels int32 [n] on the device, number of clusters, pairs above the threshold)``; with
+        ``representatives`` also the member closest to each centroid (int32 [clusters] on the device)."""
         rows = self._rows(vectors, "vectors")
         labels = torch.empty(rows.shape[0], dtype=torch.int32, device=self.device)
+        rep = torch.empty(min(rows.shape[0], self.capacity), dtype=torch.int32, device=self.device) if representatives else None
         stats = (C.c_long * 2)()
-        rc = _lib.siso_cluster(self._h, _ptr(rows), rows.shape[0], float(theta_c), int(min_size), _ptr(labels), stats)
+        rc = _lib.siso_cluster(self._h, _ptr(rows), rows.shape[0], float(theta_c), int(min_size), _ptr(labels),
+                               _ptr(rep) if representatives else None, stats)
         if rc < 0:
             self._check(int(rc))
+        if representatives:
+            return labels, int(rc), int(stats[0]), rep[:int(rc)]
         return labels, int(rc), int(stats[0])
 
     def export_meta(self) -> Tuple[torch.Tensor, torch.Tensor]:

@@ -24,14 +24,22 @@ def siso():
 
 
 def run_both(siso, oracle, x, dtype, dim, theta, min_size, capacity=None):
+    """Clusters on both sides; the representatives (the member closest to each centroid) are compared here:
+    equal wherever the oracle's best member leads the second best by more than single precision can blur."""
     n = len(x)
     capacity = capacity or max(n, 1)
     ora = oracle.OracleCache(dim, capacity, dtype)
-    want_labels, seeds, margin = ora.cluster(x, theta, min_size)
+    want_labels, seeds, margin, want_rep, rep_gap = ora.cluster(x, theta, min_size, representatives=True)
     gpu = siso.SisoCache(dim, capacity, siso_dtype(dtype))
-    labels, clusters, pairs = gpu.cluster(to_dev(x, dtype), theta, min_size)
+    labels, clusters, pairs, rep = gpu.cluster(to_dev(x, dtype), theta, min_size, representatives=True)
     torch.cuda.synchronize()
-    return ora, gpu, want_labels, seeds, margin, labels.cpu().numpy(), clusters, pairs
+    got_labels, rep = labels.cpu().numpy(), rep.cpu().numpy()
+    if clusters == len(seeds) and np.array_equal(got_labels, want_labels):
+        clear = rep_gap > 1e-5
+        assert np.array_equal(rep[clear], want_rep[clear]), "representatives differ"
+        assert all(got_labels[rep[k]] == k for k in range(clusters)), "a representative outside its cluster"
+        print(f"  representatives: {int(clear.sum())} of {clusters} compared", flush=True)
+    return ora, gpu, want_labels, seeds, margin, got_labels, clusters, pairs
 
 
 @pytest.mark.parametrize("dtype,dim,chains,min_size,seed", [
