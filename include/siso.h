@@ -14,7 +14,15 @@
  *             threshold (the comparison inside MergeCentroids taken over all
  *             pairs), then merging connected groups into their count-weighted
  *             mean while their cluster sizes add up (Algorithm 1,
- *             cluster_size).
+ *             cluster_size);
+ *   refresh - the cache replacement of Algorithm 1 (MergeCentroids,
+ *             FilteringCentroids, UpdateCentroids; section 4.2), with the
+ *             access counts that lookups keep;
+ *   t2h     - the threshold-to-hit-ratio table of a query sample and the choice
+ *             of the retrieval threshold from the M/D/1 waiting time
+ *             (section 4.3, equations 1 and 2);
+ *   cluster - community detection over a query log at the clustering threshold,
+ *             one repository row per cluster (section 4.1).
  *
  * Conventions
  *   - "device pointer" = memory of the current HIP device, owned by the caller,
@@ -61,8 +69,9 @@ enum {
  * Create a cache for `capacity` centroids of `dim` elements (bf16 storage for
  * siso_create).  dim must be in [1, 4096]; capacity in [1, 2^31 - 1].
  * Allocates device memory: per centroid dim * (2 or 4) bytes for the stored
- * vector, 4 * dim bytes for its running mean, 8 bytes for its inverse length
- * and cluster size.  *out receives the handle.  Synchronises.
+ * vector, 4 * dim bytes for its running mean, 16 bytes for its inverse length,
+ * the weight of its mean, cluster_size and access_count.  *out receives the
+ * handle.  Synchronises.
  */
 int siso_create(int dim, long capacity, siso_cache **out);
 int siso_create_ex(int dim, long capacity, int dtype, siso_cache **out);
