@@ -191,3 +191,23 @@ def test_representative_against_numpy(oracle):
         best = mem[np.argmax(u[mem] @ m)]
         assert rep[k] == best or gap[k] < 1e-12
         assert gap[k] == pytest.approx(cs[-1] - cs[-2], abs=1e-12)
+
+
+def test_clusters_are_stars_not_cliques(oracle):
+    """What Table 2 reports for the method: members of a cluster are close to one common vector, not
+    necessarily to each other, so the smallest similarity inside a cluster lies below the clustering
+    threshold (0.80 against 0.86 in the paper) while the average stays high."""
+    x, _ = W.query_log_chains(n_chains=12, dim=128, dtype="bf16", seed=21)
+    cache = oracle.OracleCache(128, len(x), "bf16")
+    labels, seeds, _ = cache.cluster(x, 0.86, 2)
+    u = W.storage_to_f32(x, "bf16").astype(np.float64)
+    u /= np.linalg.norm(u, axis=1, keepdims=True)
+    inside = []
+    for k in range(len(seeds)):
+        mem = np.flatnonzero(labels == k)
+        s = (u[mem] @ u[mem].T)[np.triu_indices(len(mem), 1)]
+        inside.append(s)
+        founder = seeds[k]
+        assert all(u[m] @ u[founder] > 0.86 for m in mem if m != founder)
+    inside = np.concatenate(inside)
+    assert 0.70 < inside.min() < 0.86 and inside.mean() > 0.90
