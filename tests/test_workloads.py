@@ -62,3 +62,39 @@ def test_zipf_stream_and_drift():
     q = wl.queries_f32(); c = wl.centroids_f32()
     cos = np.einsum("ij,ij->i", q, c[wl.planted])
     assert cos.min() > 0.98
+
+
+def test_query_log_chains_structure():
+    """The clustering log: members of a topic are close, neighbouring topics of a chain overlap at the
+    clustering threshold, second neighbours and unrelated directions do not; same seed, same log."""
+    x, topic = W.query_log_chains(n_chains=5, chain_len=4, dim=256, seed=9, n_noise=10)
+    x2, topic2 = W.query_log_chains(n_chains=5, chain_len=4, dim=256, seed=9, n_noise=10)
+    assert np.array_equal(x, x2) and np.array_equal(topic, topic2)
+    u = W.storage_to_f32(x, "bf16").astype(np.float64)
+    assert np.allclose(np.linalg.norm(u, axis=1), 1.0, atol=4e-3)
+    s = u @ u.T
+    related = topic >= 0
+    assert (topic == -1).sum() == 10 and related.sum() > 40
+    for i in np.flatnonzero(related):
+        for j in np.flatnonzero(related):
+            if i >= j:
+                continue
+            a, b = topic[i], topic[j]
+            same_chain = a // 4 == b // 4
+            if a == b:
+                assert s[i, j] > 0.97
+            elif same_chain and abs(a - b) == 1:
+                assert 0.87 < s[i, j] < 0.93
+            elif same_chain and abs(a - b) == 2:
+                assert s[i, j] < 0.85
+            elif not same_chain:
+                assert abs(s[i, j]) < 0.4
+    assert np.abs(s[~related][:, related]).max() < 0.4
+
+
+def test_cone_moves_unrelated_directions_together():
+    x = W.uniform_directions(3, 1, 200, 512)
+    y = W.into_cone(x, 3, 1.28)
+    s = (y @ y.T)[np.triu_indices(200, 1)]
+    assert abs(np.median(s) - 1.28 ** 2 / (1 + 1.28 ** 2)) < 0.02 and np.allclose(np.linalg.norm(y, axis=1), 1, atol=1e-5)
+    assert W.into_cone(x, 3, 0.0) is x
