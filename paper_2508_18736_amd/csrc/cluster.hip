@@ -196,7 +196,8 @@ extern "C" long siso_cluster(siso_cache *c, const void *vectors, long n, float t
         if (rc != SISO_OK) return rc;
         if (bad != 0) return siso_fail(c, SISO_EINVAL, "siso_cluster: %llu vectors are not finite or have no length", bad);
 
-        long cap = n * 8 > (1L << 20) ? n * 8 : (1L << 20);
+        // room for 32 pairs per vector at first (256 bytes each); a log with more gets a second pass with the exact room
+        long cap = n * 32 > (1L << 20) ? n * 32 : (1L << 20);
         for (int attempt = 0; attempt < 2 && n >= 2; ++attempt) {
             if (!d_pairs.alloc((size_t)cap * 2 * sizeof(int))) {
                 (void)hipGetLastError();

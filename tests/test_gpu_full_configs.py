@@ -269,3 +269,19 @@ def test_cluster_full_size(siso, oracle):
     for g in groups:
         sel = wl.cluster_of[rows] == g
         assert len(set(want[sel].tolist())) == 1 and want[sel][0] >= 0 and (want[sel][0] != want[~sel]).all()
+
+
+def test_cluster_a_million_vectors(siso):
+    """The 1,048,576 rows of the large workload as a query log: 32,768 topics of 32 near-duplicates,
+    16 million neighbour pairs.  Properties that hold by construction: the topics come back as
+    generated, in the order of their first rows, every cluster with 32 members."""
+    print("case: cluster 1,048,576 vectors", flush=True)
+    wl = W.c3_large(n_queries=64)
+    repo = siso.SisoCache(wl.dim, 32768, siso.BF16)
+    labels, clusters, pairs = repo.cluster(to_dev(wl.centroids, "bf16"), 0.86, 2)
+    assert clusters == 32768 and pairs == 32768 * (32 * 31 // 2)
+    first = np.full(32768, wl.K, np.int64)
+    np.minimum.at(first, wl.cluster_of, np.arange(wl.K))
+    newidx = np.empty(32768, np.int64); newidx[np.argsort(first)] = np.arange(32768)
+    assert np.array_equal(labels.cpu().numpy(), newidx[wl.cluster_of])
+    assert bool((repo.export()[2] == 32).all())
