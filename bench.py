@@ -97,6 +97,30 @@ def cpu_baseline(wl, n_batch, seconds):
             "sample": f"first {m} queries of the workload against all {wl.K} centroids, {dt:.1f} s"}
 
 
+def cpu_baseline_pairs(wl, theta, seconds):
+    """The oracle's pair search on the first m rows; its cost grows with the square of the rows, so the
+    rate for the whole triangle is the measured one scaled by (m / K)."""
+    import oracle
+
+    oracle.build()
+    threads = oracle.threads()
+
+    def run(m):
+        oc = oracle.OracleCache(wl.dim, m, wl.dtype)
+        oc.load(wl.centroids[:m])
+        t0 = time.perf_counter()
+        oc.merge(theta, cap=0)
+        return time.perf_counter() - t0
+
+    run(1024)
+    t = run(4096)
+    m = int(min(wl.K, max(4096, 4096 * (seconds / max(t, 1e-6)) ** 0.5)))
+    dt = run(m)
+    return {"value": m / dt * (m / wl.K), "unit": "rows/s", "cores": threads, "kind": "oracle",
+            "sample": f"all pairs of the first {m} rows in {dt:.1f} s ({m / dt:.0f} rows/s); the work grows with the "
+                      f"square of the rows, so the rate for all {wl.K} rows is that times {m}/{wl.K}"}
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -174,6 +198,8 @@ def main():
                                  "unit": "TFLOP/s", "frac": flop / avg_s / 1e12 / PEAK_BF16_TFLOPS,
                                  "traffic": measured_traffic(name), "kernel_ms": avg_s * 1e3}})
         add_measured_peak(siso, out["roofline"])
+        if not args.no_cpu_baseline:
+            out["cpu_baseline"] = cpu_baseline_pairs(wl, theta, args.cpu_seconds)
         print(json.dumps(out))
         return
 
