@@ -116,3 +116,16 @@ def test_cluster_edge_cases(siso, oracle):
     with pytest.raises(RuntimeError):
         gpu.cluster(to_dev(bad, "bf16"), 0.86, 1)
     assert gpu.count == 5
+
+
+@pytest.mark.parametrize("dtype,dim", [("f32", 98), ("bf16", 100), ("f32", 7), ("bf16", 4096)])
+def test_cluster_odd_dimensions(siso, oracle, dtype, dim):
+    """Dimensions that the MFMA pair search does not take (scalar kernels), the smallest and the largest."""
+    print(f"case: cluster dtype={dtype} dim={dim}", flush=True)
+    if dim >= 64:
+        x, _ = W.query_log_chains(n_chains=6, dim=dim, dtype=dtype, seed=dim)
+    else:
+        x = W.to_storage(W.uniform_directions(dim, 1, 120, dim), dtype)
+    ora, gpu, want, seeds, margin, got, clusters, pairs = run_both(siso, oracle, x, dtype, dim, 0.86, 1)
+    assert margin > 1e-3 and clusters == len(seeds) and np.array_equal(got, want)
+    compare_state(gpu, ora, dtype, "odd dimension")
