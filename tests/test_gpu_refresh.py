@@ -108,7 +108,7 @@ def test_access_counts_vs_oracle(siso, oracle):
         _, sim, _, second = ora.lookup(wl.queries, theta)
         gpu.lookup(q, theta)
     assert (np.abs(sim - 0.9) > SIM_TOL["bf16"]).all() and (np.abs(sim - 0.5) > SIM_TOL["bf16"]).all()
-    assert ((sim - second) > 1e-3).all() or True  # ties between near-duplicates may split counts: compared per cluster below
+    # (a hit whose two best centroids are closer than the gap bar may be counted for either of them)
     ol, oa = ora.export_meta()
     gl, ga = gpu.export_meta()
     ga = ga.cpu().numpy().astype(np.uint32)
