@@ -94,6 +94,8 @@ int siso_set_lookup_path(siso_cache *c, int path);
  *   "tiles_per_slice" 0 = default; >0 = centroid tiles one workgroup walks through
  *   "merge_config"    0 = default; 1 = use the scalar pair search
  *   "mfma_qblock"     0 = default; 1, 2, 4, 8, 16, 32 = query tiles that share an XCD's centroid tiles
+ *   "second_set"      1 = allocate now the second set of arrays that siso_merge_apply and siso_refresh
+ *                     gather the rebuilt cache into (otherwise their first call does); synchronises
  * Unknown names or values out of range give SISO_EINVAL.
  */
 int siso_set_option(siso_cache *c, const char *name, long value);
@@ -171,7 +173,11 @@ long siso_merge(siso_cache *c, float threshold, int *out_pairs, long cap);
  * The lowest index of a group survives with mean = sum size_i mean_i / sum size_i,
  * size = sum size_i, stored centroid = mean / |mean| rounded to the element
  * type; rows in no pair are untouched.  Survivors are packed to the front in
- * their old order and the count shrinks.  Allocates temporary device memory.
+ * their old order and the count shrinks.  The survivors are gathered into a
+ * second set of the cache's arrays, which then changes places with the first:
+ * the first call that rebuilds the cache (this one or siso_refresh) allocates
+ * that set, as much device memory again as siso_create took (option
+ * "second_set" does it ahead of time).  Allocates small temporaries per call.
  * Synchronises.
  */
 int siso_merge_apply(siso_cache *c, const int *pairs, long n_pairs, int *out_survivor);
@@ -213,7 +219,9 @@ int siso_export(siso_cache *c, void *centroids, float *means, int *counts);
  * runs on the GPU; the chain of decisions and the choice of the survivors are
  * bookkeeping on the host.  Nothing changes if an error is returned before the
  * update step (bad arguments, a non-finite row, a cluster size <= 0).
- * Allocates temporary device memory.  Synchronises.
+ * The new set is gathered into the second set of the cache's arrays (see
+ * siso_merge_apply), which then becomes the cache: nothing is copied back.
+ * Allocates temporary device memory for the repository.  Synchronises.
  *
  * siso_export_meta: copy out cluster_size [count] floats and access_count
  * [count] unsigned ints (device pointers, either may be NULL).  Asynchronous.

@@ -313,30 +313,27 @@ extern "C" int siso_refresh(siso_cache *c, const void *repo, const float *repo_s
     const long live = (long)keep.size();
 
     // ---- update step: gather the new set, then it becomes the cache ---------------------------
-    DeviceBuf d_src, d_cent2, d_mean2, d_size2, d_invn2;
+    DeviceBuf d_src;
     if (live > 0) {
-        const size_t cells = (size_t)live * d;
-        if (!d_src.alloc((size_t)live * sizeof(int)) || !d_cent2.alloc(cells * eb) || !d_mean2.alloc(cells * sizeof(float)) ||
-            !d_size2.alloc((size_t)live * sizeof(int)) || !d_invn2.alloc((size_t)live * sizeof(float))) {
+        const int rc2 = siso_second_set(c);
+        if (rc2 != SISO_OK) return rc2;
+        if (!d_src.alloc((size_t)live * sizeof(int))) {
             (void)hipGetLastError();
-            return siso_fail(c, SISO_ENOMEM, "siso_refresh: buffers for %ld centroids", live);
+            return siso_fail(c, SISO_ENOMEM, "siso_refresh: sources of %ld centroids", live);
         }
         REFRESH_TRY(hipMemcpyAsync(d_src.p, keep.data(), (size_t)live * sizeof(int), hipMemcpyHostToDevice, st), "sources to device");
         if (c->dtype == SISO_F32)
             hipLaunchKernelGGL(k_refresh_gather<float>, dim3((unsigned)live), dim3(256), 0, st, d_src.as<int>(), K0,
                                (const float *)c->cent, c->mean, c->size, c->invn, d_rows.as<float>(), d_rinv.as<float>(),
-                               repo_size, d_cent2.as<float>(), d_mean2.as<float>(), d_size2.as<int>(), d_invn2.as<float>(), d);
+                               repo_size, (float *)c->cent_b, c->mean_b, c->size_b, c->invn_b, d);
         else
             hipLaunchKernelGGL(k_refresh_gather<bf16_t>, dim3((unsigned)live), dim3(256), 0, st, d_src.as<int>(), K0,
                                (const bf16_t *)c->cent, c->mean, c->size, c->invn, d_rows.as<bf16_t>(), d_rinv.as<float>(),
-                               repo_size, d_cent2.as<bf16_t>(), d_mean2.as<float>(), d_size2.as<int>(), d_invn2.as<float>(), d);
+                               repo_size, (bf16_t *)c->cent_b, c->mean_b, c->size_b, c->invn_b, d);
         REFRESH_TRY(hipGetLastError(), "k_refresh_gather");
-        REFRESH_TRY(hipMemcpyAsync(c->cent, d_cent2.p, cells * eb, hipMemcpyDeviceToDevice, st), "new centroids");
-        REFRESH_TRY(hipMemcpyAsync(c->mean, d_mean2.p, cells * sizeof(float), hipMemcpyDeviceToDevice, st), "new means");
-        REFRESH_TRY(hipMemcpyAsync(c->size, d_size2.p, (size_t)live * sizeof(int), hipMemcpyDeviceToDevice, st), "new sizes");
-        REFRESH_TRY(hipMemcpyAsync(c->invn, d_invn2.p, (size_t)live * sizeof(float), hipMemcpyDeviceToDevice, st), "new inverse lengths");
-        REFRESH_TRY(hipMemcpyAsync(c->locality, loc2.data(), (size_t)live * sizeof(float), hipMemcpyHostToDevice, st), "new cluster sizes");
-        REFRESH_TRY(hipMemsetAsync(c->access, 0, (size_t)live * sizeof(unsigned), st), "reset access counts");
+        REFRESH_TRY(hipMemcpyAsync(c->locality_b, loc2.data(), (size_t)live * sizeof(float), hipMemcpyHostToDevice, st), "new cluster sizes");
+        REFRESH_TRY(hipMemsetAsync(c->access_b, 0, (size_t)live * sizeof(unsigned), st), "reset access counts");
+        siso_swap_sets(c);  // lookups enqueued from here on see the new set
     }
     hipLaunchKernelGGL(k_nan_tail, dim3(1), dim3(SISO_PAD_ROWS), 0, st, c->invn + live, SISO_PAD_ROWS);
     REFRESH_TRY(hipGetLastError(), "k_nan_tail");

@@ -8,6 +8,7 @@
 #include <string.h>
 
 #include <new>
+#include <utility>
 
 #include "siso_internal.h"
 
@@ -865,6 +866,48 @@ static int ensure_workspace(siso_cache *c, long n, int slices) {
     return SISO_OK;
 }
 
+int siso_second_set(siso_cache *c) {
+    if (c->cent_b) return SISO_OK;
+    const size_t cells = (size_t)c->capacity * c->dim;
+    const size_t cent_bytes = (cells + (size_t)SISO_PAD_ROWS * c->dim) * elem_bytes(c->dtype);
+    bool ok = hipMalloc(&c->cent_b, cent_bytes) == hipSuccess;
+    ok = ok && hipMemset(c->cent_b, 0, cent_bytes) == hipSuccess;
+    ok = ok && hipMalloc((void **)&c->mean_b, cells * sizeof(float)) == hipSuccess;
+    ok = ok && hipMalloc((void **)&c->size_b, (size_t)c->capacity * sizeof(int)) == hipSuccess;
+    ok = ok && hipMalloc((void **)&c->invn_b, ((size_t)c->capacity + SISO_PAD_ROWS) * sizeof(float)) == hipSuccess;
+    ok = ok && hipMemset(c->invn_b, 0, ((size_t)c->capacity + SISO_PAD_ROWS) * sizeof(float)) == hipSuccess;
+    ok = ok && hipMalloc((void **)&c->locality_b, (size_t)c->capacity * sizeof(float)) == hipSuccess;
+    ok = ok && hipMalloc((void **)&c->access_b, (size_t)c->capacity * sizeof(unsigned)) == hipSuccess;
+    ok = ok && hipDeviceSynchronize() == hipSuccess;
+    if (!ok) {
+        (void)hipGetLastError();
+        if (c->cent_b) (void)hipFree(c->cent_b);
+        if (c->mean_b) (void)hipFree(c->mean_b);
+        if (c->size_b) (void)hipFree(c->size_b);
+        if (c->invn_b) (void)hipFree(c->invn_b);
+        if (c->locality_b) (void)hipFree(c->locality_b);
+        if (c->access_b) (void)hipFree(c->access_b);
+        c->cent_b = nullptr;
+        c->mean_b = nullptr;
+        c->size_b = nullptr;
+        c->invn_b = nullptr;
+        c->locality_b = nullptr;
+        c->access_b = nullptr;
+        return siso_fail(c, SISO_ENOMEM, "second set of arrays for %ld centroids", c->capacity);
+    }
+    return SISO_OK;
+}
+
+// Work already enqueued keeps the pointers it was launched with; work enqueued from now on sees the new set.
+void siso_swap_sets(siso_cache *c) {
+    std::swap(c->cent, c->cent_b);
+    std::swap(c->mean, c->mean_b);
+    std::swap(c->size, c->size_b);
+    std::swap(c->invn, c->invn_b);
+    std::swap(c->locality, c->locality_b);
+    std::swap(c->access, c->access_b);
+}
+
 extern "C" int siso_create_ex(int dim, long capacity, int dtype, siso_cache **out) {
     if (!out) return SISO_EINVAL;
     *out = nullptr;
@@ -919,6 +962,12 @@ extern "C" void siso_destroy(siso_cache *c) {
     if (c->upd_owner) (void)hipFree(c->upd_owner);
     if (c->upd_members) (void)hipFree(c->upd_members);
     if (c->access) (void)hipFree(c->access);
+    if (c->cent_b) (void)hipFree(c->cent_b);
+    if (c->mean_b) (void)hipFree(c->mean_b);
+    if (c->size_b) (void)hipFree(c->size_b);
+    if (c->invn_b) (void)hipFree(c->invn_b);
+    if (c->locality_b) (void)hipFree(c->locality_b);
+    if (c->access_b) (void)hipFree(c->access_b);
     if (c->keys) (void)hipFree(c->keys);
     if (c->counters) (void)hipFree(c->counters);
     if (c->host_pin) (void)hipHostFree(c->host_pin);
@@ -950,6 +999,7 @@ extern "C" int siso_set_option(siso_cache *c, const char *name, long value) {
     else if (!strcmp(name, "tiles_per_slice")) c->opt_tiles_per_slice = (int)value;
     else if (!strcmp(name, "merge_config")) c->opt_merge_config = (int)value;
     else if (!strcmp(name, "mfma_qblock")) c->opt_mfma_qblock = (int)value;
+    else if (!strcmp(name, "second_set")) return value ? siso_second_set(c) : SISO_OK;
     else return siso_fail(c, SISO_EINVAL, "unknown option %s", name);
     return SISO_OK;
 }
@@ -1161,10 +1211,6 @@ extern "C" int siso_merge_apply(siso_cache *c, const int *pairs, long n_pairs, i
     int *parent = nullptr, *root = nullptr, *newpos = nullptr, *members_of = nullptr, *cursor = nullptr, *first = nullptr,
         *list = nullptr;
     unsigned char *touched = nullptr;
-    void *cent2 = nullptr;
-    float *mean2 = nullptr, *invn2 = nullptr, *loc2 = nullptr;
-    unsigned *acc2 = nullptr;
-    int *size2 = nullptr;
     int rc = SISO_OK;
     bool ok = hipMalloc((void **)&parent, (size_t)K * sizeof(int)) == hipSuccess;
     ok = ok && hipMalloc((void **)&root, (size_t)K * sizeof(int)) == hipSuccess;
@@ -1204,40 +1250,19 @@ extern "C" int siso_merge_apply(siso_cache *c, const int *pairs, long n_pairs, i
         hipLaunchKernelGGL(k_survivor_map, dim3(kb), dim3(256), 0, c->stream, root, newpos, K, out_survivor);
         rc = siso_check_hip(c, hipGetLastError(), "k_survivor_map");
     }
+    if (rc == SISO_OK && live < K) rc = siso_second_set(c);
     if (rc == SISO_OK && live < K) {
-        const size_t cells = (size_t)live * d;
-        ok = hipMalloc(&cent2, cells * elem_bytes(c->dtype)) == hipSuccess;
-        ok = ok && hipMalloc((void **)&mean2, cells * sizeof(float)) == hipSuccess;
-        ok = ok && hipMalloc((void **)&size2, (size_t)live * sizeof(int)) == hipSuccess;
-        ok = ok && hipMalloc((void **)&invn2, (size_t)live * sizeof(float)) == hipSuccess;
-        ok = ok && hipMalloc((void **)&loc2, (size_t)live * sizeof(float)) == hipSuccess;
-        ok = ok && hipMalloc((void **)&acc2, (size_t)live * sizeof(unsigned)) == hipSuccess;
-        if (!ok) {
-            (void)hipGetLastError();
-            rc = siso_fail(c, SISO_ENOMEM, "siso_merge_apply: compaction buffers");
-        } else {
-            if (c->dtype == SISO_F32)
-                hipLaunchKernelGGL(k_gather_rows<float>, dim3((unsigned)K), dim3(256), 0, c->stream, root, newpos,
-                                   (const float *)c->cent, c->mean, c->size, c->invn, c->locality, c->access,
-                                   (float *)cent2, mean2, size2, invn2, loc2, acc2, d);
-            else
-                hipLaunchKernelGGL(k_gather_rows<bf16_t>, dim3((unsigned)K), dim3(256), 0, c->stream, root, newpos,
-                                   (const bf16_t *)c->cent, c->mean, c->size, c->invn, c->locality, c->access,
-                                   (bf16_t *)cent2, mean2, size2, invn2, loc2, acc2, d);
-            rc = siso_check_hip(c, hipGetLastError(), "k_gather_rows");
-            if (rc == SISO_OK)
-                rc = siso_check_hip(c, hipMemcpyAsync(c->cent, cent2, cells * elem_bytes(c->dtype), hipMemcpyDeviceToDevice, c->stream), "copy back");
-            if (rc == SISO_OK)
-                rc = siso_check_hip(c, hipMemcpyAsync(c->mean, mean2, cells * sizeof(float), hipMemcpyDeviceToDevice, c->stream), "copy back");
-            if (rc == SISO_OK)
-                rc = siso_check_hip(c, hipMemcpyAsync(c->size, size2, (size_t)live * sizeof(int), hipMemcpyDeviceToDevice, c->stream), "copy back");
-            if (rc == SISO_OK)
-                rc = siso_check_hip(c, hipMemcpyAsync(c->invn, invn2, (size_t)live * sizeof(float), hipMemcpyDeviceToDevice, c->stream), "copy back");
-            if (rc == SISO_OK)
-                rc = siso_check_hip(c, hipMemcpyAsync(c->locality, loc2, (size_t)live * sizeof(float), hipMemcpyDeviceToDevice, c->stream), "copy back");
-            if (rc == SISO_OK)
-                rc = siso_check_hip(c, hipMemcpyAsync(c->access, acc2, (size_t)live * sizeof(unsigned), hipMemcpyDeviceToDevice, c->stream), "copy back");
-        }
+        // survivors packed to the front of the second set, which then becomes the cache
+        if (c->dtype == SISO_F32)
+            hipLaunchKernelGGL(k_gather_rows<float>, dim3((unsigned)K), dim3(256), 0, c->stream, root, newpos,
+                               (const float *)c->cent, c->mean, c->size, c->invn, c->locality, c->access,
+                               (float *)c->cent_b, c->mean_b, c->size_b, c->invn_b, c->locality_b, c->access_b, d);
+        else
+            hipLaunchKernelGGL(k_gather_rows<bf16_t>, dim3((unsigned)K), dim3(256), 0, c->stream, root, newpos,
+                               (const bf16_t *)c->cent, c->mean, c->size, c->invn, c->locality, c->access,
+                               (bf16_t *)c->cent_b, c->mean_b, c->size_b, c->invn_b, c->locality_b, c->access_b, d);
+        rc = siso_check_hip(c, hipGetLastError(), "k_gather_rows");
+        if (rc == SISO_OK) siso_swap_sets(c);
     }
     if (rc == SISO_OK) {
         hipLaunchKernelGGL(k_fill_nan, dim3(1), dim3(SISO_PAD_ROWS), 0, c->stream, c->invn + live, SISO_PAD_ROWS);
@@ -1250,12 +1275,6 @@ extern "C" int siso_merge_apply(siso_cache *c, const int *pairs, long n_pairs, i
     if (newpos) (void)hipFree(newpos);
     if (touched) (void)hipFree(touched);
     if (members_of) (void)hipFree(members_of);
-    if (cent2) (void)hipFree(cent2);
-    if (mean2) (void)hipFree(mean2);
-    if (size2) (void)hipFree(size2);
-    if (invn2) (void)hipFree(invn2);
-    if (loc2) (void)hipFree(loc2);
-    if (acc2) (void)hipFree(acc2);
     return rc;
 }
 

@@ -61,6 +61,15 @@ struct siso_cache {
     float *invn;  // [capacity] 1 / |stored centroid| (0 for a zero row, NaN for a non-finite row)
     float *locality;   // [capacity] cluster_size of Algorithm 1: grows by merges, decays by 1.1 per refresh
     unsigned *access;  // [capacity] access_count of Algorithm 1: hits since the last refresh; SISO_ACCESS_INF = infinity
+    // A second set of the six arrays, allocated the first time a call rebuilds the cache (group merge, refresh):
+    // the new set is gathered there and the two sets change places, so nothing is copied back and such calls
+    // allocate nothing afterwards.
+    void *cent_b;
+    float *mean_b;
+    int *size_b;
+    float *invn_b;
+    float *locality_b;
+    unsigned *access_b;
 
     // large update batches: first member and number of members per centroid, [capacity] each, allocated at
     // the first such batch; between calls every entry is back at (INT_MAX, 0)
@@ -273,4 +282,6 @@ int siso_pairs_mfma_launch(siso_cache *c, const void *rows, const float *invn, l
 // centroids (access_count goes up), as in serving; 0 for test lookups
 int siso_lookup_impl(siso_cache *c, const void *queries, long n, float threshold, int *out_idx, float *out_sim,
                      unsigned char *out_hit, int count_access);
-int siso_read_counter(siso_cache *c, int which, u64 *value);  // synchronises
+int siso_read_counter(siso_cache *c, int which, u64 *value);
+int siso_second_set(siso_cache *c);    // make sure the second set of arrays exists (allocates once; synchronises then)
+void siso_swap_sets(siso_cache *c);    // the second set becomes the cache, the old arrays the second set  // synchronises
