@@ -234,19 +234,37 @@ __device__ __forceinline__ bool pipe_map_block(long K, int tiles_per_slice, int 
 // End of a lookup workgroup: every lane holds (best value, block) per query column of its wave.
 // Lanes l and l^32 hold the same column; waves with the same wq share columns and meet in LDS
 // (red = at least NWC * BQ * 8 bytes that nobody reads any more).
-template <bool ROWS>
+// (value, id): the larger value, then the lower id; 0xFFFFFFFF = none
 __device__ __forceinline__ void pipe_merge(float &v, unsigned &b, float ov, unsigned ob) {
-    if constexpr (ROWS) {  // (value, row): the larger value, then the lower row; 0xFFFFFFFF = none
-        if (ov > v || (ov == v && ob < b)) {
-            v = ov;
-            b = ob;
-        }
-    } else {
-        siso_merge_candidate(v, b, ov, ob);
+    if (ov > v || (ov == v && ob < b)) {
+        v = ov;
+        b = ob;
     }
 }
 
-template <int WQ, int NWC, int BQ, int NT, bool ROWS = false>
+// The largest of the 16 scaled products a lane holds for one query column in block (A, B), and which of
+// its four register groups holds it (the lowest among equal maxima): group g = rows 8*g + 4*h .. + 3.
+// The weights of rows past the end are NaN; fmaxf and ">" pass those over.
+template <int A, int B, int G, class AccT>
+__device__ __forceinline__ float group_max(const AccT &acc, const f32x4 &w) {
+    return fmaxf(fmaxf(acc.template get<A, B, 4 * G>() * w[0], acc.template get<A, B, 4 * G + 1>() * w[1]),
+                 fmaxf(acc.template get<A, B, 4 * G + 2>() * w[2], acc.template get<A, B, 4 * G + 3>() * w[3]));
+}
+template <int A, int B, class AccT>
+__device__ __forceinline__ void block_max(const AccT &acc, const f32x4 (&w)[4], float &m, unsigned &g) {
+    m = -INFINITY;
+    g = 0;
+    static_for<0, 4>([&](auto gg) __attribute__((always_inline)) {
+        constexpr int G = decltype(gg)::value;
+        const float a = group_max<A, B, G>(acc, w[G]);
+        if (a > m) {  // groups ascend: ">" keeps the lowest among equal maxima
+            m = a;
+            g = G;
+        }
+    });
+}
+
+template <int WQ, int NWC, int BQ, int NT, bool ROWS = false>  // ROWS: the keys may be read within the launch
 __device__ __forceinline__ void pipe_reduce_keys(float (&bv)[WQ], unsigned (&bb)[WQ], unsigned char *red, int wc, int wq,
                                                  int h, int l32, int tid, long q0, long n, int slices, int s,
                                                  u64 *__restrict__ keys) {
@@ -254,7 +272,7 @@ __device__ __forceinline__ void pipe_reduce_keys(float (&bv)[WQ], unsigned (&bb)
     for (int b = 0; b < WQ; ++b) {
         const float ov = __shfl_xor(bv[b], 32);
         const unsigned ob = __shfl_xor(bb[b], 32);
-        pipe_merge<ROWS>(bv[b], bb[b], ov, ob);
+        pipe_merge(bv[b], bb[b], ov, ob);
     }
     float *red_v = (float *)red;  // [NWC][BQ]
     unsigned *red_b = (unsigned *)(red + NWC * BQ * 4);
@@ -271,7 +289,7 @@ __device__ __forceinline__ void pipe_reduce_keys(float (&bv)[WQ], unsigned (&bb)
         float v = red_v[col];
         unsigned blk = red_b[col];
 #pragma unroll
-        for (int w2 = 1; w2 < NWC; ++w2) pipe_merge<ROWS>(v, blk, red_v[w2 * BQ + col], red_b[w2 * BQ + col]);
+        for (int w2 = 1; w2 < NWC; ++w2) pipe_merge(v, blk, red_v[w2 * BQ + col], red_b[w2 * BQ + col]);
         const long q = q0 + col;
         if (q < n) keys[(size_t)q * slices + s] = (blk == 0xFFFFFFFFu) ? 0ull : pack_key(v, blk);
     }
@@ -451,7 +469,7 @@ __global__ __launch_bounds__(Cfg::NT) __attribute__((amdgpu_waves_per_eu(2, 2)))
                 f32x4 w[4];
 #pragma unroll
                 for (int g = 0; g < 4; ++g) w[g] = *(const f32x4 *)(inv_t + rb + 8 * g + 4 * h);
-                const unsigned blk = (unsigned)((c0 + rb) / SISO_RUN_ROWS) * 4u + 2u * (unsigned)h;
+                const unsigned grp = (unsigned)((c0 + rb) >> 2) + (unsigned)h;  // group of four rows: 8 * run + 2 * g + h
                 static_for<0, WQ>([&](auto ib) {
                     constexpr int B = decltype(ib)::value;
                     float m = -INFINITY;
@@ -472,13 +490,11 @@ __global__ __launch_bounds__(Cfg::NT) __attribute__((amdgpu_waves_per_eu(2, 2)))
                             bb[B] = (unsigned)(c0 + rb) + 4u * (unsigned)h + mi;
                         }
                     } else {
-                        static_for<0, 16>([&](auto ii) {
-                            constexpr int I = decltype(ii)::value;
-                            m = fmaxf(m, acc.template get<A, B, I>() * w[I >> 2][I & 3]);
-                        });
+                        unsigned g;
+                        block_max<A, B>(acc, w, m, g);
                         if (m > bv[B]) {
                             bv[B] = m;
-                            bb[B] = blk;
+                            bb[B] = grp + 2u * g;
                         }
                     }
                 });
@@ -981,17 +997,15 @@ __global__ __launch_bounds__(WideCfg::NT) __attribute__((amdgpu_waves_per_eu(1, 
                 f32x4 w[4];
 #pragma unroll
                 for (int g = 0; g < 4; ++g) w[g] = *(const f32x4 *)(inv_t + rb + 8 * g + 4 * h);
-                const unsigned blk = (unsigned)((c0 + rb) / SISO_RUN_ROWS) * 4u + 2u * (unsigned)h;
+                const unsigned grp = (unsigned)((c0 + rb) >> 2) + (unsigned)h;  // group of four rows: 8 * run + 2 * g + h
                 static_for<0, WQ>([&](auto ib) __attribute__((always_inline)) {
                     constexpr int B = decltype(ib)::value;
-                    float m = -INFINITY;
-                    static_for<0, 16>([&](auto ii) __attribute__((always_inline)) {
-                        constexpr int I = decltype(ii)::value;
-                        m = fmaxf(m, acc.template get<A, B, I>() * w[I >> 2][I & 3]);
-                    });
+                    float m;
+                    unsigned g;
+                    block_max<A, B>(acc, w, m, g);
                     if (m > bv[B]) {
                         bv[B] = m;
-                        bb[B] = blk;
+                        bb[B] = grp + 2u * g;
                     }
                 });
             });
@@ -1125,8 +1139,10 @@ int siso_mfma_slices(const siso_cache *c, long n) {
     return mfma_plan(c, n, &p) ? p.slices : 0;
 }
 
-// which kernels write keys that carry the row itself
-static int keys_carry_rows(const PipePlan &p) { return (p.cfg == 2 && PipeMid::ROWS) || (p.cfg == 3 && PipeSmall::ROWS) ? 1 : 0; }
+// what the keys of a kernel carry
+static int keys_carry_rows(const PipePlan &p) {
+    return (p.cfg == 2 && PipeMid::ROWS) || (p.cfg == 3 && PipeSmall::ROWS) ? SISO_KEY_ROWS : SISO_KEY_GROUPS4;
+}
 
 int siso_mfma_launch(siso_cache *c, const void *queries, long n, int slices, int *row_keys) {
     PipePlan p;

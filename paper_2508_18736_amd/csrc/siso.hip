@@ -136,19 +136,16 @@ __device__ __forceinline__ float chunk_dot(u32x4_t x, u32x4_t y, bf16_t) {
     }
     return s;
 }
-#define FIN_CHUNKS 8  // 16-byte chunks of a row that a lane keeps in flight
 
-// Finalize: per query, max over the slice keys, then the exact cosines of the rows of
-// the winning block (strict ">" in ascending row order, so the lowest index keeps a
-// tie), and the strict threshold test.  One 256-thread block per query: its sixteen
-// groups of 16 lanes take one centroid row each, so the 16 rows of a block are in
-// flight together.  `vec` = rows are 16-byte aligned and a whole number of 16-byte
-// chunks.
+// Finalize: per query, max over the slice keys; then either the key names the row (nothing to read), or it
+// names a group of four consecutive rows: their exact cosines (one wave per row; strict ">" in ascending
+// row order, so the lowest index keeps a tie); then the strict threshold test.  One 256-thread block
+// per query.  `vec` = rows are 16-byte aligned and a whole number of 16-byte chunks.
 template <typename T>
 __global__ __launch_bounds__(256) void k_lookup_finalize(const T *__restrict__ Q, const T *__restrict__ cent,
                                                           const float *__restrict__ invn, const u64 *__restrict__ keys,
                                                           long n, long K, int d, int slices, float threshold, int vec,
-                                                          int row_keys, int *out_idx, float *out_sim,
+                                                          int key_kind, int *out_idx, float *out_sim,
                                                           unsigned char *out_hit, unsigned *access) {
     constexpr int EPC = 16 / (int)sizeof(T);  // elements per 16-byte chunk
     __shared__ float sh_f[4];
@@ -193,50 +190,36 @@ __global__ __launch_bounds__(256) void k_lookup_finalize(const T *__restrict__ Q
     long best_i = -1;
     float best_s = -INFINITY;
     const bool finite_q = qi == qi;
-    if (row_keys) {
+    if (key_kind == SISO_KEY_ROWS) {
         // the key names the row and carries <q, c> / |c| as the kernel summed it: nothing left to read
         if (finite_q && K > 0 && key != 0) {
             best_i = (long)(0xFFFFFFFFu - (unsigned)(key & 0xFFFFFFFFull));
             best_s = unordered_bits((unsigned)(key >> 32)) * qi;
         }
     } else if (finite_q && K > 0 && key != 0) {
-        const unsigned block = 0xFFFFFFFFu - (unsigned)(key & 0xFFFFFFFFull);
-        const long run0 = (long)(block >> 2) * SISO_RUN_ROWS;
-        const int code = (int)(block & 3u);
-        // group g of pass p -> local row: one half: 8*(g/4) + 4*h + g%4; both halves: 16*p + g
-        const int passes = code == 1 ? 2 : 1;
-        for (int p = 0; p < passes; ++p) {
-            const long r = run0 + (code == 1 ? 16 * p + grp : 8 * (grp >> 2) + 2 * code + (grp & 3));
-            float acc = 0.f;
-            if (vec) {
-                // FIN_CHUNKS chunks of the row at a time, all in flight together; the sums are added in the
-                // order of the columns.  A row past the end reads the last row and is discarded below.
-                const T *crow = cent + (size_t)(r < K ? r : K - 1) * d;
-                for (int e0 = gl * EPC; e0 < d; e0 += FIN_CHUNKS * 16 * EPC) {
-                    u32x4_t cc[FIN_CHUNKS];
-#pragma unroll
-                    for (int i = 0; i < FIN_CHUNKS; ++i) {
-                        const int e = e0 + 16 * i * EPC;
-                        cc[i] = *(const u32x4_t *)(crow + (e < d ? e : 0));
-                    }
-#pragma unroll
-                    for (int i = 0; i < FIN_CHUNKS; ++i) {
-                        const int e = e0 + 16 * i * EPC;
-                        const float part = chunk_dot(sh_q[(e < d ? e : 0) / EPC], cc[i], T());
-                        acc += e < d ? part : 0.f;
-                    }
-                }
-            } else if (r < K) {
-                const T *crow = cent + (size_t)r * d;
-                for (int e = gl; e < d; e += 16) acc += widen(qrow[e]) * widen(crow[e]);
+        // the key names a group of four consecutive rows: one wave per row, its lanes share the row's chunks
+        const long r = 4L * (long)(0xFFFFFFFFu - (unsigned)(key & 0xFFFFFFFFull)) + wave;
+        float acc = 0.f;
+        if (vec) {
+            // both chunks of a lane in flight together; a row past the end reads the last row and is discarded
+            const T *crow = cent + (size_t)(r < K ? r : K - 1) * d;
+            for (int e0 = lane * EPC; e0 < d; e0 += 2 * 64 * EPC) {
+                const int e1 = e0 + 64 * EPC;
+                const u32x4_t c0v = *(const u32x4_t *)(crow + e0);
+                const u32x4_t c1v = *(const u32x4_t *)(crow + (e1 < d ? e1 : 0));
+                acc += chunk_dot(sh_q[e0 / EPC], c0v, T());
+                const float part = chunk_dot(sh_q[(e1 < d ? e1 : 0) / EPC], c1v, T());
+                acc += e1 < d ? part : 0.f;
             }
-#pragma unroll
-            for (int off = 8; off > 0; off >>= 1) acc += __shfl_xor(acc, off);
-            const float s = r < K ? acc * qi * invn[r] : __uint_as_float(0x7FC00000u);
-            if (s > best_s) {
-                best_s = s;
-                best_i = r;
-            }
+        } else if (r < K) {
+            const T *crow = cent + (size_t)r * d;
+            for (int e = lane; e < d; e += 64) acc += widen(qrow[e]) * widen(crow[e]);
+        }
+        acc = wave_sum(acc);
+        const float sv = r < K ? acc * qi * invn[r] : __uint_as_float(0x7FC00000u);
+        if (sv == sv) {  // a NaN never wins
+            best_s = sv;
+            best_i = r;
         }
     }
     if (gl == 0) {
@@ -246,7 +229,8 @@ __global__ __launch_bounds__(256) void k_lookup_finalize(const T *__restrict__ Q
     __syncthreads();
     if (t == 0) {
         // rows ascend with the group number inside a pass, and pass 1 lies above pass 0
-        for (int g = 1; g < (row_keys ? 1 : 16); ++g) {
+        // (with groups of four every wave holds one row, ascending with the wave: the 16 entries repeat them)
+        for (int g = 1; g < (key_kind == SISO_KEY_ROWS ? 1 : 16); ++g) {
             const float os = sh_s[g];
             const long oi = sh_i[g];
             if (oi >= 0 && (best_i < 0 || os > best_s || (os == best_s && oi < best_i))) {
@@ -359,7 +343,7 @@ __global__ __launch_bounds__(256) void k_lookup_scalar(const T *__restrict__ Q, 
         }
         const long q = q0 + ty * 4 + i;
         if (tx == 0 && q < n)
-            keys[(size_t)q * slices + s] = bidx[i] < 0 ? 0ull : pack_key(best[i], siso_block_of_row(bidx[i]));
+            keys[(size_t)q * slices + s] = bidx[i] < 0 ? 0ull : pack_key(best[i], (unsigned)bidx[i]);
     }
 }
 
@@ -1065,7 +1049,7 @@ int siso_lookup_impl(siso_cache *c, const void *queries, long n, float threshold
     if (rc != SISO_OK) return rc;
     const unsigned qblocks = (unsigned)n;
     const int vec = ((c->dim * elem_bytes(c->dtype)) % 16 == 0 && ((uintptr_t)queries & 15) == 0) ? 1 : 0;
-    int row_keys = 0;  // what the keys of the chosen kernel carry: the winning row, or its block of rows
+    int row_keys = SISO_KEY_ROWS;  // what the keys of the chosen kernel carry: the winning row, or its group of four rows
     if (c->count > 0) {
         siso_prof_begin(c);
         switch (path) {

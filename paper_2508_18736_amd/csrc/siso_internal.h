@@ -12,36 +12,18 @@ typedef unsigned short bf16_t;  // bfloat16 bit pattern
 
 // A phase-1 lookup kernel reduces, for every query q and every slice s of the
 // centroid range, the scaled dot products <q, c_k> / |c_k| to one 64-bit key
-//     key = ordered(value) << 32 | (0xFFFFFFFF - block)
-// where block names a group of SISO_BLOCK_ROWS centroids that holds the best
-// one, so that an unsigned max over keys picks the largest value and, among
-// equal values, the lowest block.  Key 0 means "no candidate".  The finalize
-// kernel then recomputes the cosines of the winning block exactly and picks the
-// lowest index among its maxima.
-//
-// A block is what one lane of a 32x32 MFMA accumulator holds: inside an aligned
-// run of 32 centroids, half h (0 or 1) owns the 16 rows 8*g + 4*h + j, g and j in
-// 0..3.  block = 4 * (k / 32) + code with code 0 = half 0, 2 = half 1, and 1 =
-// "both halves tie" (the two lanes that share a query column found the same
-// value); the finalize kernel then looks at all 32 rows, so the lowest index
-// still wins.  A run of 32 centroids is only ever seen by one wave, so equal
-// values from different keys always belong to different runs and the lower
-// block is the lower index.
-#define SISO_RUN_ROWS 32
-__host__ __device__ __forceinline__ unsigned siso_block_of_row(long k) {
-    return (unsigned)((k >> 5) * 4 + ((k >> 2) & 1) * 2);
-}
-// merge two (value, block) candidates of the same query; NaN never reaches here
-__device__ __forceinline__ void siso_merge_candidate(float &v, unsigned &b, float ov, unsigned ob) {
-    if (ov > v) {
-        v = ov;
-        b = ob;
-    } else if (ov == v && ob != b && ob != 0xFFFFFFFFu) {
-        if (b == 0xFFFFFFFFu) b = ob;
-        else if ((ob >> 2) == (b >> 2)) b = (b & ~3u) | 1u;
-        else if (ob < b) b = ob;
-    }
-}
+//     key = ordered(value) << 32 | (0xFFFFFFFF - id)
+// so that an unsigned max over keys picks the largest value and, among equal
+// values, the lowest id.  Key 0 means "no candidate".  The id is either the row
+// itself (kernels that can afford the exact arg-max in their epilogue: the value
+// then is the similarity but for the factor 1 / |q|), or the number k / 4 of a
+// group of four consecutive rows that holds the best one (what a lane of a
+// 32 x 32 MFMA accumulator holds in four consecutive registers: rows 8*g + 4*h
+// + j of an aligned run of 32, j = 0..3); the finalize kernel then recomputes
+// the four cosines exactly and picks the lowest index among their maxima.  Ids
+// ascend with the rows, so "the lowest id among equal values" always holds the
+// lowest index among equal maxima.
+enum { SISO_KEY_ROWS = 1, SISO_KEY_GROUPS4 = 3 };
 #define SISO_ACCESS_INF 0xFFFFFFFFu
 #define SISO_MAX_DIM 4096
 #define SISO_PAD_ROWS 256  // readable rows past the capacity of the stored-centroid array
