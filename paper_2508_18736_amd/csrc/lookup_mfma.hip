@@ -37,7 +37,7 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
-// ROWS: the keys of the lookup carry the winning row itself instead of its block of 16 rows (more
+// ROWS: the keys of the lookup carry the winning row itself instead of its group of four rows (more
 // compares per product, affordable where the kernel waits for memory anyway; the finalize step then
 // has no centroid rows to read)
 template <int WC_, int WQ_, int NWC_, int NWQ_, int NSTAGE_, int BK_ = 64, bool ROWS_ = false>
