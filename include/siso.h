@@ -270,6 +270,17 @@ long siso_cluster(siso_cache *c, const void *vectors, long n, float theta_c, int
                   int *out_representative, long *out_stats);
 
 /*
+ * The host part of siso_cluster by itself: the choice of the communities from a
+ * list of neighbour pairs (same section, same rules).  Needs no GPU.
+ *   pairs:     HOST pointer, [n_pairs][2] ints: every pair of neighbours once,
+ *              in either order, indices in [0, n), the two of a pair distinct
+ *              (SISO_EINVAL otherwise).
+ *   out_label: HOST pointer, n ints: cluster id of every vector or -1.
+ * Returns the number of clusters, or a negative error code.
+ */
+long siso_choose_communities(const int *pairs, long n_pairs, long n, int min_size, int *out_label);
+
+/*
  * Threshold-to-hit-ratio (T2H) table (section 4.3, "Adjusting theta_R to meet
  * SLO"): test lookups of a sample of queries, counted against a sweep of
  * retrieval thresholds (the paper sweeps 0.98 down to 0.6).

@@ -153,10 +153,71 @@ struct DeviceMem {  // frees on every way out
     }
 };
 
+// The greedy choice of the communities from the list of neighbour pairs (host memory, each pair once, in any
+// order): candidates = every vector with its neighbours, largest first, equal sizes by index; a candidate
+// keeps the vectors no earlier cluster took and becomes a cluster if at least min_size remain.
+// label[i] = cluster of vector i or -1; the members of cluster k, in ascending order, are
+// member[first[k] .. first[k+1]).  Linear in vectors + pairs (counting sort, one pass over the lists).
+void choose_communities(const int *h_pairs, long n_pairs, long n, int min_size, std::vector<int> &label,
+                        std::vector<long> &first, std::vector<int> &member) {
+    // ---- neighbour lists -----------------------------------------------------------------------
+    std::vector<long> start((size_t)n + 1, 0);
+    for (long p = 0; p < 2 * n_pairs; ++p) start[(size_t)h_pairs[(size_t)p] + 1] += 1;
+    long largest = 0;
+    for (long i = 0; i < n; ++i) {
+        if (start[(size_t)i + 1] > largest) largest = start[(size_t)i + 1];
+        start[(size_t)i + 1] += start[(size_t)i];
+    }
+    std::vector<int> nbr((size_t)(2 * n_pairs));
+    {
+        std::vector<long> fill(start.begin(), start.end() - 1);
+        for (long p = 0; p < n_pairs; ++p) {
+            const int a = h_pairs[(size_t)(2 * p)], b = h_pairs[(size_t)(2 * p + 1)];
+            nbr[(size_t)fill[(size_t)a]++] = b;
+            nbr[(size_t)fill[(size_t)b]++] = a;
+        }
+    }
+    // ---- candidates by size (itself + neighbours), largest first, equal sizes by index ------------
+    // a counting sort over the sizes 1 .. largest + 1
+    std::vector<long> bucket((size_t)largest + 3, 0);
+    for (long i = 0; i < n; ++i) bucket[(size_t)(largest + 1 - (start[(size_t)i + 1] - start[(size_t)i])) + 1] += 1;
+    for (long s = 0; s <= largest + 1; ++s) bucket[(size_t)s + 1] += bucket[(size_t)s];
+    std::vector<int> order((size_t)n);
+    for (long i = 0; i < n; ++i) order[(size_t)bucket[(size_t)(largest + 1 - (start[(size_t)i + 1] - start[(size_t)i]))]++] = (int)i;
+
+    // ---- greedy choice ----------------------------------------------------------------------------
+    label.assign((size_t)n, -1);
+    first.assign(1, 0);
+    member.clear();
+    member.reserve((size_t)n);
+    for (long q = 0; q < n; ++q) {
+        const long i = order[(size_t)q];
+        const long lo = start[(size_t)i], hi = start[(size_t)i + 1];
+        if (hi - lo + 1 < (long)min_size) break;   // every later candidate is smaller still
+        long left = label[(size_t)i] < 0 ? 1 : 0;
+        for (long p = lo; p < hi; ++p) left += label[(size_t)nbr[(size_t)p]] < 0 ? 1 : 0;
+        if (left < (long)min_size) continue;
+        const int id = (int)(first.size() - 1);
+        if (label[(size_t)i] < 0) {
+            label[(size_t)i] = id;
+            member.push_back((int)i);
+        }
+        for (long p = lo; p < hi; ++p) {
+            const int j = nbr[(size_t)p];
+            if (label[(size_t)j] < 0) {
+                label[(size_t)j] = id;
+                member.push_back(j);
+            }
+        }
+        std::sort(member.begin() + first.back(), member.end());   // averages take the members in ascending order
+        first.push_back((long)member.size());
+    }
+}
+
 }  // namespace
 
-extern "C" long siso_cluster(siso_cache *c, const void *vectors, long n, float theta_c, int min_size, int *out_label,
-                             int *out_representative, long *out_stats) {
+static long cluster_impl(siso_cache *c, const void *vectors, long n, float theta_c, int min_size, int *out_label,
+                         int *out_representative, long *out_stats) {
     if (!c) return SISO_EINVAL;
     if (out_stats) out_stats[0] = out_stats[1] = 0;
     if (n < 0 || min_size < 1 || (n > 0 && !vectors))
@@ -226,60 +287,12 @@ extern "C" long siso_cluster(siso_cache *c, const void *vectors, long n, float t
         d_pairs.release();
     }
 
-    // ---- neighbour lists -----------------------------------------------------------------------
-    std::vector<long> start((size_t)n + 1, 0);
-    for (long p = 0; p < 2 * n_pairs; ++p) start[(size_t)h_pairs[(size_t)p] + 1] += 1;
-    long largest = 0;
-    for (long i = 0; i < n; ++i) {
-        if (start[(size_t)i + 1] > largest) largest = start[(size_t)i + 1];
-        start[(size_t)i + 1] += start[(size_t)i];
-    }
-    std::vector<int> nbr((size_t)(2 * n_pairs));
-    {
-        std::vector<long> fill(start.begin(), start.end() - 1);
-        for (long p = 0; p < n_pairs; ++p) {
-            const int a = h_pairs[(size_t)(2 * p)], b = h_pairs[(size_t)(2 * p + 1)];
-            nbr[(size_t)fill[(size_t)a]++] = b;
-            nbr[(size_t)fill[(size_t)b]++] = a;
-        }
-    }
-    std::vector<int>().swap(h_pairs);
-
-    // ---- candidates by size (itself + neighbours), largest first, equal sizes by index ------------
-    // a counting sort over the sizes 1 .. largest + 1
-    std::vector<long> bucket((size_t)largest + 3, 0);
-    for (long i = 0; i < n; ++i) bucket[(size_t)(largest + 1 - (start[(size_t)i + 1] - start[(size_t)i])) + 1] += 1;
-    for (long s = 0; s <= largest + 1; ++s) bucket[(size_t)s + 1] += bucket[(size_t)s];
-    std::vector<int> order((size_t)n);
-    for (long i = 0; i < n; ++i) order[(size_t)bucket[(size_t)(largest + 1 - (start[(size_t)i + 1] - start[(size_t)i]))]++] = (int)i;
-
-    // ---- greedy choice ----------------------------------------------------------------------------
-    std::vector<int> label((size_t)n, -1);
-    std::vector<long> first(1, 0);   // members of cluster k: member[first[k] .. first[k+1])
+    // ---- the communities: a walk over the pairs on the host ------------------------------------------
+    std::vector<int> label;
+    std::vector<long> first;   // members of cluster k: member[first[k] .. first[k+1])
     std::vector<int> member;
-    member.reserve((size_t)n);
-    for (long q = 0; q < n; ++q) {
-        const long i = order[(size_t)q];
-        const long lo = start[(size_t)i], hi = start[(size_t)i + 1];
-        if (hi - lo + 1 < (long)min_size) break;   // every later candidate is smaller still
-        long left = label[(size_t)i] < 0 ? 1 : 0;
-        for (long p = lo; p < hi; ++p) left += label[(size_t)nbr[(size_t)p]] < 0 ? 1 : 0;
-        if (left < (long)min_size) continue;
-        const int id = (int)(first.size() - 1);
-        if (label[(size_t)i] < 0) {
-            label[(size_t)i] = id;
-            member.push_back((int)i);
-        }
-        for (long p = lo; p < hi; ++p) {
-            const int j = nbr[(size_t)p];
-            if (label[(size_t)j] < 0) {
-                label[(size_t)j] = id;
-                member.push_back(j);
-            }
-        }
-        std::sort(member.begin() + first.back(), member.end());   // averages take the members in ascending order
-        first.push_back((long)member.size());
-    }
+    choose_communities(h_pairs.data(), n_pairs, n, min_size, label, first, member);
+    std::vector<int>().swap(h_pairs);
     const long clusters = (long)first.size() - 1;
     if (clusters > c->capacity)
         return siso_fail(c, SISO_ECAPACITY, "siso_cluster: %ld clusters, capacity %ld", clusters, c->capacity);
@@ -315,4 +328,32 @@ extern "C" long siso_cluster(siso_cache *c, const void *vectors, long n, float t
     }
 #undef CLUSTER_TRY
     return clusters;
+}
+
+extern "C" long siso_cluster(siso_cache *c, const void *vectors, long n, float theta_c, int min_size, int *out_label,
+                             int *out_representative, long *out_stats) {
+    if (!c) return SISO_EINVAL;
+    try {
+        return cluster_impl(c, vectors, n, theta_c, min_size, out_label, out_representative, out_stats);
+    } catch (const std::bad_alloc &) {  // the host lists; nothing has been changed yet when they are built
+        return siso_fail(c, SISO_ENOMEM, "siso_cluster: host memory for the neighbour lists");
+    }
+}
+
+// The host part of siso_cluster alone: pairs and labels are HOST arrays.
+extern "C" long siso_choose_communities(const int *pairs, long n_pairs, long n, int min_size, int *out_label) {
+    if (n < 0 || n_pairs < 0 || min_size < 1 || (n_pairs > 0 && !pairs) || (n > 0 && !out_label)) return SISO_EINVAL;
+    for (long p = 0; p < 2 * n_pairs; ++p)
+        if (pairs[p] < 0 || pairs[p] >= n) return SISO_EINVAL;
+    for (long p = 0; p < n_pairs; ++p)
+        if (pairs[2 * p] == pairs[2 * p + 1]) return SISO_EINVAL;
+    try {
+        std::vector<int> label, member;
+        std::vector<long> first;
+        choose_communities(pairs, n_pairs, n, min_size, label, first, member);
+        for (long i = 0; i < n; ++i) out_label[i] = label[(size_t)i];
+        return (long)first.size() - 1;
+    } catch (const std::bad_alloc &) {
+        return SISO_ENOMEM;
+    }
 }

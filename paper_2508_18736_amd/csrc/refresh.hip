@@ -132,8 +132,8 @@ struct Candidate {  // an earlier repository row above the threshold
 
 }  // namespace
 
-extern "C" int siso_refresh(siso_cache *c, const void *repo, const float *repo_size, long r, float theta_c,
-                            long max_centroids, long *out_stats) {
+static int refresh_impl(siso_cache *c, const void *repo, const float *repo_size, long r, float theta_c,
+                        long max_centroids, long *out_stats) {
     if (!c) return SISO_EINVAL;
     if (out_stats) out_stats[0] = out_stats[1] = out_stats[2] = 0;
     if (r < 0 || max_centroids < 1 || max_centroids > c->capacity || (r > 0 && (!repo || !repo_size)))
@@ -346,4 +346,14 @@ extern "C" int siso_refresh(siso_cache *c, const void *repo, const float *repo_s
     }
 #undef REFRESH_TRY
     return SISO_OK;
+}
+
+extern "C" int siso_refresh(siso_cache *c, const void *repo, const float *repo_size, long r, float theta_c,
+                            long max_centroids, long *out_stats) {
+    if (!c) return SISO_EINVAL;
+    try {
+        return refresh_impl(c, repo, repo_size, r, theta_c, max_centroids, out_stats);
+    } catch (const std::bad_alloc &) {  // the host lists; they are all built before the update step
+        return siso_fail(c, SISO_ENOMEM, "siso_refresh: host memory for the bookkeeping");
+    }
 }

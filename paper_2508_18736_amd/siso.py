@@ -51,6 +51,7 @@ SYMBOLS = {
     "siso_probe": ([_it, C.POINTER(C.c_double)], _it),
     "siso_refresh": ([_vp, _vp, _vp, _lg, _fl, _lg, _vp], _it),
     "siso_cluster": ([_vp, _vp, _lg, _fl, _it, _vp, _vp, _vp], _lg),
+    "siso_choose_communities": ([_vp, _lg, _lg, _it, _vp], _lg),
     "siso_export_meta": ([_vp, _vp, _vp], _it),
     "siso_t2h": ([_vp, _vp, _lg, _vp, _it, _vp], _it),
     "siso_md1_wait": ([C.c_double, C.c_double, C.c_double], C.c_double),
@@ -65,6 +66,19 @@ for _name, (_args, _res) in SYMBOLS.items():
 
 def md1_wait(llm_time: float, arrival_rate: float, hit_ratio: float) -> float:
     return float(_lib.siso_md1_wait(float(llm_time), float(arrival_rate), float(hit_ratio)))
+
+
+def choose_communities(pairs, n: int, min_size: int = 1):
+    """The host part of the clustering: labels (numpy int32 [n]) and the number of clusters from the
+    neighbour pairs (host array [P, 2])."""
+    import numpy as np
+    pr = np.ascontiguousarray(pairs, dtype=np.int32).reshape(-1, 2)
+    labels = np.full(int(n), -1, np.int32)
+    rc = _lib.siso_choose_communities(pr.ctypes.data_as(_vp), pr.shape[0], int(n), int(min_size),
+                                      labels.ctypes.data_as(_vp))
+    if rc < 0:
+        raise SisoError(int(rc), "siso_choose_communities: bad pairs or sizes")
+    return labels, int(rc)
 
 
 def pick_threshold(thetas, hit_ratio, llm_time: float, arrival_rate: float, slo: float) -> int:
