@@ -231,6 +231,27 @@ int siso_refresh(siso_cache *c, const void *repo, const float *repo_size, long r
 int siso_export_meta(siso_cache *c, float *cluster_size, unsigned *access_count);
 
 /*
+ * The host part of siso_refresh by itself: the decisions of Algorithm 1 from
+ * the similarities that the kernels supply.  Needs no GPU; all pointers are
+ * HOST pointers.
+ *   cluster_size, access_count: [k0] of the cached centroids.
+ *   repo_size:  [r] cluster sizes of the repository rows (> 0).
+ *   best_idx, best_sim: [r] per repository row its closest cached centroid
+ *               (-1 if the cache is empty) and the cosine.
+ *   pairs, pair_cosine: [n_pairs] pairs (a, b), a < b < r, of repository rows
+ *               whose cosine exceeds theta_c, and that cosine.
+ *   out_source: room for k0 + r ints: per surviving row, in order, the cached
+ *               row it is (< k0) or k0 + the repository row that joined.
+ *   out_cluster_size: room for k0 + r floats: its cluster_size afterwards.
+ *   out_stats:  3 longs or NULL: merged, added, evicted.
+ * Returns the number of surviving rows, or a negative error code.
+ */
+long siso_refresh_plan(long k0, const float *cluster_size, const unsigned *access_count, long r,
+                       const float *repo_size, const int *best_idx, const float *best_sim, const int *pairs,
+                       const float *pair_cosine, long n_pairs, float theta_c, long max_centroids,
+                       int *out_source, float *out_cluster_size, long *out_stats);
+
+/*
  * Clustering of a query log into the centroid repository: section 4.1
  * ("Selecting a clustering algorithm": community detection at the clustering
  * threshold; "Keeping centroids in a repository": id, centroid, cluster_size)

@@ -130,6 +130,86 @@ struct Candidate {  // an earlier repository row above the threshold
     float cosine;
 };
 
+// The decisions of Algorithm 1 from what the kernels found.  Per repository row i: h_idx / h_sim = its closest
+// cached centroid and the cosine; h_pairs / h_cos = the pairs (a, b), a < b, of repository rows above the
+// threshold with their cosines.  loc / acc = cluster_size and access_count of the cached centroids (they grow
+// by the rows that join).  keep = source of every surviving row in order (cached row, or K0 + repository row),
+// loc2 = its cluster_size after the decay.
+void plan_refresh(long K0, long r, const int *h_idx, const float *h_sim, const float *h_rsize, const int *h_pairs,
+                  const float *h_cos, long n_pairs, std::vector<float> loc, std::vector<unsigned> acc, float theta_c,
+                  long max_centroids, std::vector<int> &keep, std::vector<float> &loc2, long &merged, long &added,
+                  long &evicted) {
+    // ---- the chain of the merge step, in the order of the repository ---------------------
+    // candidates of row b: the earlier rows a < b with cosine above the threshold (pairs come as a < b)
+    std::vector<long> first((size_t)r + 1, 0);
+    for (long p = 0; p < n_pairs; ++p) first[(size_t)h_pairs[2 * p + 1] + 1] += 1;
+    for (long i = 0; i < r; ++i) first[(size_t)i + 1] += first[(size_t)i];
+    std::vector<Candidate> cand((size_t)n_pairs);
+    {
+        std::vector<long> fill(first.begin(), first.end() - 1);
+        for (long p = 0; p < n_pairs; ++p) {
+            const int b = h_pairs[2 * p + 1];
+            cand[(size_t)fill[(size_t)b]++] = Candidate{h_pairs[2 * p], h_cos[(size_t)p]};
+        }
+    }
+    std::vector<long> place((size_t)r, -1);  // position in C_new of a repository row that joined
+    std::vector<int> src;                    // C_new: source of every row (cached row, or K0 + repository row)
+    src.reserve((size_t)(K0 + r));
+    for (long j = 0; j < K0; ++j) src.push_back((int)j);
+    merged = added = 0;
+    for (long i = 0; i < r; ++i) {
+        long best = h_idx[(size_t)i];
+        float bsim = h_sim[(size_t)i];
+        if (best < 0 || !(bsim == bsim)) {
+            best = -1;
+            bsim = -INFINITY;
+        }
+        for (long q = first[(size_t)i]; q < first[(size_t)i + 1]; ++q) {
+            const long pos = place[(size_t)cand[(size_t)q].row];
+            if (pos < 0) continue;  // that row did not join: it is not in C_new
+            const float s = cand[(size_t)q].cosine;
+            if (s > bsim || (s == bsim && pos < best)) {
+                bsim = s;
+                best = pos;
+            }
+        }
+        if (best >= 0 && bsim > theta_c) {
+            loc[(size_t)best] = loc[(size_t)best] + h_rsize[(size_t)i];
+            ++merged;
+        } else {
+            place[(size_t)i] = (long)src.size();
+            src.push_back((int)(K0 + i));
+            loc.push_back(h_rsize[(size_t)i]);
+            acc.push_back(SISO_ACCESS_INF);
+            ++added;
+        }
+    }
+
+    // ---- filtering step: the smallest (cluster_size, access_count) go, the first such first ----
+    const long n_new = (long)src.size();
+    evicted = 0;
+    std::vector<unsigned char> gone((size_t)n_new, 0);
+    if (n_new > max_centroids) {
+        evicted = n_new - max_centroids;
+        std::vector<int> order((size_t)n_new);
+        for (long j = 0; j < n_new; ++j) order[(size_t)j] = (int)j;
+        auto before = [&](int x, int y) {
+            if (loc[(size_t)x] != loc[(size_t)y]) return loc[(size_t)x] < loc[(size_t)y];
+            if (acc[(size_t)x] != acc[(size_t)y]) return acc[(size_t)x] < acc[(size_t)y];
+            return x < y;
+        };
+        std::nth_element(order.begin(), order.begin() + evicted, order.end(), before);
+        for (long v = 0; v < evicted; ++v) gone[(size_t)order[(size_t)v]] = 1;
+    }
+    keep.reserve((size_t)(n_new - evicted));
+    loc2.reserve((size_t)(n_new - evicted));
+    for (long j = 0; j < n_new; ++j) {
+        if (gone[(size_t)j]) continue;
+        keep.push_back(src[(size_t)j]);
+        loc2.push_back(loc[(size_t)j] / 1.1f);
+    }
+}
+
 }  // namespace
 
 static int refresh_impl(siso_cache *c, const void *repo, const float *repo_size, long r, float theta_c,
@@ -239,77 +319,12 @@ static int refresh_impl(siso_cache *c, const void *repo, const float *repo_size,
     }
     REFRESH_TRY(hipStreamSynchronize(st), "siso_refresh: synchronize");
 
-    // ---- the chain of the merge step, in the order of the repository ---------------------
-    // candidates of row b: the earlier rows a < b with cosine above the threshold (pairs come as a < b)
-    std::vector<long> first((size_t)r + 1, 0);
-    for (long p = 0; p < n_pairs; ++p) first[(size_t)h_pairs[2 * p + 1] + 1] += 1;
-    for (long i = 0; i < r; ++i) first[(size_t)i + 1] += first[(size_t)i];
-    std::vector<Candidate> cand((size_t)n_pairs);
-    {
-        std::vector<long> fill(first.begin(), first.end() - 1);
-        for (long p = 0; p < n_pairs; ++p) {
-            const int b = h_pairs[2 * p + 1];
-            cand[(size_t)fill[(size_t)b]++] = Candidate{h_pairs[2 * p], h_cos[(size_t)p]};
-        }
-    }
-    std::vector<long> place((size_t)r, -1);  // position in C_new of a repository row that joined
-    std::vector<int> src;                    // C_new: source of every row (cached row, or K0 + repository row)
-    src.reserve((size_t)(K0 + r));
-    for (long j = 0; j < K0; ++j) src.push_back((int)j);
-    long merged = 0, added = 0;
-    for (long i = 0; i < r; ++i) {
-        long best = h_idx[(size_t)i];
-        float bsim = h_sim[(size_t)i];
-        if (best < 0 || !(bsim == bsim)) {
-            best = -1;
-            bsim = -INFINITY;
-        }
-        for (long q = first[(size_t)i]; q < first[(size_t)i + 1]; ++q) {
-            const long pos = place[(size_t)cand[(size_t)q].row];
-            if (pos < 0) continue;  // that row did not join: it is not in C_new
-            const float s = cand[(size_t)q].cosine;
-            if (s > bsim || (s == bsim && pos < best)) {
-                bsim = s;
-                best = pos;
-            }
-        }
-        if (best >= 0 && bsim > theta_c) {
-            loc[(size_t)best] = loc[(size_t)best] + h_rsize[(size_t)i];
-            ++merged;
-        } else {
-            place[(size_t)i] = (long)src.size();
-            src.push_back((int)(K0 + i));
-            loc.push_back(h_rsize[(size_t)i]);
-            acc.push_back(SISO_ACCESS_INF);
-            ++added;
-        }
-    }
-
-    // ---- filtering step: the smallest (cluster_size, access_count) go, the first such first ----
-    const long n_new = (long)src.size();
-    long evicted = 0;
-    std::vector<unsigned char> gone((size_t)n_new, 0);
-    if (n_new > max_centroids) {
-        evicted = n_new - max_centroids;
-        std::vector<int> order((size_t)n_new);
-        for (long j = 0; j < n_new; ++j) order[(size_t)j] = (int)j;
-        auto before = [&](int x, int y) {
-            if (loc[(size_t)x] != loc[(size_t)y]) return loc[(size_t)x] < loc[(size_t)y];
-            if (acc[(size_t)x] != acc[(size_t)y]) return acc[(size_t)x] < acc[(size_t)y];
-            return x < y;
-        };
-        std::nth_element(order.begin(), order.begin() + evicted, order.end(), before);
-        for (long v = 0; v < evicted; ++v) gone[(size_t)order[(size_t)v]] = 1;
-    }
+    // ---- merge step and filtering step: bookkeeping on the host ----------------------------------
     std::vector<int> keep;
     std::vector<float> loc2;
-    keep.reserve((size_t)(n_new - evicted));
-    loc2.reserve((size_t)(n_new - evicted));
-    for (long j = 0; j < n_new; ++j) {
-        if (gone[(size_t)j]) continue;
-        keep.push_back(src[(size_t)j]);
-        loc2.push_back(loc[(size_t)j] / 1.1f);
-    }
+    long merged = 0, added = 0, evicted = 0;
+    plan_refresh(K0, r, h_idx.data(), h_sim.data(), h_rsize.data(), h_pairs.data(), h_cos.data(), n_pairs, loc, acc, theta_c,
+                 max_centroids, keep, loc2, merged, added, evicted);
     const long live = (long)keep.size();
 
     // ---- update step: gather the new set, then it becomes the cache ---------------------------
@@ -355,5 +370,40 @@ extern "C" int siso_refresh(siso_cache *c, const void *repo, const float *repo_s
         return refresh_impl(c, repo, repo_size, r, theta_c, max_centroids, out_stats);
     } catch (const std::bad_alloc &) {  // the host lists; they are all built before the update step
         return siso_fail(c, SISO_ENOMEM, "siso_refresh: host memory for the bookkeeping");
+    }
+}
+
+// The host part of siso_refresh alone (all pointers are HOST pointers).
+extern "C" long siso_refresh_plan(long k0, const float *cluster_size, const unsigned *access_count, long r,
+                                  const float *repo_size, const int *best_idx, const float *best_sim, const int *pairs,
+                                  const float *pair_cosine, long n_pairs, float theta_c, long max_centroids,
+                                  int *out_source, float *out_cluster_size, long *out_stats) {
+    if (k0 < 0 || r < 0 || n_pairs < 0 || max_centroids < 1 || !out_source || !out_cluster_size) return SISO_EINVAL;
+    if ((k0 > 0 && (!cluster_size || !access_count)) || (r > 0 && (!repo_size || !best_idx || !best_sim)) ||
+        (n_pairs > 0 && (!pairs || !pair_cosine)))
+        return SISO_EINVAL;
+    for (long p = 0; p < n_pairs; ++p)
+        if (pairs[2 * p] < 0 || pairs[2 * p] >= pairs[2 * p + 1] || pairs[2 * p + 1] >= r) return SISO_EINVAL;
+    for (long i = 0; i < r; ++i)
+        if (best_idx[i] >= k0 || !(repo_size[i] > 0.f)) return SISO_EINVAL;
+    try {
+        std::vector<float> loc(cluster_size, cluster_size + k0), loc2;
+        std::vector<unsigned> acc(access_count, access_count + k0);
+        std::vector<int> keep;
+        long merged = 0, added = 0, evicted = 0;
+        plan_refresh(k0, r, best_idx, best_sim, repo_size, pairs, pair_cosine, n_pairs, loc, acc, theta_c, max_centroids,
+                     keep, loc2, merged, added, evicted);
+        for (size_t j = 0; j < keep.size(); ++j) {
+            out_source[j] = keep[j];
+            out_cluster_size[j] = loc2[j];
+        }
+        if (out_stats) {
+            out_stats[0] = merged;
+            out_stats[1] = added;
+            out_stats[2] = evicted;
+        }
+        return (long)keep.size();
+    } catch (const std::bad_alloc &) {
+        return SISO_ENOMEM;
     }
 }

@@ -52,6 +52,7 @@ SYMBOLS = {
     "siso_refresh": ([_vp, _vp, _vp, _lg, _fl, _lg, _vp], _it),
     "siso_cluster": ([_vp, _vp, _lg, _fl, _it, _vp, _vp, _vp], _lg),
     "siso_choose_communities": ([_vp, _lg, _lg, _it, _vp], _lg),
+    "siso_refresh_plan": ([_lg, _vp, _vp, _lg, _vp, _vp, _vp, _vp, _vp, _lg, _fl, _lg, _vp, _vp, _vp], _lg),
     "siso_export_meta": ([_vp, _vp, _vp], _it),
     "siso_t2h": ([_vp, _vp, _lg, _vp, _it, _vp], _it),
     "siso_md1_wait": ([C.c_double, C.c_double, C.c_double], C.c_double),
@@ -79,6 +80,31 @@ def choose_communities(pairs, n: int, min_size: int = 1):
     if rc < 0:
         raise SisoError(int(rc), "siso_choose_communities: bad pairs or sizes")
     return labels, int(rc)
+
+
+def refresh_plan(cluster_size, access_count, repo_size, best_idx, best_sim, pairs, pair_cosine, theta_c: float,
+                 max_centroids: int):
+    """The host part of a refresh (host arrays in, host arrays out):
+    ``(source int32 [survivors], cluster_size float32 [survivors], (merged, added, evicted))``."""
+    import numpy as np
+    cs = np.ascontiguousarray(cluster_size, dtype=np.float32)
+    ac = np.ascontiguousarray(access_count, dtype=np.uint32)
+    rs = np.ascontiguousarray(repo_size, dtype=np.float32)
+    bi = np.ascontiguousarray(best_idx, dtype=np.int32)
+    bs = np.ascontiguousarray(best_sim, dtype=np.float32)
+    pr = np.ascontiguousarray(pairs, dtype=np.int32).reshape(-1, 2)
+    pc = np.ascontiguousarray(pair_cosine, dtype=np.float32)
+    k0, r = cs.shape[0], rs.shape[0]
+    assert ac.shape == (k0,) and bi.shape == (r,) and bs.shape == (r,) and pc.shape == (pr.shape[0],)
+    src = np.empty(k0 + r, np.int32)
+    out = np.empty(k0 + r, np.float32)
+    stats = (C.c_long * 3)()
+    p = lambda a: a.ctypes.data_as(_vp)
+    rc = _lib.siso_refresh_plan(k0, p(cs), p(ac), r, p(rs), p(bi), p(bs), p(pr), p(pc), pr.shape[0], float(theta_c),
+                                int(max_centroids), p(src), p(out), stats)
+    if rc < 0:
+        raise SisoError(int(rc), "siso_refresh_plan: bad arguments")
+    return src[:rc].copy(), out[:rc].copy(), (int(stats[0]), int(stats[1]), int(stats[2]))
 
 
 def pick_threshold(thetas, hit_ratio, llm_time: float, arrival_rate: float, slo: float) -> int:
