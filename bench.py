@@ -225,7 +225,7 @@ def main():
 
     for i in range(warmup):
         step(i)
-    cache.profile_enable(8 if streaming else 1)  # events around every 8th lookup kernel when steps are short
+    cache.profile_enable(32 if streaming else 1)  # events around every 32nd lookup kernel when steps are short
     cache.profile_read()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
