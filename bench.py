@@ -1,6 +1,10 @@
 """Benchmark of the centroid-cache hot path on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c2_mid]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c3_large]
+
+The default workload is the large compute-bound lookup (1,048,576 centroids x 1,024, batches of 16,384);
+--workload c2_mid | c4_stream | c5_merge give the mid-size lookup (with the offline passes timed beside it),
+the streaming lookup with updates between micro-batches, and the all-pairs merge.
 
 A step is one pass of the online path over one batch of synthetic queries that already
 sit in GPU memory: siso_lookup (query norms, similarity against every cached centroid,
@@ -19,7 +23,6 @@ import time
 ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
-sys.path.insert(0, os.path.join(ROOT, "tests"))
 
 PEAK_BF16_TFLOPS = 2500.0  # dense bf16 MFMA, MI355X
 PEAK_HBM_GBS = 8000.0      # HBM3E
@@ -66,7 +69,7 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=None)
     ap.add_argument("--warmup", type=int, default=None)
-    ap.add_argument("--workload", default="c2_mid", choices=["c2_mid", "c3_large", "c4_stream", "c5_merge"])
+    ap.add_argument("--workload", default="c3_large", choices=["c2_mid", "c3_large", "c4_stream", "c5_merge"])
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="CPU work given to the oracle baseline")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-merge", action="store_true")
@@ -131,7 +134,7 @@ def main():
 
     from paper_2508_18736_amd import siso
     from paper_2508_18736_amd import workloads as W
-    from gpu_util import to_dev, to_host
+    from paper_2508_18736_amd.siso import to_dev, to_host
 
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)

@@ -57,14 +57,6 @@ enum {
     SISO_ENOMEM = -4     /* device or host allocation failed */
 };
 
-/* Lookup kernel selection for siso_set_lookup_path. */
-enum {
-    SISO_PATH_AUTO = 0,   /* choose by element type, dimension and batch size       */
-    SISO_PATH_SCALAR = 1, /* LDS-tiled fp32 FMA kernel; any type and dimension       */
-    SISO_PATH_MFMA = 2,   /* fused bf16 MFMA GEMM + running arg-max (large batches)  */
-    SISO_PATH_SKINNY = 3  /* bandwidth-bound bf16 path for batches of at most 64     */
-};
-
 /*
  * Create a cache for `capacity` centroids of `dim` elements (bf16 storage for
  * siso_create).  dim must be in [1, 4096]; capacity in [1, 2^31 - 1].
@@ -81,24 +73,6 @@ void siso_destroy(siso_cache *c);
 
 /* hip_stream: a hipStream_t (NULL = the null stream).  Later calls enqueue there. */
 int siso_set_stream(siso_cache *c, void *hip_stream);
-
-/* Force one lookup kernel (SISO_PATH_*); a path that cannot handle the cache's
- * type or dimension, or the batch size of a later call, makes that call fail
- * with SISO_EINVAL. */
-int siso_set_lookup_path(siso_cache *c, int path);
-
-/*
- * Tuning knobs, for benchmarking; the defaults are chosen by the library.
- *   "mfma_config"     0 = default; 1 = 256x256 tile, 2 = 256x128, 3 = 256x64, 4 = 256x256 with half-width slabs,
- *                     5 = 256x256 with four waves of 128x128
- *   "tiles_per_slice" 0 = default; >0 = centroid tiles one workgroup walks through
- *   "merge_config"    0 = default; 1 = use the scalar pair search
- *   "mfma_qblock"     0 = default; 1, 2, 4, 8, 16, 32 = query tiles that share an XCD's centroid tiles
- *   "second_set"      1 = allocate now the second set of arrays that siso_merge_apply and siso_refresh
- *                     gather the rebuilt cache into (otherwise their first call does); synchronises
- * Unknown names or values out of range give SISO_EINVAL.
- */
-int siso_set_option(siso_cache *c, const char *name, long value);
 
 /*
  * Replace the cache contents by k centroids.
@@ -125,11 +99,24 @@ long siso_count(const siso_cache *c);
  *   out_sim:   device pointer, n floats: that similarity (-inf for an empty
  *              cache, NaN for a non-finite query, 0 for a zero-length query).
  *   out_hit:   device pointer, n bytes, or NULL: 1 where out_sim > threshold.
- * The similarity matrix is never written to memory.  Asynchronous; may grow an
- * internal workspace (which allocates) the first time a larger n is seen.
+ * The similarity matrix is never written to memory.  Asynchronous, with one
+ * exception: the first phase leaves a few keys per query in a workspace of the
+ * cache, and a call that needs more room than any before it (a larger batch, more
+ * centroids) waits for the stream and allocates.  siso_reserve sizes the workspace
+ * ahead of time.
  */
 int siso_lookup(siso_cache *c, const void *queries, long n, float threshold, int *out_idx, float *out_sim,
                 unsigned char *out_hit);
+
+/*
+ * Size the workspaces of siso_lookup, siso_update and siso_update_hits for batches
+ * of up to n queries (with the cache as full as it is now, and with a full cache),
+ * so that a serving loop whose batches stay within n neither allocates nor
+ * synchronises in those calls.  Synchronises and allocates itself if the room
+ * grows.  (Forcing another lookup kernel or tiling afterwards, see siso_bench.h,
+ * changes the need.)
+ */
+int siso_reserve(siso_cache *c, long n);
 
 /*
  * Centroid update as a segmented mean keyed by the assigned index.
@@ -143,7 +130,8 @@ int siso_lookup(siso_cache *c, const void *queries, long n, float threshold, int
  * queries.  An idx[i] >= siso_count() is skipped too and counted: see
  * siso_bad_indices.  All members of a centroid are taken in ascending i, so
  * the result does not depend on scheduling.  Asynchronous; the first batch of
- * more than 256 queries allocates 8 bytes per centroid of capacity for notes.
+ * more than 256 queries allocates 8 bytes per centroid of capacity for notes
+ * (siso_reserve does it ahead of time).
  *
  * siso_update_hits folds only the entries with hit[i] != 0 (device pointer, n
  * bytes): the outputs of siso_lookup can be passed on without touching the host.
@@ -177,7 +165,8 @@ long siso_merge(siso_cache *c, float threshold, int *out_pairs, long cap);
  * second set of the cache's arrays, which then changes places with the first:
  * the first call that rebuilds the cache (this one or siso_refresh) allocates
  * that set, as much device memory again as siso_create took (option
- * "second_set" does it ahead of time).  Allocates small temporaries per call.
+ * "second_set" of siso_bench.h does it ahead of time), before anything is
+ * changed: if that fails the cache is as it was.  Allocates small temporaries per call.
  * Synchronises.
  */
 int siso_merge_apply(siso_cache *c, const int *pairs, long n_pairs, int *out_survivor);
@@ -229,6 +218,20 @@ int siso_export(siso_cache *c, void *centroids, float *means, int *counts);
 int siso_refresh(siso_cache *c, const void *repo, const float *repo_size, long r, float theta_c, long max_centroids,
                  long *out_stats);
 int siso_export_meta(siso_cache *c, float *cluster_size, unsigned *access_count);
+
+/*
+ * Replace the cache contents by a snapshot of k centroids, taken over as it is:
+ * what siso_export and siso_export_meta copied out (the centroid repository is the
+ * persistent store of section 4.1; the paper gives no format, the arrays are it).
+ *   centroids [k][dim] element type, means [k][dim] floats, counts [k] ints (>= 1):
+ *   device pointers, required;  cluster_size [k] floats, access_count [k] unsigned
+ *   ints (0xFFFFFFFF = infinity): device pointers or NULL (cluster_size = counts,
+ *   access_count = 0).
+ * Nothing is normalised or rounded; only the inverse length of each stored row is
+ * computed.  SISO_ECAPACITY if k exceeds the capacity.  Asynchronous.
+ */
+int siso_import(siso_cache *c, const void *centroids, const float *means, const int *counts,
+                const float *cluster_size, const unsigned *access_count, long k);
 
 /*
  * The host part of siso_refresh by itself: the decisions of Algorithm 1 from
@@ -337,34 +340,6 @@ double siso_md1_wait(double llm_time, double arrival_rate, double hit_ratio);
 int siso_pick_threshold(const float *thetas, const double *hit_ratio, int m, double llm_time, double arrival_rate,
                         double slo, int *out_index);
 int siso_adjust_threshold(const float *thetas, int m, int index, double wait_estimated, double wait_measured);
-
-/*
- * Kernel timing for benchmarks.  While enabled (on = N > 0), every N-th
- * siso_lookup / siso_merge brackets its dominant kernel (the similarity kernel,
- * without the finalize kernel) with a pair of HIP events on the cache's stream
- * (an event costs a few microseconds on the stream, so short steps sample).
- * A pair of events with nothing between them already reads about 4 us;
- * siso_profile_enable measures that on the stream (it synchronises) and every
- * bracket is reduced by it.
- * siso_profile_read synchronises with the stream, returns the sum of the
- * bracketed durations in milliseconds and the number of brackets since the
- * last read (host pointers, either may be NULL), and releases the events.
- * At most 8192 brackets are kept between reads; later ones are not recorded.
- */
-int siso_profile_enable(siso_cache *c, int on);
-int siso_profile_read(siso_cache *c, double *total_ms, long *launches);
-
-/*
- * What this chip delivers, for the roofline lines of a benchmark (no cache
- * needed; runs on the null stream of the current device, allocates and frees
- * its own memory, synchronises; takes a fraction of a second):
- *   which = 0: a register-resident bf16 MFMA loop on random operands, TFLOP/s
- *              (the clock the chip sustains depends on how much operands toggle);
- *   which = 1: the same on constant operands, TFLOP/s;
- *   which = 2: a plain streaming read of 2 GiB from HBM, GB/s.
- * *out_value (host pointer) receives the rate.  SISO_OK, SISO_EINVAL or SISO_EHIP.
- */
-int siso_probe(int which, double *out_value);
 
 /* Message for the last error on this cache ("" if none).  Owned by the cache. */
 const char *siso_last_error(const siso_cache *c);

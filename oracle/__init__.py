@@ -65,6 +65,8 @@ def lib() -> C.CDLL:
         L.oracle_threads.restype = it
         L.oracle_export_meta.argtypes = [vp, vp, vp]
         L.oracle_export_meta.restype = it
+        L.oracle_import.argtypes = [vp, vp, vp, vp, vp, vp, lg]
+        L.oracle_import.restype = it
         L.oracle_refresh.argtypes = [vp, vp, vp, lg, fl, lg, vp, vp]
         L.oracle_refresh.restype = it
         db = C.c_double
@@ -169,6 +171,23 @@ class OracleCache:
         rc = lib().oracle_load(self._h, _ptr(cents), _ptr(cn), cents.shape[0])
         if rc != 0:
             raise RuntimeError(f"oracle_load failed ({rc})")
+
+    def import_state(self, centroids: np.ndarray, means: np.ndarray, sizes: np.ndarray,
+                     cluster_size: Optional[np.ndarray] = None, access_count: Optional[np.ndarray] = None) -> None:
+        """Take over a snapshot as it is: stored rows, means (float64), sizes, and the two numbers of
+        Algorithm 1 per row (default: cluster_size = size, access_count = 0)."""
+        cents = _storage(centroids, self.dtype, self.dim)
+        k = cents.shape[0]
+        mm = np.ascontiguousarray(means, dtype=np.float64)
+        sz = np.ascontiguousarray(sizes, dtype=np.int32)
+        loc = None if cluster_size is None else np.ascontiguousarray(cluster_size, dtype=np.float32)
+        acc = None if access_count is None else np.ascontiguousarray(access_count, dtype=np.uint32)
+        assert mm.shape == (k, self.dim) and sz.shape == (k,)
+        assert loc is None or loc.shape == (k,)
+        assert acc is None or acc.shape == (k,)
+        rc = lib().oracle_import(self._h, _ptr(cents), _ptr(mm), _ptr(sz), _ptr(loc), _ptr(acc), k)
+        if rc != 0:
+            raise RuntimeError(f"oracle_import failed ({rc})")
 
     def export_meta(self):
         """``(cluster_size float32, access_count uint32)`` of the live rows; 0xFFFFFFFF = infinity."""

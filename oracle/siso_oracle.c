@@ -438,6 +438,29 @@ int oracle_export(const oracle_cache *c, void *centroids, double *means, int *si
     return 0;
 }
 
+/*
+ * Take over a snapshot of k rows as it is (the counterpart of oracle_export and
+ * oracle_export_meta; no arithmetic): stored centroids in the storage type, means,
+ * sizes (>= 1), cluster_size and access_count (each of the last two may be NULL:
+ * cluster_size = size, access_count = 0).
+ */
+int oracle_import(oracle_cache *c, const void *centroids, const double *means, const int *sizes,
+                  const float *locality, const uint32_t *access, long k) {
+    if (!c || k < 0 || k > c->capacity || (k > 0 && (!centroids || !means || !sizes))) return -1;
+    for (long j = 0; j < k; ++j)
+        if (sizes[j] < 1) return -1;
+    const size_t cells = (size_t)k * c->dim;
+    memcpy(c->cent, centroids, cells * elem_size(c->dtype));
+    memcpy(c->mean, means, cells * sizeof(double));
+    memcpy(c->size, sizes, (size_t)k * sizeof(int));
+    for (long j = 0; j < k; ++j) {
+        c->locality[j] = locality ? locality[j] : (float)sizes[j];
+        c->access[j] = access ? access[j] : 0;
+    }
+    c->count = k;
+    return 0;
+}
+
 /* Copy out cluster_size (float) and access_count (infinity = 0xFFFFFFFF) of the live rows. */
 int oracle_export_meta(const oracle_cache *c, float *locality, uint32_t *access) {
     if (!c) return -1;

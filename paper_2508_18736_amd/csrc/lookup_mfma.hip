@@ -57,7 +57,8 @@ struct PipeCfg {
     static constexpr int NLA = BC / RPI / NW, NLB = BQ / RPI / NW;  // direct loads per wave and slab
     static_assert(BK == 64 || BK == 32, "slab of 64 or 32 elements");
     static constexpr int NL = NLA + NLB;
-    static constexpr int LDS_BYTES = NSTAGE * STAGE + 2 * BC * 4;
+    static constexpr int NINV = 3;  // tiles whose inverse lengths are kept at a time (see k_lookup_pipe)
+    static constexpr int LDS_BYTES = NSTAGE * STAGE + NINV * BC * 4;
     static_assert((BC / RPI) % NW == 0 && (BQ / RPI) % NW == 0, "whole row groups per wave");
     static_assert(BC <= SISO_PAD_ROWS && BC <= NT && BC % 64 == 0, "tile of inverse lengths: one direct load per wave");
     static_assert(BQ * NWC * 8 <= NSTAGE * STAGE, "reduction scratch fits in the stage buffers");
@@ -303,7 +304,14 @@ __global__ __launch_bounds__(Cfg::NT) __attribute__((amdgpu_waves_per_eu(2, 2)))
                   STAGE = Cfg::STAGE, NLA = Cfg::NLA, NLB = Cfg::NLB, NL = Cfg::NL, NSTAGE = Cfg::NSTAGE, BK = Cfg::BK,
                   RB = Cfg::RB, CPR = Cfg::CPR, RPI = Cfg::RPI, RP = Cfg::RP, KK = Cfg::KK, SUB = 32 * Cfg::RB;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-    float *inv_s = (float *)(smem + NSTAGE * STAGE);  // [2][BC], by tile parity
+    // Inverse lengths of the tiles in flight, [NINV][BC], tile ct in buffer (ct - ct_begin) % NINV.  Those of
+    // tile X are requested NSTAGE slabs ahead of its first slab, i.e. while slab X * nk - NSTAGE is multiplied,
+    // into the buffer that tile X - NINV used; that tile's epilogue ran with slab (X - NINV + 1) * nk - 1.  So
+    // the buffer is free as long as (NINV - 1) * nk >= NSTAGE, which three buffers give for every nk >= 2 (the
+    // smallest dimension has two slabs) and NSTAGE <= 4; two buffers did not for nk = 2 with three stages.
+    constexpr int NINV = Cfg::NINV;
+    static_assert((NINV - 1) * 2 >= NSTAGE, "a tile's inverse lengths outlive the requests that run ahead");
+    float *inv_s = (float *)(smem + NSTAGE * STAGE);
 
     const int tid = threadIdx.x;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
@@ -367,11 +375,12 @@ __global__ __launch_bounds__(Cfg::NT) __attribute__((amdgpu_waves_per_eu(2, 2)))
     const char *ld_q = (const char *)qbase;                              // and query side
     unsigned char *ld_sb = smem + wave * 1024;                           // this wave's first KiB of the stage
     int ld_t = 0;
+    int ld_inv = 0, cp_inv = 0;  // buffer of inverse lengths of the tile being requested / multiplied
     auto issue_part = [&](auto jj) {
         constexpr int j = decltype(jj)::value;
         if constexpr (j == 0) {
             if (ld_ks == 0 && wave < BC / 64)
-                gload_lds4(invn + (size_t)ld_ct * BC + wave * 64 + lane, inv_s + (ld_ct & 1) * BC + wave * 64);
+                gload_lds4(invn + (size_t)ld_ct * BC + wave * 64 + lane, inv_s + ld_inv * BC + wave * 64);
         }
         // (the empty statement keeps the 32-bit offset next to its use, which lets the load take the
         // uniform base from scalar registers instead of a 64-bit address per lane)
@@ -390,6 +399,7 @@ __global__ __launch_bounds__(Cfg::NT) __attribute__((amdgpu_waves_per_eu(2, 2)))
                 if (++ld_ks == nk) {
                     ld_ks = 0;
                     ++ld_ct;
+                    ld_inv = ld_inv + 1 == NINV ? 0 : ld_inv + 1;
                     ld_c += (size_t)(BC - 1) * d * 2;  // with the step below: on to the next tile's first slab
                     ld_q = (const char *)qbase - BK * 2;
                 }
@@ -462,7 +472,8 @@ __global__ __launch_bounds__(Cfg::NT) __attribute__((amdgpu_waves_per_eu(2, 2)))
         if (ks == nk - 1) {
             // tile done: scale by 1/|c|, fold into the running maximum of each query column
             const long c0 = (long)ct * BC;
-            const float *inv_t = inv_s + (ct & 1) * BC;
+            const float *inv_t = inv_s + cp_inv * BC;
+            cp_inv = cp_inv + 1 == NINV ? 0 : cp_inv + 1;
             static_for<0, WC>([&](auto ia) {
                 constexpr int A = decltype(ia)::value;
                 const int rb = (wc * WC + A) * 32;

@@ -105,6 +105,31 @@ __global__ __launch_bounds__(256) void k_load_rows(const T *__restrict__ src, co
     }
 }
 
+// siso_import: take over a snapshot as it is; only the inverse length of the stored row is computed.
+template <typename T>
+__global__ __launch_bounds__(256) void k_import_rows(const T *__restrict__ src, const float *__restrict__ src_mean,
+                                                      const int *__restrict__ src_size, const float *__restrict__ src_loc,
+                                                      const unsigned *__restrict__ src_acc, T *cent, float *mean, int *size,
+                                                      float *invn, float *locality, unsigned *access, int d) {
+    __shared__ float sh[4];
+    const long k = blockIdx.x;
+    float ss = 0.f;
+    for (int e = threadIdx.x; e < d; e += 256) {
+        const T x = src[(size_t)k * d + e];
+        cent[(size_t)k * d + e] = x;
+        mean[(size_t)k * d + e] = src_mean[(size_t)k * d + e];
+        ss += widen(x) * widen(x);
+    }
+    const float n2 = block_sum256(ss, sh);
+    if (threadIdx.x == 0) {
+        const int s = src_size[k] < 1 ? 1 : src_size[k];
+        size[k] = s;
+        invn[k] = inv_length(n2);
+        locality[k] = src_loc ? src_loc[k] : (float)s;
+        access[k] = src_acc ? src_acc[k] : 0u;
+    }
+}
+
 // 16-byte chunk dot products for the finalize kernel
 typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
 __device__ __forceinline__ float chunk_dot(const float *a, const float *b) {
@@ -1014,11 +1039,85 @@ extern "C" int siso_load(siso_cache *c, const void *centroids, const int *counts
     return SISO_OK;
 }
 
+extern "C" int siso_import(siso_cache *c, const void *centroids, const float *means, const int *counts,
+                           const float *cluster_size, const unsigned *access_count, long k) {
+    if (!c) return SISO_EINVAL;
+    if (k < 0 || (k > 0 && (!centroids || !means || !counts))) return siso_fail(c, SISO_EINVAL, "siso_import: bad arguments");
+    if (k > c->capacity) return siso_fail(c, SISO_ECAPACITY, "siso_import: %ld rows exceed capacity %ld", k, c->capacity);
+    if (k > 0) {
+        if (c->dtype == SISO_F32)
+            hipLaunchKernelGGL(k_import_rows<float>, dim3((unsigned)k), dim3(256), 0, c->stream, (const float *)centroids,
+                               means, counts, cluster_size, access_count, (float *)c->cent, c->mean, c->size, c->invn,
+                               c->locality, c->access, c->dim);
+        else
+            hipLaunchKernelGGL(k_import_rows<bf16_t>, dim3((unsigned)k), dim3(256), 0, c->stream, (const bf16_t *)centroids,
+                               means, counts, cluster_size, access_count, (bf16_t *)c->cent, c->mean, c->size, c->invn,
+                               c->locality, c->access, c->dim);
+        HIP_TRY(c, hipGetLastError());
+    }
+    hipLaunchKernelGGL(k_fill_nan, dim3(1), dim3(SISO_PAD_ROWS), 0, c->stream, c->invn + k, SISO_PAD_ROWS);
+    HIP_TRY(c, hipGetLastError());
+    c->count = k;
+    return SISO_OK;
+}
+
 static int choose_path(const siso_cache *c, long n) {
     if (c->path != SISO_PATH_AUTO) return c->path;
     if (n <= 64 && siso_skinny_slices(c, n) > 0) return SISO_PATH_SKINNY;
     if (siso_mfma_slices(c, n) > 0) return SISO_PATH_MFMA;
     return SISO_PATH_SCALAR;
+}
+
+// keys a lookup of n queries writes in its first phase, for the kernel the library would choose
+static long keys_needed(const siso_cache *c, long n) {
+    if (n < 1 || c->count < 1) return n > 0 ? n : 0;
+    int slices = 0;
+    switch (choose_path(c, n)) {
+        case SISO_PATH_SCALAR: slices = siso_scalar_slices(c, n); break;
+        case SISO_PATH_MFMA: slices = siso_mfma_slices(c, n); break;
+        case SISO_PATH_SKINNY: slices = siso_skinny_slices(c, n); break;
+    }
+    return slices > 0 ? n * (long)slices : 0;
+}
+
+static int ensure_update_notes(siso_cache *c) {
+    if (c->upd_owner) return SISO_OK;
+    bool ok = hipMalloc((void **)&c->upd_owner, (size_t)c->capacity * sizeof(int)) == hipSuccess;
+    ok = ok && hipMalloc((void **)&c->upd_members, (size_t)c->capacity * sizeof(int)) == hipSuccess;
+    if (!ok) {
+        (void)hipGetLastError();
+        if (c->upd_owner) (void)hipFree(c->upd_owner);
+        c->upd_owner = nullptr;
+        return siso_fail(c, SISO_ENOMEM, "siso_update: notes for %ld centroids", c->capacity);
+    }
+    hipLaunchKernelGGL(k_update_mark_init, dim3((unsigned)((c->capacity + 255) / 256)), dim3(256), 0, c->stream,
+                       c->upd_owner, c->upd_members, c->capacity);
+    return siso_check_hip(c, hipGetLastError(), "k_update_mark_init");
+}
+
+extern "C" int siso_reserve(siso_cache *c, long n) {
+    if (!c) return SISO_EINVAL;
+    if (n < 0 || n > 2147483647L / 4) return siso_fail(c, SISO_EINVAL, "siso_reserve: bad batch size %ld", n);
+    if (n == 0) return SISO_OK;
+    // The number of keys per query depends on the batch size only through the number of query tiles (64 rows
+    // is the smallest tile of any kernel) and on the number of centroids: take the largest need over all batch
+    // sizes up to n, for the cache as full as it is now and for a full cache.
+    long need = 0;
+    siso_cache full = *c;
+    full.count = c->capacity;
+    for (long m = 64;; m += 64) {
+        const long b = m < n ? m : n;
+        const long a = keys_needed(c, b), f = keys_needed(&full, b);
+        need = a > need ? a : need;
+        need = f > need ? f : need;
+        if (b == n) break;
+    }
+    if (need > c->keys_cap) {
+        const int rc = ensure_workspace(c, need, 1);
+        if (rc != SISO_OK) return rc;
+    }
+    if (n > 256) return ensure_update_notes(c);
+    return SISO_OK;
 }
 
 extern "C" int siso_lookup(siso_cache *c, const void *queries, long n, float threshold, int *out_idx, float *out_sim,
@@ -1087,18 +1186,8 @@ extern "C" int siso_update_hits(siso_cache *c, const void *queries, const int *i
         const dim3 grid((unsigned)m), block(256);
         int *owner = nullptr, *marked = nullptr;
         if (m > 256) {
-            if (!c->upd_owner) {
-                bool ok = hipMalloc((void **)&c->upd_owner, (size_t)c->capacity * sizeof(int)) == hipSuccess;
-                ok = ok && hipMalloc((void **)&c->upd_members, (size_t)c->capacity * sizeof(int)) == hipSuccess;
-                if (!ok) {
-                    (void)hipGetLastError();
-                    if (c->upd_owner) (void)hipFree(c->upd_owner);
-                    c->upd_owner = nullptr;
-                    return siso_fail(c, SISO_ENOMEM, "siso_update: notes for %ld centroids", c->capacity);
-                }
-                hipLaunchKernelGGL(k_update_mark_init, dim3((unsigned)((c->capacity + 255) / 256)), dim3(256), 0, c->stream,
-                                   c->upd_owner, c->upd_members, c->capacity);
-            }
+            const int rc = ensure_update_notes(c);
+            if (rc != SISO_OK) return rc;
             owner = c->upd_owner;
             marked = c->upd_members;
             hipLaunchKernelGGL(k_update_mark, dim3((unsigned)((m + 255) / 256)), dim3(256), 0, c->stream, idx + off, h, m,
@@ -1195,7 +1284,10 @@ extern "C" int siso_merge_apply(siso_cache *c, const int *pairs, long n_pairs, i
     int *parent = nullptr, *root = nullptr, *newpos = nullptr, *members_of = nullptr, *cursor = nullptr, *first = nullptr,
         *list = nullptr;
     unsigned char *touched = nullptr;
-    int rc = SISO_OK;
+    // every valid pair joins two rows, so the survivors will be gathered into the second set of arrays: make
+    // sure it exists before anything is changed in place (a failure here leaves the cache as it was)
+    int rc = n_pairs > 0 ? siso_second_set(c) : SISO_OK;
+    if (rc != SISO_OK) return rc;
     bool ok = hipMalloc((void **)&parent, (size_t)K * sizeof(int)) == hipSuccess;
     ok = ok && hipMalloc((void **)&root, (size_t)K * sizeof(int)) == hipSuccess;
     ok = ok && hipMalloc((void **)&newpos, (size_t)K * sizeof(int)) == hipSuccess;
@@ -1234,7 +1326,6 @@ extern "C" int siso_merge_apply(siso_cache *c, const int *pairs, long n_pairs, i
         hipLaunchKernelGGL(k_survivor_map, dim3(kb), dim3(256), 0, c->stream, root, newpos, K, out_survivor);
         rc = siso_check_hip(c, hipGetLastError(), "k_survivor_map");
     }
-    if (rc == SISO_OK && live < K) rc = siso_second_set(c);
     if (rc == SISO_OK && live < K) {
         // survivors packed to the front of the second set, which then becomes the cache
         if (c->dtype == SISO_F32)

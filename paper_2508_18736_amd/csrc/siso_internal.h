@@ -6,6 +6,7 @@
 #include <stdint.h>
 
 #include "siso.h"
+#include "siso_bench.h"
 
 typedef unsigned long long u64;
 typedef unsigned short bf16_t;  // bfloat16 bit pattern

@@ -1,4 +1,5 @@
-"""Thin binding over the C-ABI library ``libsiso.so`` (declared in ``include/siso.h``).
+"""Thin binding over the C-ABI library ``libsiso.so`` (declared in ``include/siso.h``; the tuning and
+timing calls in ``include/siso_bench.h``).
 
 Argument marshalling only: every step of the hot path runs in the library's HIP
 kernels.  PyTorch supplies device memory (``tensor.data_ptr()``) and the stream.
@@ -27,7 +28,7 @@ F32, BF16 = 0, 1
 PATH_AUTO, PATH_SCALAR, PATH_MFMA, PATH_SKINNY = 0, 1, 2, 3
 OK, EINVAL, ECAPACITY, EHIP, ENOMEM = 0, -1, -2, -3, -4
 
-# every symbol include/siso.h declares, with its signature
+# every symbol the headers under include/ declare, with its signature
 _vp, _lg, _it, _fl = C.c_void_p, C.c_long, C.c_int, C.c_float
 SYMBOLS = {
     "siso_create": ([_it, _lg, C.POINTER(_vp)], _it),
@@ -38,6 +39,7 @@ SYMBOLS = {
     "siso_set_option": ([_vp, C.c_char_p, _lg], _it),
     "siso_load": ([_vp, _vp, _vp, _lg], _it),
     "siso_count": ([_vp], _lg),
+    "siso_reserve": ([_vp, _lg], _it),
     "siso_lookup": ([_vp, _vp, _lg, _fl, _vp, _vp, _vp], _it),
     "siso_update": ([_vp, _vp, _vp, _lg], _it),
     "siso_update_hits": ([_vp, _vp, _vp, _vp, _lg], _it),
@@ -54,6 +56,7 @@ SYMBOLS = {
     "siso_choose_communities": ([_vp, _lg, _lg, _it, _vp], _lg),
     "siso_refresh_plan": ([_lg, _vp, _vp, _lg, _vp, _vp, _vp, _vp, _vp, _lg, _fl, _lg, _vp, _vp, _vp], _lg),
     "siso_export_meta": ([_vp, _vp, _vp], _it),
+    "siso_import": ([_vp, _vp, _vp, _vp, _vp, _vp, _lg], _it),
     "siso_t2h": ([_vp, _vp, _lg, _vp, _it, _vp], _it),
     "siso_md1_wait": ([C.c_double, C.c_double, C.c_double], C.c_double),
     "siso_pick_threshold": ([_vp, _vp, _it, C.c_double, C.c_double, C.c_double, C.POINTER(_it)], _it),
@@ -139,6 +142,23 @@ def probe(which: int) -> float:
     return float(v.value)
 
 
+def to_dev(arr, dtype: str, device: str = "cuda:0") -> torch.Tensor:
+    """Host rows (numpy; bf16 as uint16 bit patterns, as the workload generators carry them) -> device tensor."""
+    import numpy as np
+    if dtype == "bf16":
+        return torch.from_numpy(np.ascontiguousarray(arr).view(np.int16)).view(torch.bfloat16).to(device)
+    return torch.from_numpy(np.ascontiguousarray(arr, dtype=np.float32)).to(device)
+
+
+def to_host(t: torch.Tensor, dtype: str):
+    """Device tensor -> host rows (numpy; bf16 as uint16 bit patterns)."""
+    import numpy as np
+    t = t.detach().cpu().contiguous()
+    if dtype == "bf16":
+        return t.view(torch.int16).numpy().view(np.uint16)
+    return t.numpy()
+
+
 class SisoError(RuntimeError):
     def __init__(self, code: int, msg: str):
         super().__init__(f"siso error {code}: {msg}")
@@ -204,6 +224,10 @@ class SisoCache:
 
     def set_option(self, name: str, value: int) -> None:
         self._check(_lib.siso_set_option(self._h, name.encode(), int(value)))
+
+    def reserve(self, n: int) -> None:
+        """Room for lookups and updates of up to ``n`` queries, so that those calls never allocate."""
+        self._check(_lib.siso_reserve(self._h, int(n)))
 
     @property
     def count(self) -> int:
@@ -293,6 +317,24 @@ class SisoCache:
         acc = torch.empty(k, dtype=torch.int32, device=self.device)
         self._check(_lib.siso_export_meta(self._h, _ptr(loc), _ptr(acc)))
         return loc, acc.to(torch.int64) & 0xFFFFFFFF
+
+    def import_state(self, centroids: torch.Tensor, means: torch.Tensor, counts: torch.Tensor,
+                     cluster_size: Optional[torch.Tensor] = None, access_count: Optional[torch.Tensor] = None) -> None:
+        """Take over a snapshot (what ``export`` and ``export_meta`` returned) as it is.  ``access_count`` may be
+        the int64 tensor ``export_meta`` returns (0xFFFFFFFF = infinity)."""
+        cents = self._rows(centroids, "centroids")
+        k = cents.shape[0]
+        if means.device != self.device or means.dtype != torch.float32 or means.shape != cents.shape:
+            raise ValueError("means: expected a float32 tensor of the centroids' shape on the cache's device")
+        mm = means.contiguous()
+        cn = self._vec(counts, torch.int32, k, "counts")
+        loc = self._vec(cluster_size, torch.float32, k, "cluster_size")
+        acc = None
+        if access_count is not None:
+            # the low 32 bits as they are (0xFFFFFFFF stays 0xFFFFFFFF)
+            acc = (access_count.to(torch.int64) & 0xFFFFFFFF).to(torch.uint32).view(torch.int32).contiguous()
+            self._vec(acc, torch.int32, k, "access_count")
+        self._check(_lib.siso_import(self._h, _ptr(cents), _ptr(mm), _ptr(cn), _ptr(loc), _ptr(acc), k))
 
     def t2h(self, queries: torch.Tensor, thetas):
         """Hits per threshold (numpy int64) of the sample queries; thresholds are host values."""

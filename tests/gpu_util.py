@@ -15,16 +15,13 @@ DEV = "cuda:0"
 
 
 def to_dev(arr: np.ndarray, dtype: str) -> torch.Tensor:
-    if dtype == "bf16":
-        return torch.from_numpy(np.ascontiguousarray(arr).view(np.int16)).view(torch.bfloat16).to(DEV)
-    return torch.from_numpy(np.ascontiguousarray(arr, dtype=np.float32)).to(DEV)
+    from paper_2508_18736_amd import siso
+    return siso.to_dev(arr, dtype, DEV)
 
 
 def to_host(t: torch.Tensor, dtype: str) -> np.ndarray:
-    t = t.detach().cpu().contiguous()
-    if dtype == "bf16":
-        return t.view(torch.int16).numpy().view(np.uint16)
-    return t.numpy()
+    from paper_2508_18736_amd import siso
+    return siso.to_host(t, dtype)
 
 
 def siso_dtype(dtype: str) -> int:

@@ -76,6 +76,29 @@ def test_mfma_path_vs_oracle(siso, oracle, cfg, dim, K, n, tps):
     assert all(torch.equal(a, b) for a, b in zip(out, out2))
 
 
+@pytest.mark.parametrize("cfg,n", [(2, 100), (3, 40), (1, 300), (4, 300), (5, 300)])
+@pytest.mark.parametrize("tps", [3, 7])
+def test_two_slab_tiles_with_scaled_rows(siso, oracle, cfg, n, tps):
+    """The smallest dimension of the MFMA path (two slabs per tile) with workgroups that walk through
+    several tiles, a ragged last tile and stored rows of very different lengths: a tile scaled by another
+    tile's inverse lengths would lose its winners."""
+    dim, K = 128, 256 * 9 + 77
+    print(f"case: two-slab tiles cfg={cfg} n={n} tiles_per_slice={tps}", flush=True)
+    wl = W.c2_mid(n_clusters=128, per_cluster=(K + 127) // 128, n_queries=n, dim=dim, seed=77 + cfg)
+    r = np.random.default_rng(5 + tps)
+    c = wl.centroids_f32()[:K] * np.exp2(r.integers(-6, 7, size=K)).astype(np.float32)[:, None]
+    wl.centroids = W.f32_to_bf16_bits(c)
+    ora = oracle.lookup_rows(wl.centroids, wl.queries, 0.85, "bf16")
+    cache, out = run_lookup(siso, wl, 0.85, siso.PATH_MFMA, {"mfma_config": cfg, "tiles_per_slice": tps}, capacity=K + 5)
+    st = check_lookup(out, ora, 0.85, "bf16", f"two-slab cfg {cfg}")
+    assert st["max_err"] < 1e-4 and st["clear"] > n // 2
+    if n <= 64:  # the small-batch path proper (one workgroup per compute unit) on the same rows
+        cache.set_option("mfma_config", 0)
+        cache.set_lookup_path(siso.PATH_SKINNY)
+        out2 = cache.lookup(to_dev(wl.queries, "bf16"), 0.85)
+        check_lookup(out2, ora, 0.85, "bf16", "two-slab skinny")
+
+
 @pytest.mark.parametrize("dim,K,n", [(256, 5013, 64), (768, 4099, 7), (1024, 2048, 33), (768, 31, 1), (512, 70000, 32)])
 def test_skinny_path_vs_oracle(siso, oracle, dim, K, n):
     print(f"case: skinny dim={dim} K={K} n={n}", flush=True)

@@ -38,6 +38,11 @@ def compare_state(cache, oc, dtype, label):
         assert diff.mean() < 2e-3, f"{label}: {diff.mean():.2e} of stored bf16 values differ"
         a = W.bf16_bits_to_f32(g).astype(np.float64); b = W.bf16_bits_to_f32(oc_c).astype(np.float64)
         assert np.abs(a - b).max() <= 2.0 ** -8, label
+    # the two numbers of Algorithm 1 per centroid: same single-precision sums in the same order, exact counts
+    gl, ga = cache.export_meta()
+    ol, oa = oc.export_meta()
+    assert np.array_equal(gl.cpu().numpy().view(np.uint32), ol.view(np.uint32)), f"{label}: cluster_size (Algorithm 1) differs"
+    assert np.array_equal(ga.cpu().numpy().astype(np.uint32), oa), f"{label}: access_count differs"
     return err
 
 
@@ -257,3 +262,51 @@ def test_merge_apply_groups_of_many_sizes(siso, oracle):
     assert np.array_equal(surv.cpu().numpy(), oc.merge_apply(pairs))
     assert cache.count == oc.count == K - sum(sizes) + len(sizes)
     compare_state(cache, oc, dtype, "groups of many sizes")
+
+
+def test_merge_apply_meta_hand_worked_and_random(siso, oracle):
+    """cluster_size and access_count of merged groups: the example worked by hand (a member at infinity, a sum that
+    reaches infinity, a single-precision sum that depends on its order), then random groups with large access
+    counts, state taken over from a snapshot on both sides."""
+    from test_oracle_update_merge import merge_meta_state, read_merge_meta_example
+    print("case: merge_apply cluster_size / access_count", flush=True)
+    loc, acc, pairs, expect, surv = read_merge_meta_example()
+    k = len(loc)
+    cents, means, sizes = merge_meta_state(k, dim=64)
+    cache = siso.SisoCache(64, k, siso.F32)
+    dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(DEV)
+    cache.import_state(dev(cents), dev(means.astype(np.float32)), dev(sizes), dev(loc), dev(acc.astype(np.int64)))
+    gl, ga = cache.export_meta()
+    assert np.array_equal(gl.cpu().numpy(), loc) and np.array_equal(ga.cpu().numpy().astype(np.uint32), acc)
+    got = cache.merge_apply(dev(pairs)).cpu().numpy()
+    assert np.array_equal(got, surv) and cache.count == len(expect)
+    gl, ga = cache.export_meta()
+    gl, ga = gl.cpu().numpy(), ga.cpu().numpy()
+    for i, (want_l, want_a) in expect.items():
+        assert gl[i].view(np.uint32) == np.float32(want_l).view(np.uint32) and int(ga[i]) == want_a, f"survivor {i}"
+    # random: 600 rows, groups of 2..40 rows as shuffled chains, fractional cluster sizes, access counts up to 2^31
+    rng = np.random.default_rng(91)
+    K, dim = 600, 128
+    rows = W.to_storage(W.uniform_directions(92, 2, K, dim), "bf16")
+    u = W.bf16_bits_to_f32(rows).astype(np.float64)
+    means = u / np.linalg.norm(u, axis=1, keepdims=True)
+    sizes = rng.integers(1, 9, size=K).astype(np.int32)
+    loc = (rng.integers(1, 4000, size=K) / np.float32(1.1)).astype(np.float32)
+    acc = rng.integers(0, 2 ** 31, size=K).astype(np.uint32)
+    acc[rng.random(K) < 0.05] = 0xFFFFFFFF
+    acc[rng.random(K) < 0.5] //= 65536
+    perm, at, pr = rng.permutation(K), 0, []
+    for m in [2, 3, 5, 40, 17, 2, 2, 9, 33, 4, 4, 4, 8]:
+        mem = perm[at:at + m]
+        at += m
+        pr += [(int(mem[i]), int(mem[i + 1])) for i in range(m - 1)]
+    pr = np.array(pr, np.int32)[rng.permutation(len(pr))]
+    cache = siso.SisoCache(dim, K, siso.BF16)
+    cache.import_state(to_dev(rows, "bf16"), dev(means.astype(np.float32)), dev(sizes), dev(loc), dev(acc.astype(np.int64)))
+    oc = oracle.OracleCache(dim, K, "bf16")
+    oc.import_state(rows, means.astype(np.float32).astype(np.float64), sizes, loc, acc)
+    compare_state(cache, oc, "bf16", "snapshot taken over")
+    assert np.array_equal(cache.merge_apply(dev(pr)).cpu().numpy(), oc.merge_apply(pr))
+    compare_state(cache, oc, "bf16", "merge_apply with cluster sizes and access counts")
+    ol, oa = oc.export_meta()
+    assert (oa == 0xFFFFFFFF).sum() >= 3 and len(np.unique(ol)) > 100

@@ -235,3 +235,71 @@ def test_merge_apply_chains_singletons_and_errors(oracle):
     for bad in ([[0, 0]], [[0, 9]], [[-1, 2]]):
         with pytest.raises(RuntimeError):
             oc.merge_apply(np.array(bad, np.int32))
+
+
+# ------------------------------------------------- group merge: cluster_size and access_count
+def read_merge_meta_example():
+    """tests/golden/merge_meta_hand_worked.txt -> (cluster_size, access_count, pairs, expected rows, survivor map)"""
+    import os
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "merge_meta_hand_worked.txt")
+
+    def f32_of(tok):
+        return np.array([int(tok, 16)], np.uint32).view(np.float32)[0] if tok.startswith("0x") else np.float32(tok)
+
+    loc, acc, pairs, expect, surv = {}, {}, [], {}, None
+    for line in open(path):
+        t = line.split("#")[0].split()
+        if not t:
+            continue
+        if t[0] == "row":
+            loc[int(t[1])], acc[int(t[1])] = f32_of(t[3]), int(t[4], 0)
+        elif t[0] == "pair":
+            pairs.append((int(t[1]), int(t[2])))
+        elif t[0] == "expect":
+            expect[int(t[1])] = (f32_of(t[2]), int(t[3], 0))
+        elif t[0] == "survivor_map":
+            surv = np.array([int(x) for x in t[1:]], np.int32)
+    k = len(loc)
+    return (np.array([loc[i] for i in range(k)], np.float32), np.array([acc[i] for i in range(k)], np.uint32),
+            np.array(pairs, np.int32), expect, surv)
+
+
+def merge_meta_state(k, dim=4, seed=3):
+    """Rows for the example: every row its own direction, weight 1 (the vectors do not enter the two sums)."""
+    x = np.random.default_rng(seed).standard_normal((k, dim)).astype(np.float32)
+    cents = f32(x / np.linalg.norm(x, axis=1, keepdims=True))
+    return cents, cents.astype(np.float64), np.ones(k, np.int32)
+
+
+def test_group_merge_adds_cluster_sizes_and_access_counts_hand_worked(oracle):
+    loc, acc, pairs, expect, surv = read_merge_meta_example()
+    k = len(loc)
+    cents, means, sizes = merge_meta_state(k)
+    oc = oracle.OracleCache(4, k, "f32")
+    oc.import_state(cents, means, sizes, loc, acc)
+    got_l, got_a = oc.export_meta()
+    assert np.array_equal(got_l, loc) and np.array_equal(got_a, acc)      # the snapshot is taken over as it is
+    got_surv = oc.merge_apply(pairs)
+    assert np.array_equal(got_surv, surv) and oc.count == len(expect)
+    got_l, got_a = oc.export_meta()
+    for i, (want_l, want_a) in expect.items():
+        assert got_l[i].view(np.uint32) == np.float32(want_l).view(np.uint32), f"cluster_size of survivor {i}"
+        assert int(got_a[i]) == want_a, f"access_count of survivor {i}"
+    # the weights of the means add up as before (six, two, three, two rows of weight 1; one row alone)
+    assert np.array_equal(oc.export()[2], [6, 2, 3, 2, 1])
+
+
+def test_group_merge_meta_does_not_depend_on_the_order_of_the_pairs(oracle):
+    loc, acc, pairs, expect, surv = read_merge_meta_example()
+    k = len(loc)
+    cents, means, sizes = merge_meta_state(k)
+    r = np.random.default_rng(11)
+    for trial in range(5):
+        p = pairs[r.permutation(len(pairs))]
+        flip = r.random(len(p)) < 0.5
+        p = np.where(flip[:, None], p[:, ::-1], p)
+        oc = oracle.OracleCache(4, k, "f32")
+        oc.import_state(cents, means, sizes, loc, acc)
+        assert np.array_equal(oc.merge_apply(p), surv)
+        got_l, got_a = oc.export_meta()
+        assert [(float(l), int(a)) for l, a in zip(got_l, got_a)] == [(float(expect[i][0]), expect[i][1]) for i in range(5)]
