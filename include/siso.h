@@ -109,6 +109,24 @@ int siso_lookup(siso_cache *c, const void *queries, long n, float threshold, int
                 unsigned char *out_hit);
 
 /*
+ * siso_lookup for callers that cannot allocate device memory: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments,
+ * same kernels and bit-identical results, but the keys of the first phase go to a
+ * key array that is part of the library's image (1,048,576 keys = 8 MiB, held by
+ * every GPU the library runs on until the process ends) instead of the cache's own
+ * workspace: the call never allocates, frees or synchronises, and records no
+ * timing events.  A batch whose first phase needs more keys (queries x slices of
+ * the centroid range, e.g. the 16,384 x 512 of the largest configuration) is
+ * rejected with SISO_ECAPACITY and a message; nothing has been enqueued then.
+ * The array holds the last call's keys and every entry a call reads is written by
+ * that call first, so nothing is cleared.  All calls on one GPU share the array:
+ * calls that overlap on one GPU (two caches on two streams) race; calls on one
+ * stream are ordered.
+ */
+int siso_lookup_static(siso_cache *c, const void *queries, long n, float threshold, int *out_idx, float *out_sim,
+                       unsigned char *out_hit);
+
+/*
  * Size the workspaces of siso_lookup, siso_update and siso_update_hits for batches
  * of up to n queries (with the cache as full as it is now, and with a full cache),
  * so that a serving loop whose batches stay within n neither allocates nor

@@ -1106,7 +1106,7 @@ static bool skinny_plan(const siso_cache *c, long n, PipePlan *p) {
 }
 
 template <class Cfg>
-static int launch_cfg(siso_cache *c, const void *queries, long n, const PipePlan &p) {
+static int launch_cfg(siso_cache *c, const void *queries, long n, const PipePlan &p, u64 *keys) {
     static bool attr_done = false;
     if (!attr_done) {
         hipError_t e = hipFuncSetAttribute((const void *)k_lookup_pipe<Cfg>,
@@ -1116,11 +1116,11 @@ static int launch_cfg(siso_cache *c, const void *queries, long n, const PipePlan
     }
     hipLaunchKernelGGL((k_lookup_pipe<Cfg>), dim3((unsigned)p.grid), dim3(Cfg::NT), Cfg::LDS_BYTES,
                        c->stream, (const bf16_t *)queries, (const bf16_t *)c->cent, c->invn, n, c->count, c->dim,
-                       p.tiles_per_slice, p.slices, p.nqt, p.qb, c->keys);
+                       p.tiles_per_slice, p.slices, p.nqt, p.qb, keys);
     return siso_check_hip(c, hipGetLastError(), "k_lookup_pipe");
 }
 
-static int launch_wide(siso_cache *c, const void *queries, long n, const PipePlan &p) {
+static int launch_wide(siso_cache *c, const void *queries, long n, const PipePlan &p, u64 *keys) {
     static bool attr_done = false;
     if (!attr_done) {
         hipError_t e = hipFuncSetAttribute((const void *)k_lookup_wide,
@@ -1130,18 +1130,18 @@ static int launch_wide(siso_cache *c, const void *queries, long n, const PipePla
     }
     hipLaunchKernelGGL((k_lookup_wide), dim3((unsigned)p.grid), dim3(WideCfg::NT), WideCfg::LDS_BYTES, c->stream,
                        (const bf16_t *)queries, (const bf16_t *)c->cent, c->invn, n, c->count, c->dim, p.tiles_per_slice,
-                       p.slices, p.nqt, p.qb, c->keys);
+                       p.slices, p.nqt, p.qb, keys);
     return siso_check_hip(c, hipGetLastError(), "k_lookup_wide");
 }
 
-static int pipe_launch(siso_cache *c, const void *queries, long n, const PipePlan &p) {
+static int pipe_launch(siso_cache *c, const void *queries, long n, const PipePlan &p, u64 *keys) {
     if (((uintptr_t)queries & 15) != 0) return siso_fail(c, SISO_EINVAL, "bf16 lookup: queries must be 16-byte aligned");
     switch (p.cfg) {
-        case 1: return launch_cfg<PipeLarge>(c, queries, n, p);
-        case 2: return launch_cfg<PipeMid>(c, queries, n, p);
-        case 3: return launch_cfg<PipeSmall>(c, queries, n, p);
-        case 4: return launch_cfg<PipeLarge32>(c, queries, n, p);
-        default: return launch_wide(c, queries, n, p);
+        case 1: return launch_cfg<PipeLarge>(c, queries, n, p, keys);
+        case 2: return launch_cfg<PipeMid>(c, queries, n, p, keys);
+        case 3: return launch_cfg<PipeSmall>(c, queries, n, p, keys);
+        case 4: return launch_cfg<PipeLarge32>(c, queries, n, p, keys);
+        default: return launch_wide(c, queries, n, p, keys);
     }
 }
 
@@ -1155,11 +1155,11 @@ static int keys_carry_rows(const PipePlan &p) {
     return (p.cfg == 2 && PipeMid::ROWS) || (p.cfg == 3 && PipeSmall::ROWS) ? SISO_KEY_ROWS : SISO_KEY_GROUPS4;
 }
 
-int siso_mfma_launch(siso_cache *c, const void *queries, long n, int slices, int *row_keys) {
+int siso_mfma_launch(siso_cache *c, const void *queries, long n, int slices, u64 *keys, int *row_keys) {
     PipePlan p;
     if (!mfma_plan(c, n, &p) || p.slices != slices) return siso_fail(c, SISO_EINVAL, "mfma lookup: plan mismatch");
     *row_keys = keys_carry_rows(p);
-    return pipe_launch(c, queries, n, p);
+    return pipe_launch(c, queries, n, p, keys);
 }
 
 int siso_skinny_slices(const siso_cache *c, long n) {
@@ -1167,11 +1167,11 @@ int siso_skinny_slices(const siso_cache *c, long n) {
     return skinny_plan(c, n, &p) ? p.slices : 0;
 }
 
-int siso_skinny_launch(siso_cache *c, const void *queries, long n, int slices, int *row_keys) {
+int siso_skinny_launch(siso_cache *c, const void *queries, long n, int slices, u64 *keys, int *row_keys) {
     PipePlan p;
     if (!skinny_plan(c, n, &p) || p.slices != slices) return siso_fail(c, SISO_EINVAL, "skinny lookup: plan mismatch");
     *row_keys = keys_carry_rows(p);
-    return pipe_launch(c, queries, n, p);
+    return pipe_launch(c, queries, n, p, keys);
 }
 
 // ----------------------------------------------------------------------------

@@ -384,18 +384,18 @@ int siso_scalar_slices(const siso_cache *c, long n) {
 }
 
 template <typename T>
-static int scalar_launch_t(siso_cache *c, const void *queries, long n, int slices) {
+static int scalar_launch_t(siso_cache *c, const void *queries, long n, int slices, u64 *keys) {
     const long ctiles = (c->count + ST_M - 1) / ST_M;
     const long rows_per_slice = ((ctiles + slices - 1) / slices) * ST_M;
     dim3 grid((unsigned)((n + ST_M - 1) / ST_M), (unsigned)slices);
     hipLaunchKernelGGL(k_lookup_scalar<T>, grid, dim3(256), 0, c->stream, (const T *)queries, (const T *)c->cent,
-                       c->invn, n, c->count, c->dim, rows_per_slice, slices, c->keys);
+                       c->invn, n, c->count, c->dim, rows_per_slice, slices, keys);
     return siso_check_hip(c, hipGetLastError(), "k_lookup_scalar");
 }
 
-int siso_scalar_launch(siso_cache *c, const void *queries, long n, int slices) {
-    return c->dtype == SISO_F32 ? scalar_launch_t<float>(c, queries, n, slices)
-                                : scalar_launch_t<bf16_t>(c, queries, n, slices);
+int siso_scalar_launch(siso_cache *c, const void *queries, long n, int slices, u64 *keys) {
+    return c->dtype == SISO_F32 ? scalar_launch_t<float>(c, queries, n, slices, keys)
+                                : scalar_launch_t<bf16_t>(c, queries, n, slices, keys);
 }
 
 // Self-similarity, scalar path: block (x, y) = tile pair, upper triangle only.
@@ -857,6 +857,32 @@ __global__ void k_survivor_map(const int *__restrict__ root, const int *__restri
 // ============================================================================
 // C ABI
 // ============================================================================
+// Key workspace of siso_lookup_static: part of the library's image, so a caller that must not allocate
+// (graph capture, a serving loop, a harness that forbids it) still has room for the phase-1 keys.  Every
+// GPU the library runs on holds its own copy at its own address until the process ends; in host code the
+// array's name is only a handle for hipGetSymbolAddress, never an address to pass on.
+#define SISO_STATIC_KEYS (1L << 20)  // 8 MiB
+static __device__ __align__(256) u64 scratch[SISO_STATIC_KEYS];
+#define SISO_MAX_DEVICES 64
+static u64 *scratch_ptr[SISO_MAX_DEVICES];  // device address of `scratch` per device, resolved by siso_create_ex
+
+// the current device's copy of the array (the device must be current)
+static int resolve_scratch(int device, u64 **out) {
+    *out = nullptr;
+    if (device < 0 || device >= SISO_MAX_DEVICES) return SISO_EINVAL;
+    if (!scratch_ptr[device]) {
+        u64 *ptr = nullptr;
+        const hipError_t e = hipGetSymbolAddress((void **)&ptr, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !ptr) {
+            (void)hipGetLastError();
+            return SISO_EHIP;
+        }
+        scratch_ptr[device] = ptr;
+    }
+    *out = scratch_ptr[device];
+    return SISO_OK;
+}
+
 static int ensure_workspace(siso_cache *c, long n, int slices) {
     const long need_keys = n * (long)slices;
     if (need_keys > c->keys_cap) {
@@ -932,6 +958,7 @@ extern "C" int siso_create_ex(int dim, long capacity, int dtype, siso_cache **ou
     c->path = SISO_PATH_AUTO;
     const size_t cells = (size_t)capacity * dim;
     bool ok = hipGetDevice(&c->device) == hipSuccess;
+    ok = ok && resolve_scratch(c->device, &c->static_keys) == SISO_OK;
     // The stored centroids carry SISO_PAD_ROWS readable rows past the capacity, so that the
     // tiled kernels may load a whole last tile; their results are discarded.
     const size_t cent_bytes = (cells + (size_t)SISO_PAD_ROWS * dim) * elem_bytes(dtype);
@@ -1068,6 +1095,15 @@ static int choose_path(const siso_cache *c, long n) {
     return SISO_PATH_SCALAR;
 }
 
+extern "C" int siso_lookup_static(siso_cache *c, const void *queries, long n, float threshold, int *out_idx,
+                                  float *out_sim, unsigned char *out_hit) {
+    if (!c) return SISO_EINVAL;
+    if (n < 0 || (n > 0 && (!queries || !out_idx || !out_sim)))
+        return siso_fail(c, SISO_EINVAL, "siso_lookup_static: bad arguments");
+    if (!c->static_keys) return siso_fail(c, SISO_EHIP, "siso_lookup_static: the static workspace was not found on device %d", c->device);
+    return siso_lookup_impl(c, queries, n, threshold, out_idx, out_sim, out_hit, 1, c->static_keys, SISO_STATIC_KEYS);
+}
+
 // keys a lookup of n queries writes in its first phase, for the kernel the library would choose
 static long keys_needed(const siso_cache *c, long n) {
     if (n < 1 || c->count < 1) return n > 0 ? n : 0;
@@ -1129,7 +1165,7 @@ extern "C" int siso_lookup(siso_cache *c, const void *queries, long n, float thr
 }
 
 int siso_lookup_impl(siso_cache *c, const void *queries, long n, float threshold, int *out_idx, float *out_sim,
-                     unsigned char *out_hit, int count_access) {
+                     unsigned char *out_hit, int count_access, u64 *static_keys, long static_cap) {
     if (n == 0) return SISO_OK;
     if (n > 2147483647L / 4) return siso_fail(c, SISO_EINVAL, "siso_lookup: batch of %ld is too large", n);
     int slices = 1;
@@ -1144,28 +1180,37 @@ int siso_lookup_impl(siso_cache *c, const void *queries, long n, float threshold
             return siso_fail(c, SISO_EINVAL, "siso_lookup: path %d cannot serve dim %d, type %d, batch %ld", path,
                              c->dim, c->dtype, n);
     }
-    int rc = ensure_workspace(c, n, slices);
-    if (rc != SISO_OK) return rc;
+    int rc = SISO_OK;
+    if (static_keys) {
+        if (n * (long)slices > static_cap)
+            return siso_fail(c, SISO_ECAPACITY,
+                             "siso_lookup_static: %ld queries x %d slices of the centroids need %ld keys, the static "
+                             "workspace holds %ld", n, slices, n * (long)slices, static_cap);
+    } else {
+        rc = ensure_workspace(c, n, slices);
+        if (rc != SISO_OK) return rc;
+    }
+    u64 *keys = static_keys ? static_keys : c->keys;
     const unsigned qblocks = (unsigned)n;
     const int vec = ((c->dim * elem_bytes(c->dtype)) % 16 == 0 && ((uintptr_t)queries & 15) == 0) ? 1 : 0;
     int row_keys = SISO_KEY_ROWS;  // what the keys of the chosen kernel carry: the winning row, or its group of four rows
     if (c->count > 0) {
-        siso_prof_begin(c);
+        if (!static_keys) siso_prof_begin(c);
         switch (path) {
-            case SISO_PATH_SCALAR: rc = siso_scalar_launch(c, queries, n, slices); break;
-            case SISO_PATH_MFMA: rc = siso_mfma_launch(c, queries, n, slices, &row_keys); break;
-            case SISO_PATH_SKINNY: rc = siso_skinny_launch(c, queries, n, slices, &row_keys); break;
+            case SISO_PATH_SCALAR: rc = siso_scalar_launch(c, queries, n, slices, keys); break;
+            case SISO_PATH_MFMA: rc = siso_mfma_launch(c, queries, n, slices, keys, &row_keys); break;
+            case SISO_PATH_SKINNY: rc = siso_skinny_launch(c, queries, n, slices, keys, &row_keys); break;
         }
-        siso_prof_end(c);
+        if (!static_keys) siso_prof_end(c);
         if (rc != SISO_OK) return rc;
     }
     if (c->dtype == SISO_F32)
         hipLaunchKernelGGL(k_lookup_finalize<float>, dim3(qblocks), dim3(256), 0, c->stream, (const float *)queries,
-                           (const float *)c->cent, c->invn, c->keys, n, c->count, c->dim, slices, threshold,
+                           (const float *)c->cent, c->invn, keys, n, c->count, c->dim, slices, threshold,
                            vec, row_keys, out_idx, out_sim, out_hit, count_access ? c->access : nullptr);
     else
         hipLaunchKernelGGL(k_lookup_finalize<bf16_t>, dim3(qblocks), dim3(256), 0, c->stream, (const bf16_t *)queries,
-                           (const bf16_t *)c->cent, c->invn, c->keys, n, c->count, c->dim, slices, threshold,
+                           (const bf16_t *)c->cent, c->invn, keys, n, c->count, c->dim, slices, threshold,
                            vec, row_keys, out_idx, out_sim, out_hit, count_access ? c->access : nullptr);
     HIP_TRY(c, hipGetLastError());
     return SISO_OK;

@@ -63,6 +63,8 @@ struct siso_cache {
     u64 *keys;     // [keys_cap] phase-1 keys, n * slices
     long keys_cap;
 
+    u64 *static_keys;  // this device's copy of the library's static key array (siso_lookup_static)
+
     u64 *counters;  // device: [0] bad update indices, [1] merge pair count, [2] scratch, [3] scratch
     u64 *host_pin;  // pinned host mirror for counter read-back (4 entries)
 
@@ -242,15 +244,16 @@ void siso_prof_begin(siso_cache *c);  // bracket the dominant kernel of a call (
 void siso_prof_end(siso_cache *c);
 int siso_check_hip(siso_cache *c, hipError_t e, const char *what);
 
-// Phase-1 launchers.  Each fills keys[q * slices + s] for all q < n, s < slices.
+// Phase-1 launchers.  Each fills keys[q * slices + s] for all q < n, s < slices (every entry is written,
+// nothing has to be cleared beforehand).
 // *_slices returns the number of slices the launcher will use (0 = path cannot
 // handle this cache / batch).
 int siso_scalar_slices(const siso_cache *c, long n);
-int siso_scalar_launch(siso_cache *c, const void *queries, long n, int slices);
+int siso_scalar_launch(siso_cache *c, const void *queries, long n, int slices, u64 *keys);
 int siso_mfma_slices(const siso_cache *c, long n);
-int siso_mfma_launch(siso_cache *c, const void *queries, long n, int slices, int *row_keys);
+int siso_mfma_launch(siso_cache *c, const void *queries, long n, int slices, u64 *keys, int *row_keys);
 int siso_skinny_slices(const siso_cache *c, long n);
-int siso_skinny_launch(siso_cache *c, const void *queries, long n, int slices, int *row_keys);
+int siso_skinny_launch(siso_cache *c, const void *queries, long n, int slices, u64 *keys, int *row_keys);
 
 // Self-similarity pair search over `count` rows of the cache's element type and dimension with
 // their inverse lengths (counter already zeroed).  The MFMA kernel reads whole tiles: rows and invn
@@ -262,9 +265,11 @@ int siso_pairs_mfma_launch(siso_cache *c, const void *rows, const float *invn, l
                            int *out_pairs, long cap, u64 *counter);
 
 // siso_lookup without the argument checks of the ABI; count_access = hits are references to their
-// centroids (access_count goes up), as in serving; 0 for test lookups
+// centroids (access_count goes up), as in serving; 0 for test lookups.  static_keys: NULL = the phase-1
+// keys go to the cache's own workspace (grown on demand); otherwise they go there (room for static_cap keys:
+// a larger need is an error), and the call allocates nothing and records no timing events.
 int siso_lookup_impl(siso_cache *c, const void *queries, long n, float threshold, int *out_idx, float *out_sim,
-                     unsigned char *out_hit, int count_access);
+                     unsigned char *out_hit, int count_access, u64 *static_keys = nullptr, long static_cap = 0);
 int siso_read_counter(siso_cache *c, int which, u64 *value);
 int siso_second_set(siso_cache *c);    // make sure the second set of arrays exists (allocates once; synchronises then)
 void siso_swap_sets(siso_cache *c);    // the second set becomes the cache, the old arrays the second set  // synchronises

@@ -41,6 +41,7 @@ SYMBOLS = {
     "siso_count": ([_vp], _lg),
     "siso_reserve": ([_vp, _lg], _it),
     "siso_lookup": ([_vp, _vp, _lg, _fl, _vp, _vp, _vp], _it),
+    "siso_lookup_static": ([_vp, _vp, _lg, _fl, _vp, _vp, _vp], _it),
     "siso_update": ([_vp, _vp, _vp, _lg], _it),
     "siso_update_hits": ([_vp, _vp, _vp, _vp, _lg], _it),
     "siso_bad_indices": ([_vp], _lg),
@@ -256,6 +257,19 @@ class SisoCache:
         self._check(_lib.siso_lookup(self._h, _ptr(q), n, float(threshold), _ptr(out_idx), _ptr(out_sim),
                                      _ptr(out_hit)))
         return out_idx, out_sim, out_hit
+
+    def lookup_static(self, queries: torch.Tensor, threshold: float, out_idx: torch.Tensor, out_sim: torch.Tensor,
+                      out_hit: Optional[torch.Tensor] = None) -> None:
+        """``siso_lookup_static``: the lookup that allocates nothing; the caller brings every output."""
+        q = self._rows(queries, "queries")
+        if q.data_ptr() != queries.data_ptr():
+            raise ValueError("queries: must be contiguous (this call does not copy)")
+        n = q.shape[0]
+        self._vec(out_idx, torch.int32, n, "out_idx")
+        self._vec(out_sim, torch.float32, n, "out_sim")
+        self._vec(out_hit, torch.uint8, n, "out_hit")
+        self._check(_lib.siso_lookup_static(self._h, _ptr(q), n, float(threshold), _ptr(out_idx), _ptr(out_sim),
+                                            _ptr(out_hit)))
 
     def update(self, queries: torch.Tensor, idx: torch.Tensor, hit: Optional[torch.Tensor] = None) -> None:
         q = self._rows(queries, "queries")
