@@ -65,6 +65,10 @@ def lib() -> C.CDLL:
         L.oracle_threads.restype = it
         L.oracle_export_meta.argtypes = [vp, vp, vp]
         L.oracle_export_meta.restype = it
+        L.oracle_lookup_multi.argtypes = [vp, vp, lg, vp, it, it, vp, vp, vp, vp]
+        L.oracle_lookup_multi.restype = it
+        L.oracle_lookup_topk.argtypes = [vp, vp, lg, it, vp, vp]
+        L.oracle_lookup_topk.restype = it
         L.oracle_import.argtypes = [vp, vp, vp, vp, vp, vp, lg]
         L.oracle_import.restype = it
         L.oracle_refresh.argtypes = [vp, vp, vp, lg, fl, lg, vp, vp]
@@ -253,6 +257,32 @@ class OracleCache:
         if rc != 0:
             raise RuntimeError(f"oracle_lookup failed ({rc})")
         return idx, sim, hit, second
+
+    def lookup_multi(self, queries: np.ndarray, thetas, count_index: int = -1):
+        """One lookup against several thresholds: ``(idx, sim, hit uint8 [n, m], second)``."""
+        qs = _storage(queries, self.dtype, self.dim)
+        th = np.ascontiguousarray(thetas, dtype=np.float32)
+        n, m = qs.shape[0], th.shape[0]
+        idx = np.empty(n, np.int32)
+        sim = np.empty(n, np.float64)
+        hit = np.zeros((n, m), np.uint8)
+        second = np.empty(n, np.float64)
+        rc = lib().oracle_lookup_multi(self._h, _ptr(qs), n, _ptr(th), m, int(count_index), _ptr(idx), _ptr(sim),
+                                       _ptr(hit), _ptr(second))
+        if rc != 0:
+            raise RuntimeError(f"oracle_lookup_multi failed ({rc})")
+        return idx, sim, hit, second
+
+    def lookup_topk(self, queries: np.ndarray, k: int):
+        """The k closest centroids per query: ``(idx int32 [n, k], sim float64 [n, k])``."""
+        qs = _storage(queries, self.dtype, self.dim)
+        n = qs.shape[0]
+        idx = np.empty((n, int(k)), np.int32)
+        sim = np.empty((n, int(k)), np.float64)
+        rc = lib().oracle_lookup_topk(self._h, _ptr(qs), n, int(k), _ptr(idx), _ptr(sim))
+        if rc != 0:
+            raise RuntimeError(f"oracle_lookup_topk failed ({rc})")
+        return idx, sim
 
     def update(self, queries: np.ndarray, idx: np.ndarray) -> None:
         qs = _storage(queries, self.dtype, self.dim)

@@ -29,6 +29,10 @@
  *     all pairs); connected groups are replaced by their count-weighted mean,
  *     the cluster sizes add up (Algorithm 1, MergeCentroids, cluster_size).
  *
+ *   - variants of the lookup: one lookup judged against several retrieval
+ *     thresholds (the threshold is dynamic, section 3.3; the similarity does not
+ *     depend on it), and the k closest centroids instead of the closest one.
+ *
  * Readings where the paper is silent:
  *   - vectors are taken at storage precision (bf16 or fp32 widened exactly to
  *     double); similarities are true cosines of the stored values;
@@ -251,6 +255,75 @@ int oracle_lookup(oracle_cache *c, const void *queries, long n, float threshold,
         if (out_idx[i] >= 0 && out_sim[i] > (double)threshold && c->access[out_idx[i]] != ORACLE_ACCESS_INF)
             c->access[out_idx[i]] += 1;
     return 0;
+}
+
+/*
+ * One lookup judged against m retrieval thresholds at once (the threshold is dynamic,
+ * section 3.3; the similarity does not depend on it): out_hit[i * m + j] = 1 where the
+ * top-1 similarity of query i exceeds thetas[j], strictly.  count_index = the position of
+ * the threshold whose hits are references to their centroids (access_count goes up as in
+ * oracle_lookup), or -1 if these are test lookups that count nothing.
+ */
+int oracle_lookup_multi(oracle_cache *c, const void *queries, long n, const float *thetas, int m, int count_index,
+                        int *out_idx, double *out_sim, unsigned char *out_hit, double *out_second) {
+    if (!c || m < 0 || count_index >= m || count_index < -1 || (m > 0 && (!thetas || !out_hit))) return -1;
+    int rc = oracle_lookup_rows(c->cent, c->count, c->dim, c->dtype, queries, n, 0.0f, out_idx, out_sim, NULL,
+                                out_second);
+    if (rc != 0) return rc;
+    for (long i = 0; i < n; ++i)
+        for (int j = 0; j < m; ++j) {
+            const int hit = out_idx[i] >= 0 && out_sim[i] > (double)thetas[j];
+            out_hit[(size_t)i * m + j] = (unsigned char)hit;
+            if (hit && j == count_index && c->access[out_idx[i]] != ORACLE_ACCESS_INF) c->access[out_idx[i]] += 1;
+        }
+    return 0;
+}
+
+/*
+ * The k closest centroids of every query instead of the single closest one
+ * (FindClosestCentroid of Algorithm 1 taken k times): out_idx[i * k + r], out_sim[i * k + r],
+ * r = 0 .. k-1, hold the centroid with the (r+1)-th largest cosine similarity to query i and
+ * that similarity; among equal similarities the lower index comes first.  A similarity that
+ * is NaN is never chosen; when fewer than k centroids can be chosen the remaining entries
+ * are (-1, -inf); a query holding a NaN or an infinity gets (-1, NaN) throughout.
+ */
+int oracle_lookup_topk(const oracle_cache *c, const void *queries, long n, int k, int *out_idx, double *out_sim) {
+    if (!c || n < 0 || k < 1 || (n > 0 && (!queries || !out_idx || !out_sim))) return -1;
+    const long K = c->count;
+    const int d = c->dim, dt = c->dtype;
+    double *cn = (double *)malloc(sizeof(double) * (size_t)(K > 0 ? K : 1));
+    if (!cn) return -2;
+    for (long j = 0; j < K; ++j) cn[j] = row_norm(c->cent, dt, j, d);
+    int failed = 0;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (long i = 0; i < n; ++i) {
+        int *oi = out_idx + (size_t)i * k;
+        double *os = out_sim + (size_t)i * k;
+        if (!row_finite(queries, dt, i, d)) {
+            for (int r = 0; r < k; ++r) { oi[r] = -1; os[r] = NAN; }
+            continue;
+        }
+        double *sim = (double *)malloc(sizeof(double) * (size_t)(K > 0 ? K : 1));
+        char *taken = (char *)calloc((size_t)(K > 0 ? K : 1), 1);
+        if (!sim || !taken) { free(sim); free(taken); failed = 1; continue; }
+        const double qn = row_norm(queries, dt, i, d);
+        for (long j = 0; j < K; ++j) sim[j] = cosine(queries, i, qn, c->cent, j, cn[j], dt, d);
+        for (int r = 0; r < k; ++r) {
+            long best = -1;
+            for (long j = 0; j < K; ++j) {
+                if (taken[j] || isnan(sim[j])) continue;
+                if (best < 0 || sim[j] > sim[best]) best = j; /* strict: the lowest index keeps a tie */
+            }
+            if (best < 0) { oi[r] = -1; os[r] = -INFINITY; continue; }
+            taken[best] = 1;
+            oi[r] = (int)best;
+            os[r] = sim[best];
+        }
+        free(sim);
+        free(taken);
+    }
+    free(cn);
+    return failed ? -2 : 0;
 }
 
 /*
