@@ -253,6 +253,26 @@ def main():
                 "algorithmic_bytes": K * d * 2.0 + nb * d * 2.0 + K * 4.0, "kernel_ms": avg_s * 1e3,
                 "launches": launches}
 
+    variants_info = None
+    if not args.no_merge and name in ("c2_mid", "c3_large"):
+        # the lookup variants on the same batch: the whole threshold sweep as one lookup (against one lookup per
+        # threshold), and the 8 closest centroids of every query
+        def timed(fn, reps):
+            fn()
+            torch.cuda.synchronize()
+            t1 = time.perf_counter()
+            for _ in range(reps):
+                fn()
+            torch.cuda.synchronize()
+            return (time.perf_counter() - t1) / reps * 1e3
+        reps = 3 if name == "c3_large" else 20
+        q0 = queries[:nb]
+        sweep3 = [0.75, 0.85, 0.92]
+        variants_info = {"sweep_thresholds": sweep3,
+                         "sweep_one_lookup_multi_ms": timed(lambda: cache.lookup_multi(q0, sweep3), reps),
+                         "sweep_three_lookups_ms": timed(lambda: [cache.lookup(q0, t, idx, sim, hit) for t in sweep3], reps),
+                         "top8_ms": timed(lambda: cache.lookup_topk(q0, 8), reps)}
+
     t2h_info = None
     if not args.no_merge and name == "c2_mid":
         # threshold-to-hit-ratio table over a sample whose similarities spread over the sweep, then the
@@ -317,6 +337,7 @@ def main():
                 "config": {"workload": name, "centroids": K, "dim": d, "batch": nb, "thresholds": thetas,
                            "step": "siso_lookup + siso_update_hits", "hit_rate_last_batch": hit_rate,
                            "offline_merge": merge_info, "t2h": t2h_info, "refresh": refresh_info,
+                           "variants": variants_info,
                            "generate_s": round(gen_s, 1)},
                 "roofline": roof})
     add_measured_peak(siso, out["roofline"])

@@ -109,6 +109,46 @@ int siso_lookup(siso_cache *c, const void *queries, long n, float threshold, int
                 unsigned char *out_hit);
 
 /*
+ * One lookup judged against several retrieval thresholds at once.  The retrieval
+ * threshold is dynamic (section 3.3, section 4.3 "Adjusting theta_R to meet SLO") and
+ * the similarity does not depend on it, so a sweep costs one similarity pass and m
+ * comparisons per query instead of m lookups.
+ *   thetas:      HOST pointer, m thresholds, 1 <= m <= 32 (passed on as kernel
+ *                arguments: nothing is allocated or copied).
+ *   count_index: position of the threshold whose hits are references to their
+ *                centroids (access_count, as in siso_lookup), or -1: test lookups
+ *                that count nothing.
+ *   out_idx, out_sim: as in siso_lookup.
+ *   out_hit:     device pointer, [n][m] bytes: out_hit[i * m + j] = 1 where out_sim[i]
+ *                exceeds thetas[j], strictly.
+ * Asynchronous like siso_lookup (same workspace).
+ */
+int siso_lookup_multi(siso_cache *c, const void *queries, long n, const float *thetas, int m, int count_index,
+                      int *out_idx, float *out_sim, unsigned char *out_hit);
+
+/*
+ * The k closest centroids of every query: FindClosestCentroid (Algorithm 1) taken k
+ * times, for callers that re-rank or vote among several cached answers.
+ *   k:        1 <= k <= 32.
+ *   out_idx:  device pointer, [n][k] ints: out_idx[i * k + r] = the centroid with the
+ *             (r+1)-th largest cosine similarity to query i; among equal
+ *             similarities the lower index comes first.
+ *   out_sim:  device pointer, [n][k] floats: those similarities, non-increasing in r.
+ * When fewer than k centroids can be chosen (a small cache, centroids holding a NaN)
+ * the remaining entries are (-1, -inf); a query holding a NaN or an infinity gets
+ * (-1, NaN) throughout; a query without length has similarity 0 to every centroid.
+ * No threshold is involved and no access is counted.
+ * bf16 caches whose dimension is a multiple of 64 take two passes of the fused MFMA
+ * kernel (the k-th largest of the per-slice maxima of the first pass bounds the k-th
+ * best similarity from below; the second pass lists the few rows that reach the bound;
+ * their cosines are then recomputed and ranked); other caches, caches of fewer than
+ * 512 * k centroids and queries with more than 128 rows at the bound (many exact
+ * duplicates) are scanned row by row.  Asynchronous; grows a workspace of the cache
+ * (about 530 bytes per query) the first time a larger n is seen, which allocates.
+ */
+int siso_lookup_topk(siso_cache *c, const void *queries, long n, int k, int *out_idx, float *out_sim);
+
+/*
  * siso_lookup for callers that cannot allocate device memory: code under HIP graph
  * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments,
  * same kernels and bit-identical results, but the keys of the first phase go to a

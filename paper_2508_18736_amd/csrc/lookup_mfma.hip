@@ -296,10 +296,15 @@ __device__ __forceinline__ void pipe_reduce_keys(float (&bv)[WQ], unsigned (&bb)
     }
 }
 
-template <class Cfg>
+// COLLECT: instead of keeping the running maximum, every product that reaches the bound of its query is
+// listed (second pass of a top-k lookup): tau[q] = the bound of query q in the units of the products
+// (<q, c> / |c|), cand[q * cand_cap + i] = the i-th listed row, cand_cnt[q] = how many rows reached the bound
+// (also beyond cand_cap).  A row is listed exactly once: every product is formed by one lane.
+template <class Cfg, bool COLLECT = false>
 __global__ __launch_bounds__(Cfg::NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void k_lookup_pipe(
     const bf16_t *__restrict__ Q, const bf16_t *__restrict__ C, const float *__restrict__ invn, long n, long K, int d,
-    int tiles_per_slice, int slices, int nqt, int qb, u64 *__restrict__ keys) {
+    int tiles_per_slice, int slices, int nqt, int qb, u64 *__restrict__ keys, const float *__restrict__ tau,
+    int *__restrict__ cand, int *__restrict__ cand_cnt, int cand_cap) {
     constexpr int WC = Cfg::WC, WQ = Cfg::WQ, NWC = Cfg::NWC, BC = Cfg::BC, BQ = Cfg::BQ, NT = Cfg::NT, NW = Cfg::NW,
                   STAGE = Cfg::STAGE, NLA = Cfg::NLA, NLB = Cfg::NLB, NL = Cfg::NL, NSTAGE = Cfg::NSTAGE, BK = Cfg::BK,
                   RB = Cfg::RB, CPR = Cfg::CPR, RPI = Cfg::RPI, RP = Cfg::RP, KK = Cfg::KK, SUB = 32 * Cfg::RB;
@@ -361,6 +366,14 @@ __global__ __launch_bounds__(Cfg::NT) __attribute__((amdgpu_waves_per_eu(2, 2)))
     }
     Acc<false, WC, WQ> acc;  // every tile starts from a zero operand, so nothing to clear
     acc.reserve();
+    float tq[WQ];  // COLLECT: the bounds of this lane's query columns (nothing reaches +inf: rows past the batch)
+    if constexpr (COLLECT) {
+#pragma unroll
+        for (int b = 0; b < WQ; ++b) {
+            const long q = q0 + (wq * WQ + b) * 32 + l32;
+            tq[b] = q < n ? tau[q] : INFINITY;
+        }
+    }
 
     // slab t lives in stage t % NSTAGE; (ld_ct, ld_ks, ld_stage) name the slab the next issue fetches.
     // With slab 0 of a tile travel the inverse lengths of the tile's centroids (the rows past the
@@ -484,7 +497,24 @@ __global__ __launch_bounds__(Cfg::NT) __attribute__((amdgpu_waves_per_eu(2, 2)))
                 static_for<0, WQ>([&](auto ib) {
                     constexpr int B = decltype(ib)::value;
                     float m = -INFINITY;
-                    if constexpr (Cfg::ROWS) {
+                    if constexpr (COLLECT) {
+                        static_for<0, 16>([&](auto ii) {
+                            constexpr int I = decltype(ii)::value;
+                            m = fmaxf(m, acc.template get<A, B, I>() * w[I >> 2][I & 3]);
+                        });
+                        if (__ballot(m >= tq[B]) != 0) {
+                            const long q = q0 + (wq * WQ + B) * 32 + l32;
+                            const int row0 = (int)(c0 + rb) + 4 * h;  // register I holds row row0 + 8 * (I / 4) + I % 4
+                            static_for<0, 16>([&](auto ii) {
+                                constexpr int I = decltype(ii)::value;
+                                // (the weights of rows past the end are NaN: never listed)
+                                if (acc.template get<A, B, I>() * w[I >> 2][I & 3] >= tq[B]) {
+                                    const int slot = atomicAdd(cand_cnt + q, 1);
+                                    if (slot < cand_cap) cand[(size_t)q * cand_cap + slot] = row0 + 8 * (I >> 2) + (I & 3);
+                                }
+                            });
+                        }
+                    } else if constexpr (Cfg::ROWS) {
                         // the rows of a lane ascend with the register number, the tiles of a workgroup with
                         // time: ">" keeps the lowest row among equal values
                         unsigned mi = 0;
@@ -517,8 +547,10 @@ __global__ __launch_bounds__(Cfg::NT) __attribute__((amdgpu_waves_per_eu(2, 2)))
         }
         sto = sto_next;
     }
-    __syncthreads();
-    pipe_reduce_keys<WQ, NWC, BQ, NT, Cfg::ROWS>(bv, bb, smem, wc, wq, h, l32, tid, q0, n, slices, s, keys);
+    if constexpr (!COLLECT) {
+        __syncthreads();
+        pipe_reduce_keys<WQ, NWC, BQ, NT, Cfg::ROWS>(bv, bb, smem, wc, wq, h, l32, tid, q0, n, slices, s, keys);
+    }
 }
 
 // ----------------------------------------------------------------------------
@@ -1069,6 +1101,11 @@ static bool pipe_plan(const siso_cache *c, long n, int cfg, long want_wgs, PipeP
         const long mall_tps = 8192 / c->dim > 2 ? 8192 / c->dim : 2;
         if (nqt > 1 && tps > mall_tps) tps = mall_tps;
     }
+    if (c->plan_min_slices > 0) {  // a top-k lookup wants many slices: each contributes one row to its bound
+        const long want_s = c->plan_min_slices < ct ? c->plan_min_slices : ct;
+        const long t2 = ct / want_s > 1 ? ct / want_s : 1;
+        if (tps > t2) tps = t2;
+    }
     if (tps > ct) tps = ct;
     // query tiles per unit: 8 when there are that many (a centroid tile fetched into an XCD's L2 then
     // serves 8 workgroups, and 8 query tiles are about what stays resident in a 4 MB L2), fewer when the
@@ -1116,8 +1153,25 @@ static int launch_cfg(siso_cache *c, const void *queries, long n, const PipePlan
     }
     hipLaunchKernelGGL((k_lookup_pipe<Cfg>), dim3((unsigned)p.grid), dim3(Cfg::NT), Cfg::LDS_BYTES,
                        c->stream, (const bf16_t *)queries, (const bf16_t *)c->cent, c->invn, n, c->count, c->dim,
-                       p.tiles_per_slice, p.slices, p.nqt, p.qb, keys);
+                       p.tiles_per_slice, p.slices, p.nqt, p.qb, keys, (const float *)nullptr, (int *)nullptr,
+                       (int *)nullptr, 0);
     return siso_check_hip(c, hipGetLastError(), "k_lookup_pipe");
+}
+
+template <class Cfg>
+static int launch_collect(siso_cache *c, const void *queries, long n, const PipePlan &p, const float *tau, int *cand,
+                          int *cnt, int cap) {
+    static bool attr_done = false;
+    if (!attr_done) {
+        hipError_t e = hipFuncSetAttribute((const void *)k_lookup_pipe<Cfg, true>,
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, Cfg::LDS_BYTES);
+        if (e != hipSuccess) return siso_check_hip(c, e, "hipFuncSetAttribute(k_lookup_pipe, collect)");
+        attr_done = true;
+    }
+    hipLaunchKernelGGL((k_lookup_pipe<Cfg, true>), dim3((unsigned)p.grid), dim3(Cfg::NT), Cfg::LDS_BYTES,
+                       c->stream, (const bf16_t *)queries, (const bf16_t *)c->cent, c->invn, n, c->count, c->dim,
+                       p.tiles_per_slice, p.slices, p.nqt, p.qb, (u64 *)nullptr, tau, cand, cnt, cap);
+    return siso_check_hip(c, hipGetLastError(), "k_lookup_pipe (collect)");
 }
 
 static int launch_wide(siso_cache *c, const void *queries, long n, const PipePlan &p, u64 *keys) {
@@ -1172,6 +1226,34 @@ int siso_skinny_launch(siso_cache *c, const void *queries, long n, int slices, u
     if (!skinny_plan(c, n, &p) || p.slices != slices) return siso_fail(c, SISO_EINVAL, "skinny lookup: plan mismatch");
     *row_keys = keys_carry_rows(p);
     return pipe_launch(c, queries, n, p, keys);
+}
+
+// ----------------------------------------------------------------------------
+// the two passes of a top-k lookup (the caller has set c->plan_min_slices)
+// ----------------------------------------------------------------------------
+int siso_topk_mfma_slices(const siso_cache *c, long n) {
+    PipePlan p;
+    return mfma_plan(c, n, &p) ? p.slices : 0;
+}
+
+int siso_topk_mfma_pass1(siso_cache *c, const void *queries, long n, int slices, u64 *keys, int *row_keys) {
+    PipePlan p;
+    if (!mfma_plan(c, n, &p) || p.slices != slices) return siso_fail(c, SISO_EINVAL, "top-k lookup: plan mismatch");
+    *row_keys = keys_carry_rows(p);
+    return pipe_launch(c, queries, n, p, keys);
+}
+
+int siso_topk_mfma_collect(siso_cache *c, const void *queries, long n, int slices, const float *tau, int *cand,
+                           int *cnt, int cap) {
+    PipePlan p;
+    if (!mfma_plan(c, n, &p) || p.slices != slices) return siso_fail(c, SISO_EINVAL, "top-k lookup: plan mismatch");
+    if (((uintptr_t)queries & 15) != 0) return siso_fail(c, SISO_EINVAL, "bf16 lookup: queries must be 16-byte aligned");
+    switch (p.cfg) {
+        case 2: return launch_collect<PipeMid>(c, queries, n, p, tau, cand, cnt, cap);
+        case 3: return launch_collect<PipeSmall>(c, queries, n, p, tau, cand, cnt, cap);
+        case 4: return launch_collect<PipeLarge32>(c, queries, n, p, tau, cand, cnt, cap);
+        default: return launch_collect<PipeLarge>(c, queries, n, p, tau, cand, cnt, cap);  // also for the wide kernel's plan: same tiles
+    }
 }
 
 // ----------------------------------------------------------------------------

@@ -260,7 +260,7 @@ static int refresh_impl(siso_cache *c, const void *repo, const float *repo_size,
             return siso_fail(c, SISO_EINVAL, "siso_refresh: %llu repository rows are not finite or have no positive cluster size", bad);
 
         // every repository row against the cache (test lookups: no references are counted)
-        rc = siso_lookup_impl(c, d_rows.p, r, theta_c, d_idx.as<int>(), d_sim.as<float>(), nullptr, 0);
+        rc = siso_lookup_impl(c, d_rows.p, r, &theta_c, 1, -1, d_idx.as<int>(), d_sim.as<float>(), nullptr);
         if (rc != SISO_OK) return rc;
 
         // repository rows among themselves: the pairs above the threshold, then their cosines

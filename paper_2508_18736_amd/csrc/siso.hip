@@ -130,46 +130,21 @@ __global__ __launch_bounds__(256) void k_import_rows(const T *__restrict__ src, 
     }
 }
 
-// 16-byte chunk dot products for the finalize kernel
-typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
-__device__ __forceinline__ float chunk_dot(const float *a, const float *b) {
-    const float4 x = *(const float4 *)a, y = *(const float4 *)b;
-    return x.x * y.x + x.y * y.y + x.z * y.z + x.w * y.w;
-}
-__device__ __forceinline__ float chunk_dot(const bf16_t *a, const bf16_t *b) {
-    const u32x4_t x = *(const u32x4_t *)a, y = *(const u32x4_t *)b;
-    float s = 0.f;
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        s += __uint_as_float(x[i] << 16) * __uint_as_float(y[i] << 16);
-        s += __uint_as_float(x[i] & 0xFFFF0000u) * __uint_as_float(y[i] & 0xFFFF0000u);
-    }
-    return s;
-}
-
-// the same sums from chunks that are already in registers
-__device__ __forceinline__ float chunk_dot(u32x4_t x, u32x4_t y, float) {
-    return __uint_as_float(x[0]) * __uint_as_float(y[0]) + __uint_as_float(x[1]) * __uint_as_float(y[1]) +
-           __uint_as_float(x[2]) * __uint_as_float(y[2]) + __uint_as_float(x[3]) * __uint_as_float(y[3]);
-}
-__device__ __forceinline__ float chunk_dot(u32x4_t x, u32x4_t y, bf16_t) {
-    float s = 0.f;
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        s += __uint_as_float(x[i] << 16) * __uint_as_float(y[i] << 16);
-        s += __uint_as_float(x[i] & 0xFFFF0000u) * __uint_as_float(y[i] & 0xFFFF0000u);
-    }
-    return s;
-}
-
 // Finalize: per query, max over the slice keys; then either the key names the row (nothing to read), or it
 // names a group of four consecutive rows: their exact cosines (one wave per row; strict ">" in ascending
 // row order, so the lowest index keeps a tie); then the strict threshold test.  One 256-thread block
 // per query.  `vec` = rows are 16-byte aligned and a whole number of 16-byte chunks.
+// The thresholds of a call travel as kernel arguments (nothing to allocate or copy): out_hit[q * m + j] = 1 where
+// the similarity of query q exceeds v[j]; the hits at v[count_at] are the references that access counts.
+struct ThetaList {
+    float v[SISO_MULTI_MAX];
+    int m, count_at;
+};
+
 template <typename T>
 __global__ __launch_bounds__(256) void k_lookup_finalize(const T *__restrict__ Q, const T *__restrict__ cent,
                                                           const float *__restrict__ invn, const u64 *__restrict__ keys,
-                                                          long n, long K, int d, int slices, float threshold, int vec,
+                                                          long n, long K, int d, int slices, ThetaList thetas, int vec,
                                                           int key_kind, int *out_idx, float *out_sim,
                                                           unsigned char *out_hit, unsigned *access) {
     constexpr int EPC = 16 / (int)sizeof(T);  // elements per 16-byte chunk
@@ -266,10 +241,12 @@ __global__ __launch_bounds__(256) void k_lookup_finalize(const T *__restrict__ Q
         if (!finite_q) best_s = __uint_as_float(0x7FC00000u);
         out_idx[q] = (int)best_i;
         out_sim[q] = best_s;
-        const bool hit = best_i >= 0 && best_s > threshold;
-        if (out_hit) out_hit[q] = hit ? 1 : 0;
-        // a hit is a reference to its centroid (access_count of Algorithm 1); infinity stays infinity
-        if (hit && access && access[best_i] != SISO_ACCESS_INF) atomicAdd(&access[best_i], 1u);
+        for (int j = 0; j < thetas.m; ++j) {
+            const bool hit = best_i >= 0 && best_s > thetas.v[j];
+            if (out_hit) out_hit[(size_t)q * thetas.m + j] = hit ? 1 : 0;
+            // a hit is a reference to its centroid (access_count of Algorithm 1); infinity stays infinity
+            if (hit && j == thetas.count_at && access && access[best_i] != SISO_ACCESS_INF) atomicAdd(&access[best_i], 1u);
+        }
     }
 }
 
@@ -901,6 +878,8 @@ static int ensure_workspace(siso_cache *c, long n, int slices) {
     return SISO_OK;
 }
 
+int siso_ensure_keys(siso_cache *c, long need) { return ensure_workspace(c, need, 1); }
+
 int siso_second_set(siso_cache *c) {
     if (c->cent_b) return SISO_OK;
     const size_t cells = (size_t)c->capacity * c->dim;
@@ -1005,6 +984,9 @@ extern "C" void siso_destroy(siso_cache *c) {
     if (c->locality_b) (void)hipFree(c->locality_b);
     if (c->access_b) (void)hipFree(c->access_b);
     if (c->keys) (void)hipFree(c->keys);
+    if (c->topk_tau) (void)hipFree(c->topk_tau);
+    if (c->topk_cnt) (void)hipFree(c->topk_cnt);
+    if (c->topk_cand) (void)hipFree(c->topk_cand);
     if (c->counters) (void)hipFree(c->counters);
     if (c->host_pin) (void)hipHostFree(c->host_pin);
     if (c->prof_ev) {
@@ -1101,7 +1083,7 @@ extern "C" int siso_lookup_static(siso_cache *c, const void *queries, long n, fl
     if (n < 0 || (n > 0 && (!queries || !out_idx || !out_sim)))
         return siso_fail(c, SISO_EINVAL, "siso_lookup_static: bad arguments");
     if (!c->static_keys) return siso_fail(c, SISO_EHIP, "siso_lookup_static: the static workspace was not found on device %d", c->device);
-    return siso_lookup_impl(c, queries, n, threshold, out_idx, out_sim, out_hit, 1, c->static_keys, SISO_STATIC_KEYS);
+    return siso_lookup_impl(c, queries, n, &threshold, 1, 0, out_idx, out_sim, out_hit, c->static_keys, SISO_STATIC_KEYS);
 }
 
 // keys a lookup of n queries writes in its first phase, for the kernel the library would choose
@@ -1161,11 +1143,20 @@ extern "C" int siso_lookup(siso_cache *c, const void *queries, long n, float thr
     if (!c) return SISO_EINVAL;
     if (n < 0 || (n > 0 && (!queries || !out_idx || !out_sim)))
         return siso_fail(c, SISO_EINVAL, "siso_lookup: bad arguments");
-    return siso_lookup_impl(c, queries, n, threshold, out_idx, out_sim, out_hit, 1);
+    return siso_lookup_impl(c, queries, n, &threshold, 1, 0, out_idx, out_sim, out_hit);
 }
 
-int siso_lookup_impl(siso_cache *c, const void *queries, long n, float threshold, int *out_idx, float *out_sim,
-                     unsigned char *out_hit, int count_access, u64 *static_keys, long static_cap) {
+extern "C" int siso_lookup_multi(siso_cache *c, const void *queries, long n, const float *thetas, int m, int count_index,
+                                 int *out_idx, float *out_sim, unsigned char *out_hit) {
+    if (!c) return SISO_EINVAL;
+    if (n < 0 || m < 1 || m > SISO_MULTI_MAX || !thetas || count_index < -1 || count_index >= m ||
+        (n > 0 && (!queries || !out_idx || !out_sim || !out_hit)))
+        return siso_fail(c, SISO_EINVAL, "siso_lookup_multi: bad arguments (1 to %d thresholds)", SISO_MULTI_MAX);
+    return siso_lookup_impl(c, queries, n, thetas, m, count_index, out_idx, out_sim, out_hit);
+}
+
+int siso_lookup_impl(siso_cache *c, const void *queries, long n, const float *thetas, int m, int count_index,
+                     int *out_idx, float *out_sim, unsigned char *out_hit, u64 *static_keys, long static_cap) {
     if (n == 0) return SISO_OK;
     if (n > 2147483647L / 4) return siso_fail(c, SISO_EINVAL, "siso_lookup: batch of %ld is too large", n);
     int slices = 1;
@@ -1193,6 +1184,10 @@ int siso_lookup_impl(siso_cache *c, const void *queries, long n, float threshold
     u64 *keys = static_keys ? static_keys : c->keys;
     const unsigned qblocks = (unsigned)n;
     const int vec = ((c->dim * elem_bytes(c->dtype)) % 16 == 0 && ((uintptr_t)queries & 15) == 0) ? 1 : 0;
+    ThetaList tl;
+    tl.m = m;
+    tl.count_at = count_index;
+    for (int j = 0; j < SISO_MULTI_MAX; ++j) tl.v[j] = j < m ? thetas[j] : 0.f;
     int row_keys = SISO_KEY_ROWS;  // what the keys of the chosen kernel carry: the winning row, or its group of four rows
     if (c->count > 0) {
         if (!static_keys) siso_prof_begin(c);
@@ -1206,12 +1201,12 @@ int siso_lookup_impl(siso_cache *c, const void *queries, long n, float threshold
     }
     if (c->dtype == SISO_F32)
         hipLaunchKernelGGL(k_lookup_finalize<float>, dim3(qblocks), dim3(256), 0, c->stream, (const float *)queries,
-                           (const float *)c->cent, c->invn, keys, n, c->count, c->dim, slices, threshold,
-                           vec, row_keys, out_idx, out_sim, out_hit, count_access ? c->access : nullptr);
+                           (const float *)c->cent, c->invn, keys, n, c->count, c->dim, slices, tl,
+                           vec, row_keys, out_idx, out_sim, out_hit, count_index >= 0 ? c->access : nullptr);
     else
         hipLaunchKernelGGL(k_lookup_finalize<bf16_t>, dim3(qblocks), dim3(256), 0, c->stream, (const bf16_t *)queries,
-                           (const bf16_t *)c->cent, c->invn, keys, n, c->count, c->dim, slices, threshold,
-                           vec, row_keys, out_idx, out_sim, out_hit, count_access ? c->access : nullptr);
+                           (const bf16_t *)c->cent, c->invn, keys, n, c->count, c->dim, slices, tl,
+                           vec, row_keys, out_idx, out_sim, out_hit, count_index >= 0 ? c->access : nullptr);
     HIP_TRY(c, hipGetLastError());
     return SISO_OK;
 }
@@ -1499,7 +1494,8 @@ extern "C" int siso_t2h(siso_cache *c, const void *queries, long n, const float 
     hipError_t e = hipMemcpyAsync(d_th, thetas, (size_t)m * sizeof(float), hipMemcpyHostToDevice, c->stream);
     if (e == hipSuccess) e = hipMemsetAsync(d_hits, 0, (size_t)m * sizeof(u64), c->stream);
     if (e != hipSuccess) rc = siso_check_hip(c, e, "siso_t2h: set-up");
-    if (rc == SISO_OK) rc = siso_lookup_impl(c, queries, n, 0.f, idx, sim, nullptr, 0);  // test lookups are no references
+    const float no_theta = 0.f;
+    if (rc == SISO_OK) rc = siso_lookup_impl(c, queries, n, &no_theta, 1, -1, idx, sim, nullptr);  // test lookups are no references
     u64 host_hits[SISO_T2H_MAX];
     if (rc == SISO_OK) {
         hipLaunchKernelGGL(k_t2h_count, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, c->stream, sim, n, d_th, m, d_hits);

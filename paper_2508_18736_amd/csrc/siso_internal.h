@@ -27,6 +27,7 @@ typedef unsigned short bf16_t;  // bfloat16 bit pattern
 enum { SISO_KEY_ROWS = 1, SISO_KEY_GROUPS4 = 3 };
 #define SISO_ACCESS_INF 0xFFFFFFFFu
 #define SISO_MAX_DIM 4096
+#define SISO_MULTI_MAX 32  // thresholds one lookup can be judged against
 #define SISO_PAD_ROWS 256  // readable rows past the capacity of the stored-centroid array
 
 struct siso_cache {
@@ -67,6 +68,14 @@ struct siso_cache {
 
     u64 *counters;  // device: [0] bad update indices, [1] merge pair count, [2] scratch, [3] scratch
     u64 *host_pin;  // pinned host mirror for counter read-back (4 entries)
+
+    // top-k lookups: per query the bound, the number of listed rows, a flag "scan this query row by row" and
+    // the listed rows ([topk_cap] floats / ints / ints, [topk_cap][SISO_TOPK_CAND] ints), grown on demand
+    float *topk_tau;
+    int *topk_cnt;
+    int *topk_cand;
+    long topk_cap;
+    int plan_min_slices;  // > 0 while a top-k lookup plans its passes: at least this many slices (if the tiles allow)
 
     // tuning knobs (siso_set_option); 0 = library default
     int opt_mfma_config;
@@ -128,6 +137,38 @@ __device__ __forceinline__ float wave_sum(float v) {
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off);
     return v;
+}
+
+// 16-byte chunk dot products (finalize, top-k re-ranking)
+typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ float chunk_dot(const float *a, const float *b) {
+    const float4 x = *(const float4 *)a, y = *(const float4 *)b;
+    return x.x * y.x + x.y * y.y + x.z * y.z + x.w * y.w;
+}
+__device__ __forceinline__ float chunk_dot(const bf16_t *a, const bf16_t *b) {
+    const u32x4_t x = *(const u32x4_t *)a, y = *(const u32x4_t *)b;
+    float s = 0.f;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        s += __uint_as_float(x[i] << 16) * __uint_as_float(y[i] << 16);
+        s += __uint_as_float(x[i] & 0xFFFF0000u) * __uint_as_float(y[i] & 0xFFFF0000u);
+    }
+    return s;
+}
+
+// the same sums from chunks that are already in registers
+__device__ __forceinline__ float chunk_dot(u32x4_t x, u32x4_t y, float) {
+    return __uint_as_float(x[0]) * __uint_as_float(y[0]) + __uint_as_float(x[1]) * __uint_as_float(y[1]) +
+           __uint_as_float(x[2]) * __uint_as_float(y[2]) + __uint_as_float(x[3]) * __uint_as_float(y[3]);
+}
+__device__ __forceinline__ float chunk_dot(u32x4_t x, u32x4_t y, bf16_t) {
+    float s = 0.f;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        s += __uint_as_float(x[i] << 16) * __uint_as_float(y[i] << 16);
+        s += __uint_as_float(x[i] & 0xFFFF0000u) * __uint_as_float(y[i] & 0xFFFF0000u);
+    }
+    return s;
 }
 
 // Wave-ballot compaction of (i, j) pairs into out[cap][2]; every lane of the wave
@@ -255,6 +296,17 @@ int siso_mfma_launch(siso_cache *c, const void *queries, long n, int slices, u64
 int siso_skinny_slices(const siso_cache *c, long n);
 int siso_skinny_launch(siso_cache *c, const void *queries, long n, int slices, u64 *keys, int *row_keys);
 
+// Top-k lookups on the MFMA kernels: pass 1 = the phase-1 keys of a lookup planned with c->plan_min_slices;
+// pass 2 lists, per query q, the rows whose scaled product <q, c> / |c| reaches tau[q] (cand[q * cap + i],
+// i < min(cnt[q], cap); cnt counts all of them; cnt must be zero before).  Both passes sum every product in
+// the same order, so a row that set a key in pass 1 compares equal to it in pass 2.
+#define SISO_TOPK_MAX 32
+#define SISO_TOPK_CAND 128
+int siso_topk_mfma_slices(const siso_cache *c, long n);  // slices of the plan (0 = these kernels cannot serve the cache)
+int siso_topk_mfma_pass1(siso_cache *c, const void *queries, long n, int slices, u64 *keys, int *row_keys);
+int siso_topk_mfma_collect(siso_cache *c, const void *queries, long n, int slices, const float *tau, int *cand,
+                           int *cnt, int cap);
+
 // Self-similarity pair search over `count` rows of the cache's element type and dimension with
 // their inverse lengths (counter already zeroed).  The MFMA kernel reads whole tiles: rows and invn
 // must be readable for SISO_PAD_ROWS entries past count, the invn entries there holding NaN.
@@ -264,12 +316,15 @@ int siso_pairs_mfma_supported(const siso_cache *c, long count);
 int siso_pairs_mfma_launch(siso_cache *c, const void *rows, const float *invn, long count, float threshold,
                            int *out_pairs, long cap, u64 *counter);
 
-// siso_lookup without the argument checks of the ABI; count_access = hits are references to their
-// centroids (access_count goes up), as in serving; 0 for test lookups.  static_keys: NULL = the phase-1
+// siso_lookup without the argument checks of the ABI, against m thresholds (host pointer, 1 <= m <=
+// SISO_MULTI_MAX; out_hit is [n][m] or NULL); the hits at thetas[count_index] are references to their
+// centroids (access_count goes up), as in serving; count_index = -1 for test lookups.  static_keys: NULL = the phase-1
 // keys go to the cache's own workspace (grown on demand); otherwise they go there (room for static_cap keys:
 // a larger need is an error), and the call allocates nothing and records no timing events.
-int siso_lookup_impl(siso_cache *c, const void *queries, long n, float threshold, int *out_idx, float *out_sim,
-                     unsigned char *out_hit, int count_access, u64 *static_keys = nullptr, long static_cap = 0);
+int siso_lookup_impl(siso_cache *c, const void *queries, long n, const float *thetas, int m, int count_index,
+                     int *out_idx, float *out_sim, unsigned char *out_hit, u64 *static_keys = nullptr,
+                     long static_cap = 0);
 int siso_read_counter(siso_cache *c, int which, u64 *value);
+int siso_ensure_keys(siso_cache *c, long need);  // room for `need` phase-1 keys in c->keys (may synchronise and allocate)
 int siso_second_set(siso_cache *c);    // make sure the second set of arrays exists (allocates once; synchronises then)
 void siso_swap_sets(siso_cache *c);    // the second set becomes the cache, the old arrays the second set  // synchronises

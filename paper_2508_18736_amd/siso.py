@@ -41,6 +41,8 @@ SYMBOLS = {
     "siso_count": ([_vp], _lg),
     "siso_reserve": ([_vp, _lg], _it),
     "siso_lookup": ([_vp, _vp, _lg, _fl, _vp, _vp, _vp], _it),
+    "siso_lookup_multi": ([_vp, _vp, _lg, _vp, _it, _it, _vp, _vp, _vp], _it),
+    "siso_lookup_topk": ([_vp, _vp, _lg, _it, _vp, _vp], _it),
     "siso_lookup_static": ([_vp, _vp, _lg, _fl, _vp, _vp, _vp], _it),
     "siso_update": ([_vp, _vp, _vp, _lg], _it),
     "siso_update_hits": ([_vp, _vp, _vp, _vp, _lg], _it),
@@ -257,6 +259,29 @@ class SisoCache:
         self._check(_lib.siso_lookup(self._h, _ptr(q), n, float(threshold), _ptr(out_idx), _ptr(out_sim),
                                      _ptr(out_hit)))
         return out_idx, out_sim, out_hit
+
+    def lookup_multi(self, queries: torch.Tensor, thetas, count_index: int = -1
+                     ) -> Tuple[torch.Tensor, torch.Tensor, torch.Tensor]:
+        """One lookup against several thresholds (host values): ``(idx [n], sim [n], hit uint8 [n, m])``."""
+        import numpy as np
+        q = self._rows(queries, "queries")
+        n = q.shape[0]
+        th = np.ascontiguousarray(thetas, dtype=np.float32)
+        idx = torch.empty(n, dtype=torch.int32, device=self.device)
+        sim = torch.empty(n, dtype=torch.float32, device=self.device)
+        hit = torch.empty((n, th.shape[0]), dtype=torch.uint8, device=self.device)
+        self._check(_lib.siso_lookup_multi(self._h, _ptr(q), n, th.ctypes.data_as(_vp), th.shape[0], int(count_index),
+                                           _ptr(idx), _ptr(sim), _ptr(hit)))
+        return idx, sim, hit
+
+    def lookup_topk(self, queries: torch.Tensor, k: int) -> Tuple[torch.Tensor, torch.Tensor]:
+        """The k closest centroids per query: ``(idx int32 [n, k], sim float32 [n, k])``."""
+        q = self._rows(queries, "queries")
+        n = q.shape[0]
+        idx = torch.empty((n, max(int(k), 1)), dtype=torch.int32, device=self.device)
+        sim = torch.empty((n, max(int(k), 1)), dtype=torch.float32, device=self.device)
+        self._check(_lib.siso_lookup_topk(self._h, _ptr(q), n, int(k), _ptr(idx), _ptr(sim)))
+        return idx, sim
 
     def lookup_static(self, queries: torch.Tensor, threshold: float, out_idx: torch.Tensor, out_sim: torch.Tensor,
                       out_hit: Optional[torch.Tensor] = None) -> None:
