@@ -12,7 +12,7 @@
 //               centroid rows 8*(i/4) + 4*(l/32) + i%4.
 // So the maximum over centroids is taken inside a lane (over its registers and
 // over all tiles the workgroup walks through); lanes l and l^32 are combined
-// once at the end, and the waves that share a query column meet in LDS.
+// once at the end (v_permlane32_swap), and the waves that share a query column meet in LDS.
 //
 // A workgroup owns one tile of BQ queries and walks through `tiles_per_slice`
 // tiles of BC centroids, as one continuous stream of slabs of 64 elements of the
@@ -265,14 +265,22 @@ __device__ __forceinline__ void block_max(const AccT &acc, const f32x4 (&w)[4], 
     });
 }
 
+// The value lane l ^ 32 holds: v_permlane32_swap exchanges the upper half of its first register with the
+// lower half of its second; given the same value twice, the first then holds the lower half in both halves
+// and the second the upper half in both.  One instruction, no LDS crossbar.
+__device__ __forceinline__ unsigned other_half(unsigned v) {
+    const auto r = __builtin_amdgcn_permlane32_swap(v, v, false, false);
+    return (threadIdx.x & 32) ? r[0] : r[1];
+}
+
 template <int WQ, int NWC, int BQ, int NT, bool ROWS = false>  // ROWS: the keys may be read within the launch
 __device__ __forceinline__ void pipe_reduce_keys(float (&bv)[WQ], unsigned (&bb)[WQ], unsigned char *red, int wc, int wq,
                                                  int h, int l32, int tid, long q0, long n, int slices, int s,
                                                  u64 *__restrict__ keys) {
 #pragma unroll
     for (int b = 0; b < WQ; ++b) {
-        const float ov = __shfl_xor(bv[b], 32);
-        const unsigned ob = __shfl_xor(bb[b], 32);
+        const float ov = __uint_as_float(other_half(__float_as_uint(bv[b])));
+        const unsigned ob = other_half(bb[b]);
         pipe_merge(bv[b], bb[b], ov, ob);
     }
     float *red_v = (float *)red;  // [NWC][BQ]
