@@ -69,6 +69,10 @@ def lib() -> C.CDLL:
         L.oracle_lookup_multi.restype = it
         L.oracle_lookup_topk.argtypes = [vp, vp, lg, it, vp, vp]
         L.oracle_lookup_topk.restype = it
+        L.oracle_fp8_quantize.argtypes = [vp, it, lg, it, vp, vp]
+        L.oracle_fp8_quantize.restype = it
+        L.oracle_fp8_lookup_rows.argtypes = [vp, vp, lg, it, vp, it, lg, fl, vp, vp, vp, vp]
+        L.oracle_fp8_lookup_rows.restype = it
         L.oracle_import.argtypes = [vp, vp, vp, vp, vp, vp, lg]
         L.oracle_import.restype = it
         L.oracle_refresh.argtypes = [vp, vp, vp, lg, fl, lg, vp, vp]
@@ -121,6 +125,38 @@ def lookup_rows(centroids: np.ndarray, queries: np.ndarray, threshold: float, dt
                                   float(threshold), _ptr(idx), _ptr(sim), _ptr(hit), _ptr(second))
     if rc != 0:
         raise RuntimeError(f"oracle_lookup_rows failed ({rc})")
+    return idx, sim, hit, second
+
+
+def fp8_quantize(rows: np.ndarray, dtype: str):
+    """Rows of the input type -> ``(codes uint8 [n, dim], scales float32 [n])`` in the 8-bit storage format."""
+    x = _storage(rows, dtype, rows.shape[1])
+    n, dim = x.shape
+    codes = np.zeros((n, dim), np.uint8)
+    scales = np.zeros(n, np.float32)
+    rc = lib().oracle_fp8_quantize(_ptr(x), _DT[dtype], n, dim, _ptr(codes), _ptr(scales))
+    if rc != 0:
+        raise RuntimeError(f"oracle_fp8_quantize failed ({rc})")
+    return codes, scales
+
+
+def fp8_lookup_rows(cent_codes: np.ndarray, cent_scales: np.ndarray, queries: np.ndarray, threshold: float,
+                    qdtype: str = "bf16"):
+    """Lookup over rows stored in the 8-bit format (queries are quantised the same way).
+    Returns ``(idx int32, sim float64, hit uint8, second float64)``."""
+    cc = np.ascontiguousarray(cent_codes, dtype=np.uint8)
+    cs = np.ascontiguousarray(cent_scales, dtype=np.float32)
+    k, dim = cc.shape
+    qs = _storage(queries, qdtype, dim)
+    n = qs.shape[0]
+    idx = np.empty(n, np.int32)
+    sim = np.empty(n, np.float64)
+    hit = np.empty(n, np.uint8)
+    second = np.empty(n, np.float64)
+    rc = lib().oracle_fp8_lookup_rows(_ptr(cc), _ptr(cs), k, dim, _ptr(qs), _DT[qdtype], n, float(threshold), _ptr(idx),
+                                      _ptr(sim), _ptr(hit), _ptr(second))
+    if rc != 0:
+        raise RuntimeError(f"oracle_fp8_lookup_rows failed ({rc})")
     return idx, sim, hit, second
 
 

@@ -111,6 +111,144 @@ static void store(void *base, int dtype, size_t e, double x) {
     else ((uint16_t *)base)[e] = round_bf16(x);
 }
 
+/* ------------------------------------------------------------- fp8 storage */
+/*
+ * The 8-bit floating-point storage variant.  Format: OCP 8-bit floating point, E4M3
+ * (1 sign bit, 4 exponent bits with bias 7, 3 mantissa bits; exponent field 0 holds
+ * the subnormals m/8 * 2^-6; no infinities; S.1111.111 is NaN; largest finite value
+ * 448 = 0x7E).  A row is stored as one code per element plus one scale per row
+ * (blocked scaling with the row as the block); its value is scale * decode(code).
+ *
+ * Quantisation of a row x (taken at its input precision), all in single precision
+ * because the outcome is a code (an integer decision both sides must take alike):
+ *     amax  = max_t |x_t|                   (exact)
+ *     scale = amax / 448                    (one correctly rounded division)
+ *     y_t   = x_t / scale                   (one correctly rounded division)
+ *     code_t = y_t rounded to the nearest E4M3 value, ties to the even mantissa,
+ *              values beyond 448 saturate to +-448
+ * A row without length gets scale 0 and all codes 0; a row holding a NaN or an
+ * infinity gets scale NaN (it can never be chosen).
+ */
+static double e4m3_decode(uint8_t code) {
+    const int sign = code >> 7, e = (code >> 3) & 15, m = code & 7;
+    double v;
+    if (e == 15 && m == 7) return NAN;
+    if (e == 0) v = ldexp((double)m / 8.0, -6);
+    else v = ldexp(1.0 + (double)m / 8.0, e - 7);
+    return sign ? -v : v;
+}
+
+/* nearest E4M3 value of y (finite), ties to even, saturating */
+static uint8_t e4m3_encode(float y) {
+    const uint8_t sign = signbit(y) ? 0x80 : 0;
+    const double a = fabs((double)y);
+    if (a >= 448.0) return sign | 0x7E;
+    /* spacing of the E4M3 values around a: 2^(e-3) for a in [2^e, 2^(e+1)), e >= -6; 2^-9 below 2^-6 */
+    int e;
+    (void)frexp(a, &e); /* a = f * 2^e, f in [0.5, 1): a in [2^(e-1), 2^e) */
+    int step_exp = (a < ldexp(1.0, -6)) ? -9 : (e - 1) - 3;
+    const double steps = rint(ldexp(a, -step_exp)); /* rint: round half to even; a / spacing is exact */
+    const double r = ldexp(steps, step_exp);        /* the rounded value, <= 448 */
+    if (r == 0.0) return sign;
+    /* find its code: the values are ordered like their codes */
+    for (int code = 1; code <= 0x7E; ++code)
+        if (e4m3_decode((uint8_t)code) == r) return sign | (uint8_t)code;
+    return sign | 0x7E; /* not reached */
+}
+
+/*
+ * Quantise n rows of the input type (f32 or bf16) to codes [n][dim] and scales [n].
+ */
+int oracle_fp8_quantize(const void *rows, int dtype, long n, int dim, uint8_t *codes, float *scales) {
+    if (n < 0 || dim <= 0 || (n > 0 && (!rows || !codes || !scales))) return -1;
+    for (long i = 0; i < n; ++i) {
+        float amax = 0.0f;
+        int finite = 1;
+        for (int t = 0; t < dim; ++t) {
+            const float x = (float)widen(rows, dtype, (size_t)i * dim + t); /* exact: the inputs are f32 or bf16 */
+            if (!isfinite(x)) finite = 0;
+            if (fabsf(x) > amax) amax = fabsf(x);
+        }
+        if (!finite || amax == 0.0f) {
+            scales[i] = finite ? 0.0f : NAN;
+            memset(codes + (size_t)i * dim, 0, (size_t)dim);
+            continue;
+        }
+        const float scale = amax / 448.0f;
+        scales[i] = scale;
+        for (int t = 0; t < dim; ++t) {
+            const float x = (float)widen(rows, dtype, (size_t)i * dim + t);
+            codes[(size_t)i * dim + t] = e4m3_encode(x / scale);
+        }
+    }
+    return 0;
+}
+
+/*
+ * Lookup over rows stored in the 8-bit format: the queries are quantised the same
+ * way, row by row, and the similarity is the cosine of the two stored vectors,
+ *     <scale_q decode(q8), scale_c decode(c8)> / (|.| |.|) = <decode(q8), decode(c8)> / (|decode(q8)| |decode(c8)|),
+ * in double; top-1, lowest index on ties, strict threshold: as oracle_lookup_rows.
+ * cent_codes [k][dim], cent_scales [k] (a NaN scale: the row is never chosen; scale 0: a
+ * row without length, similarity 0); queries in their input type.
+ */
+int oracle_fp8_lookup_rows(const uint8_t *cent_codes, const float *cent_scales, long k, int dim, const void *queries,
+                           int qdtype, long n, float threshold, int *out_idx, double *out_sim, unsigned char *out_hit,
+                           double *out_second) {
+    if (dim <= 0 || k < 0 || n < 0 || (n > 0 && (!queries || !out_idx || !out_sim)) || (k > 0 && (!cent_codes || !cent_scales)))
+        return -1;
+    uint8_t *q8 = (uint8_t *)malloc((size_t)(n > 0 ? n : 1) * dim);
+    float *qs = (float *)malloc(sizeof(float) * (size_t)(n > 0 ? n : 1));
+    double *cn = (double *)malloc(sizeof(double) * (size_t)(k > 0 ? k : 1));
+    if (!q8 || !qs || !cn) { free(q8); free(qs); free(cn); return -2; }
+    int rc = oracle_fp8_quantize(queries, qdtype, n, dim, q8, qs);
+    for (long j = 0; j < k; ++j) {
+        double s = 0.0;
+        for (int t = 0; t < dim; ++t) {
+            const double v = e4m3_decode(cent_codes[(size_t)j * dim + t]);
+            s += v * v;
+        }
+        cn[j] = isnan(cent_scales[j]) ? NAN : sqrt(s);
+    }
+    const double theta = (double)threshold;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (long i = 0; i < n; ++i) {
+        if (rc != 0) continue;
+        int best = -1;
+        double best_s = -INFINITY, second = -INFINITY;
+        if (isnan(qs[i])) {
+            out_idx[i] = -1;
+            out_sim[i] = NAN;
+            if (out_hit) out_hit[i] = 0;
+            if (out_second) out_second[i] = NAN;
+            continue;
+        }
+        double qn = 0.0;
+        for (int t = 0; t < dim; ++t) {
+            const double v = e4m3_decode(q8[(size_t)i * dim + t]);
+            qn += v * v;
+        }
+        qn = sqrt(qn);
+        for (long j = 0; j < k; ++j) {
+            double s = 0.0;
+            if (isnan(cn[j])) continue;
+            if (qn != 0.0 && cn[j] != 0.0) {
+                for (int t = 0; t < dim; ++t)
+                    s += e4m3_decode(q8[(size_t)i * dim + t]) * e4m3_decode(cent_codes[(size_t)j * dim + t]);
+                s /= qn * cn[j];
+            }
+            if (s > best_s) { second = best_s; best_s = s; best = (int)j; }
+            else if (s > second) second = s;
+        }
+        out_idx[i] = best;
+        out_sim[i] = best_s;
+        if (out_hit) out_hit[i] = (best >= 0 && best_s > theta) ? 1 : 0;
+        if (out_second) out_second[i] = second;
+    }
+    free(q8); free(qs); free(cn);
+    return rc;
+}
+
 /* ---------------------------------------------------------------- arithmetic */
 static double row_norm(const void *base, int dtype, long row, int dim) {
     double s = 0.0;
