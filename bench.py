@@ -25,6 +25,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2500.0  # dense bf16 MFMA, MI355X
+PEAK_FP8_TFLOPS = 5000.0   # dense fp8 MFMA
 PEAK_HBM_GBS = 8000.0      # HBM3E
 
 
@@ -73,6 +74,8 @@ def parse():
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="CPU work given to the oracle baseline")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-merge", action="store_true")
+    ap.add_argument("--storage", default="bf16", choices=["bf16", "fp8"],
+                    help="fp8: the 8-bit storage variant of the cache (lookups only: a step is siso_lookup)")
     ap.add_argument("--option", action="append", default=[], help="name=value for siso_set_option")
     ap.add_argument("--path", type=int, default=0, help="siso_set_lookup_path (0 = auto)")
     ap.add_argument("--copy-probe-mib", type=int, default=0,
@@ -145,7 +148,11 @@ def main():
     wl = W.FULL_CONFIGS[name]()
     gen_s = time.perf_counter() - t0
     d, K = wl.dim, wl.K
-    cache = siso.SisoCache(d, K, siso.BF16)
+    fp8 = args.storage == "fp8"
+    if fp8 and name == "c5_merge":
+        print("bench.py: the 8-bit storage variant serves lookups only", file=sys.stderr)
+        sys.exit(2)
+    cache = siso.SisoCache(d, K, siso.FP8 if fp8 else siso.BF16)
     cache.set_lookup_path(args.path)
     for o in args.option:
         k, v = o.split("=")
@@ -158,7 +165,7 @@ def main():
         dst = src.clone()  # reads and writes copy_probe_mib MiB each
         torch.cuda.synchronize()
         del src, dst
-    out = {"n_gpus": 1, "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
+    out = {"n_gpus": 1, "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": args.storage,
            "data": "synthetic"}
     merge_info = None
 
@@ -224,7 +231,8 @@ def main():
     def step(i):
         q = queries[(i % n_batches) * nb:(i % n_batches + 1) * nb]
         cache.lookup(q, thetas[i % len(thetas)], idx, sim, hit)
-        cache.update(q, idx, hit)
+        if not fp8:
+            cache.update(q, idx, hit)
 
     for i in range(warmup):
         step(i)
@@ -241,20 +249,22 @@ def main():
     hit_rate = float(hit.float().mean().item())
     avg_s = kern_ms / 1e3 / max(launches, 1)
     flop = 2.0 * nb * K * d
+    eb = 1.0 if fp8 else 2.0  # bytes per stored element
+    peak_tflops = PEAK_FP8_TFLOPS if fp8 else PEAK_BF16_TFLOPS
     if streaming:
-        bytes_alg = K * d * 2.0 + nb * d * 2.0 + K * 4.0  # centroids + queries + inverse lengths, read once
+        bytes_alg = K * d * eb + nb * d * eb + K * 4.0  # centroids + queries + inverse lengths, read once
         roof = {"bound": "hbm", "achieved": bytes_alg / avg_s / 1e9, "peak": PEAK_HBM_GBS, "unit": "GB/s",
-                "frac": bytes_alg / avg_s / 1e9 / PEAK_HBM_GBS, "traffic": measured_traffic(name),
+                "frac": bytes_alg / avg_s / 1e9 / PEAK_HBM_GBS, "traffic": None if fp8 else measured_traffic(name),
                 "algorithmic_bytes": bytes_alg, "kernel_ms": avg_s * 1e3,
                 "launches": launches}
     else:
-        roof = {"bound": "mfma", "achieved": flop / avg_s / 1e12, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                "frac": flop / avg_s / 1e12 / PEAK_BF16_TFLOPS, "traffic": measured_traffic(name),
-                "algorithmic_bytes": K * d * 2.0 + nb * d * 2.0 + K * 4.0, "kernel_ms": avg_s * 1e3,
+        roof = {"bound": "mfma", "achieved": flop / avg_s / 1e12, "peak": peak_tflops, "unit": "TFLOP/s",
+                "frac": flop / avg_s / 1e12 / peak_tflops, "traffic": None if fp8 else measured_traffic(name),
+                "algorithmic_bytes": K * d * eb + nb * d * eb + K * 4.0, "kernel_ms": avg_s * 1e3,
                 "launches": launches}
 
     variants_info = None
-    if not args.no_merge and name in ("c2_mid", "c3_large"):
+    if not args.no_merge and not fp8 and name in ("c2_mid", "c3_large"):
         # the lookup variants on the same batch: the whole threshold sweep as one lookup (against one lookup per
         # threshold), and the 8 closest centroids of every query
         def timed(fn, reps):
@@ -274,7 +284,7 @@ def main():
                          "top8_ms": timed(lambda: cache.lookup_topk(q0, 8), reps)}
 
     t2h_info = None
-    if not args.no_merge and name == "c2_mid":
+    if not args.no_merge and not fp8 and name == "c2_mid":
         # threshold-to-hit-ratio table over a sample whose similarities spread over the sweep, then the
         # SLO-aware choice for one made-up operating point (LLM time 1 s, 1.2 requests/s, SLO 1.3 s)
         sweep = np.round(np.arange(0.98, 0.599, -0.02), 2).astype(np.float32)
@@ -290,7 +300,7 @@ def main():
                     "hit_ratio_at_0.98_0.80_0.60": [float(ratio[0]), float(ratio[9]), float(ratio[19])],
                     "picked_theta": float(sweep[pick]) if pick >= 0 else None}
 
-    if not args.no_merge and name == "c2_mid":
+    if not args.no_merge and not fp8 and name == "c2_mid":
         theta_c = 0.90
         cap = 1 << 20
         cache.merge(theta_c, cap)
@@ -311,7 +321,7 @@ def main():
                       "group_merge_ms": apply_s * 1e3, "centroids_after": cache.count}
 
     refresh_info = None
-    if not args.no_merge and name == "c2_mid":
+    if not args.no_merge and not fp8 and name == "c2_mid":
         # cache replacement (Algorithm 1) on a fresh copy of the cache: a repository of 10 % of its size, half of
         # it near cached centroids (they merge), half of it new directions (they join); room for 2 % more rows
         rng = np.random.Generator(np.random.Philox(key=4242))
@@ -335,13 +345,14 @@ def main():
     out.update({"metric": "lookup_queries_per_s", "value": nb * steps / dt, "unit": "queries/s", "steps": steps,
                 "warmup": warmup, "ms_per_step": dt / steps * 1e3,
                 "config": {"workload": name, "centroids": K, "dim": d, "batch": nb, "thresholds": thetas,
-                           "step": "siso_lookup + siso_update_hits", "hit_rate_last_batch": hit_rate,
+                           "storage": args.storage,
+                           "step": "siso_lookup" if fp8 else "siso_lookup + siso_update_hits", "hit_rate_last_batch": hit_rate,
                            "offline_merge": merge_info, "t2h": t2h_info, "refresh": refresh_info,
                            "variants": variants_info,
                            "generate_s": round(gen_s, 1)},
                 "roofline": roof})
     add_measured_peak(siso, out["roofline"])
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and not fp8:
         out["cpu_baseline"] = cpu_baseline(wl, nb, args.cpu_seconds)
     print(json.dumps(out))
 

@@ -47,7 +47,7 @@ extern "C" {
 
 typedef struct siso_cache siso_cache; /* opaque; owns all centroid state on the device */
 
-enum { SISO_F32 = 0, SISO_BF16 = 1 };
+enum { SISO_F32 = 0, SISO_BF16 = 1, SISO_FP8 = 2 /* 8-bit storage of bf16 inputs: see siso_create_ex */ };
 
 enum {
     SISO_OK = 0,
@@ -64,6 +64,20 @@ enum {
  * vector, 4 * dim bytes for its running mean, 16 bytes for its inverse length,
  * the weight of its mean, cluster_size and access_count.  *out receives the
  * handle.  Synchronises.
+ *
+ * SISO_FP8 is the 8-bit storage variant: a read-only serving copy for lookups.  Its
+ * inputs (siso_load, the lookups, siso_t2h) are bf16 rows; every stored centroid is kept
+ * as one 8-bit floating-point code per element (OCP E4M3: 1 sign, 4 exponent, 3 mantissa
+ * bits, largest value 448) and one float scale per row, value = scale * code, with
+ *     scale = max|x_t| / 448,  code_t = x_t / scale rounded to the nearest E4M3 value
+ * (single precision, ties to the even mantissa, saturating); a lookup quantises its
+ * batch the same way and returns the cosine of the two stored vectors - close to the
+ * cosine of the bf16 rows (each element keeps 4 significant bits; cosines move by about
+ * 1e-3), not equal to it.  Half the bytes of bf16 per centroid, no running means (dim
+ * bytes + 20 per centroid).  dim must be a multiple of 128, at least 256.  Available:
+ * siso_load, siso_lookup, siso_lookup_multi, siso_t2h, siso_reserve, siso_count,
+ * siso_export (codes; means must be NULL), siso_export_scales, siso_export_meta; the
+ * other calls return SISO_EINVAL.
  */
 int siso_create(int dim, long capacity, siso_cache **out);
 int siso_create_ex(int dim, long capacity, int dtype, siso_cache **out);
@@ -230,9 +244,13 @@ long siso_merge(siso_cache *c, float threshold, int *out_pairs, long cap);
 int siso_merge_apply(siso_cache *c, const int *pairs, long n_pairs, int *out_survivor);
 
 /* Copy out the live rows (device pointers, any may be NULL): stored centroids
- * [count][dim] in the element type, running means [count][dim] floats, cluster
- * sizes [count] ints.  Asynchronous. */
+ * [count][dim] in the element type (one code byte per element for SISO_FP8), running
+ * means [count][dim] floats, cluster sizes [count] ints.  Asynchronous. */
 int siso_export(siso_cache *c, void *centroids, float *means, int *counts);
+
+/* SISO_FP8 caches: the scale of every live row ([count] floats, device pointer; NaN for
+ * a row that held a NaN or an infinity).  Asynchronous. */
+int siso_export_scales(siso_cache *c, float *scales);
 
 /*
  * Cache replacement: Algorithm 1 (SISO-CacheManager), section 4.2.

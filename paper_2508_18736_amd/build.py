@@ -16,7 +16,7 @@ CSRC = os.path.join(HERE, "csrc")
 OBJ_DIR = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libsiso.so")
 
-SOURCES = ["siso.hip", "lookup_mfma.hip", "topk.hip", "refresh.hip", "cluster.hip", "probe.hip"]
+SOURCES = ["siso.hip", "lookup_mfma.hip", "topk.hip", "fp8.hip", "refresh.hip", "cluster.hip", "probe.hip"]
 
 HIPCC_FLAGS = [
     "-O3", "--offload-arch=gfx950", "-fPIC", "-std=c++17",

@@ -333,6 +333,7 @@ static long cluster_impl(siso_cache *c, const void *vectors, long n, float theta
 extern "C" long siso_cluster(siso_cache *c, const void *vectors, long n, float theta_c, int min_size, int *out_label,
                              int *out_representative, long *out_stats) {
     if (!c) return SISO_EINVAL;
+    if (c->dtype == SISO_FP8) return siso_fail(c, SISO_EINVAL, "siso_cluster: not available with the 8-bit storage");
     try {
         return cluster_impl(c, vectors, n, theta_c, min_size, out_label, out_representative, out_stats);
     } catch (const std::bad_alloc &) {  // the host lists; nothing has been changed yet when they are built

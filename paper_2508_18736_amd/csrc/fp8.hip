@@ -1,0 +1,146 @@
+// The 8-bit storage variant of the cache (SISO_FP8): bf16 rows come in, every row is kept as one OCP E4M3 code
+// per element and one scale per row (blocked scaling, the row being the block), lookups quantise the batch the
+// same way and run the fused MFMA kernel over the codes.  The similarity is the cosine of the two stored
+// vectors; the scales cancel in it, so the kernels only ever see codes and the inverse lengths of code rows.
+//
+// Quantisation of a row x, in single precision throughout (the outcome is a code, a decision both this library
+// and anything that checks it must take alike):
+//     amax = max |x_t|;  scale = amax / 448;  code_t = nearest E4M3 value of x_t / scale, ties to the even
+//     mantissa, saturating at +-448 (E4M3: 1 sign, 4 exponent bits with bias 7, 3 mantissa bits, subnormals
+//     m/8 * 2^-6, no infinities).
+// A row without length: scale 0, all codes 0; a row holding a NaN or an infinity: scale NaN, inverse length NaN.
+#include "siso_internal.h"
+
+namespace {
+
+__device__ __forceinline__ unsigned f32_to_e4m3(float y) {
+    const unsigned sign = (__float_as_uint(y) >> 24) & 0x80u;
+    const float a = fabsf(y);
+    if (a >= 448.f) return sign | 0x7Eu;
+    if (a < 0.015625f) return sign | (unsigned)(int)rintf(a * 512.f);  // multiples of 2^-9; 8 of them is 2^-6 = code 0x08
+    unsigned v = __float_as_uint(a);
+    v += 0x7FFFFu + ((v >> 20) & 1u);  // to three mantissa bits, ties to even (may carry into the exponent)
+    return sign | ((((v >> 23) - 120u) << 3) | ((v >> 20) & 7u));
+}
+
+__device__ __forceinline__ float e4m3_to_f32(unsigned code) {
+    const unsigned e = (code >> 3) & 15u, m = code & 7u;
+    const float v = e == 0 ? (float)m * 0.001953125f : __uint_as_float(((e + 120u) << 23) | (m << 20));
+    return (code & 0x80u) ? -v : v;
+}
+
+__device__ __forceinline__ float block_max256(float v, float *sh) {
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v = fmaxf(v, __shfl_xor(v, off));
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = v;
+    __syncthreads();
+    return fmaxf(fmaxf(sh[0], sh[1]), fmaxf(sh[2], sh[3]));
+}
+__device__ __forceinline__ float block_sum256f(float v, float *sh) {
+    v = wave_sum(v);
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = v;
+    __syncthreads();
+    return (sh[0] + sh[1]) + (sh[2] + sh[3]);
+}
+
+// One 256-thread block per row: codes [row][d], scale [row] (may be NULL), inv [row] = 1 / |code row| (0 for
+// a row without length, NaN for a non-finite one).  With `load`, the row is a centroid being loaded: its unit
+// direction goes to nothing (the 8-bit cache keeps no running mean), its bookkeeping is set as siso_load does.
+__global__ __launch_bounds__(256) void k_fp8_quantize(const bf16_t *__restrict__ src, int d, unsigned char *codes, float *scale,
+                                                       float *inv, const int *__restrict__ counts, int *size,
+                                                       float *locality, unsigned *access) {
+    __shared__ float sh[4];
+    constexpr int E = SISO_MAX_DIM / 256;
+    const long r = blockIdx.x;
+    const int t = threadIdx.x;
+    float x[E];
+    float amax = 0.f;
+    bool finite = true;
+#pragma unroll
+    for (int e = 0; e < E; ++e) {
+        const int col = t + e * 256;
+        x[e] = col < d ? bf16_to_f32(src[(size_t)r * d + col]) : 0.f;
+        finite = finite && fabsf(x[e]) <= 3.4e38f;  // false for NaN and infinity
+        amax = fmaxf(amax, fabsf(x[e]));
+    }
+    const float bad = block_max256(finite ? 0.f : 1.f, sh);
+    amax = block_max256(amax, sh);
+    const float sc = amax / 448.0f;
+    float ss = 0.f;
+#pragma unroll
+    for (int e = 0; e < E; ++e) {
+        const int col = t + e * 256;
+        if (col < d) {
+            const unsigned code = (bad > 0.f || amax == 0.f) ? 0u : f32_to_e4m3(x[e] / sc);
+            codes[(size_t)r * d + col] = (unsigned char)code;
+            const float back = e4m3_to_f32(code);
+            ss += back * back;
+        }
+    }
+    ss = block_sum256f(ss, sh);
+    if (t == 0) {
+        const float nanv = __uint_as_float(0x7FC00000u);
+        if (scale) scale[r] = bad > 0.f ? nanv : sc;
+        inv[r] = bad > 0.f ? nanv : inv_length(ss);
+        if (size) {
+            const int s = counts ? counts[r] : 1;
+            size[r] = s < 1 ? 1 : s;
+            locality[r] = (float)(s < 1 ? 1 : s);
+            access[r] = 0;
+        }
+    }
+}
+
+}  // namespace
+
+int siso_fp8_load(siso_cache *c, const void *centroids, const int *counts, long k) {
+    if (k > 0) {
+        hipLaunchKernelGGL(k_fp8_quantize, dim3((unsigned)k), dim3(256), 0, c->stream, (const bf16_t *)centroids, c->dim,
+                           (unsigned char *)c->cent, c->scale, c->invn, counts, c->size, c->locality, c->access);
+        return siso_check_hip(c, hipGetLastError(), "k_fp8_quantize (load)");
+    }
+    return SISO_OK;
+}
+
+// Room for the codes and inverse lengths of a batch of n queries (grown on demand: synchronises and allocates then).
+int siso_fp8_ensure_batch(siso_cache *c, long n) {
+    if (n <= c->fp8_q_cap) return SISO_OK;
+    if (c->fp8_q) {
+        const int rc = siso_check_hip(c, hipStreamSynchronize(c->stream), "fp8 lookup: synchronize");
+        if (rc != SISO_OK) return rc;
+        (void)hipFree(c->fp8_q);
+        (void)hipFree(c->fp8_qinv);
+        c->fp8_q = nullptr;
+        c->fp8_qinv = nullptr;
+        c->fp8_q_cap = 0;
+    }
+    // whole tiles of 256 rows stay readable behind the batch (the kernels clamp their rows, this is slack)
+    bool ok = hipMalloc((void **)&c->fp8_q, ((size_t)n + SISO_PAD_ROWS) * c->dim) == hipSuccess;
+    ok = ok && hipMalloc((void **)&c->fp8_qinv, (size_t)n * sizeof(float)) == hipSuccess;
+    if (!ok) {
+        (void)hipGetLastError();
+        if (c->fp8_q) (void)hipFree(c->fp8_q);
+        c->fp8_q = nullptr;
+        c->fp8_qinv = nullptr;
+        return siso_fail(c, SISO_ENOMEM, "fp8 lookup: codes of %ld queries", n);
+    }
+    c->fp8_q_cap = n;
+    return SISO_OK;
+}
+
+int siso_fp8_quantize_batch(siso_cache *c, const void *queries, long n) {
+    hipLaunchKernelGGL(k_fp8_quantize, dim3((unsigned)n), dim3(256), 0, c->stream, (const bf16_t *)queries, c->dim,
+                       (unsigned char *)c->fp8_q, (float *)nullptr, c->fp8_qinv, (const int *)nullptr, (int *)nullptr,
+                       (float *)nullptr, (unsigned *)nullptr);
+    return siso_check_hip(c, hipGetLastError(), "k_fp8_quantize (batch)");
+}
+
+extern "C" int siso_export_scales(siso_cache *c, float *scales) {
+    if (!c) return SISO_EINVAL;
+    if (c->dtype != SISO_FP8) return siso_fail(c, SISO_EINVAL, "siso_export_scales: the cache does not use the 8-bit storage");
+    if (c->count == 0 || !scales) return SISO_OK;
+    return siso_check_hip(c, hipMemcpyAsync(scales, c->scale, (size_t)c->count * sizeof(float), hipMemcpyDeviceToDevice, c->stream),
+                          "siso_export_scales");
+}

@@ -40,22 +40,25 @@ typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 // ROWS: the keys of the lookup carry the winning row itself instead of its group of four rows (more
 // compares per product, affordable where the kernel waits for memory anyway; the finalize step then
 // has no centroid rows to read)
-template <int WC_, int WQ_, int NWC_, int NWQ_, int NSTAGE_, int BK_ = 64, bool ROWS_ = false>
+// ES: bytes per element: 2 = bf16; 1 = the 8-bit storage variant (E4M3 codes: a slab then holds 128 elements
+// in the same 128 bytes per row, and a 16-byte fragment feeds two v_mfma_f32_32x32x16_fp8_fp8, one per half)
+template <int WC_, int WQ_, int NWC_, int NWQ_, int NSTAGE_, int BK_ = 64, bool ROWS_ = false, int ES_ = 2>
 struct PipeCfg {
     static constexpr int WC = WC_, WQ = WQ_, NWC = NWC_, NWQ = NWQ_, NSTAGE = NSTAGE_;
     static constexpr bool ROWS = ROWS_;
-    static constexpr int BK = BK_;            // elements of the dimension per slab (64; or 32: half lines)
-    static constexpr int RB = BK * 2;         // bytes of a tile row in a stage
-    static constexpr int CPR = BK / 8;        // 16-byte chunks per tile row
+    static constexpr int ES = ES_;
+    static constexpr int BK = BK_;            // elements of the dimension per slab (64; or 32: half lines; 128 codes)
+    static constexpr int RB = BK * ES;        // bytes of a tile row in a stage
+    static constexpr int CPR = RB / 16;       // 16-byte chunks per tile row
     static constexpr int RPI = 64 / CPR;      // tile rows one direct load of a wave fills
     static constexpr int RP = 256 / RB;       // tile rows per 256 bytes (all 64 banks)
-    static constexpr int KK = BK / 16;        // MFMA steps per slab
+    static constexpr int KK = RB / 32;        // fragment steps per slab (a step = one 16-byte chunk per lane half)
     static constexpr int BC = 32 * WC * NWC;  // centroid rows per tile
     static constexpr int BQ = 32 * WQ * NWQ;  // query rows per tile
     static constexpr int NW = NWC * NWQ, NT = 64 * NW;
     static constexpr int STAGE = (BC + BQ) * RB;
     static constexpr int NLA = BC / RPI / NW, NLB = BQ / RPI / NW;  // direct loads per wave and slab
-    static_assert(BK == 64 || BK == 32, "slab of 64 or 32 elements");
+    static_assert((ES == 2 && (BK == 64 || BK == 32)) || (ES == 1 && BK == 128), "slab of 64 or 32 bf16 elements, or 128 codes");
     static constexpr int NL = NLA + NLB;
     static constexpr int NINV = 3;  // tiles whose inverse lengths are kept at a time (see k_lookup_pipe)
     static constexpr int LDS_BYTES = NSTAGE * STAGE + NINV * BC * 4;
@@ -133,17 +136,32 @@ __device__ __forceinline__ void static_for(F &&f) {
 
 // The accumulator blocks of a wave: WC x WQ blocks of 32 x 32, 16 registers per lane each.
 // Up to 8 blocks they are ordinary values and the compiler places them.
-template <bool FIXED, int WC, int WQ>
+// One fragment step: 16 bytes per lane of either operand.  bf16: one MFMA over 16 elements (8 per lane half);
+// E4M3 codes: two MFMAs over 16 codes each (the low and the high 8 bytes of both fragments: both operands
+// split their bytes the same way, which is all a dot product asks of the order of its terms).
+template <bool F8>
+__device__ __forceinline__ f32x16 frag_mma(bf16x8 a, bf16x8 b, f32x16 c) {
+    if constexpr (F8) {
+        typedef long l2 __attribute__((ext_vector_type(2)));
+        const l2 a2 = __builtin_bit_cast(l2, a), b2 = __builtin_bit_cast(l2, b);
+        c = __builtin_amdgcn_mfma_f32_32x32x16_fp8_fp8(a2[0], b2[0], c, 0, 0, 0);
+        return __builtin_amdgcn_mfma_f32_32x32x16_fp8_fp8(a2[1], b2[1], c, 0, 0, 0);
+    } else {
+        return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+    }
+}
+
+template <bool FIXED, int WC, int WQ, bool F8 = false>
 struct Acc {
     f32x16 v[WC][WQ];
     template <int A, int B>
     __device__ __forceinline__ void first(bf16x8 a, bf16x8 b) {  // start from zero
         const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-        v[A][B] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, zero, 0, 0, 0);
+        v[A][B] = frag_mma<F8>(a, b, zero);
     }
     template <int A, int B>
     __device__ __forceinline__ void mac(bf16x8 a, bf16x8 b) {
-        v[A][B] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, v[A][B], 0, 0, 0);
+        v[A][B] = frag_mma<F8>(a, b, v[A][B]);
     }
     template <int A, int B, int I>
     __device__ __forceinline__ float get() const {
@@ -160,7 +178,7 @@ struct Acc {
 // the last blocks, after the whole scaling of the blocks before them), far beyond the 8 passes
 // such an MFMA takes; and a block is overwritten only by an MFMA issued after it was read.
 template <int WC, int WQ>
-struct Acc<true, WC, WQ> {
+struct Acc<true, WC, WQ, false> {
     template <int A, int B>
     __device__ __forceinline__ void first(bf16x8 a, bf16x8 b) {
         constexpr int R = 16 * (A * WQ + B);
@@ -315,7 +333,7 @@ __global__ __launch_bounds__(Cfg::NT) __attribute__((amdgpu_waves_per_eu(2, 2)))
     int *__restrict__ cand, int *__restrict__ cand_cnt, int cand_cap) {
     constexpr int WC = Cfg::WC, WQ = Cfg::WQ, NWC = Cfg::NWC, BC = Cfg::BC, BQ = Cfg::BQ, NT = Cfg::NT, NW = Cfg::NW,
                   STAGE = Cfg::STAGE, NLA = Cfg::NLA, NLB = Cfg::NLB, NL = Cfg::NL, NSTAGE = Cfg::NSTAGE, BK = Cfg::BK,
-                  RB = Cfg::RB, CPR = Cfg::CPR, RPI = Cfg::RPI, RP = Cfg::RP, KK = Cfg::KK, SUB = 32 * Cfg::RB;
+                  RB = Cfg::RB, CPR = Cfg::CPR, RPI = Cfg::RPI, RP = Cfg::RP, KK = Cfg::KK, SUB = 32 * Cfg::RB, ES = Cfg::ES;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     // Inverse lengths of the tiles in flight, [NINV][BC], tile ct in buffer (ct - ct_begin) % NINV.  Those of
     // tile X are requested NSTAGE slabs ahead of its first slab, i.e. while slab X * nk - NSTAGE is multiplied,
@@ -344,16 +362,16 @@ __global__ __launch_bounds__(Cfg::NT) __attribute__((amdgpu_waves_per_eu(2, 2)))
 #pragma unroll
     for (int j = 0; j < NLA; ++j) {
         const int row = (j * NW + wave) * RPI + lr;
-        a_off[j] = (unsigned)(row * d + ((slot ^ ((row / RP) % CPR)) * 8)) * 2u;
+        a_off[j] = (unsigned)(row * d * ES + ((slot ^ ((row / RP) % CPR)) * 16));
     }
 #pragma unroll
     for (int j = 0; j < NLB; ++j) {
         const int row = (j * NW + wave) * RPI + lr;
         long qr = q0 + row;
         if (qr > n - 1) qr = n - 1;
-        b_off[j] = (unsigned)((qr - q0) * d + ((slot ^ ((row / RP) % CPR)) * 8)) * 2u;
+        b_off[j] = (unsigned)((qr - q0) * d * ES + ((slot ^ ((row / RP) % CPR)) * 16));
     }
-    const bf16_t *qbase = Q + (size_t)q0 * d;
+    const char *qbase = (const char *)Q + (size_t)q0 * d * ES;
 
     // fragment read addresses of this lane: LDS byte offset of its row in the centroid / query
     // part of stage 0, plus the swizzled 16-byte slot of each of the four 16-element steps
@@ -372,7 +390,7 @@ __global__ __launch_bounds__(Cfg::NT) __attribute__((amdgpu_waves_per_eu(2, 2)))
         bv[b] = -INFINITY;
         bb[b] = 0xFFFFFFFFu;
     }
-    Acc<false, WC, WQ> acc;  // every tile starts from a zero operand, so nothing to clear
+    Acc<false, WC, WQ, ES == 1> acc;  // every tile starts from a zero operand, so nothing to clear
     acc.reserve();
     float tq[WQ];  // COLLECT: the bounds of this lane's query columns (nothing reaches +inf: rows past the batch)
     if constexpr (COLLECT) {
@@ -392,9 +410,9 @@ __global__ __launch_bounds__(Cfg::NT) __attribute__((amdgpu_waves_per_eu(2, 2)))
     // again, into a stage nobody reads any more).  The centroids are read once per block of query
     // tiles: in a lookup their loads carry the non-temporal hint so that they do not push the
     // query tiles out of L2.
-    const char *ld_c = (const char *)(C + (size_t)ct_begin * BC * d);  // first element of the slab, centroid side
-    const char *ld_q = (const char *)qbase;                              // and query side
-    unsigned char *ld_sb = smem + wave * 1024;                           // this wave's first KiB of the stage
+    const char *ld_c = (const char *)C + (size_t)ct_begin * BC * d * ES;  // first element of the slab, centroid side
+    const char *ld_q = qbase;                                              // and query side
+    unsigned char *ld_sb = smem + wave * 1024;                             // this wave's first KiB of the stage
     int ld_t = 0;
     int ld_inv = 0, cp_inv = 0;  // buffer of inverse lengths of the tile being requested / multiplied
     auto issue_part = [&](auto jj) {
@@ -421,11 +439,11 @@ __global__ __launch_bounds__(Cfg::NT) __attribute__((amdgpu_waves_per_eu(2, 2)))
                     ld_ks = 0;
                     ++ld_ct;
                     ld_inv = ld_inv + 1 == NINV ? 0 : ld_inv + 1;
-                    ld_c += (size_t)(BC - 1) * d * 2;  // with the step below: on to the next tile's first slab
-                    ld_q = (const char *)qbase - BK * 2;
+                    ld_c += (size_t)(BC - 1) * d * ES;  // with the step below: on to the next tile's first slab
+                    ld_q = qbase - RB;
                 }
-                ld_c += BK * 2;
-                ld_q += BK * 2;
+                ld_c += RB;
+                ld_q += RB;
             }
             ld_sb = (++ld_stage == NSTAGE) ? (ld_stage = 0, smem + wave * 1024) : ld_sb + STAGE;
         }
@@ -1081,6 +1099,10 @@ typedef PipeCfg<4, 2, 2, 4, 2> PipeLarge;  // 256 x 256 tile, waves of 128 x 64,
 typedef PipeCfg<2, 2, 4, 2, 3, 64, true> PipeMid;    // 256 x 128 tile, waves of 64 x 64, three stages; keys carry rows
 typedef PipeCfg<1, 2, 8, 1, 3, 64, true> PipeSmall;  // 256 x 64 tile, waves of 32 x 64, three stages; keys carry rows
 typedef PipeCfg<4, 2, 2, 4, 4, 32> PipeLarge32;  // 256 x 256 tile, slabs of 32 elements, four stages
+// the same three tiles over E4M3 codes (slabs of 128 codes); all of their keys carry rows
+typedef PipeCfg<4, 2, 2, 4, 2, 128, true, 1> F8Large;
+typedef PipeCfg<2, 2, 4, 2, 3, 128, true, 1> F8Mid;
+typedef PipeCfg<1, 2, 8, 1, 3, 128, true, 1> F8Small;
 
 // ----------------------------------------------------------------------------
 // host side
@@ -1092,7 +1114,13 @@ struct PipePlan {
 
 // cfg: 1 = PipeLarge, 2 = PipeMid, 3 = PipeSmall, 4 = PipeLarge32, 5 = the wide kernel (same tile as 1)
 static bool pipe_plan(const siso_cache *c, long n, int cfg, long want_wgs, PipePlan *p) {
-    if (c->dtype != SISO_BF16 || c->dim % 64 != 0 || c->dim < 128 || c->count < 1 || n < 1) return false;
+    if (c->count < 1 || n < 1) return false;
+    if (c->dtype == SISO_FP8) {  // slabs of 128 codes, at least two per tile
+        if (c->dim % 128 != 0 || c->dim < 256) return false;
+        if (cfg == 4 || cfg == 5) cfg = 1;
+    } else if (c->dtype != SISO_BF16 || c->dim % 64 != 0 || c->dim < 128) {
+        return false;
+    }
     if (cfg < 1 || cfg > 5) return false;
     p->cfg = cfg;
     p->bc = 256;
@@ -1198,6 +1226,13 @@ static int launch_wide(siso_cache *c, const void *queries, long n, const PipePla
 
 static int pipe_launch(siso_cache *c, const void *queries, long n, const PipePlan &p, u64 *keys) {
     if (((uintptr_t)queries & 15) != 0) return siso_fail(c, SISO_EINVAL, "bf16 lookup: queries must be 16-byte aligned");
+    if (c->dtype == SISO_FP8) {  // `queries` are codes here (the caller has quantised the batch)
+        switch (p.cfg) {
+            case 2: return launch_cfg<F8Mid>(c, queries, n, p, keys);
+            case 3: return launch_cfg<F8Small>(c, queries, n, p, keys);
+            default: return launch_cfg<F8Large>(c, queries, n, p, keys);
+        }
+    }
     switch (p.cfg) {
         case 1: return launch_cfg<PipeLarge>(c, queries, n, p, keys);
         case 2: return launch_cfg<PipeMid>(c, queries, n, p, keys);
@@ -1213,14 +1248,15 @@ int siso_mfma_slices(const siso_cache *c, long n) {
 }
 
 // what the keys of a kernel carry
-static int keys_carry_rows(const PipePlan &p) {
+static int keys_carry_rows(const siso_cache *c, const PipePlan &p) {
+    if (c->dtype == SISO_FP8) return SISO_KEY_ROWS;
     return (p.cfg == 2 && PipeMid::ROWS) || (p.cfg == 3 && PipeSmall::ROWS) ? SISO_KEY_ROWS : SISO_KEY_GROUPS4;
 }
 
 int siso_mfma_launch(siso_cache *c, const void *queries, long n, int slices, u64 *keys, int *row_keys) {
     PipePlan p;
     if (!mfma_plan(c, n, &p) || p.slices != slices) return siso_fail(c, SISO_EINVAL, "mfma lookup: plan mismatch");
-    *row_keys = keys_carry_rows(p);
+    *row_keys = keys_carry_rows(c, p);
     return pipe_launch(c, queries, n, p, keys);
 }
 
@@ -1232,7 +1268,7 @@ int siso_skinny_slices(const siso_cache *c, long n) {
 int siso_skinny_launch(siso_cache *c, const void *queries, long n, int slices, u64 *keys, int *row_keys) {
     PipePlan p;
     if (!skinny_plan(c, n, &p) || p.slices != slices) return siso_fail(c, SISO_EINVAL, "skinny lookup: plan mismatch");
-    *row_keys = keys_carry_rows(p);
+    *row_keys = keys_carry_rows(c, p);
     return pipe_launch(c, queries, n, p, keys);
 }
 
@@ -1247,7 +1283,7 @@ int siso_topk_mfma_slices(const siso_cache *c, long n) {
 int siso_topk_mfma_pass1(siso_cache *c, const void *queries, long n, int slices, u64 *keys, int *row_keys) {
     PipePlan p;
     if (!mfma_plan(c, n, &p) || p.slices != slices) return siso_fail(c, SISO_EINVAL, "top-k lookup: plan mismatch");
-    *row_keys = keys_carry_rows(p);
+    *row_keys = keys_carry_rows(c, p);
     return pipe_launch(c, queries, n, p, keys);
 }
 
@@ -1256,6 +1292,7 @@ int siso_topk_mfma_collect(siso_cache *c, const void *queries, long n, int slice
     PipePlan p;
     if (!mfma_plan(c, n, &p) || p.slices != slices) return siso_fail(c, SISO_EINVAL, "top-k lookup: plan mismatch");
     if (((uintptr_t)queries & 15) != 0) return siso_fail(c, SISO_EINVAL, "bf16 lookup: queries must be 16-byte aligned");
+    if (c->dtype != SISO_BF16) return siso_fail(c, SISO_EINVAL, "top-k lookup: bf16 caches only");
     switch (p.cfg) {
         case 2: return launch_collect<PipeMid>(c, queries, n, p, tau, cand, cnt, cap);
         case 3: return launch_collect<PipeSmall>(c, queries, n, p, tau, cand, cnt, cap);

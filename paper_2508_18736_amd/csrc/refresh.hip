@@ -215,6 +215,7 @@ void plan_refresh(long K0, long r, const int *h_idx, const float *h_sim, const f
 static int refresh_impl(siso_cache *c, const void *repo, const float *repo_size, long r, float theta_c,
                         long max_centroids, long *out_stats) {
     if (!c) return SISO_EINVAL;
+    if (c->dtype == SISO_FP8) return siso_fail(c, SISO_EINVAL, "siso_refresh: not available with the 8-bit storage");
     if (out_stats) out_stats[0] = out_stats[1] = out_stats[2] = 0;
     if (r < 0 || max_centroids < 1 || max_centroids > c->capacity || (r > 0 && (!repo || !repo_size)))
         return siso_fail(c, SISO_EINVAL, "siso_refresh: bad arguments (1 <= max_centroids <= capacity %ld)", c->capacity);

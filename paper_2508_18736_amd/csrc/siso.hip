@@ -60,7 +60,13 @@ void siso_prof_end(siso_cache *c) {
     c->prof_count++;
 }
 
-static inline size_t elem_bytes(int dtype) { return dtype == SISO_F32 ? 4 : 2; }
+static inline size_t elem_bytes(int dtype) { return dtype == SISO_F32 ? 4 : dtype == SISO_FP8 ? 1 : 2; }
+
+// the calls an 8-bit cache does not offer (it is a read-only serving copy: lookups, and siso_load to rebuild it)
+#define SISO_NOT_FP8(c, what)                                                                                        \
+    do {                                                                                                             \
+        if ((c)->dtype == SISO_FP8) return siso_fail((c), SISO_EINVAL, what ": not available with the 8-bit storage"); \
+    } while (0)
 
 // ============================================================================
 // small kernels
@@ -146,7 +152,8 @@ __global__ __launch_bounds__(256) void k_lookup_finalize(const T *__restrict__ Q
                                                           const float *__restrict__ invn, const u64 *__restrict__ keys,
                                                           long n, long K, int d, int slices, ThetaList thetas, int vec,
                                                           int key_kind, int *out_idx, float *out_sim,
-                                                          unsigned char *out_hit, unsigned *access) {
+                                                          unsigned char *out_hit, unsigned *access,
+                                                          const float *__restrict__ q_inv) {
     constexpr int EPC = 16 / (int)sizeof(T);  // elements per 16-byte chunk
     __shared__ float sh_f[4];
     __shared__ u64 sh_k[4];
@@ -158,7 +165,9 @@ __global__ __launch_bounds__(256) void k_lookup_finalize(const T *__restrict__ Q
     const T *qrow = Q + (size_t)q * d;
     // 1/|q|: 0 for a zero-length query, NaN for a non-finite one
     float ss = 0.f;
-    if (vec) {  // the row also goes to LDS: sixteen groups of lanes will read it again
+    if (q_inv) {
+        // 1 / |q| is given (the batch was quantised: Q is not read at all; such keys always name rows)
+    } else if (vec) {  // the row also goes to LDS: sixteen groups of lanes will read it again
         for (int e = t * EPC; e < d; e += 256 * EPC) {
             const u32x4_t v = *(const u32x4_t *)(qrow + e);
             sh_q[e / EPC] = v;
@@ -183,7 +192,7 @@ __global__ __launch_bounds__(256) void k_lookup_finalize(const T *__restrict__ Q
         sh_k[wave] = key;
     }
     __syncthreads();
-    const float qi = inv_length((sh_f[0] + sh_f[1]) + (sh_f[2] + sh_f[3]));
+    const float qi = q_inv ? q_inv[q] : inv_length((sh_f[0] + sh_f[1]) + (sh_f[2] + sh_f[3]));
 #pragma unroll
     for (int w = 0; w < 4; ++w) key = sh_k[w] > key ? sh_k[w] : key;
 
@@ -926,8 +935,9 @@ extern "C" int siso_create_ex(int dim, long capacity, int dtype, siso_cache **ou
     if (!out) return SISO_EINVAL;
     *out = nullptr;
     if (dim < 1 || dim > SISO_MAX_DIM || capacity < 1 || capacity > 2147483647L ||
-        (dtype != SISO_F32 && dtype != SISO_BF16))
+        (dtype != SISO_F32 && dtype != SISO_BF16 && dtype != SISO_FP8))
         return SISO_EINVAL;
+    if (dtype == SISO_FP8 && (dim % 128 != 0 || dim < 256)) return SISO_EINVAL;  // slabs of 128 codes, two per tile
     siso_cache *c = new (std::nothrow) siso_cache();
     if (!c) return SISO_ENOMEM;
     memset(c, 0, sizeof(*c));
@@ -943,7 +953,8 @@ extern "C" int siso_create_ex(int dim, long capacity, int dtype, siso_cache **ou
     const size_t cent_bytes = (cells + (size_t)SISO_PAD_ROWS * dim) * elem_bytes(dtype);
     ok = ok && hipMalloc(&c->cent, cent_bytes) == hipSuccess;
     ok = ok && hipMemset(c->cent, 0, cent_bytes) == hipSuccess;
-    ok = ok && hipMalloc((void **)&c->mean, cells * sizeof(float)) == hipSuccess;
+    if (dtype == SISO_FP8) ok = ok && hipMalloc((void **)&c->scale, (size_t)capacity * sizeof(float)) == hipSuccess;
+    else ok = ok && hipMalloc((void **)&c->mean, cells * sizeof(float)) == hipSuccess;
     ok = ok && hipMalloc((void **)&c->size, (size_t)capacity * sizeof(int)) == hipSuccess;
     ok = ok && hipMalloc((void **)&c->invn, ((size_t)capacity + SISO_PAD_ROWS) * sizeof(float)) == hipSuccess;
     ok = ok && hipMemset(c->invn, 0, ((size_t)capacity + SISO_PAD_ROWS) * sizeof(float)) == hipSuccess;
@@ -984,6 +995,9 @@ extern "C" void siso_destroy(siso_cache *c) {
     if (c->locality_b) (void)hipFree(c->locality_b);
     if (c->access_b) (void)hipFree(c->access_b);
     if (c->keys) (void)hipFree(c->keys);
+    if (c->scale) (void)hipFree(c->scale);
+    if (c->fp8_q) (void)hipFree(c->fp8_q);
+    if (c->fp8_qinv) (void)hipFree(c->fp8_qinv);
     if (c->topk_tau) (void)hipFree(c->topk_tau);
     if (c->topk_cnt) (void)hipFree(c->topk_cnt);
     if (c->topk_cand) (void)hipFree(c->topk_cand);
@@ -1005,6 +1019,7 @@ extern "C" int siso_set_stream(siso_cache *c, void *hip_stream) {
 
 extern "C" int siso_set_lookup_path(siso_cache *c, int path) {
     if (!c) return SISO_EINVAL;
+    if (c->dtype == SISO_FP8 && path == SISO_PATH_SCALAR) return siso_fail(c, SISO_EINVAL, "the 8-bit storage has no scalar kernel");
     if (path < SISO_PATH_AUTO || path > SISO_PATH_SKINNY) return siso_fail(c, SISO_EINVAL, "unknown lookup path %d", path);
     c->path = path;
     return SISO_OK;
@@ -1032,7 +1047,10 @@ extern "C" int siso_load(siso_cache *c, const void *centroids, const int *counts
     if (!c) return SISO_EINVAL;
     if (k < 0 || (k > 0 && !centroids)) return siso_fail(c, SISO_EINVAL, "siso_load: bad arguments");
     if (k > c->capacity) return siso_fail(c, SISO_ECAPACITY, "siso_load: %ld rows exceed capacity %ld", k, c->capacity);
-    if (k > 0) {
+    if (c->dtype == SISO_FP8) {
+        const int rc = siso_fp8_load(c, centroids, counts, k);
+        if (rc != SISO_OK) return rc;
+    } else if (k > 0) {
         if (c->dtype == SISO_F32)
             hipLaunchKernelGGL(k_load_rows<float>, dim3((unsigned)k), dim3(256), 0, c->stream, (const float *)centroids,
                                counts, (float *)c->cent, c->mean, c->size, c->invn, c->locality, c->access, c->dim);
@@ -1052,6 +1070,7 @@ extern "C" int siso_import(siso_cache *c, const void *centroids, const float *me
                            const float *cluster_size, const unsigned *access_count, long k) {
     if (!c) return SISO_EINVAL;
     if (k < 0 || (k > 0 && (!centroids || !means || !counts))) return siso_fail(c, SISO_EINVAL, "siso_import: bad arguments");
+    SISO_NOT_FP8(c, "siso_import");
     if (k > c->capacity) return siso_fail(c, SISO_ECAPACITY, "siso_import: %ld rows exceed capacity %ld", k, c->capacity);
     if (k > 0) {
         if (c->dtype == SISO_F32)
@@ -1082,6 +1101,7 @@ extern "C" int siso_lookup_static(siso_cache *c, const void *queries, long n, fl
     if (!c) return SISO_EINVAL;
     if (n < 0 || (n > 0 && (!queries || !out_idx || !out_sim)))
         return siso_fail(c, SISO_EINVAL, "siso_lookup_static: bad arguments");
+    SISO_NOT_FP8(c, "siso_lookup_static");  // (the batch is quantised into a workspace that grows on demand)
     if (!c->static_keys) return siso_fail(c, SISO_EHIP, "siso_lookup_static: the static workspace was not found on device %d", c->device);
     return siso_lookup_impl(c, queries, n, &threshold, 1, 0, out_idx, out_sim, out_hit, c->static_keys, SISO_STATIC_KEYS);
 }
@@ -1134,6 +1154,7 @@ extern "C" int siso_reserve(siso_cache *c, long n) {
         const int rc = ensure_workspace(c, need, 1);
         if (rc != SISO_OK) return rc;
     }
+    if (c->dtype == SISO_FP8) return siso_fp8_ensure_batch(c, n);
     if (n > 256) return ensure_update_notes(c);
     return SISO_OK;
 }
@@ -1161,6 +1182,9 @@ int siso_lookup_impl(siso_cache *c, const void *queries, long n, const float *th
     if (n > 2147483647L / 4) return siso_fail(c, SISO_EINVAL, "siso_lookup: batch of %ld is too large", n);
     int slices = 1;
     const int path = c->count > 0 ? choose_path(c, n) : SISO_PATH_SCALAR;
+    const bool fp8 = c->dtype == SISO_FP8;
+    if (fp8 && c->count > 0 && path == SISO_PATH_SCALAR)
+        return siso_fail(c, SISO_EINVAL, "siso_lookup: the 8-bit storage has no scalar kernel");
     if (c->count > 0) {
         switch (path) {
             case SISO_PATH_SCALAR: slices = siso_scalar_slices(c, n); break;
@@ -1182,6 +1206,13 @@ int siso_lookup_impl(siso_cache *c, const void *queries, long n, const float *th
         if (rc != SISO_OK) return rc;
     }
     u64 *keys = static_keys ? static_keys : c->keys;
+    const void *kernel_queries = queries;
+    if (fp8) {  // the batch as codes, quantised like the stored rows
+        rc = siso_fp8_ensure_batch(c, n);
+        if (rc == SISO_OK) rc = siso_fp8_quantize_batch(c, queries, n);
+        if (rc != SISO_OK) return rc;
+        kernel_queries = c->fp8_q;
+    }
     const unsigned qblocks = (unsigned)n;
     const int vec = ((c->dim * elem_bytes(c->dtype)) % 16 == 0 && ((uintptr_t)queries & 15) == 0) ? 1 : 0;
     ThetaList tl;
@@ -1193,8 +1224,8 @@ int siso_lookup_impl(siso_cache *c, const void *queries, long n, const float *th
         if (!static_keys) siso_prof_begin(c);
         switch (path) {
             case SISO_PATH_SCALAR: rc = siso_scalar_launch(c, queries, n, slices, keys); break;
-            case SISO_PATH_MFMA: rc = siso_mfma_launch(c, queries, n, slices, keys, &row_keys); break;
-            case SISO_PATH_SKINNY: rc = siso_skinny_launch(c, queries, n, slices, keys, &row_keys); break;
+            case SISO_PATH_MFMA: rc = siso_mfma_launch(c, kernel_queries, n, slices, keys, &row_keys); break;
+            case SISO_PATH_SKINNY: rc = siso_skinny_launch(c, kernel_queries, n, slices, keys, &row_keys); break;
         }
         if (!static_keys) siso_prof_end(c);
         if (rc != SISO_OK) return rc;
@@ -1202,11 +1233,13 @@ int siso_lookup_impl(siso_cache *c, const void *queries, long n, const float *th
     if (c->dtype == SISO_F32)
         hipLaunchKernelGGL(k_lookup_finalize<float>, dim3(qblocks), dim3(256), 0, c->stream, (const float *)queries,
                            (const float *)c->cent, c->invn, keys, n, c->count, c->dim, slices, tl,
-                           vec, row_keys, out_idx, out_sim, out_hit, count_index >= 0 ? c->access : nullptr);
+                           vec, row_keys, out_idx, out_sim, out_hit, count_index >= 0 ? c->access : nullptr,
+                           (const float *)nullptr);
     else
         hipLaunchKernelGGL(k_lookup_finalize<bf16_t>, dim3(qblocks), dim3(256), 0, c->stream, (const bf16_t *)queries,
                            (const bf16_t *)c->cent, c->invn, keys, n, c->count, c->dim, slices, tl,
-                           vec, row_keys, out_idx, out_sim, out_hit, count_index >= 0 ? c->access : nullptr);
+                           vec, row_keys, out_idx, out_sim, out_hit, count_index >= 0 ? c->access : nullptr,
+                           fp8 ? (const float *)c->fp8_qinv : (const float *)nullptr);
     HIP_TRY(c, hipGetLastError());
     return SISO_OK;
 }
@@ -1215,6 +1248,7 @@ int siso_lookup_impl(siso_cache *c, const void *queries, long n, const float *th
 
 extern "C" int siso_update_hits(siso_cache *c, const void *queries, const int *idx, const unsigned char *hit, long n) {
     if (!c) return SISO_EINVAL;
+    SISO_NOT_FP8(c, "siso_update");
     if (n < 0 || (n > 0 && (!queries || !idx))) return siso_fail(c, SISO_EINVAL, "siso_update: bad arguments");
     // A running mean folds chunk after chunk to the same mean as one big batch,
     // so very large batches are cut to bound the member scan of each block.
@@ -1288,6 +1322,7 @@ extern "C" long siso_bad_indices(siso_cache *c) {
 
 extern "C" long siso_merge(siso_cache *c, float threshold, int *out_pairs, long cap) {
     if (!c) return SISO_EINVAL;
+    SISO_NOT_FP8(c, "siso_merge");
     if (cap < 0 || (cap > 0 && !out_pairs)) return siso_fail(c, SISO_EINVAL, "siso_merge: bad arguments");
     if (c->count < 2) return 0;
     hipLaunchKernelGGL(k_zero_counter, dim3(1), dim3(1), 0, c->stream, c->counters + 1);
@@ -1307,6 +1342,7 @@ extern "C" long siso_merge(siso_cache *c, float threshold, int *out_pairs, long 
 
 extern "C" int siso_merge_apply(siso_cache *c, const int *pairs, long n_pairs, int *out_survivor) {
     if (!c) return SISO_EINVAL;
+    SISO_NOT_FP8(c, "siso_merge_apply");
     if (n_pairs < 0 || (n_pairs > 0 && !pairs)) return siso_fail(c, SISO_EINVAL, "siso_merge_apply: bad arguments");
     const long K = c->count;
     if (K == 0) return SISO_OK;
@@ -1440,6 +1476,7 @@ extern "C" int siso_profile_read(siso_cache *c, double *total_ms, long *launches
 
 extern "C" int siso_export(siso_cache *c, void *centroids, float *means, int *counts) {
     if (!c) return SISO_EINVAL;
+    if (c->dtype == SISO_FP8 && means) return siso_fail(c, SISO_EINVAL, "siso_export: the 8-bit storage keeps no running means");
     const size_t cells = (size_t)c->count * c->dim;
     if (c->count == 0) return SISO_OK;
     if (centroids)

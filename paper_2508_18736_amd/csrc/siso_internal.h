@@ -69,6 +69,14 @@ struct siso_cache {
     u64 *counters;  // device: [0] bad update indices, [1] merge pair count, [2] scratch, [3] scratch
     u64 *host_pin;  // pinned host mirror for counter read-back (4 entries)
 
+    // 8-bit storage (SISO_FP8): cent holds one E4M3 code per element, scale [capacity] the scale of every row
+    // (NaN for a non-finite row), invn the inverse lengths of the code rows; there is no running mean.
+    // fp8_q / fp8_qinv: codes and inverse code lengths of the batch being looked up, [fp8_q_cap] rows, grown on demand
+    float *scale;
+    void *fp8_q;
+    float *fp8_qinv;
+    long fp8_q_cap;
+
     // top-k lookups: per query the bound, the number of listed rows, a flag "scan this query row by row" and
     // the listed rows ([topk_cap] floats / ints / ints, [topk_cap][SISO_TOPK_CAND] ints), grown on demand
     float *topk_tau;
@@ -324,6 +332,9 @@ int siso_pairs_mfma_launch(siso_cache *c, const void *rows, const float *invn, l
 int siso_lookup_impl(siso_cache *c, const void *queries, long n, const float *thetas, int m, int count_index,
                      int *out_idx, float *out_sim, unsigned char *out_hit, u64 *static_keys = nullptr,
                      long static_cap = 0);
+int siso_fp8_load(siso_cache *c, const void *centroids, const int *counts, long k);  // siso_load of an 8-bit cache
+int siso_fp8_ensure_batch(siso_cache *c, long n);
+int siso_fp8_quantize_batch(siso_cache *c, const void *queries, long n);  // bf16 queries -> c->fp8_q, c->fp8_qinv
 int siso_read_counter(siso_cache *c, int which, u64 *value);
 int siso_ensure_keys(siso_cache *c, long need);  // room for `need` phase-1 keys in c->keys (may synchronise and allocate)
 int siso_second_set(siso_cache *c);    // make sure the second set of arrays exists (allocates once; synchronises then)

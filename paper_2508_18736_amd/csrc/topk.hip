@@ -296,6 +296,7 @@ extern "C" int siso_lookup_topk(siso_cache *c, const void *queries, long n, int 
     if (!c) return SISO_EINVAL;
     if (n < 0 || k < 1 || k > SISO_TOPK_MAX || (n > 0 && (!queries || !out_idx || !out_sim)))
         return siso_fail(c, SISO_EINVAL, "siso_lookup_topk: bad arguments (1 <= k <= %d)", SISO_TOPK_MAX);
+    if (c->dtype == SISO_FP8) return siso_fail(c, SISO_EINVAL, "siso_lookup_topk: not available with the 8-bit storage");
     if (n == 0) return SISO_OK;
     if (n > 2147483647L / 4) return siso_fail(c, SISO_EINVAL, "siso_lookup_topk: batch of %ld is too large", n);
     // the two-pass path needs many more slices than k, and rows that are whole 16-byte chunks

@@ -24,7 +24,7 @@ if not os.path.exists(LIB_PATH):
 
 _lib = C.CDLL(LIB_PATH)
 
-F32, BF16 = 0, 1
+F32, BF16, FP8 = 0, 1, 2
 PATH_AUTO, PATH_SCALAR, PATH_MFMA, PATH_SKINNY = 0, 1, 2, 3
 OK, EINVAL, ECAPACITY, EHIP, ENOMEM = 0, -1, -2, -3, -4
 
@@ -59,6 +59,7 @@ SYMBOLS = {
     "siso_choose_communities": ([_vp, _lg, _lg, _it, _vp], _lg),
     "siso_refresh_plan": ([_lg, _vp, _vp, _lg, _vp, _vp, _vp, _vp, _vp, _lg, _fl, _lg, _vp, _vp, _vp], _lg),
     "siso_export_meta": ([_vp, _vp, _vp], _it),
+    "siso_export_scales": ([_vp, _vp], _it),
     "siso_import": ([_vp, _vp, _vp, _vp, _vp, _vp, _lg], _it),
     "siso_t2h": ([_vp, _vp, _lg, _vp, _it, _vp], _it),
     "siso_md1_wait": ([C.c_double, C.c_double, C.c_double], C.c_double),
@@ -168,7 +169,7 @@ class SisoError(RuntimeError):
         self.code = code
 
 
-_TORCH_DT = {F32: torch.float32, BF16: torch.bfloat16}
+_TORCH_DT = {F32: torch.float32, BF16: torch.bfloat16, FP8: torch.bfloat16}  # what the rows handed in are made of
 
 
 def _ptr(t: Optional[torch.Tensor]):
@@ -394,6 +395,16 @@ class SisoCache:
         ms, cnt = C.c_double(0.0), C.c_long(0)
         self._check(_lib.siso_profile_read(self._h, C.byref(ms), C.byref(cnt)))
         return float(ms.value), int(cnt.value)
+
+    def export_fp8(self) -> Tuple[torch.Tensor, torch.Tensor, torch.Tensor]:
+        """8-bit caches: ``(codes uint8 [count, dim], scales float32 [count], sizes int32 [count])``."""
+        k = self.count
+        codes = torch.empty((k, self.dim), dtype=torch.uint8, device=self.device)
+        scales = torch.empty(k, dtype=torch.float32, device=self.device)
+        sizes = torch.empty(k, dtype=torch.int32, device=self.device)
+        self._check(_lib.siso_export(self._h, _ptr(codes), None, _ptr(sizes)))
+        self._check(_lib.siso_export_scales(self._h, _ptr(scales)))
+        return codes, scales, sizes
 
     def export(self) -> Tuple[torch.Tensor, torch.Tensor, torch.Tensor]:
         k = self.count

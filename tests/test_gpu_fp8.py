@@ -1,0 +1,144 @@
+"""GPU parity of the 8-bit storage variant (SISO_FP8) against the CPU oracle, through the C ABI.
+
+Bar: the codes and scales the library stores are those of the oracle, bit for bit (the quantisation is an
+integer decision taken in single precision on both sides); indices and hit flags as for the other lookups
+(exact where the oracle's top-2 gap exceeds 1e-3 and the similarity is clear of the threshold); similarities
+within 5e-4: the products of two codes are exact in the matrix cores' fp32 accumulators, the at most 4,096
+additions of a row each round by at most 2^-24 of a partial sum that Cauchy-Schwarz bounds by |q||c|, so the
+cosine is off by at most 4,096 * 2^-24 = 2.4e-4 from the sums, and about as much again from the two lengths."""
+
+import numpy as np
+import pytest
+import torch
+
+from paper_2508_18736_amd import workloads as W
+from gpu_util import DEV, check_lookup, to_dev
+import gpu_util
+
+pytestmark = pytest.mark.gpu
+gpu_util.SIM_TOL.setdefault("fp8", 5e-4)
+
+
+@pytest.fixture(scope="module")
+def siso():
+    from paper_2508_18736_amd import siso as m
+    return m
+
+
+def load_fp8(siso, wl, capacity=None):
+    cache = siso.SisoCache(wl.dim, capacity or max(wl.K, 1), siso.FP8)
+    cache.load(to_dev(wl.centroids, "bf16"))
+    return cache
+
+
+@pytest.mark.parametrize("dim,K,n", [(256, 5000, 300), (768, 2049, 513), (1024, 1500, 64), (512, 70000, 33), (256, 37, 700),
+                                      (384, 3000, 100), (4096, 600, 130), (768, 9000, 1)])
+def test_fp8_storage_and_lookup_vs_oracle(siso, oracle, dim, K, n):
+    print(f"case: fp8 dim={dim} K={K} n={n}", flush=True)
+    wl = W.c2_mid(n_clusters=128, per_cluster=(K + 127) // 128, n_queries=n, dim=dim, seed=501)
+    wl.centroids = wl.centroids[:K].copy()
+    r = np.random.default_rng(dim + n)
+    c = wl.centroids_f32() * np.exp2(r.integers(-3, 4, size=K)).astype(np.float32)[:, None]   # rows of different lengths
+    wl.centroids = W.f32_to_bf16_bits(c)
+    cache = load_fp8(siso, wl, K + 5)
+    codes, scales, sizes = cache.export_fp8()
+    oc, os_ = oracle.fp8_quantize(wl.centroids, "bf16")
+    assert np.array_equal(codes.cpu().numpy(), oc), "stored codes differ from the oracle's"
+    assert np.array_equal(scales.cpu().numpy().view(np.uint32), os_.view(np.uint32)), "scales differ"
+    assert bool((sizes == 1).all())
+    out = cache.lookup(to_dev(wl.queries, "bf16"), 0.85)
+    torch.cuda.synchronize()
+    ora = oracle.fp8_lookup_rows(oc, os_, wl.queries, 0.85)
+    st = check_lookup(out, ora, 0.85, "fp8", "fp8 lookup")
+    print(f"  {st}", flush=True)
+    assert st["max_err"] < 2e-5 and st["clear"] >= max(1, n // 3)
+    again = cache.lookup(to_dev(wl.queries, "bf16"), 0.85)
+    torch.cuda.synchronize()
+    assert all(torch.equal(a, b) for a, b in zip(out, again))
+
+
+def test_fp8_duplicates_special_values_and_thresholds(siso, oracle):
+    print("case: fp8 duplicates, special values, several thresholds", flush=True)
+    dim = 256
+    wl = W.c2_mid(n_clusters=64, per_cluster=40, n_queries=200, dim=dim, seed=502)
+    K = wl.K
+    r = np.random.default_rng(9)
+    src = r.choice(K, size=60, replace=False)
+    for a in src:
+        for b in r.choice(K, size=2, replace=False):
+            wl.centroids[b] = wl.centroids[a]
+    c = wl.centroids_f32().copy()
+    c[10] = 0.0
+    c[11, 3] = np.nan
+    c[12] *= 7.0
+    keep = wl.centroids.copy()
+    wl.centroids = W.f32_to_bf16_bits(c)
+    dup = np.setdiff1d(np.arange(K), [10, 11, 12])
+    wl.centroids[dup] = keep[dup]
+    wl.queries = W.jitter(503, 3, wl.centroids_f32(), np.resize(src, 200), 0.08, "total", "bf16")
+    q = wl.queries_f32().copy()
+    q[0] = 0.0
+    q[1, 5] = np.nan
+    q[2, 7] = np.inf
+    q[3] *= 1e-3
+    wl.queries = W.f32_to_bf16_bits(q)
+    cache = load_fp8(siso, wl)
+    oc, os_ = oracle.fp8_quantize(wl.centroids, "bf16")
+    codes, scales, _ = cache.export_fp8()
+    assert np.array_equal(codes.cpu().numpy(), oc)
+    gs = scales.cpu().numpy()
+    assert np.array_equal(np.isnan(gs), np.isnan(os_)) and np.array_equal(gs[~np.isnan(gs)], os_[~np.isnan(os_)])
+    th = np.array([0.9, 0.5, 0.99], np.float32)
+    idx, sim, hit = cache.lookup_multi(to_dev(wl.queries, "bf16"), th, count_index=1)
+    torch.cuda.synchronize()
+    for j, t in enumerate(th):
+        ora = oracle.fp8_lookup_rows(oc, os_, wl.queries, float(t))
+        tie = ora[1] == ora[3]
+        check_lookup((idx, sim, hit[:, j].contiguous()), (ora[0], ora[1], ora[2], np.where(tie, -np.inf, ora[3])), float(t), "fp8",
+                     f"fp8 theta {t}")
+    gi = idx.cpu().numpy()
+    assert tie.sum() > 100 and np.array_equal(gi[tie], ora[0][tie])      # exact ties: the lowest index, bit-exactly
+    assert gi[0] == 0 and float(sim[0]) == 0.0 and gi[1] == -1 and gi[2] == -1 and bool(torch.isnan(sim[1]))
+    acc = cache.export_meta()[1].cpu().numpy()
+    assert acc.sum() == int(hit[:, 1].sum().item())
+    # what an 8-bit cache does not offer
+    qd = to_dev(wl.queries, "bf16")
+    for call in (lambda: cache.update(qd, idx), lambda: cache.merge(0.9, 10), lambda: cache.lookup_topk(qd, 3),
+                 lambda: cache.export(), lambda: cache.set_lookup_path(siso.PATH_SCALAR)):
+        with pytest.raises(siso.SisoError):
+            call()
+    with pytest.raises(siso.SisoError):
+        siso.SisoCache(192, 10, siso.FP8)      # the dimension must be a multiple of 128
+    # the table of hit ratios over a sweep comes from the same lookup
+    sweep = np.round(np.arange(0.98, 0.599, -0.02), 2).astype(np.float32)
+    hits = cache.t2h(qd, sweep)
+    gsim = sim.cpu().numpy()
+    assert np.array_equal(hits, [(gsim > t).sum() for t in sweep])
+    empty = siso.SisoCache(dim, 16, siso.FP8)
+    ei, es, eh = empty.lookup(qd[3:9], 0.5)
+    assert (ei.cpu().numpy() == -1).all() and np.isneginf(es.cpu().numpy()).all()
+
+
+def test_fp8_mid_size_against_the_oracle_and_the_bf16_lookup(siso, oracle):
+    """The mid-size workload in the 8-bit storage: 128 sampled queries through the oracle, and how often the
+    8-bit lookup names the centroid the bf16 lookup names (the price of the storage, reported, not a parity bar)."""
+    print("case: fp8 c2_mid", flush=True)
+    wl = W.c2_mid()
+    cache = load_fp8(siso, wl)
+    q = to_dev(wl.queries, "bf16")
+    out = cache.lookup(q, 0.85)
+    ref = siso.SisoCache(wl.dim, wl.K, siso.BF16)
+    ref.load(to_dev(wl.centroids, "bf16"))
+    rout = ref.lookup(q, 0.85)
+    torch.cuda.synchronize()
+    rows = np.arange(0, wl.n, 32)
+    oc, os_ = oracle.fp8_quantize(wl.centroids, "bf16")
+    ora = oracle.fp8_lookup_rows(oc, os_, wl.queries[rows], 0.85)
+    st = check_lookup(tuple(t[rows] for t in out), ora, 0.85, "fp8", "fp8 c2")
+    same = float((out[0] == rout[0]).float().mean())
+    shift = float((out[1] - rout[1]).abs().max())
+    near = wl.planted >= 0
+    planted = float((out[0].cpu().numpy()[near] == wl.planted[near]).mean())
+    print(f"  {st}; same centroid as the bf16 lookup {same:.4f}; planted centroid found {planted:.4f}; "
+          f"largest shift of a similarity {shift:.2e}", flush=True)
+    assert st["max_err"] < 2e-5 and same > 0.9 and shift < 0.01 and torch.equal(out[2], rout[2])
