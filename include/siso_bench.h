@@ -28,7 +28,8 @@ int siso_set_lookup_path(siso_cache *c, int path);
 /*
  * Tuning knobs, for benchmarking; the defaults are chosen by the library.
  *   "mfma_config"     0 = default; 1 = 256x256 tile, 2 = 256x128, 3 = 256x64, 4 = 256x256 with half-width slabs,
- *                     5 = 256x256 with four waves of 128x128
+ *                     5 = 256x256 with four waves of 128x128; 8-bit caches: 6, 7, 8 = the tiles of 1, 2, 3 on the
+ *                     64-deep fp8 MFMA (their default), 1, 2, 3 = the same on the 16-deep one
  *   "tiles_per_slice" 0 = default; >0 = centroid tiles one workgroup walks through
  *   "merge_config"    0 = default; 1 = use the scalar pair search
  *   "mfma_qblock"     0 = default; 1, 2, 4, 8, 16, 32 = query tiles that share an XCD's centroid tiles

@@ -42,11 +42,13 @@ typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 // has no centroid rows to read)
 // ES: bytes per element: 2 = bf16; 1 = the 8-bit storage variant (E4M3 codes: a slab then holds 128 elements
 // in the same 128 bytes per row, and a 16-byte fragment feeds two v_mfma_f32_32x32x16_fp8_fp8, one per half)
-template <int WC_, int WQ_, int NWC_, int NWQ_, int NSTAGE_, int BK_ = 64, bool ROWS_ = false, int ES_ = 2>
+template <int WC_, int WQ_, int NWC_, int NWQ_, int NSTAGE_, int BK_ = 64, bool ROWS_ = false, int ES_ = 2, bool K64_ = false>
 struct PipeCfg {
     static constexpr int WC = WC_, WQ = WQ_, NWC = NWC_, NWQ = NWQ_, NSTAGE = NSTAGE_;
     static constexpr bool ROWS = ROWS_;
     static constexpr int ES = ES_;
+    static constexpr bool K64 = K64_;  // codes only: 64-deep MFMAs, 32 bytes per lane and operand (see k_lookup_pipe)
+    static_assert(!K64_ || ES_ == 1, "the 64-deep form is for one-byte elements");
     static constexpr int BK = BK_;            // elements of the dimension per slab (64; or 32: half lines; 128 codes)
     static constexpr int RB = BK * ES;        // bytes of a tile row in a stage
     static constexpr int CPR = RB / 16;       // 16-byte chunks per tile row
@@ -103,6 +105,15 @@ __device__ __forceinline__ void lds_wait(bf16x8 (&a)[NA], bf16x8 (&b)[NB]) {
 #pragma unroll
     for (int i = 0; i < NB; ++i) asm volatile("" : "+v"(b[i]));
 }
+// the same for the fragments of the 64-deep form (two chunks per block row; B in two buffers)
+template <int N, int NA, int NB>
+__device__ __forceinline__ void lds_wait64(bf16x8 (&al)[NA], bf16x8 (&ah)[NA], bf16x8 (&bl)[2][NB], bf16x8 (&bh)[2][NB]) {
+    asm volatile("s_waitcnt lgkmcnt(%1)" : "+v"(al[0]) : "n"(N));
+#pragma unroll
+    for (int i = 0; i < NA; ++i) asm volatile("" : "+v"(al[i]), "+v"(ah[i]));
+#pragma unroll
+    for (int i = 0; i < NB; ++i) asm volatile("" : "+v"(bl[0][i]), "+v"(bh[0][i]), "+v"(bl[1][i]), "+v"(bh[1][i]));
+}
 // SUB = bytes between the 32-row blocks of a wave's tile (32 tile rows)
 template <int SUB, int NA, int NB>
 __device__ __forceinline__ void lds_frags(bf16x8 (&a)[NA], bf16x8 (&b)[NB], unsigned addr_a, unsigned addr_b) {
@@ -149,6 +160,15 @@ __device__ __forceinline__ f32x16 frag_mma(bf16x8 a, bf16x8 b, f32x16 c) {
     } else {
         return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
     }
+}
+
+// The 64-deep form over E4M3 codes: 32 bytes per lane of either operand = two 16-byte chunks (scales of 2^0).
+__device__ __forceinline__ f32x16 frag_mma64(bf16x8 a_lo, bf16x8 a_hi, bf16x8 b_lo, bf16x8 b_hi, f32x16 c) {
+    typedef int i4 __attribute__((ext_vector_type(4)));
+    typedef int i8 __attribute__((ext_vector_type(8)));
+    const i8 a = __builtin_shufflevector(__builtin_bit_cast(i4, a_lo), __builtin_bit_cast(i4, a_hi), 0, 1, 2, 3, 4, 5, 6, 7);
+    const i8 b = __builtin_shufflevector(__builtin_bit_cast(i4, b_lo), __builtin_bit_cast(i4, b_hi), 0, 1, 2, 3, 4, 5, 6, 7);
+    return __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, b, c, 0, 0, 0, 0x7F7F7F7F, 0, 0x7F7F7F7F);
 }
 
 template <bool FIXED, int WC, int WQ, bool F8 = false>
@@ -459,119 +479,208 @@ __global__ __launch_bounds__(Cfg::NT) __attribute__((amdgpu_waves_per_eu(2, 2)))
     // inverse lengths ride along as one more load now and then, which only makes a wait stricter; they
     // are older than the slab issued with them, so they have landed one barrier later at the latest,
     // and the epilogue of their tile comes after that barrier because a tile has at least two slabs.)
-    constexpr int NF = WC + WQ;  // fragment reads per step
-    bf16x8 af[2][WC], bf[2][WQ];
-    for (int i = 0; i < NSTAGE && i < T; ++i) issue();
-    if (T >= NSTAGE) vm_wait<(NSTAGE - 1) * NL>();
-    else vm_wait<0>();
-    __syncthreads();
-    lds_frags<SUB>(af[0], bf[0], row_a + so[0], row_b + so[0]);
-
     int ct = ct_begin, ks = 0;
-    unsigned sto = 0;  // byte offset of the stage of slab t
-    for (int t = 0; t < T; ++t) {
-        const unsigned sto_next = (sto + STAGE == NSTAGE * STAGE) ? 0u : sto + STAGE;
-#pragma unroll
-        for (int kk = 0; kk < KK - 1; ++kk) {
-            lds_frags<SUB>(af[(kk + 1) & 1], bf[(kk + 1) & 1], row_a + sto + so[kk + 1], row_b + sto + so[kk + 1]);
-            lds_wait<NF>(af[kk & 1], bf[kk & 1]);
-            __builtin_amdgcn_sched_barrier(0);
-            if (kk == 0 && ks == 0) {
-                // first step of a tile: start from zero instead of clearing the accumulators
-                static_for<0, WC>([&](auto ia) {
-                    static_for<0, WQ>([&](auto ib) {
-                        constexpr int A = decltype(ia)::value, B = decltype(ib)::value;
-                        acc.template first<A, B>(af[0][A], bf[0][B]);
-                    });
-                });
-            } else {
-                static_for<0, WC>([&](auto ia) {
-                    static_for<0, WQ>([&](auto ib) {
-                        constexpr int A = decltype(ia)::value, B = decltype(ib)::value;
-                        acc.template mac<A, B>(af[kk & 1][A], bf[kk & 1][B]);
-                    });
-                });
-            }
-            __builtin_amdgcn_sched_barrier(0);
-        }
-        lds_wait<0>(af[1], bf[1]);
-        if (t + NSTAGE <= T) vm_wait<(NSTAGE - 2) * NL>();
-        else vm_wait<0>();
-        __syncthreads();
-        if (t + NSTAGE < T) issue();
-        if (t + 1 < T) lds_frags<SUB>(af[0], bf[0], row_a + sto_next + so[0], row_b + sto_next + so[0]);
-        __builtin_amdgcn_sched_barrier(0);
+    // A tile is done: its products are scaled by 1/|c| and folded into the running maximum of each query
+    // column.  (The tile and the buffer of its inverse lengths come by value: counters that a closure
+    // changes through a reference stay in memory.)
+    auto fold_tile = [&](const int tile, const int inv_buf) {
+        const long c0 = (long)tile * BC;
+        const float *inv_t = inv_s + inv_buf * BC;
         static_for<0, WC>([&](auto ia) {
-            static_for<0, WQ>([&](auto ib) {
-                constexpr int A = decltype(ia)::value, B = decltype(ib)::value;
-                acc.template mac<A, B>(af[1][A], bf[1][B]);
-            });
-        });
-        __builtin_amdgcn_sched_barrier(0);
-        if (ks == nk - 1) {
-            // tile done: scale by 1/|c|, fold into the running maximum of each query column
-            const long c0 = (long)ct * BC;
-            const float *inv_t = inv_s + cp_inv * BC;
-            cp_inv = cp_inv + 1 == NINV ? 0 : cp_inv + 1;
-            static_for<0, WC>([&](auto ia) {
-                constexpr int A = decltype(ia)::value;
-                const int rb = (wc * WC + A) * 32;
-                f32x4 w[4];
+            constexpr int A = decltype(ia)::value;
+            const int rb = (wc * WC + A) * 32;
+            f32x4 w[4];
 #pragma unroll
-                for (int g = 0; g < 4; ++g) w[g] = *(const f32x4 *)(inv_t + rb + 8 * g + 4 * h);
-                const unsigned grp = (unsigned)((c0 + rb) >> 2) + (unsigned)h;  // group of four rows: 8 * run + 2 * g + h
-                static_for<0, WQ>([&](auto ib) {
-                    constexpr int B = decltype(ib)::value;
-                    float m = -INFINITY;
-                    if constexpr (COLLECT) {
+            for (int g = 0; g < 4; ++g) w[g] = *(const f32x4 *)(inv_t + rb + 8 * g + 4 * h);
+            const unsigned grp = (unsigned)((c0 + rb) >> 2) + (unsigned)h;  // group of four rows: 8 * run + 2 * g + h
+            static_for<0, WQ>([&](auto ib) {
+                constexpr int B = decltype(ib)::value;
+                float m = -INFINITY;
+                if constexpr (COLLECT) {
+                    static_for<0, 16>([&](auto ii) {
+                        constexpr int I = decltype(ii)::value;
+                        m = fmaxf(m, acc.template get<A, B, I>() * w[I >> 2][I & 3]);
+                    });
+                    if (__ballot(m >= tq[B]) != 0) {
+                        const long q = q0 + (wq * WQ + B) * 32 + l32;
+                        const int row0 = (int)(c0 + rb) + 4 * h;  // register I holds row row0 + 8 * (I / 4) + I % 4
                         static_for<0, 16>([&](auto ii) {
                             constexpr int I = decltype(ii)::value;
-                            m = fmaxf(m, acc.template get<A, B, I>() * w[I >> 2][I & 3]);
-                        });
-                        if (__ballot(m >= tq[B]) != 0) {
-                            const long q = q0 + (wq * WQ + B) * 32 + l32;
-                            const int row0 = (int)(c0 + rb) + 4 * h;  // register I holds row row0 + 8 * (I / 4) + I % 4
-                            static_for<0, 16>([&](auto ii) {
-                                constexpr int I = decltype(ii)::value;
-                                // (the weights of rows past the end are NaN: never listed)
-                                if (acc.template get<A, B, I>() * w[I >> 2][I & 3] >= tq[B]) {
-                                    const int slot = atomicAdd(cand_cnt + q, 1);
-                                    if (slot < cand_cap) cand[(size_t)q * cand_cap + slot] = row0 + 8 * (I >> 2) + (I & 3);
-                                }
-                            });
-                        }
-                    } else if constexpr (Cfg::ROWS) {
-                        // the rows of a lane ascend with the register number, the tiles of a workgroup with
-                        // time: ">" keeps the lowest row among equal values
-                        unsigned mi = 0;
-                        static_for<0, 16>([&](auto ii) {
-                            constexpr int I = decltype(ii)::value;
-                            const float v = acc.template get<A, B, I>() * w[I >> 2][I & 3];
-                            if (v > m) {
-                                m = v;
-                                mi = (unsigned)(8 * (I >> 2) + (I & 3));
+                            // (the weights of rows past the end are NaN: never listed)
+                            if (acc.template get<A, B, I>() * w[I >> 2][I & 3] >= tq[B]) {
+                                const int slot = atomicAdd(cand_cnt + q, 1);
+                                if (slot < cand_cap) cand[(size_t)q * cand_cap + slot] = row0 + 8 * (I >> 2) + (I & 3);
                             }
                         });
-                        if (m > bv[B]) {
-                            bv[B] = m;
-                            bb[B] = (unsigned)(c0 + rb) + 4u * (unsigned)h + mi;
-                        }
-                    } else {
-                        unsigned g;
-                        block_max<A, B>(acc, w, m, g);
-                        if (m > bv[B]) {
-                            bv[B] = m;
-                            bb[B] = grp + 2u * g;
-                        }
                     }
+                } else if constexpr (Cfg::ROWS) {
+                    // the rows of a lane ascend with the register number, the tiles of a workgroup with
+                    // time: ">" keeps the lowest row among equal values
+                    unsigned mi = 0;
+                    static_for<0, 16>([&](auto ii) {
+                        constexpr int I = decltype(ii)::value;
+                        const float v = acc.template get<A, B, I>() * w[I >> 2][I & 3];
+                        if (v > m) {
+                            m = v;
+                            mi = (unsigned)(8 * (I >> 2) + (I & 3));
+                        }
+                    });
+                    if (m > bv[B]) {
+                        bv[B] = m;
+                        bb[B] = (unsigned)(c0 + rb) + 4u * (unsigned)h + mi;
+                    }
+                } else {
+                    unsigned g;
+                    block_max<A, B>(acc, w, m, g);
+                    if (m > bv[B]) {
+                        bv[B] = m;
+                        bb[B] = grp + 2u * g;
+                    }
+                }
+            });
+        });
+    };
+    if constexpr (Cfg::K64) {
+        // 64-deep MFMAs over codes: a slab of 128 codes is two steps; per step a lane reads two 16-byte chunks
+        // of its row of either operand (chunks 4 s + 2 h and 4 s + 2 h + 1: every lane takes them in this order,
+        // so both operands pair the same codes).  The fragments of a step are 32 bytes per block row: with six
+        // block rows two buffers of them do not fit beside 128 accumulators, so the A fragments have one buffer
+        // (a block row's fragment is read again, for the next step, behind the last MFMA that uses it: an MFMA
+        // has taken its operands when the next instruction issues, and LDS data takes far longer to come) and
+        // the B fragments two.  LDS operations complete in order; outstanding at the wait of a step, oldest
+        // first: B of this step, A of this step, B of the next step.
+        constexpr int KS = RB / 64;
+        static_assert(KS == 2, "two steps per slab");
+        bf16x8 al[WC], ah[WC], bl[2][WQ], bh[2][WQ];
+        unsigned so0[KS], so1[KS];
+#pragma unroll
+        for (int st = 0; st < KS; ++st) {
+            so0[st] = (unsigned)(((4 * st + 2 * h) ^ sw) * 16);
+            so1[st] = (unsigned)(((4 * st + 2 * h + 1) ^ sw) * 16);
+        }
+        auto read_b = [&](auto bufc, unsigned base, int st) __attribute__((always_inline)) {
+            constexpr int buf = decltype(bufc)::value;
+            static_for<0, WQ>([&](auto ib) __attribute__((always_inline)) {
+                constexpr int B = decltype(ib)::value;
+                bl[buf][B] = lds_frag<B * SUB>(row_b + base + so0[st]);
+                bh[buf][B] = lds_frag<B * SUB>(row_b + base + so1[st]);
+            });
+        };
+        auto read_a = [&](auto ia, unsigned base, int st) __attribute__((always_inline)) {
+            constexpr int A = decltype(ia)::value;
+            al[A] = lds_frag<A * SUB>(row_a + base + so0[st]);
+            ah[A] = lds_frag<A * SUB>(row_a + base + so1[st]);
+        };
+        auto wait_all_but = [&](auto nn) __attribute__((always_inline)) {
+            lds_wait64<decltype(nn)::value>(al, ah, bl, bh);
+        };
+        // one step: the MFMAs of block row A, then that row's fragment of the next step (from `next`, step nst)
+        auto step = [&](auto bufc, bool first, unsigned next, int nst) __attribute__((always_inline)) {
+            constexpr int buf = decltype(bufc)::value;
+            static_for<0, WC>([&](auto ia) __attribute__((always_inline)) {
+                constexpr int A = decltype(ia)::value;
+                static_for<0, WQ>([&](auto ib) __attribute__((always_inline)) {
+                    constexpr int B = decltype(ib)::value;
+                    const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+                    acc.v[A][B] = frag_mma64(al[A], ah[A], bl[buf][B], bh[buf][B], first ? zero : acc.v[A][B]);
+                });
+                __builtin_amdgcn_sched_barrier(0);
+                read_a(ia, next, nst);
+                __builtin_amdgcn_sched_barrier(0);
+            });
+        };
+        for (int i = 0; i < NSTAGE && i < T; ++i) issue();
+        if (T >= NSTAGE) vm_wait<(NSTAGE - 1) * NL>();
+        else vm_wait<0>();
+        __syncthreads();
+        read_b(IC<0>{}, 0u, 0);
+        static_for<0, WC>([&](auto ia) __attribute__((always_inline)) { read_a(ia, 0u, 0); });
+        unsigned sto = 0;  // byte offset of the stage of slab t
+        for (int t = 0; t < T; ++t) {
+            const unsigned sto_next = (sto + STAGE == NSTAGE * STAGE) ? 0u : sto + STAGE;
+            read_b(IC<1>{}, sto, 1);
+            wait_all_but(IC<2 * WQ>{});
+            __builtin_amdgcn_sched_barrier(0);
+            if (ks == 0) step(IC<0>{}, true, sto, 1);
+            else step(IC<0>{}, false, sto, 1);
+            wait_all_but(IC<0>{});
+            if (t + NSTAGE <= T) vm_wait<(NSTAGE - 2) * NL>();
+            else vm_wait<0>();
+            __syncthreads();
+            if (t + NSTAGE < T) issue();
+            // (behind the last slab these read the stage of a slab that does not exist: within LDS, never used)
+            read_b(IC<0>{}, sto_next, 0);
+            __builtin_amdgcn_sched_barrier(0);
+            step(IC<1>{}, false, sto_next, 0);
+            if (ks == nk - 1) {
+                fold_tile(ct, cp_inv);
+                cp_inv = cp_inv + 1 == NINV ? 0 : cp_inv + 1;
+                ks = 0;
+                ++ct;
+            } else {
+                ++ks;
+            }
+            sto = sto_next;
+        }
+    } else {
+        constexpr int NF = WC + WQ;  // fragment reads per step
+        bf16x8 af[2][WC], bf[2][WQ];
+        for (int i = 0; i < NSTAGE && i < T; ++i) issue();
+        if (T >= NSTAGE) vm_wait<(NSTAGE - 1) * NL>();
+        else vm_wait<0>();
+        __syncthreads();
+        lds_frags<SUB>(af[0], bf[0], row_a + so[0], row_b + so[0]);
+
+        unsigned sto = 0;  // byte offset of the stage of slab t
+        for (int t = 0; t < T; ++t) {
+            const unsigned sto_next = (sto + STAGE == NSTAGE * STAGE) ? 0u : sto + STAGE;
+    #pragma unroll
+            for (int kk = 0; kk < KK - 1; ++kk) {
+                lds_frags<SUB>(af[(kk + 1) & 1], bf[(kk + 1) & 1], row_a + sto + so[kk + 1], row_b + sto + so[kk + 1]);
+                lds_wait<NF>(af[kk & 1], bf[kk & 1]);
+                __builtin_amdgcn_sched_barrier(0);
+                if (kk == 0 && ks == 0) {
+                    // first step of a tile: start from zero instead of clearing the accumulators
+                    static_for<0, WC>([&](auto ia) {
+                        static_for<0, WQ>([&](auto ib) {
+                            constexpr int A = decltype(ia)::value, B = decltype(ib)::value;
+                            acc.template first<A, B>(af[0][A], bf[0][B]);
+                        });
+                    });
+                } else {
+                    static_for<0, WC>([&](auto ia) {
+                        static_for<0, WQ>([&](auto ib) {
+                            constexpr int A = decltype(ia)::value, B = decltype(ib)::value;
+                            acc.template mac<A, B>(af[kk & 1][A], bf[kk & 1][B]);
+                        });
+                    });
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            lds_wait<0>(af[1], bf[1]);
+            if (t + NSTAGE <= T) vm_wait<(NSTAGE - 2) * NL>();
+            else vm_wait<0>();
+            __syncthreads();
+            if (t + NSTAGE < T) issue();
+            if (t + 1 < T) lds_frags<SUB>(af[0], bf[0], row_a + sto_next + so[0], row_b + sto_next + so[0]);
+            __builtin_amdgcn_sched_barrier(0);
+            static_for<0, WC>([&](auto ia) {
+                static_for<0, WQ>([&](auto ib) {
+                    constexpr int A = decltype(ia)::value, B = decltype(ib)::value;
+                    acc.template mac<A, B>(af[1][A], bf[1][B]);
                 });
             });
-            ks = 0;
-            ++ct;
-        } else {
-            ++ks;
+            __builtin_amdgcn_sched_barrier(0);
+            if (ks == nk - 1) {
+                fold_tile(ct, cp_inv);
+                cp_inv = cp_inv + 1 == NINV ? 0 : cp_inv + 1;
+                ks = 0;
+                ++ct;
+            } else {
+                ++ks;
+            }
+            sto = sto_next;
         }
-        sto = sto_next;
     }
     if constexpr (!COLLECT) {
         __syncthreads();
@@ -1103,6 +1212,9 @@ typedef PipeCfg<4, 2, 2, 4, 4, 32> PipeLarge32;  // 256 x 256 tile, slabs of 32 
 typedef PipeCfg<4, 2, 2, 4, 2, 128, true, 1> F8Large;
 typedef PipeCfg<2, 2, 4, 2, 3, 128, true, 1> F8Mid;
 typedef PipeCfg<1, 2, 8, 1, 3, 128, true, 1> F8Small;
+typedef PipeCfg<4, 2, 2, 4, 2, 128, true, 1, true> F8Large64;  // the same three tiles on 64-deep MFMAs
+typedef PipeCfg<2, 2, 4, 2, 3, 128, true, 1, true> F8Mid64;
+typedef PipeCfg<1, 2, 8, 1, 3, 128, true, 1, true> F8Small64;
 
 // ----------------------------------------------------------------------------
 // host side
@@ -1118,6 +1230,11 @@ static bool pipe_plan(const siso_cache *c, long n, int cfg, long want_wgs, PipeP
     if (c->dtype == SISO_FP8) {  // slabs of 128 codes, at least two per tile
         if (c->dim % 128 != 0 || c->dim < 256) return false;
         if (cfg == 4 || cfg == 5) cfg = 1;
+        if (cfg >= 6 && cfg <= 8) {  // the three tiles on 64-deep MFMAs (plans like configurations 1 to 3)
+            const bool ok = pipe_plan(c, n, cfg - 5, want_wgs, p);
+            p->cfg = cfg;
+            return ok;
+        }
     } else if (c->dtype != SISO_BF16 || c->dim % 64 != 0 || c->dim < 128) {
         return false;
     }
@@ -1167,6 +1284,7 @@ static bool pipe_plan(const siso_cache *c, long n, int cfg, long want_wgs, PipeP
 
 static bool mfma_plan(const siso_cache *c, long n, PipePlan *p) {
     int cfg = c->opt_mfma_config;
+    if (cfg == 0 && c->dtype == SISO_FP8) cfg = n <= 64 ? 8 : n <= 128 ? 7 : 6;  // the 64-deep MFMAs
     if (cfg == 0) cfg = n <= 64 ? 3 : n <= 128 ? 2 : 5;
     // about two workgroups per compute unit when there is enough work
     return pipe_plan(c, n, cfg, 512, p);
@@ -1175,7 +1293,7 @@ static bool mfma_plan(const siso_cache *c, long n, PipePlan *p) {
 static bool skinny_plan(const siso_cache *c, long n, PipePlan *p) {
     if (n > 64) return false;
     // exactly one workgroup per compute unit: every one streams an equal share of the centroids
-    return pipe_plan(c, n, 3, 256, p);
+    return pipe_plan(c, n, c->dtype == SISO_FP8 && c->opt_mfma_config != 3 ? 8 : 3, 256, p);
 }
 
 template <class Cfg>
@@ -1230,6 +1348,9 @@ static int pipe_launch(siso_cache *c, const void *queries, long n, const PipePla
         switch (p.cfg) {
             case 2: return launch_cfg<F8Mid>(c, queries, n, p, keys);
             case 3: return launch_cfg<F8Small>(c, queries, n, p, keys);
+            case 6: return launch_cfg<F8Large64>(c, queries, n, p, keys);
+            case 7: return launch_cfg<F8Mid64>(c, queries, n, p, keys);
+            case 8: return launch_cfg<F8Small64>(c, queries, n, p, keys);
             default: return launch_cfg<F8Large>(c, queries, n, p, keys);
         }
     }

@@ -130,3 +130,8 @@ def fixed_fragment_users_not_hand_placed(lines, first=208):
         return []
     return [l for l in lines if "hand-placed" not in l and not l.endswith(":")
             and any(r >= first for r in _regs(l.split(";")[0]))]
+
+
+def private_segment_sizes(asm: str):
+    """kernel name -> bytes of per-lane scratch memory the compiler gave it (0 = everything in registers)"""
+    return {m.group(1): int(m.group(2)) for m in re.finditer(r"\.set (\S+)\.private_seg_size, (\d+)", asm)}

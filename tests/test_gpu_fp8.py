@@ -25,22 +25,27 @@ def siso():
     return m
 
 
-def load_fp8(siso, wl, capacity=None):
+def load_fp8(siso, wl, capacity=None, cfg=0):
     cache = siso.SisoCache(wl.dim, capacity or max(wl.K, 1), siso.FP8)
+    cache.set_option("mfma_config", cfg)
     cache.load(to_dev(wl.centroids, "bf16"))
     return cache
 
 
-@pytest.mark.parametrize("dim,K,n", [(256, 5000, 300), (768, 2049, 513), (1024, 1500, 64), (512, 70000, 33), (256, 37, 700),
-                                      (384, 3000, 100), (4096, 600, 130), (768, 9000, 1)])
-def test_fp8_storage_and_lookup_vs_oracle(siso, oracle, dim, K, n):
-    print(f"case: fp8 dim={dim} K={K} n={n}", flush=True)
+@pytest.mark.parametrize("dim,K,n,cfg", [(256, 5000, 300, 0), (768, 2049, 513, 0), (1024, 1500, 64, 0), (512, 70000, 33, 0),
+                                          (256, 37, 700, 0), (384, 3000, 100, 0), (4096, 600, 130, 0), (768, 9000, 1, 0),
+                                          (256, 5000, 300, 1), (768, 2049, 513, 1), (1024, 3000, 100, 2), (512, 70000, 33, 3),
+                                          (1024, 3000, 700, 6), (512, 700, 2000, 6)])
+def test_fp8_storage_and_lookup_vs_oracle(siso, oracle, dim, K, n, cfg):
+    print(f"case: fp8 dim={dim} K={K} n={n} cfg={cfg}", flush=True)
     wl = W.c2_mid(n_clusters=128, per_cluster=(K + 127) // 128, n_queries=n, dim=dim, seed=501)
     wl.centroids = wl.centroids[:K].copy()
     r = np.random.default_rng(dim + n)
     c = wl.centroids_f32() * np.exp2(r.integers(-3, 4, size=K)).astype(np.float32)[:, None]   # rows of different lengths
     wl.centroids = W.f32_to_bf16_bits(c)
-    cache = load_fp8(siso, wl, K + 5)
+    cache = load_fp8(siso, wl, K + 5, cfg)
+    if cfg in (1, 2, 6):
+        cache.set_lookup_path(siso.PATH_MFMA)
     codes, scales, sizes = cache.export_fp8()
     oc, os_ = oracle.fp8_quantize(wl.centroids, "bf16")
     assert np.array_equal(codes.cpu().numpy(), oc), "stored codes differ from the oracle's"

@@ -28,3 +28,14 @@ def test_no_instruction_touches_a_fragment_register_in_flight(source):
         assert not early, f"{name}: accumulator read too close behind its MFMA: {early[:3]}"
         checked += 1
     assert checked >= 3
+
+
+@pytest.mark.skipif(shutil.which("hipcc") is None, reason="needs hipcc")
+def test_the_mfma_kernels_keep_everything_in_registers():
+    """A counter or an accumulator that ends up in per-lane scratch memory costs a memory round trip in
+    every slab of the pipelined kernels: no kernel of the file may have a private segment."""
+    sizes = isa_check.private_segment_sizes(isa_check.device_asm("lookup_mfma.hip"))
+    pipe = [k for k in sizes if "k_lookup_pipe" in k]
+    assert len(pipe) >= 10 and any("k_lookup_wide" in k for k in sizes)
+    spilled = {k: v for k, v in sizes.items() if v}
+    assert not spilled, spilled
