@@ -31,7 +31,8 @@ int siso_set_lookup_path(siso_cache *c, int path);
  *                     5 = 256x256 with four waves of 128x128; 8-bit caches: 6, 7, 8 = the tiles of 1, 2, 3 on the
  *                     64-deep fp8 MFMA (their default), 1, 2, 3 = the same on the 16-deep one
  *   "tiles_per_slice" 0 = default; >0 = centroid tiles one workgroup walks through
- *   "merge_config"    0 = default; 1 = use the scalar pair search
+ *   "merge_config"    0 = default (bf16: the eight-wave MFMA pair search); 1 = use the scalar pair search;
+ *                     2 = the four-wave MFMA pair search (128x128 per wave)
  *   "mfma_qblock"     0 = default; 1, 2, 4, 8, 16, 32 = query tiles that share an XCD's centroid tiles
  *   "second_set"      1 = allocate now the second set of arrays that siso_merge_apply and siso_refresh
  *                     gather the rebuilt cache into (otherwise their first call does); synchronises

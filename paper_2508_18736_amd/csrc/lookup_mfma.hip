@@ -1006,6 +1006,12 @@ __global__ __launch_bounds__(WideCfg::NT) __attribute__((amdgpu_waves_per_eu(1, 
     const bf16_t *qbase = Q + (size_t)q0 * d;
     const unsigned lds0 = (unsigned)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)smem;
     unsigned char *wr = smem + wave * 1024 + lane * 16;  // this lane's 16 bytes of load 0 in stage 0
+    // (and in stage 1, as a value of its own: an LDS instruction's offset field ends at 64 KiB, and the
+    // compiler would rather keep one address per write of that stage than one base)
+    typedef __attribute__((address_space(3))) unsigned char lds_byte;
+    typedef __attribute__((address_space(3))) u32x4 lds_u32x4;
+    lds_byte *wr1 = (lds_byte *)(wr + STAGE);
+    asm volatile("" : "+v"(wr1));
 
     // fragment read addresses, as in k_lookup_pipe
     const int sw = (l32 >> 1) & 7;
@@ -1080,7 +1086,8 @@ __global__ __launch_bounds__(WideCfg::NT) __attribute__((amdgpu_waves_per_eu(1, 
             if (gs >= 0) inv_s[gs * BC + wave * 64 + lane] = gi;
         }
         // loads 0 .. NLA-1 fill the centroid rows of the stage, the others the query rows behind them
-        *(u32x4 *)(wr + p * STAGE + j * NW * 1024) = G[p][j];
+        if constexpr (p == 0) *(u32x4 *)(wr + j * NW * 1024) = G[p][j];
+        else *(lds_u32x4 *)(wr1 + j * NW * 1024) = G[p][j];
     };
     // One step = 16 MFMAs, block (A, B) = A fragment A x B fragment B of buffer `cur`, A-major.  The
     // fragments of the next step are read meanwhile: the four B fragments behind the first four
@@ -1202,6 +1209,258 @@ __global__ __launch_bounds__(WideCfg::NT) __attribute__((amdgpu_waves_per_eu(1, 
     asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");  // reads, loads and writes of the tail have landed
     lds_barrier();
     pipe_reduce_keys<WQ, NWC, BQ, NT>(bv, bb, smem, wc, wq, h, l32, tid, q0, n, slices, s, keys);
+}
+
+// ----------------------------------------------------------------------------
+// Pair search on the wide tile: the stream of tile pairs of k_pairs_stream (same units, same order, same
+// staging of the pairs found) through the pipeline of k_lookup_wide.  Both operands are tiles of the
+// centroid array (rows past the live ones exist and have NaN for an inverse length, so they never
+// reach the threshold); the inverse lengths of both tiles travel with the first slab of a pair into
+// one of two buffers, by the parity of the pair's number: the slab is written to LDS two slabs before
+// its first MFMA, i.e. (a pair has at least two slabs) behind the barrier that follows the epilogue
+// of the pair before the previous one.
+// ----------------------------------------------------------------------------
+__global__ __launch_bounds__(WideCfg::NT) __attribute__((amdgpu_waves_per_eu(1, 1), amdgpu_num_vgpr(WIDE_FRAG0))) void k_pairs_wide(
+    const bf16_t *__restrict__ C, const float *__restrict__ invn, long K, int d, int qb, float threshold,
+    int *__restrict__ out_pairs, long cap, u64 *__restrict__ counter) {
+    typedef WideCfg Cfg;
+    constexpr int WC = Cfg::WC, WQ = Cfg::WQ, NWC = Cfg::NWC, BC = Cfg::BC, BQ = Cfg::BQ, NW = Cfg::NW, STAGE = Cfg::STAGE,
+                  NLA = Cfg::NLA, NL = Cfg::NL, BK = Cfg::BK, RB = Cfg::RB, KK = Cfg::KK, SUB = 32 * Cfg::RB;
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    float *inv_a = (float *)(smem + 2 * STAGE);  // [2][BC] inverse lengths of the row tile, by parity of the pair's number
+    float *inv_b = inv_a + 2 * BC;               // [2][BQ] and of the column tile
+    int *stage = (int *)(inv_b + 2 * BQ);        // [PAIR_STAGE][2] pairs found, moved to the global list when half full
+    int *staged = stage + 2 * PAIR_STAGE;
+    u64 *flush_slot = (u64 *)(staged + 2);
+    unsigned short *masks = (unsigned short *)(flush_slot + 1);  // [NW][WC * WQ][64]: per wave, hit block and lane
+    if (threadIdx.x == 0) *staged = 0;
+
+    const int tid = threadIdx.x;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
+    const int wc = wave % NWC, wq = wave / NWC;
+    const int h = lane >> 5, l32 = lane & 31;
+    const int nk = d / BK;
+    const int tiles = (int)((K + BC - 1) / BC);
+
+    // the pairs of this workgroup: counted once, then the same sequence twice (loads run ahead of the MFMAs)
+    PairItems ld_items, cp_items;
+    ld_items.init(tiles, qb);
+    cp_items.init(tiles, qb);
+    int ld_qt = 0, ld_ct = 0, cp_qt = 0, cp_ct = 0;
+    int npairs = 0;
+    while (cp_items.next(cp_qt, cp_ct)) ++npairs;
+    if (npairs == 0) return;
+    const int T = npairs * nk;  // slabs this workgroup walks through
+    cp_items.init(tiles, qb);
+    cp_items.next(cp_qt, cp_ct);
+    ld_items.next(ld_qt, ld_ct);
+
+    // global loads and LDS layout as in k_lookup_wide
+    const int lr = lane >> 3, slot = lane & 7;
+    const int row0 = wave * 8 + lr;
+    const unsigned chunk = (unsigned)((slot ^ ((row0 >> 1) & 7)) * 16);
+    const unsigned a_voff = (unsigned)row0 * (unsigned)d * 2u + chunk;
+    const unsigned lds0 = (unsigned)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)smem;
+    unsigned char *wr = smem + wave * 1024 + lane * 16;  // this lane's 16 bytes of load 0 in stage 0
+    // (and in stage 1, as a value of its own: an LDS instruction's offset field ends at 64 KiB, and the
+    // compiler would rather keep one address per write of that stage than one base)
+    typedef __attribute__((address_space(3))) unsigned char lds_byte;
+    typedef __attribute__((address_space(3))) u32x4 lds_u32x4;
+    lds_byte *wr1 = (lds_byte *)(wr + STAGE);
+    asm volatile("" : "+v"(wr1));
+    const int sw = (l32 >> 1) & 7;
+    const unsigned row_a = lds0 + (unsigned)(((wc * WC) * 32 + l32) * RB);
+    const unsigned row_b = lds0 + (unsigned)(BC * RB + ((wq * WQ) * 32 + l32) * RB);
+    // swizzled 16-byte slot of step kk: ((2 kk + h) ^ sw) * 16 = so0 ^ 32 kk (one register instead of four)
+    const unsigned so0 = (unsigned)((h ^ sw) * 16);
+
+    Acc<true, WC, WQ> acc;
+    acc.reserve();
+
+    u32x4 G[2][NL];
+    float ga0 = 0.f, ga1 = 0.f, gb0 = 0.f, gb1 = 0.f;  // inverse lengths that travel with a pair's first slab
+    int gs0 = -1, gs1 = -1;                            // their buffer (parity of the pair's number), -1 = none
+    const char *ld_c = (const char *)(C + (size_t)ld_ct * BC * d);  // first element of the slab to load, row tile
+    const char *ld_q = (const char *)(C + (size_t)ld_qt * BQ * d);  // and column tile
+    int ld_t = 0, ld_ks = 0, ld_seq = 0;
+    auto load_part = [&](auto pp, auto jj) __attribute__((always_inline)) {
+        constexpr int p = decltype(pp)::value, j = decltype(jj)::value;
+        if constexpr (j == 0) {
+            float &ga = p == 0 ? ga0 : ga1;
+            float &gb = p == 0 ? gb0 : gb1;
+            int &gs = p == 0 ? gs0 : gs1;
+            gs = -1;
+            if (ld_ks == 0) {
+                ga = invn[(size_t)ld_ct * BC + wave * 64 + lane];
+                gb = invn[(size_t)ld_qt * BQ + wave * 64 + lane];
+                gs = ld_seq & 1;
+            }
+        }
+        // (the 32-bit offset is summed up next to its use: a scalar base, the same eight row offsets for both tiles)
+        unsigned off = a_voff;
+        asm volatile("" : "+v"(off));
+        off += (unsigned)((j % NLA) * 64) * (unsigned)d;
+        if constexpr (j < NLA) G[p][j] = *(const u32x4 *)(ld_c + off);
+        else G[p][j] = *(const u32x4 *)(ld_q + off);
+        if constexpr (j == NL - 1) {
+            if (ld_t + 1 < T) {
+                ++ld_t;
+                if (++ld_ks == nk) {
+                    ld_ks = 0;
+                    ++ld_seq;
+                    ld_items.next(ld_qt, ld_ct);
+                    ld_c = (const char *)(C + (size_t)ld_ct * BC * d);
+                    ld_q = (const char *)(C + (size_t)ld_qt * BQ * d);
+                } else {
+                    ld_c += BK * 2;
+                    ld_q += BK * 2;
+                }
+            }
+        }
+    };
+    auto write_part = [&](auto pp, auto jj) __attribute__((always_inline)) {
+        constexpr int p = decltype(pp)::value, j = decltype(jj)::value;
+        if constexpr (j == 0) {
+            const int gs = p == 0 ? gs0 : gs1;
+            if (gs >= 0) {
+                inv_a[gs * BC + wave * 64 + lane] = p == 0 ? ga0 : ga1;
+                inv_b[gs * BQ + wave * 64 + lane] = p == 0 ? gb0 : gb1;
+            }
+        }
+        if constexpr (p == 0) *(u32x4 *)(wr + j * NW * 1024) = G[p][j];
+        else *(lds_u32x4 *)(wr1 + j * NW * 1024) = G[p][j];
+    };
+    // steps, barriers and the dealing out of loads and writes between the MFMAs: see k_lookup_wide
+    auto step = [&](auto first_tag, auto cur_tag, unsigned addr_a, unsigned addr_b, auto &&extra) __attribute__((always_inline)) {
+        constexpr int cur = decltype(cur_tag)::value;
+        lgkm_wait<1>();
+        static_for<0, WC * WQ>([&](auto ii) __attribute__((always_inline)) {
+            constexpr int i = decltype(ii)::value, A = i / WQ, B = i % WQ;
+            if constexpr (i == (WC - 1) * WQ) lgkm_wait<4>();
+            if constexpr (decltype(first_tag)::value) frag_first<16 * i, Cfg::ra(A), Cfg::rb(cur, B)>();
+            else frag_mac<16 * i, Cfg::ra(A), Cfg::rb(cur, B)>();
+            extra(ii);
+            if constexpr (i < WQ) frag_read<Cfg::rb(1 - cur, i), i * SUB>(addr_b);
+            if constexpr (B == WQ - 1) frag_read<Cfg::ra(A), A * SUB>(addr_a);
+        });
+    };
+    auto lds_barrier = [&]() __attribute__((always_inline)) { asm volatile("s_barrier" ::: "memory"); };
+    auto xfer = [&](auto pp, auto jj) __attribute__((always_inline)) {
+        write_part(pp, jj);
+        load_part(pp, jj);
+    };
+    static_for<0, NL>([&](auto jj) __attribute__((always_inline)) { load_part(IC<0>{}, jj); });
+    static_for<0, NL>([&](auto jj) __attribute__((always_inline)) { load_part(IC<1>{}, jj); });
+    static_for<0, NL>([&](auto jj) __attribute__((always_inline)) { xfer(IC<0>{}, jj); });
+    static_for<0, 4>([&](auto jj) __attribute__((always_inline)) { xfer(IC<1>{}, jj); });
+    lgkm_wait<0>();
+    lds_barrier();
+    static_for<0, WQ>([&](auto kk) __attribute__((always_inline)) {
+        constexpr int k = decltype(kk)::value;
+        frag_read<Cfg::rb(0, k), k * SUB>(row_b + so0);
+    });
+    static_for<0, WC>([&](auto kk) __attribute__((always_inline)) {
+        constexpr int k = decltype(kk)::value;
+        frag_read<Cfg::ra(k), k * SUB>(row_a + so0);
+    });
+
+    int ks = 0, cp_seq = 0;
+    static_assert(KK == 4, "steps are spelled out");
+    auto slab = [&](auto pp) __attribute__((always_inline)) {
+        constexpr int p = decltype(pp)::value;
+        constexpr unsigned sto = p * STAGE, sto_next = (1 - p) * STAGE;
+        auto at = [&](unsigned row, unsigned stg, int k) __attribute__((always_inline)) {
+            unsigned sk = so0;
+            asm volatile("" : "+v"(sk));  // (summed up here every time instead of kept)
+            return (sk ^ (unsigned)(k * 32)) + (row + stg);
+        };
+        auto part = [&](auto bb_, auto j0, auto ii) __attribute__((always_inline)) {
+            constexpr int i = decltype(ii)::value;
+            if constexpr (i % 4 == 1) xfer(bb_, IC<decltype(j0)::value + i / 4>{});
+        };
+        if (ks == 0)  // a pair starts from zero
+            step(IC<1>{}, IC<0>{}, at(row_a, sto, 1), at(row_b, sto, 1), [&](auto ii) __attribute__((always_inline)) { part(IC<1 - p>{}, IC<4>{}, ii); });
+        else
+            step(IC<0>{}, IC<0>{}, at(row_a, sto, 1), at(row_b, sto, 1), [&](auto ii) __attribute__((always_inline)) { part(IC<1 - p>{}, IC<4>{}, ii); });
+        step(IC<0>{}, IC<1>{}, at(row_a, sto, 2), at(row_b, sto, 2), [&](auto ii) __attribute__((always_inline)) { part(IC<1 - p>{}, IC<8>{}, ii); });
+        step(IC<0>{}, IC<0>{}, at(row_a, sto, 3), at(row_b, sto, 3), [&](auto ii) __attribute__((always_inline)) { part(IC<1 - p>{}, IC<12>{}, ii); });
+        lgkm_wait<0>();
+        lds_barrier();
+        step(IC<0>{}, IC<1>{}, at(row_a, sto_next, 0), at(row_b, sto_next, 0), [&](auto ii) __attribute__((always_inline)) { part(pp, IC<0>{}, ii); });
+        __builtin_amdgcn_sched_barrier(0);
+        const bool pair_done = ks == nk - 1;
+        if (pair_done) {
+            // Every product above the threshold is a pair (column index < row index).  Per block the largest
+            // product under a wave ballot; a block with a pair (few have one) leaves a bit mask of its pairs per
+            // lane in LDS, and the masks are turned into list entries afterwards, block after block, by code that
+            // exists once.
+            const long c0 = (long)cp_ct * BC, q0 = (long)cp_qt * BQ;
+            const int ahead = (int)(c0 - q0 < 4096 ? c0 - q0 : 4096);  // rows by which the row tile is ahead: 0 on the diagonal
+            const float *inv_t = inv_a + (cp_seq & 1) * BC;
+            const float *inv_q = inv_b + (cp_seq & 1) * BQ;
+            unsigned short *my_masks = masks + wave * (WC * WQ * 64) + lane;  // [hit][lane] of this wave
+            // (taken from the optimiser's sight: it would keep one register per block and product, all through the
+            // kernel, for the sums this value goes into)
+            int lane_part = l32 - 4 * h;
+            asm volatile("" : "+v"(lane_part));
+            int nhit = 0;
+            u64 hit_blocks = 0;  // four bits per hit: A * WQ + B
+            {
+                float wi[WQ];
+#pragma unroll
+                for (int b = 0; b < WQ; ++b) wi[b] = inv_q[(wq * WQ + b) * 32 + l32];
+                static_for<0, WC>([&](auto ia) __attribute__((always_inline)) {
+                    constexpr int A = decltype(ia)::value;
+                    f32x4 w[4];
+#pragma unroll
+                    for (int g = 0; g < 4; ++g) w[g] = *(const f32x4 *)(inv_t + (wc * WC + A) * 32 + 8 * g + 4 * h);
+                    static_for<0, WQ>([&](auto ib) __attribute__((always_inline)) {
+                        constexpr int B = decltype(ib)::value;
+                        const float m = fmaxf(fmaxf(group_max<A, B, 0>(acc, w[0]), group_max<A, B, 1>(acc, w[1])),
+                                              fmaxf(group_max<A, B, 2>(acc, w[2]), group_max<A, B, 3>(acc, w[3])));
+                        if (__ballot(m * wi[B] > threshold) != 0) {
+                            // product I belongs to row (wc * WC + A) * 32 + 4 * h + 8 * (I / 4) + I % 4 of the row tile,
+                            // which is a pair if the column comes before it: column - first row < 8 * (I / 4) + I % 4
+                            const int before = lane_part - ahead + ((wq * WQ + B) - (wc * WC + A)) * 32;
+                            unsigned found = 0;
+                            static_for<0, 16>([&](auto ii) __attribute__((always_inline)) {
+                                constexpr int I = decltype(ii)::value;
+                                const float sim = acc.template get<A, B, I>() * w[I >> 2][I & 3] * wi[B];
+                                if (sim > threshold && before < 8 * (I >> 2) + (I & 3)) found |= 1u << I;
+                            });
+                            my_masks[nhit * 64] = (unsigned short)found;
+                            hit_blocks |= (u64)(A * WQ + B) << (4 * nhit);
+                            ++nhit;
+                        }
+                    });
+                });
+            }
+            for (int e = 0; e < nhit; ++e) {
+                const int blk = (int)(hit_blocks >> (4 * e)) & 15;
+                const unsigned found = my_masks[e * 64];
+                const int icol = (int)q0 + (wq * WQ + blk % WQ) * 32 + l32;
+                const int jrow0 = (int)c0 + (wc * WC + blk / WQ) * 32 + 4 * h;
+                emit_pairs_staged(found, icol, [&](int I) { return jrow0 + 8 * (I >> 2) + (I & 3); }, stage, staged, PAIR_STAGE,
+                                  out_pairs, cap, counter);
+            }
+            ++cp_seq;
+            cp_items.next(cp_qt, cp_ct);
+            // the pairs of this tile pair are staged (own LDS traffic done, then the barrier by hand: the
+            // compiler's barrier would also wait for the global loads in flight)
+            asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+            if (*staged > PAIR_STAGE / 2) flush_staged_pairs(stage, staged, PAIR_STAGE, flush_slot, out_pairs, cap, counter);
+        }
+        ks = pair_done ? 0 : ks + 1;
+    };
+    int t = 0;
+    for (; t + 1 < T; t += 2) {
+        slab(IC<0>{});
+        slab(IC<1>{});
+    }
+    if (t < T) slab(IC<0>{});
+    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");  // reads, loads and writes of the tail have landed
+    lds_barrier();
+    flush_staged_pairs(stage, staged, PAIR_STAGE, flush_slot, out_pairs, cap, counter);
 }
 
 typedef PipeCfg<4, 2, 2, 4, 2> PipeLarge;  // 256 x 256 tile, waves of 128 x 64, two stages
@@ -1432,22 +1691,35 @@ int siso_pairs_mfma_supported(const siso_cache *c, long count) {
 
 int siso_pairs_mfma_launch(siso_cache *c, const void *rows, const float *invn, long count, float threshold,
                            int *out_pairs, long cap, u64 *counter) {
-    typedef PipeLarge Cfg;
     if (((uintptr_t)rows & 15) != 0) return siso_fail(c, SISO_EINVAL, "pair search: rows must be 16-byte aligned");
     // one stream of tile pairs per workgroup, one workgroup per compute unit
-    const long T = (count + Cfg::BC - 1) / Cfg::BC;
+    const long T = (count + WideCfg::BC - 1) / WideCfg::BC;
     if (T > 1000000) return siso_fail(c, SISO_EINVAL, "pair search: too many tiles");
     int qb = 8;
     while (qb > 1 && qb > T) qb >>= 1;
-    constexpr int lds = Cfg::NSTAGE * Cfg::STAGE + 2 * Cfg::BC * 4 + 2 * Cfg::BQ * 4 + PAIR_STAGE * 8 + 16;
-    static_assert(lds <= 160 * 1024, "fits in LDS");
-    static bool stream_attr_done = false;
-    if (!stream_attr_done) {
-        hipError_t e = hipFuncSetAttribute((const void *)k_pairs_stream<Cfg>, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
-        if (e != hipSuccess) return siso_check_hip(c, e, "hipFuncSetAttribute(k_pairs_stream)");
-        stream_attr_done = true;
+    constexpr int room = 2 * WideCfg::BC * 4 + 2 * WideCfg::BQ * 4 + PAIR_STAGE * 8 + 16;  // inverse lengths, staged pairs
+    static bool attr_done[2] = {false, false};
+    if (c->opt_merge_config != 2) {  // 2 = the four-wave kernel below
+        typedef PipeLarge Cfg;
+        constexpr int lds = Cfg::NSTAGE * Cfg::STAGE + room;
+        static_assert(lds <= 160 * 1024, "fits in LDS");
+        if (!attr_done[0]) {
+            hipError_t e = hipFuncSetAttribute((const void *)k_pairs_stream<Cfg>, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+            if (e != hipSuccess) return siso_check_hip(c, e, "hipFuncSetAttribute(k_pairs_stream)");
+            attr_done[0] = true;
+        }
+        hipLaunchKernelGGL((k_pairs_stream<Cfg>), dim3(256), dim3(Cfg::NT), lds, c->stream, (const bf16_t *)rows, invn, count,
+                           c->dim, qb, threshold, out_pairs, cap, counter);
+        return siso_check_hip(c, hipGetLastError(), "k_pairs_stream");
     }
-    hipLaunchKernelGGL((k_pairs_stream<Cfg>), dim3(256), dim3(Cfg::NT), lds, c->stream, (const bf16_t *)rows, invn, count,
-                       c->dim, qb, threshold, out_pairs, cap, counter);
-    return siso_check_hip(c, hipGetLastError(), "k_pairs_stream");
+    constexpr int lds = 2 * WideCfg::STAGE + room + WideCfg::NW * WideCfg::WC * WideCfg::WQ * 64 * 2;  // and the pair masks
+    static_assert(lds <= 160 * 1024, "fits in LDS");
+    if (!attr_done[1]) {
+        hipError_t e = hipFuncSetAttribute((const void *)k_pairs_wide, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+        if (e != hipSuccess) return siso_check_hip(c, e, "hipFuncSetAttribute(k_pairs_wide)");
+        attr_done[1] = true;
+    }
+    hipLaunchKernelGGL(k_pairs_wide, dim3(256), dim3(WideCfg::NT), lds, c->stream, (const bf16_t *)rows, invn, count, c->dim, qb,
+                       threshold, out_pairs, cap, counter);
+    return siso_check_hip(c, hipGetLastError(), "k_pairs_wide");
 }

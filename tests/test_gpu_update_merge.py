@@ -162,6 +162,12 @@ def test_merge_pairs_and_groups_match_oracle(siso, oracle, dtype, dim, groups, c
     cache.set_option("merge_config", 0)
     got_s = sorted_pairs(got_s.cpu().numpy())
     assert all(edge[i, j] for i, j in set(map(tuple, got_s)) ^ set(map(tuple, got)))
+    # and so does the four-wave MFMA kernel (where the MFMA kernels apply at all, it is the other one)
+    cache.set_option("merge_config", 2)
+    got_8, total_8 = cache.merge(theta, cap=total + 100)
+    cache.set_option("merge_config", 0)
+    got_8 = sorted_pairs(got_8.cpu().numpy())
+    assert total_8 == len(got_8) and all(edge[i, j] for i, j in set(map(tuple, got_8)) ^ set(map(tuple, got)))
     # a second run gives the same set (the order of emission is free)
     again, total_a = cache.merge(theta, cap=total + 100)
     assert total_a == gtotal and np.array_equal(sorted_pairs(again.cpu().numpy()), got)
@@ -226,9 +232,12 @@ def test_merge_dense_pairs_overflow_the_staging_buffer(siso, oracle):
     oc.load(rows)
     want, total = oc.merge(0.9)
     assert total == groups * copies * (copies - 1) // 2
-    got, gtotal = cache.merge(0.9, cap=total)
-    assert gtotal == total
-    assert np.array_equal(sorted_pairs(got.cpu().numpy()), want)
+    for config in (0, 2):  # the eight-wave kernel and the four-wave one
+        cache.set_option("merge_config", config)
+        got, gtotal = cache.merge(0.9, cap=total)
+        assert gtotal == total, config
+        assert np.array_equal(sorted_pairs(got.cpu().numpy()), want), config
+    cache.set_option("merge_config", 0)
     # a cap in the middle of it all: full count, exactly cap valid pairs, no duplicates
     few, t2 = cache.merge(0.9, cap=5000)
     few = few.cpu().numpy()
