@@ -73,6 +73,8 @@ def lib() -> C.CDLL:
         L.oracle_fp8_quantize.restype = it
         L.oracle_fp8_lookup_rows.argtypes = [vp, vp, lg, it, vp, it, lg, fl, vp, vp, vp, vp]
         L.oracle_fp8_lookup_rows.restype = it
+        L.oracle_fp8_lookup_topk_rows.argtypes = [vp, vp, lg, it, vp, it, lg, it, vp, vp]
+        L.oracle_fp8_lookup_topk_rows.restype = it
         L.oracle_import.argtypes = [vp, vp, vp, vp, vp, vp, lg]
         L.oracle_import.restype = it
         L.oracle_refresh.argtypes = [vp, vp, vp, lg, fl, lg, vp, vp]
@@ -158,6 +160,23 @@ def fp8_lookup_rows(cent_codes: np.ndarray, cent_scales: np.ndarray, queries: np
     if rc != 0:
         raise RuntimeError(f"oracle_fp8_lookup_rows failed ({rc})")
     return idx, sim, hit, second
+
+
+def fp8_lookup_topk_rows(cent_codes: np.ndarray, cent_scales: np.ndarray, queries: np.ndarray, k: int,
+                         qdtype: str = "bf16"):
+    """The k closest rows of an 8-bit store per query: ``(idx int32 [n, k], sim float64 [n, k])``."""
+    cc = np.ascontiguousarray(cent_codes, dtype=np.uint8)
+    cs = np.ascontiguousarray(cent_scales, dtype=np.float32)
+    rows, dim = cc.shape
+    qs = _storage(queries, qdtype, dim)
+    n = qs.shape[0]
+    idx = np.empty((n, int(k)), np.int32)
+    sim = np.empty((n, int(k)), np.float64)
+    rc = lib().oracle_fp8_lookup_topk_rows(_ptr(cc), _ptr(cs), rows, dim, _ptr(qs), _DT[qdtype], n, int(k), _ptr(idx),
+                                           _ptr(sim))
+    if rc != 0:
+        raise RuntimeError(f"oracle_fp8_lookup_topk_rows failed ({rc})")
+    return idx, sim
 
 
 def md1_wait(L: float, lam: float, h: float) -> float:

@@ -249,6 +249,78 @@ int oracle_fp8_lookup_rows(const uint8_t *cent_codes, const float *cent_scales, 
     return rc;
 }
 
+/*
+ * The k closest rows of an 8-bit store instead of the single closest one: the similarities of
+ * oracle_fp8_lookup_rows (queries quantised like the rows, cosine of the two code vectors, in
+ * double), ranked as oracle_lookup_topk ranks: larger similarity first, the lower index among
+ * equal ones; a row with a NaN scale is never chosen; (-1, -inf) where fewer than k rows can be
+ * chosen; (-1, NaN) throughout for a query holding a NaN or an infinity.
+ */
+int oracle_fp8_lookup_topk_rows(const uint8_t *cent_codes, const float *cent_scales, long k, int dim, const void *queries,
+                                int qdtype, long n, int kk, int *out_idx, double *out_sim) {
+    if (dim <= 0 || k < 0 || n < 0 || kk < 1 || (n > 0 && (!queries || !out_idx || !out_sim)) ||
+        (k > 0 && (!cent_codes || !cent_scales)))
+        return -1;
+    uint8_t *q8 = (uint8_t *)malloc((size_t)(n > 0 ? n : 1) * dim);
+    float *qs = (float *)malloc(sizeof(float) * (size_t)(n > 0 ? n : 1));
+    double *cn = (double *)malloc(sizeof(double) * (size_t)(k > 0 ? k : 1));
+    if (!q8 || !qs || !cn) { free(q8); free(qs); free(cn); return -2; }
+    int rc = oracle_fp8_quantize(queries, qdtype, n, dim, q8, qs);
+    for (long j = 0; j < k; ++j) {
+        double s = 0.0;
+        for (int t = 0; t < dim; ++t) {
+            const double v = e4m3_decode(cent_codes[(size_t)j * dim + t]);
+            s += v * v;
+        }
+        cn[j] = isnan(cent_scales[j]) ? NAN : sqrt(s);
+    }
+    int failed = 0;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (long i = 0; i < n; ++i) {
+        int *oi = out_idx + (size_t)i * kk;
+        double *os = out_sim + (size_t)i * kk;
+        if (rc != 0) continue;
+        if (isnan(qs[i])) {
+            for (int r = 0; r < kk; ++r) { oi[r] = -1; os[r] = NAN; }
+            continue;
+        }
+        double *sim = (double *)malloc(sizeof(double) * (size_t)(k > 0 ? k : 1));
+        char *taken = (char *)calloc((size_t)(k > 0 ? k : 1), 1);
+        if (!sim || !taken) { free(sim); free(taken); failed = 1; continue; }
+        double qn = 0.0;
+        for (int t = 0; t < dim; ++t) {
+            const double v = e4m3_decode(q8[(size_t)i * dim + t]);
+            qn += v * v;
+        }
+        qn = sqrt(qn);
+        for (long j = 0; j < k; ++j) {
+            double s = 0.0;
+            if (isnan(cn[j])) { sim[j] = NAN; continue; }
+            if (qn != 0.0 && cn[j] != 0.0) {
+                for (int t = 0; t < dim; ++t)
+                    s += e4m3_decode(q8[(size_t)i * dim + t]) * e4m3_decode(cent_codes[(size_t)j * dim + t]);
+                s /= qn * cn[j];
+            }
+            sim[j] = s;
+        }
+        for (int r = 0; r < kk; ++r) {
+            long best = -1;
+            for (long j = 0; j < k; ++j) {
+                if (taken[j] || isnan(sim[j])) continue;
+                if (best < 0 || sim[j] > sim[best]) best = j; /* strict: the lowest index keeps a tie */
+            }
+            if (best < 0) { oi[r] = -1; os[r] = -INFINITY; continue; }
+            taken[best] = 1;
+            oi[r] = (int)best;
+            os[r] = sim[best];
+        }
+        free(sim);
+        free(taken);
+    }
+    free(q8); free(qs); free(cn);
+    return failed ? -2 : rc;
+}
+
 /* ---------------------------------------------------------------- arithmetic */
 static double row_norm(const void *base, int dtype, long row, int dim) {
     double s = 0.0;

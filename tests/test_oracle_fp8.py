@@ -134,3 +134,47 @@ def test_fp8_lookup_degenerate_rows(oracle):
     assert hit.tolist() == [1, 0, 0, 0]
     idx, sim, hit, second = oracle.fp8_lookup_rows(cc[:0], cs[:0], q, 0.5, "f32")
     assert (idx[[0, 1, 3]] == -1).all() and np.isneginf(sim[[0, 1, 3]]).all()
+
+
+@pytest.mark.parametrize("dim,K,n,k", [(64, 300, 30, 5), (128, 700, 12, 9)])
+def test_fp8_topk_is_the_ranking_of_the_cosines_of_the_stored_vectors(oracle, dim, K, n, k):
+    """numpy route: decode table from the format's definition, cosines in float64, a stable sort (equal cosines keep
+    their index order); planted exact duplicates must come out in index order."""
+    wl = W.c2_mid(n_clusters=16, per_cluster=(K + 15) // 16, n_queries=n, dim=dim, dtype="bf16", sigma=0.4, seed=404)
+    wl.centroids = wl.centroids[:K].copy()
+    wl.centroids[211] = wl.centroids[5]
+    wl.centroids[90] = wl.centroids[5]
+    wl.queries[0] = wl.centroids[5]              # its three copies tie at the top: 5, 90, 211
+    cc, cs = oracle.fp8_quantize(wl.centroids, "bf16")
+    idx, sim = oracle.fp8_lookup_topk_rows(cc, cs, wl.queries, k)
+    assert idx.shape == (n, k) and idx[0, :3].tolist() == [5, 90, 211] and np.all(sim[0, :3] == sim[0, 0])
+    tab = decode_table()
+    qc, _ = oracle.fp8_quantize(wl.queries, "bf16")
+    C, Q = tab[cc], tab[qc]
+    S = (Q / np.linalg.norm(Q, axis=1, keepdims=True)) @ (C / np.linalg.norm(C, axis=1, keepdims=True)).T
+    order = np.argsort(-S, axis=1, kind="stable")[:, :k]
+    top = np.take_along_axis(S, order, axis=1)
+    assert np.abs(top - sim).max() < 1e-12
+    clear = np.abs(np.diff(np.take_along_axis(S, np.argsort(-S, axis=1, kind="stable")[:, :k + 1], axis=1), axis=1)).min(axis=1) > 1e-9
+    assert clear.sum() >= n // 2 and np.array_equal(idx[clear], order[clear])
+    assert np.all(np.diff(sim, axis=1) <= 0)
+    # k = 1 is the lookup
+    one_idx, one_sim = oracle.fp8_lookup_topk_rows(cc, cs, wl.queries, 1)
+    ref = oracle.fp8_lookup_rows(cc, cs, wl.queries, 0.5)
+    assert np.array_equal(one_idx[:, 0], ref[0]) and np.array_equal(one_sim[:, 0], ref[1])
+
+
+def test_fp8_topk_degenerate_rows(oracle):
+    dim = 16
+    c = np.zeros((4, dim), np.float32)
+    c[0, 0] = 1.0
+    c[1, 1] = 3.0
+    c[3, 0] = np.nan           # never chosen; row 2 has no length: similarity 0
+    cc, cs = oracle.fp8_quantize(c, "f32")
+    q = np.zeros((3, dim), np.float32)
+    q[0, 1] = 5.0              # row 1, then the zeros of rows 0 and 2 in index order
+    q[2, 3] = np.inf           # q[1] has no length: similarity 0 to every row that can be chosen
+    idx, sim = oracle.fp8_lookup_topk_rows(cc, cs, q, 4, "f32")
+    assert idx[0].tolist() == [1, 0, 2, -1] and sim[0, 0] == 1.0 and sim[0, 1] == 0.0 and np.isneginf(sim[0, 3])
+    assert idx[1].tolist() == [0, 1, 2, -1] and np.all(sim[1, :3] == 0.0)
+    assert (idx[2] == -1).all() and np.isnan(sim[2]).all()
