@@ -264,7 +264,7 @@ def main():
                 "launches": launches}
 
     variants_info = None
-    if not args.no_merge and not fp8 and name in ("c2_mid", "c3_large"):
+    if not args.no_merge and name in ("c2_mid", "c3_large"):
         # the lookup variants on the same batch: the whole threshold sweep as one lookup (against one lookup per
         # threshold), and the 8 closest centroids of every query
         def timed(fn, reps):

@@ -75,7 +75,7 @@ enum {
  * cosine of the bf16 rows (each element keeps 4 significant bits; cosines move by about
  * 1e-3), not equal to it.  Half the bytes of bf16 per centroid, no running means (dim
  * bytes + 20 per centroid).  dim must be a multiple of 128, at least 256.  Available:
- * siso_load, siso_lookup, siso_lookup_multi, siso_t2h, siso_reserve, siso_count,
+ * siso_load, siso_lookup, siso_lookup_multi, siso_lookup_topk, siso_t2h, siso_reserve, siso_count,
  * siso_export (codes; means must be NULL), siso_export_scales, siso_export_meta; the
  * other calls return SISO_EINVAL.
  */
@@ -152,9 +152,11 @@ int siso_lookup_multi(siso_cache *c, const void *queries, long n, const float *t
  * the remaining entries are (-1, -inf); a query holding a NaN or an infinity gets
  * (-1, NaN) throughout; a query without length has similarity 0 to every centroid.
  * No threshold is involved and no access is counted.
- * bf16 caches whose dimension is a multiple of 64 take two passes of the fused MFMA
- * kernel (the k-th largest of the per-slice maxima of the first pass bounds the k-th
- * best similarity from below; the second pass lists the few rows that reach the bound;
+ * bf16 caches whose dimension is a multiple of 64, and 8-bit caches (the batch is
+ * quantised as in a lookup; similarities are those of the stored code vectors), take
+ * two passes of the fused MFMA kernel (the k-th largest of the per-slice maxima of
+ * the first pass bounds the k-th best similarity from below; the second pass lists
+ * the few rows that reach the bound;
  * their cosines are then recomputed and ranked); other caches, caches of fewer than
  * 512 * k centroids and queries with more than 128 rows at the bound (many exact
  * duplicates) are scanned row by row.  Asynchronous; grows a workspace of the cache

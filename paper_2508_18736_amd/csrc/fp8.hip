@@ -23,12 +23,6 @@ __device__ __forceinline__ unsigned f32_to_e4m3(float y) {
     return sign | ((((v >> 23) - 120u) << 3) | ((v >> 20) & 7u));
 }
 
-__device__ __forceinline__ float e4m3_to_f32(unsigned code) {
-    const unsigned e = (code >> 3) & 15u, m = code & 7u;
-    const float v = e == 0 ? (float)m * 0.001953125f : __uint_as_float(((e + 120u) << 23) | (m << 20));
-    return (code & 0x80u) ? -v : v;
-}
-
 __device__ __forceinline__ float block_max256(float v, float *sh) {
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) v = fmaxf(v, __shfl_xor(v, off));

@@ -1671,8 +1671,16 @@ int siso_topk_mfma_collect(siso_cache *c, const void *queries, long n, int slice
                            int *cnt, int cap) {
     PipePlan p;
     if (!mfma_plan(c, n, &p) || p.slices != slices) return siso_fail(c, SISO_EINVAL, "top-k lookup: plan mismatch");
-    if (((uintptr_t)queries & 15) != 0) return siso_fail(c, SISO_EINVAL, "bf16 lookup: queries must be 16-byte aligned");
-    if (c->dtype != SISO_BF16) return siso_fail(c, SISO_EINVAL, "top-k lookup: bf16 caches only");
+    if (((uintptr_t)queries & 15) != 0) return siso_fail(c, SISO_EINVAL, "top-k lookup: queries must be 16-byte aligned");
+    if (c->dtype == SISO_FP8) {  // (`queries` are codes; the two passes run on the 64-deep kernels only)
+        switch (p.cfg) {
+            case 6: return launch_collect<F8Large64>(c, queries, n, p, tau, cand, cnt, cap);
+            case 7: return launch_collect<F8Mid64>(c, queries, n, p, tau, cand, cnt, cap);
+            case 8: return launch_collect<F8Small64>(c, queries, n, p, tau, cand, cnt, cap);
+            default: return siso_fail(c, SISO_EINVAL, "top-k lookup: no collecting kernel for configuration %d", p.cfg);
+        }
+    }
+    if (c->dtype != SISO_BF16) return siso_fail(c, SISO_EINVAL, "top-k lookup: bf16 and 8-bit caches only");
     switch (p.cfg) {
         case 2: return launch_collect<PipeMid>(c, queries, n, p, tau, cand, cnt, cap);
         case 3: return launch_collect<PipeSmall>(c, queries, n, p, tau, cand, cnt, cap);

@@ -118,6 +118,18 @@ __device__ __forceinline__ bf16_t f32_to_bf16(float f) {
 __device__ __forceinline__ float widen(float v) { return v; }
 __device__ __forceinline__ float widen(bf16_t v) { return bf16_to_f32(v); }
 
+// One OCP E4M3 code of the 8-bit storage (1 sign, 4 exponent bits with bias 7, 3 mantissa bits, subnormals
+// m/8 * 2^-6); a type of its own so that templates can tell a code from a byte.
+struct fp8_t {
+    unsigned char v;
+};
+__device__ __forceinline__ float e4m3_to_f32(unsigned code) {
+    const unsigned e = (code >> 3) & 15u, m = code & 7u;
+    const float v = e == 0 ? (float)m * 0.001953125f : __uint_as_float(((e + 120u) << 23) | (m << 20));
+    return (code & 0x80u) ? -v : v;
+}
+__device__ __forceinline__ float widen(fp8_t c) { return e4m3_to_f32(c.v); }
+
 __device__ __forceinline__ void narrow(float v, float *out) { *out = v; }
 __device__ __forceinline__ void narrow(float v, bf16_t *out) { *out = f32_to_bf16(v); }
 
@@ -175,6 +187,16 @@ __device__ __forceinline__ float chunk_dot(u32x4_t x, u32x4_t y, bf16_t) {
     for (int i = 0; i < 4; ++i) {
         s += __uint_as_float(x[i] << 16) * __uint_as_float(y[i] << 16);
         s += __uint_as_float(x[i] & 0xFFFF0000u) * __uint_as_float(y[i] & 0xFFFF0000u);
+    }
+    return s;
+}
+
+__device__ __forceinline__ float chunk_dot(u32x4_t x, u32x4_t y, fp8_t) {  // sixteen codes
+    float s = 0.f;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+#pragma unroll
+        for (int b = 0; b < 32; b += 8) s += e4m3_to_f32((x[i] >> b) & 0xFFu) * e4m3_to_f32((y[i] >> b) & 0xFFu);
     }
     return s;
 }

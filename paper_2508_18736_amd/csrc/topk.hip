@@ -1,13 +1,14 @@
 // The k closest centroids of every query (FindClosestCentroid of Algorithm 1 taken k times).
 //
-// Fast path (bf16 caches the MFMA kernels can serve, at least 512 * k centroids): two passes of the
+// Fast path (bf16 and 8-bit caches the MFMA kernels can serve, at least 512 * k centroids): two passes of the
 // fused GEMM.  Pass 1 is the first phase of an ordinary lookup: per query and slice of the centroid
 // range the largest scaled product <q, c> / |c|.  Slices hold different rows, so the k-th largest of
 // those maxima is reached by at least k rows: a lower bound on the k-th best.  Pass 2 forms all products
 // again and lists, per query, the rows that reach its bound - the k best are among them, and with many
 // more slices than k there are rarely more than a few k of them.  The cosines of the listed rows are then
 // recomputed (as the finalize step of a lookup does) and ranked: larger cosine first, lower index among
-// equal cosines.
+// equal cosines.  For an 8-bit cache the batch is quantised first, as in a lookup, and everything here sees codes
+// and the inverse lengths of code rows.
 // General path: every centroid row by row, one workgroup per query, each wave keeping its k best in its
 // lanes.  It serves the other caches and, behind the fast path, the queries with more listed rows than the
 // list holds (many exact duplicates at the bound, a query without length).
@@ -82,7 +83,8 @@ template <typename T>
 __global__ __launch_bounds__(256) void k_topk_select(const T *__restrict__ Q, const T *__restrict__ cent,
                                                       const float *__restrict__ invn, long K, int d, int k,
                                                       const int *__restrict__ cand, const int *__restrict__ cnt, int cap,
-                                                      int *scan, int *out_idx, float *out_sim) {
+                                                      const float *__restrict__ q_inv, int *scan, int *out_idx,
+                                                      float *out_sim) {
     constexpr int EPC = 16 / (int)sizeof(T);
     __shared__ float sh_f[4];
     __shared__ u32x4_t sh_q[SISO_MAX_DIM / EPC];
@@ -95,12 +97,13 @@ __global__ __launch_bounds__(256) void k_topk_select(const T *__restrict__ Q, co
     for (int e = t * EPC; e < d; e += 256 * EPC) {
         const u32x4_t v = *(const u32x4_t *)(qrow + e);
         sh_q[e / EPC] = v;
-        ss += chunk_dot(v, v, T());
+        if (!q_inv) ss += chunk_dot(v, v, T());
     }
     ss = wave_sum(ss);
     if (lane == 0) sh_f[wave] = ss;
     __syncthreads();
-    const float qi = inv_length((sh_f[0] + sh_f[1]) + (sh_f[2] + sh_f[3]));
+    // (q_inv: the inverse lengths that came with the quantised batch)
+    const float qi = q_inv ? q_inv[q] : inv_length((sh_f[0] + sh_f[1]) + (sh_f[2] + sh_f[3]));
     const int listed = cnt[q];
     if (!(qi == qi)) {  // a query holding a NaN or an infinity
         for (int r = t; r < k; r += 256) {
@@ -150,7 +153,8 @@ __global__ __launch_bounds__(256) void k_topk_select(const T *__restrict__ Q, co
 template <typename T>
 __global__ __launch_bounds__(256) void k_topk_scan(const T *__restrict__ Q, const T *__restrict__ cent,
                                                     const float *__restrict__ invn, long K, int d, int k, int vec,
-                                                    const int *__restrict__ scan, int *out_idx, float *out_sim) {
+                                                    const float *__restrict__ q_inv, const int *__restrict__ scan,
+                                                    int *out_idx, float *out_sim) {
     constexpr int EPC = 16 / (int)sizeof(T);
     __shared__ float sh_f[4];
     __shared__ u32x4_t sh_q[SISO_MAX_DIM / EPC];
@@ -173,7 +177,7 @@ __global__ __launch_bounds__(256) void k_topk_scan(const T *__restrict__ Q, cons
     ss = wave_sum(ss);
     if (lane == 0) sh_f[wave] = ss;
     __syncthreads();
-    const float qi = inv_length((sh_f[0] + sh_f[1]) + (sh_f[2] + sh_f[3]));
+    const float qi = q_inv ? q_inv[q] : inv_length((sh_f[0] + sh_f[1]) + (sh_f[2] + sh_f[3]));
     if (!(qi == qi)) {
         for (int r = t; r < k; r += 256) {
             out_idx[(size_t)q * k + r] = -1;
@@ -265,7 +269,8 @@ int ensure_topk_workspace(siso_cache *c, long n) {
 }
 
 template <typename T>
-int topk_launch(siso_cache *c, const void *queries, long n, int k, int slices, int *out_idx, float *out_sim) {
+int topk_launch(siso_cache *c, const void *queries, long n, int k, int slices, const float *q_inv, int *out_idx,
+                float *out_sim) {
     const T *Q = (const T *)queries;
     const T *cent = (const T *)c->cent;
     const int vec = ((c->dim * sizeof(T)) % 16 == 0 && ((uintptr_t)queries & 15) == 0) ? 1 : 0;
@@ -279,13 +284,13 @@ int topk_launch(siso_cache *c, const void *queries, long n, int k, int slices, i
             rc = siso_topk_mfma_collect(c, queries, n, slices, c->topk_tau, c->topk_cand, cnt, SISO_TOPK_CAND);
         if (rc != SISO_OK) return rc;
         hipLaunchKernelGGL(k_topk_select<T>, dim3((unsigned)n), dim3(256), 0, c->stream, Q, cent, c->invn, c->count, c->dim, k,
-                           c->topk_cand, cnt, SISO_TOPK_CAND, flags, out_idx, out_sim);
+                           c->topk_cand, cnt, SISO_TOPK_CAND, q_inv, flags, out_idx, out_sim);
         rc = siso_check_hip(c, hipGetLastError(), "k_topk_select");
         if (rc != SISO_OK) return rc;
         scan = flags;
     }
     hipLaunchKernelGGL(k_topk_scan<T>, dim3((unsigned)n), dim3(256), 0, c->stream, Q, cent, c->invn, c->count, c->dim, k, vec,
-                       scan, out_idx, out_sim);
+                       q_inv, scan, out_idx, out_sim);
     return siso_check_hip(c, hipGetLastError(), "k_topk_scan");
 }
 
@@ -296,26 +301,36 @@ extern "C" int siso_lookup_topk(siso_cache *c, const void *queries, long n, int 
     if (!c) return SISO_EINVAL;
     if (n < 0 || k < 1 || k > SISO_TOPK_MAX || (n > 0 && (!queries || !out_idx || !out_sim)))
         return siso_fail(c, SISO_EINVAL, "siso_lookup_topk: bad arguments (1 <= k <= %d)", SISO_TOPK_MAX);
-    if (c->dtype == SISO_FP8) return siso_fail(c, SISO_EINVAL, "siso_lookup_topk: not available with the 8-bit storage");
     if (n == 0) return SISO_OK;
     if (n > 2147483647L / 4) return siso_fail(c, SISO_EINVAL, "siso_lookup_topk: batch of %ld is too large", n);
-    // the two-pass path needs many more slices than k, and rows that are whole 16-byte chunks
+    const bool fp8 = c->dtype == SISO_FP8;
+    int rc = SISO_OK;
+    const void *rows = queries;  // what the kernels read: the batch, or its codes
+    if (fp8) {
+        rc = siso_fp8_ensure_batch(c, n);
+        if (rc == SISO_OK) rc = siso_fp8_quantize_batch(c, queries, n);
+        if (rc != SISO_OK) return rc;
+        rows = c->fp8_q;
+    }
+    // the two-pass path needs many more slices than k, and rows that are whole 16-byte chunks; for codes
+    // it exists on the 64-deep kernels only
     int slices = 0;
-    if (c->count >= 512L * k && c->dtype == SISO_BF16 && ((uintptr_t)queries & 15) == 0) {
+    const bool mfma_ok = c->dtype == SISO_BF16 || (fp8 && (c->opt_mfma_config == 0 || (c->opt_mfma_config >= 6 && c->opt_mfma_config <= 8)));
+    if (c->count >= 512L * k && mfma_ok && ((uintptr_t)rows & 15) == 0) {
         c->plan_min_slices = 8 * k;
         slices = siso_topk_mfma_slices(c, n);
         if (slices < 2 * k || slices > 4096) slices = 0;  // (the bound kernel keeps a query's keys in LDS)
     }
-    int rc = SISO_OK;
     if (slices > 0) {
         rc = ensure_topk_workspace(c, n);
         if (rc == SISO_OK) rc = siso_ensure_keys(c, n * (long)slices);
         int row_keys = 0;
-        if (rc == SISO_OK) rc = siso_topk_mfma_pass1(c, queries, n, slices, c->keys, &row_keys);
+        if (rc == SISO_OK) rc = siso_topk_mfma_pass1(c, rows, n, slices, c->keys, &row_keys);
     }
     if (rc == SISO_OK)
-        rc = c->dtype == SISO_F32 ? topk_launch<float>(c, queries, n, k, slices, out_idx, out_sim)
-                                  : topk_launch<bf16_t>(c, queries, n, k, slices, out_idx, out_sim);
+        rc = c->dtype == SISO_F32 ? topk_launch<float>(c, rows, n, k, slices, nullptr, out_idx, out_sim)
+             : fp8              ? topk_launch<fp8_t>(c, rows, n, k, slices, c->fp8_qinv, out_idx, out_sim)
+                                : topk_launch<bf16_t>(c, rows, n, k, slices, nullptr, out_idx, out_sim);
     c->plan_min_slices = 0;
     return rc;
 }

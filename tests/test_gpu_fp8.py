@@ -12,7 +12,7 @@ import pytest
 import torch
 
 from paper_2508_18736_amd import workloads as W
-from gpu_util import DEV, check_lookup, to_dev
+from gpu_util import DEV, check_lookup, check_topk, to_dev
 import gpu_util
 
 pytestmark = pytest.mark.gpu
@@ -108,7 +108,7 @@ def test_fp8_duplicates_special_values_and_thresholds(siso, oracle):
     assert acc.sum() == int(hit[:, 1].sum().item())
     # what an 8-bit cache does not offer
     qd = to_dev(wl.queries, "bf16")
-    for call in (lambda: cache.update(qd, idx), lambda: cache.merge(0.9, 10), lambda: cache.lookup_topk(qd, 3),
+    for call in (lambda: cache.update(qd, idx), lambda: cache.merge(0.9, 10),
                  lambda: cache.export(), lambda: cache.set_lookup_path(siso.PATH_SCALAR)):
         with pytest.raises(siso.SisoError):
             call()
@@ -147,3 +147,64 @@ def test_fp8_mid_size_against_the_oracle_and_the_bf16_lookup(siso, oracle):
     print(f"  {st}; same centroid as the bf16 lookup {same:.4f}; planted centroid found {planted:.4f}; "
           f"largest shift of a similarity {shift:.2e}", flush=True)
     assert st["max_err"] < 2e-5 and same > 0.9 and shift < 0.01 and torch.equal(out[2], rout[2])
+
+
+@pytest.mark.parametrize("dim,K,n,k", [(256, 700, 40, 5),        # row by row
+                                       (512, 20000, 300, 8),     # two passes: 256 x 256 tiles
+                                       (768, 9000, 64, 4),       # two passes: 256 x 64 tiles
+                                       (1024, 6000, 100, 1), (256, 40, 9, 32)])
+def test_fp8_topk_vs_oracle(siso, oracle, dim, K, n, k):
+    print(f"case: fp8 topk dim={dim} K={K} n={n} k={k}", flush=True)
+    wl = W.c2_mid(n_clusters=256, per_cluster=(K + 255) // 256, n_queries=n, dim=dim, sigma=0.3, seed=511)
+    wl.centroids = wl.centroids[:K].copy()
+    r = np.random.default_rng(17)
+    for a in r.choice(K, size=min(20, K // 4), replace=False):          # exact duplicates at distant rows
+        for b in r.choice(K, size=2, replace=False):
+            wl.centroids[b] = wl.centroids[a]
+    cache = load_fp8(siso, wl, K + 9)
+    out = cache.lookup_topk(to_dev(wl.queries, "bf16"), k)
+    torch.cuda.synchronize()
+    oc, os_ = oracle.fp8_quantize(wl.centroids, "bf16")
+    ora = oracle.fp8_lookup_topk_rows(oc, os_, wl.queries, k)
+    st = check_topk(out, ora, "fp8", "fp8 topk")
+    print(f"  {st}", flush=True)
+    assert st["clear"] >= min(n, n * min(k, K) // 8) and st["max_err"] < 2e-5 and st["same"] > 0.97
+    # rank 1 is the lookup
+    one = cache.lookup(to_dev(wl.queries, "bf16"), 0.5)
+    assert torch.equal(one[0], out[0][:, 0].contiguous())
+    assert float((one[1] - out[1][:, 0]).abs().max()) < 5e-5   # (the lookup keeps the matrix cores' own sum)
+    again = cache.lookup_topk(to_dev(wl.queries, "bf16"), k)
+    torch.cuda.synchronize()
+    assert torch.equal(again[0], out[0]) and torch.equal(again[1], out[1])
+
+
+def test_fp8_topk_degenerate_queries_and_mid_size(siso, oracle):
+    """A query without length, one holding an infinity, one that equals many rows; then the mid-size workload
+    (65,536 x 768, 4,096 queries, k = 8) with 64 sampled queries through the oracle."""
+    print("case: fp8 topk degenerate + c2_mid", flush=True)
+    wl = W.c2_mid(n_clusters=64, per_cluster=150, n_queries=8, dim=256, seed=512)
+    wl.centroids[100:400] = wl.centroids[7]                 # 301 equal rows: more than the list of a query holds
+    q = wl.centroids_f32()[[7, 8, 9, 10]].copy()
+    q[1] = 0.0
+    q[2, 5] = np.inf
+    qb = W.f32_to_bf16_bits(q)
+    cache = load_fp8(siso, wl)
+    out = cache.lookup_topk(to_dev(qb, "bf16"), 16)
+    torch.cuda.synchronize()
+    oc, os_ = oracle.fp8_quantize(wl.centroids, "bf16")
+    ora = oracle.fp8_lookup_topk_rows(oc, os_, qb, 16)
+    check_topk(out, ora, "fp8", "fp8 topk degenerate")
+    gi = out[0].cpu().numpy()
+    assert gi[0].tolist() == [7] + list(range(100, 115)) and gi[1].tolist() == list(range(16)) and (gi[2] == -1).all()
+
+    wl = W.c2_mid()
+    cache = load_fp8(siso, wl)
+    out = cache.lookup_topk(to_dev(wl.queries, "bf16"), 8)
+    torch.cuda.synchronize()
+    rows = np.arange(0, wl.n, 64)
+    oc, os_ = oracle.fp8_quantize(wl.centroids, "bf16")
+    st = check_topk((out[0][rows], out[1][rows]), oracle.fp8_lookup_topk_rows(oc, os_, wl.queries[rows], 8), "fp8", "c2 fp8 top-8")
+    print(f"  {st}", flush=True)
+    assert st["clear"] >= 40 and st["same"] > 0.97 and st["max_err"] < 2e-5
+    one = cache.lookup(to_dev(wl.queries, "bf16"), 0.85)
+    assert torch.equal(one[0], out[0][:, 0].contiguous())

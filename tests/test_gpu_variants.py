@@ -10,7 +10,7 @@ import pytest
 import torch
 
 from paper_2508_18736_amd import workloads as W
-from gpu_util import DEV, GAP, SIM_TOL, check_lookup, siso_dtype, to_dev
+from gpu_util import DEV, GAP, SIM_TOL, check_lookup, check_topk, siso_dtype, to_dev
 
 pytestmark = pytest.mark.gpu
 
@@ -19,37 +19,6 @@ pytestmark = pytest.mark.gpu
 def siso():
     from paper_2508_18736_amd import siso as m
     return m
-
-
-def check_topk(gpu, ora, dtype, label):
-    gi, gs = gpu[0].cpu().numpy(), gpu[1].cpu().numpy().astype(np.float64)
-    oi, os_ = ora
-    n, k = oi.shape
-    tol = SIM_TOL[dtype]
-    assert np.array_equal(np.isnan(gs), np.isnan(os_)), f"{label}: NaN pattern"
-    assert np.array_equal(np.isneginf(gs), np.isneginf(os_)), f"{label}: empty entries"
-    fin = np.isfinite(os_)
-    assert np.array_equal(gi[~fin], oi[~fin]), label
-    err = np.abs(gs[fin] - os_[fin])
-    assert err.size == 0 or err.max() <= tol, f"{label}: similarity error {err.max():.3e}"
-    both = fin[:, 1:] & fin[:, :-1]
-    assert np.all(np.diff(np.where(fin, gs, 0.0), axis=1)[both] <= 0), f"{label}: not sorted"
-    pad = np.full((n, 1), np.inf)
-    left = np.abs(np.diff(np.concatenate([pad, os_], axis=1), axis=1))     # gap to the rank before
-    right = np.abs(np.diff(np.concatenate([os_, -pad], axis=1), axis=1))   # gap to the rank after
-    left, right = np.nan_to_num(left, nan=np.inf), np.nan_to_num(right, nan=np.inf)
-    clear = fin & (left > GAP) & (right > GAP)
-    bad = clear & (gi != oi)
-    assert not bad.any(), f"{label}: {bad.sum()} indices differ at ranks with clear gaps, first {np.argwhere(bad)[:4].tolist()}"
-    # runs of exactly equal similarities (equal rows) come in index order on both sides
-    tie = fin & ((left == 0) | (right == 0))
-    assert np.array_equal(gi[tie], oi[tie]), f"{label}: exact ties"
-    # each row names k different centroids, and the set agrees except for members near the k-th similarity
-    for q in range(n):
-        row = gi[q][gi[q] >= 0]
-        assert len(set(row.tolist())) == len(row), f"{label}: a centroid twice in query {q}"
-    return {"clear": int(clear.sum()), "ties": int(tie.sum()), "max_err": float(err.max()) if err.size else 0.0,
-            "same": float((gi == oi).mean())}
 
 
 # -------------------------------------------------------------------- several thresholds
