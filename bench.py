@@ -74,6 +74,7 @@ def parse():
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="CPU work given to the oracle baseline")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-merge", action="store_true")
+    ap.add_argument("--two-calls", action="store_true", help="a step as siso_lookup + siso_update_hits instead of siso_lookup_update")
     ap.add_argument("--storage", default="bf16", choices=["bf16", "fp8"],
                     help="fp8: the 8-bit storage variant of the cache (lookups only: a step is siso_lookup)")
     ap.add_argument("--option", action="append", default=[], help="name=value for siso_set_option")
@@ -228,11 +229,16 @@ def main():
     sim = torch.empty(nb, dtype=torch.float32, device="cuda:0")
     hit = torch.empty(nb, dtype=torch.uint8, device="cuda:0")
 
+    two_calls = fp8 or args.two_calls
+
     def step(i):
         q = queries[(i % n_batches) * nb:(i % n_batches + 1) * nb]
-        cache.lookup(q, thetas[i % len(thetas)], idx, sim, hit)
-        if not fp8:
-            cache.update(q, idx, hit)
+        if two_calls:
+            cache.lookup(q, thetas[i % len(thetas)], idx, sim, hit)
+            if not fp8:
+                cache.update(q, idx, hit)
+        else:
+            cache.lookup_update(q, thetas[i % len(thetas)], idx, sim, hit)
 
     for i in range(warmup):
         step(i)
@@ -346,7 +352,7 @@ def main():
                 "warmup": warmup, "ms_per_step": dt / steps * 1e3,
                 "config": {"workload": name, "centroids": K, "dim": d, "batch": nb, "thresholds": thetas,
                            "storage": args.storage,
-                           "step": "siso_lookup" if fp8 else "siso_lookup + siso_update_hits", "hit_rate_last_batch": hit_rate,
+                           "step": "siso_lookup" if fp8 else "siso_lookup + siso_update_hits" if two_calls else "siso_lookup_update", "hit_rate_last_batch": hit_rate,
                            "offline_merge": merge_info, "t2h": t2h_info, "refresh": refresh_info,
                            "variants": variants_info,
                            "generate_s": round(gen_s, 1)},

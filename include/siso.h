@@ -213,7 +213,26 @@ int siso_reserve(siso_cache *c, long n);
 int siso_update(siso_cache *c, const void *queries, const int *idx, long n);
 int siso_update_hits(siso_cache *c, const void *queries, const int *idx, const unsigned char *hit, long n);
 
-/* Number of out-of-range indices seen by updates since the cache was created.
+/*
+ * One step of the online loop as one call: siso_lookup, then siso_update_hits with the
+ * lookup's own outputs - every query that hits is folded into its centroid before the
+ * next batch is looked up (the running mean of section 3.1's centroids, applied where
+ * FindClosestCentroid of Algorithm 1 found a match).  Arguments as siso_lookup (out_hit
+ * may not be NULL); outputs and state are bit for bit those of the two calls.
+ * Batches of at most 256 queries whose lookup runs on kernels that name the winning
+ * row (bf16 batches of at most 128 on the MFMA kernels, fp32 caches) finish in one
+ * kernel that ends the lookup and applies the update: the workgroups of the batch tell
+ * each other their (index, hit) through 256 slots of device memory of the cache, and
+ * each waits, a bounded time, until all slots of the call are written; one that gives up
+ * (never observed: all workgroups are resident together) leaves its centroid as it was
+ * and is counted by siso_bad_indices.  Other batches run the two calls.  Asynchronous;
+ * allocates what siso_lookup and siso_update_hits would (siso_reserve avoids that).
+ */
+int siso_lookup_update(siso_cache *c, const void *queries, long n, float threshold, int *out_idx, float *out_sim,
+                       unsigned char *out_hit);
+
+/* Number of queries that updates skipped since the cache was created: out-of-range
+ * indices, and hits that a siso_lookup_update gave up on.
  * Synchronises with the stream.  Negative = error code. */
 long siso_bad_indices(siso_cache *c);
 

@@ -451,6 +451,49 @@ __global__ void k_update_mark_init(int *owner, int *members, long capacity) {
     }
 }
 
+// The end of an update, by the block that leads centroid k: acc = the sum of its `members` unit-length members
+// (this thread's elements t + 256 e), m_old / size_old = the mean and its weight as they were.  Writes the
+// new mean and weight, the stored row (the mean at unit length, rounded to the storage type; left alone when
+// the mean has no length) and its inverse length.
+template <typename T, int UPD_MAXE_T>
+__device__ __forceinline__ void update_write(int k, int d, int size_old, int members, const float (&m_old)[UPD_MAXE_T],
+                                             const float (&acc)[UPD_MAXE_T], T *cent, float *mean, int *size, float *invn,
+                                             float *sh) {
+    const int t = threadIdx.x;
+    const float n_old = (float)size_old;
+    const float n_new = n_old + (float)members;
+    float m[UPD_MAXE_T];
+    float ss = 0.f;
+#pragma unroll
+    for (int e = 0; e < UPD_MAXE_T; ++e) {
+        const int col = t + e * 256;
+        m[e] = 0.f;
+        if (col < d) {
+            m[e] = (n_old * m_old[e] + acc[e]) / n_new;
+            mean[(size_t)k * d + col] = m[e];
+            ss += m[e] * m[e];
+        }
+    }
+    const float n2 = block_sum256(ss, sh);
+    if (t == 0) size[k] = size_old + members;
+    if (!(n2 > 0.f) || n2 > 3.0e38f) return;
+    const float nrm = sqrtf(n2);
+    float cs = 0.f;
+#pragma unroll
+    for (int e = 0; e < UPD_MAXE_T; ++e) {
+        const int col = t + e * 256;
+        if (col < d) {
+            T r;
+            narrow(m[e] / nrm, &r);
+            cent[(size_t)k * d + col] = r;
+            const float back = widen(r);
+            cs += back * back;
+        }
+    }
+    const float c2 = block_sum256(cs, sh);
+    if (t == 0) invn[k] = inv_length(c2);
+}
+
 // UPD_MAXE_T = elements of a row per thread (4 for dim <= 1024, else 16).  owner / marked = the notes
 // of k_update_mark, or NULL: then every block finds out by itself whether it is the first member.
 template <typename T, int UPD_MAXE_T>
@@ -565,39 +608,179 @@ __global__ __launch_bounds__(256) void k_update(const T *__restrict__ Q, const i
         }
     }
     if (members == 0) return;
-    const float n_old = (float)size_old;
-    const float n_new = n_old + (float)members;
-    float m[UPD_MAXE_T];
-    float ss = 0.f;
-#pragma unroll
-    for (int e = 0; e < UPD_MAXE_T; ++e) {
-        const int col = t + e * 256;
-        m[e] = 0.f;
-        if (col < d) {
-            m[e] = (n_old * m_old[e] + acc[e]) / n_new;
-            mean[(size_t)k * d + col] = m[e];
-            ss += m[e] * m[e];
-        }
-    }
-    const float n2 = block_sum256(ss, sh);
-    if (t == 0) size[k] = size_old + members;
-    if (!(n2 > 0.f) || n2 > 3.0e38f) return;
-    const float nrm = sqrtf(n2);
-    float cs = 0.f;
-#pragma unroll
-    for (int e = 0; e < UPD_MAXE_T; ++e) {
-        const int col = t + e * 256;
-        if (col < d) {
-            T r;
-            narrow(m[e] / nrm, &r);
-            cent[(size_t)k * d + col] = r;
-            const float back = widen(r);
-            cs += back * back;
-        }
-    }
-    const float c2 = block_sum256(cs, sh);
-    if (t == 0) invn[k] = inv_length(c2);
+    update_write<T, UPD_MAXE_T>(k, d, size_old, members, m_old, acc, cent, mean, size, invn, sh);
 }
+
+// ============================================================================
+// The end of a small lookup and the update of its hits as one kernel (siso_lookup_update, at most 256
+// queries, keys that name rows): block q does what k_lookup_finalize does for query q, then what k_update
+// does for it, with the same arithmetic in the same order, so the outputs and the state are those of the
+// two kernels bit for bit.  What a block needs from the others is their (index, hit) - to know whether it
+// leads its centroid and which other queries fold into it - and that crosses the grid through a board of
+// one 64-bit slot per query: (number of the call, hit, index), written and read with device-scope atomic
+// operations.  A slot is valid when it carries the number of this call, so nothing is cleared and no fence
+// is needed (the rows and means the blocks read were written by earlier kernels).  All blocks of the grid
+// are resident together (at most 256 small blocks), so the wait for the slots ends; it is bounded all the
+// same: a block that gives up leaves its centroid as it was and counts its query as not applied.
+// Saves a launch and the gap before it, and the loads of the update (own row, mean of the centroid) are on
+// their way while the block waits for the board.
+// ============================================================================
+#define FOLD_BOARD 256
+__device__ __forceinline__ u64 board_entry(unsigned call, bool hit, int idx) {
+    return ((u64)call << 33) | ((u64)(hit ? 1 : 0) << 32) | (u64)(unsigned)idx;
+}
+template <typename T, int UPD_MAXE_T>
+__global__ __launch_bounds__(256) void k_finalize_update(const T *__restrict__ Q, const u64 *__restrict__ keys, long n, long K,
+                                                          int d, int slices, float theta, int vec, int *out_idx,
+                                                          float *out_sim, unsigned char *out_hit, unsigned *access, T *cent,
+                                                          float *mean, int *size, float *invn, u64 *board, unsigned call,
+                                                          int spin_limit, u64 *gave_up) {
+    constexpr int EPC = 16 / (int)sizeof(T);
+    __shared__ float sh[4];
+    __shared__ float sh_f[4];
+    __shared__ u64 sh_k[4];
+    __shared__ u64 masks[4];
+    __shared__ u64 sh_board[FOLD_BOARD];
+    __shared__ int sh_all;
+    const long me = blockIdx.x;
+    const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+    const T *qrow = Q + (size_t)me * d;
+    // this block's own query in the layout of the update, asked for first
+    T xr[UPD_MAXE_T];
+#pragma unroll
+    for (int e = 0; e < UPD_MAXE_T; ++e) {
+        const int col = t + e * 256;
+        xr[e] = qrow[col < d ? col : 0];
+    }
+    // --- k_lookup_finalize for keys that name rows: 1/|q| and the largest key
+    float ss = 0.f;
+    if (vec) {
+        for (int e = t * EPC; e < d; e += 256 * EPC) {
+            const u32x4_t v = *(const u32x4_t *)(qrow + e);
+            ss += chunk_dot(v, v, T());
+        }
+    } else {
+        for (int e = t; e < d; e += 256) ss += widen(qrow[e]) * widen(qrow[e]);
+    }
+    u64 key = 0;
+    for (int s = t; s < slices; s += 256) {
+        const u64 k2 = keys[(size_t)me * slices + s];
+        key = k2 > key ? k2 : key;
+    }
+    ss = wave_sum(ss);
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) {
+        const u64 o = __shfl_xor(key, off);
+        key = o > key ? o : key;
+    }
+    if (lane == 0) {
+        sh_f[wave] = ss;
+        sh_k[wave] = key;
+    }
+    __syncthreads();
+    const float qi = inv_length((sh_f[0] + sh_f[1]) + (sh_f[2] + sh_f[3]));
+#pragma unroll
+    for (int w = 0; w < 4; ++w) key = sh_k[w] > key ? sh_k[w] : key;
+    long best_i = -1;
+    float best_s = -INFINITY;
+    const bool finite_q = qi == qi;
+    if (finite_q && K > 0 && key != 0) {
+        best_i = (long)(0xFFFFFFFFu - (unsigned)(key & 0xFFFFFFFFull));
+        best_s = unordered_bits((unsigned)(key >> 32)) * qi;
+    }
+    if (!finite_q) best_s = __uint_as_float(0x7FC00000u);
+    const bool hit = best_i >= 0 && best_s > theta;
+    if (t == 0) {
+        out_idx[me] = (int)best_i;
+        out_sim[me] = best_s;
+        out_hit[me] = hit ? 1 : 0;
+        if (hit && access && access[best_i] != SISO_ACCESS_INF) atomicAdd(&access[best_i], 1u);
+        __hip_atomic_store(board + me, board_entry(call, hit, (int)best_i), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    if (!hit) return;
+    // --- k_update for query `me`: its centroid's mean and weight, on their way during the wait
+    const int k = (int)best_i;
+    float x_me[UPD_MAXE_T], m_old[UPD_MAXE_T];
+#pragma unroll
+    for (int e = 0; e < UPD_MAXE_T; ++e) {
+        const int col = t + e * 256;
+        m_old[e] = mean[(size_t)k * d + (col < d ? col : 0)];
+    }
+    const int size_old = size[k];
+#pragma unroll
+    for (int e = 0; e < UPD_MAXE_T; ++e) {
+        x_me[e] = t + e * 256 < d ? widen(xr[e]) : 0.f;
+        asm volatile("" ::"v"(x_me[e]), "v"(m_old[e]));  // (the loads are issued here, not behind the wait)
+    }
+    // the board: wave 0 reads the slots until all of them carry this call's number
+    if (wave == 0) {
+        bool all = false;
+        for (int tries = 0; tries < spin_limit && !all; ++tries) {
+            bool mine = true;
+            for (int j = lane; j < (int)n; j += 64) {
+                const u64 v = __hip_atomic_load(board + j, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                sh_board[j] = v;
+                mine = mine && (unsigned)(v >> 33) == call;
+            }
+            all = __ballot(!mine) == 0;
+            if (!all) __builtin_amdgcn_s_sleep(4);
+        }
+        if (lane == 0) sh_all = all ? 1 : 0;
+    }
+    __syncthreads();
+    if (!sh_all) {
+        if (t == 0) atomicAdd(gave_up, 1ull);
+        return;
+    }
+    float acc[UPD_MAXE_T];
+#pragma unroll
+    for (int e = 0; e < UPD_MAXE_T; ++e) acc[e] = 0.f;
+    int members = 0;
+    auto fold = [&](const float(&x)[UPD_MAXE_T]) {
+        float s2 = 0.f;
+#pragma unroll
+        for (int e = 0; e < UPD_MAXE_T; ++e) s2 += x[e] * x[e];
+        const float n2 = block_sum256(s2, sh);
+        const float inv = inv_length(n2);
+        if (inv == inv && inv > 0.f) {
+            const float nrm = sqrtf(n2);
+#pragma unroll
+            for (int e = 0; e < UPD_MAXE_T; ++e) acc[e] += x[e] / nrm;
+            ++members;
+        }
+    };
+    // the members of centroid k in ascending order (a hit whose index is k)
+    const bool m = t < (int)n && sh_board[t] == board_entry(call, true, k);
+    const u64 mask = __ballot(m);
+    if (lane == 0) masks[wave] = mask;
+    __syncthreads();
+    for (int w = 0; w < 4; ++w) {
+        u64 mm = masks[w];
+        while (mm) {
+            const int b = __ffsll((long long)mm) - 1;
+            mm &= mm - 1;
+            const long jj = w * 64 + b;
+            if (jj < me) return;  // an earlier member leads this centroid (uniform over the block)
+            if (jj == me) {
+                fold(x_me);
+                continue;
+            }
+            T yr[UPD_MAXE_T];
+            float x[UPD_MAXE_T];
+#pragma unroll
+            for (int e = 0; e < UPD_MAXE_T; ++e) {
+                const int col = t + e * 256;
+                yr[e] = Q[(size_t)jj * d + (col < d ? col : 0)];
+            }
+#pragma unroll
+            for (int e = 0; e < UPD_MAXE_T; ++e) x[e] = t + e * 256 < d ? widen(yr[e]) : 0.f;
+            fold(x);
+        }
+    }
+    if (members == 0) return;
+    update_write<T, UPD_MAXE_T>(k, d, size_old, members, m_old, acc, cent, mean, size, invn, sh);
+}
+
 
 // ============================================================================
 // group merge: lock-free union-find (the lower index becomes the root), group
@@ -960,9 +1143,10 @@ extern "C" int siso_create_ex(int dim, long capacity, int dtype, siso_cache **ou
     ok = ok && hipMemset(c->invn, 0, ((size_t)capacity + SISO_PAD_ROWS) * sizeof(float)) == hipSuccess;
     ok = ok && hipMalloc((void **)&c->locality, (size_t)capacity * sizeof(float)) == hipSuccess;
     ok = ok && hipMalloc((void **)&c->access, (size_t)capacity * sizeof(unsigned)) == hipSuccess;
-    ok = ok && hipMalloc((void **)&c->counters, 4 * sizeof(u64)) == hipSuccess;
+    // (behind the four counters: the board of siso_lookup_update, one slot per query of a small batch)
+    ok = ok && hipMalloc((void **)&c->counters, (4 + FOLD_BOARD) * sizeof(u64)) == hipSuccess;
     ok = ok && hipHostMalloc((void **)&c->host_pin, 4 * sizeof(u64), hipHostMallocDefault) == hipSuccess;
-    ok = ok && hipMemset(c->counters, 0, 4 * sizeof(u64)) == hipSuccess;
+    ok = ok && hipMemset(c->counters, 0, (4 + FOLD_BOARD) * sizeof(u64)) == hipSuccess;
     ok = ok && hipDeviceSynchronize() == hipSuccess;
     if (!ok) {
         (void)hipGetLastError();
@@ -1177,7 +1361,8 @@ extern "C" int siso_lookup_multi(siso_cache *c, const void *queries, long n, con
 }
 
 int siso_lookup_impl(siso_cache *c, const void *queries, long n, const float *thetas, int m, int count_index,
-                     int *out_idx, float *out_sim, unsigned char *out_hit, u64 *static_keys, long static_cap) {
+                     int *out_idx, float *out_sim, unsigned char *out_hit, u64 *static_keys, long static_cap, int *folded) {
+    if (folded) *folded = 0;
     if (n == 0) return SISO_OK;
     if (n > 2147483647L / 4) return siso_fail(c, SISO_EINVAL, "siso_lookup: batch of %ld is too large", n);
     int slices = 1;
@@ -1229,6 +1414,26 @@ int siso_lookup_impl(siso_cache *c, const void *queries, long n, const float *th
         }
         if (!static_keys) siso_prof_end(c);
         if (rc != SISO_OK) return rc;
+    }
+    if (folded && n <= FOLD_BOARD && c->count > 0 && row_keys == SISO_KEY_ROWS && !fp8 && m == 1 && out_hit) {
+        // the end of the lookup and the update of its hits as one kernel (see k_finalize_update)
+        c->fold_call = c->fold_call >= 0x7FFFFFFFu ? 1u : c->fold_call + 1u;
+        const int spin_limit = 1 << 18;  // polls of the board (a microsecond or two each) before a block gives up
+#define SISO_LAUNCH_FOLD(T, E)                                                                                            \
+    hipLaunchKernelGGL((k_finalize_update<T, E>), dim3(qblocks), dim3(256), 0, c->stream, (const T *)queries, keys, n, c->count, \
+                       c->dim, slices, thetas[0], vec, out_idx, out_sim, out_hit, count_index >= 0 ? c->access : nullptr, \
+                       (T *)c->cent, c->mean, c->size, c->invn, c->counters + 4, c->fold_call, spin_limit, c->counters)
+        if (c->dtype == SISO_F32) {
+            if (c->dim <= 1024) SISO_LAUNCH_FOLD(float, 4);
+            else SISO_LAUNCH_FOLD(float, 16);
+        } else {
+            if (c->dim <= 1024) SISO_LAUNCH_FOLD(bf16_t, 4);
+            else SISO_LAUNCH_FOLD(bf16_t, 16);
+        }
+#undef SISO_LAUNCH_FOLD
+        HIP_TRY(c, hipGetLastError());
+        *folded = 1;
+        return SISO_OK;
     }
     if (c->dtype == SISO_F32)
         hipLaunchKernelGGL(k_lookup_finalize<float>, dim3(qblocks), dim3(256), 0, c->stream, (const float *)queries,
@@ -1285,6 +1490,18 @@ extern "C" int siso_update_hits(siso_cache *c, const void *queries, const int *i
 
 extern "C" int siso_update(siso_cache *c, const void *queries, const int *idx, long n) {
     return siso_update_hits(c, queries, idx, nullptr, n);
+}
+
+extern "C" int siso_lookup_update(siso_cache *c, const void *queries, long n, float threshold, int *out_idx, float *out_sim,
+                                  unsigned char *out_hit) {
+    if (!c) return SISO_EINVAL;
+    SISO_NOT_FP8(c, "siso_lookup_update");
+    if (n < 0 || (n > 0 && (!queries || !out_idx || !out_sim || !out_hit)))
+        return siso_fail(c, SISO_EINVAL, "siso_lookup_update: bad arguments");
+    int folded = 0;
+    const int rc = siso_lookup_impl(c, queries, n, &threshold, 1, 0, out_idx, out_sim, out_hit, nullptr, 0, &folded);
+    if (rc != SISO_OK || folded || n == 0) return rc;
+    return siso_update_hits(c, queries, out_idx, out_hit, n);
 }
 
 int siso_read_counter(siso_cache *c, int which, u64 *value) {

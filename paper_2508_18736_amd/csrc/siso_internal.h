@@ -66,7 +66,8 @@ struct siso_cache {
 
     u64 *static_keys;  // this device's copy of the library's static key array (siso_lookup_static)
 
-    u64 *counters;  // device: [0] bad update indices, [1] merge pair count, [2] scratch, [3] scratch
+    u64 *counters;  // device: [0] bad update indices, [1] merge pair count, [2] scratch, [3] scratch; behind them the
+                    // board of siso_lookup_update (256 slots)
     u64 *host_pin;  // pinned host mirror for counter read-back (4 entries)
 
     // 8-bit storage (SISO_FP8): cent holds one E4M3 code per element, scale [capacity] the scale of every row
@@ -84,6 +85,7 @@ struct siso_cache {
     int *topk_cand;
     long topk_cap;
     int plan_min_slices;  // > 0 while a top-k lookup plans its passes: at least this many slices (if the tiles allow)
+    unsigned fold_call;   // number of the last siso_lookup_update that ended in one kernel (stamps its board entries)
 
     // tuning knobs (siso_set_option); 0 = library default
     int opt_mfma_config;
@@ -351,9 +353,12 @@ int siso_pairs_mfma_launch(siso_cache *c, const void *rows, const float *invn, l
 // centroids (access_count goes up), as in serving; count_index = -1 for test lookups.  static_keys: NULL = the phase-1
 // keys go to the cache's own workspace (grown on demand); otherwise they go there (room for static_cap keys:
 // a larger need is an error), and the call allocates nothing and records no timing events.
+// folded: NULL = a lookup and nothing else; otherwise the caller is about to fold the hits into their centroids
+// and *folded tells whether the lookup has already done it (small batches: one kernel ends the lookup and
+// applies the update).
 int siso_lookup_impl(siso_cache *c, const void *queries, long n, const float *thetas, int m, int count_index,
                      int *out_idx, float *out_sim, unsigned char *out_hit, u64 *static_keys = nullptr,
-                     long static_cap = 0);
+                     long static_cap = 0, int *folded = nullptr);
 int siso_fp8_load(siso_cache *c, const void *centroids, const int *counts, long k);  // siso_load of an 8-bit cache
 int siso_fp8_ensure_batch(siso_cache *c, long n);
 int siso_fp8_quantize_batch(siso_cache *c, const void *queries, long n);  // bf16 queries -> c->fp8_q, c->fp8_qinv

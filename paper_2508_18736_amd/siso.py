@@ -41,6 +41,7 @@ SYMBOLS = {
     "siso_count": ([_vp], _lg),
     "siso_reserve": ([_vp, _lg], _it),
     "siso_lookup": ([_vp, _vp, _lg, _fl, _vp, _vp, _vp], _it),
+    "siso_lookup_update": ([_vp, _vp, _lg, _fl, _vp, _vp, _vp], _it),
     "siso_lookup_multi": ([_vp, _vp, _lg, _vp, _it, _it, _vp, _vp, _vp], _it),
     "siso_lookup_topk": ([_vp, _vp, _lg, _it, _vp, _vp], _it),
     "siso_lookup_static": ([_vp, _vp, _lg, _fl, _vp, _vp, _vp], _it),
@@ -259,6 +260,25 @@ class SisoCache:
         self._vec(out_hit, torch.uint8, n, "out_hit")
         self._check(_lib.siso_lookup(self._h, _ptr(q), n, float(threshold), _ptr(out_idx), _ptr(out_sim),
                                      _ptr(out_hit)))
+        return out_idx, out_sim, out_hit
+
+    def lookup_update(self, queries: torch.Tensor, threshold: float, out_idx: Optional[torch.Tensor] = None,
+                      out_sim: Optional[torch.Tensor] = None, out_hit: Optional[torch.Tensor] = None
+                      ) -> Tuple[torch.Tensor, torch.Tensor, torch.Tensor]:
+        """``lookup`` and ``update(queries, idx, hit)`` with its outputs, as one call."""
+        q = self._rows(queries, "queries")
+        n = q.shape[0]
+        if out_idx is None:
+            out_idx = torch.empty(n, dtype=torch.int32, device=self.device)
+        if out_sim is None:
+            out_sim = torch.empty(n, dtype=torch.float32, device=self.device)
+        if out_hit is None:
+            out_hit = torch.empty(n, dtype=torch.uint8, device=self.device)
+        self._vec(out_idx, torch.int32, n, "out_idx")
+        self._vec(out_sim, torch.float32, n, "out_sim")
+        self._vec(out_hit, torch.uint8, n, "out_hit")
+        self._check(_lib.siso_lookup_update(self._h, _ptr(q), n, float(threshold), _ptr(out_idx), _ptr(out_sim),
+                                            _ptr(out_hit)))
         return out_idx, out_sim, out_hit
 
     def lookup_multi(self, queries: torch.Tensor, thetas, count_index: int = -1

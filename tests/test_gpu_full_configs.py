@@ -112,8 +112,11 @@ def test_c4_stream_full(siso, oracle):
 
     def gpu_step(b):
         q = q_all[b * B:(b + 1) * B]
-        cache.lookup(q, th, idx_log[b], sim_log[b], hit_log[b])
-        cache.update(q, idx_log[b], hit_log[b])          # no host synchronisation between the two
+        if b % 2 == 0:   # the step as one call (its tail is one kernel) and as two: the same arithmetic, bit for bit
+            cache.lookup_update(q, th, idx_log[b], sim_log[b], hit_log[b])
+        else:
+            cache.lookup(q, th, idx_log[b], sim_log[b], hit_log[b])
+            cache.update(q, idx_log[b], hit_log[b])          # no host synchronisation between the two
 
     def lockstep(b, label):
         gpu_step(b)

@@ -319,3 +319,57 @@ def test_merge_apply_meta_hand_worked_and_random(siso, oracle):
     compare_state(cache, oc, "bf16", "merge_apply with cluster sizes and access counts")
     ol, oa = oc.export_meta()
     assert (oa == 0xFFFFFFFF).sum() >= 3 and len(np.unique(ol)) > 100
+
+
+def same_state(a, b):
+    """Two caches hold bit-identical centroids, means, sizes and metadata."""
+    ea, eb = a.export(), b.export()
+    ma, mb = a.export_meta(), b.export_meta()
+    torch.cuda.synchronize()
+    return all(torch.equal(x.view(torch.uint8) if x.dtype.is_floating_point else x,
+                           y.view(torch.uint8) if y.dtype.is_floating_point else y) for x, y in zip(ea + ma, eb + mb))
+
+
+@pytest.mark.parametrize("dtype,dim,K,n,clusters", [
+    ("bf16", 768, 5000, 64, 256),      # batches of 64: the streaming shape (256 x 64 tiles)
+    ("bf16", 256, 3000, 100, 8),       # 256 x 128 tiles; few clusters: many queries share a centroid
+    ("bf16", 1024, 2000, 1, 16), ("bf16", 2048, 900, 37, 4),
+    ("f32", 384, 1024, 256, 16),       # the scalar kernel, a full board
+    ("bf16", 768, 5000, 200, 64),      # the wide kernel names groups of rows: the two calls
+    ("f32", 96, 700, 300, 16)])        # more queries than the board has slots: the two calls
+def test_lookup_update_is_lookup_then_update_hits(siso, oracle, dtype, dim, K, n, clusters):
+    print(f"case: lookup_update {dtype} dim={dim} K={K} n={n}", flush=True)
+    wl = W.c2_mid(n_clusters=clusters, per_cluster=(K + clusters - 1) // clusters, n_queries=n * 6, dim=dim, dtype=dtype, seed=77)
+    wl.centroids = wl.centroids[:K].copy()
+    counts = W.random_counts(78, K, 1, 5)
+    one = siso.SisoCache(dim, K, siso_dtype(dtype))
+    two = siso.SisoCache(dim, K, siso_dtype(dtype))
+    oc = oracle.OracleCache(dim, K, dtype)
+    for c in (one, two):
+        c.load(to_dev(wl.centroids, dtype), torch.from_numpy(counts).to(DEV))
+    oc.load(wl.centroids, counts)
+    theta = 0.85
+    for step in range(6):
+        qs = wl.queries[step * n:(step + 1) * n].copy()
+        if step == 2 and n >= 4:
+            qs[1] = qs[0]                      # the same query twice: two members of one centroid for sure
+            qs[3] = 0                          # a query without length: no hit, nothing folded
+        q = to_dev(qs, dtype)
+        out = one.lookup_update(q, theta)
+        ref = two.lookup(q, theta)
+        two.update(q, ref[0], ref[2])
+        torch.cuda.synchronize()
+        assert all(torch.equal(a, b) for a, b in zip(out[:1] + out[2:], ref[:1] + ref[2:])), f"step {step}: idx / hit"
+        assert torch.equal(out[1].view(torch.int32), ref[1].view(torch.int32)), f"step {step}: sim"
+        assert same_state(one, two), f"step {step}: state differs from lookup + update_hits"
+        # and against the oracle: lookup on its state, fold its hits
+        ora = oc.lookup(qs, theta)
+        st = check_lookup(out, ora, theta, dtype, f"lookup_update step {step}")
+        gh = out[2].cpu().numpy()
+        if np.array_equal(gh, ora[2]) and np.array_equal(out[0].cpu().numpy()[gh == 1], ora[0][gh == 1]):
+            oc.update(qs, np.where(ora[2] == 1, ora[0], -1).astype(np.int32))
+        else:   # a similarity within rounding of the threshold or of the runner-up: the oracle follows the GPU's choice
+            oc.update(qs, np.where(gh == 1, out[0].cpu().numpy(), -1).astype(np.int32))
+        compare_state(one, oc, dtype, f"lookup_update step {step}")
+    assert int(one.export()[2].sum().item()) > int(counts.sum())        # something was folded
+    assert one.bad_indices() == 0
