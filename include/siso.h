@@ -222,8 +222,9 @@ int siso_update_hits(siso_cache *c, const void *queries, const int *idx, const u
  * Batches of at most 256 queries whose lookup runs on kernels that name the winning
  * row (bf16 batches of at most 128 on the MFMA kernels, fp32 caches) finish in one
  * kernel that ends the lookup and applies the update: the workgroups of the batch tell
- * each other their (index, hit) through 256 slots of device memory of the cache, and
- * each waits, a bounded time, until all slots of the call are written; one that gives up
+ * each other their (index, hit) through 256 slots of device memory of the cache (emptied
+ * by the kernel before, so the call can be captured in a graph and replayed), and each
+ * waits, a bounded time, until all slots of the batch are written; one that gives up
  * (never observed: all workgroups are resident together) leaves its centroid as it was
  * and is counted by siso_bad_indices.  Other batches run the two calls.  Asynchronous;
  * allocates what siso_lookup and siso_update_hits would (siso_reserve avoids that).

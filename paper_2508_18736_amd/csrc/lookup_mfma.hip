@@ -350,11 +350,13 @@ template <class Cfg, bool COLLECT = false>
 __global__ __launch_bounds__(Cfg::NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void k_lookup_pipe(
     const bf16_t *__restrict__ Q, const bf16_t *__restrict__ C, const float *__restrict__ invn, long n, long K, int d,
     int tiles_per_slice, int slices, int nqt, int qb, u64 *__restrict__ keys, const float *__restrict__ tau,
-    int *__restrict__ cand, int *__restrict__ cand_cnt, int cand_cap) {
+    int *__restrict__ cand, int *__restrict__ cand_cnt, int cand_cap, u64 *__restrict__ board) {
     constexpr int WC = Cfg::WC, WQ = Cfg::WQ, NWC = Cfg::NWC, BC = Cfg::BC, BQ = Cfg::BQ, NT = Cfg::NT, NW = Cfg::NW,
                   STAGE = Cfg::STAGE, NLA = Cfg::NLA, NLB = Cfg::NLB, NL = Cfg::NL, NSTAGE = Cfg::NSTAGE, BK = Cfg::BK,
                   RB = Cfg::RB, CPR = Cfg::CPR, RPI = Cfg::RPI, RP = Cfg::RP, KK = Cfg::KK, SUB = 32 * Cfg::RB, ES = Cfg::ES;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    // (a step that ends in k_finalize_update: the slots of its board are emptied here, a kernel ahead)
+    if (board != nullptr && blockIdx.x == 0 && threadIdx.x < SISO_FOLD_BOARD) board[threadIdx.x] = 0;
     // Inverse lengths of the tiles in flight, [NINV][BC], tile ct in buffer (ct - ct_begin) % NINV.  Those of
     // tile X are requested NSTAGE slabs ahead of its first slab, i.e. while slab X * nk - NSTAGE is multiplied,
     // into the buffer that tile X - NINV used; that tile's epilogue ran with slab (X - NINV + 1) * nk - 1.  So
@@ -1567,7 +1569,8 @@ static int launch_cfg(siso_cache *c, const void *queries, long n, const PipePlan
     hipLaunchKernelGGL((k_lookup_pipe<Cfg>), dim3((unsigned)p.grid), dim3(Cfg::NT), Cfg::LDS_BYTES,
                        c->stream, (const bf16_t *)queries, (const bf16_t *)c->cent, c->invn, n, c->count, c->dim,
                        p.tiles_per_slice, p.slices, p.nqt, p.qb, keys, (const float *)nullptr, (int *)nullptr,
-                       (int *)nullptr, 0);
+                       (int *)nullptr, 0, c->board_to_clear);
+    c->board_to_clear = nullptr;  // taken
     return siso_check_hip(c, hipGetLastError(), "k_lookup_pipe");
 }
 
@@ -1583,7 +1586,7 @@ static int launch_collect(siso_cache *c, const void *queries, long n, const Pipe
     }
     hipLaunchKernelGGL((k_lookup_pipe<Cfg, true>), dim3((unsigned)p.grid), dim3(Cfg::NT), Cfg::LDS_BYTES,
                        c->stream, (const bf16_t *)queries, (const bf16_t *)c->cent, c->invn, n, c->count, c->dim,
-                       p.tiles_per_slice, p.slices, p.nqt, p.qb, (u64 *)nullptr, tau, cand, cnt, cap);
+                       p.tiles_per_slice, p.slices, p.nqt, p.qb, (u64 *)nullptr, tau, cand, cnt, cap, (u64 *)nullptr);
     return siso_check_hip(c, hipGetLastError(), "k_lookup_pipe (collect)");
 }
 

@@ -307,9 +307,11 @@ __device__ __forceinline__ void scalar_tile(const T *__restrict__ A, long a0, lo
 template <typename T>
 __global__ __launch_bounds__(256) void k_lookup_scalar(const T *__restrict__ Q, const T *__restrict__ cent,
                                                         const float *__restrict__ invn, long n, long K, int d,
-                                                        long rows_per_slice, int slices, u64 *keys) {
+                                                        long rows_per_slice, int slices, u64 *keys, u64 *board) {
     __shared__ float As[ST_K][ST_M + 4];
     __shared__ float Bs[ST_K][ST_M + 4];
+    // (a step that ends in k_finalize_update: the slots of its board are emptied here, a kernel ahead)
+    if (board != nullptr && blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x < SISO_FOLD_BOARD) board[threadIdx.x] = 0;
     const long q0 = (long)blockIdx.x * ST_M;
     const int s = blockIdx.y;
     const long c_begin = (long)s * rows_per_slice;
@@ -375,7 +377,8 @@ static int scalar_launch_t(siso_cache *c, const void *queries, long n, int slice
     const long rows_per_slice = ((ctiles + slices - 1) / slices) * ST_M;
     dim3 grid((unsigned)((n + ST_M - 1) / ST_M), (unsigned)slices);
     hipLaunchKernelGGL(k_lookup_scalar<T>, grid, dim3(256), 0, c->stream, (const T *)queries, (const T *)c->cent,
-                       c->invn, n, c->count, c->dim, rows_per_slice, slices, keys);
+                       c->invn, n, c->count, c->dim, rows_per_slice, slices, keys, c->board_to_clear);
+    c->board_to_clear = nullptr;  // taken
     return siso_check_hip(c, hipGetLastError(), "k_lookup_scalar");
 }
 
@@ -451,6 +454,24 @@ __global__ void k_update_mark_init(int *owner, int *members, long capacity) {
     }
 }
 
+// One member of a centroid: x = this thread's elements (t + 256 e) of the query; the query at unit length is
+// added to acc (queries without length or with a non-finite element are passed over).  Uniform over the
+// block.  Every operation is spelled out with its rounding, here and in update_write, so that k_update and
+// k_finalize_update do the same arithmetic whatever the compiler would fuse in either of them.
+template <int UPD_MAXE_T>
+__device__ __forceinline__ bool fold_member(const float (&x)[UPD_MAXE_T], float (&acc)[UPD_MAXE_T], float *sh) {
+    float ss = 0.f;
+#pragma unroll
+    for (int e = 0; e < UPD_MAXE_T; ++e) ss = __fmaf_rn(x[e], x[e], ss);
+    const float n2 = block_sum256(ss, sh);
+    const float inv = inv_length(n2);
+    if (!(inv == inv && inv > 0.f)) return false;
+    const float nrm = sqrtf(n2);
+#pragma unroll
+    for (int e = 0; e < UPD_MAXE_T; ++e) acc[e] = __fadd_rn(acc[e], __fdiv_rn(x[e], nrm));
+    return true;
+}
+
 // The end of an update, by the block that leads centroid k: acc = the sum of its `members` unit-length members
 // (this thread's elements t + 256 e), m_old / size_old = the mean and its weight as they were.  Writes the
 // new mean and weight, the stored row (the mean at unit length, rounded to the storage type; left alone when
@@ -469,9 +490,9 @@ __device__ __forceinline__ void update_write(int k, int d, int size_old, int mem
         const int col = t + e * 256;
         m[e] = 0.f;
         if (col < d) {
-            m[e] = (n_old * m_old[e] + acc[e]) / n_new;
+            m[e] = __fdiv_rn(__fmaf_rn(n_old, m_old[e], acc[e]), n_new);
             mean[(size_t)k * d + col] = m[e];
-            ss += m[e] * m[e];
+            ss = __fmaf_rn(m[e], m[e], ss);
         }
     }
     const float n2 = block_sum256(ss, sh);
@@ -484,10 +505,10 @@ __device__ __forceinline__ void update_write(int k, int d, int size_old, int mem
         const int col = t + e * 256;
         if (col < d) {
             T r;
-            narrow(m[e] / nrm, &r);
+            narrow(__fdiv_rn(m[e], nrm), &r);
             cent[(size_t)k * d + col] = r;
             const float back = widen(r);
-            cs += back * back;
+            cs = __fmaf_rn(back, back, cs);
         }
     }
     const float c2 = block_sum256(cs, sh);
@@ -556,17 +577,7 @@ __global__ __launch_bounds__(256) void k_update(const T *__restrict__ Q, const i
     int members = 0;
     // fold one query (its elements of this thread in x) into the sum; uniform over the block
     auto fold = [&](const float(&x)[UPD_MAXE_T]) {
-        float ss = 0.f;
-#pragma unroll
-        for (int e = 0; e < UPD_MAXE_T; ++e) ss += x[e] * x[e];
-        const float n2 = block_sum256(ss, sh);
-        const float inv = inv_length(n2);
-        if (inv == inv && inv > 0.f) {
-            const float nrm = sqrtf(n2);
-#pragma unroll
-            for (int e = 0; e < UPD_MAXE_T; ++e) acc[e] += x[e] / nrm;
-            ++members;
-        }
+        if (fold_member<UPD_MAXE_T>(x, acc, sh)) ++members;
     };
     if (alone) {
         fold(x_me);
@@ -617,23 +628,25 @@ __global__ __launch_bounds__(256) void k_update(const T *__restrict__ Q, const i
 // does for it, with the same arithmetic in the same order, so the outputs and the state are those of the
 // two kernels bit for bit.  What a block needs from the others is their (index, hit) - to know whether it
 // leads its centroid and which other queries fold into it - and that crosses the grid through a board of
-// one 64-bit slot per query: (number of the call, hit, index), written and read with device-scope atomic
-// operations.  A slot is valid when it carries the number of this call, so nothing is cleared and no fence
-// is needed (the rows and means the blocks read were written by earlier kernels).  All blocks of the grid
+// one 64-bit slot per query: (written, hit, index), written and read with device-scope atomic operations.
+// The slots are emptied by the kernel before this one - the first phase of the same lookup, whose first
+// block does it when siso_lookup_update asks for it - so the end of that kernel stands between the emptying
+// and the first entry, also when the launches are replayed from a captured graph, and no fence is needed
+// (the rows and means the blocks read were written by earlier kernels too).  All blocks of the grid
 // are resident together (at most 256 small blocks), so the wait for the slots ends; it is bounded all the
 // same: a block that gives up leaves its centroid as it was and counts its query as not applied.
 // Saves a launch and the gap before it, and the loads of the update (own row, mean of the centroid) are on
 // their way while the block waits for the board.
 // ============================================================================
-#define FOLD_BOARD 256
-__device__ __forceinline__ u64 board_entry(unsigned call, bool hit, int idx) {
-    return ((u64)call << 33) | ((u64)(hit ? 1 : 0) << 32) | (u64)(unsigned)idx;
+#define FOLD_BOARD SISO_FOLD_BOARD
+__device__ __forceinline__ u64 board_entry(bool hit, int idx) {
+    return (1ull << 63) | ((u64)(hit ? 1 : 0) << 32) | (u64)(unsigned)idx;
 }
 template <typename T, int UPD_MAXE_T>
 __global__ __launch_bounds__(256) void k_finalize_update(const T *__restrict__ Q, const u64 *__restrict__ keys, long n, long K,
                                                           int d, int slices, float theta, int vec, int *out_idx,
                                                           float *out_sim, unsigned char *out_hit, unsigned *access, T *cent,
-                                                          float *mean, int *size, float *invn, u64 *board, unsigned call,
+                                                          float *mean, int *size, float *invn, u64 *board,
                                                           int spin_limit, u64 *gave_up) {
     constexpr int EPC = 16 / (int)sizeof(T);
     __shared__ float sh[4];
@@ -695,7 +708,7 @@ __global__ __launch_bounds__(256) void k_finalize_update(const T *__restrict__ Q
         out_sim[me] = best_s;
         out_hit[me] = hit ? 1 : 0;
         if (hit && access && access[best_i] != SISO_ACCESS_INF) atomicAdd(&access[best_i], 1u);
-        __hip_atomic_store(board + me, board_entry(call, hit, (int)best_i), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_store(board + me, board_entry(hit, (int)best_i), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
     if (!hit) return;
     // --- k_update for query `me`: its centroid's mean and weight, on their way during the wait
@@ -712,7 +725,7 @@ __global__ __launch_bounds__(256) void k_finalize_update(const T *__restrict__ Q
         x_me[e] = t + e * 256 < d ? widen(xr[e]) : 0.f;
         asm volatile("" ::"v"(x_me[e]), "v"(m_old[e]));  // (the loads are issued here, not behind the wait)
     }
-    // the board: wave 0 reads the slots until all of them carry this call's number
+    // the board: wave 0 reads the slots until all of them are written
     if (wave == 0) {
         bool all = false;
         for (int tries = 0; tries < spin_limit && !all; ++tries) {
@@ -720,7 +733,7 @@ __global__ __launch_bounds__(256) void k_finalize_update(const T *__restrict__ Q
             for (int j = lane; j < (int)n; j += 64) {
                 const u64 v = __hip_atomic_load(board + j, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 sh_board[j] = v;
-                mine = mine && (unsigned)(v >> 33) == call;
+                mine = mine && (v >> 63) != 0;
             }
             all = __ballot(!mine) == 0;
             if (!all) __builtin_amdgcn_s_sleep(4);
@@ -737,20 +750,10 @@ __global__ __launch_bounds__(256) void k_finalize_update(const T *__restrict__ Q
     for (int e = 0; e < UPD_MAXE_T; ++e) acc[e] = 0.f;
     int members = 0;
     auto fold = [&](const float(&x)[UPD_MAXE_T]) {
-        float s2 = 0.f;
-#pragma unroll
-        for (int e = 0; e < UPD_MAXE_T; ++e) s2 += x[e] * x[e];
-        const float n2 = block_sum256(s2, sh);
-        const float inv = inv_length(n2);
-        if (inv == inv && inv > 0.f) {
-            const float nrm = sqrtf(n2);
-#pragma unroll
-            for (int e = 0; e < UPD_MAXE_T; ++e) acc[e] += x[e] / nrm;
-            ++members;
-        }
+        if (fold_member<UPD_MAXE_T>(x, acc, sh)) ++members;
     };
     // the members of centroid k in ascending order (a hit whose index is k)
-    const bool m = t < (int)n && sh_board[t] == board_entry(call, true, k);
+    const bool m = t < (int)n && sh_board[t] == board_entry(true, k);
     const u64 mask = __ballot(m);
     if (lane == 0) masks[wave] = mask;
     __syncthreads();
@@ -1144,9 +1147,9 @@ extern "C" int siso_create_ex(int dim, long capacity, int dtype, siso_cache **ou
     ok = ok && hipMalloc((void **)&c->locality, (size_t)capacity * sizeof(float)) == hipSuccess;
     ok = ok && hipMalloc((void **)&c->access, (size_t)capacity * sizeof(unsigned)) == hipSuccess;
     // (behind the four counters: the board of siso_lookup_update, one slot per query of a small batch)
-    ok = ok && hipMalloc((void **)&c->counters, (4 + FOLD_BOARD) * sizeof(u64)) == hipSuccess;
+    ok = ok && hipMalloc((void **)&c->counters, (4 + SISO_FOLD_BOARD) * sizeof(u64)) == hipSuccess;
     ok = ok && hipHostMalloc((void **)&c->host_pin, 4 * sizeof(u64), hipHostMallocDefault) == hipSuccess;
-    ok = ok && hipMemset(c->counters, 0, (4 + FOLD_BOARD) * sizeof(u64)) == hipSuccess;
+    ok = ok && hipMemset(c->counters, 0, (4 + SISO_FOLD_BOARD) * sizeof(u64)) == hipSuccess;
     ok = ok && hipDeviceSynchronize() == hipSuccess;
     if (!ok) {
         (void)hipGetLastError();
@@ -1405,6 +1408,8 @@ int siso_lookup_impl(siso_cache *c, const void *queries, long n, const float *th
     tl.count_at = count_index;
     for (int j = 0; j < SISO_MULTI_MAX; ++j) tl.v[j] = j < m ? thetas[j] : 0.f;
     int row_keys = SISO_KEY_ROWS;  // what the keys of the chosen kernel carry: the winning row, or its group of four rows
+    const bool may_fold = folded && n <= SISO_FOLD_BOARD && c->count > 0 && !fp8 && m == 1 && out_hit;
+    c->board_to_clear = may_fold ? c->counters + 4 : nullptr;
     if (c->count > 0) {
         if (!static_keys) siso_prof_begin(c);
         switch (path) {
@@ -1413,16 +1418,21 @@ int siso_lookup_impl(siso_cache *c, const void *queries, long n, const float *th
             case SISO_PATH_SKINNY: rc = siso_skinny_launch(c, kernel_queries, n, slices, keys, &row_keys); break;
         }
         if (!static_keys) siso_prof_end(c);
-        if (rc != SISO_OK) return rc;
+        if (rc != SISO_OK) {
+            c->board_to_clear = nullptr;
+            return rc;
+        }
     }
-    if (folded && n <= FOLD_BOARD && c->count > 0 && row_keys == SISO_KEY_ROWS && !fp8 && m == 1 && out_hit) {
+    // (a kernel that empties the board takes the pointer; one that does not know of it leaves it)
+    const bool board_emptied = may_fold && c->board_to_clear == nullptr;
+    c->board_to_clear = nullptr;
+    if (board_emptied && row_keys == SISO_KEY_ROWS) {
         // the end of the lookup and the update of its hits as one kernel (see k_finalize_update)
-        c->fold_call = c->fold_call >= 0x7FFFFFFFu ? 1u : c->fold_call + 1u;
         const int spin_limit = 1 << 18;  // polls of the board (a microsecond or two each) before a block gives up
 #define SISO_LAUNCH_FOLD(T, E)                                                                                            \
     hipLaunchKernelGGL((k_finalize_update<T, E>), dim3(qblocks), dim3(256), 0, c->stream, (const T *)queries, keys, n, c->count, \
                        c->dim, slices, thetas[0], vec, out_idx, out_sim, out_hit, count_index >= 0 ? c->access : nullptr, \
-                       (T *)c->cent, c->mean, c->size, c->invn, c->counters + 4, c->fold_call, spin_limit, c->counters)
+                       (T *)c->cent, c->mean, c->size, c->invn, c->counters + 4, spin_limit, c->counters)
         if (c->dtype == SISO_F32) {
             if (c->dim <= 1024) SISO_LAUNCH_FOLD(float, 4);
             else SISO_LAUNCH_FOLD(float, 16);

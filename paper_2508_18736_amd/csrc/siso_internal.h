@@ -27,6 +27,7 @@ typedef unsigned short bf16_t;  // bfloat16 bit pattern
 enum { SISO_KEY_ROWS = 1, SISO_KEY_GROUPS4 = 3 };
 #define SISO_ACCESS_INF 0xFFFFFFFFu
 #define SISO_MAX_DIM 4096
+#define SISO_FOLD_BOARD 256  // queries of a siso_lookup_update that ends in one kernel: one slot each
 #define SISO_MULTI_MAX 32  // thresholds one lookup can be judged against
 #define SISO_PAD_ROWS 256  // readable rows past the capacity of the stored-centroid array
 
@@ -67,7 +68,7 @@ struct siso_cache {
     u64 *static_keys;  // this device's copy of the library's static key array (siso_lookup_static)
 
     u64 *counters;  // device: [0] bad update indices, [1] merge pair count, [2] scratch, [3] scratch; behind them the
-                    // board of siso_lookup_update (256 slots)
+                    // board of siso_lookup_update (SISO_FOLD_BOARD slots)
     u64 *host_pin;  // pinned host mirror for counter read-back (4 entries)
 
     // 8-bit storage (SISO_FP8): cent holds one E4M3 code per element, scale [capacity] the scale of every row
@@ -85,7 +86,8 @@ struct siso_cache {
     int *topk_cand;
     long topk_cap;
     int plan_min_slices;  // > 0 while a top-k lookup plans its passes: at least this many slices (if the tiles allow)
-    unsigned fold_call;   // number of the last siso_lookup_update that ended in one kernel (stamps its board entries)
+    u64 *board_to_clear;  // not NULL while siso_lookup_update launches its first phase: a kernel that empties these
+                          // slots sets it back to NULL
 
     // tuning knobs (siso_set_option); 0 = library default
     int opt_mfma_config;

@@ -1,4 +1,4 @@
-"""The serving calls (siso_lookup, siso_update_hits) never synchronise and, once warmed up, never
+"""The serving calls (siso_lookup, siso_update_hits, siso_lookup_update) never synchronise and, once warmed up, never
 allocate: a loop of them can be captured in a HIP graph and replayed.  Every replay is checked
 against the eager result, with eager work and synchronisations of the program between replays."""
 
@@ -18,9 +18,11 @@ def siso():
     return m
 
 
-@pytest.mark.parametrize("n", [64, 300])
-def test_lookup_and_update_in_a_graph(siso, n):
-    print(f"case: graph n={n}", flush=True)
+@pytest.mark.parametrize("n,one_call", [(64, False), (300, False), (64, True), (100, True), (300, True)])
+def test_lookup_and_update_in_a_graph(siso, n, one_call):
+    """one_call: the step is siso_lookup_update (small batches: one kernel ends the lookup and applies the update; the
+    number that marks a launch's entries on its board lives on the device, so every replay has its own)."""
+    print(f"case: graph n={n} one_call={one_call}", flush=True)
     wl = W.c4_stream(n_clusters=256, per_cluster=8, batches=4, batch=n, dim=256, seed=23)
     cents = to_dev(wl.centroids, "bf16")
     batches = [to_dev(wl.queries[b * n:(b + 1) * n], "bf16") for b in range(4)]
@@ -50,12 +52,16 @@ def test_lookup_and_update_in_a_graph(siso, n):
         q_in.copy_(batches[0])
         cache.lookup(q_in, 0.85, idx, sim, hit)  # warm-up: workspaces and kernel attributes are set now
         cache.update(q_in, idx, hit)
+        cache.lookup_update(q_in, 0.85, idx, sim, hit)
         cache.load(cents)                         # back to the initial state
     side.synchronize()
     graph = torch.cuda.CUDAGraph()
     with torch.cuda.graph(graph, stream=side):
-        cache.lookup(q_in, 0.85, idx, sim, hit)
-        cache.update(q_in, idx, hit)
+        if one_call:
+            cache.lookup_update(q_in, 0.85, idx, sim, hit)
+        else:
+            cache.lookup(q_in, 0.85, idx, sim, hit)
+            cache.update(q_in, idx, hit)
     for b, q in enumerate(batches):
         q_in.copy_(q)                             # eager work of the program between the replays
         torch.cuda.synchronize()
@@ -68,3 +74,4 @@ def test_lookup_and_update_in_a_graph(siso, n):
     torch.cuda.synchronize()
     for g, w in zip(got_state, want_state):
         assert torch.equal(g, w)
+    assert cache.bad_indices() == 0
