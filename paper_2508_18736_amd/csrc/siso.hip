@@ -1127,6 +1127,7 @@ extern "C" int siso_create_ex(int dim, long capacity, int dtype, siso_cache **ou
     siso_cache *c = new (std::nothrow) siso_cache();
     if (!c) return SISO_ENOMEM;
     memset(c, 0, sizeof(*c));
+    c->opt_fold_spin_limit = -1;
     c->dim = dim;
     c->capacity = capacity;
     c->dtype = dtype;
@@ -1214,11 +1215,16 @@ extern "C" int siso_set_lookup_path(siso_cache *c, int path) {
 
 extern "C" int siso_set_option(siso_cache *c, const char *name, long value) {
     if (!c || !name) return SISO_EINVAL;
+    if (!strcmp(name, "fold_spin_limit") && value == -1) {
+        c->opt_fold_spin_limit = -1;
+        return SISO_OK;
+    }
     if (value < 0 || value > 1000000) return siso_fail(c, SISO_EINVAL, "option %s: value %ld out of range", name, value);
     if (!strcmp(name, "mfma_config")) c->opt_mfma_config = (int)value;
     else if (!strcmp(name, "tiles_per_slice")) c->opt_tiles_per_slice = (int)value;
     else if (!strcmp(name, "merge_config")) c->opt_merge_config = (int)value;
     else if (!strcmp(name, "mfma_qblock")) c->opt_mfma_qblock = (int)value;
+    else if (!strcmp(name, "fold_spin_limit")) c->opt_fold_spin_limit = (int)value;
     else if (!strcmp(name, "second_set")) return value ? siso_second_set(c) : SISO_OK;
     else return siso_fail(c, SISO_EINVAL, "unknown option %s", name);
     return SISO_OK;
@@ -1428,7 +1434,8 @@ int siso_lookup_impl(siso_cache *c, const void *queries, long n, const float *th
     c->board_to_clear = nullptr;
     if (board_emptied && row_keys == SISO_KEY_ROWS) {
         // the end of the lookup and the update of its hits as one kernel (see k_finalize_update)
-        const int spin_limit = 1 << 18;  // polls of the board (a microsecond or two each) before a block gives up
+        // polls of the board (a microsecond or two each) before a block gives up
+        const int spin_limit = c->opt_fold_spin_limit >= 0 ? c->opt_fold_spin_limit : 1 << 18;
 #define SISO_LAUNCH_FOLD(T, E)                                                                                            \
     hipLaunchKernelGGL((k_finalize_update<T, E>), dim3(qblocks), dim3(256), 0, c->stream, (const T *)queries, keys, n, c->count, \
                        c->dim, slices, thetas[0], vec, out_idx, out_sim, out_hit, count_index >= 0 ? c->access : nullptr, \

@@ -94,6 +94,7 @@ struct siso_cache {
     int opt_tiles_per_slice;
     int opt_merge_config;
     int opt_mfma_qblock;
+    int opt_fold_spin_limit;  // -1 = default
 
     // kernel timing (siso_profile_enable / siso_profile_read)
     int profile_on;       // 0 = off, N = bracket every N-th call

@@ -373,3 +373,64 @@ def test_lookup_update_is_lookup_then_update_hits(siso, oracle, dtype, dim, K, n
         compare_state(one, oc, dtype, f"lookup_update step {step}")
     assert int(one.export()[2].sum().item()) > int(counts.sum())        # something was folded
     assert one.bad_indices() == 0
+
+
+def test_lookup_update_workgroups_that_give_up_leave_the_cache_alone(siso, oracle):
+    """The wait of the one-kernel end is bounded.  With a limit of zero looks at the board every workgroup whose
+    query hits gives up at once: the lookup's outputs are unchanged, no centroid is touched, and every hit is
+    counted as not applied.  With the default limit again the same batch is folded."""
+    print("case: lookup_update, bounded wait", flush=True)
+    wl = W.c2_mid(n_clusters=64, per_cluster=16, n_queries=64, dim=256, seed=79)
+    cache = siso.SisoCache(wl.dim, wl.K, siso.BF16)
+    cache.load(to_dev(wl.centroids, "bf16"))
+    q = to_dev(wl.queries, "bf16")
+    ref = cache.lookup(q, 0.85)
+    before = [x.clone() for x in cache.export()]
+    cache.set_option("fold_spin_limit", 0)
+    out = cache.lookup_update(q, 0.85)
+    torch.cuda.synchronize()
+    hits = int(ref[2].sum().item())
+    assert hits > 20 and all(torch.equal(a, b) for a, b in zip(out, ref))
+    assert all(torch.equal(a, b) for a, b in zip(cache.export(), before))
+    assert cache.bad_indices() == hits
+    cache.set_option("fold_spin_limit", -1)
+    cache.lookup_update(q, 0.85)
+    torch.cuda.synchronize()
+    assert int(cache.export()[2].sum().item()) == wl.K + hits and cache.bad_indices() == hits
+    oc = oracle.OracleCache(wl.dim, wl.K, "bf16")
+    oc.load(wl.centroids)
+    ora = oc.lookup(wl.queries, 0.85)
+    oc.update(wl.queries, np.where(ora[2] == 1, ora[0], -1).astype(np.int32))
+    # (the access counts saw three lookups on the GPU: compare what the update writes)
+    assert np.array_equal(cache.export()[2].cpu().numpy(), oc.export()[2])
+    assert np.abs(cache.export()[1].cpu().numpy().astype(np.float64) - oc.export()[1]).max() <= MEAN_TOL
+
+
+def test_lookup_update_next_to_a_long_kernel_on_another_stream(siso, oracle):
+    """The workgroups of the one-kernel end wait for each other; they must all get onto the chip even while another
+    stream keeps it busy with large lookups of another cache."""
+    print("case: lookup_update beside large lookups on another stream", flush=True)
+    big = W.c2_mid(n_clusters=2048, per_cluster=16, n_queries=4096, dim=768, seed=80)
+    big_cache = siso.SisoCache(big.dim, big.K, siso.BF16)
+    big_cache.load(to_dev(big.centroids, "bf16"))
+    bq = to_dev(big.queries, "bf16")
+    big_out = big_cache.lookup(bq, 0.85)     # its outputs stay allocated: the other stream writes them while this one goes on
+    wl = W.c4_stream(n_clusters=256, per_cluster=8, batches=40, batch=64, dim=256, seed=81)
+    alone, beside = siso.SisoCache(wl.dim, wl.K, siso.BF16), siso.SisoCache(wl.dim, wl.K, siso.BF16)
+    qs = to_dev(wl.queries, "bf16")
+    for c in (alone, beside):
+        c.load(to_dev(wl.centroids, "bf16"))
+        c.reserve(64)
+    outs_alone = [tuple(x.clone() for x in alone.lookup_update(qs[b * 64:(b + 1) * 64], 0.85)) for b in range(40)]
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    big_cache.set_stream(side)
+    outs = []
+    for b in range(40):
+        big_cache.lookup(bq, 0.85, *big_out)       # 0.3 ms each, on the other stream
+        outs.append(tuple(x.clone() for x in beside.lookup_update(qs[b * 64:(b + 1) * 64], 0.85)))
+    torch.cuda.synchronize()
+    big_cache.set_stream(torch.cuda.current_stream())
+    for b in range(40):
+        assert all(torch.equal(x, y) for x, y in zip(outs[b], outs_alone[b])), f"batch {b}"
+    assert same_state(alone, beside) and beside.bad_indices() == 0
