@@ -256,25 +256,16 @@ __device__ __forceinline__ void emit_pairs(unsigned mask, int i, RowOf row_of, i
 }
 
 // The same with a staging buffer of the workgroup in LDS (stage[room][2], *staged = entries taken):
-// the wave takes its slots with one LDS atomic, which costs a fraction of the round trip of a global
+// the lanes take their slots with LDS atomics, which cost a fraction of the round trip of a global
 // one; what does not fit any more goes straight to the global list.  Every lane must call it.
 template <class RowOf>
 __device__ __forceinline__ void emit_pairs_staged(unsigned mask, int i, RowOf row_of, int *stage, int *staged, int room,
                                                   int *out, long cap, u64 *counter) {
-    const int lane = threadIdx.x & 63;
+    // few lanes hold pairs (a block of 32 x 32 products with one group of near-duplicates in it): each of them
+    // takes its slots with an LDS atomic of its own, which is cheaper than a prefix sum over the wave
     const int cnt = __popc(mask);
-    int incl = cnt;
-#pragma unroll
-    for (int off = 1; off < 64; off <<= 1) {
-        const int t = __shfl_up(incl, off);
-        if (lane >= off) incl += t;
-    }
-    const int total = __shfl(incl, 63);
-    if (total == 0) return;
-    int base = 0;
-    if (lane == 63) base = atomicAdd(staged, total);
-    base = __shfl(base, 63);
-    int pos = base + incl - cnt;
+    if (__ballot(cnt != 0) == 0) return;
+    int pos = cnt != 0 ? atomicAdd(staged, cnt) : 0;
     unsigned rest = 0;  // pairs of this lane that found no room
     while (mask != 0) {
         const int I = __ffs((int)mask) - 1;
@@ -287,7 +278,7 @@ __device__ __forceinline__ void emit_pairs_staged(unsigned mask, int i, RowOf ro
         }
         ++pos;
     }
-    if (base + total > room) emit_pairs(rest, i, row_of, out, cap, counter);  // uniform over the wave
+    if (__ballot(rest != 0) != 0) emit_pairs(rest, i, row_of, out, cap, counter);  // uniform over the wave
 }
 
 // Move the staged pairs of the workgroup to the global list and empty the buffer.  Every thread of
