@@ -638,7 +638,6 @@ __global__ __launch_bounds__(256) void k_update(const T *__restrict__ Q, const i
 // Saves a launch and the gap before it, and the loads of the update (own row, mean of the centroid) are on
 // their way while the block waits for the board.
 // ============================================================================
-#define FOLD_BOARD SISO_FOLD_BOARD
 __device__ __forceinline__ u64 board_entry(bool hit, int idx) {
     return (1ull << 63) | ((u64)(hit ? 1 : 0) << 32) | (u64)(unsigned)idx;
 }
@@ -653,7 +652,7 @@ __global__ __launch_bounds__(256) void k_finalize_update(const T *__restrict__ Q
     __shared__ float sh_f[4];
     __shared__ u64 sh_k[4];
     __shared__ u64 masks[4];
-    __shared__ u64 sh_board[FOLD_BOARD];
+    __shared__ u64 sh_board[SISO_FOLD_BOARD];
     __shared__ int sh_all;
     const long me = blockIdx.x;
     const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
