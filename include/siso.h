@@ -9,7 +9,8 @@
  *             threshold test that judges a cache hit (Algorithm 1,
  *             MergeCentroids; section 3.1; batched online search: section 4.3);
  *   update  - fold queries into their centroid, the centroid being the average
- *             point of its group of vectors (section 3.1);
+ *             point of its group of vectors (section 3.1); lookup and update
+ *             of the hits as one call for the online loop;
  *   merge   - all-pairs centroid self-similarity above the clustering
  *             threshold (the comparison inside MergeCentroids taken over all
  *             pairs), then merging connected groups into their count-weighted
@@ -31,8 +32,9 @@
  *     The library never keeps a caller pointer after the call's work has
  *     finished on the stream.
  *   - All GPU work is enqueued on the stream given to siso_set_stream (the
- *     null stream by default).  siso_lookup, siso_update and siso_update_hits
- *     never synchronise with the host; the other calls say when they do.
+ *     null stream by default).  siso_lookup, siso_update, siso_update_hits and
+ *     siso_lookup_update never synchronise with the host; the other calls say
+ *     when they do.
  *   - Every call returns SISO_OK (0) or a negative error code; n = 0 is a
  *     successful no-op.  siso_last_error gives a message for the last failure
  *     on that cache.  No C++ exception crosses this boundary.
