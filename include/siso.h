@@ -77,9 +77,9 @@ enum {
  * cosine of the bf16 rows (each element keeps 4 significant bits; cosines move by about
  * 1e-3), not equal to it.  Half the bytes of bf16 per centroid, no running means (dim
  * bytes + 20 per centroid).  dim must be a multiple of 128, at least 256.  Available:
- * siso_load, siso_lookup, siso_lookup_multi, siso_lookup_topk, siso_t2h, siso_reserve, siso_count,
- * siso_export (codes; means must be NULL), siso_export_scales, siso_export_meta; the
- * other calls return SISO_EINVAL.
+ * siso_load, siso_lookup, siso_lookup_multi, siso_lookup_topk, siso_lookup_static,
+ * siso_t2h, siso_reserve, siso_count, siso_export (codes; means must be NULL),
+ * siso_export_scales, siso_export_meta; the other calls return SISO_EINVAL.
  */
 int siso_create(int dim, long capacity, siso_cache **out);
 int siso_create_ex(int dim, long capacity, int dtype, siso_cache **out);
@@ -179,7 +179,8 @@ int siso_lookup_topk(siso_cache *c, const void *queries, long n, int k, int *out
  * The array holds the last call's keys and every entry a call reads is written by
  * that call first, so nothing is cleared.  All calls on one GPU share the array:
  * calls that overlap on one GPU (two caches on two streams) race; calls on one
- * stream are ordered.
+ * stream are ordered.  An 8-bit cache quantises the batch into a workspace of the
+ * cache that siso_reserve sizes: a larger batch is rejected with SISO_ECAPACITY.
  */
 int siso_lookup_static(siso_cache *c, const void *queries, long n, float threshold, int *out_idx, float *out_sim,
                        unsigned char *out_hit);

@@ -1293,7 +1293,10 @@ extern "C" int siso_lookup_static(siso_cache *c, const void *queries, long n, fl
     if (!c) return SISO_EINVAL;
     if (n < 0 || (n > 0 && (!queries || !out_idx || !out_sim)))
         return siso_fail(c, SISO_EINVAL, "siso_lookup_static: bad arguments");
-    SISO_NOT_FP8(c, "siso_lookup_static");  // (the batch is quantised into a workspace that grows on demand)
+    // (an 8-bit cache quantises the batch into a workspace that siso_reserve sizes: this call does not grow it)
+    if (c->dtype == SISO_FP8 && n > c->fp8_q_cap)
+        return siso_fail(c, SISO_ECAPACITY, "siso_lookup_static: room for the codes of %ld queries, %ld asked for (siso_reserve sizes it)",
+                         c->fp8_q_cap, n);
     if (!c->static_keys) return siso_fail(c, SISO_EHIP, "siso_lookup_static: the static workspace was not found on device %d", c->device);
     return siso_lookup_impl(c, queries, n, &threshold, 1, 0, out_idx, out_sim, out_hit, c->static_keys, SISO_STATIC_KEYS);
 }

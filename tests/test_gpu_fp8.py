@@ -208,3 +208,44 @@ def test_fp8_topk_degenerate_queries_and_mid_size(siso, oracle):
     assert st["clear"] >= 40 and st["same"] > 0.97 and st["max_err"] < 2e-5
     one = cache.lookup(to_dev(wl.queries, "bf16"), 0.85)
     assert torch.equal(one[0], out[0][:, 0].contiguous())
+
+
+def test_fp8_lookup_that_allocates_nothing_and_its_replay_from_a_graph(siso, oracle):
+    """siso_lookup_static on an 8-bit cache: the batch is quantised into the workspace that siso_reserve sized (a
+    larger batch is refused); results are those of siso_lookup bit for bit; captured in a graph, every replay
+    gives the eager result."""
+    print("case: fp8 lookup_static + graph", flush=True)
+    wl = W.c4_stream(n_clusters=512, per_cluster=8, batches=4, batch=64, dim=256, seed=513)
+    cache = load_fp8(siso, wl)
+    qs = [to_dev(wl.queries[b * 64:(b + 1) * 64], "bf16") for b in range(4)]
+    out = tuple(torch.empty(64, dtype=t, device=DEV) for t in (torch.int32, torch.float32, torch.uint8))
+    fresh = load_fp8(siso, wl)
+    with pytest.raises(siso.SisoError):
+        fresh.lookup_static(qs[0], 0.85, *out)          # nothing reserved yet
+    cache.reserve(64)
+    want = [tuple(x.clone() for x in cache.lookup(q, 0.85)) for q in qs]
+    for q, w in zip(qs, want):
+        cache.lookup_static(q, 0.85, *out)
+        torch.cuda.synchronize()
+        assert all(torch.equal(a, b) for a, b in zip(out, w))
+    with pytest.raises(siso.SisoError):
+        cache.lookup_static(to_dev(wl.queries[:65], "bf16"), 0.85, *(torch.empty(65, dtype=t.dtype, device=DEV) for t in out))
+    oc, os_ = oracle.fp8_quantize(wl.centroids, "bf16")
+    check_lookup(want[0], oracle.fp8_lookup_rows(oc, os_, wl.queries[:64], 0.85), 0.85, "fp8", "fp8 static")
+    q_in = torch.empty_like(qs[0])
+    side = torch.cuda.Stream()
+    cache.set_stream(side)
+    with torch.cuda.stream(side):
+        q_in.copy_(qs[0])
+        cache.lookup_static(q_in, 0.85, *out)
+    side.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        cache.lookup_static(q_in, 0.85, *out)
+    for q, w in zip(qs, want):
+        q_in.copy_(q)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert all(torch.equal(a, b) for a, b in zip(out, w))
+    cache.set_stream(torch.cuda.current_stream())
