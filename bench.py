@@ -260,12 +260,12 @@ def main():
     if streaming:
         bytes_alg = K * d * eb + nb * d * eb + K * 4.0  # centroids + queries + inverse lengths, read once
         roof = {"bound": "hbm", "achieved": bytes_alg / avg_s / 1e9, "peak": PEAK_HBM_GBS, "unit": "GB/s",
-                "frac": bytes_alg / avg_s / 1e9 / PEAK_HBM_GBS, "traffic": None if fp8 else measured_traffic(name),
+                "frac": bytes_alg / avg_s / 1e9 / PEAK_HBM_GBS, "traffic": measured_traffic(name + ("_fp8" if fp8 else "")),
                 "algorithmic_bytes": bytes_alg, "kernel_ms": avg_s * 1e3,
                 "launches": launches}
     else:
         roof = {"bound": "mfma", "achieved": flop / avg_s / 1e12, "peak": peak_tflops, "unit": "TFLOP/s",
-                "frac": flop / avg_s / 1e12 / peak_tflops, "traffic": None if fp8 else measured_traffic(name),
+                "frac": flop / avg_s / 1e12 / peak_tflops, "traffic": measured_traffic(name + ("_fp8" if fp8 else "")),
                 "algorithmic_bytes": K * d * eb + nb * d * eb + K * 4.0, "kernel_ms": avg_s * 1e3,
                 "launches": launches}
 
