@@ -254,6 +254,29 @@ def main():
     cache.profile_enable(False)
     hit_rate = float(hit.float().mean().item())
     avg_s = kern_ms / 1e3 / max(launches, 1)
+    graph_ms = None
+    if streaming and not two_calls and not args.no_merge:
+        # the same steps once more, 64 of them captured in a HIP graph and replayed (the calls neither allocate nor
+        # synchronise, and the one-kernel end of a step keeps nothing on the host between launches)
+        side = torch.cuda.Stream()
+        cache.set_stream(side)
+        with torch.cuda.stream(side):
+            step(0)
+        side.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            for i in range(64):
+                step(i)
+        for _ in range(4):
+            graph.replay()
+        torch.cuda.synchronize()
+        reps = max(1, steps // 64)
+        t1 = time.perf_counter()
+        for _ in range(reps):
+            graph.replay()
+        torch.cuda.synchronize()
+        graph_ms = (time.perf_counter() - t1) / (reps * 64) * 1e3
+        cache.set_stream(torch.cuda.current_stream())
     flop = 2.0 * nb * K * d
     eb = 1.0 if fp8 else 2.0  # bytes per stored element
     peak_tflops = PEAK_FP8_TFLOPS if fp8 else PEAK_BF16_TFLOPS
@@ -262,7 +285,12 @@ def main():
         roof = {"bound": "hbm", "achieved": bytes_alg / avg_s / 1e9, "peak": PEAK_HBM_GBS, "unit": "GB/s",
                 "frac": bytes_alg / avg_s / 1e9 / PEAK_HBM_GBS, "traffic": measured_traffic(name + ("_fp8" if fp8 else "")),
                 "algorithmic_bytes": bytes_alg, "kernel_ms": avg_s * 1e3,
-                "launches": launches}
+                "launches": launches,
+                # the same bytes over the whole step (every kernel, launch and gap of it): the streaming target
+                "step_frac": bytes_alg / (dt / steps) / 1e9 / PEAK_HBM_GBS}
+        if graph_ms:
+            roof["graph_replay_ms_per_step"] = graph_ms
+            roof["graph_replay_step_frac"] = bytes_alg / (graph_ms / 1e3) / 1e9 / PEAK_HBM_GBS
     else:
         roof = {"bound": "mfma", "achieved": flop / avg_s / 1e12, "peak": peak_tflops, "unit": "TFLOP/s",
                 "frac": flop / avg_s / 1e12 / peak_tflops, "traffic": measured_traffic(name + ("_fp8" if fp8 else "")),
