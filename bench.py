@@ -230,10 +230,20 @@ def main():
     hit = torch.empty(nb, dtype=torch.uint8, device="cuda:0")
 
     two_calls = fp8 or args.two_calls
+    master = None
+    if fp8 and streaming:
+        # the online loop with an 8-bit serving copy: the bf16 cache keeps the running means, the copy follows it
+        master = siso.SisoCache(d, K, siso.BF16)
+        master.load(to_dev(wl.centroids, "bf16"))
+        master.reserve(nb)
 
     def step(i):
         q = queries[(i % n_batches) * nb:(i % n_batches + 1) * nb]
-        if two_calls:
+        if master is not None:
+            cache.lookup(q, thetas[i % len(thetas)], idx, sim, hit)
+            master.update(q, idx, hit)
+            cache.follow(master, idx, hit)
+        elif two_calls:
             cache.lookup(q, thetas[i % len(thetas)], idx, sim, hit)
             if not fp8:
                 cache.update(q, idx, hit)
@@ -380,7 +390,8 @@ def main():
                 "warmup": warmup, "ms_per_step": dt / steps * 1e3,
                 "config": {"workload": name, "centroids": K, "dim": d, "batch": nb, "thresholds": thetas,
                            "storage": args.storage,
-                           "step": "siso_lookup" if fp8 else "siso_lookup + siso_update_hits" if two_calls else "siso_lookup_update", "hit_rate_last_batch": hit_rate,
+                           "step": ("siso_lookup (8-bit copy) + siso_update_hits (bf16 master) + siso_fp8_follow" if master is not None else
+                                    "siso_lookup" if fp8 else "siso_lookup + siso_update_hits" if two_calls else "siso_lookup_update"), "hit_rate_last_batch": hit_rate,
                            "offline_merge": merge_info, "t2h": t2h_info, "refresh": refresh_info,
                            "variants": variants_info,
                            "generate_s": round(gen_s, 1)},

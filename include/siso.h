@@ -79,7 +79,8 @@ enum {
  * bytes + 20 per centroid).  dim must be a multiple of 128, at least 256.  Available:
  * siso_load, siso_lookup, siso_lookup_multi, siso_lookup_topk, siso_lookup_static,
  * siso_t2h, siso_reserve, siso_count, siso_export (codes; means must be NULL),
- * siso_export_scales, siso_export_meta; the other calls return SISO_EINVAL.
+ * siso_export_scales, siso_export_meta, siso_fp8_follow; the other calls return
+ * SISO_EINVAL.
  */
 int siso_create(int dim, long capacity, siso_cache **out);
 int siso_create_ex(int dim, long capacity, int dtype, siso_cache **out);
@@ -276,6 +277,21 @@ int siso_export(siso_cache *c, void *centroids, float *means, int *counts);
 /* SISO_FP8 caches: the scale of every live row ([count] floats, device pointer; NaN for
  * a row that held a NaN or an infinity).  Asynchronous. */
 int siso_export_scales(siso_cache *c, float *scales);
+
+/*
+ * An 8-bit cache as the serving copy of a bf16 cache that is updated online (the
+ * running mean of section 3.1 is kept by the bf16 cache, the lookups of section 4.3
+ * run on the copy): after siso_update / siso_update_hits on `master`, the same idx
+ * (and hit, nullable: then every entry counts) bring the copy up to date - each of
+ * those centroids is quantised again from the master's stored row, exactly as siso_load
+ * would quantise it, and takes the weight of its mean over.  Entries below 0 or beyond
+ * the live rows are skipped.  Both caches must hold the same number of centroids of the
+ * same dimension (after a merge or a refresh of the master, load the copy again).
+ *   idx, hit: device pointers, n entries.
+ * Asynchronous on the copy's stream; the caller orders it behind the master's update
+ * (same stream, or an event).
+ */
+int siso_fp8_follow(siso_cache *copy, const siso_cache *master, const int *idx, const unsigned char *hit, long n);
 
 /*
  * Cache replacement: Algorithm 1 (SISO-CacheManager), section 4.2.

@@ -42,12 +42,21 @@ __device__ __forceinline__ float block_sum256f(float v, float *sh) {
 // One 256-thread block per row: codes [row][d], scale [row] (may be NULL), inv [row] = 1 / |code row| (0 for
 // a row without length, NaN for a non-finite one).  With `load`, the row is a centroid being loaded: its unit
 // direction goes to nothing (the 8-bit cache keeps no running mean), its bookkeeping is set as siso_load does.
+// With `rows` (siso_fp8_follow), block b handles row rows[b] of both sides, if `pick` is NULL or pick[b] != 0 and
+// the row lies below `limit`; `counts` are then the sizes of all rows, not of the blocks, and only the size is kept.
 __global__ __launch_bounds__(256) void k_fp8_quantize(const bf16_t *__restrict__ src, int d, unsigned char *codes, float *scale,
                                                        float *inv, const int *__restrict__ counts, int *size,
-                                                       float *locality, unsigned *access) {
+                                                       float *locality, unsigned *access,
+                                                       const int *__restrict__ rows, const unsigned char *__restrict__ pick,
+                                                       long limit) {
     __shared__ float sh[4];
     constexpr int E = SISO_MAX_DIM / 256;
-    const long r = blockIdx.x;
+    long r = blockIdx.x;
+    if (rows) {
+        if (pick && !pick[blockIdx.x]) return;
+        r = rows[blockIdx.x];
+        if (r < 0 || r >= limit) return;
+    }
     const int t = threadIdx.x;
     float x[E];
     float amax = 0.f;
@@ -81,8 +90,10 @@ __global__ __launch_bounds__(256) void k_fp8_quantize(const bf16_t *__restrict__
         if (size) {
             const int s = counts ? counts[r] : 1;
             size[r] = s < 1 ? 1 : s;
-            locality[r] = (float)(s < 1 ? 1 : s);
-            access[r] = 0;
+            if (!rows) {
+                locality[r] = (float)(s < 1 ? 1 : s);
+                access[r] = 0;
+            }
         }
     }
 }
@@ -92,7 +103,8 @@ __global__ __launch_bounds__(256) void k_fp8_quantize(const bf16_t *__restrict__
 int siso_fp8_load(siso_cache *c, const void *centroids, const int *counts, long k) {
     if (k > 0) {
         hipLaunchKernelGGL(k_fp8_quantize, dim3((unsigned)k), dim3(256), 0, c->stream, (const bf16_t *)centroids, c->dim,
-                           (unsigned char *)c->cent, c->scale, c->invn, counts, c->size, c->locality, c->access);
+                           (unsigned char *)c->cent, c->scale, c->invn, counts, c->size, c->locality, c->access,
+                           (const int *)nullptr, (const unsigned char *)nullptr, 0L);
         return siso_check_hip(c, hipGetLastError(), "k_fp8_quantize (load)");
     }
     return SISO_OK;
@@ -127,7 +139,7 @@ int siso_fp8_ensure_batch(siso_cache *c, long n) {
 int siso_fp8_quantize_batch(siso_cache *c, const void *queries, long n) {
     hipLaunchKernelGGL(k_fp8_quantize, dim3((unsigned)n), dim3(256), 0, c->stream, (const bf16_t *)queries, c->dim,
                        (unsigned char *)c->fp8_q, (float *)nullptr, c->fp8_qinv, (const int *)nullptr, (int *)nullptr,
-                       (float *)nullptr, (unsigned *)nullptr);
+                       (float *)nullptr, (unsigned *)nullptr, (const int *)nullptr, (const unsigned char *)nullptr, 0L);
     return siso_check_hip(c, hipGetLastError(), "k_fp8_quantize (batch)");
 }
 
@@ -137,4 +149,23 @@ extern "C" int siso_export_scales(siso_cache *c, float *scales) {
     if (c->count == 0 || !scales) return SISO_OK;
     return siso_check_hip(c, hipMemcpyAsync(scales, c->scale, (size_t)c->count * sizeof(float), hipMemcpyDeviceToDevice, c->stream),
                           "siso_export_scales");
+}
+
+// An 8-bit cache as the serving copy of a bf16 cache that is updated online: the rows idx[i] (where hit is NULL
+// or hit[i] != 0) are quantised again from the master's stored centroids, as siso_load would quantise them, and
+// take the master's weights over.  Enqueued on the copy's stream.
+extern "C" int siso_fp8_follow(siso_cache *copy, const siso_cache *master, const int *idx, const unsigned char *hit, long n) {
+    if (!copy) return SISO_EINVAL;
+    if (!master || n < 0 || (n > 0 && !idx)) return siso_fail(copy, SISO_EINVAL, "siso_fp8_follow: bad arguments");
+    if (copy->dtype != SISO_FP8 || master->dtype != SISO_BF16 || copy->dim != master->dim)
+        return siso_fail(copy, SISO_EINVAL, "siso_fp8_follow: an 8-bit cache follows a bf16 cache of the same dimension");
+    if (copy->count != master->count)
+        return siso_fail(copy, SISO_EINVAL, "siso_fp8_follow: the copy holds %ld centroids, the master %ld (load the copy again)",
+                         copy->count, master->count);
+    if (n == 0) return SISO_OK;
+    if (n > 2147483647L) return siso_fail(copy, SISO_EINVAL, "siso_fp8_follow: batch of %ld is too large", n);
+    hipLaunchKernelGGL(k_fp8_quantize, dim3((unsigned)n), dim3(256), 0, copy->stream, (const bf16_t *)master->cent, copy->dim,
+                       (unsigned char *)copy->cent, copy->scale, copy->invn, (const int *)master->size, copy->size,
+                       copy->locality, copy->access, idx, hit, copy->count);
+    return siso_check_hip(copy, hipGetLastError(), "k_fp8_quantize (follow)");
 }

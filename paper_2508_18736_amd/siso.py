@@ -61,6 +61,7 @@ SYMBOLS = {
     "siso_refresh_plan": ([_lg, _vp, _vp, _lg, _vp, _vp, _vp, _vp, _vp, _lg, _fl, _lg, _vp, _vp, _vp], _lg),
     "siso_export_meta": ([_vp, _vp, _vp], _it),
     "siso_export_scales": ([_vp, _vp], _it),
+    "siso_fp8_follow": ([_vp, _vp, _vp, _vp, _lg], _it),
     "siso_import": ([_vp, _vp, _vp, _vp, _vp, _vp, _lg], _it),
     "siso_t2h": ([_vp, _vp, _lg, _vp, _it, _vp], _it),
     "siso_md1_wait": ([C.c_double, C.c_double, C.c_double], C.c_double),
@@ -415,6 +416,14 @@ class SisoCache:
         ms, cnt = C.c_double(0.0), C.c_long(0)
         self._check(_lib.siso_profile_read(self._h, C.byref(ms), C.byref(cnt)))
         return float(ms.value), int(cnt.value)
+
+    def follow(self, master: "SisoCache", idx: torch.Tensor, hit: Optional[torch.Tensor] = None) -> None:
+        """8-bit serving copy: quantise the centroids ``idx`` (where ``hit``) again from the bf16 ``master``."""
+        n = idx.shape[0]
+        self._vec(idx, torch.int32, n, "idx")
+        if hit is not None:
+            self._vec(hit, torch.uint8, n, "hit")
+        self._check(_lib.siso_fp8_follow(self._h, master._h, _ptr(idx), _ptr(hit) if hit is not None else None, n))
 
     def export_fp8(self) -> Tuple[torch.Tensor, torch.Tensor, torch.Tensor]:
         """8-bit caches: ``(codes uint8 [count, dim], scales float32 [count], sizes int32 [count])``."""

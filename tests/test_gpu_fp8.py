@@ -249,3 +249,56 @@ def test_fp8_lookup_that_allocates_nothing_and_its_replay_from_a_graph(siso, ora
         torch.cuda.synchronize()
         assert all(torch.equal(a, b) for a, b in zip(out, w))
     cache.set_stream(torch.cuda.current_stream())
+
+
+def test_fp8_copy_follows_a_bf16_cache_that_is_updated_online(siso, oracle):
+    """The online loop with an 8-bit serving copy: lookups on the copy, the hits folded into the bf16 master, the
+    touched centroids quantised again into the copy (siso_fp8_follow).  After every batch the copy's codes, scales
+    and weights are those of the oracle's quantisation of the master's stored rows, bit for bit; the lookups
+    agree with the oracle's 8-bit lookup over those rows."""
+    print("case: fp8 copy follows its master", flush=True)
+    wl = W.c4_stream(n_clusters=256, per_cluster=8, batches=12, batch=64, dim=256, seed=514)
+    master = siso.SisoCache(wl.dim, wl.K, siso.BF16)
+    master.load(to_dev(wl.centroids, "bf16"))
+    copy = load_fp8(siso, wl)
+    oc = oracle.OracleCache(wl.dim, wl.K, "bf16")
+    oc.load(wl.centroids)
+    folded = 0
+    for b in range(12):
+        qs = wl.queries[b * 64:(b + 1) * 64].copy()
+        if b == 3:
+            qs[5] = qs[4]                                   # two members of one centroid in a batch
+        q = to_dev(qs, "bf16")
+        out = copy.lookup(q, 0.85)
+        master.update(q, out[0], out[2])
+        copy.follow(master, out[0], out[2])
+        torch.cuda.synchronize()
+        rows = oc.export()[0]
+        codes, scales = oracle.fp8_quantize(rows, "bf16")
+        ora = oracle.fp8_lookup_rows(codes, scales, qs, 0.85)
+        check_lookup(out, ora, 0.85, "fp8", f"batch {b}")
+        gi, gh = out[0].cpu().numpy(), out[2].cpu().numpy()
+        oc.update(qs, np.where(gh == 1, gi, -1).astype(np.int32))      # the oracle folds what the GPU folded
+        folded += int(gh.sum())
+        # master against the oracle (stored bf16 rows may differ by one step next to a rounding boundary: then the
+        # copy is compared with the quantisation of the master's own rows)
+        from gpu_util import to_host
+        mrows = to_host(master.export()[0], "bf16")
+        want_c, want_s = oracle.fp8_quantize(mrows, "bf16")
+        gc, gs, gz = copy.export_fp8()
+        assert np.array_equal(gc.cpu().numpy(), want_c), f"batch {b}: codes"
+        assert np.array_equal(gs.cpu().numpy().view(np.uint32), want_s.view(np.uint32)), f"batch {b}: scales"
+        assert np.array_equal(gz.cpu().numpy(), master.export()[2].cpu().numpy()), f"batch {b}: weights"
+        assert (mrows != oc.export()[0]).mean() < 2e-3
+    assert folded > 300 and int(master.export()[2].sum().item()) == wl.K + folded
+    # entries out of range are passed over; caches that do not match are refused
+    junk = torch.tensor([-1, wl.K, wl.K + 7], dtype=torch.int32, device=DEV)
+    before = [x.clone() for x in copy.export_fp8()]
+    copy.follow(master, junk)
+    torch.cuda.synchronize()
+    assert all(torch.equal(a, b) for a, b in zip(copy.export_fp8(), before))
+    other = siso.SisoCache(wl.dim, wl.K + 1, siso.BF16)
+    other.load(to_dev(wl.centroids[:10], "bf16"))
+    for bad_master in (other, copy):
+        with pytest.raises(siso.SisoError):
+            copy.follow(bad_master, out[0])
