@@ -239,10 +239,12 @@ def main():
 
     def step(i):
         q = queries[(i % n_batches) * nb:(i % n_batches + 1) * nb]
-        if master is not None:
+        if master is not None and args.two_calls:
             cache.lookup(q, thetas[i % len(thetas)], idx, sim, hit)
             master.update(q, idx, hit)
             cache.follow(master, idx, hit)
+        elif master is not None:
+            cache.lookup_update_with(master, q, thetas[i % len(thetas)], idx, sim, hit)
         elif two_calls:
             cache.lookup(q, thetas[i % len(thetas)], idx, sim, hit)
             if not fp8:
@@ -265,11 +267,13 @@ def main():
     hit_rate = float(hit.float().mean().item())
     avg_s = kern_ms / 1e3 / max(launches, 1)
     graph_ms = None
-    if streaming and not two_calls and not args.no_merge:
+    if streaming and not args.two_calls and not args.no_merge:
         # the same steps once more, 64 of them captured in a HIP graph and replayed (the calls neither allocate nor
         # synchronise, and the one-kernel end of a step keeps nothing on the host between launches)
         side = torch.cuda.Stream()
-        cache.set_stream(side)
+        both = [c_ for c_ in (cache, master) if c_ is not None]
+        for c_ in both:
+            c_.set_stream(side)
         with torch.cuda.stream(side):
             step(0)
         side.synchronize()
@@ -286,7 +290,8 @@ def main():
             graph.replay()
         torch.cuda.synchronize()
         graph_ms = (time.perf_counter() - t1) / (reps * 64) * 1e3
-        cache.set_stream(torch.cuda.current_stream())
+        for c_ in both:
+            c_.set_stream(torch.cuda.current_stream())
     flop = 2.0 * nb * K * d
     eb = 1.0 if fp8 else 2.0  # bytes per stored element
     peak_tflops = PEAK_FP8_TFLOPS if fp8 else PEAK_BF16_TFLOPS
@@ -390,7 +395,8 @@ def main():
                 "warmup": warmup, "ms_per_step": dt / steps * 1e3,
                 "config": {"workload": name, "centroids": K, "dim": d, "batch": nb, "thresholds": thetas,
                            "storage": args.storage,
-                           "step": ("siso_lookup (8-bit copy) + siso_update_hits (bf16 master) + siso_fp8_follow" if master is not None else
+                           "step": ("siso_lookup (8-bit copy) + siso_update_hits (bf16 master) + siso_fp8_follow" if master is not None and args.two_calls else
+                                    "siso_fp8_lookup_update (8-bit copy, bf16 master)" if master is not None else
                                     "siso_lookup" if fp8 else "siso_lookup + siso_update_hits" if two_calls else "siso_lookup_update"), "hit_rate_last_batch": hit_rate,
                            "offline_merge": merge_info, "t2h": t2h_info, "refresh": refresh_info,
                            "variants": variants_info,

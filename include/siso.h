@@ -79,8 +79,8 @@ enum {
  * bytes + 20 per centroid).  dim must be a multiple of 128, at least 256.  Available:
  * siso_load, siso_lookup, siso_lookup_multi, siso_lookup_topk, siso_lookup_static,
  * siso_t2h, siso_reserve, siso_count, siso_export (codes; means must be NULL),
- * siso_export_scales, siso_export_meta, siso_fp8_follow; the other calls return
- * SISO_EINVAL.
+ * siso_export_scales, siso_export_meta, siso_fp8_follow, siso_fp8_lookup_update; the
+ * other calls return SISO_EINVAL.
  */
 int siso_create(int dim, long capacity, siso_cache **out);
 int siso_create_ex(int dim, long capacity, int dtype, siso_cache **out);
@@ -292,6 +292,19 @@ int siso_export_scales(siso_cache *c, float *scales);
  * (same stream, or an event).
  */
 int siso_fp8_follow(siso_cache *copy, const siso_cache *master, const int *idx, const unsigned char *hit, long n);
+
+/*
+ * One step of the online loop with an 8-bit serving copy, as one call: siso_lookup on
+ * `copy`, siso_update_hits of its hits on `master`, siso_fp8_follow of the copy; outputs
+ * and the state of both caches are bit for bit those of the three calls.  Arguments as
+ * siso_lookup_update; both caches on the same stream, with the same centroids (as for
+ * siso_fp8_follow).  Batches of at most 256 queries end in the one kernel that
+ * siso_lookup_update describes, which also quantises the rewritten centroids into the
+ * copy; others run the three calls.  A hit given up on is counted by siso_bad_indices
+ * of the copy.  Asynchronous.
+ */
+int siso_fp8_lookup_update(siso_cache *copy, siso_cache *master, const void *queries, long n, float threshold, int *out_idx,
+                           float *out_sim, unsigned char *out_hit);
 
 /*
  * Cache replacement: Algorithm 1 (SISO-CacheManager), section 4.2.

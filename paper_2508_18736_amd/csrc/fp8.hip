@@ -13,32 +13,6 @@
 
 namespace {
 
-__device__ __forceinline__ unsigned f32_to_e4m3(float y) {
-    const unsigned sign = (__float_as_uint(y) >> 24) & 0x80u;
-    const float a = fabsf(y);
-    if (a >= 448.f) return sign | 0x7Eu;
-    if (a < 0.015625f) return sign | (unsigned)(int)rintf(a * 512.f);  // multiples of 2^-9; 8 of them is 2^-6 = code 0x08
-    unsigned v = __float_as_uint(a);
-    v += 0x7FFFFu + ((v >> 20) & 1u);  // to three mantissa bits, ties to even (may carry into the exponent)
-    return sign | ((((v >> 23) - 120u) << 3) | ((v >> 20) & 7u));
-}
-
-__device__ __forceinline__ float block_max256(float v, float *sh) {
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) v = fmaxf(v, __shfl_xor(v, off));
-    __syncthreads();
-    if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = v;
-    __syncthreads();
-    return fmaxf(fmaxf(sh[0], sh[1]), fmaxf(sh[2], sh[3]));
-}
-__device__ __forceinline__ float block_sum256f(float v, float *sh) {
-    v = wave_sum(v);
-    __syncthreads();
-    if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = v;
-    __syncthreads();
-    return (sh[0] + sh[1]) + (sh[2] + sh[3]);
-}
-
 // One 256-thread block per row: codes [row][d], scale [row] (may be NULL), inv [row] = 1 / |code row| (0 for
 // a row without length, NaN for a non-finite one).  With `load`, the row is a centroid being loaded: its unit
 // direction goes to nothing (the 8-bit cache keeps no running mean), its bookkeeping is set as siso_load does.
@@ -59,34 +33,13 @@ __global__ __launch_bounds__(256) void k_fp8_quantize(const bf16_t *__restrict__
     }
     const int t = threadIdx.x;
     float x[E];
-    float amax = 0.f;
-    bool finite = true;
 #pragma unroll
     for (int e = 0; e < E; ++e) {
         const int col = t + e * 256;
         x[e] = col < d ? bf16_to_f32(src[(size_t)r * d + col]) : 0.f;
-        finite = finite && fabsf(x[e]) <= 3.4e38f;  // false for NaN and infinity
-        amax = fmaxf(amax, fabsf(x[e]));
     }
-    const float bad = block_max256(finite ? 0.f : 1.f, sh);
-    amax = block_max256(amax, sh);
-    const float sc = amax / 448.0f;
-    float ss = 0.f;
-#pragma unroll
-    for (int e = 0; e < E; ++e) {
-        const int col = t + e * 256;
-        if (col < d) {
-            const unsigned code = (bad > 0.f || amax == 0.f) ? 0u : f32_to_e4m3(x[e] / sc);
-            codes[(size_t)r * d + col] = (unsigned char)code;
-            const float back = e4m3_to_f32(code);
-            ss += back * back;
-        }
-    }
-    ss = block_sum256f(ss, sh);
+    fp8_store_row<E>(x, d, codes + (size_t)r * d, scale ? scale + r : nullptr, inv + r, sh);
     if (t == 0) {
-        const float nanv = __uint_as_float(0x7FC00000u);
-        if (scale) scale[r] = bad > 0.f ? nanv : sc;
-        inv[r] = bad > 0.f ? nanv : inv_length(ss);
         if (size) {
             const int s = counts ? counts[r] : 1;
             size[r] = s < 1 ? 1 : s;

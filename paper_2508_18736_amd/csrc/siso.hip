@@ -475,11 +475,12 @@ __device__ __forceinline__ bool fold_member(const float (&x)[UPD_MAXE_T], float 
 // The end of an update, by the block that leads centroid k: acc = the sum of its `members` unit-length members
 // (this thread's elements t + 256 e), m_old / size_old = the mean and its weight as they were.  Writes the
 // new mean and weight, the stored row (the mean at unit length, rounded to the storage type; left alone when
-// the mean has no length) and its inverse length.
+// the mean has no length: false then) and its inverse length; `stored` receives this thread's elements of the
+// stored row.
 template <typename T, int UPD_MAXE_T>
-__device__ __forceinline__ void update_write(int k, int d, int size_old, int members, const float (&m_old)[UPD_MAXE_T],
+__device__ __forceinline__ bool update_write(int k, int d, int size_old, int members, const float (&m_old)[UPD_MAXE_T],
                                              const float (&acc)[UPD_MAXE_T], T *cent, float *mean, int *size, float *invn,
-                                             float *sh) {
+                                             float *sh, float (&stored)[UPD_MAXE_T]) {
     const int t = threadIdx.x;
     const float n_old = (float)size_old;
     const float n_new = n_old + (float)members;
@@ -497,22 +498,25 @@ __device__ __forceinline__ void update_write(int k, int d, int size_old, int mem
     }
     const float n2 = block_sum256(ss, sh);
     if (t == 0) size[k] = size_old + members;
-    if (!(n2 > 0.f) || n2 > 3.0e38f) return;
+    if (!(n2 > 0.f) || n2 > 3.0e38f) return false;
     const float nrm = sqrtf(n2);
     float cs = 0.f;
 #pragma unroll
     for (int e = 0; e < UPD_MAXE_T; ++e) {
         const int col = t + e * 256;
+        stored[e] = 0.f;
         if (col < d) {
             T r;
             narrow(__fdiv_rn(m[e], nrm), &r);
             cent[(size_t)k * d + col] = r;
             const float back = widen(r);
+            stored[e] = back;
             cs = __fmaf_rn(back, back, cs);
         }
     }
     const float c2 = block_sum256(cs, sh);
     if (t == 0) invn[k] = inv_length(c2);
+    return true;
 }
 
 // UPD_MAXE_T = elements of a row per thread (4 for dim <= 1024, else 16).  owner / marked = the notes
@@ -619,7 +623,8 @@ __global__ __launch_bounds__(256) void k_update(const T *__restrict__ Q, const i
         }
     }
     if (members == 0) return;
-    update_write<T, UPD_MAXE_T>(k, d, size_old, members, m_old, acc, cent, mean, size, invn, sh);
+    float stored[UPD_MAXE_T];
+    update_write<T, UPD_MAXE_T>(k, d, size_old, members, m_old, acc, cent, mean, size, invn, sh, stored);
 }
 
 // ============================================================================
@@ -637,6 +642,9 @@ __global__ __launch_bounds__(256) void k_update(const T *__restrict__ Q, const i
 // same: a block that gives up leaves its centroid as it was and counts its query as not applied.
 // Saves a launch and the gap before it, and the loads of the update (own row, mean of the centroid) are on
 // their way while the block waits for the board.
+// With an 8-bit serving copy (siso_fp8_lookup_update) the keys and 1/|q| are the copy's, the centroid arrays the
+// bf16 master's, and the block that rewrites a centroid quantises the new stored row into the copy as well
+// (fp8_store_row: what k_fp8_quantize would store).
 // ============================================================================
 __device__ __forceinline__ u64 board_entry(bool hit, int idx) {
     return (1ull << 63) | ((u64)(hit ? 1 : 0) << 32) | (u64)(unsigned)idx;
@@ -646,7 +654,9 @@ __global__ __launch_bounds__(256) void k_finalize_update(const T *__restrict__ Q
                                                           int d, int slices, float theta, int vec, int *out_idx,
                                                           float *out_sim, unsigned char *out_hit, unsigned *access, T *cent,
                                                           float *mean, int *size, float *invn, u64 *board,
-                                                          int spin_limit, u64 *gave_up) {
+                                                          int spin_limit, u64 *gave_up, const float *__restrict__ q_inv,
+                                                          unsigned char *copy_codes, float *copy_scale, float *copy_inv,
+                                                          int *copy_size) {
     constexpr int EPC = 16 / (int)sizeof(T);
     __shared__ float sh[4];
     __shared__ float sh_f[4];
@@ -664,9 +674,10 @@ __global__ __launch_bounds__(256) void k_finalize_update(const T *__restrict__ Q
         const int col = t + e * 256;
         xr[e] = qrow[col < d ? col : 0];
     }
-    // --- k_lookup_finalize for keys that name rows: 1/|q| and the largest key
+    // --- k_lookup_finalize for keys that name rows: 1/|q| (given, if the batch was quantised) and the largest key
     float ss = 0.f;
-    if (vec) {
+    if (q_inv) {
+    } else if (vec) {
         for (int e = t * EPC; e < d; e += 256 * EPC) {
             const u32x4_t v = *(const u32x4_t *)(qrow + e);
             ss += chunk_dot(v, v, T());
@@ -690,7 +701,7 @@ __global__ __launch_bounds__(256) void k_finalize_update(const T *__restrict__ Q
         sh_k[wave] = key;
     }
     __syncthreads();
-    const float qi = inv_length((sh_f[0] + sh_f[1]) + (sh_f[2] + sh_f[3]));
+    const float qi = q_inv ? q_inv[me] : inv_length((sh_f[0] + sh_f[1]) + (sh_f[2] + sh_f[3]));
 #pragma unroll
     for (int w = 0; w < 4; ++w) key = sh_k[w] > key ? sh_k[w] : key;
     long best_i = -1;
@@ -780,7 +791,12 @@ __global__ __launch_bounds__(256) void k_finalize_update(const T *__restrict__ Q
         }
     }
     if (members == 0) return;
-    update_write<T, UPD_MAXE_T>(k, d, size_old, members, m_old, acc, cent, mean, size, invn, sh);
+    float stored[UPD_MAXE_T];
+    const bool rewritten = update_write<T, UPD_MAXE_T>(k, d, size_old, members, m_old, acc, cent, mean, size, invn, sh, stored);
+    if (copy_codes) {  // the 8-bit copy follows
+        if (t == 0) copy_size[k] = size_old + members;
+        if (rewritten) fp8_store_row<UPD_MAXE_T>(stored, d, copy_codes + (size_t)k * d, copy_scale + k, copy_inv + k, sh);
+    }
 }
 
 
@@ -1416,7 +1432,7 @@ int siso_lookup_impl(siso_cache *c, const void *queries, long n, const float *th
     tl.count_at = count_index;
     for (int j = 0; j < SISO_MULTI_MAX; ++j) tl.v[j] = j < m ? thetas[j] : 0.f;
     int row_keys = SISO_KEY_ROWS;  // what the keys of the chosen kernel carry: the winning row, or its group of four rows
-    const bool may_fold = folded && n <= SISO_FOLD_BOARD && c->count > 0 && !fp8 && m == 1 && out_hit;
+    const bool may_fold = folded && n <= SISO_FOLD_BOARD && c->count > 0 && (!fp8 || c->fold_master) && m == 1 && out_hit;
     c->board_to_clear = may_fold ? c->counters + 4 : nullptr;
     if (c->count > 0) {
         if (!static_keys) siso_prof_begin(c);
@@ -1435,14 +1451,18 @@ int siso_lookup_impl(siso_cache *c, const void *queries, long n, const float *th
     const bool board_emptied = may_fold && c->board_to_clear == nullptr;
     c->board_to_clear = nullptr;
     if (board_emptied && row_keys == SISO_KEY_ROWS) {
+        const siso_cache *ms = c->fold_master;  // the bf16 cache behind an 8-bit copy, or NULL
+        siso_cache *tgt = ms ? const_cast<siso_cache *>(ms) : c;
         // the end of the lookup and the update of its hits as one kernel (see k_finalize_update)
         // polls of the board (a microsecond or two each) before a block gives up
         const int spin_limit = c->opt_fold_spin_limit >= 0 ? c->opt_fold_spin_limit : 1 << 18;
 #define SISO_LAUNCH_FOLD(T, E)                                                                                            \
     hipLaunchKernelGGL((k_finalize_update<T, E>), dim3(qblocks), dim3(256), 0, c->stream, (const T *)queries, keys, n, c->count, \
                        c->dim, slices, thetas[0], vec, out_idx, out_sim, out_hit, count_index >= 0 ? c->access : nullptr, \
-                       (T *)c->cent, c->mean, c->size, c->invn, c->counters + 4, spin_limit, c->counters)
-        if (c->dtype == SISO_F32) {
+                       (T *)tgt->cent, tgt->mean, tgt->size, tgt->invn, c->counters + 4, spin_limit, c->counters,         \
+                       ms ? (const float *)c->fp8_qinv : (const float *)nullptr, ms ? (unsigned char *)c->cent : nullptr, \
+                       ms ? c->scale : nullptr, ms ? c->invn : nullptr, ms ? c->size : nullptr)
+        if (tgt->dtype == SISO_F32) {
             if (c->dim <= 1024) SISO_LAUNCH_FOLD(float, 4);
             else SISO_LAUNCH_FOLD(float, 16);
         } else {
@@ -1505,6 +1525,25 @@ extern "C" int siso_update_hits(siso_cache *c, const void *queries, const int *i
         HIP_TRY(c, hipGetLastError());
     }
     return SISO_OK;
+}
+
+extern "C" int siso_fp8_lookup_update(siso_cache *copy, siso_cache *master, const void *queries, long n, float threshold,
+                                      int *out_idx, float *out_sim, unsigned char *out_hit) {
+    if (!copy) return SISO_EINVAL;
+    if (!master || n < 0 || (n > 0 && (!queries || !out_idx || !out_sim || !out_hit)))
+        return siso_fail(copy, SISO_EINVAL, "siso_fp8_lookup_update: bad arguments");
+    if (copy->dtype != SISO_FP8 || master->dtype != SISO_BF16 || copy->dim != master->dim || copy->count != master->count)
+        return siso_fail(copy, SISO_EINVAL, "siso_fp8_lookup_update: an 8-bit cache and a bf16 cache with the same centroids");
+    if (copy->stream != master->stream)
+        return siso_fail(copy, SISO_EINVAL, "siso_fp8_lookup_update: both caches must work on the same stream");
+    if (n == 0) return SISO_OK;
+    int folded = 0;
+    copy->fold_master = master;
+    const int rc = siso_lookup_impl(copy, queries, n, &threshold, 1, 0, out_idx, out_sim, out_hit, nullptr, 0, &folded);
+    copy->fold_master = nullptr;
+    if (rc != SISO_OK || folded) return rc;
+    const int rc2 = siso_update_hits(master, queries, out_idx, out_hit, n);
+    return rc2 != SISO_OK ? rc2 : siso_fp8_follow(copy, master, out_idx, out_hit, n);
 }
 
 extern "C" int siso_update(siso_cache *c, const void *queries, const int *idx, long n) {

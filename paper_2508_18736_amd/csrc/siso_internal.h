@@ -86,6 +86,7 @@ struct siso_cache {
     int *topk_cand;
     long topk_cap;
     int plan_min_slices;  // > 0 while a top-k lookup plans its passes: at least this many slices (if the tiles allow)
+    const siso_cache *fold_master;  // not NULL while siso_fp8_lookup_update runs its lookup on this 8-bit copy
     u64 *board_to_clear;  // not NULL while siso_lookup_update launches its first phase: a kernel that empties these
                           // slots sets it back to NULL
 
@@ -204,6 +205,66 @@ __device__ __forceinline__ float chunk_dot(u32x4_t x, u32x4_t y, fp8_t) {  // si
         for (int b = 0; b < 32; b += 8) s += e4m3_to_f32((x[i] >> b) & 0xFFu) * e4m3_to_f32((y[i] >> b) & 0xFFu);
     }
     return s;
+}
+
+// ---- the quantiser of the 8-bit storage (k_fp8_quantize, and the end of siso_fp8_lookup_update)
+__device__ __forceinline__ unsigned f32_to_e4m3(float y) {
+    const unsigned sign = (__float_as_uint(y) >> 24) & 0x80u;
+    const float a = fabsf(y);
+    if (a >= 448.f) return sign | 0x7Eu;
+    if (a < 0.015625f) return sign | (unsigned)(int)rintf(a * 512.f);  // multiples of 2^-9; 8 of them is 2^-6 = code 0x08
+    unsigned v = __float_as_uint(a);
+    v += 0x7FFFFu + ((v >> 20) & 1u);  // to three mantissa bits, ties to even (may carry into the exponent)
+    return sign | ((((v >> 23) - 120u) << 3) | ((v >> 20) & 7u));
+}
+__device__ __forceinline__ float block_max256(float v, float *sh) {
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v = fmaxf(v, __shfl_xor(v, off));
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = v;
+    __syncthreads();
+    return fmaxf(fmaxf(sh[0], sh[1]), fmaxf(sh[2], sh[3]));
+}
+__device__ __forceinline__ float block_sum256f(float v, float *sh) {
+    v = wave_sum(v);
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = v;
+    __syncthreads();
+    return (sh[0] + sh[1]) + (sh[2] + sh[3]);
+}
+// One row by a 256-thread block: x = this thread's elements (columns t + 256 e; 0 beyond d).  Writes the codes,
+// the scale (if asked for) and 1 / |code row| (0 for a row without length, NaN for a non-finite one).
+template <int E>
+__device__ __forceinline__ void fp8_store_row(const float (&x)[E], int d, unsigned char *codes_row, float *scale_out,
+                                              float *inv_out, float *sh) {
+    const int t = threadIdx.x;
+    float amax = 0.f;
+    bool finite = true;
+#pragma unroll
+    for (int e = 0; e < E; ++e) {
+        finite = finite && fabsf(x[e]) <= 3.4e38f;  // false for NaN and infinity
+        amax = fmaxf(amax, fabsf(x[e]));
+    }
+    const float bad = block_max256(finite ? 0.f : 1.f, sh);
+    amax = block_max256(amax, sh);
+    const float sc = amax / 448.0f;
+    float ss = 0.f;
+#pragma unroll
+    for (int e = 0; e < E; ++e) {
+        const int col = t + e * 256;
+        if (col < d) {
+            const unsigned code = (bad > 0.f || amax == 0.f) ? 0u : f32_to_e4m3(__fdiv_rn(x[e], sc));
+            codes_row[col] = (unsigned char)code;
+            const float back = e4m3_to_f32(code);
+            ss = __fmaf_rn(back, back, ss);
+        }
+    }
+    ss = block_sum256f(ss, sh);
+    if (t == 0) {
+        const float nanv = __uint_as_float(0x7FC00000u);
+        if (scale_out) *scale_out = bad > 0.f ? nanv : sc;
+        *inv_out = bad > 0.f ? nanv : inv_length(ss);
+    }
 }
 
 // Wave-ballot compaction of (i, j) pairs into out[cap][2]; every lane of the wave

@@ -62,6 +62,7 @@ SYMBOLS = {
     "siso_export_meta": ([_vp, _vp, _vp], _it),
     "siso_export_scales": ([_vp, _vp], _it),
     "siso_fp8_follow": ([_vp, _vp, _vp, _vp, _lg], _it),
+    "siso_fp8_lookup_update": ([_vp, _vp, _vp, _lg, _fl, _vp, _vp, _vp], _it),
     "siso_import": ([_vp, _vp, _vp, _vp, _vp, _vp, _lg], _it),
     "siso_t2h": ([_vp, _vp, _lg, _vp, _it, _vp], _it),
     "siso_md1_wait": ([C.c_double, C.c_double, C.c_double], C.c_double),
@@ -424,6 +425,25 @@ class SisoCache:
         if hit is not None:
             self._vec(hit, torch.uint8, n, "hit")
         self._check(_lib.siso_fp8_follow(self._h, master._h, _ptr(idx), _ptr(hit) if hit is not None else None, n))
+
+    def lookup_update_with(self, master: "SisoCache", queries: torch.Tensor, threshold: float,
+                           out_idx: Optional[torch.Tensor] = None, out_sim: Optional[torch.Tensor] = None,
+                           out_hit: Optional[torch.Tensor] = None) -> Tuple[torch.Tensor, torch.Tensor, torch.Tensor]:
+        """8-bit serving copy: ``lookup`` here, ``update`` of the hits on the bf16 ``master``, ``follow``: one call."""
+        q = master._rows(queries, "queries")
+        n = q.shape[0]
+        if out_idx is None:
+            out_idx = torch.empty(n, dtype=torch.int32, device=self.device)
+        if out_sim is None:
+            out_sim = torch.empty(n, dtype=torch.float32, device=self.device)
+        if out_hit is None:
+            out_hit = torch.empty(n, dtype=torch.uint8, device=self.device)
+        self._vec(out_idx, torch.int32, n, "out_idx")
+        self._vec(out_sim, torch.float32, n, "out_sim")
+        self._vec(out_hit, torch.uint8, n, "out_hit")
+        self._check(_lib.siso_fp8_lookup_update(self._h, master._h, _ptr(q), n, float(threshold), _ptr(out_idx), _ptr(out_sim),
+                                                _ptr(out_hit)))
+        return out_idx, out_sim, out_hit
 
     def export_fp8(self) -> Tuple[torch.Tensor, torch.Tensor, torch.Tensor]:
         """8-bit caches: ``(codes uint8 [count, dim], scales float32 [count], sizes int32 [count])``."""

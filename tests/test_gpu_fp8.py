@@ -302,3 +302,40 @@ def test_fp8_copy_follows_a_bf16_cache_that_is_updated_online(siso, oracle):
     for bad_master in (other, copy):
         with pytest.raises(siso.SisoError):
             copy.follow(bad_master, out[0])
+
+
+@pytest.mark.parametrize("dim,K,n", [(256, 2048, 64), (768, 5000, 100), (512, 3000, 200), (1024, 1500, 256), (2048, 900, 33),
+                                     (256, 2048, 300)])
+def test_fp8_lookup_update_is_the_three_calls(siso, oracle, dim, K, n):
+    """siso_fp8_lookup_update against siso_lookup (copy) + siso_update_hits (master) + siso_fp8_follow on a twin pair
+    of caches: outputs and both states bit for bit, over several batches; the 8-bit lookups against the oracle."""
+    print(f"case: fp8 lookup_update dim={dim} K={K} n={n}", flush=True)
+    wl = W.c2_mid(n_clusters=32, per_cluster=(K + 31) // 32, n_queries=n * 4, dim=dim, seed=515)
+    wl.centroids = wl.centroids[:K].copy()
+    pairs = []
+    for _ in range(2):
+        m = siso.SisoCache(dim, K, siso.BF16)
+        m.load(to_dev(wl.centroids, "bf16"))
+        pairs.append((load_fp8(siso, wl), m))
+    (ca, ma), (cb, mb) = pairs
+    for step in range(4):
+        qs = wl.queries[step * n:(step + 1) * n].copy()
+        if step == 1 and n >= 4:
+            qs[2] = qs[0]
+        q = to_dev(qs, "bf16")
+        codes, scales, _ = cb.export_fp8()
+        out = ca.lookup_update_with(ma, q, 0.85)
+        ref = cb.lookup(q, 0.85)
+        mb.update(q, ref[0], ref[2])
+        cb.follow(mb, ref[0], ref[2])
+        torch.cuda.synchronize()
+        assert torch.equal(out[0], ref[0]) and torch.equal(out[2], ref[2]), f"step {step}"
+        assert torch.equal(out[1].view(torch.int32), ref[1].view(torch.int32)), f"step {step}: sim"
+        for x, y in zip(ca.export_fp8() + ma.export() + ca.export_meta(), cb.export_fp8() + mb.export() + cb.export_meta()):
+            assert torch.equal(x.view(torch.uint8) if x.dtype.is_floating_point else x,
+                               y.view(torch.uint8) if y.dtype.is_floating_point else y), f"step {step}: state"
+        ora = oracle.fp8_lookup_rows(codes.cpu().numpy(), scales.cpu().numpy(), qs, 0.85)
+        check_lookup(out, ora, 0.85, "fp8", f"fp8 lookup_update step {step}")
+    assert int(ma.export()[2].sum().item()) > K and ca.bad_indices() == 0
+    with pytest.raises(siso.SisoError):
+        ma.lookup_update_with(ca, q, 0.85)              # the wrong way round
