@@ -79,8 +79,8 @@ enum {
  * bytes + 20 per centroid).  dim must be a multiple of 128, at least 256.  Available:
  * siso_load, siso_lookup, siso_lookup_multi, siso_lookup_topk, siso_lookup_static,
  * siso_t2h, siso_reserve, siso_count, siso_export (codes; means must be NULL),
- * siso_export_scales, siso_export_meta, siso_fp8_follow, siso_fp8_lookup_update; the
- * other calls return SISO_EINVAL.
+ * siso_export_scales, siso_export_meta, siso_fp8_follow, siso_fp8_lookup_update,
+ * siso_fp8_hand_counts, siso_fp8_resync; the other calls return SISO_EINVAL.
  */
 int siso_create(int dim, long capacity, siso_cache **out);
 int siso_create_ex(int dim, long capacity, int dtype, siso_cache **out);
@@ -286,7 +286,7 @@ int siso_export_scales(siso_cache *c, float *scales);
  * those centroids is quantised again from the master's stored row, exactly as siso_load
  * would quantise it, and takes the weight of its mean over.  Entries below 0 or beyond
  * the live rows are skipped.  Both caches must hold the same number of centroids of the
- * same dimension (after a merge or a refresh of the master, load the copy again).
+ * same dimension (after a merge or a refresh of the master: siso_fp8_resync).
  *   idx, hit: device pointers, n entries.
  * Asynchronous on the copy's stream; the caller orders it behind the master's update
  * (same stream, or an event).
@@ -305,6 +305,24 @@ int siso_fp8_follow(siso_cache *copy, const siso_cache *master, const int *idx, 
  */
 int siso_fp8_lookup_update(siso_cache *copy, siso_cache *master, const void *queries, long n, float threshold, int *out_idx,
                            float *out_sim, unsigned char *out_hit);
+
+/*
+ * The 8-bit copy around a merge or a refresh of its master (Algorithm 1, section 4.2,
+ * filters by the references that the lookups count, and those run on the copy; both calls
+ * renumber the master's rows):
+ *   siso_fp8_hand_counts  adds the references the copy's lookups have counted since the
+ *       last hand-over to the master's access counts (saturating at infinity, which
+ *       stays) and starts the copy's at zero again; same number of centroids on both.
+ *   siso_fp8_resync  makes the copy the 8-bit image of the master as it stands: every live
+ *       row quantised as siso_load would quantise it, weights and cluster sizes taken
+ *       over, reference counts zero, siso_count(copy) = siso_count(master).
+ *       SISO_ECAPACITY if the master holds more rows than the copy has room for.
+ * The usual order: hand_counts, siso_refresh (or siso_merge + siso_merge_apply) on the
+ * master, resync.  Both asynchronous on the copy's stream; the caller orders them against
+ * the master's work (same stream, or an event).
+ */
+int siso_fp8_hand_counts(siso_cache *copy, siso_cache *master);
+int siso_fp8_resync(siso_cache *copy, const siso_cache *master);
 
 /*
  * Cache replacement: Algorithm 1 (SISO-CacheManager), section 4.2.

@@ -51,6 +51,23 @@ __global__ __launch_bounds__(256) void k_fp8_quantize(const bf16_t *__restrict__
     }
 }
 
+// the inverse lengths behind the last live row: NaN, so that no row of a partial tile can win
+__global__ void k_pad_nan(float *p, int count) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < count) p[i] = __uint_as_float(0x7FC00000u);
+}
+
+// to[k] += from[k], saturating at "infinity" (which stays); from[k] = 0
+__global__ void k_hand_counts(unsigned *from, unsigned *to, long k) {
+    const long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= k) return;
+    const unsigned a = from[i], b = to[i];
+    from[i] = 0;
+    if (a == 0 || b == SISO_ACCESS_INF) return;
+    const u64 sum = (u64)a + (u64)b;
+    to[i] = sum >= (u64)SISO_ACCESS_INF ? SISO_ACCESS_INF : (unsigned)sum;
+}
+
 }  // namespace
 
 int siso_fp8_load(siso_cache *c, const void *centroids, const int *counts, long k) {
@@ -121,4 +138,49 @@ extern "C" int siso_fp8_follow(siso_cache *copy, const siso_cache *master, const
                        (unsigned char *)copy->cent, copy->scale, copy->invn, (const int *)master->size, copy->size,
                        copy->locality, copy->access, idx, hit, copy->count);
     return siso_check_hip(copy, hipGetLastError(), "k_fp8_quantize (follow)");
+}
+
+static int fp8_pair_check(siso_cache *copy, const siso_cache *master, const char *who) {
+    if (!master) return siso_fail(copy, SISO_EINVAL, "%s: bad arguments", who);
+    if (copy->dtype != SISO_FP8 || master->dtype != SISO_BF16 || copy->dim != master->dim)
+        return siso_fail(copy, SISO_EINVAL, "%s: an 8-bit cache follows a bf16 cache of the same dimension", who);
+    return SISO_OK;
+}
+
+// The copy becomes the 8-bit image of the master as it stands (after a merge or a refresh, which renumber the rows):
+// every live row quantised as siso_load would, sizes and cluster sizes taken over, reference counts started at zero.
+extern "C" int siso_fp8_resync(siso_cache *copy, const siso_cache *master) {
+    if (!copy) return SISO_EINVAL;
+    int rc = fp8_pair_check(copy, master, "siso_fp8_resync");
+    if (rc != SISO_OK) return rc;
+    const long k = master->count;
+    if (k > copy->capacity)
+        return siso_fail(copy, SISO_ECAPACITY, "siso_fp8_resync: the master holds %ld centroids, the copy has room for %ld", k, copy->capacity);
+    rc = siso_fp8_load(copy, master->cent, master->size, k);   // sizes, cluster size = size, references = 0
+    if (rc != SISO_OK) return rc;
+    if (k > 0) {
+        rc = siso_check_hip(copy, hipMemcpyAsync(copy->locality, master->locality, (size_t)k * sizeof(float), hipMemcpyDeviceToDevice,
+                                                 copy->stream), "siso_fp8_resync: cluster sizes");
+        if (rc != SISO_OK) return rc;
+    }
+    hipLaunchKernelGGL(k_pad_nan, dim3(1), dim3(SISO_PAD_ROWS), 0, copy->stream, copy->invn + k, SISO_PAD_ROWS);
+    rc = siso_check_hip(copy, hipGetLastError(), "k_pad_nan");
+    if (rc != SISO_OK) return rc;
+    copy->count = k;
+    return SISO_OK;
+}
+
+// The references the copy's lookups have counted go to the master (Algorithm 1 filters by them), saturating at
+// infinity; the copy starts counting at zero again.
+extern "C" int siso_fp8_hand_counts(siso_cache *copy, siso_cache *master) {
+    if (!copy) return SISO_EINVAL;
+    const int rc = fp8_pair_check(copy, master, "siso_fp8_hand_counts");
+    if (rc != SISO_OK) return rc;
+    if (copy->count != master->count)
+        return siso_fail(copy, SISO_EINVAL, "siso_fp8_hand_counts: the copy holds %ld centroids, the master %ld", copy->count,
+                         master->count);
+    const long k = copy->count;
+    if (k == 0) return SISO_OK;
+    hipLaunchKernelGGL(k_hand_counts, dim3((unsigned)((k + 255) / 256)), dim3(256), 0, copy->stream, copy->access, master->access, k);
+    return siso_check_hip(copy, hipGetLastError(), "k_hand_counts");
 }

@@ -63,6 +63,8 @@ SYMBOLS = {
     "siso_export_scales": ([_vp, _vp], _it),
     "siso_fp8_follow": ([_vp, _vp, _vp, _vp, _lg], _it),
     "siso_fp8_lookup_update": ([_vp, _vp, _vp, _lg, _fl, _vp, _vp, _vp], _it),
+    "siso_fp8_hand_counts": ([_vp, _vp], _it),
+    "siso_fp8_resync": ([_vp, _vp], _it),
     "siso_import": ([_vp, _vp, _vp, _vp, _vp, _vp, _lg], _it),
     "siso_t2h": ([_vp, _vp, _lg, _vp, _it, _vp], _it),
     "siso_md1_wait": ([C.c_double, C.c_double, C.c_double], C.c_double),
@@ -425,6 +427,14 @@ class SisoCache:
         if hit is not None:
             self._vec(hit, torch.uint8, n, "hit")
         self._check(_lib.siso_fp8_follow(self._h, master._h, _ptr(idx), _ptr(hit) if hit is not None else None, n))
+
+    def hand_counts(self, master: "SisoCache") -> None:
+        """8-bit serving copy: the references its lookups counted go to the ``master``'s access counts."""
+        self._check(_lib.siso_fp8_hand_counts(self._h, master._h))
+
+    def resync(self, master: "SisoCache") -> None:
+        """8-bit serving copy: become the image of the ``master`` as it stands (after its merge or refresh)."""
+        self._check(_lib.siso_fp8_resync(self._h, master._h))
 
     def lookup_update_with(self, master: "SisoCache", queries: torch.Tensor, threshold: float,
                            out_idx: Optional[torch.Tensor] = None, out_sim: Optional[torch.Tensor] = None,

@@ -339,3 +339,113 @@ def test_fp8_lookup_update_is_the_three_calls(siso, oracle, dim, K, n):
     assert int(ma.export()[2].sum().item()) > K and ca.bad_indices() == 0
     with pytest.raises(siso.SisoError):
         ma.lookup_update_with(ca, q, 0.85)              # the wrong way round
+
+
+def test_fp8_copy_through_a_refresh(siso, oracle):
+    """An 8-bit serving copy around Algorithm 1 on its master: the references its lookups counted are handed to
+    the master (siso_fp8_hand_counts), the master is refreshed, the copy becomes its image again (siso_fp8_resync).
+    The master against the oracle's refresh with the same counts; the copy against the oracle's quantisation of
+    the refreshed rows, bit for bit; its lookups against the oracle's 8-bit lookup."""
+    print("case: fp8 copy through a refresh of its master", flush=True)
+    from gpu_util import to_host
+    dim, n_cur, M = 256, 500, 520
+    wl = W.c5_merge(n_groups=300, copies=4, dim=dim, sigma=0.05, dtype="bf16", seed=956)
+    cur, repo = wl.centroids[:n_cur], wl.centroids[n_cur:]
+    rng = np.random.Generator(np.random.Philox(key=91))
+    counts = rng.integers(1, 50, size=n_cur).astype(np.int32)
+    sizes = rng.integers(1, 30, size=repo.shape[0]).astype(np.float32)
+    cap = wl.K + 16
+    master = siso.SisoCache(dim, cap, siso.BF16)
+    copy = siso.SisoCache(dim, cap, siso.FP8)
+    for c in (master, copy):
+        c.load(to_dev(cur, "bf16"), torch.from_numpy(counts).to(DEV))
+    oc = oracle.OracleCache(dim, cap, "bf16")
+    oc.load(cur, counts)
+    codes, scales = oracle.fp8_quantize(cur, "bf16")
+    expected = np.zeros(n_cur, np.uint32)
+    for b in range(3):
+        # some centroids asked for often, most never
+        rows = rng.integers(0, 60 + 100 * b, size=100)
+        noise = rng.standard_normal((100, dim)).astype(np.float32) * np.float32(0.02 / np.sqrt(dim))
+        qs = W.to_storage(W.storage_to_f32(cur[rows], "bf16") + noise, "bf16")
+        out = copy.lookup(to_dev(qs, "bf16"), 0.9)
+        torch.cuda.synchronize()
+        ora = oracle.fp8_lookup_rows(codes, scales, qs, 0.9)
+        st = check_lookup(out, ora, 0.9, "fp8", f"traffic {b}")
+        assert st["clear"] == 100 and np.array_equal(out[0].cpu().numpy(), ora[0]) and np.array_equal(out[2].cpu().numpy(), ora[2])
+        expected += np.bincount(ora[0][ora[2] != 0], minlength=n_cur).astype(np.uint32)
+    assert expected.sum() > 250 and (expected == 0).sum() > 200
+    assert np.array_equal(copy.export_meta()[1].cpu().numpy().astype(np.uint32), expected)
+    assert int(master.export_meta()[1].sum().item()) == 0
+    copy.hand_counts(master)
+    copy.hand_counts(master)                      # nothing left to hand over
+    torch.cuda.synchronize()
+    assert np.array_equal(master.export_meta()[1].cpu().numpy().astype(np.uint32), expected)
+    assert int(copy.export_meta()[1].sum().item()) == 0
+
+    # the oracle's cache with the same counts, then Algorithm 1 on both
+    o_c, o_m, o_s = oc.export()
+    oc.import_state(o_c, o_m, o_s, oc.export_meta()[0], expected)
+    want = oc.refresh(repo, sizes, 0.9, M)
+    got = master.refresh(to_dev(repo, "bf16"), torch.from_numpy(sizes).to(DEV), 0.9, M)
+    print(f"  oracle (merged, added, evicted, margin) = {want}; gpu = {got}", flush=True)
+    assert want[3] > 0.02 and got == want[:3] and got[2] > 0
+    o_c, o_m, o_s = oc.export()
+    g_c, g_m, g_s = master.export()
+    assert master.count == oc.count and (to_host(g_c, "bf16") == o_c).all() and (g_s.cpu().numpy() == o_s).all()
+    o_loc, o_acc = oc.export_meta()
+    g_loc, g_acc = master.export_meta()
+    assert (g_loc.cpu().numpy() == o_loc).all() and (g_acc.cpu().numpy().astype(np.uint32) == o_acc).all()
+
+    with pytest.raises(siso.SisoError):
+        copy.hand_counts(master)                  # the rows no longer correspond
+    copy.resync(master)
+    torch.cuda.synchronize()
+    assert copy.count == master.count
+    codes, scales = oracle.fp8_quantize(o_c, "bf16")
+    gc, gs, gz = copy.export_fp8()
+    assert np.array_equal(gc.cpu().numpy(), codes) and np.array_equal(gs.cpu().numpy().view(np.uint32), scales.view(np.uint32))
+    assert np.array_equal(gz.cpu().numpy(), o_s)
+    c_loc, c_acc = copy.export_meta()
+    assert (c_loc.cpu().numpy() == o_loc).all() and int(c_acc.sum().item()) == 0
+    K2 = oc.count
+    rows = rng.integers(0, K2, size=333)
+    noise = rng.standard_normal((333, dim)).astype(np.float32) * np.float32(0.02 / np.sqrt(dim))
+    qs = W.to_storage(W.storage_to_f32(o_c[rows], "bf16") + noise, "bf16")
+    out = copy.lookup(to_dev(qs, "bf16"), 0.9)
+    torch.cuda.synchronize()
+    ora = oracle.fp8_lookup_rows(codes, scales, qs, 0.9)
+    st = check_lookup(out, ora, 0.9, "fp8", "after the resync")
+    assert st["clear"] > 300
+    # the references go to the master, saturating at infinity, which stays (a centroid that a refresh has just
+    # taken in holds it until the filtering step; here two rows are given such counts by hand)
+    g_c, g_m, g_s = master.export()
+    g_loc, g_acc = master.export_meta()
+    g_acc = g_acc.clone()
+    g_acc[int(rows[0])] = 0xFFFFFFFF
+    g_acc[int(rows[1])] = 0xFFFFFFFE
+    assert rows[0] != rows[1]
+    master.import_state(g_c, g_m, g_s, g_loc, g_acc)
+    copy.hand_counts(master)
+    torch.cuda.synchronize()
+    acc2 = master.export_meta()[1].cpu().numpy().astype(np.uint64)
+    hits = np.bincount(ora[0][ora[2] != 0], minlength=K2).astype(np.uint64)
+    assert ((ora[1] - ora[3]) > 1e-3).all() and hits[rows[0]] >= 1 and hits[rows[1]] >= 1 and hits.sum() > 300
+    want_acc = hits.copy()
+    want_acc[rows[0]] = 0xFFFFFFFF
+    want_acc[rows[1]] = min(0xFFFFFFFE + int(hits[rows[1]]), 0xFFFFFFFF)
+    assert np.array_equal(acc2, want_acc) and int(copy.export_meta()[1].sum().item()) == 0
+    # the online step goes on from here
+    q = to_dev(qs[:64], "bf16")
+    out = copy.lookup_update_with(master, q, 0.9)
+    torch.cuda.synchronize()
+    want_c, want_s = oracle.fp8_quantize(to_host(master.export()[0], "bf16"), "bf16")
+    gc, gs, gz = copy.export_fp8()
+    assert np.array_equal(gc.cpu().numpy(), want_c) and np.array_equal(gs.cpu().numpy().view(np.uint32), want_s.view(np.uint32))
+    assert np.array_equal(gz.cpu().numpy(), master.export()[2].cpu().numpy()) and int(out[2].sum().item()) > 50
+    # a copy without room for the master's rows is refused
+    small = siso.SisoCache(dim, 100, siso.FP8)
+    with pytest.raises(siso.SisoError):
+        small.resync(master)
+    with pytest.raises(siso.SisoError):
+        master.resync(copy)
