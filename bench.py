@@ -79,6 +79,9 @@ def parse():
                     help="fp8: the 8-bit storage variant of the cache (lookups only: a step is siso_lookup)")
     ap.add_argument("--option", action="append", default=[], help="name=value for siso_set_option")
     ap.add_argument("--path", type=int, default=0, help="siso_set_lookup_path (0 = auto)")
+    ap.add_argument("--operands", default="workload", choices=["workload", "signs", "ones", "zeros"],
+                    help="diagnosis of the power limit: the same shapes, launches and bytes with operand values that switch "
+                         "fewer bits in the matrix cores (+-1.0 with the workload's signs, all 1.0, all 0.0)")
     ap.add_argument("--copy-probe-mib", type=int, default=0,
                     help="also run one plain device copy of this many MiB (a known-size reference for byte counters)")
     return ap.parse_args()
@@ -158,7 +161,16 @@ def main():
     for o in args.option:
         k, v = o.split("=")
         cache.set_option(k, int(v))
-    cents = to_dev(wl.centroids, "bf16")
+    def operands(t):
+        if args.operands == "signs":
+            return torch.where(t > 0, 1.0, -1.0).to(t.dtype)
+        if args.operands == "ones":
+            return torch.ones_like(t)
+        if args.operands == "zeros":
+            return torch.zeros_like(t)
+        return t
+
+    cents = operands(to_dev(wl.centroids, "bf16"))
     cache.load(cents)
     del cents
     if args.copy_probe_mib > 0:
@@ -167,7 +179,7 @@ def main():
         torch.cuda.synchronize()
         del src, dst
     out = {"n_gpus": 1, "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": args.storage,
-           "data": "synthetic"}
+           "data": "synthetic" if args.operands == "workload" else f"synthetic shapes, operand values replaced ({args.operands})"}
     merge_info = None
 
     if name == "c5_merge":
@@ -213,13 +225,15 @@ def main():
         add_measured_peak(siso, out["roofline"])
         if not args.no_cpu_baseline:
             out["cpu_baseline"] = cpu_baseline_pairs(wl, theta, args.cpu_seconds)
+        if args.operands != "workload":
+            out["config"]["operands"] = args.operands
         print(json.dumps(out))
         return
 
     streaming = name == "c4_stream"
     nb = wl.batch if streaming else wl.n
     n_batches = wl.n // nb
-    queries = to_dev(wl.queries, "bf16")
+    queries = operands(to_dev(wl.queries, "bf16"))
     # enough steps for a steady state (the first ones run on a chip that is still ramping its clocks up):
     # the whole stream of 4,096 batches; 200 mid-size batches; 10 large ones
     steps = args.steps or (4096 if streaming else 10 if name == "c3_large" else 200)
@@ -405,6 +419,8 @@ def main():
     add_measured_peak(siso, out["roofline"])
     if not args.no_cpu_baseline and not fp8:
         out["cpu_baseline"] = cpu_baseline(wl, nb, args.cpu_seconds)
+    if args.operands != "workload":
+        out["config"]["operands"] = args.operands
     print(json.dumps(out))
 
 
