@@ -79,6 +79,8 @@ def lib() -> C.CDLL:
         L.oracle_import.restype = it
         L.oracle_refresh.argtypes = [vp, vp, vp, lg, fl, lg, vp, vp]
         L.oracle_refresh.restype = it
+        L.oracle_refresh_gap.argtypes = [vp, vp, vp, lg, fl, lg, vp, vp, vp]
+        L.oracle_refresh_gap.restype = it
         db = C.c_double
         L.oracle_t2h.argtypes = [vp, vp, lg, vp, it, vp]
         L.oracle_t2h.restype = it
@@ -258,18 +260,21 @@ class OracleCache:
             raise RuntimeError(f"oracle_export_meta failed ({rc})")
         return loc, acc
 
-    def refresh(self, repo: np.ndarray, repo_size, theta_c: float, max_centroids: int):
-        """Algorithm 1.  Returns ``(merged, added, evicted, min_margin)``."""
+    def refresh(self, repo: np.ndarray, repo_size, theta_c: float, max_centroids: int, want_gap: bool = False):
+        """Algorithm 1.  Returns ``(merged, added, evicted, min_margin)``; with ``want_gap`` a fifth entry: the
+        smallest lead of the closest centroid over the second-closest among the rows that were merged."""
         rows = _storage(repo, self.dtype, self.dim)
         sizes = np.ascontiguousarray(repo_size, dtype=np.float32)
         assert sizes.shape == (rows.shape[0],)
         stats = np.zeros(3, np.int64)
         margin = C.c_double(0.0)
-        rc = lib().oracle_refresh(self._h, _ptr(rows), _ptr(sizes), rows.shape[0], float(theta_c),
-                                  int(max_centroids), _ptr(stats), C.byref(margin))
+        gap = C.c_double(0.0)
+        rc = lib().oracle_refresh_gap(self._h, _ptr(rows), _ptr(sizes), rows.shape[0], float(theta_c),
+                                      int(max_centroids), _ptr(stats), C.byref(margin), C.byref(gap) if want_gap else None)
         if rc != 0:
             raise RuntimeError(f"oracle_refresh failed ({rc})")
-        return int(stats[0]), int(stats[1]), int(stats[2]), float(margin.value)
+        out = (int(stats[0]), int(stats[1]), int(stats[2]), float(margin.value))
+        return out + (float(gap.value),) if want_gap else out
 
     def cluster(self, vectors: np.ndarray, theta_c: float, min_size: int = 1, representatives: bool = False):
         """Community detection; the cache becomes the repository of the clusters.

@@ -776,8 +776,22 @@ int oracle_export_meta(const oracle_cache *c, float *locality, uint32_t *access)
  * max(1, round(repo_size)).  stats (nullable) = {merged, added, evicted};
  * min_margin (nullable) = the smallest |cosine - theta_c| met in a decision.
  */
+int oracle_refresh_gap(oracle_cache *c, const void *repo, const float *repo_size, long r, float theta_c,
+                       long max_centroids, long *stats, double *min_margin, double *min_gap);
+
 int oracle_refresh(oracle_cache *c, const void *repo, const float *repo_size, long r, float theta_c,
                    long max_centroids, long *stats, double *min_margin) {
+    return oracle_refresh_gap(c, repo, repo_size, r, theta_c, max_centroids, stats, min_margin, NULL);
+}
+
+/*
+ * The same, and (min_gap, nullable) how close FindClosestCentroid came to a different answer: the smallest
+ * difference between the closest and the second-closest cosine over the repository rows that were merged
+ * (a row that is not merged joins C_new whichever centroid was closest).  Exactly equal cosines (equal rows:
+ * the lowest index wins on both sides) do not count.  A diagnostic for the parity tests; nothing else changes.
+ */
+int oracle_refresh_gap(oracle_cache *c, const void *repo, const float *repo_size, long r, float theta_c,
+                       long max_centroids, long *stats, double *min_margin, double *min_gap) {
     if (!c || r < 0 || max_centroids < 1 || max_centroids > c->capacity || (r > 0 && (!repo || !repo_size))) return -1;
     const int d = c->dim, dt = c->dtype;
     for (long i = 0; i < r; ++i)
@@ -802,7 +816,7 @@ int oracle_refresh(oracle_cache *c, const void *repo, const float *repo_size, lo
     memcpy(acc, c->access, (size_t)k0 * sizeof(uint32_t));
     for (long j = 0; j < k0; ++j) norm[j] = row_norm(cent, dt, j, d);
     long cnt = k0, merged = 0, added = 0, evicted = 0;
-    double margin = INFINITY;
+    double margin = INFINITY, gap = INFINITY;
 
     /* merge step */
     for (long i = 0; i < r; ++i) {
@@ -829,6 +843,12 @@ int oracle_refresh(oracle_cache *c, const void *repo, const float *repo_size, lo
         }
         if (best >= 0 && fabs(bsim - (double)theta_c) < margin) margin = fabs(bsim - (double)theta_c);
         if (best >= 0 && bsim > (double)theta_c) {
+            if (min_gap)
+                for (long j = 0; j < cnt; ++j) {
+                    if (j == best) continue;
+                    const double sj = cosine(repo, i, ni, cent, j, norm[j], dt, d);
+                    if (sj != bsim && bsim - sj < gap) gap = bsim - sj;
+                }
             loc[best] = loc[best] + repo_size[i];
             ++merged;
         } else {
@@ -872,6 +892,7 @@ int oracle_refresh(oracle_cache *c, const void *repo, const float *repo_size, lo
     c->count = cnt;
     if (stats) { stats[0] = merged; stats[1] = added; stats[2] = evicted; }
     if (min_margin) *min_margin = margin;
+    if (min_gap) *min_gap = gap;
     free(cent); free(mean); free(norm); free(size); free(loc); free(acc);
     return 0;
 }

@@ -82,8 +82,21 @@ def check_topk(gpu, ora, dtype, label):
     clear = fin & (left > GAP) & (right > GAP)
     bad = clear & (gi != oi)
     assert not bad.any(), f"{label}: {bad.sum()} indices differ at ranks with clear gaps, first {np.argwhere(bad)[:4].tolist()}"
-    # runs of exactly equal similarities (equal rows) come in index order on both sides
+    # runs of exactly equal similarities (equal rows) come in index order on both sides - checked where the run's two
+    # outer neighbours are further away than single precision can blur (a third row within 1e-5 of the run may
+    # land before, inside or behind it in fp32)
     tie = fin & ((left == 0) | (right == 0))
+    edge_ok = np.ones_like(tie)
+    for q in range(n):
+        r = 0
+        while r < k:
+            e = r
+            while e + 1 < k and tie[q, e] and right[q, e] == 0:
+                e += 1
+            if e > r and not (left[q, r] > 1e-5 and right[q, e] > 1e-5):
+                edge_ok[q, r:e + 1] = False
+            r = e + 1
+    tie &= edge_ok
     assert np.array_equal(gi[tie], oi[tie]), f"{label}: exact ties"
     # each row names k different centroids, and the set agrees except for members near the k-th similarity
     for q in range(n):

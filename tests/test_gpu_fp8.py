@@ -386,10 +386,10 @@ def test_fp8_copy_through_a_refresh(siso, oracle):
     # the oracle's cache with the same counts, then Algorithm 1 on both
     o_c, o_m, o_s = oc.export()
     oc.import_state(o_c, o_m, o_s, oc.export_meta()[0], expected)
-    want = oc.refresh(repo, sizes, 0.9, M)
+    want = oc.refresh(repo, sizes, 0.9, M, want_gap=True)
     got = master.refresh(to_dev(repo, "bf16"), torch.from_numpy(sizes).to(DEV), 0.9, M)
-    print(f"  oracle (merged, added, evicted, margin) = {want}; gpu = {got}", flush=True)
-    assert want[3] > 0.02 and got == want[:3] and got[2] > 0
+    print(f"  oracle (merged, added, evicted, margin, lead of the closest) = {want}; gpu = {got}", flush=True)
+    assert want[3] > 0.02 and want[4] > 1e-6 and got == want[:3] and got[2] > 0
     o_c, o_m, o_s = oc.export()
     g_c, g_m, g_s = master.export()
     assert master.count == oc.count and (to_host(g_c, "bf16") == o_c).all() and (g_s.cpu().numpy() == o_s).all()

@@ -256,10 +256,11 @@ def test_refresh_mid_size_vs_oracle(siso, oracle):
     ora.load(wl.centroids, counts)
     gpu = siso.SisoCache(dim, K + r, siso.BF16)
     gpu.load(to_dev(wl.centroids, "bf16"), torch.from_numpy(counts).to("cuda:0"))
-    want = ora.refresh(repo, sizes, 0.9, M)
+    want = ora.refresh(repo, sizes, 0.9, M, want_gap=True)
     got = gpu.refresh(to_dev(repo, "bf16"), torch.from_numpy(sizes).to("cuda:0"), 0.9, M)
-    print(f"  oracle (merged, added, evicted, margin) = {want}; gpu = {got}", flush=True)
+    print(f"  oracle (merged, added, evicted, margin, lead of the closest) = {want}; gpu = {got}", flush=True)
     assert want[3] > 10 * SIM_TOL["bf16"]
+    assert want[4] > 1e-6     # every closest centroid leads by more than single precision can blur
     assert got == want[:3] and want[1] > 900 and want[2] > 300
     oc, _, osz = ora.export()
     gc, _, gsz = gpu.export()

@@ -81,6 +81,24 @@ def test_refresh_is_sequential_and_takes_the_closest(oracle):
     assert (loc[0] > loc[1]) == (a >= b)  # ... the closer one in the arithmetic of the stored values, index 0 on a tie
 
 
+def test_refresh_reports_the_lead_of_the_closest_centroid(oracle):
+    # cache at 0 and 30 degrees; rows at 20 degrees (closest 30 at cos 10, second 0 at cos 20) and at 2 degrees
+    # (closest 0 at cos 2, second 30 at cos 28); a row at 100 degrees joins and does not count; margin: cos 10 - 0.9
+    cache = make_cache(oracle, [(0, 1), (30, 1)])
+    merged, added, evicted, margin, lead = cache.refresh(plane([20, 100, 2]), [1, 1, 1], 0.9, 8, want_gap=True)
+    cosd = lambda a: math.cos(math.radians(a))
+    assert (merged, added, evicted) == (2, 1, 0)
+    assert abs(lead - (cosd(10) - cosd(20))) < 1e-7 and cosd(10) - cosd(20) < cosd(2) - cosd(28)
+    assert abs(margin - (cosd(10) - 0.9)) < 1e-6
+    # equal rows tie exactly and do not count: the lead is then the one over the next different cosine
+    cache = make_cache(oracle, [(0, 1), (0, 1), (30, 1)])
+    lead = cache.refresh(plane([5]), [1], 0.9, 8, want_gap=True)[4]
+    assert abs(lead - (cosd(5) - cosd(25))) < 1e-7
+    # without a merged row there is no lead
+    cache = make_cache(oracle, [(0, 1)])
+    assert cache.refresh(plane([90]), [1], 0.9, 8, want_gap=True)[4] == math.inf
+
+
 def test_refresh_threshold_extremes_and_conservation(oracle):
     wl = W.c5_merge(n_groups=40, copies=4, dim=64, seed=5)
     cents = W.storage_to_f32(wl.centroids, "bf16")
