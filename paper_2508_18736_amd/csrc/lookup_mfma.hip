@@ -346,7 +346,8 @@ __device__ __forceinline__ void pipe_reduce_keys(float (&bv)[WQ], unsigned (&bb)
 // listed (second pass of a top-k lookup): tau[q] = the bound of query q in the units of the products
 // (<q, c> / |c|), cand[q * cand_cap + i] = the i-th listed row, cand_cnt[q] = how many rows reached the bound
 // (also beyond cand_cap).  A row is listed exactly once: every product is formed by one lane.
-template <class Cfg, bool COLLECT = false>
+// STREAM: the centroid loads carry the non-temporal hint (see stream_hint below).
+template <class Cfg, bool COLLECT = false, bool STREAM = false>
 __global__ __launch_bounds__(Cfg::NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void k_lookup_pipe(
     const bf16_t *__restrict__ Q, const bf16_t *__restrict__ C, const float *__restrict__ invn, long n, long K, int d,
     int tiles_per_slice, int slices, int nqt, int qb, u64 *__restrict__ keys, const float *__restrict__ tau,
@@ -429,9 +430,8 @@ __global__ __launch_bounds__(Cfg::NT) __attribute__((amdgpu_waves_per_eu(2, 2)))
     int ld_ct = ct_begin, ld_ks = 0, ld_stage = 0;
     // One part = one direct load of this wave; part NL - 1 also moves on to the next slab, but
     // never past the last one (the wide path issues unconditionally and so fetches the last slab
-    // again, into a stage nobody reads any more).  The centroids are read once per block of query
-    // tiles: in a lookup their loads carry the non-temporal hint so that they do not push the
-    // query tiles out of L2.
+    // again, into a stage nobody reads any more).  With STREAM the centroid loads carry the
+    // non-temporal hint (stream_hint decides per launch).
     const char *ld_c = (const char *)C + (size_t)ct_begin * BC * d * ES;  // first element of the slab, centroid side
     const char *ld_q = qbase;                                              // and query side
     unsigned char *ld_sb = smem + wave * 1024;                             // this wave's first KiB of the stage
@@ -448,7 +448,8 @@ __global__ __launch_bounds__(Cfg::NT) __attribute__((amdgpu_waves_per_eu(2, 2)))
         if constexpr (j < NLA) {
             unsigned off = a_off[j];
             asm volatile("" : "+v"(off));
-            gload_lds16_nt(ld_c + off, ld_sb + j * NW * 1024);
+            if constexpr (STREAM) gload_lds16_nt(ld_c + off, ld_sb + j * NW * 1024);
+            else gload_lds16(ld_c + off, ld_sb + j * NW * 1024);
         } else {
             unsigned off = b_off[j - NLA];
             asm volatile("" : "+v"(off));
@@ -1056,7 +1057,7 @@ __global__ __launch_bounds__(WideCfg::NT) __attribute__((amdgpu_waves_per_eu(1, 
             unsigned off = a_voff;
             asm volatile("" : "+v"(off));  // keeps the 32-bit offset next to its use: scalar base + lane offset
             const u32x4 *src = (const u32x4 *)(ld_c + (size_t)j * 64 * d + off);
-            G[p][j] = __builtin_nontemporal_load(src);
+            G[p][j] = *src;  // (no streaming mark: the workgroups of an XCD share these lines in L2, see stream_hint)
         } else {
             // (computed here every time: eight more loop-invariant registers would not fit)
             int row = row0;
@@ -1557,37 +1558,63 @@ static bool skinny_plan(const siso_cache *c, long n, PipePlan *p) {
     return pipe_plan(c, n, c->dtype == SISO_FP8 && c->opt_mfma_config != 3 ? 8 : 3, 256, p);
 }
 
-template <class Cfg>
-static int launch_cfg(siso_cache *c, const void *queries, long n, const PipePlan &p, u64 *keys) {
+// Should the centroid loads of a launch carry the non-temporal hint?  With one tile of queries every centroid
+// line is read by exactly one workgroup, once: marked as streaming, 384 MiB of centroids pass in 63 us instead
+// of 72 (they no longer push each other through the caches).  A set that the 256 MB memory-side cache can hold
+// most of is better left there for the next call (192 MiB: 30.0 us per pass unmarked, 32.7 marked; the two meet
+// at 288 MiB, rows and codes alike); and with several query tiles the workgroups of an XCD share the lines in
+// L2, where the mark makes them leave early (large batches over codes: 6 % slower marked; over bf16 rows, wide
+// kernel: 1.5 %).
+#define SISO_STREAM_BYTES (288l << 20)
+static bool stream_hint(const siso_cache *c, const PipePlan &p) {
+    if (c->opt_stream_hint > 0) return c->opt_stream_hint == 1;
+    const long bytes = c->count * (long)c->dim * (c->dtype == SISO_FP8 ? 1 : 2);
+    return p.nqt == 1 && bytes > SISO_STREAM_BYTES;
+}
+
+template <class Cfg, bool COLLECT, bool STREAM>
+static int pipe_attr(siso_cache *c) {
     static bool attr_done = false;
     if (!attr_done) {
-        hipError_t e = hipFuncSetAttribute((const void *)k_lookup_pipe<Cfg>,
+        hipError_t e = hipFuncSetAttribute((const void *)k_lookup_pipe<Cfg, COLLECT, STREAM>,
                                            hipFuncAttributeMaxDynamicSharedMemorySize, Cfg::LDS_BYTES);
         if (e != hipSuccess) return siso_check_hip(c, e, "hipFuncSetAttribute(k_lookup_pipe)");
         attr_done = true;
     }
-    hipLaunchKernelGGL((k_lookup_pipe<Cfg>), dim3((unsigned)p.grid), dim3(Cfg::NT), Cfg::LDS_BYTES,
+    return SISO_OK;
+}
+
+template <class Cfg, bool STREAM>
+static int launch_cfg2(siso_cache *c, const void *queries, long n, const PipePlan &p, u64 *keys) {
+    const int rc = pipe_attr<Cfg, false, STREAM>(c);
+    if (rc != SISO_OK) return rc;
+    hipLaunchKernelGGL((k_lookup_pipe<Cfg, false, STREAM>), dim3((unsigned)p.grid), dim3(Cfg::NT), Cfg::LDS_BYTES,
                        c->stream, (const bf16_t *)queries, (const bf16_t *)c->cent, c->invn, n, c->count, c->dim,
                        p.tiles_per_slice, p.slices, p.nqt, p.qb, keys, (const float *)nullptr, (int *)nullptr,
                        (int *)nullptr, 0, c->board_to_clear);
     c->board_to_clear = nullptr;  // taken
     return siso_check_hip(c, hipGetLastError(), "k_lookup_pipe");
 }
-
 template <class Cfg>
-static int launch_collect(siso_cache *c, const void *queries, long n, const PipePlan &p, const float *tau, int *cand,
-                          int *cnt, int cap) {
-    static bool attr_done = false;
-    if (!attr_done) {
-        hipError_t e = hipFuncSetAttribute((const void *)k_lookup_pipe<Cfg, true>,
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, Cfg::LDS_BYTES);
-        if (e != hipSuccess) return siso_check_hip(c, e, "hipFuncSetAttribute(k_lookup_pipe, collect)");
-        attr_done = true;
-    }
-    hipLaunchKernelGGL((k_lookup_pipe<Cfg, true>), dim3((unsigned)p.grid), dim3(Cfg::NT), Cfg::LDS_BYTES,
+static int launch_cfg(siso_cache *c, const void *queries, long n, const PipePlan &p, u64 *keys) {
+    return stream_hint(c, p) ? launch_cfg2<Cfg, true>(c, queries, n, p, keys) : launch_cfg2<Cfg, false>(c, queries, n, p, keys);
+}
+
+template <class Cfg, bool STREAM>
+static int launch_collect2(siso_cache *c, const void *queries, long n, const PipePlan &p, const float *tau, int *cand,
+                           int *cnt, int cap) {
+    const int rc = pipe_attr<Cfg, true, STREAM>(c);
+    if (rc != SISO_OK) return rc;
+    hipLaunchKernelGGL((k_lookup_pipe<Cfg, true, STREAM>), dim3((unsigned)p.grid), dim3(Cfg::NT), Cfg::LDS_BYTES,
                        c->stream, (const bf16_t *)queries, (const bf16_t *)c->cent, c->invn, n, c->count, c->dim,
                        p.tiles_per_slice, p.slices, p.nqt, p.qb, (u64 *)nullptr, tau, cand, cnt, cap, (u64 *)nullptr);
     return siso_check_hip(c, hipGetLastError(), "k_lookup_pipe (collect)");
+}
+template <class Cfg>
+static int launch_collect(siso_cache *c, const void *queries, long n, const PipePlan &p, const float *tau, int *cand,
+                          int *cnt, int cap) {
+    return stream_hint(c, p) ? launch_collect2<Cfg, true>(c, queries, n, p, tau, cand, cnt, cap)
+                             : launch_collect2<Cfg, false>(c, queries, n, p, tau, cand, cnt, cap);
 }
 
 static int launch_wide(siso_cache *c, const void *queries, long n, const PipePlan &p, u64 *keys) {

@@ -1240,6 +1240,7 @@ extern "C" int siso_set_option(siso_cache *c, const char *name, long value) {
     else if (!strcmp(name, "merge_config")) c->opt_merge_config = (int)value;
     else if (!strcmp(name, "mfma_qblock")) c->opt_mfma_qblock = (int)value;
     else if (!strcmp(name, "fold_spin_limit")) c->opt_fold_spin_limit = (int)value;
+    else if (!strcmp(name, "stream_hint") && value <= 2) c->opt_stream_hint = (int)value;
     else if (!strcmp(name, "second_set")) return value ? siso_second_set(c) : SISO_OK;
     else return siso_fail(c, SISO_EINVAL, "unknown option %s", name);
     return SISO_OK;

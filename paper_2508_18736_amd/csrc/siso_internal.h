@@ -96,6 +96,7 @@ struct siso_cache {
     int opt_merge_config;
     int opt_mfma_qblock;
     int opt_fold_spin_limit;  // -1 = default
+    int opt_stream_hint;      // 0 = default; 1 = mark the centroid loads of the eight-wave lookups as streaming, 2 = never
 
     // kernel timing (siso_profile_enable / siso_profile_read)
     int profile_on;       // 0 = off, N = bracket every N-th call

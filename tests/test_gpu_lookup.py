@@ -76,6 +76,30 @@ def test_mfma_path_vs_oracle(siso, oracle, cfg, dim, K, n, tps):
     assert all(torch.equal(a, b) for a, b in zip(out, out2))
 
 
+@pytest.mark.parametrize("storage,cfg,n", [("bf16", 3, 50), ("bf16", 2, 128), ("bf16", 1, 300), ("fp8", 8, 64), ("fp8", 7, 100),
+                                            ("fp8", 6, 300), ("fp8", 3, 33)])
+def test_streaming_mark_changes_nothing(siso, oracle, storage, cfg, n):
+    """The centroid loads of the eight-wave kernels with and without the non-temporal mark (two instantiations,
+    chosen per launch by size): the same outputs bit for bit, the lookup and the k closest."""
+    print(f"case: streaming mark {storage} cfg={cfg} n={n}", flush=True)
+    wl = W.c2_mid(n_clusters=64, per_cluster=50, n_queries=n, dim=256, seed=61)
+    outs = []
+    for hint in (0, 1, 2):
+        cache = siso.SisoCache(wl.dim, wl.K, siso.FP8 if storage == "fp8" else siso.BF16)
+        cache.set_option("mfma_config", cfg)
+        cache.set_option("stream_hint", hint)
+        cache.load(to_dev(wl.centroids, "bf16"))
+        q = to_dev(wl.queries, "bf16")
+        outs.append(tuple(cache.lookup(q, 0.85)) + tuple(cache.lookup_topk(q, 5)))
+    torch.cuda.synchronize()
+    for o in outs[1:]:
+        assert all(torch.equal(a, b) for a, b in zip(o, outs[0]))
+    if storage == "bf16":
+        check_lookup(outs[1][:3], oracle.lookup_rows(wl.centroids, wl.queries, 0.85, "bf16"), 0.85, "bf16", "marked")
+    with pytest.raises(siso.SisoError):
+        cache.set_option("stream_hint", 3)
+
+
 @pytest.mark.parametrize("cfg,n", [(2, 100), (3, 40), (1, 300), (4, 300), (5, 300)])
 @pytest.mark.parametrize("tps", [3, 7])
 def test_two_slab_tiles_with_scaled_rows(siso, oracle, cfg, n, tps):
