@@ -261,7 +261,7 @@ __device__ __forceinline__ bool pipe_map_block(long K, int tiles_per_slice, int 
         g = xcd % gp;
         b = xcd / gp + (8 / gp) * u;
     }
-    if (g >= groups || b >= nqb) return false;
+    if (g >= groups || b >= nqb || i >= qb * sb) return false;  // (qb need not divide 32: the last places stay empty)
     qt = b * qb + i % qb;
     s = g * sb + i / qb;
     if (qt >= nqt || s >= slices) return false;
@@ -1529,9 +1529,47 @@ static bool pipe_plan(const siso_cache *c, long n, int cfg, long want_wgs, PipeP
     int qb = c->opt_mfma_qblock > 0 ? c->opt_mfma_qblock : 8;
     if (qb != 1 && qb != 2 && qb != 4 && qb != 8 && qb != 16 && qb != 32) return false;
     if (c->opt_mfma_qblock <= 0) {
-        while (qb > 1 && qb > nqt) qb >>= 1;
+        // (any number from 1 to 32 will do for the kernels: a unit then uses qb * (32 / qb) of its 32 places)
+        if (qb > nqt) qb = (int)nqt;
         if (c->opt_tiles_per_slice <= 0 && (ct + tps - 1) / tps < 32 / qb) tps = ct / (32 / qb) > 1 ? ct / (32 / qb) : 1;
         while (qb < 32 && qb * 2 <= nqt && (ct + tps - 1) / tps < 32 / qb) qb <<= 1;
+        // blocks of query tiles of even size: 9 tiles as 5 + 4 rather than 8 + 1 (a block's places without a tile
+        // stay empty: 9 tiles in blocks of 8 took as long as 11 tiles' worth of work)
+        const long nqb = (nqt + qb - 1) / qb;
+        qb = (int)((nqt + nqb - 1) / nqb);
+    }
+    // The groups of slices are dealt out to the XCDs in turn (pipe_map_block), and the 32 compute units of an XCD
+    // take its workgroups (a slice x a query tile each, equally long) in rounds: a slice length that leaves the
+    // last round of groups to a few XCDs, or the last round of workgroups to a few units, makes the rest wait
+    // (3 query tiles over 1,024 centroid tiles: 11 groups of 6-tile slices put twice the work on three XCDs, 482 us;
+    // 8 groups of 8-tile slices, 336 us).  Among the lengths up to the one chosen above, take the one with the
+    // fewest tile periods on the busiest XCD, a round counted as its tiles plus half a tile for getting started.
+    if (c->opt_tiles_per_slice <= 0 && c->plan_min_slices <= 0 && nqt > 1) {
+        const long sb = 32 / qb;
+        const long lo = tps / 4 > 2 ? tps / 4 : (tps < 2 ? tps : 2);
+        auto periods = [&](long t) -> double {  // < 0: the other mapping (every XCD has a share of every group)
+            const long sl = (ct + t - 1) / t, gr = (sl + sb - 1) / sb;
+            if (gr <= 4) return -1.0;
+            long busiest = 0;
+            for (long x = 0; x < 8 && x < gr; ++x) {  // XCD x owns the groups x, x + 8, ...
+                long mine = 0;
+                for (long g = x; g < gr; g += 8) mine += (g + 1) * sb <= sl ? sb : sl - g * sb;
+                if (mine > busiest) busiest = mine;
+            }
+            const long rounds = (busiest * nqt + 31) / 32;
+            return (double)rounds * ((double)t + 0.5);
+        };
+        long best = tps;
+        double least = periods(tps);
+        if (least >= 0)
+            for (long t = tps - 1; t >= lo; --t) {
+                const double w = periods(t);
+                if (w >= 0 && w < least * 0.99) {
+                    least = w;
+                    best = t;
+                }
+            }
+        tps = best;
     }
     const long slices = (ct + tps - 1) / tps;
     if (nqt * slices > 2147483647L || slices > 1000000) return false;

@@ -76,6 +76,29 @@ def test_mfma_path_vs_oracle(siso, oracle, cfg, dim, K, n, tps):
     assert all(torch.equal(a, b) for a, b in zip(out, out2))
 
 
+@pytest.mark.parametrize("n,K,dim", [(700, 5000, 256), (1300, 9000, 128), (1700, 40000, 128), (2305, 3000, 256), (2400, 70000, 128),
+                                     (5000, 2049, 128)])
+def test_numbers_of_query_tiles_that_do_not_fill_the_blocks(siso, oracle, n, K, dim):
+    """3, 6, 7, 10 and 20 tiles of queries: the blocks of query tiles that share an XCD's centroid tiles are of even
+    size then (a number that need not divide the 32 places of a unit), and the slice length is chosen for an even
+    load on the XCDs.  Every query against the oracle, also through the k closest (whose second pass lists each
+    row once)."""
+    print(f"case: ragged query tiles n={n} K={K} dim={dim}", flush=True)
+    wl = W.c2_mid(n_clusters=64, per_cluster=(K + 63) // 64, n_queries=n, dim=dim, seed=47)
+    wl.centroids = wl.centroids[:K].copy()
+    ora = oracle.lookup_rows(wl.centroids, wl.queries, 0.85, "bf16")
+    for cfg in (0, 1):
+        cache, out = run_lookup(siso, wl, 0.85, siso.PATH_MFMA, {"mfma_config": cfg}, capacity=K)
+        st = check_lookup(out, ora, 0.85, "bf16", f"ragged cfg {cfg}")
+        assert st["max_err"] < 1e-4
+    oc = oracle.OracleCache(dim, K, "bf16")
+    oc.load(wl.centroids)
+    from gpu_util import check_topk
+    tk = cache.lookup_topk(to_dev(wl.queries, "bf16"), 6)
+    torch.cuda.synchronize()
+    check_topk(tk, oc.lookup_topk(wl.queries, 6), "bf16", "ragged top 6")
+
+
 @pytest.mark.parametrize("storage,cfg,n", [("bf16", 3, 50), ("bf16", 2, 128), ("bf16", 1, 300), ("fp8", 8, 64), ("fp8", 7, 100),
                                             ("fp8", 6, 300), ("fp8", 3, 33)])
 def test_streaming_mark_changes_nothing(siso, oracle, storage, cfg, n):
