@@ -37,7 +37,8 @@ int siso_set_lookup_path(siso_cache *c, int path);
  *   "fold_spin_limit" -1 = default; >= 0: how often a workgroup of siso_lookup_update's one-kernel end looks at the
  *                     board before it gives up (0: at once - for tests of that path)
  *   "stream_hint"     0 = default (the centroid loads of a lookup are marked non-temporal when the batch is one
- *                     tile of queries and the centroids exceed 288 MiB); 1 = always, 2 = never (eight-wave kernels)
+ *                     tile of queries and the centroids exceed 288 MiB, or, four-wave kernel, when they exceed
+ *                     288 MiB); 1 = always, 2 = never
  *   "second_set"      1 = allocate now the second set of arrays that siso_merge_apply and siso_refresh
  *                     gather the rebuilt cache into (otherwise their first call does); synchronises
  * Unknown names or values out of range give SISO_EINVAL.

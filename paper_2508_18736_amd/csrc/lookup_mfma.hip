@@ -976,6 +976,8 @@ struct WideCfg {
     static_assert(WIDE_FRAG0 + 4 * WC + 8 * WQ == 256, "fragments fill the registers behind the allocator's share");
 };
 
+// STREAM: the centroid loads carry the non-temporal hint (stream_hint_wide decides per launch).
+template <bool STREAM>
 __global__ __launch_bounds__(WideCfg::NT) __attribute__((amdgpu_waves_per_eu(1, 1), amdgpu_num_vgpr(WIDE_FRAG0))) void k_lookup_wide(
     const bf16_t *__restrict__ Q, const bf16_t *__restrict__ C, const float *__restrict__ invn, long n, long K, int d,
     int tiles_per_slice, int slices, int nqt, int qb, u64 *__restrict__ keys) {
@@ -1057,7 +1059,8 @@ __global__ __launch_bounds__(WideCfg::NT) __attribute__((amdgpu_waves_per_eu(1, 
             unsigned off = a_voff;
             asm volatile("" : "+v"(off));  // keeps the 32-bit offset next to its use: scalar base + lane offset
             const u32x4 *src = (const u32x4 *)(ld_c + (size_t)j * 64 * d + off);
-            G[p][j] = *src;  // (no streaming mark: the workgroups of an XCD share these lines in L2, see stream_hint)
+            if constexpr (STREAM) G[p][j] = __builtin_nontemporal_load(src);
+            else G[p][j] = *src;
         } else {
             // (computed here every time: eight more loop-invariant registers would not fit)
             int row = row0;
@@ -1655,18 +1658,31 @@ static int launch_collect(siso_cache *c, const void *queries, long n, const Pipe
                              : launch_collect2<Cfg, false>(c, queries, n, p, tau, cand, cnt, cap);
 }
 
-static int launch_wide(siso_cache *c, const void *queries, long n, const PipePlan &p, u64 *keys) {
+// The wide kernel runs with several query tiles: its workgroups share the centroid lines in L2 either way.  A set
+// that the memory-side cache holds is faster unmarked (96 MiB: 1.2 %, on every machine tried); over 2 GiB the two
+// are within 1.7 % of each other, one ahead on one machine and the other on the next, and the marked loads move
+// less through the fabric (35-43 GiB a launch against 48-118): marked there.
+static bool stream_hint_wide(const siso_cache *c) {
+    if (c->opt_stream_hint > 0) return c->opt_stream_hint == 1;
+    return c->count * (long)c->dim * 2 > SISO_STREAM_BYTES;
+}
+
+template <bool STREAM>
+static int launch_wide2(siso_cache *c, const void *queries, long n, const PipePlan &p, u64 *keys) {
     static bool attr_done = false;
     if (!attr_done) {
-        hipError_t e = hipFuncSetAttribute((const void *)k_lookup_wide,
+        hipError_t e = hipFuncSetAttribute((const void *)k_lookup_wide<STREAM>,
                                            hipFuncAttributeMaxDynamicSharedMemorySize, WideCfg::LDS_BYTES);
         if (e != hipSuccess) return siso_check_hip(c, e, "hipFuncSetAttribute(k_lookup_wide)");
         attr_done = true;
     }
-    hipLaunchKernelGGL((k_lookup_wide), dim3((unsigned)p.grid), dim3(WideCfg::NT), WideCfg::LDS_BYTES, c->stream,
+    hipLaunchKernelGGL((k_lookup_wide<STREAM>), dim3((unsigned)p.grid), dim3(WideCfg::NT), WideCfg::LDS_BYTES, c->stream,
                        (const bf16_t *)queries, (const bf16_t *)c->cent, c->invn, n, c->count, c->dim, p.tiles_per_slice,
                        p.slices, p.nqt, p.qb, keys);
     return siso_check_hip(c, hipGetLastError(), "k_lookup_wide");
+}
+static int launch_wide(siso_cache *c, const void *queries, long n, const PipePlan &p, u64 *keys) {
+    return stream_hint_wide(c) ? launch_wide2<true>(c, queries, n, p, keys) : launch_wide2<false>(c, queries, n, p, keys);
 }
 
 static int pipe_launch(siso_cache *c, const void *queries, long n, const PipePlan &p, u64 *keys) {

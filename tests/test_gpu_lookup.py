@@ -99,7 +99,7 @@ def test_numbers_of_query_tiles_that_do_not_fill_the_blocks(siso, oracle, n, K, 
     check_topk(tk, oc.lookup_topk(wl.queries, 6), "bf16", "ragged top 6")
 
 
-@pytest.mark.parametrize("storage,cfg,n", [("bf16", 3, 50), ("bf16", 2, 128), ("bf16", 1, 300), ("fp8", 8, 64), ("fp8", 7, 100),
+@pytest.mark.parametrize("storage,cfg,n", [("bf16", 3, 50), ("bf16", 2, 128), ("bf16", 1, 300), ("bf16", 5, 700), ("fp8", 8, 64), ("fp8", 7, 100),
                                             ("fp8", 6, 300), ("fp8", 3, 33)])
 def test_streaming_mark_changes_nothing(siso, oracle, storage, cfg, n):
     """The centroid loads of the eight-wave kernels with and without the non-temporal mark (two instantiations,
