@@ -718,8 +718,8 @@ __global__ __launch_bounds__(Cfg::NT) __attribute__((amdgpu_waves_per_eu(2, 2)))
 // each other without a gap, only the accumulators start from zero again.
 // The 32 workgroups of an XCD take the tile pairs of one unit (8 column tiles x 4 row tiles) at a
 // time, as in the lookup, so that a tile fetched into that L2 serves several of them; the XCDs own
-// the groups of four row tiles in turns, in alternating direction, which gives each an equal share
-// of the triangle.
+// the groups of four row tiles in turns, in alternating direction and from the longest rows to the
+// shortest, which gives each an equal share of the triangle.
 // ----------------------------------------------------------------------------
 struct PairItems {
     int xcd, i, qb, sb, nqb, groups, tiles, units, u;
@@ -739,9 +739,12 @@ struct PairItems {
         while (u < units) {
             const int round = u / nqb, b = u % nqb;
             ++u;
-            const int g = round * 8 + ((round & 1) ? 7 - xcd : xcd);
+            // (the groups from the bottom of the triangle upwards: the round that not every XCD takes part in is
+            // then the one with the least work - 196 row tiles: 28 % more than its share on one XCD otherwise)
+            const int gi = round * 8 + ((round & 1) ? 7 - xcd : xcd);
+            const int g = groups - 1 - gi;
             const int q = b * qb + i % qb, s = g * sb + i / qb;
-            if (g >= groups || q >= tiles || s >= tiles || s < q) continue;
+            if (gi >= groups || q >= tiles || s >= tiles || s < q) continue;
             qt = q;
             ct = s;
             return true;
