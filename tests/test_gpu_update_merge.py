@@ -108,6 +108,56 @@ def test_update_matches_oracle(siso, oracle, dtype, dim, n):
     assert torch.equal(before, cache.export()[1])
 
 
+@pytest.mark.parametrize("dtype,dim,n,hot", [("bf16", 256, 5000, 3000), ("f32", 384, 3000, 2200), ("bf16", 1024, 9000, 9000),
+                                             ("bf16", 768, 40000, 20000)])
+def test_update_with_a_centroid_that_takes_thousands_of_members(siso, oracle, dtype, dim, n, hot):
+    """A burst of near-identical queries in one large batch: one centroid takes `hot` members, a second one 300, the
+    rest a few each (the block that leads a centroid folds its members one after the other: slow for such a
+    centroid, and exact).  Means, sizes and stored rows against the oracle; a zero row and a row with a NaN among
+    the burst are passed over."""
+    print(f"case: update with a hot centroid {dtype} dim={dim} n={n} hot={hot}", flush=True)
+    K = 2000
+    wl = W.c2_mid(n_clusters=50, per_cluster=40, n_queries=n, dim=dim, dtype=dtype, seed=88)
+    r = np.random.default_rng(5)
+    idx = r.integers(0, K, size=n).astype(np.int32)
+    where = r.permutation(n)
+    idx[where[:hot]] = 777
+    idx[where[hot:hot + 300]] = 1500 if hot + 300 <= n else 777
+    c32 = W.storage_to_f32(wl.centroids, dtype)
+    q32 = c32[idx] + r.standard_normal((n, dim)).astype(np.float32) * np.float32(0.1 / np.sqrt(dim))
+    q32 *= r.uniform(0.5, 2.0, size=(n, 1)).astype(np.float32)
+    q32[where[3]] = 0.0                        # members without length or with a NaN: passed over
+    q32[where[7], 5] = np.nan
+    queries = W.to_storage(q32, dtype)
+    counts = W.random_counts(89, K, 1, 9)
+    cache = siso.SisoCache(dim, K, siso_dtype(dtype))
+    cache.load(to_dev(wl.centroids, dtype), torch.from_numpy(counts).to(DEV))
+    oc = oracle.OracleCache(dim, K, dtype)
+    oc.load(wl.centroids, counts)
+    q = to_dev(queries, dtype)
+    t0 = torch.cuda.Event(enable_timing=True)
+    t1 = torch.cuda.Event(enable_timing=True)
+    cache.update(q, torch.from_numpy(idx).to(DEV))            # allocates the notes of a large batch
+    cache.load(to_dev(wl.centroids, dtype), torch.from_numpy(counts).to(DEV))
+    t0.record()
+    cache.update(q, torch.from_numpy(idx).to(DEV))
+    t1.record()
+    torch.cuda.synchronize()
+    print(f"  update of {n} queries, {hot} of them into one centroid: {t0.elapsed_time(t1) * 1e3:.0f} us", flush=True)
+    oc.update(queries, idx)
+    compare_state(cache, oc, dtype, "hot centroid")
+    sizes = cache.export()[2].cpu().numpy()
+    assert sizes[777] == counts[777] + int((idx == 777).sum()) - int(idx[where[3]] == 777) - int(idx[where[7]] == 777)
+    assert cache.bad_indices() == 0
+    # the same batch again in a different order: the same means within the tolerance, the same sizes
+    perm = r.permutation(n)
+    cache2 = siso.SisoCache(dim, K, siso_dtype(dtype))
+    cache2.load(to_dev(wl.centroids, dtype), torch.from_numpy(counts).to(DEV))
+    cache2.update(to_dev(queries[perm], dtype), torch.from_numpy(idx[perm]).to(DEV))
+    a, b = cache.export(), cache2.export()
+    assert torch.equal(a[2], b[2]) and (a[1] - b[1]).abs().max().item() <= MEAN_TOL
+
+
 def test_update_fold_misses_policy(siso, oracle):
     """The library folds whatever it is told to: here the misses instead of the hits."""
     print("case: update folding misses", flush=True)
