@@ -153,7 +153,8 @@ __global__ __launch_bounds__(256) void k_lookup_finalize(const T *__restrict__ Q
                                                           long n, long K, int d, int slices, ThetaList thetas, int vec,
                                                           int key_kind, int *out_idx, float *out_sim,
                                                           unsigned char *out_hit, unsigned *access,
-                                                          const float *__restrict__ q_inv) {
+                                                          const float *__restrict__ q_inv, int *upd_owner,
+                                                          int *upd_members) {
     constexpr int EPC = 16 / (int)sizeof(T);  // elements per 16-byte chunk
     __shared__ float sh_f[4];
     __shared__ u64 sh_k[4];
@@ -255,6 +256,12 @@ __global__ __launch_bounds__(256) void k_lookup_finalize(const T *__restrict__ Q
             if (out_hit) out_hit[(size_t)q * thetas.m + j] = hit ? 1 : 0;
             // a hit is a reference to its centroid (access_count of Algorithm 1); infinity stays infinity
             if (hit && j == thetas.count_at && access && access[best_i] != SISO_ACCESS_INF) atomicAdd(&access[best_i], 1u);
+            // siso_lookup_update on a large batch: the notes that k_update_mark would take (first member and
+            // number of members of each centroid), taken here, a launch earlier
+            if (hit && j == 0 && upd_owner) {
+                atomicMin(&upd_owner[best_i], (int)q);
+                atomicAdd(&upd_members[best_i], 1);
+            }
         }
     }
 }
@@ -1475,23 +1482,28 @@ int siso_lookup_impl(siso_cache *c, const void *queries, long n, const float *th
         *folded = 1;
         return SISO_OK;
     }
+    const bool mark = c->mark_in_finalize == 1 && m == 1 && c->upd_owner != nullptr;
     if (c->dtype == SISO_F32)
         hipLaunchKernelGGL(k_lookup_finalize<float>, dim3(qblocks), dim3(256), 0, c->stream, (const float *)queries,
                            (const float *)c->cent, c->invn, keys, n, c->count, c->dim, slices, tl,
                            vec, row_keys, out_idx, out_sim, out_hit, count_index >= 0 ? c->access : nullptr,
-                           (const float *)nullptr);
+                           (const float *)nullptr, mark ? c->upd_owner : nullptr, mark ? c->upd_members : nullptr);
     else
         hipLaunchKernelGGL(k_lookup_finalize<bf16_t>, dim3(qblocks), dim3(256), 0, c->stream, (const bf16_t *)queries,
                            (const bf16_t *)c->cent, c->invn, keys, n, c->count, c->dim, slices, tl,
                            vec, row_keys, out_idx, out_sim, out_hit, count_index >= 0 ? c->access : nullptr,
-                           fp8 ? (const float *)c->fp8_qinv : (const float *)nullptr);
+                           fp8 ? (const float *)c->fp8_qinv : (const float *)nullptr, mark ? c->upd_owner : nullptr,
+                           mark ? c->upd_members : nullptr);
     HIP_TRY(c, hipGetLastError());
+    if (mark) c->mark_in_finalize = 2;  // done
     return SISO_OK;
 }
 
 #define UPDATE_CHUNK 32768L
 
-extern "C" int siso_update_hits(siso_cache *c, const void *queries, const int *idx, const unsigned char *hit, long n) {
+// premarked: the notes of this batch (one chunk) have been taken already, by the finalize step of its lookup
+static int update_hits_impl(siso_cache *c, const void *queries, const int *idx, const unsigned char *hit, long n,
+                            bool premarked) {
     if (!c) return SISO_EINVAL;
     SISO_NOT_FP8(c, "siso_update");
     if (n < 0 || (n > 0 && (!queries || !idx))) return siso_fail(c, SISO_EINVAL, "siso_update: bad arguments");
@@ -1509,8 +1521,9 @@ extern "C" int siso_update_hits(siso_cache *c, const void *queries, const int *i
             if (rc != SISO_OK) return rc;
             owner = c->upd_owner;
             marked = c->upd_members;
-            hipLaunchKernelGGL(k_update_mark, dim3((unsigned)((m + 255) / 256)), dim3(256), 0, c->stream, idx + off, h, m,
-                               c->count, owner, marked);
+            if (!premarked)
+                hipLaunchKernelGGL(k_update_mark, dim3((unsigned)((m + 255) / 256)), dim3(256), 0, c->stream, idx + off, h,
+                                   m, c->count, owner, marked);
         }
 #define SISO_LAUNCH_UPDATE(T, E, QP)                                                                            \
     hipLaunchKernelGGL((k_update<T, E>), grid, block, 0, c->stream, QP, idx + off, h, m, (T *)c->cent, c->mean, \
@@ -1526,6 +1539,10 @@ extern "C" int siso_update_hits(siso_cache *c, const void *queries, const int *i
         HIP_TRY(c, hipGetLastError());
     }
     return SISO_OK;
+}
+
+extern "C" int siso_update_hits(siso_cache *c, const void *queries, const int *idx, const unsigned char *hit, long n) {
+    return update_hits_impl(c, queries, idx, hit, n, false);
 }
 
 extern "C" int siso_fp8_lookup_update(siso_cache *copy, siso_cache *master, const void *queries, long n, float threshold,
@@ -1558,9 +1575,21 @@ extern "C" int siso_lookup_update(siso_cache *c, const void *queries, long n, fl
     if (n < 0 || (n > 0 && (!queries || !out_idx || !out_sim || !out_hit)))
         return siso_fail(c, SISO_EINVAL, "siso_lookup_update: bad arguments");
     int folded = 0;
+    // a large batch (one chunk of the update): the end of the lookup takes the update's notes itself
+    c->mark_in_finalize = 0;
+    if (n > 256 && n <= UPDATE_CHUNK && ensure_update_notes(c) == SISO_OK) c->mark_in_finalize = 1;
     const int rc = siso_lookup_impl(c, queries, n, &threshold, 1, 0, out_idx, out_sim, out_hit, nullptr, 0, &folded);
-    if (rc != SISO_OK || folded || n == 0) return rc;
-    return siso_update_hits(c, queries, out_idx, out_hit, n);
+    const bool premarked = c->mark_in_finalize == 2;
+    c->mark_in_finalize = 0;
+    if (rc != SISO_OK || folded || n == 0) {
+        if (premarked) {  // (a failure behind the notes: leave them as a fresh cache has them)
+            hipLaunchKernelGGL(k_update_mark_init, dim3((unsigned)((c->capacity + 255) / 256)), dim3(256), 0, c->stream,
+                               c->upd_owner, c->upd_members, c->capacity);
+            (void)hipGetLastError();
+        }
+        return rc;
+    }
+    return update_hits_impl(c, queries, out_idx, out_hit, n, premarked);
 }
 
 int siso_read_counter(siso_cache *c, int which, u64 *value) {

@@ -87,6 +87,8 @@ struct siso_cache {
     long topk_cap;
     int plan_min_slices;  // > 0 while a top-k lookup plans its passes: at least this many slices (if the tiles allow)
     const siso_cache *fold_master;  // not NULL while siso_fp8_lookup_update runs its lookup on this 8-bit copy
+    int mark_in_finalize;  // siso_lookup_update on a large batch: 1 = the finalize step shall take the update's notes
+                           // (first member and number of members per centroid), 2 = it has; 0 otherwise
     u64 *board_to_clear;  // not NULL while siso_lookup_update launches its first phase: a kernel that empties these
                           // slots sets it back to NULL
 

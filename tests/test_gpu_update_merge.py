@@ -386,7 +386,9 @@ def same_state(a, b):
     ("bf16", 1024, 2000, 1, 16), ("bf16", 2048, 900, 37, 4),
     ("f32", 384, 1024, 256, 16),       # the scalar kernel, a full board
     ("bf16", 768, 5000, 200, 64),      # the wide kernel names groups of rows: the two calls
-    ("f32", 96, 700, 300, 16)])        # more queries than the board has slots: the two calls
+    ("f32", 96, 700, 300, 16),         # more queries than the board has slots: the two calls, the notes of the
+    ("bf16", 256, 4000, 700, 8),       # update taken by the end of the lookup (large batches, many members per
+    ("bf16", 1024, 3000, 1500, 64)])   # centroid)
 def test_lookup_update_is_lookup_then_update_hits(siso, oracle, dtype, dim, K, n, clusters):
     print(f"case: lookup_update {dtype} dim={dim} K={K} n={n}", flush=True)
     wl = W.c2_mid(n_clusters=clusters, per_cluster=(K + clusters - 1) // clusters, n_queries=n * 6, dim=dim, dtype=dtype, seed=77)
